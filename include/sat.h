@@ -1,0 +1,244 @@
+/*
+ * libsat — one graph partition's SAT (staleness-alleviated training) GCN layer
+ * step on one MI355X (gfx950): pull of cached halo embeddings, correction by
+ * the embedding predictor, normalised-adjacency aggregation, feature transform,
+ * the matching backward pass, and push of fresh embeddings.
+ *
+ * Plain C ABI. No function takes or returns a framework type.
+ *
+ * Conventions (all entry points)
+ * ------------------------------
+ *  - Every function returns a sat_status; SAT_OK is 0, errors are negative.
+ *    Arguments are validated on the host BEFORE anything is enqueued: a call
+ *    that returns an error has had no effect on device memory.
+ *  - "device pointer" = memory of the current HIP device; "host pointer" =
+ *    ordinary process memory. The library allocates no device memory, keeps no
+ *    pointer past the kernels it enqueues, and owns nothing: every buffer is
+ *    the caller's. Scratch comes from a caller-supplied workspace whose size a
+ *    *_workspace_bytes() query returns.
+ *  - Compute calls take `stream` (a hipStream_t passed as void*, NULL = the
+ *    null stream), enqueue their kernels there and return without waiting.
+ *  - Dense matrices are row-major with an explicit leading dimension `ld`
+ *    counted in ELEMENTS (ld >= number of columns). Padding columns
+ *    [d, ld) are never read for arithmetic and never written.
+ *  - Node ids are int32_t; row offsets (rowptr, split, colptr) are int64_t.
+ *  - Element types: SAT_F32 (float). SAT_BF16 is reserved; calls that are
+ *    given it return SAT_EUNSUPPORTED. Accumulation is always fp32.
+ *  - Kernels bound-check every id they read from device memory: an id outside
+ *    its table is skipped (gather/push: that row is not copied; aggregation:
+ *    that entry contributes nothing). They never fault on bad ids, but the
+ *    result is then unspecified for the rows concerned.
+ *
+ * Notation follows the paper: V_m local (in-subgraph) nodes of partition m,
+ * n_local = |V_m|; halo = out-of-subgraph 1-hop neighbours, n_halo of them;
+ * n_bar = n_local + n_halo; H_bar^(l) = [H_in^(l) ; H_out_hat^(l)] one buffer
+ * of n_bar rows, local rows first; P = A_hat = D~^-1/2 (A + I) D~^-1/2 with
+ * GLOBAL degrees, P = P_in + P_out.
+ */
+#ifndef SAT_H_
+#define SAT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t sat_status;
+
+enum {
+  SAT_OK = 0,
+  SAT_EINVAL = -1,       /* null pointer, negative size, ld < d, inconsistent sizes */
+  SAT_EUNSUPPORTED = -2, /* element type or a dimension outside what is compiled in */
+  SAT_EALIGN = -3,       /* a pointer or ld breaks a stated alignment requirement */
+  SAT_EWORKSPACE = -4,   /* workspace pointer null or smaller than the query says */
+  SAT_EHIP = -5          /* a HIP call or launch failed; see sat_last_hip_error() */
+};
+
+enum { SAT_F32 = 0, SAT_BF16 = 1 };
+enum { SAT_ACT_IDENTITY = 0, SAT_ACT_RELU = 1 };
+
+/*
+ * Local view of partition m (Eq. 2: in-subgraph vs out-of-subgraph neighbours;
+ * appendix: P = P_in + P_out; Sec. "Temporal graphs": the partition plus its
+ * 1-hop neighbourhood). Canonical form, one valid encoding only:
+ *   rows    = local nodes in ascending global id;
+ *   columns = relabelled ids: local node -> its rank in V_m, halo node ->
+ *             n_local + its rank among halo nodes (ascending global id);
+ *   each row holds its self-loop and all neighbours, sorted ascending by
+ *   relabelled id, hence every local column precedes every halo column;
+ *   split[i] is the offset (into col/val) of row i's first halo column
+ *   (= rowptr[i+1] if it has none);
+ *   val[k] = A_hat entry, stored as ONE fp32 product isd[i] * isd[j] where
+ *   isd[v] = fp32(1 / sqrt(1 + deg(v))) rounded once from fp64.
+ * The halo block P_out is also stored transposed (CSR of P_out^T): for halo
+ * node u, h_row[h_colptr[u] .. h_colptr[u+1]) are its local neighbours in
+ * ascending order with values h_val; h_self[u] = A_hat[u,u] = isd[u]^2.
+ * All pointers are device pointers for the compute calls below and host
+ * pointers for sat_partition_view_build().
+ */
+typedef struct sat_part_view {
+  int64_t n_local, n_halo, nnz, nnz_halo;
+  const int64_t* rowptr;   /* [n_local + 1] */
+  const int64_t* split;    /* [n_local]     */
+  const int32_t* col;      /* [nnz], values in [0, n_local + n_halo) */
+  const float* val;        /* [nnz]         */
+  const int64_t* h_colptr; /* [n_halo + 1]  */
+  const int32_t* h_row;    /* [nnz_halo], values in [0, n_local) */
+  const float* h_val;      /* [nnz_halo]    */
+  const float* h_self;     /* [n_halo]      */
+} sat_part_view;
+
+/*
+ * Parameters omega of one hidden layer's embedding predictor g_omega
+ * (Sec. "Embedding Predictor": an RNN-GNN made of an LSTM and a GCN). Device
+ * pointers, fp32, row-major, dense (no padding):
+ *   Wx [4*d_s, d], Wh [4*d_s, d_s], b [4*d_s]  LSTM, gate blocks stacked i,f,g,o
+ *   Wg [d_s, d]                                weight of the GCN hop
+ */
+typedef struct sat_predictor {
+  const float* Wx;
+  const float* Wh;
+  const float* b;
+  const float* Wg;
+  int32_t d;    /* embedding width of the layer */
+  int32_t d_s;  /* LSTM hidden size; must be a multiple of 32, at most 128 */
+  int32_t tau;  /* window length, 1 <= tau <= 8 */
+  int32_t bypass; /* nonzero: plain historical embeddings, no correction */
+} sat_predictor;
+
+/* ---------------------------------------------------------------- utilities */
+const char* sat_status_string(sat_status s); /* static string, never NULL */
+int32_t sat_last_hip_error(void); /* hipError_t of this thread's last SAT_EHIP, else 0 */
+int32_t sat_version(void);        /* major*10000 + minor*100 + patch */
+
+/* ------------------------------------------------- setup: partition view
+ * (Eq. 2; appendix P = P_in + P_out). HOST pointers, runs on the CPU, once
+ * per partition. Input: a simple undirected graph as symmetric CSR without
+ * self-loops (g_rowptr [N+1], g_col ascending inside a row, ids in [0,N)),
+ * the partition vector part[N] and the partition m to view. g_deg (nullable)
+ * overrides the neighbour count of every node used for normalisation; NULL
+ * means the row lengths of the CSR. (Rows of nodes outside partition m are
+ * never read, so a caller that only holds partition m's rows passes them
+ * plus g_deg for everybody.)
+ * _sizes() reports the four counts; the caller allocates and calls _build(),
+ * which fills arrays of exactly those sizes (layout: see sat_part_view;
+ * local_ids [n_local] and halo_ids [n_halo] are ascending GLOBAL ids).
+ * Errors: SAT_EINVAL on null pointers, N < 0, ids out of range, a
+ * non-monotone rowptr, or a self-loop / unsorted row inside partition m.
+ */
+sat_status sat_partition_view_sizes(int64_t N, const int64_t* g_rowptr, const int32_t* g_col,
+                                    const int32_t* part, int32_t m, int64_t* n_local,
+                                    int64_t* n_halo, int64_t* nnz, int64_t* nnz_halo);
+sat_status sat_partition_view_build(int64_t N, const int64_t* g_rowptr, const int32_t* g_col,
+                                    const int32_t* g_deg, const int32_t* part, int32_t m,
+                                    int32_t* local_ids, int32_t* halo_ids, int64_t* rowptr,
+                                    int64_t* split, int32_t* col, float* val, int64_t* h_colptr,
+                                    int32_t* h_row, float* h_val, float* h_self);
+
+/* ------------------------------------------------- pull (Alg. 1 "Pull H_out")
+ * out[k, 0:d) = table[ids[k], 0:d) for k in [0, n). A bit-exact copy.
+ * table: device, [n_rows, ld_table]; ids: device int32 [n] (repeats allowed);
+ * out: device, [n, ld_out]; must not overlap table. Used for the halo rows of
+ * the static input features (layer 0), for plain historical embeddings, and
+ * to assemble the predictor's window.
+ */
+sat_status sat_history_gather(const void* table, int64_t n_rows, int64_t ld_table,
+                              const int32_t* ids, int64_t n, int32_t d, void* out,
+                              int64_t ld_out, int32_t dtype, void* stream);
+
+/* ------------------------------------- push (Alg. 1 "Push computed embeddings")
+ * table[ids[k], 0:d) = H[k, 0:d) for k in [0, n). Bit-exact copy; ids must be
+ * distinct (otherwise which copy survives is unspecified). Other rows and the
+ * columns [d, ld_table) are untouched.
+ */
+sat_status sat_history_push(void* table, int64_t n_rows, int64_t ld_table, const int32_t* ids,
+                            int64_t n, int32_t d, const void* H, int64_t ld_h, int32_t dtype,
+                            void* stream);
+
+/* -------------------- embedding predictor g_omega (Eq. 7; Sec. "Embedding Predictor")
+ * Writes the predicted halo embeddings H_out_hat into rows [n_local, n_bar)
+ * of Hbar [n_bar, ld]:
+ *   1. per node u of the partition and its halo, S_u = last hidden state of a
+ *      one-layer LSTM (zero initial state) run over u's tau cached embeddings,
+ *      oldest first;
+ *   2. per halo node u, Delta_u = (A_hat[u,u] S_u + sum over local neighbours v
+ *      of A_hat[u,v] S_v) Wg   (one GCN propagation, no activation);
+ *   3. H_out_hat[u] = newest cached embedding of u + Delta_u.
+ * With w->bypass set, step 3 alone with Delta = 0 (a copy of the newest rows).
+ * slots: HOST array of tau DEVICE pointers, oldest first; slot s is a matrix
+ * [*, ld_slot]. Row of node k (k in [0, n_bar), local nodes first) inside a
+ * slot is ids[k] if ids != NULL (device int32 [n_bar]; lets the call read the
+ * history table in place), else k. n_rows_slot bounds the row index.
+ * Local rows of Hbar are not touched. Hbar must not overlap any slot.
+ * Workspace: sat_predict_workspace_bytes(); 256-byte aligned device memory.
+ */
+int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, int32_t d, int32_t d_s,
+                                    int32_t tau);
+sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w, const void* const* slots,
+                       int64_t n_rows_slot, int64_t ld_slot, const int32_t* ids, void* Hbar,
+                       int64_t ld, int32_t dtype, void* workspace, int64_t workspace_bytes,
+                       void* stream);
+
+/* --------------- aggregation (appendix, SAT forward: P_in H_in + P_out H_out_hat)
+ * AGG [n_local, ld_out] = [P_in | P_out] * Hbar [n_bar, ld_in], d columns.
+ * AGG must not overlap Hbar.
+ */
+int64_t sat_spmm_workspace_bytes(const sat_part_view* pv_sizes_only, int32_t d);
+sat_status sat_spmm_fwd(const sat_part_view* pv, const void* Hbar, int64_t ld_in, int32_t d,
+                        int32_t dtype, void* AGG, int64_t ld_out, void* workspace,
+                        int64_t workspace_bytes, void* stream);
+
+/* ---------------- transpose aggregation (appendix, SAT backward: P_in^T D W^T)
+ * dH_local [n_local, ld_out] = P_in^T * dAGG [n_local, ld_in]. P_in is
+ * symmetric (A_hat is, and local ids label rows and columns alike), so this
+ * walks the local-column prefix [rowptr[i], split[i]) of every row.
+ * If dH_halo != NULL also dH_halo [n_halo, ld_halo] = P_out^T * dAGG through
+ * the transposed halo block. The SAT step itself never uses dH_halo: predicted
+ * halo embeddings are constants of the step.
+ */
+sat_status sat_spmm_bwd(const sat_part_view* pv, const void* dAGG, int64_t ld_in, int32_t d,
+                        int32_t dtype, void* dH_local, int64_t ld_out, void* dH_halo,
+                        int64_t ld_halo, void* workspace, int64_t workspace_bytes, void* stream);
+
+/* --------------------- feature transform (appendix: Z = (P H) W, H' = sigma(Z))
+ * H [n, ld_h] = act(AGG [n, ld_a] * W [d_in, ld_w]) with d_out columns;
+ * act = SAT_ACT_RELU on hidden layers, SAT_ACT_IDENTITY on the last. No bias.
+ */
+sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in, int32_t d_out,
+                         const void* W, int64_t ld_w, int32_t act, int32_t dtype, void* H,
+                         int64_t ld_h, void* stream);
+
+/* ------ backward of the feature transform (appendix: D = G o sigma'(Z),
+ * G_W = (P H)^T D, gradient to the aggregate D W^T)
+ *   dZ   = dH o [Hout > 0]     (act = RELU; Hout is the forward's output, and
+ *                               Hout > 0 exactly where Z > 0) or dH (IDENTITY,
+ *                               Hout may be NULL);
+ *   dW   [d_in, ld_dw] = AGG^T dZ   (fp32; reduced over all n rows in a fixed
+ *                               order, so results are run-to-run identical);
+ *   dAGG [n, ld_da]    = dZ W^T     (skipped if dAGG == NULL, e.g. layer 0).
+ * Workspace: sat_dense_bwd_workspace_bytes(); 256-byte aligned device memory.
+ */
+int64_t sat_dense_bwd_workspace_bytes(int64_t n, int32_t d_in, int32_t d_out);
+sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* Hout, int64_t ld_ho,
+                         const void* AGG, int64_t ld_a, const void* W, int64_t ld_w, int64_t n,
+                         int32_t d_in, int32_t d_out, int32_t act, int32_t dtype, float* dW,
+                         int64_t ld_dw, void* dAGG, int64_t ld_da, void* workspace,
+                         int64_t workspace_bytes, void* stream);
+
+/* ---------------- local loss gradient (Eq. 4 with softmax cross-entropy)
+ * dH [n, ld_dh] = (softmax(HL[n, ld_hl], over n_classes columns) - onehot(y)) / n;
+ * y: device int32 [n] in [0, n_classes). If loss != NULL (device float[1]) the
+ * mean cross-entropy is written there (summed in a fixed order).
+ * Workspace: sat_loss_workspace_bytes(n) bytes, 256-byte aligned (only
+ * needed when loss != NULL).
+ */
+int64_t sat_loss_workspace_bytes(int64_t n);
+sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
+                         const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh, float* loss,
+                         void* workspace, int64_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAT_H_ */

@@ -1,0 +1,246 @@
+// Feature transform H' = sigma((P H) W) and its backward (appendix: forward
+// Z = P H W, H' = sigma(Z); backward D = G o sigma'(Z), G_W = (P H)^T D, and
+// D W^T handed to the transpose aggregation).
+//
+// All three products run on the fp32 MFMA pipe through one tile kernel:
+//   forward : C = AGG * W            A KContig (AGG rows), B MNContig (W rows)
+//   dAGG    : C = dZ * W^T           A KContig with relu mask, B KContig (W read transposed)
+//   dW      : C = AGG^T * dZ         A MNContig (AGG rows are k), B MNContig with relu
+//             mask; K = n is split over blockIdx.z and the partial tiles are
+//             summed by a second kernel in a fixed order (no float atomics, so
+//             results are identical from run to run).
+// dZ = dH o [Hout > 0] is never written to memory: the mask is applied while the
+// operand tile is loaded.
+#include "gemm_tile.h"
+#include "sat_internal.h"
+
+namespace {
+
+using namespace sat::gemm;
+
+enum Epilogue { kStore = 0, kStoreRelu = 1, kStorePartial = 2 };
+
+template <Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, int64_t M,
+                                                          int64_t N, int64_t K,
+                                                          int64_t k_per_split, float* C,
+                                                          int64_t ldc, int64_t split_stride) {
+  __shared__ __attribute__((aligned(16))) float As[TILE_FLOATS];
+  __shared__ __attribute__((aligned(16))) float Bs[TILE_FLOATS];
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
+  const int64_t n0 = static_cast<int64_t>(blockIdx.y) * BN;
+  const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * k_per_split;
+  const int64_t k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  TileRegs<BM> ra;
+  TileRegs<BN> rb;
+  if (k_begin < k_end) {
+    load_tile<BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
+    load_tile<BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
+  }
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    __syncthreads();
+    store_tile<BM, LA>(ra, As, t);
+    store_tile<BN, LB>(rb, Bs, t);
+    __syncthreads();
+    if (k0 + BK < k_end) {
+      load_tile<BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
+      load_tile<BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
+    }
+    mma_step(As, Bs, wm, wn, lane, acc);
+  }
+
+  float* Cb = C;
+  if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * split_stride;
+  const int col_in_block = lane & 31;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int64_t n = n0 + wn * 64 + j * 32 + col_in_block;
+      if (n >= N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
+        if (m < M) {
+          float x = acc[i][j][r];
+          if constexpr (EPI == kStoreRelu) x = x > 0.f ? x : 0.f;
+          Cb[m * ldc + n] = x;
+        }
+      }
+    }
+  }
+}
+
+// out[i] = sum_s part[s * stride + i] for s ascending (fixed order).
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part,
+                                                              int64_t stride, int splits,
+                                                              int64_t rows, int cols,
+                                                              int64_t ld_part,
+                                                              float* __restrict__ out,
+                                                              int64_t ld_out) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= rows * cols) return;
+  const int64_t r = idx / cols;
+  const int c = static_cast<int>(idx - r * cols);
+  const float* p = part + r * ld_part + c;
+  float s = 0.f;
+  for (int k = 0; k < splits; ++k) s += p[k * stride];
+  out[r * ld_out + c] = s;
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+struct SplitPlan {
+  int splits;
+  int64_t k_per_split;
+  int64_t ld_part;       // floats per row of a partial tile
+  int64_t split_stride;  // floats per partial matrix
+};
+
+// How the reduction over the n rows of dW = AGG^T dZ is cut into blocks. Aims
+// at a few workgroups per compute unit while keeping every slice >= 8 K-steps.
+SplitPlan plan_dw(int64_t n, int32_t d_in, int32_t d_out) {
+  SplitPlan p;
+  const int64_t tiles = ((d_in + BM - 1) / BM) * static_cast<int64_t>((d_out + BN - 1) / BN);
+  int64_t want = (1024 + tiles - 1) / tiles;
+  int64_t max_by_k = (n + 8 * BK - 1) / (8 * BK);
+  if (max_by_k < 1) max_by_k = 1;
+  int64_t s = want < max_by_k ? want : max_by_k;
+  if (s < 1) s = 1;
+  p.k_per_split = round_up((n + s - 1) / s, BK);
+  if (p.k_per_split < BK) p.k_per_split = BK;
+  p.splits = static_cast<int>((n + p.k_per_split - 1) / p.k_per_split);
+  if (p.splits < 1) p.splits = 1;
+  p.ld_part = round_up(d_out, 4);
+  p.split_stride = static_cast<int64_t>(d_in) * p.ld_part;
+  return p;
+}
+
+sat_status check_mat(const void* p, int64_t rows, int64_t cols, int64_t ld) {
+  if (rows > 0 && cols > 0) {
+    if (!p || ld < cols) return SAT_EINVAL;
+    if (!sat::aligned16(p) || (ld % 4) != 0) return SAT_EALIGN;
+  }
+  return SAT_OK;
+}
+
+}  // namespace
+
+extern "C" sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in,
+                                    int32_t d_out, const void* W, int64_t ld_w, int32_t act,
+                                    int32_t dtype, void* H, int64_t ld_h, void* stream) {
+  if (n < 0 || d_in < 0 || d_out < 0) return SAT_EINVAL;
+  if (act != SAT_ACT_IDENTITY && act != SAT_ACT_RELU) return SAT_EINVAL;
+  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  sat_status st;
+  if ((st = check_mat(AGG, n, d_in, ld_a)) != SAT_OK) return st;
+  if ((st = check_mat(W, d_in, d_out, ld_w)) != SAT_OK) return st;
+  if ((st = check_mat(H, n, d_out, ld_h)) != SAT_OK) return st;
+  if (n == 0 || d_out == 0) return SAT_OK;
+  const int64_t gx = (n + BM - 1) / BM;
+  if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
+  const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_out + BN - 1) / BN), 1);
+  const Operand a{static_cast<const float*>(AGG), ld_a, nullptr, 0};
+  const Operand b{static_cast<const float*>(W), ld_w, nullptr, 0};
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int64_t K = d_in;
+  if (act == SAT_ACT_RELU)
+    gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStoreRelu>
+        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, 0);
+  else
+    gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStore>
+        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, 0);
+  return sat::check_launch();
+}
+
+extern "C" int64_t sat_dense_bwd_workspace_bytes(int64_t n, int32_t d_in, int32_t d_out) {
+  if (n <= 0 || d_in <= 0 || d_out <= 0) return 0;
+  const SplitPlan p = plan_dw(n, d_in, d_out);
+  return static_cast<int64_t>(p.splits) * p.split_stride * static_cast<int64_t>(sizeof(float));
+}
+
+extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* Hout,
+                                    int64_t ld_ho, const void* AGG, int64_t ld_a, const void* W,
+                                    int64_t ld_w, int64_t n, int32_t d_in, int32_t d_out,
+                                    int32_t act, int32_t dtype, float* dW, int64_t ld_dw,
+                                    void* dAGG, int64_t ld_da, void* workspace,
+                                    int64_t workspace_bytes, void* stream) {
+  if (n < 0 || d_in < 0 || d_out < 0) return SAT_EINVAL;
+  if (act != SAT_ACT_IDENTITY && act != SAT_ACT_RELU) return SAT_EINVAL;
+  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  sat_status st;
+  if ((st = check_mat(dH, n, d_out, ld_dh)) != SAT_OK) return st;
+  if (act == SAT_ACT_RELU && (st = check_mat(Hout, n, d_out, ld_ho)) != SAT_OK) return st;
+  if ((st = check_mat(AGG, n, d_in, ld_a)) != SAT_OK) return st;
+  if ((st = check_mat(W, d_in, d_out, ld_w)) != SAT_OK) return st;
+  if ((st = check_mat(dW, d_in, d_out, ld_dw)) != SAT_OK) return st;
+  if (dAGG && (st = check_mat(dAGG, n, d_in, ld_da)) != SAT_OK) return st;
+  if (d_in == 0 || d_out == 0) return SAT_OK;
+  const int64_t need = sat_dense_bwd_workspace_bytes(n, d_in, d_out);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return SAT_EWORKSPACE;
+  if (need > 0 && !sat::aligned256(workspace)) return SAT_EALIGN;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool relu = act == SAT_ACT_RELU;
+  const float* mask = relu ? static_cast<const float*>(Hout) : nullptr;
+
+  // dW = AGG^T dZ : M = d_in, N = d_out, K = n, split over blockIdx.z
+  if (n == 0) {
+    // empty reduction: dW = 0 (a tiny fill through the reduce kernel with 0 splits)
+    const int64_t total = static_cast<int64_t>(d_in) * d_out;
+    reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
+        dW, 0, 0, d_in, d_out, ld_dw, dW, ld_dw);
+    return sat::check_launch();
+  }
+  {
+    const SplitPlan p = plan_dw(n, d_in, d_out);
+    const dim3 grid(static_cast<unsigned>((d_in + BM - 1) / BM),
+                    static_cast<unsigned>((d_out + BN - 1) / BN), static_cast<unsigned>(p.splits));
+    const Operand a{static_cast<const float*>(AGG), ld_a, nullptr, 0};
+    const Operand b{static_cast<const float*>(dH), ld_dh, mask, ld_ho};
+    float* part = static_cast<float*>(workspace);
+    if (relu)
+      gemm_f32_kernel<Layout::MNContig, false, Layout::MNContig, true, kStorePartial>
+          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
+                                      p.split_stride);
+    else
+      gemm_f32_kernel<Layout::MNContig, false, Layout::MNContig, false, kStorePartial>
+          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
+                                      p.split_stride);
+    if ((st = sat::check_launch()) != SAT_OK) return st;
+    const int64_t total = static_cast<int64_t>(d_in) * d_out;
+    reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
+        part, p.split_stride, p.splits, d_in, d_out, p.ld_part, dW, ld_dw);
+    if ((st = sat::check_launch()) != SAT_OK) return st;
+  }
+
+  // dAGG = dZ W^T : M = n, N = d_in, K = d_out
+  if (dAGG) {
+    const int64_t gx = (n + BM - 1) / BM;
+    if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_in + BN - 1) / BN), 1);
+    const Operand a{static_cast<const float*>(dH), ld_dh, mask, ld_ho};
+    const Operand b{static_cast<const float*>(W), ld_w, nullptr, 0};
+    const int64_t K = d_out;
+    if (relu)
+      gemm_f32_kernel<Layout::KContig, true, Layout::KContig, false, kStore>
+          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, 0);
+    else
+      gemm_f32_kernel<Layout::KContig, false, Layout::KContig, false, kStore>
+          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, 0);
+    if ((st = sat::check_launch()) != SAT_OK) return st;
+  }
+  return SAT_OK;
+}

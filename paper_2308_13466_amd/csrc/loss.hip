@@ -1,0 +1,104 @@
+// Gradient of the local loss (Eq. 4 with softmax cross-entropy as Loss):
+// dH = (softmax(H^(L)) - onehot(y)) / n over the partition's local nodes, and
+// optionally the mean loss itself. One wavefront per node; classes are spread
+// over the 64 lanes and reduced with lane-xor shuffles. The loss is summed in
+// two fixed-order stages (per block into the workspace, then one block), so
+// it is identical from run to run.
+#include <math.h>
+
+#include "sat_internal.h"
+
+namespace {
+
+using sat::kWave;
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+  return x;
+}
+
+__global__ __launch_bounds__(256) void xent_grad_kernel(const float* __restrict__ HL,
+                                                        int64_t ld_hl, int64_t n, int32_t C,
+                                                        const int32_t* __restrict__ y,
+                                                        float* __restrict__ dH, int64_t ld_dh,
+                                                        float* __restrict__ block_loss) {
+  __shared__ float wave_loss[4];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+  float nll = 0.f;
+  if (row < n) {
+    const float* h = HL + row * ld_hl;
+    float mx = -INFINITY;
+    for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, h[c]);
+    mx = wave_max(mx);
+    float se = 0.f;
+    for (int c = lane; c < C; c += kWave) se += expf(h[c] - mx);
+    se = wave_sum(se);
+    const float inv_n = 1.0f / static_cast<float>(n);
+    const int32_t label = y[row];
+    float* g = dH + row * ld_dh;
+    for (int c = lane; c < C; c += kWave) {
+      const float p = expf(h[c] - mx) / se;
+      g[c] = (p - (c == label ? 1.f : 0.f)) * inv_n;
+    }
+    if (label >= 0 && label < C) nll = logf(se) + mx - h[label];
+  }
+  if (block_loss) {
+    if (lane == 0) wave_loss[wave] = nll;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      block_loss[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
+  }
+}
+
+// Single block: loss = (sum of m partials, fixed strided order + tree) / n.
+__global__ __launch_bounds__(256) void loss_finish_kernel(const float* __restrict__ part,
+                                                          int64_t m, int64_t n,
+                                                          float* __restrict__ loss) {
+  __shared__ float sh[256];
+  float s = 0.f;
+  for (int64_t i = threadIdx.x; i < m; i += 256) s += part[i];
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (static_cast<int>(threadIdx.x) < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = sh[0] / static_cast<float>(n);
+}
+
+}  // namespace
+
+extern "C" int64_t sat_loss_workspace_bytes(int64_t n) {
+  if (n <= 0) return 0;
+  return ((n + 3) / 4) * static_cast<int64_t>(sizeof(float));
+}
+
+extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
+                                    const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh,
+                                    float* loss, void* workspace, int64_t workspace_bytes,
+                                    void* stream) {
+  if (n < 0 || n_classes <= 0) return SAT_EINVAL;
+  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  if (n == 0) return SAT_OK;
+  if (!HL || !y || !dH || ld_hl < n_classes || ld_dh < n_classes) return SAT_EINVAL;
+  const int64_t blocks = (n + 3) / 4;
+  if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
+  if (loss && (!workspace || workspace_bytes < sat_loss_workspace_bytes(n))) return SAT_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  xent_grad_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(
+      static_cast<const float*>(HL), ld_hl, n, n_classes, y, static_cast<float*>(dH), ld_dh,
+      loss ? static_cast<float*>(workspace) : nullptr);
+  sat_status st = sat::check_launch();
+  if (st != SAT_OK || !loss) return st;
+  loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(static_cast<const float*>(workspace), blocks,
+                                                   n, loss);
+  return sat::check_launch();
+}
