@@ -1,0 +1,354 @@
+#!/usr/bin/env python3
+"""Benchmark of one partition's SAT GCN training step on one MI355X.
+
+A "step" is one pass of the whole hot path over one partition: predictor
+inference for every hidden layer (reading the history ring in place), pull of
+the static halo features, per layer aggregation + feature transform + push,
+the cross-entropy gradient, and the backward pass. Inputs are seeded and
+synthetic and are resident in HBM before the timed region starts.
+
+Prints ONE JSON line. `value` is CSR entries aggregated per second over the
+whole step (GTEPS), i.e. (entries walked by all aggregation calls of a step) /
+(wall time of the step, every call included).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
+# scaled by a copy kernel of known size); filled in from the committed profile
+# summaries, None where no counter run exists for that workload / kernel.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+class CallTimers:
+    """HIP event pairs around every library call, on the stream the calls are
+    enqueued on (torch's current stream), collected over the timed steps."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = []
+        self.enabled = False
+
+    def record(self, name, fn):
+        if not self.enabled:
+            fn()
+            return
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.pairs.append((name, a, b))
+
+    def summary(self):
+        out = {}
+        for name, a, b in self.pairs:
+            ms = a.elapsed_time(b)
+            tot, cnt = out.get(name, (0.0, 0))
+            out[name] = (tot + ms, cnt + 1)
+        return {k: dict(total_ms=v[0], launches=v[1], avg_ms=v[0] / v[1]) for k, v in out.items()}
+
+
+def build_inputs(cfg, log):
+    """Host-side seeded inputs of one workload (no method arithmetic here)."""
+    import numpy as np
+    import sat_synth as syn
+    ss = syn.substreams(cfg["seed"])
+    t0 = time.time()
+    g = syn.cached_graph(cfg, ss["graph"])
+    log("graph: N=%d nnz=%d (%.1fs)" % (g.N, g.nnz, time.time() - t0))
+    dims = cfg["dims"]
+    L = len(dims) - 1
+    wss = ss["weights"].spawn(L)
+    Ws = [syn.glorot_uniform_f32(wss[l], dims[l], dims[l + 1]) for l in range(L)]
+    pss = ss["predictor"].spawn(L)
+    omegas = [None] + [syn.predictor_params_f32(pss[l], dims[l], cfg["d_s"]) for l in range(1, L)]
+    return ss, g, Ws, omegas
+
+
+def ld_of(d, mult=32):
+    return (d + mult - 1) // mult * mult
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "dense", "large"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--unfused-pull", action="store_true",
+                    help="assemble the predictor window with sat_history_gather first")
+    ap.add_argument("--bypass", action="store_true", help="plain historical embeddings")
+    ap.add_argument("--quiet", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one partition on ONE GPU; --gpus %d is not supported "
+              "(no collectives, no sharding across GPUs in this library)" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    def log(msg):
+        if not args.quiet:
+            print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import numpy as np
+    import torch
+    import sat_synth as syn
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd.step import PartitionStep
+    sat.lib()   # raises if libsat.so has not been built; there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    cfg = syn.get_config(args.workload)
+    dims, tau, d_s = cfg["dims"], cfg["tau"], cfg["d_s"]
+    if args.workload == "tiny":
+        d_s = 32
+    L = len(dims) - 1
+    ss, g, Ws, omegas = build_inputs(dict(cfg, d_s=d_s), log)
+    t0 = time.time()
+    view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"])
+    n_l, n_h = view["n_local"], view["n_halo"]
+    n_bar = n_l + n_h
+    log("partition view: n_local=%d n_halo=%d nnz=%d nnz_halo=%d max_deg=%d (%.1fs)" % (
+        n_l, n_h, view["nnz"], view["nnz_halo"], int(np.diff(view["rowptr"]).max()),
+        time.time() - t0))
+
+    # ---- device-resident inputs
+    t0 = time.time()
+    ld = [ld_of(d) for d in dims]
+    X_host = syn.normal_f32(ss["features"], g.N, dims[0], ld=ld[0])
+    X_d = torch.from_numpy(X_host).to(dev)
+    hss = ss["history"].spawn(L)
+    hist_d = [None]
+    hist_host_newest = [None]
+    for l in range(1, L):
+        slots = syn.history_standin_f32(hss[l], g.N, dims[l], tau, cfg["noise_std"], ld=ld[l])
+        hist_d.append([torch.from_numpy(s).to(dev) for s in slots])
+        hist_host_newest.append(slots)      # kept for the CPU baseline sample
+    table_ids = np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32)
+    ids_d = torch.from_numpy(table_ids).to(dev)
+    Ws_d = []
+    for l in range(L):
+        w = np.zeros((dims[l], ld_of(dims[l + 1], 4)), np.float32)
+        w[:, :dims[l + 1]] = Ws[l]
+        Ws_d.append(torch.from_numpy(w).to(dev))
+    keep, preds = [], [None]
+    for l in range(1, L):
+        pd = {k: torch.from_numpy(omegas[l][k]).to(dev) for k in omegas[l]}
+        keep.append(pd)
+        preds.append(sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], d_s, tau,
+                                   bypass=args.bypass))
+    y = syn.labels_i32(ss["labels"], n_l, dims[-1])
+    y_d = torch.from_numpy(y).to(dev)
+    timers = CallTimers(torch)
+    step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
+                         fused_pull=not args.unfused_pull, timers=timers)
+    torch.cuda.synchronize()
+    log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
+        torch.cuda.memory_allocated() / 1e9, time.time() - t0))
+
+    # ---- warm-up, then the timed region
+    for _ in range(args.warmup):
+        step.forward_backward()
+    torch.cuda.synchronize()
+    timers.enabled = True
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step.forward_backward()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    timers.enabled = False
+    ms_per_step = 1e3 * elapsed / args.steps
+    edges = step.edges_per_step()
+    gteps = edges / (ms_per_step * 1e-3) / 1e9
+    calls = timers.summary()
+    loss = float(step.loss.item())
+    log("ms/step %.3f  GTEPS %.2f  loss %.5f" % (ms_per_step, gteps, loss))
+
+    # ---- per-kernel-class roofline figures (algorithmic bytes / flops per launch)
+    s = 4
+    nnz, nnz_loc, nnz_halo = view["nnz"], step.nnz_local, view["nnz_halo"]
+
+    def spmm_bytes(entries, rows, d):       # per entry: col + val + one feature row;
+        return entries * (8 + d * s) + rows * (8 + d * s)   # per row: rowptr + output row
+
+    classes = {}
+
+    def add(cls, name, bound, work):
+        if name not in calls:
+            return
+        c = classes.setdefault(cls, dict(bound=bound, work=0.0, ms=0.0, launches=0))
+        c["work"] += work * calls[name]["launches"]
+        c["ms"] += calls[name]["total_ms"]
+        c["launches"] += calls[name]["launches"]
+
+    for l in range(L):
+        add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]))
+        if l >= 1:
+            add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]))
+        add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dims[l + 1])
+        add("dense_bwd", "dense_bwd_l%d" % l, "mfma",
+            (4.0 if l >= 1 else 2.0) * n_l * dims[l] * dims[l + 1])
+        if l >= 1:
+            add("push", "push_l%d" % l, "hbm", n_l * (2 * dims[l] * s + 4))
+            add("gather", "gather_l%d" % l, "hbm", n_bar * (2 * dims[l] * s + 4))
+            if not args.bypass:
+                flops = (2.0 * n_bar * 4 * d_s * (tau * dims[l] + (tau - 1) * d_s)
+                         + 2.0 * nnz_halo * d_s + 2.0 * n_h * d_s * dims[l])
+                add("predict", "predict_l%d" % l, "mfma", flops)
+            else:
+                add("gather", "predict_l%d" % l, "hbm", n_h * (2 * dims[l] * s + 4))
+    add("gather", "gather_l0", "hbm", n_h * (2 * dims[0] * s + 4))
+    add("loss", "loss_grad", "hbm", n_l * (2 * dims[L] * s + 4))
+
+    roof_all = {}
+    for cls, c in classes.items():
+        sec = c["ms"] * 1e-3
+        if c["bound"] == "hbm":
+            ach, peak, unit = c["work"] / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = c["work"] / sec / 1e12, MFMA_F32_PEAK_TFLOPS, "TFLOP/s"
+        roof_all[cls] = dict(bound=c["bound"], achieved=round(ach, 2), peak=peak, unit=unit,
+                             frac=round(ach / peak, 4),
+                             avg_launch_ms=round(c["ms"] / c["launches"], 4),
+                             ms_per_step=round(c["ms"] / args.steps, 4),
+                             launches_per_step=c["launches"] // args.steps,
+                             traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
+    dominant = max(roof_all, key=lambda k: roof_all[k]["ms_per_step"])
+    roofline = dict(kernel=dominant, **roof_all[dominant])
+
+    # ---- CPU oracle on a bounded sample, rank 0, host cores
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(view, dims, tau, d_s, X_host, hist_host_newest, table_ids, Ws, omegas,
+                           y, edges, bypass=args.bypass, log=log)
+
+    out = {
+        "metric": "GTEPS aggregated (CSR entries aggregated per second over one partition's "
+                  "SAT GCN step, fwd+bwd, predictor and history pull/push included)",
+        "value": round(gteps, 3), "unit": "GTEPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "graph": cfg["kind"], "N": g.N,
+                   "partition": "%d of %d" % (cfg["part"], cfg["n_parts"]),
+                   "n_local": n_l, "n_halo": n_h, "nnz": nnz, "nnz_local_local": nnz_loc,
+                   "dims": dims, "tau": tau, "d_s": d_s,
+                   "predictor": "bypass" if args.bypass else "every step",
+                   "pull": "unfused" if args.unfused_pull else "fused into predict",
+                   "entries_per_step": edges},
+        "ms_per_layer_step": round(ms_per_step / L, 4),
+        "ms_by_call": {k: round(v["total_ms"] / args.steps, 4) for k, v in sorted(calls.items())},
+        "roofline": roofline,
+        "roofline_all": roof_all,
+        "cpu_baseline": cpu,
+        "loss": round(loss, 6),
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(view, dims, tau, d_s, X_host, hist_host, table_ids, Ws, omegas, y, edges,
+                 bypass, log, sample_rows=1024, sample_nodes=4096):
+    """Time the oracle (as it stands) on a row sample of every call of the step
+    and extrapolate each call by rows_total / rows_sampled (rows of every call
+    are independent of one another)."""
+    import numpy as np
+    from oracle import sat_oracle as orc
+    try:
+        from threadpoolctl import threadpool_limits
+    except ImportError:                                   # pragma: no cover
+        threadpool_limits = None
+    L = len(dims) - 1
+    n_l, n_h = view["n_local"], view["n_halo"]
+    n_bar = n_l + n_h
+    rng = np.random.default_rng(1234)
+    rows = np.sort(rng.choice(n_l, size=min(sample_rows, n_l), replace=False))
+    nodes = np.sort(rng.choice(n_bar, size=min(sample_nodes, n_bar), replace=False))
+    halo = np.sort(rng.choice(n_h, size=min(sample_rows, n_h), replace=False)) if n_h else None
+    f_rows, f_nodes = n_l / len(rows), n_bar / len(nodes)
+    f_halo = (n_h / len(halo)) if n_h else 0.0
+
+    def run():
+        est = 0.0
+        t_all = time.perf_counter()
+        Hbars = [X_host[table_ids][:, :dims[0]]]
+        for l in range(1, L):
+            Hbars.append(hist_host[l][-1][table_ids][:, :dims[l]])   # stand-in activations
+        prep = time.perf_counter() - t_all
+        for l in range(1, L):
+            if bypass:
+                continue
+            win = [hist_host[l][s][table_ids[nodes]][:, :dims[l]] for s in range(tau)]
+            t0 = time.perf_counter()
+            orc.lstm_last_hidden(win, omegas[l]["Wx"], omegas[l]["Wh"], omegas[l]["b"])
+            est += (time.perf_counter() - t0) * f_nodes
+            if n_h:
+                sub = dict(view, n_halo=len(halo),
+                           h_colptr=np.concatenate([[0], np.cumsum(
+                               view["h_colptr"][halo + 1] - view["h_colptr"][halo])]),
+                           h_row=np.concatenate([view["h_row"][view["h_colptr"][u]:view["h_colptr"][u + 1]]
+                                                 for u in halo]),
+                           h_val=np.concatenate([view["h_val"][view["h_colptr"][u]:view["h_colptr"][u + 1]]
+                                                 for u in halo]),
+                           h_self=view["h_self"][halo])
+                S = np.zeros((n_l + len(halo), d_s), np.float32)
+                t0 = time.perf_counter()
+                orc.predictor_hop(sub, S, omegas[l]["Wg"])
+                est += (time.perf_counter() - t0) * f_halo
+        g = None
+        aggs = []
+        for l in range(L):
+            t0 = time.perf_counter()
+            a = orc.spmm_fwd_rows(view, Hbars[l], rows)
+            z, h = orc.dense_fwd(a, Ws[l], 1 if l < L - 1 else 0)
+            est += (time.perf_counter() - t0) * f_rows
+            aggs.append((a, z, h))
+        t0 = time.perf_counter()
+        _, g = orc.loss_and_grad(aggs[-1][2], y[rows])
+        est += (time.perf_counter() - t0) * f_rows
+        for l in range(L - 1, -1, -1):
+            a, z, h = aggs[l]
+            t0 = time.perf_counter()
+            dW, dA, _ = orc.dense_bwd(g[:, :dims[l + 1]], z, a, Ws[l], 1 if l < L - 1 else 0)
+            est += (time.perf_counter() - t0) * f_rows
+            if l >= 1:
+                dA_full = np.zeros((n_l, dims[l]), np.float32)      # stand-in upstream gradient
+                dA_full[rows] = dA
+                t0 = time.perf_counter()
+                g = orc.spmm_bwd_rows(view, dA_full, rows)
+                est += (time.perf_counter() - t0) * f_rows
+        return est, prep
+
+    t0 = time.time()
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            est, prep = run()
+        cores = 1
+    else:
+        est, prep = run()
+        cores = os.cpu_count() or 1
+    log("cpu oracle: estimated %.1f s per step on %d core(s) (sample run took %.1fs)" % (
+        est, cores, time.time() - t0))
+    return {"value": round(edges / est / 1e9, 6), "unit": "GTEPS", "cores": cores,
+            "kind": "oracle",
+            "sample": "%d of %d local rows per aggregation/transform call, %d of %d nodes for the "
+                      "predictor LSTM, %d of %d halo rows for its hop; each call's time scaled by "
+                      "rows_total/rows_sampled; estimated %.1f s per step" % (
+                          len(rows), n_l, len(nodes), n_bar, 0 if halo is None else len(halo),
+                          n_h, est)}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,167 @@
+"""One partition's SAT GCN training step as a sequence of libsat calls.
+
+Orchestration only: this module owns the device buffers (torch tensors, used
+as plain memory) and issues the C-ABI calls in the order of the paper's inner
+loop (Alg. 1): pull / predict, forward per layer, push, local loss, backward.
+No arithmetic happens here.
+
+Order inside a step t (history ring of tau slots per hidden layer):
+  1. predictions for every hidden layer l = 1..L-1 from the tau slots as they
+     stood at the end of step t-1 (so no push of step t is visible to them);
+  2. for l = 0..L-1: halo rows of layer 0 are the static features (pull);
+     AGG_l = [P_in | P_out] Hbar_l; H_{l+1} = act(AGG_l W_l), written straight
+     into the local rows of Hbar_{l+1}; push H_{l+1} into slot t mod tau of the
+     layer's ring (it overwrites the oldest epoch);
+  3. dH_L from the cross-entropy; for l = L-1..0: dW_l, dAGG_l; dH_l = P_in^T dAGG_l
+     for l >= 1 (halo rows are constants of the step: no gradient for them).
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _ld(d, mult=32):
+    return (d + mult - 1) // mult * mult
+
+
+class PartitionStep:
+    """Buffers and call sequence for one partition.
+
+    view: dict of host arrays from binding.partition_view_build.
+    X_table: device [n_rows_x, ld_x] input features of all nodes the ids refer to.
+    hist: hist[l] for l = 1..L-1 is a list of tau device tables [n_rows_h, ld_l]
+          (hist[0] unused); ring position is tracked here.
+    table_ids: device int32 [n_bar]; row of each local-then-halo node in X_table
+          and in every history table.
+    Ws: device weights, Ws[l] is [d_l, ld_w_l] with ld_w_l = _ld(d_{l+1}, 4).
+    predictors: predictors[l] a binding.Predictor for l = 1..L-1 (None: bypass).
+    y: device int32 [n_local] labels.
+    """
+
+    def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
+                 fused_pull=True, timers=None):
+        dev = X_table.device
+        self.dims = list(dims)
+        self.L = len(dims) - 1
+        self.tau = tau
+        self.view = view
+        self.n_local, self.n_halo = view["n_local"], view["n_halo"]
+        self.n_bar = self.n_local + self.n_halo
+        self.nnz = view["nnz"]
+        self.nnz_local = int(np.sum(view["split"] - view["rowptr"][:-1]))
+        t = {k: torch.from_numpy(np.ascontiguousarray(view[k])).to(dev)
+             for k in ("rowptr", "split", "col", "val", "h_colptr", "h_row", "h_val", "h_self")}
+        self.pv = B.PartView(view["n_local"], view["n_halo"], view["nnz"], view["nnz_halo"], **t)
+        self.X_table, self.hist, self.table_ids = X_table, hist, table_ids
+        self.halo_table_ids = table_ids[self.n_local:]
+        self.local_table_ids = table_ids[:self.n_local]
+        self.Ws, self.predictors, self.y = Ws, predictors, y
+        self.fused_pull = fused_pull
+        self.t = 0
+        self.timers = timers
+
+        f32 = dict(dtype=torch.float32, device=dev)
+        L, n_l, n_bar = self.L, self.n_local, self.n_bar
+        self.ld = [_ld(d) for d in dims]
+        self.ld_w = [_ld(dims[l + 1], 4) for l in range(L)]
+        self.Hbar = [torch.zeros((n_bar, self.ld[l]), **f32) for l in range(L)]
+        self.logits = torch.zeros((n_l, self.ld[L]), **f32)
+        self.AGG = [torch.zeros((n_l, self.ld[l]), **f32) for l in range(L)]
+        self.dH = [torch.zeros((n_l, self.ld[l]), **f32) for l in range(L + 1)]
+        self.dAGG = [torch.zeros((n_l, self.ld[l]), **f32) if l >= 1 else None for l in range(L)]
+        self.dW = [torch.zeros((dims[l], self.ld_w[l]), **f32) for l in range(L)]
+        self.loss = torch.zeros(1, **f32)
+        ws_bytes = [B.loss_workspace_bytes(n_l)]
+        ws_bytes += [B.dense_bwd_workspace_bytes(n_l, dims[l], dims[l + 1]) for l in range(L)]
+        for l in range(1, L):
+            if predictors[l] is not None:
+                ws_bytes.append(B.predict_workspace_bytes(n_l, self.n_halo, dims[l],
+                                                          predictors[l].d_s, tau))
+        self.ws_bytes = max(ws_bytes + [256])
+        self.ws = torch.empty((self.ws_bytes + 3) // 4, **f32)
+        if not fused_pull:
+            self.window = [[torch.zeros((n_bar, self.ld[l]), **f32) for _ in range(tau)]
+                           if l >= 1 else None for l in range(L)]
+        # local rows of layer 0 are static: pulled once
+        B.history_gather(X_table, X_table.shape[0], X_table.shape[1], self.local_table_ids,
+                         n_l, dims[0], self.Hbar[0], self.ld[0], stream=self._stream())
+
+    @staticmethod
+    def _stream():
+        return torch.cuda.current_stream().cuda_stream
+
+    def _timed(self, name, fn):
+        if self.timers is None:
+            fn()
+        else:
+            self.timers.record(name, fn)
+
+    def slot_order(self):
+        """Ring slots oldest -> newest as seen by step t's predictions."""
+        return [(self.t + s) % self.tau for s in range(self.tau)]
+
+    def forward_backward(self):
+        L, dims, ld, n_l, n_h, n_bar = self.L, self.dims, self.ld, self.n_local, self.n_halo, self.n_bar
+        st = self._stream()
+        order = self.slot_order()
+        # 1. predicted halo embeddings of every hidden layer
+        for l in range(1, L):
+            slots = [self.hist[l][s] for s in order]
+            n_rows, ld_t = slots[0].shape
+            w = self.predictors[l]
+            if self.fused_pull or w.bypass:
+                self._timed("predict_l%d" % l, lambda: B.predict(
+                    self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], ld[l],
+                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+            else:
+                for k, s in enumerate(slots):
+                    self._timed("gather_l%d" % l, lambda: B.history_gather(
+                        s, n_rows, ld_t, self.table_ids, n_bar, dims[l], self.window[l][k],
+                        ld[l], stream=st))
+                self._timed("predict_l%d" % l, lambda: B.predict(
+                    self.pv, w, self.window[l], n_bar, ld[l], None, self.Hbar[l], ld[l],
+                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+        # 2. forward
+        w_slot = self.t % self.tau
+        for l in range(L):
+            if l == 0 and n_h > 0:
+                halo0 = self.Hbar[0][n_l:]
+                self._timed("gather_l0", lambda: B.history_gather(
+                    self.X_table, self.X_table.shape[0], self.X_table.shape[1],
+                    self.halo_table_ids, n_h, dims[0], halo0, ld[0], stream=st))
+            self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
+                self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], stream=st))
+            last = l == L - 1
+            out = self.logits if last else self.Hbar[l + 1]
+            self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
+                self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
+                B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], stream=st))
+            if not last:
+                tab = self.hist[l + 1][w_slot]
+                self._timed("push_l%d" % (l + 1), lambda: B.history_push(
+                    tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
+                    self.Hbar[l + 1], ld[l + 1], stream=st))
+        # 3. loss gradient and backward
+        self._timed("loss_grad", lambda: B.loss_grad(
+            self.logits, ld[L], n_l, dims[L], self.y, self.dH[L], ld[L], loss=self.loss,
+            workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+        for l in range(L - 1, -1, -1):
+            last = l == L - 1
+            hout = None if last else self.Hbar[l + 1]
+            self._timed("dense_bwd_l%d" % l, lambda: B.dense_bwd(
+                self.dH[l + 1], ld[l + 1], hout, 0 if last else ld[l + 1], self.AGG[l], ld[l],
+                self.Ws[l], self.ld_w[l], n_l, dims[l], dims[l + 1],
+                B.ACT_IDENTITY if last else B.ACT_RELU, self.dW[l], self.ld_w[l],
+                self.dAGG[l], ld[l] if l >= 1 else 0,
+                workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+            if l >= 1:
+                self._timed("spmm_bwd_l%d" % l, lambda: B.spmm_bwd(
+                    self.pv, self.dAGG[l], ld[l], dims[l], self.dH[l], ld[l], stream=st))
+        self.t += 1
+
+    # ------------------------------------------------------------ accounting
+    def edges_per_step(self):
+        """CSR entries walked by the aggregation calls of one step: nnz per
+        forward layer plus the local-local entries per backward layer >= 1."""
+        return self.nnz * self.L + self.nnz_local * (self.L - 1)

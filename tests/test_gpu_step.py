@@ -1,0 +1,209 @@
+"""GPU parity of the whole partition step (pull, predict, forward, push, loss,
+backward) against the oracle's chain started from the same seeded inputs, on
+the Tiny and Medium configurations, for two consecutive steps so that the
+history ring rotates once."""
+import numpy as np
+import pytest
+
+import sat_synth as syn
+from oracle import sat_oracle as orc
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-5
+
+
+def build_problem(name, scale_nodes=None):
+    """Seeded inputs of one configuration (host arrays only)."""
+    cfg = syn.get_config(name)
+    if scale_nodes:
+        cfg["N"] = scale_nodes
+    ss = syn.substreams(cfg["seed"])
+    g = syn.make_graph(cfg, np.random.default_rng(ss["graph"]))
+    dims, L, tau = cfg["dims"], len(cfg["dims"]) - 1, cfg["tau"]
+    X = syn.normal_f32(ss["features"], g.N, dims[0])
+    wss = ss["weights"].spawn(L)
+    Ws = [syn.glorot_uniform_f32(wss[l], dims[l], dims[l + 1]) for l in range(L)]
+    pss = ss["predictor"].spawn(L)
+    omegas = [None] + [syn.predictor_params_f32(pss[l], dims[l], cfg["d_s"]) for l in range(1, L)]
+    return cfg, ss, g, X, Ws, omegas
+
+
+def fresh_history(cfg, ss, g, X, Ws):
+    """History tables per the configuration: the unpartitioned GCN's embeddings
+    of every node (computed by the oracle) plus N(0, noise_std^2) per slot."""
+    L, tau = len(Ws), cfg["tau"]
+    Hfull = orc.full_graph_gcn(g.N, g.rowptr, g.col, X, Ws)
+    nss = ss["noise"].spawn(L * tau)
+    hist = [None]
+    for l in range(1, L):
+        base = Hfull[l].astype(np.float32)
+        hist.append([base + syn.normal_f32(nss[l * tau + s], g.N, base.shape[1], std=cfg["noise_std"])
+                     for s in range(tau)])
+    return Hfull, hist
+
+
+def oracle_step(view, X, hist, order, w_slot, Ws, omegas, y, bypass=False):
+    ids = np.concatenate([view["local_ids"], view["halo_ids"]])
+    L = len(Ws)
+    halo_hat = [None]
+    for l in range(1, L):
+        win = [hist[l][s][ids] for s in order]
+        halo_hat.append(orc.predict(view, omegas[l], win, bypass=bypass))
+    st = orc.partition_step(view, X[view["local_ids"]], X[view["halo_ids"]], halo_hat, Ws, y)
+    for l in range(1, L):
+        orc.history_push(hist[l][w_slot], view["local_ids"], st["H"][l].astype(np.float32))
+    st["halo_hat"] = halo_hat
+    return st
+
+
+def neighbours(view, rows):
+    """Local rows sharing a P_in entry with any of `rows` (P_in is symmetric)."""
+    out = set()
+    for i in rows:
+        out.update(int(c) for c in view["col"][view["rowptr"][i]:view["split"][i]])
+    return out
+
+
+def check_backward(gu, view, st, dW_gpu, dAGG_gpu, dH_gpu, dims):
+    """Compare the backward pass. relu'(Z) is a 0/1 decision taken on an fp32 Z
+    by the GPU and on an fp64 Z by the oracle; where |Z| is within rounding of 0
+    either decision is valid, so rows reached by such an element are left out
+    of the row-wise comparisons and their possible contribution is added to
+    the tolerance of dW."""
+    L = len(dims) - 1
+    bad = set()                 # rows of dH^(l+1) whose value may legitimately differ
+    n_amb_total = 0
+    for l in range(L - 1, -1, -1):
+        Z, AGG = st["Z"][l], st["AGG"][l]
+        if l < L - 1:
+            thr = 2e-6 * np.sqrt(np.mean(Z * Z))   # ~20x the fp32 rounding of Z
+            amb = np.abs(Z) < thr
+            n_amb_total += int(amb.sum())
+            bad |= set(int(i) for i in np.flatnonzero(amb.any(axis=1)))
+        rows_bad = np.array(sorted(bad), dtype=np.int64)
+        ok = np.ones(view["n_local"], dtype=bool)
+        ok[rows_bad] = False
+        # dW: contribution of the doubtful rows bounds the admissible difference
+        ref = st["dW"][l]
+        slack = np.zeros_like(ref)
+        if rows_bad.size:
+            up = np.abs(dH_or(st, l + 1, L)[rows_bad])
+            slack = 2.0 * np.abs(AGG[rows_bad]).T @ up
+        rms = np.sqrt(np.mean(ref * ref))
+        err = np.abs(dW_gpu[l] - ref)
+        assert np.all(err <= RTOL * (np.abs(ref) + rms) + slack), "dW layer %d" % l
+        if l >= 1:
+            gu.assert_close(dAGG_gpu[l][ok], st["dAGG"][l][ok], RTOL, "dAGG layer %d" % l)
+            bad = neighbours(view, bad) | bad
+            ok = np.ones(view["n_local"], dtype=bool)
+            ok[np.array(sorted(bad), dtype=np.int64)] = False
+            gu.assert_close(dH_gpu[l][ok], st["dH_in"][l][ok], RTOL, "dH_in layer %d" % l)
+    return n_amb_total, len(bad)
+
+
+def dH_or(st, l, L):
+    """Gradient arriving at H^(l): loss gradient for l = L, else dH_in[l]."""
+    if l == L:
+        return orc.loss_and_grad(st["H"][L], st["y"])[1]
+    return st["dH_in"][l]
+
+
+@pytest.mark.parametrize("name,fused", [("tiny", True), ("tiny", False), ("medium", True)])
+def test_partition_step_two_steps(name, fused):
+    import torch
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd.step import PartitionStep
+    from tests import gpu_util as gu
+    print("[case] step %s fused_pull=%s" % (name, fused), flush=True)
+    cfg, ss, g, X, Ws, omegas = build_problem(name)
+    if name == "tiny":
+        cfg["d_s"] = 32
+        pss = ss["predictor"].spawn(len(Ws))
+        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32)
+                           for l in range(1, len(Ws))]
+    dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
+    m = cfg["part"]
+    Hfull, hist = fresh_history(cfg, ss, g, X, Ws)
+    view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, m)
+    oview = orc.partition_view(g.N, g.rowptr, g.col, g.part, m)
+    for k in ("rowptr", "split", "col", "halo_ids", "local_ids", "h_colptr", "h_row"):
+        assert np.array_equal(view[k], oview[k])
+    y = syn.labels_i32(ss["labels"], view["n_local"], dims[-1])
+    print("[case] n_local=%d n_halo=%d nnz=%d" % (view["n_local"], view["n_halo"], view["nnz"]),
+          flush=True)
+
+    ld = [gu.ld_for(d) for d in dims]
+    X_d = gu.to_dev(X, ld[0])
+    hist_d = [None] + [[gu.to_dev(t, ld[l]) for t in hist[l]] for l in range(1, L)]
+    ids_d = gu.to_dev(np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32))
+    Ws_d = [gu.to_dev(Ws[l], gu.ld_for(dims[l + 1], 4)) for l in range(L)]
+    preds = [None]
+    keep = []
+    for l in range(1, L):
+        pd = {k: gu.to_dev(omegas[l][k]) for k in omegas[l]}
+        keep.append(pd)
+        preds.append(sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], cfg["d_s"], tau))
+    step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, gu.to_dev(y), tau,
+                         fused_pull=fused)
+    ohist = [None] + [[t.copy() for t in hist[l]] for l in range(1, L)]
+    n_l = view["n_local"]
+    for t in range(2):
+        order = [(t + s) % tau for s in range(tau)]
+        assert step.slot_order() == order
+        step.forward_backward()
+        gu.sync()
+        st = oracle_step(oview, X, ohist, order, t % tau, Ws, omegas, y)
+        st["y"] = y
+        for l in range(1, L):
+            gu.assert_close(gu.to_host(step.Hbar[l], dims[l])[n_l:], st["halo_hat"][l], RTOL,
+                            "predicted halo rows, layer %d step %d" % (l, t))
+        for l in range(L):
+            gu.assert_close(gu.to_host(step.AGG[l], dims[l]), st["AGG"][l], RTOL, "AGG %d" % l)
+            out = step.logits if l == L - 1 else step.Hbar[l + 1]
+            gu.assert_close(gu.to_host(out, dims[l + 1])[:n_l], st["H"][l + 1], RTOL, "H %d" % (l + 1))
+        assert abs(float(step.loss.item()) - st["loss"]) <= 2 * RTOL * abs(st["loss"])
+        # push: the table rows hold exactly what the forward produced
+        for l in range(1, L):
+            tab = step.hist[l][t % tau].cpu().numpy()
+            assert np.array_equal(tab[view["local_ids"], :dims[l]],
+                                  gu.to_host(step.Hbar[l], dims[l])[:n_l])
+            others = np.setdiff1d(np.arange(g.N), view["local_ids"])
+            assert np.array_equal(tab[others, :dims[l]], ohist[l][t % tau][others])
+        dW_gpu = [gu.to_host(step.dW[l], dims[l + 1]) for l in range(L)]
+        dAGG_gpu = [None] + [gu.to_host(step.dAGG[l], dims[l]) for l in range(1, L)]
+        dH_gpu = [None] + [gu.to_host(step.dH[l], dims[l]) for l in range(1, L)]
+        n_amb, n_bad = check_backward(gu, oview, st, dW_gpu, dAGG_gpu, dH_gpu, dims)
+        print("[case] step %d ok: loss %.6f, %d relu decisions within rounding of 0, %d rows excluded"
+              % (t, st["loss"], n_amb, n_bad), flush=True)
+        assert n_bad < 0.02 * n_l
+
+
+def test_zero_staleness_invariant_on_gpu():
+    """History equal to the fresh embeddings and the predictor bypassed: the
+    partition's forward must reproduce rows V_m of the unpartitioned GCN."""
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd.step import PartitionStep
+    from tests import gpu_util as gu
+    print("[case] zero-staleness invariant, tiny", flush=True)
+    cfg, ss, g, X, Ws, omegas = build_problem("tiny")
+    dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
+    Hfull = orc.full_graph_gcn(g.N, g.rowptr, g.col, X, Ws)
+    for m in (0, 1):
+        view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, m)
+        y = syn.labels_i32(ss["labels"], view["n_local"], dims[-1])
+        ld = [gu.ld_for(d) for d in dims]
+        hist_d = [None] + [[gu.to_dev(Hfull[l].astype(np.float32), ld[l]) for _ in range(tau)]
+                           for l in range(1, L)]
+        ids_d = gu.to_dev(np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32))
+        Ws_d = [gu.to_dev(Ws[l], gu.ld_for(dims[l + 1], 4)) for l in range(L)]
+        preds = [None] + [sat.Predictor(None, None, None, None, dims[l], 32, tau, bypass=True)
+                          for l in range(1, L)]
+        step = PartitionStep(view, dims, gu.to_dev(X, ld[0]), hist_d, ids_d, Ws_d, preds,
+                             gu.to_dev(y), tau)
+        step.forward_backward()
+        gu.sync()
+        n_l = view["n_local"]
+        for l in range(1, L + 1):
+            out = step.logits if l == L else step.Hbar[l]
+            gu.assert_close(gu.to_host(out, dims[l])[:n_l], Hfull[l][view["local_ids"]], 2e-5,
+                            "H^(%d) vs unpartitioned GCN, partition %d" % (l, m))
