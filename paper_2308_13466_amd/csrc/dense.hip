@@ -18,72 +18,6 @@ namespace {
 
 using namespace sat::gemm;
 
-enum Epilogue { kStore = 0, kStoreRelu = 1, kStorePartial = 2 };
-
-template <Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, int64_t M,
-                                                          int64_t N, int64_t K,
-                                                          int64_t k_per_split, float* C,
-                                                          int64_t ldc, int64_t split_stride) {
-  __shared__ __attribute__((aligned(16))) float As[TILE_FLOATS];
-  __shared__ __attribute__((aligned(16))) float Bs[TILE_FLOATS];
-  const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
-  const int64_t n0 = static_cast<int64_t>(blockIdx.y) * BN;
-  const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * k_per_split;
-  const int64_t k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
-
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  TileRegs<BM> ra;
-  TileRegs<BN> rb;
-  if (k_begin < k_end) {
-    load_tile<BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
-    load_tile<BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
-  }
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-    __syncthreads();
-    store_tile<BM, LA>(ra, As, t);
-    store_tile<BN, LB>(rb, Bs, t);
-    __syncthreads();
-    if (k0 + BK < k_end) {
-      load_tile<BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
-      load_tile<BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
-    }
-    mma_step(As, Bs, wm, wn, lane, acc);
-  }
-
-  float* Cb = C;
-  if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * split_stride;
-  const int col_in_block = lane & 31;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int64_t n = n0 + wn * 64 + j * 32 + col_in_block;
-      if (n >= N) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
-        if (m < M) {
-          float x = acc[i][j][r];
-          if constexpr (EPI == kStoreRelu) x = x > 0.f ? x : 0.f;
-          Cb[m * ldc + n] = x;
-        }
-      }
-    }
-  }
-}
-
 // out[i] = sum_s part[s * stride + i] for s ascending (fixed order).
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part,
                                                               int64_t stride, int splits,
@@ -159,10 +93,10 @@ extern "C" sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, in
   const int64_t K = d_in;
   if (act == SAT_ACT_RELU)
     gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStoreRelu>
-        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, 0);
+        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, EpiArgs{});
   else
     gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStore>
-        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, 0);
+        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, EpiArgs{});
   return sat::check_launch();
 }
 
@@ -214,11 +148,11 @@ extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* H
     if (relu)
       gemm_f32_kernel<Layout::MNContig, false, Layout::MNContig, true, kStorePartial>
           <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
-                                      p.split_stride);
+                                      EpiArgs{p.split_stride, nullptr, 0, nullptr, 0, 0});
     else
       gemm_f32_kernel<Layout::MNContig, false, Layout::MNContig, false, kStorePartial>
           <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
-                                      p.split_stride);
+                                      EpiArgs{p.split_stride, nullptr, 0, nullptr, 0, 0});
     if ((st = sat::check_launch()) != SAT_OK) return st;
     const int64_t total = static_cast<int64_t>(d_in) * d_out;
     reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
@@ -236,10 +170,10 @@ extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* H
     const int64_t K = d_out;
     if (relu)
       gemm_f32_kernel<Layout::KContig, true, Layout::KContig, false, kStore>
-          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, 0);
+          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, EpiArgs{});
     else
       gemm_f32_kernel<Layout::KContig, false, Layout::KContig, false, kStore>
-          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, 0);
+          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, EpiArgs{});
     if ((st = sat::check_launch()) != SAT_OK) return st;
   }
   return SAT_OK;

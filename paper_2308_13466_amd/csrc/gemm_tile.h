@@ -142,6 +142,91 @@ __device__ __forceinline__ int acc_row(int r, int lane) {
   return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
 }
 
+// kStore: C = acc; kStoreRelu: C = max(acc, 0); kStorePartial: slice blockIdx.z of a
+// split-K workspace; kStoreAddRows: C[m, :] = acc + add[row(m), :] with
+// row(m) = add_ids ? add_ids[m] : add_base + m (rows outside [0, add_rows) are skipped).
+enum Epilogue { kStore = 0, kStoreRelu = 1, kStorePartial = 2, kStoreAddRows = 3 };
+
+struct EpiArgs {
+  int64_t split_stride;
+  const float* add;
+  int64_t ld_add;
+  const int32_t* add_ids;
+  int64_t add_base;
+  int64_t add_rows;
+};
+
+
+template <Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, int64_t M,
+                                                          int64_t N, int64_t K,
+                                                          int64_t k_per_split, float* C,
+                                                          int64_t ldc, EpiArgs ep) {
+  __shared__ __attribute__((aligned(16))) float As[TILE_FLOATS];
+  __shared__ __attribute__((aligned(16))) float Bs[TILE_FLOATS];
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
+  const int64_t n0 = static_cast<int64_t>(blockIdx.y) * BN;
+  const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * k_per_split;
+  const int64_t k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  TileRegs<BM> ra;
+  TileRegs<BN> rb;
+  if (k_begin < k_end) {
+    load_tile<BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
+    load_tile<BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
+  }
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    __syncthreads();
+    store_tile<BM, LA>(ra, As, t);
+    store_tile<BN, LB>(rb, Bs, t);
+    __syncthreads();
+    if (k0 + BK < k_end) {
+      load_tile<BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
+      load_tile<BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
+    }
+    mma_step(As, Bs, wm, wn, lane, acc);
+  }
+
+  float* Cb = C;
+  if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * ep.split_stride;
+  const int col_in_block = lane & 31;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int64_t n = n0 + wn * 64 + j * 32 + col_in_block;
+      if (n >= N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
+        if (m < M) {
+          float x = acc[i][j][r];
+          if constexpr (EPI == kStoreRelu) x = x > 0.f ? x : 0.f;
+          if constexpr (EPI == kStoreAddRows) {
+            const int64_t src = ep.add_ids ? static_cast<int64_t>(ep.add_ids[m]) : ep.add_base + m;
+            if (src < 0 || src >= ep.add_rows) continue;  // bad id: leave the row alone
+            x += ep.add[src * ep.ld_add + n];
+          }
+          Cb[m * ldc + n] = x;
+        }
+      }
+    }
+  }
+}
+
+
 }  // namespace gemm
 }  // namespace sat
 

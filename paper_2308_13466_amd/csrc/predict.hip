@@ -12,10 +12,14 @@
 //   LDS k-major, which is exactly the A-operand layout of the next step's
 //   recurrent product. Only S = h_tau [n_bar, d_s] is written to memory. The
 //   window rows can be read straight out of the history table through ids.
-//  hop_kernel: a workgroup owns 64 halo nodes: gathers and weights the S rows
-//   of each node's local neighbours (transposed halo block) plus its own,
-//   keeps the [64, d_s] aggregate in LDS, multiplies by Wg on the MFMA pipe and
-//   adds the newest cached embedding in the epilogue.
+//  hop: the aggregation kernel of spmm.hip walks the transposed halo block with
+//   the diagonal term (A_hat[u,u] S_u) folded in and leaves the [n_halo, d_s]
+//   aggregate in the workspace; the tile GEMM multiplies it by Wg and adds the
+//   newest cached embedding, fetched through the id list, in its epilogue.
+//   (Halo nodes have very few local neighbours each, so the gather is a
+//   latency problem: it needs many independent rows in flight, which the
+//   row-per-wavefront aggregation kernel provides and a fused tile kernel
+//   walking its rows one after another did not.)
 #include <math.h>
 
 #include "gemm_tile.h"
@@ -26,6 +30,11 @@ namespace sat {
 sat_status row_gather(const void* src, int64_t ld_src, void* dst, int64_t ld_dst,
                       const int32_t* ids, int64_t id_base, int64_t n, int64_t n_src_rows,
                       int32_t d, hipStream_t stream);
+// spmm.hip: Y = M X (+ diag(self_val) X[self_off + i])
+sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const int32_t* col,
+                       const float* val, const float* X, int64_t ld_x, int64_t n_x_rows, float* Y,
+                       int64_t ld_y, int64_t n_rows, int32_t d, const float* self_val,
+                       int64_t self_off, hipStream_t stream);
 }  // namespace sat
 
 namespace {
@@ -180,121 +189,6 @@ __global__ __launch_bounds__(256) void lstm_kernel(SlotPtrs slots, int tau, int6
   }
 }
 
-template <int DS>
-__global__ __launch_bounds__(256) void hop_kernel(const int64_t* __restrict__ h_colptr,
-                                                  const int32_t* __restrict__ h_row,
-                                                  const float* __restrict__ h_val,
-                                                  const float* __restrict__ h_self,
-                                                  int64_t n_local, int64_t n_halo,
-                                                  const float* __restrict__ S,
-                                                  const float* __restrict__ Wg, int d,
-                                                  const float* __restrict__ newest,
-                                                  int64_t n_rows_slot, int64_t ld_slot,
-                                                  const int32_t* __restrict__ ids,
-                                                  float* __restrict__ Hbar, int64_t ld) {
-  constexpr int BMH = 64;             // halo nodes per workgroup
-  constexpr int G = DS / 4;           // lanes covering one S row with 16-byte loads
-  constexpr int NG = kWave / G;       // neighbours taken at once by a wavefront
-  constexpr int LDG = BMH + 4;
-  __shared__ __attribute__((aligned(16))) float Ag[DS * LDG];      // aggregate, k-major
-  __shared__ __attribute__((aligned(16))) float Bs[BK * LDS_LD];   // Wg tile [32 x 128]
-
-  const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int64_t u0 = static_cast<int64_t>(blockIdx.x) * BMH;
-
-  // ---- phase 1: Ag[:, m] = h_self[u] S[n_local+u] + sum_k h_val[k] S[h_row[k]]
-  {
-    const int gl = lane % G, grp = lane / G;
-    for (int rr = 0; rr < BMH / 4; ++rr) {
-      const int m = wave * (BMH / 4) + rr;
-      const int64_t u = u0 + m;
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-      if (u < n_halo) {
-        if (grp == 0) {
-          const f32x4 x = *reinterpret_cast<const f32x4*>(S + (n_local + u) * DS + gl * 4);
-          acc = h_self[u] * x;
-        }
-        const int64_t s = h_colptr[u], e = h_colptr[u + 1];
-        for (int64_t base = s; base < e; base += kWave) {
-          const int cnt = static_cast<int>(e - base < kWave ? e - base : kWave);
-          int32_t rj = 0;
-          float vj = 0.f;
-          if (lane < cnt) {
-            rj = h_row[base + lane];
-            vj = h_val[base + lane];
-          }
-          const bool ok = static_cast<uint32_t>(rj) < static_cast<uint64_t>(n_local);
-          for (int j = 0; j < cnt; j += NG) {
-            const int32_t r2 = __shfl(rj, j + grp);
-            const float v2 = __shfl(vj, j + grp);
-            const bool ok2 = __shfl(static_cast<int>(ok), j + grp) != 0 && (j + grp < cnt);
-            if (ok2) {
-              const f32x4 x = *reinterpret_cast<const f32x4*>(S + static_cast<int64_t>(r2) * DS + gl * 4);
-              acc += v2 * x;
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int off = G; off < kWave; off <<= 1) {
-        acc.x += __shfl_xor(acc.x, off);
-        acc.y += __shfl_xor(acc.y, off);
-        acc.z += __shfl_xor(acc.z, off);
-        acc.w += __shfl_xor(acc.w, off);
-      }
-      if (grp == 0) {
-        Ag[(gl * 4 + 0) * LDG + m] = acc.x;
-        Ag[(gl * 4 + 1) * LDG + m] = acc.y;
-        Ag[(gl * 4 + 2) * LDG + m] = acc.z;
-        Ag[(gl * 4 + 3) * LDG + m] = acc.w;
-      }
-    }
-  }
-
-  // ---- phase 2: Hbar[n_local + u, :] = newest[u, :] + Ag^T Wg, 128 columns at a time
-  const int wm = wave >> 1, wn = wave & 1;
-  const int kr = lane >> 5, c = lane & 31;
-  const Operand opg{Wg, static_cast<int64_t>(d), nullptr, 0};
-  // table row of the newest embedding for the rows this lane stores
-  for (int n0 = 0; n0 < d; n0 += 128) {
-    f32x16 acc[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-    TileRegs<128> rb;
-    load_tile<128, Layout::MNContig, false>(opg, n0, d, 0, DS, rb, t);
-    for (int k0 = 0; k0 < DS; k0 += BK) {
-      __syncthreads();  // also orders phase 1's Ag writes before the first read
-      store_tile<128, Layout::MNContig>(rb, Bs, t);
-      __syncthreads();
-      if (k0 + BK < DS) load_tile<128, Layout::MNContig, false>(opg, n0, d, k0 + BK, DS, rb, t);
-#pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        const float a = Ag[(k0 + kk + kr) * LDG + 32 * wm + c];
-        const float b0 = Bs[(kk + kr) * LDS_LD + 64 * wn + c];
-        const float b1 = Bs[(kk + kr) * LDS_LD + 64 * wn + 32 + c];
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc[1], 0, 0, 0);
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int64_t u = u0 + 32 * wm + acc_row(r, lane);
-      if (u >= n_halo) continue;
-      int64_t src = ids ? static_cast<int64_t>(ids[n_local + u]) : n_local + u;
-      if (src < 0 || src >= n_rows_slot) continue;  // bad id: leave the row alone
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int col = n0 + 64 * wn + 32 * j + c;
-        if (col < d) Hbar[(n_local + u) * ld + col] = newest[src * ld_slot + col] + acc[j][r];
-      }
-    }
-  }
-}
-
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 }  // namespace
@@ -304,7 +198,9 @@ extern "C" int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, 
   (void)d;
   (void)tau;
   if (n_local < 0 || n_halo < 0 || d_s <= 0) return 0;
-  return round_up((n_local + n_halo) * static_cast<int64_t>(d_s) * 4, 256);
+  // S [n_bar, d_s] followed by the hop aggregate [n_halo, d_s]
+  return round_up((n_local + n_halo) * static_cast<int64_t>(d_s) * 4, 256) +
+         round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256);
 }
 
 extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w,
@@ -358,13 +254,6 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
     lstm_kernel<DS><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(               \
         sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->Wx, w->Wh, w->b, S);              \
   } while (0)
-#define SAT_HOP(DS)                                                                           \
-  do {                                                                                        \
-    const int64_t blocks = (pv->n_halo + 63) / 64;                                            \
-    hop_kernel<DS><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(                \
-        pv->h_colptr, pv->h_row, pv->h_val, pv->h_self, pv->n_local, pv->n_halo, S, w->Wg, d, \
-        newest, n_rows_slot, ld_slot, ids, static_cast<float*>(Hbar), ld);                    \
-  } while (0)
   switch (w->d_s) {
     case 32: SAT_LSTM(32); break;
     case 64: SAT_LSTM(64); break;
@@ -372,12 +261,22 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   }
   sat_status rc = sat::check_launch();
   if (rc != SAT_OK) return rc;
-  switch (w->d_s) {
-    case 32: SAT_HOP(32); break;
-    case 64: SAT_HOP(64); break;
-    default: SAT_HOP(128); break;
-  }
 #undef SAT_LSTM
-#undef SAT_HOP
+  // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
+  float* Agg = S + round_up(n_bar * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
+  rc = sat::launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val, S, w->d_s,
+                        pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, pv->h_self, pv->n_local, st);
+  if (rc != SAT_OK) return rc;
+  // hop, part 2: Hbar[n_local + u, :] = newest[row(u), :] + Agg[u, :] Wg
+  {
+    const int64_t gx = (pv->n_halo + BM - 1) / BM;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d + BN - 1) / BN), 1);
+    const Operand a{Agg, static_cast<int64_t>(w->d_s), nullptr, 0};
+    const Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
+    const EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
+                     n_rows_slot};
+    gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStoreAddRows>
+        <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
+  }
   return sat::check_launch();
 }

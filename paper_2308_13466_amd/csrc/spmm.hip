@@ -2,18 +2,27 @@
 // forward) and its transpose products (appendix, SAT backward).
 //
 // The work is a gather of nnz feature rows: 2 flops per 4 gathered bytes, so
-// the memory system is the only bound. Mapping for 64-wide wavefronts:
-//   * one wavefront per CSR row (row-split); the row's column ids and values
-//     are read 64 at a time with one coalesced access and handed out with
-//     cross-lane reads;
+// the memory system is the only bound and the design goal is bytes in flight.
+// Mapping for 64-wide wavefronts:
+//   * a workgroup of 8 wavefronts owns 8 consecutive CSR rows, one row per
+//     wavefront (row-split);
+//   * the row's column ids and values are read 64 at a time with one coalesced
+//     access and handed out with cross-lane reads;
 //   * a group of G lanes covers a feature row with 16-byte loads (G = 64 for
-//     d >= 256 floats: exactly one 1 KiB row per wavefront access); for narrower
-//     rows the 64/G groups take different neighbours at once and are summed
-//     with lane-xor shuffles at the end;
-//   * up to NCH 16-byte accumulators per lane, so rows up to 1024 floats wide
-//     are aggregated in a single walk of the index list.
+//     256 floats: one 1 KiB row per wavefront access); for narrower rows the
+//     64/G groups take different neighbours at once and are summed with
+//     lane-xor shuffles at the end;
+//   * U neighbours per group are fetched back to back before any of them is
+//     used, so a wavefront keeps U * NCH KiB of gathers in flight;
+//   * up to NCH 16-byte accumulators per lane: rows up to 1024 floats wide are
+//     aggregated in a single walk of the index list;
+//   * degree skew: a row longer than kLongRow entries is not walked by its
+//     owner alone; after the short rows are done, all 8 wavefronts of the
+//     workgroup split it into 8 contiguous pieces and their partial sums are
+//     added through LDS in a fixed order (deterministic, no atomics).
 // The same kernel serves P_in^T (the local-column prefix of each row, P_in
-// being symmetric) and P_out^T (through the transposed halo block).
+// being symmetric), P_out^T (through the transposed halo block) and the
+// predictor's hop (transposed halo block plus a diagonal term).
 #include "sat_internal.h"
 
 namespace {
@@ -21,64 +30,84 @@ namespace {
 using sat::kWave;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int G, int NCH>
-__global__ __launch_bounds__(256) void spmm_row_wave_kernel(
-    const int64_t* __restrict__ row_begin, const int64_t* __restrict__ row_end,
-    const int32_t* __restrict__ col, const float* __restrict__ val, const float* __restrict__ X,
-    int64_t ld_x, int64_t n_x_rows, float* __restrict__ Y, int64_t ld_y, int64_t n_rows,
-    int32_t d) {
-  constexpr int NG = kWave / G;  // neighbours processed at once by a wavefront
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + wave;
-  if (row >= n_rows) return;
+constexpr int kRowsPerBlock = 8;   // wavefronts per workgroup
+constexpr int kLongRow = 512;      // entries; longer rows are walked cooperatively
+
+struct SpmmArgs {
+  const int64_t* row_begin;
+  const int64_t* row_end;
+  const int32_t* col;
+  const float* val;
+  const float* X;
+  int64_t ld_x;
+  int64_t n_x_rows;
+  float* Y;
+  int64_t ld_y;
+  int64_t n_rows;
+  int32_t d;
+  const float* self_val;  // nullable: Y[i] += self_val[i] * X[self_off + i]
+  int64_t self_off;
+};
+
+// acc += sum over entries [s, e) of val * X[col]; all lanes of the wavefront take part.
+template <int G, int NCH, int U>
+__device__ __forceinline__ void walk_entries(const SpmmArgs& a, int64_t s, int64_t e, int col_base,
+                                             int lane, f32x4 (&acc)[NCH]) {
+  constexpr int NG = kWave / G;
   const int gl = lane % G;
   const int grp = lane / G;
-  const int col_base = blockIdx.y * (G * 4 * NCH);
-  const int64_t s = row_begin[row];
-  const int64_t e = row_end[row];
-
-  f32x4 acc[NCH];
-#pragma unroll
-  for (int ch = 0; ch < NCH; ++ch) acc[ch] = f32x4{0.f, 0.f, 0.f, 0.f};
-
+  const float* Xc = a.X + col_base;
   for (int64_t base = s; base < e; base += kWave) {
     const int cnt = static_cast<int>(e - base < kWave ? e - base : kWave);
     int32_t c = 0;
     float v = 0.f;
     if (lane < cnt) {
-      c = col[base + lane];
-      v = val[base + lane];
+      c = a.col[base + lane];
+      v = a.val[base + lane];
     }
-    const bool ok = static_cast<uint32_t>(c) < static_cast<uint64_t>(n_x_rows);
-    for (int j = 0; j < cnt; j += NG) {
-      int32_t cj;
-      float vj;
-      bool okj;
-      if constexpr (G == kWave) {
-        cj = __builtin_amdgcn_readlane(c, j);
-        vj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), j));
-        okj = __builtin_amdgcn_readlane(static_cast<int>(ok), j) != 0;
-      } else {
-        cj = __shfl(c, j + grp);
-        vj = __shfl(v, j + grp);
-        okj = __shfl(static_cast<int>(ok), j + grp) != 0 && (j + grp < cnt);
+    if (static_cast<uint32_t>(c) >= static_cast<uint64_t>(a.n_x_rows)) {  // bad id: no contribution
+      c = 0;
+      v = 0.f;
+    }
+    for (int j0 = 0; j0 < cnt; j0 += NG * U) {
+      int32_t cj[U];
+      float vj[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        // entries past the end re-read the last valid row with weight 0
+        const int idx = j0 + u * NG + grp;
+        const int idc = idx < cnt ? idx : cnt - 1;
+        if constexpr (G == kWave) {
+          cj[u] = __builtin_amdgcn_readlane(c, idc);
+          vj[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), idc));
+        } else {
+          cj[u] = __shfl(c, idc);
+          vj[u] = __shfl(v, idc);
+        }
+        if (idx >= cnt) vj[u] = 0.f;
       }
-      if (okj) {
-        const float* xr = X + static_cast<int64_t>(cj) * ld_x + col_base;
+      f32x4 x[U][NCH];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const float* xr = Xc + static_cast<int64_t>(cj[u]) * a.ld_x;
 #pragma unroll
         for (int ch = 0; ch < NCH; ++ch) {
           const int c0 = (ch * G + gl) * 4;
-          if (col_base + c0 < d) {
-            const f32x4 x = *reinterpret_cast<const f32x4*>(xr + c0);
-            acc[ch] += vj * x;
-          }
+          x[u][ch] = (col_base + c0 < a.d) ? *reinterpret_cast<const f32x4*>(xr + c0)
+                                           : f32x4{0.f, 0.f, 0.f, 0.f};
         }
       }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) acc[ch] += vj[u] * x[u][ch];
     }
   }
+}
 
-  if constexpr (NG > 1) {
+template <int G, int NCH>
+__device__ __forceinline__ void reduce_groups(f32x4 (&acc)[NCH]) {
+  if constexpr (G < kWave) {
 #pragma unroll
     for (int off = G; off < kWave; off <<= 1) {
 #pragma unroll
@@ -90,52 +119,153 @@ __global__ __launch_bounds__(256) void spmm_row_wave_kernel(
       }
     }
   }
-  if (grp == 0) {
-    float* yr = Y + row * ld_y + col_base;
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) {
-      const int c0 = (ch * G + gl) * 4;
-      const int left = d - (col_base + c0);
-      if (left >= 4) {
-        *reinterpret_cast<f32x4*>(yr + c0) = acc[ch];
-      } else if (left > 0) {
-        yr[c0] = acc[ch].x;
-        if (left > 1) yr[c0 + 1] = acc[ch].y;
-        if (left > 2) yr[c0 + 2] = acc[ch].z;
-      }
-    }
+}
+
+__device__ __forceinline__ void store_masked(float* y, int left, const f32x4& v) {
+  if (left >= 4) {
+    *reinterpret_cast<f32x4*>(y) = v;
+  } else if (left > 0) {
+    y[0] = v.x;
+    if (left > 1) y[1] = v.y;
+    if (left > 2) y[2] = v.z;
   }
 }
 
-// Y[n_rows, d] = M * X where row i of M is (col, val)[row_begin[i] .. row_end[i]).
+template <int G, int NCH, int U>
+__global__ __launch_bounds__(kRowsPerBlock * kWave) void spmm_kernel(SpmmArgs a) {
+  constexpr int kPartFloats = G * 4 * NCH;  // floats of one wavefront's partial row
+  __shared__ int64_t long_s[kRowsPerBlock], long_e[kRowsPerBlock];
+  __shared__ __attribute__((aligned(16))) float part[kRowsPerBlock][kPartFloats];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock;
+  const int64_t row = row0 + wave;
+  const int gl = lane % G;
+  const int grp = lane / G;
+  const int col_base = blockIdx.y * kPartFloats;
+
+  int64_t s = 0, e = 0;
+  if (row < a.n_rows) {
+    s = a.row_begin[row];
+    e = a.row_end[row];
+  }
+  const bool is_long = (e - s) > kLongRow;
+  if (lane == 0) {
+    long_s[wave] = is_long ? s : 0;
+    long_e[wave] = is_long ? e : 0;
+  }
+
+  // ---- short rows: one wavefront each
+  if (row < a.n_rows && !is_long) {
+    f32x4 acc[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) acc[ch] = f32x4{0.f, 0.f, 0.f, 0.f};
+    walk_entries<G, NCH, U>(a, s, e, col_base, lane, acc);
+    if (a.self_val != nullptr && grp == 0) {
+      const float sv = a.self_val[row];
+      const float* xr = a.X + (a.self_off + row) * a.ld_x + col_base;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        const int c0 = (ch * G + gl) * 4;
+        if (col_base + c0 < a.d) acc[ch] += sv * *reinterpret_cast<const f32x4*>(xr + c0);
+      }
+    }
+    reduce_groups<G, NCH>(acc);
+    if (grp == 0) {
+      float* yr = a.Y + row * a.ld_y + col_base;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        const int c0 = (ch * G + gl) * 4;
+        store_masked(yr + c0, a.d - (col_base + c0), acc[ch]);
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- long rows of this workgroup: all wavefronts share each one
+  for (int w = 0; w < kRowsPerBlock; ++w) {
+    const int64_t ls = long_s[w], le = long_e[w];
+    if (le <= ls) continue;  // uniform over the workgroup
+    const int64_t piece = ((le - ls + kRowsPerBlock - 1) / kRowsPerBlock + kWave - 1) / kWave * kWave;
+    int64_t ps = ls + wave * piece;
+    int64_t pe = ps + piece < le ? ps + piece : le;
+    if (ps > le) ps = le;
+    f32x4 acc[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) acc[ch] = f32x4{0.f, 0.f, 0.f, 0.f};
+    walk_entries<G, NCH, U>(a, ps, pe, col_base, lane, acc);
+    const int64_t lrow = row0 + w;
+    if (a.self_val != nullptr && wave == 0 && grp == 0) {
+      const float sv = a.self_val[lrow];
+      const float* xr = a.X + (a.self_off + lrow) * a.ld_x + col_base;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        const int c0 = (ch * G + gl) * 4;
+        if (col_base + c0 < a.d) acc[ch] += sv * *reinterpret_cast<const f32x4*>(xr + c0);
+      }
+    }
+    reduce_groups<G, NCH>(acc);
+    if (grp == 0) {
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch)
+        *reinterpret_cast<f32x4*>(&part[wave][(ch * G + gl) * 4]) = acc[ch];
+    }
+    __syncthreads();
+    // fixed-order sum of the 8 partial rows, 16 bytes per thread
+    for (int q = threadIdx.x; q < kPartFloats / 4; q += kRowsPerBlock * kWave) {
+      f32x4 sum = *reinterpret_cast<const f32x4*>(&part[0][q * 4]);
+#pragma unroll
+      for (int k = 1; k < kRowsPerBlock; ++k) sum += *reinterpret_cast<const f32x4*>(&part[k][q * 4]);
+      store_masked(a.Y + lrow * a.ld_y + col_base + q * 4, a.d - (col_base + q * 4), sum);
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+namespace sat {
+
+// Y[n_rows, d] = M * X (+ diag(self_val) * X[self_off + i]) where row i of M is
+// (col, val)[row_begin[i] .. row_end[i]). Pointers are device pointers; X and Y
+// 16-byte aligned with ld % 4 == 0 (checked by the callers).
 sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const int32_t* col,
                        const float* val, const float* X, int64_t ld_x, int64_t n_x_rows, float* Y,
-                       int64_t ld_y, int64_t n_rows, int32_t d, hipStream_t stream) {
+                       int64_t ld_y, int64_t n_rows, int32_t d, const float* self_val,
+                       int64_t self_off, hipStream_t stream) {
   if (n_rows == 0 || d == 0) return SAT_OK;
-  const int64_t bx = (n_rows + 3) / 4;
+  const int64_t bx = (n_rows + kRowsPerBlock - 1) / kRowsPerBlock;
   if (bx > INT32_MAX) return SAT_EUNSUPPORTED;
   const int nvec = (d + 3) / 4;
-  const dim3 block(256);
-#define SAT_SPMM_LAUNCH(G, NCH)                                                               \
+  const dim3 block(kRowsPerBlock * kWave);
+  const SpmmArgs a{row_begin, row_end, col, val, X, ld_x, n_x_rows, Y, ld_y, n_rows, d, self_val,
+                   self_off};
+#define SAT_SPMM_LAUNCH(G, NCH, U)                                                            \
   do {                                                                                        \
     const int per_pass = (G) * 4 * (NCH);                                                     \
     const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>((d + per_pass - 1) / per_pass)); \
-    spmm_row_wave_kernel<G, NCH><<<grid, block, 0, stream>>>(row_begin, row_end, col, val, X, \
-                                                             ld_x, n_x_rows, Y, ld_y, n_rows, d); \
+    spmm_kernel<G, NCH, U><<<grid, block, 0, stream>>>(a);                                    \
   } while (0)
-  if (nvec <= 1) SAT_SPMM_LAUNCH(1, 1);
-  else if (nvec <= 2) SAT_SPMM_LAUNCH(2, 1);
-  else if (nvec <= 4) SAT_SPMM_LAUNCH(4, 1);
-  else if (nvec <= 8) SAT_SPMM_LAUNCH(8, 1);
-  else if (nvec <= 16) SAT_SPMM_LAUNCH(16, 1);
-  else if (nvec <= 32) SAT_SPMM_LAUNCH(32, 1);
-  else if (nvec <= 64) SAT_SPMM_LAUNCH(64, 1);
-  else if (nvec <= 128) SAT_SPMM_LAUNCH(64, 2);
-  else if (nvec <= 192) SAT_SPMM_LAUNCH(64, 3);
-  else SAT_SPMM_LAUNCH(64, 4);
+  if (nvec <= 1) SAT_SPMM_LAUNCH(1, 1, 4);
+  else if (nvec <= 2) SAT_SPMM_LAUNCH(2, 1, 4);
+  else if (nvec <= 4) SAT_SPMM_LAUNCH(4, 1, 4);
+  else if (nvec <= 8) SAT_SPMM_LAUNCH(8, 1, 4);
+  else if (nvec <= 16) SAT_SPMM_LAUNCH(16, 1, 4);
+  else if (nvec <= 32) SAT_SPMM_LAUNCH(32, 1, 4);
+  else if (nvec <= 64) SAT_SPMM_LAUNCH(64, 1, 8);
+  else if (nvec <= 128) SAT_SPMM_LAUNCH(64, 2, 4);
+  else if (nvec <= 192) SAT_SPMM_LAUNCH(64, 3, 2);
+  else SAT_SPMM_LAUNCH(64, 4, 2);
 #undef SAT_SPMM_LAUNCH
   return sat::check_launch();
 }
+
+}  // namespace sat
+
+namespace {
+
+using sat::launch_spmm;
 
 sat_status validate_view(const sat_part_view* pv) {
   if (!pv) return SAT_EINVAL;
@@ -175,7 +305,7 @@ extern "C" sat_status sat_spmm_fwd(const sat_part_view* pv, const void* Hbar, in
   if ((st = validate_dense(AGG, pv->n_local, ld_out, d)) != SAT_OK) return st;
   return launch_spmm(pv->rowptr, pv->rowptr + 1, pv->col, pv->val, static_cast<const float*>(Hbar),
                      ld_in, pv->n_local + pv->n_halo, static_cast<float*>(AGG), ld_out,
-                     pv->n_local, d, static_cast<hipStream_t>(stream));
+                     pv->n_local, d, nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
 extern "C" sat_status sat_spmm_bwd(const sat_part_view* pv, const void* dAGG, int64_t ld_in,
@@ -198,9 +328,9 @@ extern "C" sat_status sat_spmm_bwd(const sat_part_view* pv, const void* dAGG, in
   hipStream_t s = static_cast<hipStream_t>(stream);
   // P_in^T = P_in: row i's local columns are [rowptr[i], split[i])
   st = launch_spmm(pv->rowptr, pv->split, pv->col, pv->val, static_cast<const float*>(dAGG), ld_in,
-                   pv->n_local, static_cast<float*>(dH_local), ld_out, pv->n_local, d, s);
+                   pv->n_local, static_cast<float*>(dH_local), ld_out, pv->n_local, d, nullptr, 0, s);
   if (st != SAT_OK || !dH_halo) return st;
   return launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val,
                      static_cast<const float*>(dAGG), ld_in, pv->n_local,
-                     static_cast<float*>(dH_halo), ld_halo, pv->n_halo, d, s);
+                     static_cast<float*>(dH_halo), ld_halo, pv->n_halo, d, nullptr, 0, s);
 }
