@@ -204,10 +204,31 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, 
   const int col_in_block = lane & 31;
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
+    // rows of the residual operand for this lane's 16 accumulator rows; fetched
+    // for all rows before any store so the loads overlap instead of queueing
+    // behind the stores
+    int64_t src[16];
+    if constexpr (EPI == kStoreAddRows) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
+        int64_t sr = -1;
+        if (m < M) {
+          sr = ep.add_ids ? static_cast<int64_t>(ep.add_ids[m]) : ep.add_base + m;
+          if (sr < 0 || sr >= ep.add_rows) sr = -1;  // bad id: leave the row alone
+        }
+        src[r] = sr;
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int64_t n = n0 + wn * 64 + j * 32 + col_in_block;
       if (n >= N) continue;
+      float addv[16];
+      if constexpr (EPI == kStoreAddRows) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) addv[r] = src[r] >= 0 ? ep.add[src[r] * ep.ld_add + n] : 0.f;
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
@@ -215,9 +236,8 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, 
           float x = acc[i][j][r];
           if constexpr (EPI == kStoreRelu) x = x > 0.f ? x : 0.f;
           if constexpr (EPI == kStoreAddRows) {
-            const int64_t src = ep.add_ids ? static_cast<int64_t>(ep.add_ids[m]) : ep.add_base + m;
-            if (src < 0 || src >= ep.add_rows) continue;  // bad id: leave the row alone
-            x += ep.add[src * ep.ld_add + n];
+            if (src[r] < 0) continue;
+            x += addv[r];
           }
           Cb[m * ldc + n] = x;
         }

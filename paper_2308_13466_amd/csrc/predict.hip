@@ -49,15 +49,27 @@ struct SlotPtrs {
 
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
 
+// out[c * R + r] = in[r * C + c]: the LSTM weights are re-laid k-major once per
+// call so that the gate-weight tiles load with coalesced 16-byte accesses and go
+// to LDS without a transposing store.
+__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, int R, int C,
+                                                        float* __restrict__ out) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= R * C) return;
+  const int c = idx / R, r = idx - c * R;
+  out[idx] = in[r * C + c];
+}
+
+// WxT [d, 4*DS] and WhT [DS, 4*DS] are the transposed (k-major) weights.
 template <int DS>
-__global__ __launch_bounds__(256) void lstm_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
-                                                   int64_t ld_slot,
-                                                   const int32_t* __restrict__ ids,
-                                                   int64_t n_nodes, int d,
-                                                   const float* __restrict__ Wx,
-                                                   const float* __restrict__ Wh,
-                                                   const float* __restrict__ bias,
-                                                   float* __restrict__ S) {
+__global__ __launch_bounds__(256, DS <= 64 ? 2 : 1) void lstm_kernel(SlotPtrs slots, int tau,
+                                                      int64_t n_rows_slot, int64_t ld_slot,
+                                                      const int32_t* __restrict__ ids,
+                                                      int64_t n_nodes, int d,
+                                                      const float* __restrict__ WxT,
+                                                      const float* __restrict__ WhT,
+                                                      const float* __restrict__ bias,
+                                                      float* __restrict__ S) {
   constexpr int WN = DS / 32;   // wavefronts along hidden units
   constexpr int WM = 4 / WN;    // wavefronts along nodes
   constexpr int BMR = 32 * WM;  // nodes per workgroup
@@ -95,8 +107,8 @@ __global__ __launch_bounds__(256) void lstm_kernel(SlotPtrs slots, int tau, int6
   for (int r = 0; r < 16; ++r) cstate[r] = 0.f;
   float hval[16];
 
-  const Operand opx{Wx, static_cast<int64_t>(d), nullptr, 0};
-  const Operand oph{Wh, static_cast<int64_t>(DS), nullptr, 0};
+  const Operand opx{WxT, static_cast<int64_t>(NB), nullptr, 0};
+  const Operand oph{WhT, static_cast<int64_t>(NB), nullptr, 0};
 
   for (int s = 0; s < tau; ++s) {
     f32x16 acc[4];
@@ -126,15 +138,15 @@ __global__ __launch_bounds__(256) void lstm_kernel(SlotPtrs slots, int tau, int6
     TileRegs<BMR> ra;
     TileRegs<NB> rb;
     load_x(0, ra);
-    load_tile<NB, Layout::KContig, false>(opx, 0, NB, 0, d, rb, t);
+    load_tile<NB, Layout::MNContig, false>(opx, 0, NB, 0, d, rb, t);
     for (int k0 = 0; k0 < d; k0 += BK) {
       __syncthreads();
       store_tile<BMR, Layout::KContig>(ra, As, t);
-      store_tile<NB, Layout::KContig>(rb, Bs, t);
+      store_tile<NB, Layout::MNContig>(rb, Bs, t);
       __syncthreads();
       if (k0 + BK < d) {
         load_x(k0 + BK, ra);
-        load_tile<NB, Layout::KContig, false>(opx, 0, NB, k0 + BK, d, rb, t);
+        load_tile<NB, Layout::MNContig, false>(opx, 0, NB, k0 + BK, d, rb, t);
       }
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 2) {
@@ -148,12 +160,12 @@ __global__ __launch_bounds__(256) void lstm_kernel(SlotPtrs slots, int tau, int6
     }
     // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
     if (s > 0) {
-      load_tile<NB, Layout::KContig, false>(oph, 0, NB, 0, DS, rb, t);
+      load_tile<NB, Layout::MNContig, false>(oph, 0, NB, 0, DS, rb, t);
       for (int k0 = 0; k0 < DS; k0 += BK) {
         __syncthreads();
-        store_tile<NB, Layout::KContig>(rb, Bs, t);
+        store_tile<NB, Layout::MNContig>(rb, Bs, t);
         __syncthreads();
-        if (k0 + BK < DS) load_tile<NB, Layout::KContig, false>(oph, 0, NB, k0 + BK, DS, rb, t);
+        if (k0 + BK < DS) load_tile<NB, Layout::MNContig, false>(oph, 0, NB, k0 + BK, DS, rb, t);
 #pragma unroll
         for (int kk = 0; kk < BK; kk += 2) {
           const float a = Hs[(k0 + kk + kr) * LDH + 32 * wm + c];
@@ -198,9 +210,12 @@ extern "C" int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, 
   (void)d;
   (void)tau;
   if (n_local < 0 || n_halo < 0 || d_s <= 0) return 0;
-  // S [n_bar, d_s] followed by the hop aggregate [n_halo, d_s]
+  // S [n_bar, d_s], the hop aggregate [n_halo, d_s], then the k-major copies of
+  // Wx [d, 4 d_s] and Wh [d_s, 4 d_s]
   return round_up((n_local + n_halo) * static_cast<int64_t>(d_s) * 4, 256) +
-         round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256);
+         round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256) +
+         round_up(static_cast<int64_t>(d) * 4 * d_s * 4, 256) +
+         round_up(static_cast<int64_t>(d_s) * 4 * d_s * 4, 256);
 }
 
 extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w,
@@ -234,7 +249,7 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
 
   if (!w->Wx || !w->Wh || !w->b || !w->Wg) return SAT_EINVAL;
   if (w->d_s != 32 && w->d_s != 64 && w->d_s != 128) return SAT_EUNSUPPORTED;
-  if ((d % 4) != 0) return SAT_EUNSUPPORTED;  // Wx, Wg rows are d floats, read 16 bytes at a time
+  if ((d % 4) != 0) return SAT_EUNSUPPORTED;  // Wg rows are d floats, read 16 bytes at a time
   if (!sat::aligned16(w->Wx) || !sat::aligned16(w->Wh) || !sat::aligned16(w->Wg)) return SAT_EALIGN;
   if (!pv->h_colptr || !pv->h_self || (pv->nnz_halo > 0 && (!pv->h_row || !pv->h_val)))
     return SAT_EINVAL;
@@ -242,6 +257,16 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   if (!workspace || workspace_bytes < need) return SAT_EWORKSPACE;
   if (!sat::aligned256(workspace)) return SAT_EALIGN;
   float* S = static_cast<float*>(workspace);
+  float* Agg = S + round_up(n_bar * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
+  float* WxT = Agg + round_up(pv->n_halo * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
+  float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
+  {
+    const int nb = 4 * w->d_s;
+    transpose_kernel<<<dim3((nb * d + 255) / 256), dim3(256), 0, st>>>(w->Wx, nb, d, WxT);
+    transpose_kernel<<<dim3((nb * w->d_s + 255) / 256), dim3(256), 0, st>>>(w->Wh, nb, w->d_s, WhT);
+    sat_status rc0 = sat::check_launch();
+    if (rc0 != SAT_OK) return rc0;
+  }
 
   SlotPtrs sp;
   for (int s = 0; s < kMaxTau; ++s)
@@ -252,7 +277,7 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
     constexpr int rows = 32 * (4 / ((DS) / 32));                                              \
     const int64_t blocks = (n_bar + rows - 1) / rows;                                         \
     lstm_kernel<DS><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(               \
-        sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->Wx, w->Wh, w->b, S);              \
+        sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, WxT, WhT, w->b, S);              \
   } while (0)
   switch (w->d_s) {
     case 32: SAT_LSTM(32); break;
@@ -263,7 +288,6 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   if (rc != SAT_OK) return rc;
 #undef SAT_LSTM
   // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
-  float* Agg = S + round_up(n_bar * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
   rc = sat::launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val, S, w->d_s,
                         pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, pv->h_self, pv->n_local, st);
   if (rc != SAT_OK) return rc;
