@@ -162,8 +162,9 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, 
                                                           int64_t N, int64_t K,
                                                           int64_t k_per_split, float* C,
                                                           int64_t ldc, EpiArgs ep) {
-  __shared__ __attribute__((aligned(16))) float As[TILE_FLOATS];
-  __shared__ __attribute__((aligned(16))) float Bs[TILE_FLOATS];
+  __shared__ __attribute__((aligned(16))) float smem[2 * TILE_FLOATS];
+  float* As = smem;
+  float* Bs = smem + TILE_FLOATS;
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -199,48 +200,69 @@ __global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, 
     mma_step(As, Bs, wm, wn, lane, acc);
   }
 
+  // ---- epilogue: the tile goes through LDS (the operand buffers are free now)
+  // so that global accesses are 16 bytes per lane and 512 bytes per row
+  // segment; two passes of 64 rows each fit the 33 KiB of operand staging.
   float* Cb = C;
   if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * ep.split_stride;
-  const int col_in_block = lane & 31;
+  const int c = lane & 31;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    // rows of the residual operand for this lane's 16 accumulator rows; fetched
-    // for all rows before any store so the loads overlap instead of queueing
-    // behind the stores
-    int64_t src[16];
+  for (int p = 0; p < 2; ++p) {
+    __syncthreads();
+    if (wm == p) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            smem[(i * 32 + acc_row(r, lane)) * LDS_LD + wn * 64 + j * 32 + c] = acc[i][j][r];
+    }
+    __syncthreads();
+    const int64_t n = n0 + ((t & 31) << 2);
+    int64_t src[8];
     if constexpr (EPI == kStoreAddRows) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
+      for (int q = 0; q < 8; ++q) {
+        const int64_t m = m0 + p * 64 + (t >> 5) + 8 * q;
         int64_t sr = -1;
         if (m < M) {
           sr = ep.add_ids ? static_cast<int64_t>(ep.add_ids[m]) : ep.add_base + m;
           if (sr < 0 || sr >= ep.add_rows) sr = -1;  // bad id: leave the row alone
         }
-        src[r] = sr;
+        src[q] = sr;
+      }
+    }
+    f32x4 v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      v[q] = *reinterpret_cast<const f32x4*>(&smem[((t >> 5) + 8 * q) * LDS_LD + ((t & 31) << 2)]);
+      if constexpr (EPI == kStoreRelu) {
+        v[q].x = v[q].x > 0.f ? v[q].x : 0.f;
+        v[q].y = v[q].y > 0.f ? v[q].y : 0.f;
+        v[q].z = v[q].z > 0.f ? v[q].z : 0.f;
+        v[q].w = v[q].w > 0.f ? v[q].w : 0.f;
+      }
+      if constexpr (EPI == kStoreAddRows) {
+        if (src[q] >= 0 && n < N)
+          v[q] += *reinterpret_cast<const f32x4*>(ep.add + src[q] * ep.ld_add + n);
       }
     }
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int64_t n = n0 + wn * 64 + j * 32 + col_in_block;
-      if (n >= N) continue;
-      float addv[16];
+    for (int q = 0; q < 8; ++q) {
+      const int64_t m = m0 + p * 64 + (t >> 5) + 8 * q;
+      if (m >= M || n >= N) continue;
       if constexpr (EPI == kStoreAddRows) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) addv[r] = src[r] >= 0 ? ep.add[src[r] * ep.ld_add + n] : 0.f;
+        if (src[q] < 0) continue;
       }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t m = m0 + wm * 64 + i * 32 + acc_row(r, lane);
-        if (m < M) {
-          float x = acc[i][j][r];
-          if constexpr (EPI == kStoreRelu) x = x > 0.f ? x : 0.f;
-          if constexpr (EPI == kStoreAddRows) {
-            if (src[r] < 0) continue;
-            x += addv[r];
-          }
-          Cb[m * ldc + n] = x;
-        }
+      float* y = Cb + m * ldc + n;
+      const int64_t left = N - n;
+      if (left >= 4) {
+        *reinterpret_cast<f32x4*>(y) = v[q];
+      } else {
+        y[0] = v[q].x;
+        if (left > 1) y[1] = v[q].y;
+        if (left > 2) y[2] = v[q].z;
       }
     }
   }

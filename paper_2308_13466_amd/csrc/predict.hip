@@ -34,7 +34,7 @@ sat_status row_gather(const void* src, int64_t ld_src, void* dst, int64_t ld_dst
 sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const int32_t* col,
                        const float* val, const float* X, int64_t ld_x, int64_t n_x_rows, float* Y,
                        int64_t ld_y, int64_t n_rows, int32_t d, const float* self_val,
-                       int64_t self_off, hipStream_t stream);
+                       int64_t self_off, int64_t total_entries, hipStream_t stream);
 }  // namespace sat
 
 namespace {
@@ -47,7 +47,17 @@ struct SlotPtrs {
   const float* p[kMaxTau];
 };
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+// Gate non-linearities on the hardware exp2 / reciprocal units (about 1 ulp
+// each): sigmoid(x) = 1 / (1 + 2^(-x log2 e)), tanh(x) = 2 sigmoid(2x) - 1. The
+// absolute error is ~2e-7, two orders below the 1e-5 the results are held to,
+// and they cost a handful of instructions instead of a libm call each; the
+// cell update runs 5 of them per hidden unit per step between MFMA phases.
+__device__ __forceinline__ float sigmoidf_(float x) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+__device__ __forceinline__ float tanhf_(float x) {
+  return 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.8853900817779268f * x)) - 1.0f;
+}
 
 // out[c * R + r] = in[r * C + c]: the LSTM weights are re-laid k-major once per
 // call so that the gate-weight tiles load with coalesced 16-byte accesses and go
@@ -148,13 +158,26 @@ __global__ __launch_bounds__(256, DS <= 64 ? 2 : 1) void lstm_kernel(SlotPtrs sl
         load_x(k0 + BK, ra);
         load_tile<NB, Layout::MNContig, false>(opx, 0, NB, k0 + BK, d, rb, t);
       }
+      if (s == 0) {   // c_0 = 0: the forget gate's block is not needed in the first step
 #pragma unroll
-      for (int kk = 0; kk < BK; kk += 2) {
-        const float a = As[(kk + kr) * LDA + 32 * wm + c];
+        for (int kk = 0; kk < BK; kk += 2) {
+          const float a = As[(kk + kr) * LDA + 32 * wm + c];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float bv = Bs[(kk + kr) * LDB + g * DS + 32 * wn + c];
-          acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[g], 0, 0, 0);
+          for (int g = 0; g < 4; ++g) {
+            if (g == 1) continue;
+            const float bv = Bs[(kk + kr) * LDB + g * DS + 32 * wn + c];
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[g], 0, 0, 0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 2) {
+          const float a = As[(kk + kr) * LDA + 32 * wm + c];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float bv = Bs[(kk + kr) * LDB + g * DS + 32 * wn + c];
+            acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[g], 0, 0, 0);
+          }
         }
       }
     }
@@ -181,11 +204,15 @@ __global__ __launch_bounds__(256, DS <= 64 ? 2 : 1) void lstm_kernel(SlotPtrs sl
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const float gi = sigmoidf_(acc[0][r] + b_i);
-      const float gf = sigmoidf_(acc[1][r] + b_f);
-      const float gg = tanhf(acc[2][r] + b_g);
+      const float gg = tanhf_(acc[2][r] + b_g);
       const float go = sigmoidf_(acc[3][r] + b_o);
-      cstate[r] = gf * cstate[r] + gi * gg;
-      hval[r] = go * tanhf(cstate[r]);
+      if (s == 0) {
+        cstate[r] = gi * gg;   // c_0 = 0: the forget gate has nothing to scale
+      } else {
+        const float gf = sigmoidf_(acc[1][r] + b_f);
+        cstate[r] = gf * cstate[r] + gi * gg;
+      }
+      hval[r] = go * tanhf_(cstate[r]);
     }
     if (s + 1 < tau) {
       __syncthreads();  // every wavefront has finished reading Hs for this step
@@ -289,7 +316,8 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
 #undef SAT_LSTM
   // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
   rc = sat::launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val, S, w->d_s,
-                        pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, pv->h_self, pv->n_local, st);
+                        pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, pv->h_self, pv->n_local,
+                        pv->nnz_halo, st);
   if (rc != SAT_OK) return rc;
   // hop, part 2: Hbar[n_local + u, :] = newest[row(u), :] + Agg[u, :] Wg
   {

@@ -47,6 +47,8 @@ struct SpmmArgs {
   int32_t d;
   const float* self_val;  // nullable: Y[i] += self_val[i] * X[self_off + i]
   int64_t self_off;
+  int64_t skip_upto;      // wavefront-per-row kernel: rows with <= skip_upto entries belong to
+                          // the group-per-row kernel and are left alone (-1: none)
 };
 
 // acc += sum over entries [s, e) of val * X[col]; all lanes of the wavefront take part.
@@ -151,13 +153,14 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void spmm_kernel(SpmmArgs a)
     e = a.row_end[row];
   }
   const bool is_long = (e - s) > kLongRow;
+  const bool mine = (e - s) > a.skip_upto;
   if (lane == 0) {
     long_s[wave] = is_long ? s : 0;
     long_e[wave] = is_long ? e : 0;
   }
 
   // ---- short rows: one wavefront each
-  if (row < a.n_rows && !is_long) {
+  if (row < a.n_rows && !is_long && mine) {
     f32x4 acc[NCH];
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) acc[ch] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -223,6 +226,67 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void spmm_kernel(SpmmArgs a)
   }
 }
 
+
+// Short rows, narrow features (G <= 32, one 16-byte accumulator per lane): a
+// group of G lanes owns a whole row, so a wavefront works on 64/G rows at once.
+// When rows hold only a handful of entries (the transposed halo block averages
+// under three) the walk is a chain of dependent loads per row, and the number of
+// rows in flight is what sets the speed. Rows longer than max_len are left to
+// the wavefront-per-row kernel.
+template <int G, int U>
+__global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max_len) {
+  constexpr int NG = kWave / G;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int gl = lane % G;
+  const int grp = lane / G;
+  const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * NG + grp;
+  int64_t s = 0, e = 0;
+  if (row < a.n_rows) {
+    s = a.row_begin[row];
+    e = a.row_end[row];
+  }
+  const bool mine = row < a.n_rows && (e - s) <= max_len;
+  if (!mine) e = s;
+  const int c0 = gl * 4;
+  const bool col_ok = c0 < a.d;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (mine && a.self_val != nullptr && col_ok)
+    acc = a.self_val[row] * *reinterpret_cast<const f32x4*>(a.X + (a.self_off + row) * a.ld_x + c0);
+  for (int64_t base = s; base < e; base += G) {
+    const int cnt = static_cast<int>(e - base < G ? e - base : G);
+    int32_t c = 0;
+    float v = 0.f;
+    if (gl < cnt) {
+      c = a.col[base + gl];
+      v = a.val[base + gl];
+    }
+    if (static_cast<uint32_t>(c) >= static_cast<uint64_t>(a.n_x_rows)) {
+      c = 0;
+      v = 0.f;
+    }
+    for (int j0 = 0; j0 < cnt; j0 += U) {
+      int32_t cj[U];
+      float vj[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int idx = j0 + u;
+        const int idc = idx < cnt ? idx : cnt - 1;
+        cj[u] = __shfl(c, grp * G + idc);
+        vj[u] = __shfl(v, grp * G + idc);
+        if (idx >= cnt) vj[u] = 0.f;
+      }
+      f32x4 x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        x[u] = col_ok ? *reinterpret_cast<const f32x4*>(a.X + static_cast<int64_t>(cj[u]) * a.ld_x + c0)
+                      : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc += vj[u] * x[u];
+    }
+  }
+  if (mine && col_ok) store_masked(a.Y + row * a.ld_y + c0, a.d - c0, acc);
+}
+
 }  // namespace
 
 namespace sat {
@@ -233,14 +297,36 @@ namespace sat {
 sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const int32_t* col,
                        const float* val, const float* X, int64_t ld_x, int64_t n_x_rows, float* Y,
                        int64_t ld_y, int64_t n_rows, int32_t d, const float* self_val,
-                       int64_t self_off, hipStream_t stream) {
+                       int64_t self_off, int64_t total_entries, hipStream_t stream) {
   if (n_rows == 0 || d == 0) return SAT_OK;
   const int64_t bx = (n_rows + kRowsPerBlock - 1) / kRowsPerBlock;
   if (bx > INT32_MAX) return SAT_EUNSUPPORTED;
   const int nvec = (d + 3) / 4;
   const dim3 block(kRowsPerBlock * kWave);
-  const SpmmArgs a{row_begin, row_end, col, val, X, ld_x, n_x_rows, Y, ld_y, n_rows, d, self_val,
-                   self_off};
+  SpmmArgs a{row_begin, row_end, col, val, X, ld_x, n_x_rows, Y, ld_y, n_rows, d, self_val,
+             self_off, -1};
+  // Few entries per row and narrow features: rows of up to kGroupMaxLen entries go to
+  // the group-per-row kernel, the rest (if any) to the wavefront-per-row kernel.
+  constexpr int64_t kGroupMaxLen = 64;
+  if (nvec <= 32 && total_entries < 16 * n_rows) {
+    int g = 1;
+    while (g < nvec) g <<= 1;
+    const int64_t rows_per_block = 4 * (kWave / g);
+    const int64_t gb = (n_rows + rows_per_block - 1) / rows_per_block;
+    if (gb > INT32_MAX) return SAT_EUNSUPPORTED;
+    const dim3 ggrid(static_cast<unsigned>(gb));
+    switch (g) {
+      case 1: spmm_group_kernel<1, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
+      case 2: spmm_group_kernel<2, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
+      case 4: spmm_group_kernel<4, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
+      case 8: spmm_group_kernel<8, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
+      case 16: spmm_group_kernel<16, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
+      default: spmm_group_kernel<32, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
+    }
+    sat_status st = sat::check_launch();
+    if (st != SAT_OK) return st;
+    a.skip_upto = kGroupMaxLen;
+  }
 #define SAT_SPMM_LAUNCH(G, NCH, U)                                                            \
   do {                                                                                        \
     const int per_pass = (G) * 4 * (NCH);                                                     \
@@ -305,7 +391,7 @@ extern "C" sat_status sat_spmm_fwd(const sat_part_view* pv, const void* Hbar, in
   if ((st = validate_dense(AGG, pv->n_local, ld_out, d)) != SAT_OK) return st;
   return launch_spmm(pv->rowptr, pv->rowptr + 1, pv->col, pv->val, static_cast<const float*>(Hbar),
                      ld_in, pv->n_local + pv->n_halo, static_cast<float*>(AGG), ld_out,
-                     pv->n_local, d, nullptr, 0, static_cast<hipStream_t>(stream));
+                     pv->n_local, d, nullptr, 0, pv->nnz, static_cast<hipStream_t>(stream));
 }
 
 extern "C" sat_status sat_spmm_bwd(const sat_part_view* pv, const void* dAGG, int64_t ld_in,
@@ -328,9 +414,9 @@ extern "C" sat_status sat_spmm_bwd(const sat_part_view* pv, const void* dAGG, in
   hipStream_t s = static_cast<hipStream_t>(stream);
   // P_in^T = P_in: row i's local columns are [rowptr[i], split[i])
   st = launch_spmm(pv->rowptr, pv->split, pv->col, pv->val, static_cast<const float*>(dAGG), ld_in,
-                   pv->n_local, static_cast<float*>(dH_local), ld_out, pv->n_local, d, nullptr, 0, s);
+                   pv->n_local, static_cast<float*>(dH_local), ld_out, pv->n_local, d, nullptr, 0, pv->nnz - pv->nnz_halo, s);
   if (st != SAT_OK || !dH_halo) return st;
   return launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val,
                      static_cast<const float*>(dAGG), ld_in, pv->n_local,
-                     static_cast<float*>(dH_halo), ld_halo, pv->n_halo, d, nullptr, 0, s);
+                     static_cast<float*>(dH_halo), ld_halo, pv->n_halo, d, nullptr, 0, pv->nnz_halo, s);
 }
