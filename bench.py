@@ -90,6 +90,10 @@ def main():
     ap.add_argument("--unfused-pull", action="store_true",
                     help="assemble the predictor window with sat_history_gather first")
     ap.add_argument("--bypass", action="store_true", help="plain historical embeddings")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also launch one plain row copy of known size (1 GiB read + 1 GiB "
+                         "written, identity ids) so that a rocprofv3 --pmc run of this command "
+                         "can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -159,6 +163,18 @@ def main():
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))
+
+    if args.pmc_calibration:
+        rows, width = 1 << 20, 256
+        src = torch.ones((rows, width), dtype=torch.float32, device=dev)
+        dst = torch.zeros((rows, width), dtype=torch.float32, device=dev)
+        ident = torch.arange(rows, dtype=torch.int32, device=dev)
+        sat.history_gather(src, rows, width, ident, rows, width, dst, width,
+                           stream=torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        log("calibration copy: %d rows x %d floats (%.0f bytes read, same written)" % (
+            rows, width, rows * width * 4.0))
+        del src, dst, ident
 
     # ---- warm-up, then the timed region
     for _ in range(args.warmup):

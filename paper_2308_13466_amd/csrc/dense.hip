@@ -18,7 +18,7 @@ namespace {
 
 using namespace sat::gemm;
 
-// out[i] = sum_s part[s * stride + i] for s ascending (fixed order).
+// out[i] = sum over slices s of part[s * stride + i], in a fixed order.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part,
                                                               int64_t stride, int splits,
                                                               int64_t rows, int cols,
@@ -30,9 +30,16 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   const int64_t r = idx / cols;
   const int c = static_cast<int>(idx - r * cols);
   const float* p = part + r * ld_part + c;
-  float s = 0.f;
-  for (int k = 0; k < splits; ++k) s += p[k * stride];
-  out[r * ld_out + c] = s;
+  // eight independent running sums (slices k, k+8, ...) so eight loads are in flight,
+  // combined in a fixed tree: the result does not depend on timing
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  int k = 0;
+  for (; k + 8 <= splits; k += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s[u] += p[(k + u) * stride];
+  }
+  for (int u = 0; k < splits; ++k, ++u) s[u] += p[k * stride];
+  out[r * ld_out + c] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
 }
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }

@@ -11,6 +11,8 @@
 namespace {
 
 using sat::kWave;
+constexpr int kRowsPerWave = 8;    // nodes a wavefront handles one after another
+constexpr int kRowsPerBlock = 4 * kRowsPerWave;
 
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
@@ -31,9 +33,10 @@ __global__ __launch_bounds__(256) void xent_grad_kernel(const float* __restrict_
   __shared__ float wave_loss[4];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
-  const int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + wave;
   float nll = 0.f;
-  if (row < n) {
+  for (int rr = 0; rr < kRowsPerWave; ++rr) {
+    const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave + rr;
+    if (row >= n) break;
     const float* h = HL + row * ld_hl;
     float mx = -INFINITY;
     for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, h[c]);
@@ -48,7 +51,7 @@ __global__ __launch_bounds__(256) void xent_grad_kernel(const float* __restrict_
       const float p = expf(h[c] - mx) / se;
       g[c] = (p - (c == label ? 1.f : 0.f)) * inv_n;
     }
-    if (label >= 0 && label < C) nll = logf(se) + mx - h[label];
+    if (label >= 0 && label < C) nll += logf(se) + mx - h[label];
   }
   if (block_loss) {
     if (lane == 0) wave_loss[wave] = nll;
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(256) void loss_finish_kernel(const float* __restric
 
 extern "C" int64_t sat_loss_workspace_bytes(int64_t n) {
   if (n <= 0) return 0;
-  return ((n + 3) / 4) * static_cast<int64_t>(sizeof(float));
+  return ((n + kRowsPerBlock - 1) / kRowsPerBlock) * static_cast<int64_t>(sizeof(float));
 }
 
 extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
@@ -89,7 +92,7 @@ extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, in
   if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
   if (n == 0) return SAT_OK;
   if (!HL || !y || !dH || ld_hl < n_classes || ld_dh < n_classes) return SAT_EINVAL;
-  const int64_t blocks = (n + 3) / 4;
+  const int64_t blocks = (n + kRowsPerBlock - 1) / kRowsPerBlock;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
   if (loss && (!workspace || workspace_bytes < sat_loss_workspace_bytes(n))) return SAT_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);

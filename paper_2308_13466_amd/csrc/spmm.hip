@@ -47,8 +47,6 @@ struct SpmmArgs {
   int32_t d;
   const float* self_val;  // nullable: Y[i] += self_val[i] * X[self_off + i]
   int64_t self_off;
-  int64_t skip_upto;      // wavefront-per-row kernel: rows with <= skip_upto entries belong to
-                          // the group-per-row kernel and are left alone (-1: none)
 };
 
 // acc += sum over entries [s, e) of val * X[col]; all lanes of the wavefront take part.
@@ -153,14 +151,13 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void spmm_kernel(SpmmArgs a)
     e = a.row_end[row];
   }
   const bool is_long = (e - s) > kLongRow;
-  const bool mine = (e - s) > a.skip_upto;
   if (lane == 0) {
     long_s[wave] = is_long ? s : 0;
     long_e[wave] = is_long ? e : 0;
   }
 
   // ---- short rows: one wavefront each
-  if (row < a.n_rows && !is_long && mine) {
+  if (row < a.n_rows && !is_long) {
     f32x4 acc[NCH];
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) acc[ch] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -231,8 +228,9 @@ __global__ __launch_bounds__(kRowsPerBlock * kWave) void spmm_kernel(SpmmArgs a)
 // group of G lanes owns a whole row, so a wavefront works on 64/G rows at once.
 // When rows hold only a handful of entries (the transposed halo block averages
 // under three) the walk is a chain of dependent loads per row, and the number of
-// rows in flight is what sets the speed. Rows longer than max_len are left to
-// the wavefront-per-row kernel.
+// rows in flight is what sets the speed. A row longer than max_len is walked
+// afterwards by all 64 lanes of the wavefront its group belongs to (64/G
+// neighbours at a time), so the occasional longer row does not stall one group.
 template <int G, int U>
 __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max_len) {
   constexpr int NG = kWave / G;
@@ -245,6 +243,7 @@ __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max
     s = a.row_begin[row];
     e = a.row_end[row];
   }
+  const int64_t s0 = s, e0 = e;
   const bool mine = row < a.n_rows && (e - s) <= max_len;
   if (!mine) e = s;
   const int c0 = gl * 4;
@@ -285,6 +284,20 @@ __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max
     }
   }
   if (mine && col_ok) store_masked(a.Y + row * a.ld_y + c0, a.d - c0, acc);
+
+  // rows too long for one group: one bit per group, handled one after another
+  uint64_t todo = __ballot(row < a.n_rows && !mine && gl == 0);
+  while (todo) {
+    const int src = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    const int64_t rs = __shfl(s0, src), re = __shfl(e0, src), r = __shfl(row, src);
+    f32x4 wacc[1] = {f32x4{0.f, 0.f, 0.f, 0.f}};
+    walk_entries<G, 1, U>(a, rs, re, 0, lane, wacc);
+    if (a.self_val != nullptr && grp == 0 && col_ok)
+      wacc[0] += a.self_val[r] * *reinterpret_cast<const f32x4*>(a.X + (a.self_off + r) * a.ld_x + c0);
+    reduce_groups<G, 1>(wacc);
+    if (grp == 0 && col_ok) store_masked(a.Y + r * a.ld_y + c0, a.d - c0, wacc[0]);
+  }
 }
 
 }  // namespace
@@ -303,10 +316,9 @@ sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const i
   if (bx > INT32_MAX) return SAT_EUNSUPPORTED;
   const int nvec = (d + 3) / 4;
   const dim3 block(kRowsPerBlock * kWave);
-  SpmmArgs a{row_begin, row_end, col, val, X, ld_x, n_x_rows, Y, ld_y, n_rows, d, self_val,
-             self_off, -1};
-  // Few entries per row and narrow features: rows of up to kGroupMaxLen entries go to
-  // the group-per-row kernel, the rest (if any) to the wavefront-per-row kernel.
+  const SpmmArgs a{row_begin, row_end, col, val, X, ld_x, n_x_rows, Y, ld_y, n_rows, d, self_val,
+                   self_off};
+  // Few entries per row and narrow features: a group of lanes per row.
   constexpr int64_t kGroupMaxLen = 64;
   if (nvec <= 32 && total_entries < 16 * n_rows) {
     int g = 1;
@@ -323,9 +335,7 @@ sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const i
       case 16: spmm_group_kernel<16, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
       default: spmm_group_kernel<32, 4><<<ggrid, dim3(256), 0, stream>>>(a, kGroupMaxLen); break;
     }
-    sat_status st = sat::check_launch();
-    if (st != SAT_OK) return st;
-    a.skip_upto = kGroupMaxLen;
+    return sat::check_launch();
   }
 #define SAT_SPMM_LAUNCH(G, NCH, U)                                                            \
   do {                                                                                        \
