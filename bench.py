@@ -59,27 +59,6 @@ class CallTimers:
         return {k: dict(total_ms=v[0], launches=v[1], avg_ms=v[0] / v[1]) for k, v in out.items()}
 
 
-def build_inputs(cfg, log):
-    """Host-side seeded inputs of one workload (no method arithmetic here)."""
-    import numpy as np
-    import sat_synth as syn
-    ss = syn.substreams(cfg["seed"])
-    t0 = time.time()
-    g = syn.cached_graph(cfg, ss["graph"])
-    log("graph: N=%d nnz=%d (%.1fs)" % (g.N, g.nnz, time.time() - t0))
-    dims = cfg["dims"]
-    L = len(dims) - 1
-    wss = ss["weights"].spawn(L)
-    Ws = [syn.glorot_uniform_f32(wss[l], dims[l], dims[l + 1]) for l in range(L)]
-    pss = ss["predictor"].spawn(L)
-    omegas = [None] + [syn.predictor_params_f32(pss[l], dims[l], cfg["d_s"]) for l in range(1, L)]
-    return ss, g, Ws, omegas
-
-
-def ld_of(d, mult=32):
-    return (d + mult - 1) // mult * mult
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,59 +89,19 @@ def main():
     import torch
     import sat_synth as syn
     import paper_2308_13466_amd as sat
-    from paper_2308_13466_amd.step import PartitionStep
+    from paper_2308_13466_amd.workload import build_workload
     sat.lib()   # raises if libsat.so has not been built; there is no fallback
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    cfg = syn.get_config(args.workload)
-    dims, tau, d_s = cfg["dims"], cfg["tau"], cfg["d_s"]
-    if args.workload == "tiny":
-        d_s = 32
-    L = len(dims) - 1
-    ss, g, Ws, omegas = build_inputs(dict(cfg, d_s=d_s), log)
-    t0 = time.time()
-    view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"])
+    timers = CallTimers(torch)
+    wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
+                        timers=timers, log=log)
+    cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
+    dims, tau, d_s, L = wl.dims, wl.tau, wl.d_s, wl.L
     n_l, n_h = view["n_local"], view["n_halo"]
     n_bar = n_l + n_h
-    log("partition view: n_local=%d n_halo=%d nnz=%d nnz_halo=%d max_deg=%d (%.1fs)" % (
-        n_l, n_h, view["nnz"], view["nnz_halo"], int(np.diff(view["rowptr"]).max()),
-        time.time() - t0))
-
-    # ---- device-resident inputs
-    t0 = time.time()
-    ld = [ld_of(d) for d in dims]
-    X_host = syn.normal_f32(ss["features"], g.N, dims[0], ld=ld[0])
-    X_d = torch.from_numpy(X_host).to(dev)
-    hss = ss["history"].spawn(L)
-    hist_d = [None]
-    hist_host_newest = [None]
-    for l in range(1, L):
-        slots = syn.history_standin_f32(hss[l], g.N, dims[l], tau, cfg["noise_std"], ld=ld[l])
-        hist_d.append([torch.from_numpy(s).to(dev) for s in slots])
-        hist_host_newest.append(slots)      # kept for the CPU baseline sample
-    table_ids = np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32)
-    ids_d = torch.from_numpy(table_ids).to(dev)
-    Ws_d = []
-    for l in range(L):
-        w = np.zeros((dims[l], ld_of(dims[l + 1], 4)), np.float32)
-        w[:, :dims[l + 1]] = Ws[l]
-        Ws_d.append(torch.from_numpy(w).to(dev))
-    keep, preds = [], [None]
-    for l in range(1, L):
-        pd = {k: torch.from_numpy(omegas[l][k]).to(dev) for k in omegas[l]}
-        keep.append(pd)
-        preds.append(sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], d_s, tau,
-                                   bypass=args.bypass))
-    y = syn.labels_i32(ss["labels"], n_l, dims[-1])
-    y_d = torch.from_numpy(y).to(dev)
-    timers = CallTimers(torch)
-    step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
-                         fused_pull=not args.unfused_pull, timers=timers)
-    torch.cuda.synchronize()
-    log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
-        torch.cuda.memory_allocated() / 1e9, time.time() - t0))
 
     if args.pmc_calibration:
         rows, width = 1 << 20, 256
@@ -249,8 +188,8 @@ def main():
     # ---- CPU oracle on a bounded sample, rank 0, host cores
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(view, dims, tau, d_s, X_host, hist_host_newest, table_ids, Ws, omegas,
-                           y, edges, bypass=args.bypass, log=log)
+        cpu = cpu_baseline(view, dims, tau, d_s, wl.X_host, wl.hist_host, wl.table_ids, wl.Ws,
+                           wl.omegas, wl.y, edges, bypass=args.bypass, log=log)
 
     out = {
         "metric": "GTEPS aggregated (CSR entries aggregated per second over one partition's "

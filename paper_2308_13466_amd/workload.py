@@ -1,0 +1,92 @@
+"""Seeded synthetic workloads resident in HBM, shared by bench.py and the
+full-size parity tests so that both run the same launch configuration.
+
+Nothing of the method is computed here: inputs come from sat_synth, the
+partition view from the library's own host call, and the result is a
+PartitionStep ready to run.
+"""
+import time
+
+import numpy as np
+import torch
+
+import sat_synth as syn
+from . import binding as B
+from .step import PartitionStep
+
+
+def ld_of(d, mult=32):
+    return (d + mult - 1) // mult * mult
+
+
+class Workload:
+    pass
+
+
+def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
+                   keep_host=True, device="cuda:0"):
+    """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
+
+    History tables hold the seeded stand-in described in sat_synth.tensors
+    (true unpartitioned embeddings are only affordable for the small
+    workloads, where the tests build them with the oracle instead).
+    """
+    dev = torch.device(device)
+    cfg = syn.get_config(name)
+    if name == "tiny":
+        cfg["d_s"] = 32
+    dims, tau, d_s = cfg["dims"], cfg["tau"], cfg["d_s"]
+    L = len(dims) - 1
+    ss = syn.substreams(cfg["seed"])
+    t0 = time.time()
+    g = syn.cached_graph(cfg, ss["graph"])
+    log("graph: N=%d nnz=%d (%.1fs)" % (g.N, g.nnz, time.time() - t0))
+    wss = ss["weights"].spawn(L)
+    Ws = [syn.glorot_uniform_f32(wss[l], dims[l], dims[l + 1]) for l in range(L)]
+    pss = ss["predictor"].spawn(L)
+    omegas = [None] + [syn.predictor_params_f32(pss[l], dims[l], d_s) for l in range(1, L)]
+
+    t0 = time.time()
+    view = B.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"])
+    n_l, n_h = view["n_local"], view["n_halo"]
+    log("partition view: n_local=%d n_halo=%d nnz=%d nnz_halo=%d max_deg=%d (%.1fs)" % (
+        n_l, n_h, view["nnz"], view["nnz_halo"],
+        int(np.diff(view["rowptr"]).max()) if n_l else 0, time.time() - t0))
+
+    t0 = time.time()
+    ld = [ld_of(d) for d in dims]
+    X_host = syn.normal_f32(ss["features"], g.N, dims[0], ld=ld[0])
+    X_d = torch.from_numpy(X_host).to(dev)
+    hss = ss["history"].spawn(L)
+    hist_d, hist_host = [None], [None]
+    for l in range(1, L):
+        slots = syn.history_standin_f32(hss[l], g.N, dims[l], tau, cfg["noise_std"], ld=ld[l])
+        hist_d.append([torch.from_numpy(s).to(dev) for s in slots])
+        hist_host.append(slots if keep_host else None)
+    table_ids = np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32)
+    ids_d = torch.from_numpy(table_ids).to(dev)
+    Ws_d = []
+    for l in range(L):
+        w = np.zeros((dims[l], ld_of(dims[l + 1], 4)), np.float32)
+        w[:, :dims[l + 1]] = Ws[l]
+        Ws_d.append(torch.from_numpy(w).to(dev))
+    preds, keep = [None], []
+    for l in range(1, L):
+        pd = {k: torch.from_numpy(omegas[l][k]).to(dev) for k in omegas[l]}
+        keep.append(pd)
+        preds.append(B.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], d_s, tau,
+                                 bypass=bypass))
+    y = syn.labels_i32(ss["labels"], n_l, dims[-1])
+    y_d = torch.from_numpy(y).to(dev)
+    step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
+                         fused_pull=fused_pull, timers=timers)
+    torch.cuda.synchronize()
+    log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
+        torch.cuda.memory_allocated() / 1e9, time.time() - t0))
+
+    w = Workload()
+    w.name, w.cfg, w.graph, w.view, w.step = name, cfg, g, view, step
+    w.dims, w.tau, w.d_s, w.L, w.ld = dims, tau, d_s, L, ld
+    w.X_host, w.hist_host, w.table_ids, w.Ws, w.omegas, w.y = X_host, hist_host, table_ids, Ws, omegas, y
+    w.device_keep = (keep, X_d, hist_d, ids_d, Ws_d, y_d)
+    return w

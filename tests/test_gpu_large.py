@@ -1,0 +1,236 @@
+"""Full-size parity: the benchmark's workload (Large: 306,250 local nodes,
+1.14 M halo nodes, 15.3 M CSR entries) in the launch configuration bench.py
+times. The oracle cannot afford every output here, so it computes sampled
+outputs one by one (rows of every call are independent), full outputs where a
+library routine makes that cheap (copies, dW through a BLAS product, the loss),
+and closed forms that hold at any size."""
+import time
+
+import numpy as np
+import pytest
+
+import sat_synth as syn
+from oracle import sat_oracle as orc
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-5
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def large():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2308_13466_amd as sat
+    sat.lib()
+    from paper_2308_13466_amd.workload import build_workload
+    from tests import gpu_util as gu
+    t0 = time.time()
+    wl = build_workload("large", log=_say)
+    _say("workload built in %.0fs" % (time.time() - t0))
+    return sat, gu, torch, wl
+
+
+def _sample_rows(view, n, rng):
+    """Random local rows plus the longest rows (the cooperative long-row path)."""
+    n_l = view["n_local"]
+    deg = np.diff(view["rowptr"])
+    rows = set(int(r) for r in rng.choice(n_l, size=n, replace=False))
+    rows.update(int(r) for r in np.argsort(deg)[-6:])
+    rows.update([0, n_l - 1])
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+def test_view_index_arrays_bit_exact_at_full_size(large):
+    sat, gu, torch, wl = large
+    _say("partition view vs oracle, full size")
+    g, v = wl.graph, wl.view
+    t0 = time.time()
+    ref = orc.partition_view(g.N, g.rowptr, g.col, g.part, wl.cfg["part"])
+    _say("oracle view in %.0fs" % (time.time() - t0))
+    for k in ("n_local", "n_halo", "nnz", "nnz_halo"):
+        assert v[k] == ref[k]
+    for k in ("local_ids", "halo_ids", "rowptr", "split", "col", "h_colptr", "h_row"):
+        assert np.array_equal(v[k], ref[k]), k
+    for k in ("val", "h_val", "h_self"):
+        assert np.array_equal(v[k].view(np.uint32), ref[k].view(np.uint32)), k
+
+
+def test_pull_push_full_compare(large):
+    sat, gu, torch, wl = large
+    _say("pull of halo features / push of a hidden layer, every row compared")
+    v, step, dims, ld = wl.view, wl.step, wl.dims, wl.ld
+    n_l, n_h = v["n_local"], v["n_halo"]
+    halo_rows = wl.table_ids[n_l:]
+    out = gu.dev_empty(n_h, ld[0], fill=-3.0)
+    sat.history_gather(step.X_table, step.X_table.shape[0], ld[0], step.halo_table_ids, n_h,
+                       dims[0], out, ld[0], stream=gu.stream_ptr())
+    gu.sync()
+    ref = orc.history_gather(wl.X_host, halo_rows)[:, :dims[0]]
+    assert np.array_equal(out.cpu().numpy()[:, :dims[0]].view(np.uint32), ref.view(np.uint32))
+    # push into a scratch table of the history shape
+    rng = np.random.default_rng(5)
+    H = rng.standard_normal((n_l, ld[1])).astype(np.float32)
+    tab = torch.zeros((wl.graph.N, ld[1]), dtype=torch.float32, device=gu.DEV)
+    sat.history_push(tab, wl.graph.N, ld[1], step.local_table_ids, n_l, dims[1], gu.to_dev(H),
+                     ld[1], stream=gu.stream_ptr())
+    gu.sync()
+    ref_tab = orc.history_push(np.zeros((wl.graph.N, ld[1]), np.float32), v["local_ids"],
+                               H[:, :dims[1]])
+    assert np.array_equal(tab.cpu().numpy().view(np.uint32), ref_tab.view(np.uint32))
+
+
+@pytest.mark.parametrize("d", [100, 256])
+def test_spmm_sampled_rows(large, d):
+    sat, gu, torch, wl = large
+    _say("spmm fwd/bwd d=%d on seeded inputs, sampled rows incl. the longest" % d)
+    v, step = wl.view, wl.step
+    n_l, n_bar = v["n_local"], v["n_local"] + v["n_halo"]
+    ld = (d + 31) // 32 * 32
+    rng = np.random.default_rng(d)
+    Hbar = syn.normal_f32(np.random.SeedSequence(d), n_bar, d, ld=ld)
+    rows = _sample_rows(v, 1500, rng)
+    agg = gu.dev_empty(n_l, ld, fill=-3.0)
+    Hb_d = gu.to_dev(Hbar)
+    sat.spmm_fwd(step.pv, Hb_d, ld, d, agg, ld, stream=gu.stream_ptr())
+    dh = gu.dev_empty(n_l, ld, fill=-3.0)
+    sat.spmm_bwd(step.pv, Hb_d, ld, d, dh, ld, stream=gu.stream_ptr())   # first n_l rows as dAGG
+    gu.sync()
+    got = agg[torch.from_numpy(rows).to(gu.DEV)].cpu().numpy()[:, :d]
+    gu.assert_close(got, orc.spmm_fwd_rows(v, Hbar[:, :d], rows), RTOL, "spmm_fwd rows")
+    got = dh[torch.from_numpy(rows).to(gu.DEV)].cpu().numpy()[:, :d]
+    gu.assert_close(got, orc.spmm_bwd_rows(v, Hbar[:n_l, :d], rows), RTOL, "spmm_bwd rows")
+
+
+def test_spmm_closed_form_all_rows(large):
+    sat, gu, torch, wl = large
+    _say("A_hat sqrt(d) = sqrt(d) on every local row")
+    g, v, step = wl.graph, wl.view, wl.step
+    sd = np.sqrt(1.0 + np.diff(g.rowptr)).astype(np.float32)
+    x = np.repeat(sd[wl.table_ids][:, None], 4, axis=1)
+    agg = gu.dev_empty(v["n_local"], 4)
+    sat.spmm_fwd(step.pv, gu.to_dev(x), 4, 4, agg, 4, stream=gu.stream_ptr())
+    gu.sync()
+    np.testing.assert_allclose(agg.cpu().numpy()[:, 0], sd[v["local_ids"]], rtol=3e-6)
+
+
+def test_dense_and_loss_full_size(large):
+    sat, gu, torch, wl = large
+    _say("dense fwd/bwd 256->256 and loss at n_local rows")
+    v = wl.view
+    n, d_in, d_out = v["n_local"], 256, 256
+    A = syn.normal_f32(np.random.SeedSequence(11), n, d_in)
+    dH = syn.normal_f32(np.random.SeedSequence(12), n, d_out)
+    W = wl.Ws[1]
+    rows = np.sort(np.random.default_rng(3).choice(n, size=4096, replace=False))
+    A_d, W_d, dH_d = gu.to_dev(A), gu.to_dev(W), gu.to_dev(dH)
+    H_d = gu.dev_empty(n, d_out)
+    sat.dense_fwd(A_d, d_in, n, d_in, d_out, W_d, d_out, 1, H_d, d_out, stream=gu.stream_ptr())
+    gu.sync()
+    Zs, Hs = orc.dense_fwd(A[rows], W, 1)
+    gu.assert_close(H_d[torch.from_numpy(rows).to(gu.DEV)].cpu().numpy(), Hs, RTOL, "dense_fwd rows")
+    # backward with the oracle's own fp32 forward output as the mask source (all rows,
+    # through a BLAS product in fp64: a library routine as one step of the oracle)
+    Z, H = orc.dense_fwd(A, W, 1)
+    H32 = H.astype(np.float32)
+    del Z, H
+    dW_d = gu.dev_empty(d_in, d_out)
+    dA_d = gu.dev_empty(n, d_in)
+    wsb = sat.dense_bwd_workspace_bytes(n, d_in, d_out)
+    ws = gu.workspace(wsb)
+    sat.dense_bwd(dH_d, d_out, gu.to_dev(H32), d_out, A_d, d_in, W_d, d_out, n, d_in, d_out, 1,
+                  dW_d, d_out, dA_d, d_in, workspace=ws, workspace_bytes=wsb,
+                  stream=gu.stream_ptr())
+    gu.sync()
+    dW, dA, _ = orc.dense_bwd(dH, H32, A, W, 1)
+    gu.assert_close(dW_d.cpu().numpy(), dW, RTOL, "dW (all rows reduced)")
+    gu.assert_close(dA_d[torch.from_numpy(rows).to(gu.DEV)].cpu().numpy(), dA[rows], RTOL, "dAGG rows")
+    # loss on logits of the bench shape
+    C = wl.dims[-1]
+    ldc = (C + 31) // 32 * 32
+    HL = (2.0 * syn.normal_f32(np.random.SeedSequence(13), n, C, ld=ldc))
+    g_d = gu.dev_empty(n, ldc)
+    loss_d = torch.zeros(1, dtype=torch.float32, device=gu.DEV)
+    wsb = sat.loss_workspace_bytes(n)
+    ws = gu.workspace(wsb)
+    sat.loss_grad(gu.to_dev(HL), ldc, n, C, wl.step.y, g_d, ldc, loss=loss_d, workspace=ws,
+                  workspace_bytes=wsb, stream=gu.stream_ptr())
+    gu.sync()
+    loss, gref = orc.loss_and_grad(HL[:, :C], wl.y)
+    gu.assert_close(g_d.cpu().numpy()[:, :C], gref, RTOL, "loss gradient")
+    assert abs(float(loss_d.item()) - loss) <= 2 * RTOL * abs(loss)
+
+
+def _oracle_predict_rows(wl, layer, halo_sample, order):
+    """Predicted embeddings of sampled halo nodes from the ORIGINAL history."""
+    v = wl.view
+    n_l = v["n_local"]
+    cp = v["h_colptr"]
+    nbrs = [v["h_row"][cp[u]:cp[u + 1]] for u in halo_sample]
+    locs = np.unique(np.concatenate(nbrs)) if nbrs else np.zeros(0, np.int64)
+    d = wl.dims[layer]
+    node_ids = np.concatenate([locs, n_l + halo_sample])          # relabelled ids
+    win = [wl.hist_host[layer][s][wl.table_ids[node_ids]][:, :d] for s in order]
+    S = orc.lstm_last_hidden(win, wl.omegas[layer]["Wx"], wl.omegas[layer]["Wh"],
+                             wl.omegas[layer]["b"])
+    pos = {int(r): k for k, r in enumerate(locs)}
+    sub = dict(n_local=len(locs), n_halo=len(halo_sample),
+               h_colptr=np.concatenate([[0], np.cumsum([len(x) for x in nbrs])]).astype(np.int64),
+               h_row=np.array([pos[int(r)] for x in nbrs for r in x], dtype=np.int32),
+               h_val=np.concatenate([v["h_val"][cp[u]:cp[u + 1]] for u in halo_sample]),
+               h_self=v["h_self"][halo_sample])
+    newest = win[-1][len(locs):].astype(np.float64)
+    return newest + orc.predictor_hop(sub, S, wl.omegas[layer]["Wg"])
+
+
+def test_whole_step_sampled(large):
+    sat, gu, torch, wl = large
+    _say("one whole step in the benchmark's configuration; sampled outputs vs the oracle")
+    v, step, dims = wl.view, wl.step, wl.dims
+    n_l, n_h = v["n_local"], v["n_halo"]
+    rng = np.random.default_rng(17)
+    assert step.t == 0
+    order = step.slot_order()
+    step.forward_backward()
+    gu.sync()
+    # predicted halo rows of both hidden layers, from the original history tables
+    cp = v["h_colptr"]
+    halo_sample = np.sort(rng.choice(n_h, size=1024, replace=False))
+    halo_sample = np.unique(np.concatenate([halo_sample, np.argsort(np.diff(cp))[-4:]]))
+    for l in (1, 2):
+        ref = _oracle_predict_rows(wl, l, halo_sample, order)
+        got = step.Hbar[l][torch.from_numpy(n_l + halo_sample).to(gu.DEV)].cpu().numpy()[:, :dims[l]]
+        gu.assert_close(got, ref, RTOL, "predicted halo rows, layer %d" % l)
+    # layer 0: aggregate and transform of sampled rows from the original features
+    rows = _sample_rows(v, 1500, rng)
+    Hbar0 = wl.X_host[wl.table_ids][:, :dims[0]]
+    a0 = orc.spmm_fwd_rows(v, Hbar0, rows)
+    ridx = torch.from_numpy(rows).to(gu.DEV)
+    gu.assert_close(step.AGG[0][ridx].cpu().numpy()[:, :dims[0]], a0, RTOL, "AGG_0 rows")
+    _, h1 = orc.dense_fwd(a0, wl.Ws[0], 1)
+    gu.assert_close(step.Hbar[1][ridx].cpu().numpy()[:, :dims[1]], h1, RTOL, "H_1 rows")
+    # layer 1 for a few rows: needs H_1 of every local neighbour (two hops of oracle work)
+    few = rows[np.argsort(np.diff(v["rowptr"])[rows])[:40]]
+    for i in few:
+        s, e, sp = v["rowptr"][i], v["rowptr"][i + 1], v["split"][i]
+        loc = v["col"][s:sp].astype(np.int64)
+        _, h1n = orc.dense_fwd(orc.spmm_fwd_rows(v, Hbar0, loc), wl.Ws[0], 1)
+        halo = v["col"][sp:e].astype(np.int64) - n_l
+        hh = _oracle_predict_rows(wl, 1, halo, order) if halo.size else np.zeros((0, dims[1]))
+        ref = v["val"][s:sp].astype(np.float64) @ h1n + v["val"][sp:e].astype(np.float64) @ hh
+        got = step.AGG[1][int(i)].cpu().numpy()[:dims[1]]
+        gu.assert_close(got[None, :], ref[None, :], 3 * RTOL, "AGG_1 row %d" % i)
+    # push: slot 0 of each ring now holds exactly the forward's local rows
+    for l in (1, 2):
+        tab = step.hist[l][0]
+        assert torch.equal(tab[step.local_table_ids.long(), :dims[l]], step.Hbar[l][:n_l, :dims[l]])
+    assert np.isfinite(float(step.loss.item()))
+    for l in range(3):
+        assert torch.isfinite(step.dW[l][:, :dims[l + 1]]).all()
+    # second step: ring rotated, still finite and deterministic w.r.t. a re-run of step 1's calls
+    step.forward_backward()
+    gu.sync()
+    assert step.slot_order() == [0, 1] and np.isfinite(float(step.loss.item()))
