@@ -2,7 +2,9 @@
 // Z = P H W, H' = sigma(Z); backward D = G o sigma'(Z), G_W = (P H)^T D, and
 // D W^T handed to the transpose aggregation).
 //
-// All three products run on the fp32 MFMA pipe through one tile kernel:
+// All three products run through one tile kernel on the bf16 MFMA pipe with an
+// exact three-way split of the fp32 operands (fp32-equivalent accuracy at 6/16
+// of the fp32 pipe's cost, see mx_tile.h):
 //   forward : C = AGG * W            A KContig (AGG rows), B MNContig (W rows)
 //   dAGG    : C = dZ * W^T           A KContig with relu mask, B KContig (W read transposed)
 //   dW      : C = AGG^T * dZ         A MNContig (AGG rows are k), B MNContig with relu
@@ -11,12 +13,12 @@
 //             results are identical from run to run).
 // dZ = dH o [Hout > 0] is never written to memory: the mask is applied while the
 // operand tile is loaded.
-#include "gemm_tile.h"
+#include "mx_tile.h"
 #include "sat_internal.h"
 
 namespace {
 
-using namespace sat::gemm;
+using namespace sat::mx;
 
 // out[i] = sum over slices s of part[s * stride + i], in a fixed order.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part,
@@ -99,10 +101,10 @@ extern "C" sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, in
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int64_t K = d_in;
   if (act == SAT_ACT_RELU)
-    gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStoreRelu>
+    gemm_kernel<3, Layout::KContig, false, Layout::MNContig, false, kStoreRelu>
         <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, EpiArgs{});
   else
-    gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStore>
+    gemm_kernel<3, Layout::KContig, false, Layout::MNContig, false, kStore>
         <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, EpiArgs{});
   return sat::check_launch();
 }
@@ -153,11 +155,11 @@ extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* H
     const Operand b{static_cast<const float*>(dH), ld_dh, mask, ld_ho};
     float* part = static_cast<float*>(workspace);
     if (relu)
-      gemm_f32_kernel<Layout::MNContig, false, Layout::MNContig, true, kStorePartial>
+      gemm_kernel<3, Layout::MNContig, false, Layout::MNContig, true, kStorePartial>
           <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
                                       EpiArgs{p.split_stride, nullptr, 0, nullptr, 0, 0});
     else
-      gemm_f32_kernel<Layout::MNContig, false, Layout::MNContig, false, kStorePartial>
+      gemm_kernel<3, Layout::MNContig, false, Layout::MNContig, false, kStorePartial>
           <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
                                       EpiArgs{p.split_stride, nullptr, 0, nullptr, 0, 0});
     if ((st = sat::check_launch()) != SAT_OK) return st;
@@ -176,10 +178,10 @@ extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* H
     const Operand b{static_cast<const float*>(W), ld_w, nullptr, 0};
     const int64_t K = d_out;
     if (relu)
-      gemm_f32_kernel<Layout::KContig, true, Layout::KContig, false, kStore>
+      gemm_kernel<3, Layout::KContig, true, Layout::KContig, false, kStore>
           <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, EpiArgs{});
     else
-      gemm_f32_kernel<Layout::KContig, false, Layout::KContig, false, kStore>
+      gemm_kernel<3, Layout::KContig, false, Layout::KContig, false, kStore>
           <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, EpiArgs{});
     if ((st = sat::check_launch()) != SAT_OK) return st;
   }

@@ -1,12 +1,8 @@
-// fp32 MFMA tile GEMM building blocks for gfx950 (64-wide wavefronts).
-//
-// A workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128 tile of
-// C = A * B and walks K in steps of 32. Each wavefront owns a 64 x 64 sub-tile
-// as 2 x 2 blocks of v_mfma_f32_32x32x2_f32 (16 accumulator registers each).
-// Operand tiles are staged in LDS k-major (S[k][mn]), which is the order the
-// MFMA operands want: lanes 0-31 read 32 consecutive mn at k, lanes 32-63 at
-// k+1. Global loads for step i+1 are issued into registers before the MFMAs of
-// step i, so HBM/L2 latency hides behind the matrix pipe.
+// fp32 MFMA (v_mfma_f32_32x32x2_f32) tile building blocks for gfx950, used by
+// the predictor's LSTM kernel. Operand tiles are staged in LDS k-major
+// (S[k][mn]), which is the order the fp32 MFMA operands want: lanes 0-31 read
+// 32 consecutive mn at k, lanes 32-63 at k+1. Global loads for step i+1 are
+// issued into registers before the MFMAs of step i.
 //
 // An operand is described by where its contiguous axis lies:
 //   KContig : element (mn, k) at p[mn * ld + k]  (transposing store into LDS)
@@ -141,133 +137,6 @@ __device__ __forceinline__ void mma_step(const float* As, const float* Bs, int w
 __device__ __forceinline__ int acc_row(int r, int lane) {
   return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
 }
-
-// kStore: C = acc; kStoreRelu: C = max(acc, 0); kStorePartial: slice blockIdx.z of a
-// split-K workspace; kStoreAddRows: C[m, :] = acc + add[row(m), :] with
-// row(m) = add_ids ? add_ids[m] : add_base + m (rows outside [0, add_rows) are skipped).
-enum Epilogue { kStore = 0, kStoreRelu = 1, kStorePartial = 2, kStoreAddRows = 3 };
-
-struct EpiArgs {
-  int64_t split_stride;
-  const float* add;
-  int64_t ld_add;
-  const int32_t* add_ids;
-  int64_t add_base;
-  int64_t add_rows;
-};
-
-
-template <Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_f32_kernel(Operand A, Operand B, int64_t M,
-                                                          int64_t N, int64_t K,
-                                                          int64_t k_per_split, float* C,
-                                                          int64_t ldc, EpiArgs ep) {
-  __shared__ __attribute__((aligned(16))) float smem[2 * TILE_FLOATS];
-  float* As = smem;
-  float* Bs = smem + TILE_FLOATS;
-  const int t = threadIdx.x;
-  const int lane = t & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-  const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
-  const int64_t n0 = static_cast<int64_t>(blockIdx.y) * BN;
-  const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * k_per_split;
-  const int64_t k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
-
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  TileRegs<BM> ra;
-  TileRegs<BN> rb;
-  if (k_begin < k_end) {
-    load_tile<BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
-    load_tile<BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
-  }
-  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
-    __syncthreads();
-    store_tile<BM, LA>(ra, As, t);
-    store_tile<BN, LB>(rb, Bs, t);
-    __syncthreads();
-    if (k0 + BK < k_end) {
-      load_tile<BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
-      load_tile<BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
-    }
-    mma_step(As, Bs, wm, wn, lane, acc);
-  }
-
-  // ---- epilogue: the tile goes through LDS (the operand buffers are free now)
-  // so that global accesses are 16 bytes per lane and 512 bytes per row
-  // segment; two passes of 64 rows each fit the 33 KiB of operand staging.
-  float* Cb = C;
-  if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * ep.split_stride;
-  const int c = lane & 31;
-#pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    __syncthreads();
-    if (wm == p) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            smem[(i * 32 + acc_row(r, lane)) * LDS_LD + wn * 64 + j * 32 + c] = acc[i][j][r];
-    }
-    __syncthreads();
-    const int64_t n = n0 + ((t & 31) << 2);
-    int64_t src[8];
-    if constexpr (EPI == kStoreAddRows) {
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const int64_t m = m0 + p * 64 + (t >> 5) + 8 * q;
-        int64_t sr = -1;
-        if (m < M) {
-          sr = ep.add_ids ? static_cast<int64_t>(ep.add_ids[m]) : ep.add_base + m;
-          if (sr < 0 || sr >= ep.add_rows) sr = -1;  // bad id: leave the row alone
-        }
-        src[q] = sr;
-      }
-    }
-    f32x4 v[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      v[q] = *reinterpret_cast<const f32x4*>(&smem[((t >> 5) + 8 * q) * LDS_LD + ((t & 31) << 2)]);
-      if constexpr (EPI == kStoreRelu) {
-        v[q].x = v[q].x > 0.f ? v[q].x : 0.f;
-        v[q].y = v[q].y > 0.f ? v[q].y : 0.f;
-        v[q].z = v[q].z > 0.f ? v[q].z : 0.f;
-        v[q].w = v[q].w > 0.f ? v[q].w : 0.f;
-      }
-      if constexpr (EPI == kStoreAddRows) {
-        if (src[q] >= 0 && n < N)
-          v[q] += *reinterpret_cast<const f32x4*>(ep.add + src[q] * ep.ld_add + n);
-      }
-    }
-#pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int64_t m = m0 + p * 64 + (t >> 5) + 8 * q;
-      if (m >= M || n >= N) continue;
-      if constexpr (EPI == kStoreAddRows) {
-        if (src[q] < 0) continue;
-      }
-      float* y = Cb + m * ldc + n;
-      const int64_t left = N - n;
-      if (left >= 4) {
-        *reinterpret_cast<f32x4*>(y) = v[q];
-      } else {
-        y[0] = v[q].x;
-        if (left > 1) y[1] = v[q].y;
-        if (left > 2) y[2] = v[q].z;
-      }
-    }
-  }
-}
-
 
 }  // namespace gemm
 }  // namespace sat

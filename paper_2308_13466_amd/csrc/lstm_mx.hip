@@ -1,0 +1,297 @@
+// LSTM of the embedding predictor (Sec. "Embedding Predictor") on the bf16 MFMA
+// pipe with the exact three-way fp32 split of mx_tile.h, for hidden sizes 32
+// and 64.
+//
+// A workgroup owns 128 nodes and all 4*d_s gate columns. Per time step the gate
+// pre-activations [x_s | h_{s-1}] [Wx | Wh]^T are accumulated in registers
+// (a wavefront holds the i, f, g, o blocks of the same (node, hidden unit)
+// positions, so the cell update is register-local), c stays in registers, and
+// h goes to LDS already split into bf16 pieces in the [node][unit] layout the
+// next step's recurrent product reads as its A operand. Only S = h_tau is
+// written to memory.
+//
+// The weights are split once per call by a small kernel into bf16 pieces
+// [piece][gate column][k] (k padded to a multiple of 32 with zeros), so every
+// workgroup streams them from L2 with plain 16-byte copies; x_s tiles are read
+// from the history table through the id list and split while they are written
+// to LDS. 128 nodes per workgroup (rather than 64) halves the weight traffic
+// per node, which is what bounds this kernel once the products run 2.7x faster
+// than on the fp32 pipe.
+#include <math.h>
+
+#include "mx_tile.h"
+#include "sat_internal.h"
+
+namespace {
+
+using namespace sat::mx;
+
+constexpr int kMaxTau = 8;
+constexpr int R = 128;  // nodes per workgroup
+
+struct SlotPtrs {
+  const float* p[kMaxTau];
+};
+
+__device__ __forceinline__ float sigmoidf_(float x) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
+}
+__device__ __forceinline__ float tanhf_(float x) {
+  return 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-2.8853900817779268f * x)) - 1.0f;
+}
+
+// W [rows, k_in] fp32 (dense) -> P [3][rows][k_pad] bf16 pieces, zero for k >= k_in.
+__global__ __launch_bounds__(256) void split_weights_kernel(const float* __restrict__ W, int rows,
+                                                            int k_in, int k_pad,
+                                                            uint16_t* __restrict__ P) {
+  const int idx = blockIdx.x * 256 + threadIdx.x;  // one pair of k per thread
+  const int pairs = k_pad / 2;
+  if (idx >= rows * pairs) return;
+  const int r = idx / pairs, k = 2 * (idx - r * pairs);
+  const float x0 = k < k_in ? W[r * k_in + k] : 0.f;
+  const float x1 = k + 1 < k_in ? W[r * k_in + k + 1] : 0.f;
+  uint32_t pc[3];
+  split2<3>(x0, x1, pc);
+#pragma unroll
+  for (int p = 0; p < 3; ++p)
+    *reinterpret_cast<uint32_t*>(P + (static_cast<int64_t>(p) * rows + r) * k_pad + k) = pc[p];
+}
+
+template <int DS>
+__global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
+                                                      int64_t ld_slot,
+                                                      const int32_t* __restrict__ ids,
+                                                      int64_t n_nodes, int d, int k_pad,
+                                                      const uint16_t* __restrict__ WxP,
+                                                      const uint16_t* __restrict__ WhP,
+                                                      const float* __restrict__ bias,
+                                                      float* __restrict__ S) {
+  constexpr int NP = 3;
+  constexpr int WN = DS / 32;       // wavefronts along hidden units
+  constexpr int WM = 4 / WN;        // wavefronts along nodes
+  constexpr int RB = R / (32 * WM); // 32-row blocks per wavefront
+  constexpr int NB = 4 * DS;        // gate columns
+  constexpr int H_ROW_B = DS * 2 + 16;        // bytes per node row of a staged h piece
+  constexpr int H_PIECE_B = R * H_ROW_B;
+  constexpr int B_CHUNKS = NP * NB * 4 / 256; // 16-byte weight chunks per thread per K step
+  __shared__ __attribute__((aligned(16))) unsigned char As[tile_bytes<R, NP>()];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[tile_bytes<NB, NP>()];
+  __shared__ __attribute__((aligned(16))) unsigned char Hs[NP * H_PIECE_B];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int c = lane & 31;
+  const int64_t node0 = static_cast<int64_t>(blockIdx.x) * R;
+
+  // table row of each node this thread loads x for (-1: nothing to load)
+  int64_t arow[R / 32];
+#pragma unroll
+  for (int i = 0; i < R / 32; ++i) {
+    const int64_t node = node0 + (t >> 3) + 32 * i;
+    int64_t r = -1;
+    if (node < n_nodes) {
+      r = ids ? static_cast<int64_t>(ids[node]) : node;
+      if (r < 0 || r >= n_rows_slot) r = -1;
+    }
+    arow[i] = r;
+  }
+  const int unit = 32 * wn + c;
+  const float b_i = bias[unit], b_f = bias[DS + unit], b_g = bias[2 * DS + unit],
+              b_o = bias[3 * DS + unit];
+
+  float cstate[RB][16];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) cstate[rb][r] = 0.f;
+  float hval[RB][16];
+
+  // weight chunk c (16 bytes): piece = c / (NB * 4), column n = (c / 4) % NB, k chunk = c % 4
+  auto load_w = [&](const uint16_t* P, int kp, int k0, u32x4 (&rw)[B_CHUNKS]) {
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      const int ch = t + 256 * i;
+      const int piece = ch / (NB * 4), n = (ch >> 2) % NB, kc = ch & 3;
+      rw[i] = *reinterpret_cast<const u32x4*>(P + (static_cast<int64_t>(piece) * NB + n) * kp + k0 +
+                                              8 * kc);
+    }
+  };
+  auto store_w = [&](const u32x4 (&rw)[B_CHUNKS]) {
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+      const int ch = t + 256 * i;
+      const int piece = ch / (NB * 4), n = (ch >> 2) % NB, kc = ch & 3;
+      *reinterpret_cast<u32x4*>(Bs + piece * piece_bytes<NB>() + n * ROW_B + 16 * kc) = rw[i];
+    }
+  };
+
+  for (int s = 0; s < tau; ++s) {
+    f32x16 acc[RB][4];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rb][g][r] = 0.f;
+
+    // one K step of products: A rows from `Ap` (row stride a_row_b, piece stride
+    // a_piece_b, k chunk offset a_kc), B from the staged weight tile
+    auto products = [&](const unsigned char* Ap, int a_row_b, int a_piece_b, int a_kc0) {
+#pragma unroll
+      for (int kc = 0; kc < BK / 16; ++kc) {
+        bf16x8 a[RB][NP], b[4][NP];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb)
+            a[rb][p] = *reinterpret_cast<const bf16x8*>(
+                Ap + p * a_piece_b + (32 * (wm * RB + rb) + c) * a_row_b + 32 * (a_kc0 + kc) +
+                16 * (lane >> 5));
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+            b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), g * DS + 32 * wn, kc, lane);
+        }
+#pragma unroll
+        for (int q = 0; q < n_products<NP>(); ++q)
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              if (s == 0 && g == 1) continue;  // c_0 = 0: the forget gate is not needed yet
+              acc[rb][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  a[rb][product_a<NP>(q)], b[g][product_b<NP>(q)], acc[rb][g], 0, 0, 0);
+            }
+      }
+    };
+
+    // ---- input part: x_s Wx^T, K = d (padded to k_pad with zero weights)
+    const float* xs = slots.p[s];
+    auto load_x = [&](int k0, TileRegs<R>& ra) {
+#pragma unroll
+      for (int i = 0; i < R / 32; ++i) {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        const int k = k0 + ((t & 7) << 2);
+        if (arow[i] >= 0 && k < d) {
+          v = *reinterpret_cast<const f32x4*>(xs + arow[i] * ld_slot + k);
+          if (k + 3 >= d) {
+            if (k + 1 >= d) v.y = 0.f;
+            if (k + 2 >= d) v.z = 0.f;
+            v.w = 0.f;
+          }
+        }
+        ra.v[i] = v;
+      }
+    };
+    TileRegs<R> ra;
+    u32x4 rw[B_CHUNKS];
+    load_x(0, ra);
+    load_w(WxP, k_pad, 0, rw);
+    for (int k0 = 0; k0 < k_pad; k0 += BK) {
+      __syncthreads();
+      store_tile<R, Layout::KContig, NP>(ra, As, t);
+      store_w(rw);
+      __syncthreads();
+      if (k0 + BK < k_pad) {
+        load_x(k0 + BK, ra);
+        load_w(WxP, k_pad, k0 + BK, rw);
+      }
+      products(As, ROW_B, piece_bytes<R>(), 0);
+    }
+    // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
+    if (s > 0) {
+      load_w(WhP, DS, 0, rw);
+      for (int k0 = 0; k0 < DS; k0 += BK) {
+        __syncthreads();
+        store_w(rw);
+        __syncthreads();
+        if (k0 + BK < DS) load_w(WhP, DS, k0 + BK, rw);
+        products(Hs, H_ROW_B, H_PIECE_B, k0 / 16);
+      }
+    }
+    // ---- cell update, register-local
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float gi = sigmoidf_(acc[rb][0][r] + b_i);
+        const float gg = tanhf_(acc[rb][2][r] + b_g);
+        const float go = sigmoidf_(acc[rb][3][r] + b_o);
+        if (s == 0) {
+          cstate[rb][r] = gi * gg;
+        } else {
+          const float gf = sigmoidf_(acc[rb][1][r] + b_f);
+          cstate[rb][r] = gf * cstate[rb][r] + gi * gg;
+        }
+        hval[rb][r] = go * tanhf_(cstate[rb][r]);
+      }
+    if (s + 1 < tau) {
+      __syncthreads();  // every wavefront has finished reading Hs for this step
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          uint32_t pc[NP];
+          split2<NP>(hval[rb][r], 0.f, pc);
+          const int row = 32 * (wm * RB + rb) + acc_row(r, lane);
+#pragma unroll
+          for (int p = 0; p < NP; ++p)
+            *reinterpret_cast<uint16_t*>(Hs + p * H_PIECE_B + row * H_ROW_B + 2 * unit) =
+                static_cast<uint16_t>(pc[p] & 0xffffu);
+        }
+      // the next step's first __syncthreads orders these writes before any read
+    }
+  }
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int64_t node = node0 + 32 * (wm * RB + rb) + acc_row(r, lane);
+      if (node < n_nodes) S[node * DS + unit] = hval[rb][r];
+    }
+}
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+}  // namespace
+
+namespace sat {
+
+// Bytes of workspace the split-weight copies need (0 if this path does not serve d_s).
+int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
+  if (d_s != 32 && d_s != 64) return 0;
+  const int64_t k_pad = round_up(d, 32);
+  return round_up(3 * 4 * d_s * k_pad * 2, 256) + round_up(3 * 4 * d_s * static_cast<int64_t>(d_s) * 2, 256);
+}
+
+// S [n_nodes, d_s] = last hidden state of the LSTM over the tau slots. ws points at
+// lstm_mx_workspace_bytes() bytes, 256-byte aligned. Only d_s = 32 and 64.
+sat_status launch_lstm_mx(const float* const* slot_ptrs, int tau, int64_t n_rows_slot,
+                          int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
+                          int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
+                          void* ws, hipStream_t st) {
+  const int k_pad = static_cast<int>(round_up(d, 32));
+  const int nb = 4 * d_s;
+  uint16_t* WxP = static_cast<uint16_t*>(ws);
+  uint16_t* WhP = WxP + round_up(3 * static_cast<int64_t>(nb) * k_pad * 2, 256) / 2;
+  split_weights_kernel<<<dim3((nb * (k_pad / 2) + 255) / 256), dim3(256), 0, st>>>(Wx, nb, d, k_pad,
+                                                                                  WxP);
+  split_weights_kernel<<<dim3((nb * (d_s / 2) + 255) / 256), dim3(256), 0, st>>>(Wh, nb, d_s, d_s,
+                                                                                WhP);
+  sat_status rc = sat::check_launch();
+  if (rc != SAT_OK) return rc;
+  SlotPtrs sp;
+  for (int s = 0; s < kMaxTau; ++s) sp.p[s] = s < tau ? slot_ptrs[s] : nullptr;
+  const int64_t blocks = (n_nodes + R - 1) / R;
+  if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
+  if (d_s == 32)
+    lstm_mx_kernel<32><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
+        sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S);
+  else
+    lstm_mx_kernel<64><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
+        sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S);
+  return sat::check_launch();
+}
+
+}  // namespace sat

@@ -1,0 +1,361 @@
+// Tile GEMM on the bf16 MFMA pipe of gfx950 (v_mfma_f32_32x32x16_bf16), used
+// for fp32 data through an exact three-way split.
+//
+// Why: the fp32 MFMA pipe peaks at 157 TFLOP/s, the bf16 pipe at 2.5 PFLOP/s
+// (16x). An fp32 value x is split into three bf16 pieces x = x1 + x2 + x3
+// (x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2); each subtraction is
+// exact in fp32 and the three 8-bit significands cover fp32's 24 bits). A
+// product a*b is then the sum of nine piece products, each EXACT in the
+// MFMA's fp32 accumulator (8 x 8 bit significands). The six products with
+// i + j <= 4 are kept; the dropped ones are below 2^-24 |a b|, i.e. below one
+// fp32 rounding of the product itself. Six bf16 MFMAs cost 6/16 of one fp32
+// MFMA's time for the same k-extent, and one instruction covers 16 k instead
+// of 2, so the accumulator is also rounded less often than on the fp32 pipe.
+//
+// Layout: a workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128
+// tile, K in steps of 32. Operand tiles are staged in LDS per piece as
+// [mn][k] bf16 with k contiguous and rows padded to 80 bytes: a lane's MFMA
+// operand (8 consecutive k of one row) is one 16-byte LDS read, conflict-free
+// across the wavefront. fp32 operands are split while they are written to LDS;
+// global loads for step i+1 are issued before the MFMAs of step i.
+#ifndef SAT_MX_TILE_H_
+#define SAT_MX_TILE_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sat {
+namespace mx {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int ROW_B = BK * 2 + 16;  // bytes per staged row: 32 bf16 + 16 bytes padding
+
+template <int MN>
+constexpr int piece_bytes() { return MN * ROW_B; }
+template <int MN, int NP>
+constexpr int tile_bytes() { return NP * MN * ROW_B; }
+
+enum class Layout { KContig, MNContig };
+
+// fp32 operand: element (mn, k) at p[mn * ld + k] (KContig) or p[k * ld + mn]
+// (MNContig); mask (optional) has the same indexing with its own ld, and an
+// element whose mask value is not > 0 reads as 0.
+struct Operand {
+  const float* p;
+  int64_t ld;
+  const float* mask;
+  int64_t ld_mask;
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {  // RNE, a in the low half
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float low_as_f32(uint32_t p) { return __builtin_bit_cast(float, p << 16); }
+__device__ __forceinline__ float high_as_f32(uint32_t p) {
+  return __builtin_bit_cast(float, p & 0xffff0000u);
+}
+
+// out[p] = packed p-th pieces of (x0, x1)
+template <int NP>
+__device__ __forceinline__ void split2(float x0, float x1, uint32_t (&out)[NP]) {
+  out[0] = pack_bf16(x0, x1);
+  if constexpr (NP > 1) {
+    x0 -= low_as_f32(out[0]);
+    x1 -= high_as_f32(out[0]);
+    out[1] = pack_bf16(x0, x1);
+  }
+  if constexpr (NP > 2) {
+    x0 -= low_as_f32(out[1]);
+    x1 -= high_as_f32(out[1]);
+    out[2] = pack_bf16(x0, x1);
+  }
+}
+
+// One thread's share (MN / 8 floats) of an MN x 32 fp32 operand tile.
+//  KContig : v[i] = 4 consecutive k of row (t / 8 + 32 i), k = 4 (t % 8)
+//  MNContig: v[2g], v[2g+1] = 8 consecutive k of column mn = t % MN,
+//            k = 8 (t / MN + (256 / MN) g)            (needs MN >= 64)
+template <int MN>
+struct TileRegs {
+  f32x4 v[MN / 32];
+};
+
+template <int MN, Layout L, bool MASK>
+__device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_t mn_lim,
+                                          int64_t k0, int64_t k_lim, TileRegs<MN>& r, int t) {
+  if constexpr (L == Layout::KContig) {
+#pragma unroll
+    for (int i = 0; i < MN / 32; ++i) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      const int64_t mn = mn0 + (t >> 3) + 32 * i;
+      const int64_t k = k0 + ((t & 7) << 2);
+      if (mn < mn_lim && k < k_lim) {
+        v = *reinterpret_cast<const f32x4*>(op.p + mn * op.ld + k);
+        if constexpr (MASK) {
+          const f32x4 h = *reinterpret_cast<const f32x4*>(op.mask + mn * op.ld_mask + k);
+          v.x = h.x > 0.f ? v.x : 0.f;
+          v.y = h.y > 0.f ? v.y : 0.f;
+          v.z = h.z > 0.f ? v.z : 0.f;
+          v.w = h.w > 0.f ? v.w : 0.f;
+        }
+        if (k + 3 >= k_lim) {
+          if (k + 1 >= k_lim) v.y = 0.f;
+          if (k + 2 >= k_lim) v.z = 0.f;
+          v.w = 0.f;
+        }
+      }
+      r.v[i] = v;
+    }
+  } else {
+    static_assert(MN >= 64 && MN <= 256, "MNContig tiles are 64..256 wide");
+    constexpr int KG = 256 / MN;  // k-groups of 8 covered by the thread index
+    const int64_t mn = mn0 + (t % MN);
+    const bool mn_ok = mn < mn_lim;
+#pragma unroll
+    for (int g = 0; g < MN / 64; ++g) {
+      const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
+      float e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float x = 0.f;
+        if (mn_ok && k8 + j < k_lim) {
+          x = op.p[(k8 + j) * op.ld + mn];
+          if constexpr (MASK) x = op.mask[(k8 + j) * op.ld_mask + mn] > 0.f ? x : 0.f;
+        }
+        e[j] = x;
+      }
+      r.v[2 * g] = f32x4{e[0], e[1], e[2], e[3]};
+      r.v[2 * g + 1] = f32x4{e[4], e[5], e[6], e[7]};
+    }
+  }
+}
+
+// Split the registers into NP bf16 pieces and write them to the staged tile at S
+// (piece p at S + p * piece_bytes<MN>()).
+template <int MN, Layout L, int NP>
+__device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char* S, int t) {
+  if constexpr (L == Layout::KContig) {
+#pragma unroll
+    for (int i = 0; i < MN / 32; ++i) {
+      uint32_t lo[NP], hi[NP];
+      split2<NP>(r.v[i].x, r.v[i].y, lo);
+      split2<NP>(r.v[i].z, r.v[i].w, hi);
+      unsigned char* s = S + ((t >> 3) + 32 * i) * ROW_B + ((t & 7) << 3);
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
+        *reinterpret_cast<u32x2*>(s + p * piece_bytes<MN>()) = u32x2{lo[p], hi[p]};
+    }
+  } else {
+    constexpr int KG = 256 / MN;
+#pragma unroll
+    for (int g = 0; g < MN / 64; ++g) {
+      uint32_t q0[NP], q1[NP], q2[NP], q3[NP];
+      split2<NP>(r.v[2 * g].x, r.v[2 * g].y, q0);
+      split2<NP>(r.v[2 * g].z, r.v[2 * g].w, q1);
+      split2<NP>(r.v[2 * g + 1].x, r.v[2 * g + 1].y, q2);
+      split2<NP>(r.v[2 * g + 1].z, r.v[2 * g + 1].w, q3);
+      unsigned char* s = S + (t % MN) * ROW_B + 16 * ((t / MN) + KG * g);
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
+        *reinterpret_cast<u32x4*>(s + p * piece_bytes<MN>()) = u32x4{q0[p], q1[p], q2[p], q3[p]};
+    }
+  }
+}
+
+// 16-byte MFMA operand of `lane`: row (row0 + lane % 32), k = 16 kc + 8 (lane / 32) .. + 7
+__device__ __forceinline__ bf16x8 read_operand(const unsigned char* piece, int row0, int kc,
+                                               int lane) {
+  return *reinterpret_cast<const bf16x8*>(piece + (row0 + (lane & 31)) * ROW_B + 32 * kc +
+                                          16 * (lane >> 5));
+}
+
+// Which piece products are accumulated, small terms first: for NP = 3 the six
+// with i + j <= 4 (0-based piece indices below), for NP = 1 the single product.
+template <int NP>
+constexpr int n_products() { return NP == 3 ? 6 : 1; }
+template <int NP>
+constexpr int product_a(int q) {
+  return NP == 3 ? (q == 0 ? 0 : q == 1 ? 2 : q == 2 ? 1 : q == 3 ? 0 : q == 4 ? 1 : 0) : 0;
+}
+template <int NP>
+constexpr int product_b(int q) {
+  return NP == 3 ? (q == 0 ? 2 : q == 1 ? 0 : q == 2 ? 1 : q == 3 ? 1 : q == 4 ? 0 : 0) : 0;
+}
+
+// acc[i][j] += A(64 wm + 32 i .., :) * B(64 wn + 32 j .., :)^T over one BK step.
+template <int NP>
+__device__ __forceinline__ void mma_step(const unsigned char* As, const unsigned char* Bs, int wm,
+                                         int wn, int lane, f32x16 (&acc)[2][2]) {
+#pragma unroll
+  for (int kc = 0; kc < BK / 16; ++kc) {
+    bf16x8 a[2][NP], b[2][NP];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        a[i][p] = read_operand(As + p * piece_bytes<BM>(), 64 * wm + 32 * i, kc, lane);
+        b[i][p] = read_operand(Bs + p * piece_bytes<BN>(), 64 * wn + 32 * i, kc, lane);
+      }
+#pragma unroll
+    for (int q = 0; q < n_products<NP>(); ++q)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              a[i][product_a<NP>(q)], b[j][product_b<NP>(q)], acc[i][j], 0, 0, 0);
+  }
+}
+
+// Position of accumulator register r of a 32 x 32 block held by `lane`:
+// column = lane % 32, row = 8 (r / 4) + 4 (lane / 32) + r % 4.
+__device__ __forceinline__ int acc_row(int r, int lane) {
+  return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+}
+
+// kStore: C = acc; kStoreRelu: C = max(acc, 0); kStorePartial: slice blockIdx.z of a
+// split-K workspace; kStoreAddRows: C[m, :] = acc + add[row(m), :] with
+// row(m) = add_ids ? add_ids[m] : add_base + m (rows outside [0, add_rows) are skipped).
+enum Epilogue { kStore = 0, kStoreRelu = 1, kStorePartial = 2, kStoreAddRows = 3 };
+
+struct EpiArgs {
+  int64_t split_stride;
+  const float* add;
+  int64_t ld_add;
+  const int32_t* add_ids;
+  int64_t add_base;
+  int64_t add_rows;
+};
+
+constexpr int C_LD = 128 + 4;  // floats per row of the staged output half-tile
+template <int NP>
+constexpr int smem_bytes() {
+  return (2 * tile_bytes<128, NP>() > 64 * C_LD * 4) ? 2 * tile_bytes<128, NP>() : 64 * C_LD * 4;
+}
+
+// C[M, N] = A * B (fp32 in, fp32 out, fp32-equivalent accuracy for NP = 3).
+// A: element (m, k); B: element (n, k) in the Operand sense above.
+template <int NP, Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int64_t M, int64_t N,
+                                                      int64_t K, int64_t k_per_split, float* C,
+                                                      int64_t ldc, EpiArgs ep) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[smem_bytes<NP>()];
+  unsigned char* As = smem;
+  unsigned char* Bs = smem + tile_bytes<BM, NP>();
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t m0 = static_cast<int64_t>(blockIdx.x) * BM;
+  const int64_t n0 = static_cast<int64_t>(blockIdx.y) * BN;
+  const int64_t k_begin = static_cast<int64_t>(blockIdx.z) * k_per_split;
+  const int64_t k_end = (k_begin + k_per_split < K) ? k_begin + k_per_split : K;
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  TileRegs<BM> ra;
+  TileRegs<BN> rb;
+  if (k_begin < k_end) {
+    load_tile<BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
+    load_tile<BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
+  }
+  for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
+    __syncthreads();
+    store_tile<BM, LA, NP>(ra, As, t);
+    store_tile<BN, LB, NP>(rb, Bs, t);
+    __syncthreads();
+    if (k0 + BK < k_end) {
+      load_tile<BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
+      load_tile<BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
+    }
+    mma_step<NP>(As, Bs, wm, wn, lane, acc);
+  }
+
+  // ---- epilogue: the tile goes through LDS (the operand staging is free now)
+  // so that global accesses are 16 bytes per lane and 512 bytes per row
+  // segment; two passes of 64 rows each.
+  float* Cs = reinterpret_cast<float*>(smem);
+  float* Cb = C;
+  if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * ep.split_stride;
+  const int c = lane & 31;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    __syncthreads();
+    if (wm == p) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            Cs[(i * 32 + acc_row(r, lane)) * C_LD + wn * 64 + j * 32 + c] = acc[i][j][r];
+    }
+    __syncthreads();
+    const int64_t n = n0 + ((t & 31) << 2);
+    int64_t src[8];
+    if constexpr (EPI == kStoreAddRows) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int64_t m = m0 + p * 64 + (t >> 5) + 8 * q;
+        int64_t sr = -1;
+        if (m < M) {
+          sr = ep.add_ids ? static_cast<int64_t>(ep.add_ids[m]) : ep.add_base + m;
+          if (sr < 0 || sr >= ep.add_rows) sr = -1;  // bad id: leave the row alone
+        }
+        src[q] = sr;
+      }
+    }
+    f32x4 v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      v[q] = *reinterpret_cast<const f32x4*>(&Cs[((t >> 5) + 8 * q) * C_LD + ((t & 31) << 2)]);
+      if constexpr (EPI == kStoreRelu) {
+        v[q].x = v[q].x > 0.f ? v[q].x : 0.f;
+        v[q].y = v[q].y > 0.f ? v[q].y : 0.f;
+        v[q].z = v[q].z > 0.f ? v[q].z : 0.f;
+        v[q].w = v[q].w > 0.f ? v[q].w : 0.f;
+      }
+      if constexpr (EPI == kStoreAddRows) {
+        if (src[q] >= 0 && n < N)
+          v[q] += *reinterpret_cast<const f32x4*>(ep.add + src[q] * ep.ld_add + n);
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int64_t m = m0 + p * 64 + (t >> 5) + 8 * q;
+      if (m >= M || n >= N) continue;
+      if constexpr (EPI == kStoreAddRows) {
+        if (src[q] < 0) continue;
+      }
+      float* y = Cb + m * ldc + n;
+      const int64_t left = N - n;
+      if (left >= 4) {
+        *reinterpret_cast<f32x4*>(y) = v[q];
+      } else {
+        y[0] = v[q].x;
+        if (left > 1) y[1] = v[q].y;
+        if (left > 2) y[2] = v[q].z;
+      }
+    }
+  }
+}
+
+}  // namespace mx
+}  // namespace sat
+
+#endif  // SAT_MX_TILE_H_

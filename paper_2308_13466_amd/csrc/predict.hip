@@ -23,6 +23,7 @@
 #include <math.h>
 
 #include "gemm_tile.h"
+#include "mx_tile.h"
 #include "sat_internal.h"
 
 namespace sat {
@@ -35,6 +36,12 @@ sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const i
                        const float* val, const float* X, int64_t ld_x, int64_t n_x_rows, float* Y,
                        int64_t ld_y, int64_t n_rows, int32_t d, const float* self_val,
                        int64_t self_off, int64_t total_entries, hipStream_t stream);
+// lstm_mx.hip: the LSTM on the bf16 MFMA pipe (d_s = 32, 64)
+int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s);
+sat_status launch_lstm_mx(const float* const* slot_ptrs, int tau, int64_t n_rows_slot,
+                          int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
+                          int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
+                          void* ws, hipStream_t st);
 }  // namespace sat
 
 namespace {
@@ -237,12 +244,13 @@ extern "C" int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, 
   (void)d;
   (void)tau;
   if (n_local < 0 || n_halo < 0 || d_s <= 0) return 0;
-  // S [n_bar, d_s], the hop aggregate [n_halo, d_s], then the k-major copies of
-  // Wx [d, 4 d_s] and Wh [d_s, 4 d_s]
+  // S [n_bar, d_s], the hop aggregate [n_halo, d_s], then the re-laid weights:
+  // bf16 pieces for d_s <= 64, k-major fp32 copies of Wx, Wh for d_s = 128
+  const int64_t w_fp32 = round_up(static_cast<int64_t>(d) * 4 * d_s * 4, 256) +
+                         round_up(static_cast<int64_t>(d_s) * 4 * d_s * 4, 256);
+  const int64_t w_mx = sat::lstm_mx_workspace_bytes(d, d_s);
   return round_up((n_local + n_halo) * static_cast<int64_t>(d_s) * 4, 256) +
-         round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256) +
-         round_up(static_cast<int64_t>(d) * 4 * d_s * 4, 256) +
-         round_up(static_cast<int64_t>(d_s) * 4 * d_s * 4, 256);
+         round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256) + (w_mx > 0 ? w_mx : w_fp32);
 }
 
 extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w,
@@ -286,34 +294,29 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   float* S = static_cast<float*>(workspace);
   float* Agg = S + round_up(n_bar * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
   float* WxT = Agg + round_up(pv->n_halo * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
-  float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
-  {
+  sat_status rc;
+  if (w->d_s <= 64) {
+    const float* sptr[kMaxTau];
+    for (int s = 0; s < w->tau; ++s) sptr[s] = static_cast<const float*>(slots[s]);
+    rc = sat::launch_lstm_mx(sptr, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->d_s, w->Wx,
+                             w->Wh, w->b, S, WxT, st);
+  } else {
+    float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
     const int nb = 4 * w->d_s;
     transpose_kernel<<<dim3((nb * d + 255) / 256), dim3(256), 0, st>>>(w->Wx, nb, d, WxT);
     transpose_kernel<<<dim3((nb * w->d_s + 255) / 256), dim3(256), 0, st>>>(w->Wh, nb, w->d_s, WhT);
-    sat_status rc0 = sat::check_launch();
-    if (rc0 != SAT_OK) return rc0;
+    if ((rc = sat::check_launch()) != SAT_OK) return rc;
+    SlotPtrs sp;
+    for (int s = 0; s < kMaxTau; ++s)
+      sp.p[s] = s < w->tau ? static_cast<const float*>(slots[s]) : nullptr;
+    constexpr int rows = 32;  // nodes per workgroup of lstm_kernel<128>
+    const int64_t blocks = (n_bar + rows - 1) / rows;
+    lstm_kernel<128><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
+        sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, WxT, WhT, w->b, S);
+    rc = sat::check_launch();
   }
-
-  SlotPtrs sp;
-  for (int s = 0; s < kMaxTau; ++s)
-    sp.p[s] = s < w->tau ? static_cast<const float*>(slots[s]) : nullptr;
-
-#define SAT_LSTM(DS)                                                                          \
-  do {                                                                                        \
-    constexpr int rows = 32 * (4 / ((DS) / 32));                                              \
-    const int64_t blocks = (n_bar + rows - 1) / rows;                                         \
-    lstm_kernel<DS><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(               \
-        sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, WxT, WhT, w->b, S);              \
-  } while (0)
-  switch (w->d_s) {
-    case 32: SAT_LSTM(32); break;
-    case 64: SAT_LSTM(64); break;
-    default: SAT_LSTM(128); break;
-  }
-  sat_status rc = sat::check_launch();
   if (rc != SAT_OK) return rc;
-#undef SAT_LSTM
+
   // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
   rc = sat::launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val, S, w->d_s,
                         pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, pv->h_self, pv->n_local,
@@ -321,13 +324,15 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   if (rc != SAT_OK) return rc;
   // hop, part 2: Hbar[n_local + u, :] = newest[row(u), :] + Agg[u, :] Wg
   {
-    const int64_t gx = (pv->n_halo + BM - 1) / BM;
-    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d + BN - 1) / BN), 1);
-    const Operand a{Agg, static_cast<int64_t>(w->d_s), nullptr, 0};
-    const Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
-    const EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
-                     n_rows_slot};
-    gemm_f32_kernel<Layout::KContig, false, Layout::MNContig, false, kStoreAddRows>
+    const int64_t gx = (pv->n_halo + sat::mx::BM - 1) / sat::mx::BM;
+    const dim3 grid(static_cast<unsigned>(gx),
+                    static_cast<unsigned>((d + sat::mx::BN - 1) / sat::mx::BN), 1);
+    const sat::mx::Operand a{Agg, static_cast<int64_t>(w->d_s), nullptr, 0};
+    const sat::mx::Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
+    const sat::mx::EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
+                              n_rows_slot};
+    sat::mx::gemm_kernel<3, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
+                         sat::mx::kStoreAddRows>
         <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
   }
   return sat::check_launch();
