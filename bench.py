@@ -215,7 +215,7 @@ def main():
 
 
 def cpu_baseline(view, dims, tau, d_s, X_host, hist_host, table_ids, Ws, omegas, y, edges,
-                 bypass, log, sample_rows=1024, sample_nodes=4096):
+                 bypass, log, sample_rows=8192, sample_nodes=65536):
     """Time the oracle (as it stands) on a row sample of every call of the step
     and extrapolate each call by rows_total / rows_sampled (rows of every call
     are independent of one another)."""

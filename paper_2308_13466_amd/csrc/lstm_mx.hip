@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
   constexpr int H_ROW_B = DS * 2 + 16;        // bytes per node row of a staged h piece
   constexpr int H_PIECE_B = R * H_ROW_B;
   constexpr int B_CHUNKS = NP * NB * 4 / 256; // 16-byte weight chunks per thread per K step
-  __shared__ __attribute__((aligned(16))) unsigned char As[tile_bytes<R, NP>()];
+  __shared__ __attribute__((aligned(16))) unsigned char As[2 * tile_bytes<R, NP>()];
   __shared__ __attribute__((aligned(16))) unsigned char Bs[tile_bytes<NB, NP>()];
   __shared__ __attribute__((aligned(16))) unsigned char Hs[NP * H_PIECE_B];
 
@@ -123,9 +123,34 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
     for (int i = 0; i < B_CHUNKS; ++i) {
       const int ch = t + 256 * i;
       const int piece = ch / (NB * 4), n = (ch >> 2) % NB, kc = ch & 3;
-      *reinterpret_cast<u32x4*>(Bs + piece * piece_bytes<NB>() + n * ROW_B + 16 * kc) = rw[i];
+      *reinterpret_cast<u32x4*>(Bs + piece * piece_bytes<NB>() + swz(n, kc)) = rw[i];
     }
   };
+
+  const int nk = k_pad / BK;
+  auto load_x = [&](int j, TileRegs<R>& ra) {   // x tile j of the stream (zeros past the end)
+    const int sj = j / nk;
+    const int k = (j - sj * nk) * BK + ((t & 7) << 2);
+    const bool live = sj < tau;
+    const float* xs = slots.p[live ? sj : 0];
+#pragma unroll
+    for (int i = 0; i < R / 32; ++i) {
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (live && arow[i] >= 0 && k < d) {
+        v = *reinterpret_cast<const f32x4*>(xs + arow[i] * ld_slot + k);
+        if (k + 3 >= d) {
+          if (k + 1 >= d) v.y = 0.f;
+          if (k + 2 >= d) v.z = 0.f;
+          v.w = 0.f;
+        }
+      }
+      ra.v[i] = v;
+    }
+  };
+  TileRegs<R> ra0;
+  load_x(0, ra0);
+  store_tile<R, Layout::KContig, NP>(ra0, As, t);   // tile 0 -> half 0 of the double buffer
+  load_x(1, ra0);
 
   for (int s = 0; s < tau; ++s) {
     f32x16 acc[RB][4];
@@ -136,9 +161,10 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[rb][g][r] = 0.f;
 
-    // one K step of products: A rows from `Ap` (row stride a_row_b, piece stride
-    // a_piece_b, k chunk offset a_kc), B from the staged weight tile
-    auto products = [&](const unsigned char* Ap, int a_row_b, int a_piece_b, int a_kc0) {
+    // one K step of products, B from the staged weight tile
+    // A operand: the staged x tile `Ax` (swizzled 64-byte rows), or if Ax == nullptr
+    // the h pieces in Hs (padded rows), k chunk offset a_kc0
+    auto products = [&](const unsigned char* Ax, int a_kc0) {
 #pragma unroll
       for (int kc = 0; kc < BK / 16; ++kc) {
         bf16x8 a[RB][NP], b[4][NP];
@@ -146,9 +172,10 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
         for (int p = 0; p < NP; ++p) {
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb)
-            a[rb][p] = *reinterpret_cast<const bf16x8*>(
-                Ap + p * a_piece_b + (32 * (wm * RB + rb) + c) * a_row_b + 32 * (a_kc0 + kc) +
-                16 * (lane >> 5));
+            a[rb][p] = Ax ? read_operand(Ax + p * piece_bytes<R>(), 32 * (wm * RB + rb), kc, lane)
+                          : *reinterpret_cast<const bf16x8*>(
+                                Hs + p * H_PIECE_B + (32 * (wm * RB + rb) + c) * H_ROW_B +
+                                32 * (a_kc0 + kc) + 16 * (lane >> 5));
 #pragma unroll
           for (int g = 0; g < 4; ++g)
             b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), g * DS + 32 * wn, kc, lane);
@@ -166,38 +193,23 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
       }
     };
 
-    // ---- input part: x_s Wx^T, K = d (padded to k_pad with zero weights)
-    const float* xs = slots.p[s];
-    auto load_x = [&](int k0, TileRegs<R>& ra) {
-#pragma unroll
-      for (int i = 0; i < R / 32; ++i) {
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        const int k = k0 + ((t & 7) << 2);
-        if (arow[i] >= 0 && k < d) {
-          v = *reinterpret_cast<const f32x4*>(xs + arow[i] * ld_slot + k);
-          if (k + 3 >= d) {
-            if (k + 1 >= d) v.y = 0.f;
-            if (k + 2 >= d) v.z = 0.f;
-            v.w = 0.f;
-          }
-        }
-        ra.v[i] = v;
-      }
-    };
-    TileRegs<R> ra;
+    // ---- input part: x_s Wx^T, K = d (padded to k_pad with zero weights). The x
+    // tiles of all time steps form one stream j = s * nk + i. Their rows come
+    // from HBM through the id list (the slowest loads of the kernel), so they get
+    // two product phases to arrive: while tile j is multiplied out of one half of
+    // the LDS double buffer, tile j+1 already sits in the other half and tile j+2
+    // is in flight in registers. Weight tiles (L2) are one step ahead in registers.
     u32x4 rw[B_CHUNKS];
-    load_x(0, ra);
     load_w(WxP, k_pad, 0, rw);
-    for (int k0 = 0; k0 < k_pad; k0 += BK) {
+    for (int i = 0; i < nk; ++i) {
+      const int j = s * nk + i;
       __syncthreads();
-      store_tile<R, Layout::KContig, NP>(ra, As, t);
       store_w(rw);
+      store_tile<R, Layout::KContig, NP>(ra0, As + ((j + 1) & 1) * tile_bytes<R, NP>(), t);
       __syncthreads();
-      if (k0 + BK < k_pad) {
-        load_x(k0 + BK, ra);
-        load_w(WxP, k_pad, k0 + BK, rw);
-      }
-      products(As, ROW_B, piece_bytes<R>(), 0);
+      load_x(j + 2, ra0);
+      if (i + 1 < nk) load_w(WxP, k_pad, (i + 1) * BK, rw);
+      products(As + (j & 1) * tile_bytes<R, NP>(), 0);
     }
     // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
     if (s > 0) {
@@ -207,7 +219,7 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
         store_w(rw);
         __syncthreads();
         if (k0 + BK < DS) load_w(WhP, DS, k0 + BK, rw);
-        products(Hs, H_ROW_B, H_PIECE_B, k0 / 16);
+        products(nullptr, k0 / 16);
       }
     }
     // ---- cell update, register-local

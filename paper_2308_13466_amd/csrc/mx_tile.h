@@ -14,10 +14,13 @@
 //
 // Layout: a workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128
 // tile, K in steps of 32. Operand tiles are staged in LDS per piece as
-// [mn][k] bf16 with k contiguous and rows padded to 80 bytes: a lane's MFMA
-// operand (8 consecutive k of one row) is one 16-byte LDS read, conflict-free
-// across the wavefront. fp32 operands are split while they are written to LDS;
-// global loads for step i+1 are issued before the MFMAs of step i.
+// [mn][k] bf16 with k contiguous, 64 bytes per row and no padding; the four
+// 16-byte chunks of a row are stored at chunk ^ ((row >> 1) & 3). A lane's MFMA
+// operand (8 consecutive k of one row) is one 16-byte LDS read, and with this
+// swizzle both those reads (32 consecutive rows, one chunk) and the tile
+// writes (whole rows) are free of bank conflicts. fp32 operands are split while
+// they are written to LDS; global loads for step i+1 are issued before the
+// MFMAs of step i.
 #ifndef SAT_MX_TILE_H_
 #define SAT_MX_TILE_H_
 
@@ -36,7 +39,12 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int ROW_B = BK * 2 + 16;  // bytes per staged row: 32 bf16 + 16 bytes padding
+constexpr int ROW_B = BK * 2;  // bytes per staged row: 32 bf16, chunks swizzled (see swz)
+
+// byte offset inside a staged piece of 16-byte chunk `chunk` (0..3) of row `row`
+__device__ __forceinline__ int swz(int row, int chunk) {
+  return row * ROW_B + ((chunk ^ ((row >> 1) & 3)) << 4);
+}
 
 template <int MN>
 constexpr int piece_bytes() { return MN * ROW_B; }
@@ -149,7 +157,7 @@ __device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char*
       uint32_t lo[NP], hi[NP];
       split2<NP>(r.v[i].x, r.v[i].y, lo);
       split2<NP>(r.v[i].z, r.v[i].w, hi);
-      unsigned char* s = S + ((t >> 3) + 32 * i) * ROW_B + ((t & 7) << 3);
+      unsigned char* s = S + swz((t >> 3) + 32 * i, (t & 7) >> 1) + ((t & 1) << 3);
 #pragma unroll
       for (int p = 0; p < NP; ++p)
         *reinterpret_cast<u32x2*>(s + p * piece_bytes<MN>()) = u32x2{lo[p], hi[p]};
@@ -163,7 +171,7 @@ __device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char*
       split2<NP>(r.v[2 * g].z, r.v[2 * g].w, q1);
       split2<NP>(r.v[2 * g + 1].x, r.v[2 * g + 1].y, q2);
       split2<NP>(r.v[2 * g + 1].z, r.v[2 * g + 1].w, q3);
-      unsigned char* s = S + (t % MN) * ROW_B + 16 * ((t / MN) + KG * g);
+      unsigned char* s = S + swz(t % MN, (t / MN) + KG * g);
 #pragma unroll
       for (int p = 0; p < NP; ++p)
         *reinterpret_cast<u32x4*>(s + p * piece_bytes<MN>()) = u32x4{q0[p], q1[p], q2[p], q3[p]};
@@ -174,8 +182,7 @@ __device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char*
 // 16-byte MFMA operand of `lane`: row (row0 + lane % 32), k = 16 kc + 8 (lane / 32) .. + 7
 __device__ __forceinline__ bf16x8 read_operand(const unsigned char* piece, int row0, int kc,
                                                int lane) {
-  return *reinterpret_cast<const bf16x8*>(piece + (row0 + (lane & 31)) * ROW_B + 32 * kc +
-                                          16 * (lane >> 5));
+  return *reinterpret_cast<const bf16x8*>(piece + swz(row0 + (lane & 31), 2 * kc + (lane >> 5)));
 }
 
 // Which piece products are accumulated, small terms first: for NP = 3 the six
