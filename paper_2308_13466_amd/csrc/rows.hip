@@ -15,68 +15,77 @@ using sat::kWave;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // GATHER: dense[k, :] = table[ids[k], :]   (SCATTER: table[ids[k], :] = dense[k, :])
+// Rows are handled as bytes (row_bytes, leading dimensions in bytes), so the same
+// kernels serve 4-byte and 2-byte elements; the tail after the last whole
+// 16-byte chunk is copied in 2-byte units.
 template <int G, bool SCATTER>
 __global__ __launch_bounds__(256) void row_copy_vec_kernel(
-    const uint32_t* __restrict__ src, int64_t ld_src, uint32_t* __restrict__ dst, int64_t ld_dst,
-    const int32_t* __restrict__ ids, int64_t id_base, int64_t n, int64_t n_table_rows, int32_t d) {
+    const unsigned char* __restrict__ src, int64_t ld_src, unsigned char* __restrict__ dst,
+    int64_t ld_dst, const int32_t* __restrict__ ids, int64_t id_base, int64_t n,
+    int64_t n_table_rows, int32_t row_bytes) {
   constexpr int kRowsPerBlock = 256 / G;
   const int lane_in_group = threadIdx.x % G;
   const int64_t k = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + threadIdx.x / G;
   if (k >= n) return;
   const int64_t r = ids ? static_cast<int64_t>(ids[k]) : k + id_base;
   if (r < 0 || r >= n_table_rows) return;  // bad id: skip the row
-  const uint32_t* s = src + (SCATTER ? k : r) * ld_src;
-  uint32_t* t = dst + (SCATTER ? r : k) * ld_dst;
-  const int nvec = d >> 2;
+  const unsigned char* s = src + (SCATTER ? k : r) * ld_src;
+  unsigned char* t = dst + (SCATTER ? r : k) * ld_dst;
+  const int nvec = row_bytes >> 4;
   for (int v = lane_in_group; v < nvec; v += G) {
     const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(s) + v);
     __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(t) + v);
   }
-  for (int c = (nvec << 2) + lane_in_group; c < d; c += G) t[c] = s[c];
+  const uint16_t* s2 = reinterpret_cast<const uint16_t*>(s);
+  uint16_t* t2 = reinterpret_cast<uint16_t*>(t);
+  for (int c = (nvec << 3) + lane_in_group; c < (row_bytes >> 1); c += G) t2[c] = s2[c];
 }
 
-// Fallback for rows that are not 16-byte aligned: element-wise.
+// Fallback for rows that are not 16-byte aligned: 2-byte units.
 template <bool SCATTER>
 __global__ __launch_bounds__(256) void row_copy_elem_kernel(
-    const uint32_t* __restrict__ src, int64_t ld_src, uint32_t* __restrict__ dst, int64_t ld_dst,
-    const int32_t* __restrict__ ids, int64_t id_base, int64_t n, int64_t n_table_rows, int32_t d) {
+    const unsigned char* __restrict__ src, int64_t ld_src, unsigned char* __restrict__ dst,
+    int64_t ld_dst, const int32_t* __restrict__ ids, int64_t id_base, int64_t n,
+    int64_t n_table_rows, int32_t row_bytes) {
   const int lane = threadIdx.x % kWave;
   const int64_t k = static_cast<int64_t>(blockIdx.x) * (256 / kWave) + threadIdx.x / kWave;
   if (k >= n) return;
   const int64_t r = ids ? static_cast<int64_t>(ids[k]) : k + id_base;
   if (r < 0 || r >= n_table_rows) return;
-  const uint32_t* s = src + (SCATTER ? k : r) * ld_src;
-  uint32_t* t = dst + (SCATTER ? r : k) * ld_dst;
-  for (int c = lane; c < d; c += kWave) t[c] = s[c];
+  const uint16_t* s = reinterpret_cast<const uint16_t*>(src + (SCATTER ? k : r) * ld_src);
+  uint16_t* t = reinterpret_cast<uint16_t*>(dst + (SCATTER ? r : k) * ld_dst);
+  for (int c = lane; c < (row_bytes >> 1); c += kWave) t[c] = s[c];
 }
 
+// ld_src / ld_dst in ELEMENTS of es bytes (es = 2 or 4), d elements per row.
 template <bool SCATTER>
 sat_status launch_row_copy(const void* src, int64_t ld_src, void* dst, int64_t ld_dst,
                            const int32_t* ids, int64_t id_base, int64_t n, int64_t n_table_rows,
-                           int32_t d, hipStream_t stream) {
+                           int32_t d, int es, hipStream_t stream) {
   if (n == 0 || d == 0) return SAT_OK;
-  const uint32_t* s = static_cast<const uint32_t*>(src);
-  uint32_t* t = static_cast<uint32_t*>(dst);
-  const bool vec = sat::aligned16(src) && sat::aligned16(dst) && (ld_src % 4 == 0) &&
-                   (ld_dst % 4 == 0);
+  const unsigned char* s = static_cast<const unsigned char*>(src);
+  unsigned char* t = static_cast<unsigned char*>(dst);
+  const int64_t lds = ld_src * es, ldd = ld_dst * es;
+  const int32_t row_bytes = d * es;
+  const bool vec = sat::aligned16(src) && sat::aligned16(dst) && (lds % 16 == 0) && (ldd % 16 == 0);
   if (!vec) {
     const int64_t blocks = (n + 3) / 4;
     if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
     row_copy_elem_kernel<SCATTER><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream>>>(
-        s, ld_src, t, ld_dst, ids, id_base, n, n_table_rows, d);
+        s, lds, t, ldd, ids, id_base, n, n_table_rows, row_bytes);
     return sat::check_launch();
   }
-  const int nvec = (d + 3) / 4;
+  const int nvec = (row_bytes + 15) / 16;
   int g = 1;
   while (g < 64 && g < nvec) g <<= 1;
   const int64_t rows_per_block = 256 / g;
   const int64_t blocks = (n + rows_per_block - 1) / rows_per_block;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
   const dim3 grid(static_cast<unsigned>(blocks)), block(256);
-#define SAT_ROWCOPY_CASE(G)                                                                 \
-  case G:                                                                                   \
-    row_copy_vec_kernel<G, SCATTER><<<grid, block, 0, stream>>>(s, ld_src, t, ld_dst, ids,    \
-                                                                id_base, n, n_table_rows, d); \
+#define SAT_ROWCOPY_CASE(G)                                                                    \
+  case G:                                                                                      \
+    row_copy_vec_kernel<G, SCATTER><<<grid, block, 0, stream>>>(s, lds, t, ldd, ids, id_base, n, \
+                                                                n_table_rows, row_bytes);      \
     break;
   switch (g) {
     SAT_ROWCOPY_CASE(1)
@@ -94,7 +103,7 @@ sat_status launch_row_copy(const void* src, int64_t ld_src, void* dst, int64_t l
 sat_status validate(const void* table, int64_t n_rows, int64_t ld_table, const int32_t* ids,
                     int64_t n, int32_t d, const void* dense, int64_t ld_dense, int32_t dtype) {
   if (n < 0 || d < 0 || n_rows < 0) return SAT_EINVAL;
-  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
   if (n == 0 || d == 0) return SAT_OK;
   if (!table || !ids || !dense) return SAT_EINVAL;
   if (ld_table < d || ld_dense < d) return SAT_EINVAL;
@@ -104,11 +113,13 @@ sat_status validate(const void* table, int64_t n_rows, int64_t ld_table, const i
 }  // namespace
 
 namespace sat {
-// dst[k, 0:d) = src[(ids ? ids[k] : k + id_base), 0:d); used by the predictor's bypass mode.
+// dst[k, 0:d) = src[(ids ? ids[k] : k + id_base), 0:d), elements of es bytes; used by the
+// predictor's bypass mode.
 sat_status row_gather(const void* src, int64_t ld_src, void* dst, int64_t ld_dst,
                       const int32_t* ids, int64_t id_base, int64_t n, int64_t n_src_rows,
-                      int32_t d, hipStream_t stream) {
-  return launch_row_copy<false>(src, ld_src, dst, ld_dst, ids, id_base, n, n_src_rows, d, stream);
+                      int32_t d, int es, hipStream_t stream) {
+  return launch_row_copy<false>(src, ld_src, dst, ld_dst, ids, id_base, n, n_src_rows, d, es,
+                                stream);
 }
 }  // namespace sat
 
@@ -118,7 +129,7 @@ extern "C" sat_status sat_history_gather(const void* table, int64_t n_rows, int6
   sat_status st = validate(table, n_rows, ld_table, ids, n, d, out, ld_out, dtype);
   if (st != SAT_OK) return st;
   return launch_row_copy<false>(table, ld_table, out, ld_out, ids, 0, n, n_rows, d,
-                                static_cast<hipStream_t>(stream));
+                                dtype == SAT_BF16 ? 2 : 4, static_cast<hipStream_t>(stream));
 }
 
 extern "C" sat_status sat_history_push(void* table, int64_t n_rows, int64_t ld_table,
@@ -127,5 +138,5 @@ extern "C" sat_status sat_history_push(void* table, int64_t n_rows, int64_t ld_t
   sat_status st = validate(table, n_rows, ld_table, ids, n, d, H, ld_h, dtype);
   if (st != SAT_OK) return st;
   return launch_row_copy<true>(H, ld_h, table, ld_table, ids, 0, n, n_rows, d,
-                               static_cast<hipStream_t>(stream));
+                               dtype == SAT_BF16 ? 2 : 4, static_cast<hipStream_t>(stream));
 }

@@ -9,11 +9,12 @@ from .configs import CONFIGS, get_config
 from .graphs import (Graph, sbm_graph, chung_lu_planted_graph, ring_graph, make_graph,
                      cached_graph)
 from .tensors import (substreams, normal_f32, glorot_uniform_f32, labels_i32,
-                      predictor_params_f32, history_standin_f32)
+                      predictor_params_f32, history_standin_f32, bf16_bits_from_f32,
+                      f32_from_bf16_bits)
 
 __all__ = [
     "CONFIGS", "get_config", "Graph", "sbm_graph", "chung_lu_planted_graph",
     "ring_graph", "make_graph", "cached_graph", "substreams", "normal_f32",
     "glorot_uniform_f32", "labels_i32", "predictor_params_f32",
-    "history_standin_f32",
+    "history_standin_f32", "bf16_bits_from_f32", "f32_from_bf16_bits",
 ]

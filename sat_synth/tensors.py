@@ -102,3 +102,16 @@ def history_standin_f32(ss, rows, cols, tau, noise_std, ld=None):
         t += base
         slots.append(t)
     return slots
+
+
+def bf16_bits_from_f32(a):
+    """Round fp32 values to bfloat16 (nearest, ties to even); returns the 16-bit
+    patterns as uint16. A storage-format conversion only."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounded = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def f32_from_bf16_bits(b):
+    """Exact fp32 value of every bfloat16 bit pattern in b (uint16)."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)

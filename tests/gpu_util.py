@@ -79,3 +79,19 @@ def assert_close(got, ref, rtol, what=""):
 def normwise(got, ref):
     ref = np.asarray(ref, np.float64)
     return float(np.linalg.norm(np.asarray(got, np.float64) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def to_dev_bits(bits, ld=None, pad_bits=0x7FC0):
+    """uint16 bf16 patterns [rows, d] -> device uint16 tensor [rows, ld]; padding
+    columns hold a NaN pattern by default."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    if ld is None or ld == bits.shape[1]:
+        return torch.from_numpy(bits.view(np.int16)).to(DEV)
+    out = np.full((bits.shape[0], ld), pad_bits, dtype=np.uint16)
+    out[:, :bits.shape[1]] = bits
+    return torch.from_numpy(out.view(np.int16)).to(DEV)
+
+
+def bits_to_host(t, d=None):
+    a = t.detach().cpu().numpy().view(np.uint16)
+    return a if d is None else a[:, :d]

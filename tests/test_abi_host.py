@@ -108,7 +108,7 @@ def test_compute_calls_validate_before_launch(sat):
     # all of these must fail on the host; none may touch a device (none exists here)
     L = sat.lib()
     assert L.sat_history_gather(None, 10, 8, None, 4, 8, None, 8, 0, None) == -1
-    assert L.sat_history_gather(None, 10, 8, None, 4, 8, None, 8, 1, None) == -2     # bf16
+    assert L.sat_history_gather(None, 10, 8, None, 4, 8, None, 8, 7, None) == -1     # no such dtype
     assert L.sat_history_gather(None, 10, 8, None, 0, 8, None, 8, 0, None) == 0      # empty: no-op
     assert L.sat_history_push(None, 10, 4, None, 4, 8, None, 8, 0, None) == -1
     assert L.sat_dense_fwd(None, 8, 4, 8, 8, None, 8, 1, 0, None, 8, None) == -1
