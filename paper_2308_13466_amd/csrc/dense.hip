@@ -72,10 +72,75 @@ SplitPlan plan_dw(int64_t n, int32_t d_in, int32_t d_out) {
   return p;
 }
 
-sat_status check_mat(const void* p, int64_t rows, int64_t cols, int64_t ld) {
+sat_status check_mat(const void* p, int64_t rows, int64_t cols, int64_t ld, int es = 4) {
   if (rows > 0 && cols > 0) {
     if (!p || ld < cols) return SAT_EINVAL;
-    if (!sat::aligned16(p) || (ld % 4) != 0) return SAT_EALIGN;
+    if (!sat::aligned16(p) || ((ld * es) % 16) != 0) return SAT_EALIGN;
+  }
+  return SAT_OK;
+}
+
+// ES = bytes per element of AGG, W, H (4: fp32, 2: bf16)
+template <int ES>
+sat_status run_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in, int32_t d_out,
+                   const void* W, int64_t ld_w, int32_t act, void* H, int64_t ld_h, hipStream_t s) {
+  const int64_t gx = (n + BM - 1) / BM;
+  if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
+  const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_out + BN - 1) / BN), 1);
+  const Operand a{AGG, ld_a, nullptr, 0};
+  const Operand b{W, ld_w, nullptr, 0};
+  const int64_t K = d_in;
+  if (act == SAT_ACT_RELU)
+    gemm_kernel<ES, Layout::KContig, false, Layout::MNContig, false, kStoreRelu, ES>
+        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, H, ld_h, EpiArgs{});
+  else
+    gemm_kernel<ES, Layout::KContig, false, Layout::MNContig, false, kStore, ES>
+        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, H, ld_h, EpiArgs{});
+  return sat::check_launch();
+}
+
+template <int ES>
+sat_status run_bwd(const void* dH, int64_t ld_dh, const void* mask, int64_t ld_ho, const void* AGG,
+                   int64_t ld_a, const void* W, int64_t ld_w, int64_t n, int32_t d_in,
+                   int32_t d_out, float* dW, int64_t ld_dw, void* dAGG, int64_t ld_da,
+                   float* part, hipStream_t s) {
+  sat_status st;
+  const bool relu = mask != nullptr;
+  // dW = AGG^T dZ : M = d_in, N = d_out, K = n, split over blockIdx.z; fp32 out
+  {
+    const SplitPlan p = plan_dw(n, d_in, d_out);
+    const dim3 grid(static_cast<unsigned>((d_in + BM - 1) / BM),
+                    static_cast<unsigned>((d_out + BN - 1) / BN), static_cast<unsigned>(p.splits));
+    const Operand a{AGG, ld_a, nullptr, 0};
+    const Operand b{dH, ld_dh, mask, ld_ho};
+    const EpiArgs ep{p.split_stride, nullptr, 0, nullptr, 0, 0};
+    if (relu)
+      gemm_kernel<ES, Layout::MNContig, false, Layout::MNContig, true, kStorePartial, 4>
+          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part, ep);
+    else
+      gemm_kernel<ES, Layout::MNContig, false, Layout::MNContig, false, kStorePartial, 4>
+          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part, ep);
+    if ((st = sat::check_launch()) != SAT_OK) return st;
+    const int64_t total = static_cast<int64_t>(d_in) * d_out;
+    reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
+        part, p.split_stride, p.splits, d_in, d_out, p.ld_part, dW, ld_dw);
+    if ((st = sat::check_launch()) != SAT_OK) return st;
+  }
+  // dAGG = dZ W^T : M = n, N = d_in, K = d_out
+  if (dAGG) {
+    const int64_t gx = (n + BM - 1) / BM;
+    if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_in + BN - 1) / BN), 1);
+    const Operand a{dH, ld_dh, mask, ld_ho};
+    const Operand b{W, ld_w, nullptr, 0};
+    const int64_t K = d_out;
+    if (relu)
+      gemm_kernel<ES, Layout::KContig, true, Layout::KContig, false, kStore, ES>
+          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, dAGG, ld_da, EpiArgs{});
+    else
+      gemm_kernel<ES, Layout::KContig, false, Layout::KContig, false, kStore, ES>
+          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, dAGG, ld_da, EpiArgs{});
+    if ((st = sat::check_launch()) != SAT_OK) return st;
   }
   return SAT_OK;
 }
@@ -87,26 +152,16 @@ extern "C" sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, in
                                     int32_t dtype, void* H, int64_t ld_h, void* stream) {
   if (n < 0 || d_in < 0 || d_out < 0) return SAT_EINVAL;
   if (act != SAT_ACT_IDENTITY && act != SAT_ACT_RELU) return SAT_EINVAL;
-  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
+  const int es = dtype == SAT_BF16 ? 2 : 4;
   sat_status st;
-  if ((st = check_mat(AGG, n, d_in, ld_a)) != SAT_OK) return st;
-  if ((st = check_mat(W, d_in, d_out, ld_w)) != SAT_OK) return st;
-  if ((st = check_mat(H, n, d_out, ld_h)) != SAT_OK) return st;
+  if ((st = check_mat(AGG, n, d_in, ld_a, es)) != SAT_OK) return st;
+  if ((st = check_mat(W, d_in, d_out, ld_w, es)) != SAT_OK) return st;
+  if ((st = check_mat(H, n, d_out, ld_h, es)) != SAT_OK) return st;
   if (n == 0 || d_out == 0) return SAT_OK;
-  const int64_t gx = (n + BM - 1) / BM;
-  if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
-  const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_out + BN - 1) / BN), 1);
-  const Operand a{static_cast<const float*>(AGG), ld_a, nullptr, 0};
-  const Operand b{static_cast<const float*>(W), ld_w, nullptr, 0};
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const int64_t K = d_in;
-  if (act == SAT_ACT_RELU)
-    gemm_kernel<3, Layout::KContig, false, Layout::MNContig, false, kStoreRelu>
-        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, EpiArgs{});
-  else
-    gemm_kernel<3, Layout::KContig, false, Layout::MNContig, false, kStore>
-        <<<grid, dim3(256), 0, s>>>(a, b, n, d_out, K, K > 0 ? K : 1, static_cast<float*>(H), ld_h, EpiArgs{});
-  return sat::check_launch();
+  return es == 2 ? run_fwd<2>(AGG, ld_a, n, d_in, d_out, W, ld_w, act, H, ld_h, s)
+                 : run_fwd<4>(AGG, ld_a, n, d_in, d_out, W, ld_w, act, H, ld_h, s);
 }
 
 extern "C" int64_t sat_dense_bwd_workspace_bytes(int64_t n, int32_t d_in, int32_t d_out) {
@@ -123,67 +178,31 @@ extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* H
                                     int64_t workspace_bytes, void* stream) {
   if (n < 0 || d_in < 0 || d_out < 0) return SAT_EINVAL;
   if (act != SAT_ACT_IDENTITY && act != SAT_ACT_RELU) return SAT_EINVAL;
-  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
+  const int es = dtype == SAT_BF16 ? 2 : 4;
   sat_status st;
-  if ((st = check_mat(dH, n, d_out, ld_dh)) != SAT_OK) return st;
-  if (act == SAT_ACT_RELU && (st = check_mat(Hout, n, d_out, ld_ho)) != SAT_OK) return st;
-  if ((st = check_mat(AGG, n, d_in, ld_a)) != SAT_OK) return st;
-  if ((st = check_mat(W, d_in, d_out, ld_w)) != SAT_OK) return st;
-  if ((st = check_mat(dW, d_in, d_out, ld_dw)) != SAT_OK) return st;
-  if (dAGG && (st = check_mat(dAGG, n, d_in, ld_da)) != SAT_OK) return st;
+  if ((st = check_mat(dH, n, d_out, ld_dh, es)) != SAT_OK) return st;
+  if (act == SAT_ACT_RELU && (st = check_mat(Hout, n, d_out, ld_ho, es)) != SAT_OK) return st;
+  if ((st = check_mat(AGG, n, d_in, ld_a, es)) != SAT_OK) return st;
+  if ((st = check_mat(W, d_in, d_out, ld_w, es)) != SAT_OK) return st;
+  if ((st = check_mat(dW, d_in, d_out, ld_dw, 4)) != SAT_OK) return st;
+  if (dAGG && (st = check_mat(dAGG, n, d_in, ld_da, es)) != SAT_OK) return st;
   if (d_in == 0 || d_out == 0) return SAT_OK;
   const int64_t need = sat_dense_bwd_workspace_bytes(n, d_in, d_out);
   if (need > 0 && (!workspace || workspace_bytes < need)) return SAT_EWORKSPACE;
   if (need > 0 && !sat::aligned256(workspace)) return SAT_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const bool relu = act == SAT_ACT_RELU;
-  const float* mask = relu ? static_cast<const float*>(Hout) : nullptr;
-
-  // dW = AGG^T dZ : M = d_in, N = d_out, K = n, split over blockIdx.z
   if (n == 0) {
-    // empty reduction: dW = 0 (a tiny fill through the reduce kernel with 0 splits)
+    // empty reduction: dW = 0 (the reduce kernel with zero slices writes zeros)
     const int64_t total = static_cast<int64_t>(d_in) * d_out;
     reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
         dW, 0, 0, d_in, d_out, ld_dw, dW, ld_dw);
     return sat::check_launch();
   }
-  {
-    const SplitPlan p = plan_dw(n, d_in, d_out);
-    const dim3 grid(static_cast<unsigned>((d_in + BM - 1) / BM),
-                    static_cast<unsigned>((d_out + BN - 1) / BN), static_cast<unsigned>(p.splits));
-    const Operand a{static_cast<const float*>(AGG), ld_a, nullptr, 0};
-    const Operand b{static_cast<const float*>(dH), ld_dh, mask, ld_ho};
-    float* part = static_cast<float*>(workspace);
-    if (relu)
-      gemm_kernel<3, Layout::MNContig, false, Layout::MNContig, true, kStorePartial>
-          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
-                                      EpiArgs{p.split_stride, nullptr, 0, nullptr, 0, 0});
-    else
-      gemm_kernel<3, Layout::MNContig, false, Layout::MNContig, false, kStorePartial>
-          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part,
-                                      EpiArgs{p.split_stride, nullptr, 0, nullptr, 0, 0});
-    if ((st = sat::check_launch()) != SAT_OK) return st;
-    const int64_t total = static_cast<int64_t>(d_in) * d_out;
-    reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
-        part, p.split_stride, p.splits, d_in, d_out, p.ld_part, dW, ld_dw);
-    if ((st = sat::check_launch()) != SAT_OK) return st;
-  }
-
-  // dAGG = dZ W^T : M = n, N = d_in, K = d_out
-  if (dAGG) {
-    const int64_t gx = (n + BM - 1) / BM;
-    if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
-    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_in + BN - 1) / BN), 1);
-    const Operand a{static_cast<const float*>(dH), ld_dh, mask, ld_ho};
-    const Operand b{static_cast<const float*>(W), ld_w, nullptr, 0};
-    const int64_t K = d_out;
-    if (relu)
-      gemm_kernel<3, Layout::KContig, true, Layout::KContig, false, kStore>
-          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, EpiArgs{});
-    else
-      gemm_kernel<3, Layout::KContig, false, Layout::KContig, false, kStore>
-          <<<grid, dim3(256), 0, s>>>(a, b, n, d_in, K, K, static_cast<float*>(dAGG), ld_da, EpiArgs{});
-    if ((st = sat::check_launch()) != SAT_OK) return st;
-  }
-  return SAT_OK;
+  const void* mask = act == SAT_ACT_RELU ? Hout : nullptr;
+  float* part = static_cast<float*>(workspace);
+  return es == 2 ? run_bwd<2>(dH, ld_dh, mask, ld_ho, AGG, ld_a, W, ld_w, n, d_in, d_out, dW, ld_dw,
+                              dAGG, ld_da, part, s)
+                 : run_bwd<4>(dH, ld_dh, mask, ld_ho, AGG, ld_a, W, ld_w, n, d_in, d_out, dW, ld_dw,
+                              dAGG, ld_da, part, s);
 }

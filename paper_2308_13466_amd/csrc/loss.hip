@@ -25,10 +25,27 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-__global__ __launch_bounds__(256) void xent_grad_kernel(const float* __restrict__ HL,
+// element access for fp32 (ES = 4) or bf16 (ES = 2) rows; bf16 stores round to nearest-even
+template <int ES>
+__device__ __forceinline__ float ld_elem(const void* row, int c) {
+  if constexpr (ES == 4) return static_cast<const float*>(row)[c];
+  else return __builtin_bit_cast(float, static_cast<uint32_t>(static_cast<const uint16_t*>(row)[c]) << 16);
+}
+template <int ES>
+__device__ __forceinline__ void st_elem(void* row, int c, float x) {
+  if constexpr (ES == 4) {
+    static_cast<float*>(row)[c] = x;
+  } else {
+    static_cast<__bf16*>(row)[c] = static_cast<__bf16>(x);
+  }
+}
+
+template <int ES>
+__global__ __launch_bounds__(256) void xent_grad_kernel(const unsigned char* __restrict__ HL,
                                                         int64_t ld_hl, int64_t n, int32_t C,
                                                         const int32_t* __restrict__ y,
-                                                        float* __restrict__ dH, int64_t ld_dh,
+                                                        unsigned char* __restrict__ dH,
+                                                        int64_t ld_dh,
                                                         float* __restrict__ block_loss) {
   __shared__ float wave_loss[4];
   const int lane = threadIdx.x & (kWave - 1);
@@ -37,21 +54,21 @@ __global__ __launch_bounds__(256) void xent_grad_kernel(const float* __restrict_
   for (int rr = 0; rr < kRowsPerWave; ++rr) {
     const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave + rr;
     if (row >= n) break;
-    const float* h = HL + row * ld_hl;
+    const unsigned char* h = HL + row * ld_hl * ES;
     float mx = -INFINITY;
-    for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, h[c]);
+    for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, ld_elem<ES>(h, c));
     mx = wave_max(mx);
     float se = 0.f;
-    for (int c = lane; c < C; c += kWave) se += expf(h[c] - mx);
+    for (int c = lane; c < C; c += kWave) se += expf(ld_elem<ES>(h, c) - mx);
     se = wave_sum(se);
     const float inv_n = 1.0f / static_cast<float>(n);
     const int32_t label = y[row];
-    float* g = dH + row * ld_dh;
+    unsigned char* g = dH + row * ld_dh * ES;
     for (int c = lane; c < C; c += kWave) {
-      const float p = expf(h[c] - mx) / se;
-      g[c] = (p - (c == label ? 1.f : 0.f)) * inv_n;
+      const float p = expf(ld_elem<ES>(h, c) - mx) / se;
+      st_elem<ES>(g, c, (p - (c == label ? 1.f : 0.f)) * inv_n);
     }
-    if (label >= 0 && label < C) nll += logf(se) + mx - h[label];
+    if (label >= 0 && label < C) nll += logf(se) + mx - ld_elem<ES>(h, label);
   }
   if (block_loss) {
     if (lane == 0) wave_loss[wave] = nll;
@@ -89,16 +106,22 @@ extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, in
                                     float* loss, void* workspace, int64_t workspace_bytes,
                                     void* stream) {
   if (n < 0 || n_classes <= 0) return SAT_EINVAL;
-  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
   if (n == 0) return SAT_OK;
   if (!HL || !y || !dH || ld_hl < n_classes || ld_dh < n_classes) return SAT_EINVAL;
   const int64_t blocks = (n + kRowsPerBlock - 1) / kRowsPerBlock;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
   if (loss && (!workspace || workspace_bytes < sat_loss_workspace_bytes(n))) return SAT_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  xent_grad_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(
-      static_cast<const float*>(HL), ld_hl, n, n_classes, y, static_cast<float*>(dH), ld_dh,
-      loss ? static_cast<float*>(workspace) : nullptr);
+  const unsigned char* hl = static_cast<const unsigned char*>(HL);
+  unsigned char* dh = static_cast<unsigned char*>(dH);
+  float* bl = loss ? static_cast<float*>(workspace) : nullptr;
+  if (dtype == SAT_BF16)
+    xent_grad_kernel<2><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(
+        hl, ld_hl, n, n_classes, y, dh, ld_dh, bl);
+  else
+    xent_grad_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(
+        hl, ld_hl, n, n_classes, y, dh, ld_dh, bl);
   sat_status st = sat::check_launch();
   if (st != SAT_OK || !loss) return st;
   loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(static_cast<const float*>(workspace), blocks,

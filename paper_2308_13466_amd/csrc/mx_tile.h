@@ -1,5 +1,5 @@
 // Tile GEMM on the bf16 MFMA pipe of gfx950 (v_mfma_f32_32x32x16_bf16), used
-// for fp32 data through an exact three-way split.
+// for bf16 data directly and for fp32 data through an exact three-way split.
 //
 // Why: the fp32 MFMA pipe peaks at 157 TFLOP/s, the bf16 pipe at 2.5 PFLOP/s
 // (16x). An fp32 value x is split into three bf16 pieces x = x1 + x2 + x3
@@ -53,13 +53,14 @@ constexpr int tile_bytes() { return NP * MN * ROW_B; }
 
 enum class Layout { KContig, MNContig };
 
-// fp32 operand: element (mn, k) at p[mn * ld + k] (KContig) or p[k * ld + mn]
-// (MNContig); mask (optional) has the same indexing with its own ld, and an
-// element whose mask value is not > 0 reads as 0.
+// Operand of fp32 or bf16 elements (the kernel's template parameter says which):
+// element (mn, k) at p[mn * ld + k] (KContig) or p[k * ld + mn] (MNContig), ld in
+// elements; mask (optional, same element type) has the same indexing with its
+// own ld, and an element whose mask value is not > 0 reads as 0.
 struct Operand {
-  const float* p;
+  const void* p;
   int64_t ld;
-  const float* mask;
+  const void* mask;
   int64_t ld_mask;
 };
 
@@ -107,9 +108,9 @@ __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_
       const int64_t mn = mn0 + (t >> 3) + 32 * i;
       const int64_t k = k0 + ((t & 7) << 2);
       if (mn < mn_lim && k < k_lim) {
-        v = *reinterpret_cast<const f32x4*>(op.p + mn * op.ld + k);
+        v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(op.p) + mn * op.ld + k);
         if constexpr (MASK) {
-          const f32x4 h = *reinterpret_cast<const f32x4*>(op.mask + mn * op.ld_mask + k);
+          const f32x4 h = *reinterpret_cast<const f32x4*>(static_cast<const float*>(op.mask) + mn * op.ld_mask + k);
           v.x = h.x > 0.f ? v.x : 0.f;
           v.y = h.y > 0.f ? v.y : 0.f;
           v.z = h.z > 0.f ? v.z : 0.f;
@@ -136,8 +137,9 @@ __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_
       for (int j = 0; j < 8; ++j) {
         float x = 0.f;
         if (mn_ok && k8 + j < k_lim) {
-          x = op.p[(k8 + j) * op.ld + mn];
-          if constexpr (MASK) x = op.mask[(k8 + j) * op.ld_mask + mn] > 0.f ? x : 0.f;
+          x = static_cast<const float*>(op.p)[(k8 + j) * op.ld + mn];
+          if constexpr (MASK)
+            x = static_cast<const float*>(op.mask)[(k8 + j) * op.ld_mask + mn] > 0.f ? x : 0.f;
         }
         e[j] = x;
       }
@@ -177,6 +179,112 @@ __device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char*
         *reinterpret_cast<u32x4*>(s + p * piece_bytes<MN>()) = u32x4{q0[p], q1[p], q2[p], q3[p]};
     }
   }
+}
+
+// ---- bf16 operands (one piece, no split): the tile is MN x 32 bf16 = MN / 64
+// 16-byte chunks per thread.
+//  KContig : chunk c = t + 256 i is row c / 4, k = 8 (c % 4): a plain 16-byte copy
+//  MNContig: v[g] = 8 consecutive k of column mn = t % MN, k = 8 (t / MN + (256 / MN) g),
+//            gathered with 2-byte loads (coalesced across the wavefront)
+template <int MN>
+struct TileRegsB {
+  u32x4 v[MN / 64];
+};
+
+// bf16 value > 0: sign clear and not zero
+__device__ __forceinline__ bool bf16_pos(uint32_t h) { return (h & 0x8000u) == 0 && (h & 0x7fffu) != 0; }
+
+template <int MN, Layout L, bool MASK>
+__device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int64_t mn_lim,
+                                            int64_t k0, int64_t k_lim, TileRegsB<MN>& r, int t) {
+  const uint16_t* P = static_cast<const uint16_t*>(op.p);
+  const uint16_t* Mk = static_cast<const uint16_t*>(op.mask);
+  if constexpr (L == Layout::KContig) {
+#pragma unroll
+    for (int i = 0; i < MN / 64; ++i) {
+      const int c = t + 256 * i;
+      const int64_t mn = mn0 + (c >> 2);
+      const int64_t k = k0 + ((c & 3) << 3);
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (mn < mn_lim && k < k_lim) {
+        v = *reinterpret_cast<const u32x4*>(P + mn * op.ld + k);
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        if constexpr (MASK) {
+          const u32x4 hv = *reinterpret_cast<const u32x4*>(Mk + mn * op.ld_mask + k);
+          const uint32_t h[4] = {hv.x, hv.y, hv.z, hv.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            w[q] &= (bf16_pos(h[q] & 0xffffu) ? 0xffffu : 0u) | (bf16_pos(h[q] >> 16) ? 0xffff0000u : 0u);
+        }
+        const int valid = static_cast<int>(k_lim - k);   // elements of this chunk inside K
+        if (valid < 8) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (2 * q >= valid) w[q] = 0u;
+            else if (2 * q + 1 >= valid) w[q] &= 0xffffu;
+          }
+        }
+        v = u32x4{w[0], w[1], w[2], w[3]};
+      }
+      r.v[i] = v;
+    }
+  } else {
+    static_assert(MN >= 64 && MN <= 256, "MNContig tiles are 64..256 wide");
+    constexpr int KG = 256 / MN;
+    const int64_t mn = mn0 + (t % MN);
+    const bool mn_ok = mn < mn_lim;
+#pragma unroll
+    for (int g = 0; g < MN / 64; ++g) {
+      const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
+      uint32_t e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        uint32_t x = 0u;
+        if (mn_ok && k8 + j < k_lim) {
+          x = P[(k8 + j) * op.ld + mn];
+          if constexpr (MASK) x = bf16_pos(Mk[(k8 + j) * op.ld_mask + mn]) ? x : 0u;
+        }
+        e[j] = x;
+      }
+      r.v[g] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+    }
+  }
+}
+
+template <int MN, Layout L>
+__device__ __forceinline__ void store_tile_b(const TileRegsB<MN>& r, unsigned char* S, int t) {
+  if constexpr (L == Layout::KContig) {
+#pragma unroll
+    for (int i = 0; i < MN / 64; ++i) {
+      const int c = t + 256 * i;
+      *reinterpret_cast<u32x4*>(S + swz(c >> 2, c & 3)) = r.v[i];
+    }
+  } else {
+    constexpr int KG = 256 / MN;
+#pragma unroll
+    for (int g = 0; g < MN / 64; ++g)
+      *reinterpret_cast<u32x4*>(S + swz(t % MN, (t / MN) + KG * g)) = r.v[g];
+  }
+}
+
+// Element-size dispatch: ES = 4 -> fp32 operands split into three pieces,
+// ES = 2 -> bf16 operands used as they are.
+template <int ES> struct Pieces { static constexpr int N = ES == 4 ? 3 : 1; };
+template <int ES, int MN> struct RegsOf;
+template <int MN> struct RegsOf<4, MN> { typedef TileRegs<MN> type; };
+template <int MN> struct RegsOf<2, MN> { typedef TileRegsB<MN> type; };
+
+template <int ES, int MN, Layout L, bool MASK>
+__device__ __forceinline__ void load_any(const Operand& op, int64_t mn0, int64_t mn_lim, int64_t k0,
+                                         int64_t k_lim, typename RegsOf<ES, MN>::type& r, int t) {
+  if constexpr (ES == 4) load_tile<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t);
+  else load_tile_b<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t);
+}
+template <int ES, int MN, Layout L>
+__device__ __forceinline__ void store_any(const typename RegsOf<ES, MN>::type& r, unsigned char* S,
+                                          int t) {
+  if constexpr (ES == 4) store_tile<MN, L, 3>(r, S, t);
+  else store_tile_b<MN, L>(r, S, t);
 }
 
 // 16-byte MFMA operand of `lane`: row (row0 + lane % 32), k = 16 kc + 8 (lane / 32) .. + 7
@@ -236,7 +344,7 @@ enum Epilogue { kStore = 0, kStoreRelu = 1, kStorePartial = 2, kStoreAddRows = 3
 
 struct EpiArgs {
   int64_t split_stride;
-  const float* add;
+  const void* add;   // residual rows, same element type as C
   int64_t ld_add;
   const int32_t* add_ids;
   int64_t add_base;
@@ -249,12 +357,15 @@ constexpr int smem_bytes() {
   return (2 * tile_bytes<128, NP>() > 64 * C_LD * 4) ? 2 * tile_bytes<128, NP>() : 64 * C_LD * 4;
 }
 
-// C[M, N] = A * B (fp32 in, fp32 out, fp32-equivalent accuracy for NP = 3).
+// C[M, N] = A * B. ESI = bytes per input element: 4 -> fp32 operands, three-way
+// split, fp32-equivalent accuracy; 2 -> bf16 operands, one product. ESO = bytes per
+// output element (fp32, or bf16 rounded to nearest-even); sums are fp32 either way.
 // A: element (m, k); B: element (n, k) in the Operand sense above.
-template <int NP, Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI>
+template <int ESI, Layout LA, bool MASK_A, Layout LB, bool MASK_B, int EPI, int ESO = 4>
 __global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int64_t M, int64_t N,
-                                                      int64_t K, int64_t k_per_split, float* C,
+                                                      int64_t K, int64_t k_per_split, void* C,
                                                       int64_t ldc, EpiArgs ep) {
+  constexpr int NP = Pieces<ESI>::N;
   __shared__ __attribute__((aligned(16))) unsigned char smem[smem_bytes<NP>()];
   unsigned char* As = smem;
   unsigned char* Bs = smem + tile_bytes<BM, NP>();
@@ -275,30 +386,31 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int6
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  TileRegs<BM> ra;
-  TileRegs<BN> rb;
+  typename RegsOf<ESI, BM>::type ra;
+  typename RegsOf<ESI, BN>::type rb;
   if (k_begin < k_end) {
-    load_tile<BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
-    load_tile<BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
+    load_any<ESI, BM, LA, MASK_A>(A, m0, M, k_begin, k_end, ra, t);
+    load_any<ESI, BN, LB, MASK_B>(B, n0, N, k_begin, k_end, rb, t);
   }
   for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
     __syncthreads();
-    store_tile<BM, LA, NP>(ra, As, t);
-    store_tile<BN, LB, NP>(rb, Bs, t);
+    store_any<ESI, BM, LA>(ra, As, t);
+    store_any<ESI, BN, LB>(rb, Bs, t);
     __syncthreads();
     if (k0 + BK < k_end) {
-      load_tile<BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
-      load_tile<BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
+      load_any<ESI, BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
+      load_any<ESI, BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
     }
     mma_step<NP>(As, Bs, wm, wn, lane, acc);
   }
 
   // ---- epilogue: the tile goes through LDS (the operand staging is free now)
-  // so that global accesses are 16 bytes per lane and 512 bytes per row
-  // segment; two passes of 64 rows each.
+  // so that global accesses are 4 consecutive columns per lane and whole row
+  // segments per wavefront; two passes of 64 rows each.
   float* Cs = reinterpret_cast<float*>(smem);
-  float* Cb = C;
-  if constexpr (EPI == kStorePartial) Cb += static_cast<int64_t>(blockIdx.z) * ep.split_stride;
+  unsigned char* Cb = static_cast<unsigned char*>(C);
+  if constexpr (EPI == kStorePartial)
+    Cb += static_cast<int64_t>(blockIdx.z) * ep.split_stride * ESO;
   const int c = lane & 31;
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
@@ -338,8 +450,19 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int6
         v[q].w = v[q].w > 0.f ? v[q].w : 0.f;
       }
       if constexpr (EPI == kStoreAddRows) {
-        if (src[q] >= 0 && n < N)
-          v[q] += *reinterpret_cast<const f32x4*>(ep.add + src[q] * ep.ld_add + n);
+        if (src[q] >= 0 && n < N) {
+          if constexpr (ESO == 4) {
+            v[q] += *reinterpret_cast<const f32x4*>(static_cast<const float*>(ep.add) +
+                                                    src[q] * ep.ld_add + n);
+          } else {
+            const u32x2 w = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(ep.add) +
+                                                            src[q] * ep.ld_add + n);
+            v[q].x += low_as_f32(w.x);
+            v[q].y += high_as_f32(w.x);
+            v[q].z += low_as_f32(w.y);
+            v[q].w += high_as_f32(w.y);
+          }
+        }
       }
     }
 #pragma unroll
@@ -349,14 +472,26 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int6
       if constexpr (EPI == kStoreAddRows) {
         if (src[q] < 0) continue;
       }
-      float* y = Cb + m * ldc + n;
       const int64_t left = N - n;
-      if (left >= 4) {
-        *reinterpret_cast<f32x4*>(y) = v[q];
+      if constexpr (ESO == 4) {
+        float* y = reinterpret_cast<float*>(Cb) + m * ldc + n;
+        if (left >= 4) {
+          *reinterpret_cast<f32x4*>(y) = v[q];
+        } else {
+          y[0] = v[q].x;
+          if (left > 1) y[1] = v[q].y;
+          if (left > 2) y[2] = v[q].z;
+        }
       } else {
-        y[0] = v[q].x;
-        if (left > 1) y[1] = v[q].y;
-        if (left > 2) y[2] = v[q].z;
+        uint16_t* y = reinterpret_cast<uint16_t*>(Cb) + m * ldc + n;
+        const u32x2 w = {pack_bf16(v[q].x, v[q].y), pack_bf16(v[q].z, v[q].w)};
+        if (left >= 4) {
+          *reinterpret_cast<u32x2*>(y) = w;
+        } else {
+          y[0] = static_cast<uint16_t>(w.x & 0xffffu);
+          if (left > 1) y[1] = static_cast<uint16_t>(w.x >> 16);
+          if (left > 2) y[2] = static_cast<uint16_t>(w.y & 0xffffu);
+        }
       }
     }
   }

@@ -331,7 +331,7 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
     const sat::mx::Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
     const sat::mx::EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
                               n_rows_slot};
-    sat::mx::gemm_kernel<3, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
+    sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
                          sat::mx::kStoreAddRows>
         <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
   }

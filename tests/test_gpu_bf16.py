@@ -94,3 +94,60 @@ def test_bf16_spmm_parity(env, kind, d):
     if n_h:
         gu.assert_close(syn.f32_from_bf16_bits(gu.bits_to_host(dh, d))[:n_h], rh, RTOL_BF16,
                         "bf16 spmm_bwd halo")
+
+
+@pytest.mark.parametrize("n,d_in,d_out,act", [(2048, 64, 32, 1), (1000, 128, 256, 1),
+                                              (777, 256, 256, 1), (513, 256, 176, 0),
+                                              (300, 600, 256, 1), (129, 104, 48, 0), (5, 8, 8, 1)])
+def test_bf16_dense_fwd_bwd_parity(env, n, d_in, d_out, act):
+    sat, gu, torch = env
+    _say("bf16 dense n=%d %d->%d act=%d" % (n, d_in, d_out, act))
+    rng = np.random.default_rng(n + d_in)
+    a_bits, A = _bf16(rng.standard_normal((n, d_in)).astype(np.float32))
+    w_bits, W = _bf16(syn.glorot_uniform_f32(np.random.SeedSequence(n), d_in, d_out))
+    g_bits, dH = _bf16(rng.standard_normal((n, d_out)).astype(np.float32))
+    ld_a, ld_w, ld_h = gu.ld_for(d_in, 8), gu.ld_for(d_out, 8), gu.ld_for(d_out, 32)
+    A_d, W_d, dH_d = gu.to_dev_bits(a_bits, ld_a), gu.to_dev_bits(w_bits, ld_w), gu.to_dev_bits(g_bits, ld_h)
+    H_d = torch.full((n, ld_h), 77, dtype=torch.int16, device=gu.DEV)
+    sat.dense_fwd(A_d, ld_a, n, d_in, d_out, W_d, ld_w, act, H_d, ld_h, dtype=sat.BF16,
+                  stream=gu.stream_ptr())
+    gu.sync()
+    Z, H = orc.dense_fwd(A, W, act)
+    got = syn.f32_from_bf16_bits(gu.bits_to_host(H_d, d_out))
+    gu.assert_close(got, H, RTOL_BF16, "bf16 dense_fwd")
+    rms = np.sqrt(np.mean(H * H))
+    assert np.all(np.abs(got - H) <= 2.0 ** -8 * np.abs(H) + 1e-5 * rms)   # one rounding of an fp32 sum
+    assert np.all(gu.bits_to_host(H_d)[:, d_out:] == 77)
+    # backward: mask from the oracle's forward output rounded to bf16 (both sides see the same mask)
+    h_bits, H16 = _bf16(H.astype(np.float32))
+    Hm_d = gu.to_dev_bits(h_bits, ld_h)
+    dW_d = gu.dev_empty(d_in, ld_w, fill=-3.0)
+    dA_d = torch.full((n, ld_a), 77, dtype=torch.int16, device=gu.DEV)
+    wsb = sat.dense_bwd_workspace_bytes(n, d_in, d_out)
+    ws = gu.workspace(wsb)
+    sat.dense_bwd(dH_d, ld_h, Hm_d, ld_h, A_d, ld_a, W_d, ld_w, n, d_in, d_out, act, dW_d, ld_w,
+                  dA_d, ld_a, dtype=sat.BF16, workspace=ws, workspace_bytes=wsb, stream=gu.stream_ptr())
+    gu.sync()
+    dW, dA, _ = orc.dense_bwd(dH, H16, A, W, act)
+    gu.assert_close(gu.to_host(dW_d, d_out), dW, 1e-5, "bf16 dW (fp32 out, exact bf16 products)")
+    gu.assert_close(syn.f32_from_bf16_bits(gu.bits_to_host(dA_d, d_in)), dA, RTOL_BF16, "bf16 dAGG")
+
+
+@pytest.mark.parametrize("n,C", [(2048, 8), (1001, 40), (70, 172)])
+def test_bf16_loss_grad_parity(env, n, C):
+    sat, gu, torch = env
+    _say("bf16 loss n=%d C=%d" % (n, C))
+    rng = np.random.default_rng(C)
+    h_bits, HL = _bf16((3.0 * rng.standard_normal((n, C))).astype(np.float32))
+    y = rng.integers(0, C, size=n).astype(np.int32)
+    ld = gu.ld_for(C, 8)
+    g_d = torch.full((n, ld), 77, dtype=torch.int16, device=gu.DEV)
+    loss_d = torch.zeros(1, dtype=torch.float32, device=gu.DEV)
+    wsb = sat.loss_workspace_bytes(n)
+    ws = gu.workspace(wsb)
+    sat.loss_grad(gu.to_dev_bits(h_bits, ld), ld, n, C, gu.to_dev(y), g_d, ld, loss=loss_d,
+                  dtype=sat.BF16, workspace=ws, workspace_bytes=wsb, stream=gu.stream_ptr())
+    gu.sync()
+    loss, g = orc.loss_and_grad(HL, y)
+    gu.assert_close(syn.f32_from_bf16_bits(gu.bits_to_host(g_d, C)), g, RTOL_BF16, "bf16 dH^(L)")
+    assert abs(float(loss_d.item()) - loss) <= 2e-5 * abs(loss)
