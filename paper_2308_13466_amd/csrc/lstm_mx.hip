@@ -30,7 +30,7 @@ constexpr int kMaxTau = 8;
 constexpr int R = 128;  // nodes per workgroup
 
 struct SlotPtrs {
-  const float* p[kMaxTau];
+  const void* p[kMaxTau];
 };
 
 __device__ __forceinline__ float sigmoidf_(float x) {
@@ -57,7 +57,9 @@ __global__ __launch_bounds__(256) void split_weights_kernel(const float* __restr
     *reinterpret_cast<uint32_t*>(P + (static_cast<int64_t>(p) * rows + r) * k_pad + k) = pc[p];
 }
 
-template <int DS>
+// ESX = bytes per element of the cached embeddings x (4: fp32, split three ways;
+// 2: bf16, used as it is, so the input products need one x piece only).
+template <int DS, int ESX>
 __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
                                                       int64_t ld_slot,
                                                       const int32_t* __restrict__ ids,
@@ -86,10 +88,12 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
   const int64_t node0 = static_cast<int64_t>(blockIdx.x) * R;
 
   // table row of each node this thread loads x for (-1: nothing to load)
-  int64_t arow[R / 32];
+  // (fp32: rows t / 8 + 32 i, four of them; bf16: rows t / 4 + 64 i, two of them)
+  constexpr int XROWS = ESX == 4 ? R / 32 : R / 64;
+  int64_t arow[XROWS];
 #pragma unroll
-  for (int i = 0; i < R / 32; ++i) {
-    const int64_t node = node0 + (t >> 3) + 32 * i;
+  for (int i = 0; i < XROWS; ++i) {
+    const int64_t node = node0 + (ESX == 4 ? (t >> 3) + 32 * i : (t >> 2) + 64 * i);
     int64_t r = -1;
     if (node < n_nodes) {
       r = ids ? static_cast<int64_t>(ids[node]) : node;
@@ -128,28 +132,46 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
   };
 
   const int nk = k_pad / BK;
-  auto load_x = [&](int j, TileRegs<R>& ra) {   // x tile j of the stream (zeros past the end)
+  typedef typename RegsOf<ESX, R>::type XRegs;
+  auto load_x = [&](int j, XRegs& ra) {   // x tile j of the stream (zeros past the end)
     const int sj = j / nk;
-    const int k = (j - sj * nk) * BK + ((t & 7) << 2);
     const bool live = sj < tau;
-    const float* xs = slots.p[live ? sj : 0];
+    if constexpr (ESX == 4) {
+      const int k = (j - sj * nk) * BK + ((t & 7) << 2);
+      const float* xs = static_cast<const float*>(slots.p[live ? sj : 0]);
 #pragma unroll
-    for (int i = 0; i < R / 32; ++i) {
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
-      if (live && arow[i] >= 0 && k < d) {
-        v = *reinterpret_cast<const f32x4*>(xs + arow[i] * ld_slot + k);
-        if (k + 3 >= d) {
-          if (k + 1 >= d) v.y = 0.f;
-          if (k + 2 >= d) v.z = 0.f;
-          v.w = 0.f;
+      for (int i = 0; i < XROWS; ++i) {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (live && arow[i] >= 0 && k < d) {
+          v = *reinterpret_cast<const f32x4*>(xs + arow[i] * ld_slot + k);
+          if (k + 3 >= d) {
+            if (k + 1 >= d) v.y = 0.f;
+            if (k + 2 >= d) v.z = 0.f;
+            v.w = 0.f;
+          }
         }
+        ra.v[i] = v;
       }
-      ra.v[i] = v;
+    } else {
+      const int k = (j - sj * nk) * BK + ((t & 3) << 3);
+      const uint16_t* xs = static_cast<const uint16_t*>(slots.p[live ? sj : 0]);
+#pragma unroll
+      for (int i = 0; i < XROWS; ++i) {
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (live && arow[i] >= 0 && k < d) {   // d % 8 == 0 here: whole chunks only
+          v = *reinterpret_cast<const u32x4*>(xs + arow[i] * ld_slot + k);
+        }
+        ra.v[i] = v;
+      }
     }
   };
-  TileRegs<R> ra0;
+  auto store_x = [&](const XRegs& ra, unsigned char* dst) {
+    if constexpr (ESX == 4) store_tile<R, Layout::KContig, NP>(ra, dst, t);
+    else store_tile_b<R, Layout::KContig>(ra, dst, t);
+  };
+  XRegs ra0;
   load_x(0, ra0);
-  store_tile<R, Layout::KContig, NP>(ra0, As, t);   // tile 0 -> half 0 of the double buffer
+  store_x(ra0, As);   // tile 0 -> half 0 of the double buffer
   load_x(1, ra0);
 
   for (int s = 0; s < tau; ++s) {
@@ -161,15 +183,19 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[rb][g][r] = 0.f;
 
-    // one K step of products, B from the staged weight tile
+    // one K step of products, B from the staged weight tile (always three pieces).
     // A operand: the staged x tile `Ax` (swizzled 64-byte rows), or if Ax == nullptr
-    // the h pieces in Hs (padded rows), k chunk offset a_kc0
-    auto products = [&](const unsigned char* Ax, int a_kc0) {
+    // the h pieces in Hs (padded rows), k chunk offset a_kc0. NPA = number of A
+    // pieces: 3 for fp32 data (six products), 1 for bf16 x (three products:
+    // the value itself against each weight piece, smallest first).
+    auto products = [&](auto npa_tag, const unsigned char* Ax, int a_kc0) {
+      constexpr int NPA = decltype(npa_tag)::value;
+      constexpr int NQ = NPA == 3 ? 6 : 3;
 #pragma unroll
       for (int kc = 0; kc < BK / 16; ++kc) {
-        bf16x8 a[RB][NP], b[4][NP];
+        bf16x8 a[RB][NPA], b[4][NP];
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
+        for (int p = 0; p < NPA; ++p)
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb)
             a[rb][p] = Ax ? read_operand(Ax + p * piece_bytes<R>(), 32 * (wm * RB + rb), kc, lane)
@@ -177,19 +203,23 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
                                 Hs + p * H_PIECE_B + (32 * (wm * RB + rb) + c) * H_ROW_B +
                                 32 * (a_kc0 + kc) + 16 * (lane >> 5));
 #pragma unroll
+        for (int p = 0; p < NP; ++p)
+#pragma unroll
           for (int g = 0; g < 4; ++g)
             b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), g * DS + 32 * wn, kc, lane);
-        }
 #pragma unroll
-        for (int q = 0; q < n_products<NP>(); ++q)
+        for (int q = 0; q < NQ; ++q) {
+          const int pa = NPA == 3 ? product_a<3>(q) : 0;
+          const int pb = NPA == 3 ? product_b<3>(q) : 2 - q;
 #pragma unroll
           for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
               if (s == 0 && g == 1) continue;  // c_0 = 0: the forget gate is not needed yet
-              acc[rb][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  a[rb][product_a<NP>(q)], b[g][product_b<NP>(q)], acc[rb][g], 0, 0, 0);
+              acc[rb][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb][pa], b[g][pb], acc[rb][g],
+                                                                   0, 0, 0);
             }
+        }
       }
     };
 
@@ -205,11 +235,11 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
       const int j = s * nk + i;
       __syncthreads();
       store_w(rw);
-      store_tile<R, Layout::KContig, NP>(ra0, As + ((j + 1) & 1) * tile_bytes<R, NP>(), t);
+      store_x(ra0, As + ((j + 1) & 1) * tile_bytes<R, NP>());
       __syncthreads();
       load_x(j + 2, ra0);
       if (i + 1 < nk) load_w(WxP, k_pad, (i + 1) * BK, rw);
-      products(As + (j & 1) * tile_bytes<R, NP>(), 0);
+      products(std::integral_constant<int, ESX == 4 ? 3 : 1>{}, As + (j & 1) * tile_bytes<R, NP>(), 0);
     }
     // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
     if (s > 0) {
@@ -219,7 +249,7 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
         store_w(rw);
         __syncthreads();
         if (k0 + BK < DS) load_w(WhP, DS, k0 + BK, rw);
-        products(nullptr, k0 / 16);
+        products(std::integral_constant<int, 3>{}, nullptr, k0 / 16);
       }
     }
     // ---- cell update, register-local
@@ -277,9 +307,10 @@ int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
   return round_up(3 * 4 * d_s * k_pad * 2, 256) + round_up(3 * 4 * d_s * static_cast<int64_t>(d_s) * 2, 256);
 }
 
-// S [n_nodes, d_s] = last hidden state of the LSTM over the tau slots. ws points at
+// S [n_nodes, d_s] = last hidden state of the LSTM over the tau slots (elements of
+// es_x bytes: 4 fp32, 2 bf16; weights and S are fp32). ws points at
 // lstm_mx_workspace_bytes() bytes, 256-byte aligned. Only d_s = 32 and 64.
-sat_status launch_lstm_mx(const float* const* slot_ptrs, int tau, int64_t n_rows_slot,
+sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
                           void* ws, hipStream_t st) {
@@ -297,12 +328,15 @@ sat_status launch_lstm_mx(const float* const* slot_ptrs, int tau, int64_t n_rows
   for (int s = 0; s < kMaxTau; ++s) sp.p[s] = s < tau ? slot_ptrs[s] : nullptr;
   const int64_t blocks = (n_nodes + R - 1) / R;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
-  if (d_s == 32)
-    lstm_mx_kernel<32><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
-        sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S);
-  else
-    lstm_mx_kernel<64><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
-        sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S);
+  const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+#define SAT_LSTM_MX(DS, ESX)                                                                   \
+  lstm_mx_kernel<DS, ESX><<<grid, block, 0, st>>>(sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, \
+                                                  k_pad, WxP, WhP, b, S)
+  if (d_s == 32 && es_x == 4) SAT_LSTM_MX(32, 4);
+  else if (d_s == 32) SAT_LSTM_MX(32, 2);
+  else if (es_x == 4) SAT_LSTM_MX(64, 4);
+  else SAT_LSTM_MX(64, 2);
+#undef SAT_LSTM_MX
   return sat::check_launch();
 }
 

@@ -38,7 +38,7 @@ sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const i
                        int64_t self_off, int64_t total_entries, hipStream_t stream);
 // lstm_mx.hip: the LSTM on the bf16 MFMA pipe (d_s = 32, 64)
 int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s);
-sat_status launch_lstm_mx(const float* const* slot_ptrs, int tau, int64_t n_rows_slot,
+sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
                           void* ws, hipStream_t st);
@@ -261,7 +261,8 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   if (!pv || !w || !slots) return SAT_EINVAL;
   if (pv->n_local < 0 || pv->n_halo < 0 || pv->nnz_halo < 0 || n_rows_slot < 0) return SAT_EINVAL;
   if (w->d < 0 || w->tau < 1) return SAT_EINVAL;
-  if (dtype != SAT_F32) return dtype == SAT_BF16 ? SAT_EUNSUPPORTED : SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
+  const int es = dtype == SAT_BF16 ? 2 : 4;
   if (w->tau > kMaxTau) return SAT_EUNSUPPORTED;
   const int64_t n_bar = pv->n_local + pv->n_halo;
   if (n_bar > INT32_MAX) return SAT_EUNSUPPORTED;
@@ -270,21 +271,23 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   if (!Hbar || ld < d || ld_slot < d) return SAT_EINVAL;
   for (int s = 0; s < w->tau; ++s)
     if (!slots[s]) return SAT_EINVAL;
-  if (!sat::aligned16(Hbar) || (ld % 4) != 0 || (ld_slot % 4) != 0) return SAT_EALIGN;
+  if (!sat::aligned16(Hbar) || ((ld * es) % 16) != 0 || ((ld_slot * es) % 16) != 0)
+    return SAT_EALIGN;
   for (int s = 0; s < w->tau; ++s)
     if (!sat::aligned16(slots[s])) return SAT_EALIGN;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const float* newest = static_cast<const float*>(slots[w->tau - 1]);
-  float* halo_out = static_cast<float*>(Hbar) + pv->n_local * ld;
+  const void* newest = slots[w->tau - 1];
+  void* halo_out = static_cast<unsigned char*>(Hbar) + pv->n_local * ld * es;
 
   if (w->bypass) {
     return sat::row_gather(newest, ld_slot, halo_out, ld, ids ? ids + pv->n_local : nullptr,
-                           pv->n_local, pv->n_halo, n_rows_slot, d, 4, st);
+                           pv->n_local, pv->n_halo, n_rows_slot, d, es, st);
   }
 
   if (!w->Wx || !w->Wh || !w->b || !w->Wg) return SAT_EINVAL;
   if (w->d_s != 32 && w->d_s != 64 && w->d_s != 128) return SAT_EUNSUPPORTED;
   if ((d % 4) != 0) return SAT_EUNSUPPORTED;  // Wg rows are d floats, read 16 bytes at a time
+  if (es == 2 && ((d % 8) != 0 || w->d_s > 64)) return SAT_EUNSUPPORTED;  // bf16 rows: 16-byte chunks
   if (!sat::aligned16(w->Wx) || !sat::aligned16(w->Wh) || !sat::aligned16(w->Wg)) return SAT_EALIGN;
   if (!pv->h_colptr || !pv->h_self || (pv->nnz_halo > 0 && (!pv->h_row || !pv->h_val)))
     return SAT_EINVAL;
@@ -296,9 +299,7 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   float* WxT = Agg + round_up(pv->n_halo * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
   sat_status rc;
   if (w->d_s <= 64) {
-    const float* sptr[kMaxTau];
-    for (int s = 0; s < w->tau; ++s) sptr[s] = static_cast<const float*>(slots[s]);
-    rc = sat::launch_lstm_mx(sptr, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->d_s, w->Wx,
+    rc = sat::launch_lstm_mx(slots, es, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->d_s, w->Wx,
                              w->Wh, w->b, S, WxT, st);
   } else {
     float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
@@ -331,9 +332,14 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
     const sat::mx::Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
     const sat::mx::EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
                               n_rows_slot};
-    sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
-                         sat::mx::kStoreAddRows>
-        <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
+    if (es == 4)
+      sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
+                           sat::mx::kStoreAddRows, 4>
+          <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
+    else   // fp32 aggregate and weights, bf16 residual rows and output
+      sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
+                           sat::mx::kStoreAddRows, 2>
+          <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
   }
   return sat::check_launch();
 }

@@ -151,3 +151,53 @@ def test_bf16_loss_grad_parity(env, n, C):
     loss, g = orc.loss_and_grad(HL, y)
     gu.assert_close(syn.f32_from_bf16_bits(gu.bits_to_host(g_d, C)), g, RTOL_BF16, "bf16 dH^(L)")
     assert abs(float(loss_d.item()) - loss) <= 2e-5 * abs(loss)
+
+
+@pytest.mark.parametrize("kind,d,d_s,tau,use_ids", [("tiny", 32, 32, 2, False),
+                                                    ("powerlaw", 256, 64, 2, True),
+                                                    ("powerlaw", 104, 64, 3, False),
+                                                    ("hub", 40, 32, 1, True)])
+def test_bf16_predict_parity(env, kind, d, d_s, tau, use_ids):
+    sat, gu, torch = env
+    _say("bf16 predict %s d=%d d_s=%d tau=%d ids=%s" % (kind, d, d_s, tau, use_ids))
+    g = _graph(kind)
+    v = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    n_l, n_h = v["n_local"], v["n_halo"]
+    n_bar = n_l + n_h
+    rng = np.random.default_rng(d + d_s)
+    p = syn.predictor_params_f32(np.random.SeedSequence(d_s), d, d_s)
+    ld = gu.ld_for(d, 32)
+    if use_ids:
+        ids = np.concatenate([v["local_ids"], v["halo_ids"]]).astype(np.int32)
+        n_rows = g.N
+    else:
+        ids, n_rows = None, n_bar
+    base = np.maximum(rng.standard_normal((n_rows, d)), 0).astype(np.float32)
+    tabs = [_bf16((base + 0.05 * rng.standard_normal((n_rows, d))).astype(np.float32))
+            for _ in range(tau)]
+    win = [t[1][ids] if use_ids else t[1] for t in tabs]
+    ref = orc.predict(v, p, win)
+    pv = gu.upload_view(v)
+    pd = {k: gu.to_dev(p[k]) for k in p}
+    w = sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], d, d_s, tau)
+    slots_d = [gu.to_dev_bits(t[0], ld) for t in tabs]
+    Hbar = torch.full((n_bar, ld), 77, dtype=torch.int16, device=gu.DEV)
+    wsb = sat.predict_workspace_bytes(n_l, n_h, d, d_s, tau)
+    ws = gu.workspace(wsb)
+    ids_d = gu.to_dev(ids) if use_ids else None
+    sat.predict(pv, w, slots_d, n_rows, ld, ids_d, Hbar, ld, dtype=sat.BF16, workspace=ws,
+                workspace_bytes=wsb, stream=gu.stream_ptr())
+    gu.sync()
+    got = gu.bits_to_host(Hbar)
+    assert np.all(got[:n_l] == 77) and np.all(got[:, d:] == 77)
+    gu.assert_close(syn.f32_from_bf16_bits(got[n_l:, :d]), ref, RTOL_BF16, "bf16 predict")
+    # the only rounding is the final store: within one bf16 step of the oracle
+    out = syn.f32_from_bf16_bits(got[n_l:, :d])
+    rms = np.sqrt(np.mean(ref * ref))
+    assert np.all(np.abs(out - ref) <= 2.0 ** -8 * np.abs(ref) + 2e-5 * rms)
+    wb = sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], d, d_s, tau, bypass=True)
+    Hb2 = torch.full((n_bar, ld), 77, dtype=torch.int16, device=gu.DEV)
+    sat.predict(pv, wb, slots_d, n_rows, ld, ids_d, Hb2, ld, dtype=sat.BF16, stream=gu.stream_ptr())
+    gu.sync()
+    newest_bits = (tabs[-1][0][ids] if use_ids else tabs[-1][0])[n_l:]
+    assert np.array_equal(gu.bits_to_host(Hb2)[n_l:, :d], newest_bits)
