@@ -136,6 +136,18 @@ def partition_view(N, g_rowptr, g_col, part, m, g_deg=None):
 
 
 # --------------------------------------------------------------------------
+# bf16 storage mode: tensors kept in HBM as bfloat16 are rounded when they are
+# stored; all arithmetic stays fp64 here (fp32 on the GPU).
+# --------------------------------------------------------------------------
+def round_bf16(a):
+    """Nearest bfloat16 value (ties to even) of every element, returned as fp64."""
+    u = np.asarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
+    return r.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------
 # Pull / push (Alg. 1: "Pull H_out", "Push computed embeddings")
 # --------------------------------------------------------------------------
 def history_gather(table, ids):
@@ -324,8 +336,13 @@ def predict(view, omega, slots, bypass=False):
 # --------------------------------------------------------------------------
 # Whole step of one partition (Alg. 1 inner body; Eq. 7; appendix fwd / bwd)
 # --------------------------------------------------------------------------
-def partition_step(view, X_local, X_halo, halo_hat, Ws, y):
+def partition_step(view, X_local, X_halo, halo_hat, Ws, y, store=None):
     """Forward and backward of an L-layer GCN on one partition.
+
+    store (optional): applied to every tensor the step keeps in memory between
+    calls (AGG, H, the loss gradient, dAGG, dH_in) - the identity for fp32
+    storage, round_bf16 for the bf16 storage mode. dW is an fp32 output and
+    is never rounded.
 
     X_local / X_halo: input features of local / halo nodes (layer 0 uses the
     true features of halo nodes: they are static, nothing is stale).
@@ -335,27 +352,35 @@ def partition_step(view, X_local, X_halo, halo_hat, Ws, y):
     Returns dict with per-layer lists AGG, Z, H (H[0] = X_local), the loss,
     dW per layer, and dH_in per layer (None for layer 0).
     """
+    if store is None:
+        store = lambda t: t
     L = len(Ws)
     H = [np.asarray(X_local, np.float64)]
     AGG, Z = [], []
     for l in range(L):
         halo = X_halo if l == 0 else halo_hat[l]
         Hbar = np.concatenate([H[l], np.asarray(halo, np.float64)], axis=0)
-        a = spmm_fwd(view, Hbar)
+        a = store(spmm_fwd(view, Hbar))
         z, h = dense_fwd(a, Ws[l], 1 if l < L - 1 else 0)
         AGG.append(a)
         Z.append(z)
-        H.append(h)
+        H.append(store(h))
     loss, g = loss_and_grad(H[L], y)
+    g = store(g)
     dW = [None] * L
     dH_in = [None] * L
     dZ = [None] * L
     dAGGs = [None] * L
     for l in range(L - 1, -1, -1):
-        dW[l], dAGG, dZ[l] = dense_bwd(g, Z[l], AGG[l], Ws[l], 1 if l < L - 1 else 0)
+        # relu'(Z) = [H > 0]: the stored forward output is the mask (for bf16 storage a
+        # positive Z never rounds to zero, so this is the same decision)
+        dW[l], dAGG, dZ[l] = dense_bwd(g, H[l + 1] if l < L - 1 else Z[l], AGG[l], Ws[l],
+                                       1 if l < L - 1 else 0)
+        dAGG = store(dAGG)
         dAGGs[l] = dAGG
         if l >= 1:
             g, _ = spmm_bwd(view, dAGG)
+            g = store(g)
             dH_in[l] = g
     return dict(AGG=AGG, Z=Z, H=H, loss=loss, dW=dW, dH_in=dH_in, dZ=dZ, dAGG=dAGGs)
 

@@ -34,14 +34,17 @@ class PartitionStep:
           (hist[0] unused); ring position is tracked here.
     table_ids: device int32 [n_bar]; row of each local-then-halo node in X_table
           and in every history table.
-    Ws: device weights, Ws[l] is [d_l, ld_w_l] with ld_w_l = _ld(d_{l+1}, 4).
+    Ws: device weights, Ws[l] is [d_l, ld_w_l] (ld_w_l a multiple of 4 floats / 8 bf16).
+    dtype: binding.F32 or binding.BF16 - element type of features, activations,
+          history tables and Ws (dW, the loss and the predictor parameters are fp32).
     predictors: predictors[l] a binding.Predictor for l = 1..L-1 (None: bypass).
     y: device int32 [n_local] labels.
     """
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
-                 fused_pull=True, timers=None):
+                 fused_pull=True, timers=None, dtype=B.F32):
         dev = X_table.device
+        self.dtype = dtype
         self.dims = list(dims)
         self.L = len(dims) - 1
         self.tau = tau
@@ -62,15 +65,17 @@ class PartitionStep:
         self.timers = timers
 
         f32 = dict(dtype=torch.float32, device=dev)
+        act = dict(dtype=torch.bfloat16 if dtype == B.BF16 else torch.float32, device=dev)
         L, n_l, n_bar = self.L, self.n_local, self.n_bar
         self.ld = [_ld(d) for d in dims]
-        self.ld_w = [_ld(dims[l + 1], 4) for l in range(L)]
-        self.Hbar = [torch.zeros((n_bar, self.ld[l]), **f32) for l in range(L)]
-        self.logits = torch.zeros((n_l, self.ld[L]), **f32)
-        self.AGG = [torch.zeros((n_l, self.ld[l]), **f32) for l in range(L)]
-        self.dH = [torch.zeros((n_l, self.ld[l]), **f32) for l in range(L + 1)]
-        self.dAGG = [torch.zeros((n_l, self.ld[l]), **f32) if l >= 1 else None for l in range(L)]
-        self.dW = [torch.zeros((dims[l], self.ld_w[l]), **f32) for l in range(L)]
+        self.ld_w = [Ws[l].shape[1] for l in range(L)]
+        self.Hbar = [torch.zeros((n_bar, self.ld[l]), **act) for l in range(L)]
+        self.logits = torch.zeros((n_l, self.ld[L]), **act)
+        self.AGG = [torch.zeros((n_l, self.ld[l]), **act) for l in range(L)]
+        self.dH = [torch.zeros((n_l, self.ld[l]), **act) for l in range(L + 1)]
+        self.dAGG = [torch.zeros((n_l, self.ld[l]), **act) if l >= 1 else None for l in range(L)]
+        self.ld_dw = [_ld(dims[l + 1], 4) for l in range(L)]
+        self.dW = [torch.zeros((dims[l], self.ld_dw[l]), **f32) for l in range(L)]   # always fp32
         self.loss = torch.zeros(1, **f32)
         ws_bytes = [B.loss_workspace_bytes(n_l)]
         ws_bytes += [B.dense_bwd_workspace_bytes(n_l, dims[l], dims[l + 1]) for l in range(L)]
@@ -81,11 +86,11 @@ class PartitionStep:
         self.ws_bytes = max(ws_bytes + [256])
         self.ws = torch.empty((self.ws_bytes + 3) // 4, **f32)
         if not fused_pull:
-            self.window = [[torch.zeros((n_bar, self.ld[l]), **f32) for _ in range(tau)]
+            self.window = [[torch.zeros((n_bar, self.ld[l]), **act) for _ in range(tau)]
                            if l >= 1 else None for l in range(L)]
         # local rows of layer 0 are static: pulled once
         B.history_gather(X_table, X_table.shape[0], X_table.shape[1], self.local_table_ids,
-                         n_l, dims[0], self.Hbar[0], self.ld[0], stream=self._stream())
+                         n_l, dims[0], self.Hbar[0], self.ld[0], dtype=dtype, stream=self._stream())
 
     @staticmethod
     def _stream():
@@ -104,6 +109,7 @@ class PartitionStep:
     def forward_backward(self):
         L, dims, ld, n_l, n_h, n_bar = self.L, self.dims, self.ld, self.n_local, self.n_halo, self.n_bar
         st = self._stream()
+        dt = self.dtype
         order = self.slot_order()
         # 1. predicted halo embeddings of every hidden layer
         for l in range(1, L):
@@ -112,15 +118,15 @@ class PartitionStep:
             w = self.predictors[l]
             if self.fused_pull or w.bypass:
                 self._timed("predict_l%d" % l, lambda: B.predict(
-                    self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], ld[l],
+                    self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], ld[l], dtype=dt,
                     workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
             else:
                 for k, s in enumerate(slots):
                     self._timed("gather_l%d" % l, lambda: B.history_gather(
                         s, n_rows, ld_t, self.table_ids, n_bar, dims[l], self.window[l][k],
-                        ld[l], stream=st))
+                        ld[l], dtype=dt, stream=st))
                 self._timed("predict_l%d" % l, lambda: B.predict(
-                    self.pv, w, self.window[l], n_bar, ld[l], None, self.Hbar[l], ld[l],
+                    self.pv, w, self.window[l], n_bar, ld[l], None, self.Hbar[l], ld[l], dtype=dt,
                     workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
         # 2. forward
         w_slot = self.t % self.tau
@@ -129,22 +135,22 @@ class PartitionStep:
                 halo0 = self.Hbar[0][n_l:]
                 self._timed("gather_l0", lambda: B.history_gather(
                     self.X_table, self.X_table.shape[0], self.X_table.shape[1],
-                    self.halo_table_ids, n_h, dims[0], halo0, ld[0], stream=st))
+                    self.halo_table_ids, n_h, dims[0], halo0, ld[0], dtype=dt, stream=st))
             self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
-                self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], stream=st))
+                self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], dtype=dt, stream=st))
             last = l == L - 1
             out = self.logits if last else self.Hbar[l + 1]
             self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
                 self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
-                B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], stream=st))
+                B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], dtype=dt, stream=st))
             if not last:
                 tab = self.hist[l + 1][w_slot]
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
-                    self.Hbar[l + 1], ld[l + 1], stream=st))
+                    self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))
         # 3. loss gradient and backward
         self._timed("loss_grad", lambda: B.loss_grad(
-            self.logits, ld[L], n_l, dims[L], self.y, self.dH[L], ld[L], loss=self.loss,
+            self.logits, ld[L], n_l, dims[L], self.y, self.dH[L], ld[L], loss=self.loss, dtype=dt,
             workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
         for l in range(L - 1, -1, -1):
             last = l == L - 1
@@ -152,12 +158,12 @@ class PartitionStep:
             self._timed("dense_bwd_l%d" % l, lambda: B.dense_bwd(
                 self.dH[l + 1], ld[l + 1], hout, 0 if last else ld[l + 1], self.AGG[l], ld[l],
                 self.Ws[l], self.ld_w[l], n_l, dims[l], dims[l + 1],
-                B.ACT_IDENTITY if last else B.ACT_RELU, self.dW[l], self.ld_w[l],
-                self.dAGG[l], ld[l] if l >= 1 else 0,
+                B.ACT_IDENTITY if last else B.ACT_RELU, self.dW[l], self.ld_dw[l],
+                self.dAGG[l], ld[l] if l >= 1 else 0, dtype=dt,
                 workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
             if l >= 1:
                 self._timed("spmm_bwd_l%d" % l, lambda: B.spmm_bwd(
-                    self.pv, self.dAGG[l], ld[l], dims[l], self.dH[l], ld[l], stream=st))
+                    self.pv, self.dAGG[l], ld[l], dims[l], self.dH[l], ld[l], dtype=dt, stream=st))
         self.t += 1
 
     # ------------------------------------------------------------ accounting

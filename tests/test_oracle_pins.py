@@ -450,3 +450,29 @@ def test_predictor_identity_cases():
 def test_staleness_norm_is_frobenius():
     a = np.array([[3.0, 0.0], [0.0, 4.0]])
     assert orc.staleness(a, np.zeros((2, 2))) == 5.0
+
+
+def test_round_bf16_matches_library_conversion():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(30)
+    x = np.concatenate([rng.standard_normal(50000), 1e-3 * rng.standard_normal(1000),
+                        [0.0, 1.0, -1.0, 1.00390625, 1.01171875, 3.0e38]]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(orc.round_bf16(x), ref)
+    # halfway cases go to the even neighbour: 1 + 2^-8 -> 1, 1 + 3 * 2^-8 -> 1 + 2^-6
+    assert orc.round_bf16(np.float32(1.00390625)) == 1.0
+    assert orc.round_bf16(np.float32(1.01171875)) == 1.015625
+
+
+def test_partition_step_store_hook_only_rounds_storage():
+    g, v, X, Ws, halo_hat, y = _fd_problem()
+    Xl, Xh = X[v["local_ids"]], X[v["halo_ids"]]
+    a = orc.partition_step(v, Xl, Xh, halo_hat, Ws, y)
+    b = orc.partition_step(v, Xl, Xh, halo_hat, Ws, y, store=lambda t: t)
+    assert a["loss"] == b["loss"] and all(np.array_equal(p, q) for p, q in zip(a["dW"], b["dW"]))
+    c = orc.partition_step(v, Xl, Xh, halo_hat, Ws, y, store=orc.round_bf16)
+    assert abs(c["loss"] - a["loss"]) < 2e-2 * abs(a["loss"])
+    for l in range(len(Ws)):
+        assert np.array_equal(c["AGG"][l], orc.round_bf16(c["AGG"][l]))
+        rel = np.linalg.norm(c["dW"][l] - a["dW"][l]) / np.linalg.norm(a["dW"][l])
+        assert rel < 3e-2
