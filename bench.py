@@ -80,7 +80,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "dense", "large"])
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "dense", "large", "scale_small"])
+    ap.add_argument("--dtype", default=None, choices=["f32", "bf16"],
+                    help="storage type of features, activations, history and weights "
+                         "(default: the workload's own; sums are fp32 either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--unfused-pull", action="store_true",
                     help="assemble the predictor window with sat_history_gather first")
@@ -113,7 +116,8 @@ def main():
 
     timers = CallTimers(torch)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
-                        timers=timers, log=log)
+                        timers=timers, log=log, dtype=args.dtype)
+    bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
     dims, tau, d_s, L = wl.dims, wl.tau, wl.d_s, wl.L
     n_l, n_h = view["n_local"], view["n_halo"]
@@ -150,7 +154,12 @@ def main():
     log("ms/step %.3f  GTEPS %.2f  loss %.5f" % (ms_per_step, gteps, loss))
 
     # ---- per-kernel-class roofline figures (algorithmic bytes / flops per launch)
-    s = 4
+    s = 2 if bf16 else 4
+    # dense MFMA peak the contractions are priced against: fp32 data is split into
+    # three bf16 pieces (six products per element pair); bf16 data needs one product
+    # in the feature transforms and three in the predictor (fp32 parameters, bf16 x)
+    peak_dense = 2500.0 if bf16 else MFMA_SPLIT_PEAK_TFLOPS
+    peak_predict = 2500.0 / 3.0 if bf16 else MFMA_SPLIT_PEAK_TFLOPS
     nnz, nnz_loc, nnz_halo = view["nnz"], step.nnz_local, view["nnz_halo"]
 
     def spmm_bytes(entries, rows, d):       # per entry: col + val + one feature row;
@@ -191,13 +200,15 @@ def main():
         if c["bound"] == "hbm":
             ach, peak, unit = c["work"] / sec / 1e9, HBM_PEAK_GBS, "GB/s"
         else:
-            ach, peak, unit = c["work"] / sec / 1e12, round(MFMA_SPLIT_PEAK_TFLOPS, 1), "TFLOP/s"
+            ach, unit = c["work"] / sec / 1e12, "TFLOP/s"
+            peak = round(peak_predict if cls == "predict" else peak_dense, 1)
         roof_all[cls] = dict(bound=c["bound"], achieved=round(ach, 2), peak=peak, unit=unit,
                              frac=round(ach / peak, 4),
                              avg_launch_ms=round(c["ms"] / c["launches"], 4),
                              ms_per_step=round(c["ms"] / args.steps, 4),
                              launches_per_step=c["launches"] // args.steps,
-                             traffic=MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
+                             traffic=None if bf16 != (cfg.get("dtype") == "bf16") else
+                             MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
     # The dominant KERNEL: classes whose calls are one kernel each (aggregation, pull,
     # push, forward transform, loss) are kernels; "predict" and "dense_bwd" are calls
     # made of several kernels, none of which outweighs the aggregation kernel (see the
@@ -218,7 +229,7 @@ def main():
                   "SAT GCN step, fwd+bwd, predictor and history pull/push included)",
         "value": round(gteps, 3), "unit": "GTEPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "graph": cfg["kind"], "N": g.N,
                    "partition": "%d of %d" % (cfg["part"], cfg["n_parts"]),
                    "n_local": n_l, "n_halo": n_h, "nnz": nnz, "nnz_local_local": nnz_loc,

@@ -22,8 +22,17 @@
  *    counted in ELEMENTS (ld >= number of columns). Padding columns
  *    [d, ld) are never read for arithmetic and never written.
  *  - Node ids are int32_t; row offsets (rowptr, split, colptr) are int64_t.
- *  - Element types: SAT_F32 (float). SAT_BF16 is reserved; calls that are
- *    given it return SAT_EUNSUPPORTED. Accumulation is always fp32.
+ *  - Element types (`dtype`): SAT_F32 (float) or SAT_BF16 (bfloat16, the
+ *    upper 16 bits of a float). dtype is the STORAGE type of every `void*`
+ *    matrix of the call (features, activations, history tables, layer
+ *    weights W and the gradients with those shapes). Every sum is carried in
+ *    fp32 and rounded to nearest-even once, where the result is stored.
+ *    Pointers typed `float*` are fp32 in both modes: the partition view's
+ *    values, the predictor's parameters, dW and the loss.
+ *  - Alignment of matrices other than gather/push operands: base pointer
+ *    16-byte aligned and ld * sizeof(element) a multiple of 16 (ld % 4 == 0
+ *    for fp32, ld % 8 == 0 for bf16), else SAT_EALIGN. Gather and push accept
+ *    any ld (they fall back to element-wise copies).
  *  - Kernels bound-check every id they read from device memory: an id outside
  *    its table is skipped (gather/push: that row is not copied; aggregation:
  *    that entry contributes nothing). They never fault on bad ids, but the
@@ -102,7 +111,7 @@ typedef struct sat_predictor {
   const float* b;
   const float* Wg;
   int32_t d;    /* embedding width of the layer */
-  int32_t d_s;  /* LSTM hidden size; must be a multiple of 32, at most 128 */
+  int32_t d_s;  /* LSTM hidden size: 32, 64 or 128 (bf16 embeddings: 32 or 64) */
   int32_t tau;  /* window length, 1 <= tau <= 8 */
   int32_t bypass; /* nonzero: plain historical embeddings, no correction */
 } sat_predictor;
@@ -171,6 +180,8 @@ sat_status sat_history_push(void* table, int64_t n_rows, int64_t ld_table, const
  * slot is ids[k] if ids != NULL (device int32 [n_bar]; lets the call read the
  * history table in place), else k. n_rows_slot bounds the row index.
  * Local rows of Hbar are not touched. Hbar must not overlap any slot.
+ * dtype is the element type of the slots and of Hbar; the parameters in *w are
+ * fp32. d must be a multiple of 4 (fp32) or 8 (bf16), else SAT_EUNSUPPORTED.
  * Workspace: sat_predict_workspace_bytes(); 256-byte aligned device memory.
  */
 int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, int32_t d, int32_t d_s,

@@ -3,23 +3,25 @@
 // over the partition-plus-halo graph). Output: predicted halo embeddings,
 // written in place into the halo rows of Hbar.
 //
-// Two kernels.
-//  lstm_kernel: a workgroup owns 32*WM nodes and all 4*d_s gate columns. Per
-//   time step the gate pre-activations [x_s | h_{s-1}] [Wx | Wh]^T are one fp32
-//   MFMA GEMM whose accumulators never leave registers: a wavefront holds the
-//   i, f, g, o blocks of the same (node, hidden-unit) positions, so the cell
-//   update is register-local; c stays in registers across steps and h goes to
-//   LDS k-major, which is exactly the A-operand layout of the next step's
-//   recurrent product. Only S = h_tau [n_bar, d_s] is written to memory. The
-//   window rows can be read straight out of the history table through ids.
-//  hop: the aggregation kernel of spmm.hip walks the transposed halo block with
-//   the diagonal term (A_hat[u,u] S_u) folded in and leaves the [n_halo, d_s]
-//   aggregate in the workspace; the tile GEMM multiplies it by Wg and adds the
-//   newest cached embedding, fetched through the id list, in its epilogue.
-//   (Halo nodes have very few local neighbours each, so the gather is a
-//   latency problem: it needs many independent rows in flight, which the
-//   row-per-wavefront aggregation kernel provides and a fused tile kernel
-//   walking its rows one after another did not.)
+// Steps of a call (each its own kernel, all on the caller's stream):
+//  1. LSTM. d_s = 32, 64: lstm_mx.hip, gate pre-activations on the bf16 MFMA pipe
+//     (fp32 operands split exactly into three bf16 pieces, six products per
+//     element pair; bf16 history rows are used as they are, three products). A
+//     workgroup owns 128 nodes and all 4*d_s gate columns; c stays in registers
+//     across the tau steps and h goes through LDS in the A-operand layout of the
+//     next step's recurrent product. d_s = 128 (fp32 rows only): lstm_kernel
+//     below, the same scheme on the fp32 MFMA instruction. Only S = h_tau
+//     [n_bar, d_s] (fp32) is written to memory; the window rows are read straight
+//     out of the history tables through ids.
+//  2. hop aggregation: the kernel of spmm.hip walks the transposed halo block
+//     with the diagonal term (A_hat[u,u] S_u) folded in and leaves the
+//     [n_halo, d_s] aggregate in the workspace. Halo nodes have very few local
+//     neighbours each, so this gather is a latency problem: it needs many
+//     independent rows in flight, which that kernel's group-per-row form gives.
+//  3. hop product: the tile GEMM of mx_tile.h multiplies the aggregate by Wg and,
+//     in its epilogue, adds the newest cached embedding (fetched through the id
+//     list) and stores the halo rows of Hbar in the call's element type.
+// With bypass set the call is one row gather of the newest slot.
 #include <math.h>
 
 #include "gemm_tile.h"

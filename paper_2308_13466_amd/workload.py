@@ -23,9 +23,23 @@ class Workload:
     pass
 
 
+def _upload(a, bf16, dev):
+    """Host fp32 matrix -> device tensor; in bf16 mode the values are rounded to
+    bfloat16 on the host (a storage conversion) and the 16-bit patterns uploaded.
+    Returns (device tensor, host fp32 array holding exactly the uploaded values)."""
+    if not bf16:
+        return torch.from_numpy(a).to(dev), a
+    bits = syn.bf16_bits_from_f32(a)
+    t = torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    return t, syn.f32_from_bf16_bits(bits)
+
+
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
-                   keep_host=True, device="cuda:0"):
+                   keep_host=True, device="cuda:0", dtype=None):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
+
+    dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
+    host copies kept for the tests hold the rounded values the device holds.
 
     History tables hold the seeded stand-in described in sat_synth.tensors
     (true unpartitioned embeddings are only affordable for the small
@@ -36,6 +50,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     if name == "tiny":
         cfg["d_s"] = 32
     dims, tau, d_s = cfg["dims"], cfg["tau"], cfg["d_s"]
+    dtype = dtype or cfg.get("dtype", "f32")
+    bf16 = dtype == "bf16"
     L = len(dims) - 1
     ss = syn.substreams(cfg["seed"])
     t0 = time.time()
@@ -56,20 +72,25 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     t0 = time.time()
     ld = [ld_of(d) for d in dims]
     X_host = syn.normal_f32(ss["features"], g.N, dims[0], ld=ld[0])
-    X_d = torch.from_numpy(X_host).to(dev)
+    X_d, X_host = _upload(X_host, bf16, dev)
     hss = ss["history"].spawn(L)
     hist_d, hist_host = [None], [None]
     for l in range(1, L):
         slots = syn.history_standin_f32(hss[l], g.N, dims[l], tau, cfg["noise_std"], ld=ld[l])
-        hist_d.append([torch.from_numpy(s).to(dev) for s in slots])
-        hist_host.append(slots if keep_host else None)
+        up = [_upload(s, bf16, dev) for s in slots]
+        del slots
+        hist_d.append([u[0] for u in up])
+        hist_host.append([u[1] for u in up] if keep_host else None)
+        del up
     table_ids = np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32)
     ids_d = torch.from_numpy(table_ids).to(dev)
     Ws_d = []
     for l in range(L):
-        w = np.zeros((dims[l], ld_of(dims[l + 1], 4)), np.float32)
+        w = np.zeros((dims[l], ld_of(dims[l + 1], 8 if bf16 else 4)), np.float32)
         w[:, :dims[l + 1]] = Ws[l]
-        Ws_d.append(torch.from_numpy(w).to(dev))
+        w_d, w_host = _upload(w, bf16, dev)
+        Ws_d.append(w_d)
+        Ws[l] = w_host[:, :dims[l + 1]]
     preds, keep = [None], []
     for l in range(1, L):
         pd = {k: torch.from_numpy(omegas[l][k]).to(dev) for k in omegas[l]}
@@ -79,14 +100,14 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     y = syn.labels_i32(ss["labels"], n_l, dims[-1])
     y_d = torch.from_numpy(y).to(dev)
     step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
-                         fused_pull=fused_pull, timers=timers)
+                         fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))
 
     w = Workload()
     w.name, w.cfg, w.graph, w.view, w.step = name, cfg, g, view, step
-    w.dims, w.tau, w.d_s, w.L, w.ld = dims, tau, d_s, L, ld
+    w.dims, w.tau, w.d_s, w.L, w.ld, w.dtype = dims, tau, d_s, L, ld, dtype
     w.X_host, w.hist_host, w.table_ids, w.Ws, w.omegas, w.y = X_host, hist_host, table_ids, Ws, omegas, y
     w.device_keep = (keep, X_d, hist_d, ids_d, Ws_d, y_d)
     return w

@@ -30,6 +30,13 @@ CONFIGS = {
         gamma=2.3, cut=0.20, dims=[100, 256, 256, 47], noise_std=0.05,
         tau=2, d_s=64, seed=0,
     ),
+    # ogbn-papers100M-shaped (128 features / 172 classes, mean degree 29, bf16
+    # storage) at 1/32 of its node count: one partition of 8 holds 434 k nodes
+    "scale_small": dict(
+        kind="chung_lu", N=3_470_000, n_parts=8, part=0, mean_deg=29.0,
+        gamma=2.2, cut=0.20, dims=[128, 256, 256, 172], noise_std=0.05,
+        tau=2, d_s=64, seed=0, dtype="bf16",
+    ),
 }
 
 

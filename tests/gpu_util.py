@@ -53,8 +53,11 @@ def sync():
     torch.cuda.synchronize()
 
 
-def assert_close(got, ref, rtol, what=""):
+def assert_close(got, ref, rtol, what="", max_bad_rows=0):
     """|got - ref| <= rtol * (|ref| + rms(ref)) element-wise.
+
+    max_bad_rows > 0 lets that many rows hold elements outside the bound (used
+    only where a valid 0/1 decision upstream may differ between the two sides).
 
     A pure element-wise relative bound cannot hold for sums that nearly cancel;
     the rms of the reference matrix is the magnitude the rounding error of one
@@ -70,6 +73,11 @@ def assert_close(got, ref, rtol, what=""):
     err = np.abs(got - ref)
     bound = rtol * (np.abs(ref) + rms)
     bad = err > bound
+    if max_bad_rows and bad.any() and bad.ndim == 2:
+        n_rows_bad = int(bad.any(axis=1).sum())
+        if n_rows_bad <= max_bad_rows:
+            return
+        what = "%s [%d rows outside, %d allowed]" % (what, n_rows_bad, max_bad_rows)
     if bad.any():
         i = np.unravel_index(np.argmax(err - bound), err.shape)
         raise AssertionError("%s: %d of %d elements outside rtol=%g; worst at %s: got %r ref %r (rms %g)"

@@ -1,0 +1,101 @@
+"""GPU parity of the whole partition step in bf16 storage mode: features,
+activations, history tables and layer weights are bfloat16 in memory, every sum
+runs in fp32 (fp64 in the oracle) and is rounded once where it is stored. The
+oracle chain applies the same storage rounding (its `store` hook), so the two
+sides differ by accumulation order and by the rare stored element whose sum
+lies within fp32 rounding of a bfloat16 tie. Tolerance: 2e-2 relative."""
+import numpy as np
+import pytest
+
+import sat_synth as syn
+from oracle import sat_oracle as orc
+from tests.test_gpu_step import build_problem, fresh_history, oracle_step, check_backward
+
+pytestmark = pytest.mark.gpu
+RTOL = 2e-2
+
+
+def _r(a):
+    """fp32 array rounded to bfloat16 values (kept as fp32)."""
+    return syn.f32_from_bf16_bits(syn.bf16_bits_from_f32(a))
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium"])
+def test_partition_step_bf16_two_steps(name):
+    import torch
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd import binding as B
+    from paper_2308_13466_amd.step import PartitionStep
+    from tests import gpu_util as gu
+    print("[case] bf16 step %s" % name, flush=True)
+    cfg, ss, g, X, Ws, omegas = build_problem(name)
+    if name == "tiny":
+        cfg["d_s"] = 32
+        pss = ss["predictor"].spawn(len(Ws))
+        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32)
+                           for l in range(1, len(Ws))]
+    dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
+    m = cfg["part"]
+    _, hist = fresh_history(cfg, ss, g, X, Ws)
+    # what the device holds: bfloat16 values
+    X = _r(X)
+    Ws = [_r(w) for w in Ws]
+    hist = [None] + [[_r(t) for t in hist[l]] for l in range(1, L)]
+    view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, m)
+    oview = orc.partition_view(g.N, g.rowptr, g.col, g.part, m)
+    y = syn.labels_i32(ss["labels"], view["n_local"], dims[-1])
+    n_l = view["n_local"]
+    print("[case] n_local=%d n_halo=%d nnz=%d" % (n_l, view["n_halo"], view["nnz"]), flush=True)
+
+    def up(a, ld):
+        return gu.to_dev_bits(syn.bf16_bits_from_f32(a), ld).view(torch.bfloat16)
+
+    def down(t, d):
+        return syn.f32_from_bf16_bits(gu.bits_to_host(t.view(torch.int16), d))
+
+    ld = [gu.ld_for(d) for d in dims]
+    X_d = up(X, ld[0])
+    hist_d = [None] + [[up(t, ld[l]) for t in hist[l]] for l in range(1, L)]
+    ids_d = gu.to_dev(np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32))
+    Ws_d = [up(Ws[l], gu.ld_for(dims[l + 1], 8)) for l in range(L)]
+    preds, keep = [None], []
+    for l in range(1, L):
+        pd = {k: gu.to_dev(omegas[l][k]) for k in omegas[l]}
+        keep.append(pd)
+        preds.append(sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], cfg["d_s"], tau))
+    step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, gu.to_dev(y), tau,
+                         dtype=B.BF16)
+    ohist = [None] + [[t.copy() for t in hist[l]] for l in range(1, L)]
+    for t in range(2):
+        order = [(t + s) % tau for s in range(tau)]
+        step.forward_backward()
+        gu.sync()
+        st = oracle_step(oview, X, ohist, order, t % tau, Ws, omegas, y, store=orc.round_bf16)
+        st["y"] = y
+        for l in range(1, L):
+            gu.assert_close(down(step.Hbar[l], dims[l])[n_l:], st["halo_hat"][l], RTOL,
+                            "predicted halo rows, layer %d step %d" % (l, t))
+        for l in range(L):
+            gu.assert_close(down(step.AGG[l], dims[l]), st["AGG"][l], RTOL, "AGG %d" % l)
+            out = step.logits if l == L - 1 else step.Hbar[l + 1]
+            gu.assert_close(down(out, dims[l + 1])[:n_l], st["H"][l + 1], RTOL, "H %d" % (l + 1))
+        assert abs(float(step.loss.item()) - st["loss"]) <= 5e-3 * abs(st["loss"])
+        # push: the table rows hold exactly the bits the forward stored
+        for l in range(1, L):
+            tab = gu.bits_to_host(step.hist[l][t % tau].view(torch.int16))
+            assert np.array_equal(tab[view["local_ids"], :dims[l]],
+                                  gu.bits_to_host(step.Hbar[l].view(torch.int16), dims[l])[:n_l])
+            others = np.setdiff1d(np.arange(g.N), view["local_ids"])
+            assert np.array_equal(tab[others, :dims[l]],
+                                  syn.bf16_bits_from_f32(ohist[l][t % tau][others]))
+        dW_gpu = [gu.to_host(step.dW[l], dims[l + 1]) for l in range(L)]
+        dAGG_gpu = [None] + [down(step.dAGG[l], dims[l]) for l in range(1, L)]
+        dH_gpu = [None] + [down(step.dH[l], dims[l]) for l in range(1, L)]
+        # a stored bfloat16 element can differ by one ulp between the two sides (a sum
+        # within fp32 rounding of a tie); such an element shifts a later Z by ~1e-4 of
+        # its scale, so a few relu decisions outside the excluded band may still
+        # differ: allow 0.5 % of the rows to carry one
+        n_amb, n_bad = check_backward(gu, oview, st, dW_gpu, dAGG_gpu, dH_gpu, dims, rtol=RTOL,
+                                      amb_rel=2e-5, max_bad_rows=max(2, n_l // 200))
+        print("[case] bf16 step %d ok: loss %.6f, %d relu decisions in the excluded band, "
+              "%d rows excluded" % (t, st["loss"], n_amb, n_bad), flush=True)
