@@ -34,7 +34,7 @@ sat_status row_gather(const void* src, int64_t ld_src, void* dst, int64_t ld_dst
                       const int32_t* ids, int64_t id_base, int64_t n, int64_t n_src_rows,
                       int32_t d, int es, hipStream_t stream);
 // spmm.hip: Y = M X (+ diag(self_val) X[self_off + i])
-sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const int32_t* col,
+sat_status launch_spmm(const int64_t* rowptr, const int64_t* row_end, const int32_t* col,
                        const float* val, const void* X, int64_t ld_x, int64_t n_x_rows, void* Y,
                        int64_t ld_y, int64_t n_rows, int32_t d, int es, const float* self_val,
                        int64_t self_off, int64_t total_entries, hipStream_t stream);
@@ -321,7 +321,7 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   if (rc != SAT_OK) return rc;
 
   // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
-  rc = sat::launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val, S, w->d_s,
+  rc = sat::launch_spmm(pv->h_colptr, nullptr, pv->h_row, pv->h_val, S, w->d_s,
                         pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, 4, pv->h_self, pv->n_local,
                         pv->nnz_halo, st);
   if (rc != SAT_OK) return rc;

@@ -2,28 +2,37 @@
 // forward) and its transpose products (appendix, SAT backward).
 //
 // The work is a gather of nnz feature rows: 2 flops per 4 gathered bytes, so
-// the memory system is the only bound and the design goal is bytes in flight.
-// Mapping for 64-wide wavefronts:
-//   * a workgroup of 8 wavefronts owns 8 consecutive CSR rows, one row per
-//     wavefront (row-split);
-//   * the row's column ids and values are read 64 at a time with one coalesced
-//     access and handed out with cross-lane reads;
-//   * a group of G lanes covers a feature row with 16-byte loads (G = 64 for
-//     256 floats: one 1 KiB row per wavefront access); for narrower rows the
-//     64/G groups take different neighbours at once and are summed with
-//     lane-xor shuffles at the end (bf16 rows: a 16-byte load is 8 elements, so
-//     256 bf16 take 32 lanes and two neighbours go at once);
-//   * U neighbours per group are fetched back to back before any of them is
-//     used, so a wavefront keeps U * NCH KiB of gathers in flight;
-//   * up to NCH 16-byte accumulators per lane: rows up to 1024 floats wide are
-//     aggregated in a single walk of the index list;
-//   * degree skew: a row longer than kLongRow entries is not walked by its
-//     owner alone; after the short rows are done, all 8 wavefronts of the
-//     workgroup split it into 8 contiguous pieces and their partial sums are
-//     added through LDS in a fixed order (deterministic, no atomics).
-// The same kernel serves P_in^T (the local-column prefix of each row, P_in
-// being symmetric), P_out^T (through the transposed halo block) and the
-// predictor's hop (transposed halo block plus a diagonal term).
+// the memory system is the only bound and the design goal is bytes in flight,
+// whatever the degree distribution looks like.
+//
+// spmm_stream_kernel (entry-balanced row split):
+//   * a workgroup of 8 wavefronts owns R consecutive CSR rows; their entries
+//     are one contiguous span of the index arrays, which is cut into 8 equal
+//     pieces, one per wavefront, regardless of where rows begin and end. A hub
+//     row is thereby spread over the wavefronts of its workgroup, and a
+//     wavefront never idles because its row happened to be short;
+//   * all 64 lanes cover one feature row (4, 8 or 16 bytes per lane and up to
+//     4 such chunks, so 256 B .. 4 KiB rows are one entry per access);
+//   * the entry list is consumed as a stream through a ring of U gathers in
+//     flight: as soon as the oldest gather has been added to the running row
+//     sum its registers are refilled with the entry U positions ahead, across
+//     row boundaries. Column ids and values are read 64 at a time, one chunk
+//     ahead, and handed out with cross-lane reads into scalar registers;
+//   * a row ends when the stream position passes its end offset (a scalar
+//     compare per entry): the running sum is stored and cleared. Rows without
+//     entries are stored as zeros on the way;
+//   * a row cut by a piece boundary leaves partial sums in LDS; after a
+//     barrier they are added in wavefront order (deterministic, no atomics);
+//   * entries whose column id is outside the operand (the halo columns, when
+//     the transpose product P_in^T walks only local columns) are squeezed out
+//     of each 64-entry chunk before the ring sees them.
+// spmm_group_kernel: rows of a handful of entries and narrow features (the
+//   transposed halo block of the predictor's hop): a group of G lanes per row,
+//   64/G rows per wavefront, because there the number of independent rows in
+//   flight is what sets the speed.
+// The same code serves P_in^T (P_in being symmetric), P_out^T (through the
+// transposed halo block) and the predictor's hop (transposed halo block plus a
+// diagonal term).
 #include "sat_internal.h"
 
 namespace {
@@ -32,96 +41,103 @@ using sat::kWave;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kRowsPerBlock = 8;   // wavefronts per workgroup
-constexpr int kLongRow = 512;      // entries; longer rows are walked cooperatively
+constexpr int kWaves = 8;            // wavefronts per workgroup
+constexpr int kMaxRowsPerBlock = 128;
+constexpr int32_t kEnd = 0x7fffffff;
+constexpr int kFold = 32;            // entries summed into one first-level partial sum
 
-// A 16-byte chunk of a feature row held as fp32: 4 fp32 elements, or 8 bf16
-// elements kept de-interleaved (q[0] = elements 0,2,4,6, q[1] = elements 1,3,5,7:
-// widening a packed pair is then one shift and one mask on the whole vector).
-// ES = bytes per element. Sums are always carried in fp32; bf16 results are
-// rounded to nearest-even once, when the output row is stored.
-template <int ES>
-struct Chunk {
-  static constexpr int N = 16 / ES;   // elements
-  static constexpr int NV = N / 4;    // fp32 vectors
-  f32x4 q[NV];
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // two RNE bf16, lo in the low half
+  const f32x2 pr = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+}
+
+// NW consecutive 32-bit words of a feature row, held as fp32. ES = bytes per
+// element: 4 (fp32: NW elements) or 2 (bf16: 2*NW elements, kept de-interleaved:
+// lo = even elements, hi = odd elements, so widening is one shift and one mask
+// on the whole vector). Sums are carried in fp32; bf16 results are rounded to
+// nearest-even once, when the output row is stored.
+template <int ES, int NW>
+struct Piece {
+  typedef float F __attribute__((ext_vector_type(NW)));
+  typedef uint32_t W __attribute__((ext_vector_type(NW)));
+  static constexpr int N = NW * 4 / ES;   // elements
+  static constexpr int NQ = 4 / ES == 2 ? 2 : 1;
+  F q[NQ];
   __device__ __forceinline__ void zero() {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) q[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < NQ; ++k) q[k] = F(0.f);
   }
-  __device__ __forceinline__ void load(const unsigned char* p) {
+  static __device__ __forceinline__ W load_raw(const unsigned char* p) {
+    return *reinterpret_cast<const W*>(p);
+  }
+  __device__ __forceinline__ void load(const unsigned char* p) { widen(load_raw(p)); }
+  __device__ __forceinline__ void widen(const W w) {
     if constexpr (ES == 4) {
-      q[0] = *reinterpret_cast<const f32x4*>(p);
+      q[0] = __builtin_bit_cast(F, w);
     } else {
-      const u32x4 w = *reinterpret_cast<const u32x4*>(p);
-      q[0] = __builtin_bit_cast(f32x4, w << 16);
-      q[1] = __builtin_bit_cast(f32x4, w & 0xffff0000u);
+      q[0] = __builtin_bit_cast(F, w << 16);
+      q[1] = __builtin_bit_cast(F, w & 0xffff0000u);
     }
   }
-  __device__ __forceinline__ void fma(float s, const Chunk& x) {
+  __device__ __forceinline__ void fma(float s, const Piece& x) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) q[k] += s * x.q[k];
+    for (int k = 0; k < NQ; ++k) q[k] += s * x.q[k];
   }
-  __device__ __forceinline__ void add(const Chunk& x) {
+  __device__ __forceinline__ void add(const Piece& x) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) q[k] += x.q[k];
+    for (int k = 0; k < NQ; ++k) q[k] += x.q[k];
   }
   __device__ __forceinline__ void xor_add(int off) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) {
-      q[k].x += __shfl_xor(q[k].x, off);
-      q[k].y += __shfl_xor(q[k].y, off);
-      q[k].z += __shfl_xor(q[k].z, off);
-      q[k].w += __shfl_xor(q[k].w, off);
-    }
+    for (int k = 0; k < NQ; ++k)
+#pragma unroll
+      for (int i = 0; i < NW; ++i) q[k][i] += __shfl_xor(q[k][i], off);
   }
-  // raw fp32 image (N floats) for the LDS partial-sum buffer
+  // raw fp32 image (N floats) for LDS partial sums
   __device__ __forceinline__ void to_lds(float* p) const {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) *reinterpret_cast<f32x4*>(p + 4 * k) = q[k];
+    for (int k = 0; k < NQ; ++k) *reinterpret_cast<F*>(p + NW * k) = q[k];
   }
   __device__ __forceinline__ void from_lds(const float* p) {
 #pragma unroll
-    for (int k = 0; k < NV; ++k) q[k] = *reinterpret_cast<const f32x4*>(p + 4 * k);
+    for (int k = 0; k < NQ; ++k) q[k] = *reinterpret_cast<const F*>(p + NW * k);
   }
-  // store the first min(left, N) elements at p (p is 16-byte aligned)
+  // store the first min(left, N) elements at p (p aligned to 4 * NW bytes)
   __device__ __forceinline__ void store(unsigned char* p, int left) const {
+    W w;
     if constexpr (ES == 4) {
-      if (left >= 4) {
-        *reinterpret_cast<f32x4*>(p) = q[0];
-      } else {
-        float* y = reinterpret_cast<float*>(p);
-        y[0] = q[0].x;
-        if (left > 1) y[1] = q[0].y;
-        if (left > 2) y[2] = q[0].z;
-      }
+      w = __builtin_bit_cast(W, q[0]);
     } else {
-      u32x4 w;
-      w.x = pack2(q[0].x, q[1].x);
-      w.y = pack2(q[0].y, q[1].y);
-      w.z = pack2(q[0].z, q[1].z);
-      w.w = pack2(q[0].w, q[1].w);
-      if (left >= 8) {
-        *reinterpret_cast<u32x4*>(p) = w;
-      } else {
-        uint16_t* y = reinterpret_cast<uint16_t*>(p);
-        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-        for (int i = 0; i < left; ++i)
-          y[i] = static_cast<uint16_t>((i & 1) ? (ww[i >> 1] >> 16) : (ww[i >> 1] & 0xffffu));
+#pragma unroll
+      for (int i = 0; i < NW; ++i) w[i] = pack2(q[0][i], q[1][i]);
+    }
+    if (left >= N) {
+      *reinterpret_cast<W*>(p) = w;
+    } else if constexpr (ES == 4) {
+      uint32_t* y = reinterpret_cast<uint32_t*>(p);
+#pragma unroll
+      for (int i = 0; i < NW; ++i)
+        if (i < left) y[i] = w[i];
+    } else {
+      uint16_t* y = reinterpret_cast<uint16_t*>(p);
+#pragma unroll
+      for (int i = 0; i < NW; ++i) {
+        if (2 * i < left) y[2 * i] = static_cast<uint16_t>(w[i] & 0xffffu);
+        if (2 * i + 1 < left) y[2 * i + 1] = static_cast<uint16_t>(w[i] >> 16);
       }
     }
   }
-  static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {  // RNE, lo in the low half
-    const f32x2 pr = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
-  }
 };
 
+template <int ES>
+using Chunk = Piece<ES, 4>;   // 16 bytes of a row
+
 struct SpmmArgs {
-  const int64_t* row_begin;
+  const int64_t* row_begin;  // row i is entries [row_begin[i], row_end[i]) ...
   const int64_t* row_end;
+  const int64_t* rowptr;     // ... a prefix of [rowptr[i], rowptr[i+1]); entries of that range
+                             // at or after row_end[i] have col >= n_x_rows
   const int32_t* col;
   const float* val;
   const unsigned char* X;  // [n_x_rows, ld_x] elements of ES bytes
@@ -131,21 +147,267 @@ struct SpmmArgs {
   int64_t ld_y;            // bytes
   int64_t n_rows;
   int32_t d;               // elements per row
+  int32_t rows_per_block;  // stream kernel: R rows per workgroup for the first n_big_blocks
+  int32_t n_big_blocks;    // workgroups, R / 4 rows for the rest (see launch_spmm_es)
   const float* self_val;   // nullable: Y[i] += self_val[i] * X[self_off + i]
   int64_t self_off;
 };
 
-// acc += sum over entries [s, e) of val * X[col]; all lanes of the wavefront take part.
-// Lane (grp, gl) handles chunk (ch * G + gl) of the feature row, counted from
-// element col_base.
-template <int ES, int G, int NCH, int U>
-__device__ __forceinline__ void walk_entries(const SpmmArgs& a, int64_t s, int64_t e, int col_base,
-                                             int lane, Chunk<ES> (&acc)[NCH]) {
+__device__ __forceinline__ int rl(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ float rlf(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+template <int ES, int NW, int NCH, int U>
+__global__ __launch_bounds__(kWaves * kWave) void spmm_stream_kernel(SpmmArgs a) {
+  typedef Piece<ES, NW> P;
+  constexpr int EPL = P::N;                       // elements per lane per chunk
+  constexpr int kPassElems = kWave * EPL * NCH;   // elements of a row covered by one pass
+  __shared__ int64_t rp[kMaxRowsPerBlock + 1];
+  __shared__ int32_t head_row[kWaves], head_closed[kWaves], tail_row[kWaves];
+  __shared__ __attribute__((aligned(16))) float part[kWaves][2][kPassElems];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int big = a.rows_per_block, nbig = a.n_big_blocks;
+  const int bid = blockIdx.x;
+  const int R = bid < nbig ? big : big / 4;
+  const int64_t row0 = bid < nbig ? static_cast<int64_t>(bid) * big
+                                  : static_cast<int64_t>(nbig) * big + static_cast<int64_t>(bid - nbig) * R;
+  const int nr = static_cast<int>(a.n_rows - row0 < R ? a.n_rows - row0 : R);
+  const int col_base = blockIdx.y * kPassElems;
+
+  for (int t = threadIdx.x; t <= nr; t += kWaves * kWave) rp[t] = a.rowptr[row0 + t];
+  if (threadIdx.x < kWaves) {
+    head_row[threadIdx.x] = -1;
+    head_closed[threadIdx.x] = 0;
+    tail_row[threadIdx.x] = -1;
+  }
+  __syncthreads();
+
+  // this lane's slice of a row: element offsets and validity per chunk
+  int el0[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) el0[ch] = col_base + (ch * kWave + lane) * EPL;
+
+  auto store_row = [&](int r, P (&acc)[NCH]) {   // final value of local row r of this workgroup
+    const int64_t row = row0 + r;
+    if (a.self_val != nullptr) {
+      const float sv = a.self_val[row];
+      const unsigned char* xr = a.X + (a.self_off + row) * a.ld_x;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch)
+        if (el0[ch] < a.d) {
+          P x;
+          x.load(xr + static_cast<int64_t>(el0[ch]) * ES);
+          acc[ch].fma(sv, x);
+        }
+    }
+    unsigned char* yr = a.Y + row * a.ld_y;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      const int left = a.d - el0[ch];
+      if (left > 0) acc[ch].store(yr + static_cast<int64_t>(el0[ch]) * ES, left);
+    }
+  };
+
+  const int64_t e0 = rp[0];
+  const int32_t total = static_cast<int32_t>(rp[nr] - e0);   // < 2^31: checked by the host
+  const int32_t per = ((total + kWaves - 1) / kWaves + kWave - 1) / kWave * kWave;
+  const int32_t ps = wave * per;                                  // offsets relative to e0
+  const int32_t pe = ps + per < total ? ps + per : total;
+
+  if (wave == 0 || ps < total) {
+    // first row of this piece: rows that end at or before ps belong to earlier pieces
+    int cur = 0;
+    if (wave != 0)
+      for (int k0 = 0; k0 < nr; k0 += kWave) {
+        const int k = k0 + lane;
+        cur += __builtin_popcountll(__ballot(k < nr && static_cast<int32_t>(rp[k + 1] - e0) <= ps));
+      }
+    cur = __builtin_amdgcn_readfirstlane(cur);
+    const int first = cur;
+    const bool head_partial =
+        __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur < nr ? cur : nr] - e0)) < ps;
+    int32_t cur_end =
+        cur < nr ? __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur + 1] - e0)) : kEnd;
+
+    // Two-level sum: `acc` takes the products of up to kFold entries, then is folded into
+    // `tot`. A plain running sum over a hub row's thousand-odd entries of one piece lets
+    // the rounding errors of like-signed terms pile up linearly.
+    P acc[NCH], tot[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      acc[ch].zero();
+      tot[ch].zero();
+    }
+    int rounds = 0;
+
+    auto flush = [&]() {   // row `cur` ends inside this piece
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) acc[ch].add(tot[ch]);
+      if (cur == first && head_partial) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) acc[ch].to_lds(&part[wave][0][(ch * kWave + lane) * EPL]);
+        if (lane == 0) {
+          head_row[wave] = cur;
+          head_closed[wave] = 1;
+        }
+      } else {
+        store_row(cur, acc);
+      }
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        acc[ch].zero();
+        tot[ch].zero();
+      }
+      ++cur;
+      cur_end = cur < nr ? __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur + 1] - e0)) : kEnd;
+    };
+
+    // ---- index chunks: `c, v, p` hold the current 64 (squeezed) entries, `rc, rv` the raw next ones
+    int32_t c = 0, p = 0, rc = 0;
+    float v = 0.f, rv = 0.f;
+    int cnt = 0, idx = 0;             // entries in the current chunk / next one to hand out
+    int32_t raw_base = ps;            // offset of the raw chunk
+    bool has_raw = ps < pe;
+    auto load_raw = [&]() {
+      const int32_t o = raw_base + lane;
+      rc = -1;
+      rv = 0.f;
+      if (o < pe) {
+        rc = a.col[e0 + o];
+        rv = a.val[e0 + o];
+      }
+    };
+    if (has_raw) load_raw();
+    auto shift = [&]() {              // raw chunk -> current chunk (squeezed), fetch the following raw chunk
+      const bool ok = static_cast<uint32_t>(rc) < static_cast<uint64_t>(a.n_x_rows);
+      const uint64_t mask = __ballot(ok);
+      cnt = __builtin_popcountll(mask);
+      const int32_t o = raw_base + lane;
+      const int n_raw = pe - raw_base < kWave ? pe - raw_base : kWave;
+      if (cnt == n_raw) {             // nothing to squeeze out (valid entries are lanes 0..n_raw-1)
+        c = rc;
+        v = rv;
+        p = o;
+      } else {
+        const int below = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0));
+        const int dest = (ok ? below : cnt + (lane - below)) << 2;
+        c = __builtin_amdgcn_ds_permute(dest, rc);
+        v = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(dest, __builtin_bit_cast(int, rv)));
+        p = __builtin_amdgcn_ds_permute(dest, o);
+      }
+      idx = 0;
+      raw_base += kWave;
+      has_raw = raw_base < pe;
+      if (has_raw) load_raw();
+    };
+
+    // ---- ring of U gathers
+    typename P::W x[U][NCH];          // raw words; widened to fp32 when they are added
+    float sv[U];
+    int32_t sp[U];
+    auto fetch = [&](int u) {
+      while (idx >= cnt) {
+        if (!has_raw) {
+          sp[u] = kEnd;
+          return;
+        }
+        shift();
+      }
+      const int32_t cj = rl(c, idx);
+      sv[u] = rlf(v, idx);
+      sp[u] = rl(p, idx);
+      ++idx;
+      const unsigned char* xr = a.X + static_cast<int64_t>(cj) * a.ld_x;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        if (el0[ch] < a.d)
+          x[u][ch] = P::load_raw(xr + static_cast<int64_t>(el0[ch]) * ES);
+        else
+          x[u][ch] = typename P::W(0u);
+      }
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) fetch(u);
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (sp[u] == kEnd) {
+          more = false;
+          break;
+        }
+        while (sp[u] >= cur_end) flush();
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+          P xw;
+          xw.widen(x[u][ch]);
+          acc[ch].fma(sv[u], xw);
+        }
+        fetch(u);
+      }
+      if (++rounds == kFold / U) {
+        rounds = 0;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+          tot[ch].add(acc[ch]);
+          acc[ch].zero();
+        }
+      }
+    }
+    // rows that end inside this piece after its last entry (trailing skipped entries, empty rows)
+    while (cur < nr && cur_end <= pe) flush();
+    // a row that continues into the next piece
+    if (cur < nr && __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur] - e0)) < pe) {
+      const int slot = (cur == first && head_partial) ? 0 : 1;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) acc[ch].add(tot[ch]);
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) acc[ch].to_lds(&part[wave][slot][(ch * kWave + lane) * EPL]);
+      if (lane == 0) {
+        if (slot == 0)
+          head_row[wave] = cur;   // the whole piece lies inside one row; head_closed stays 0
+        else
+          tail_row[wave] = cur;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- rows cut by piece boundaries: the wavefront in whose piece the row ended adds the
+  // partial sums in piece order: the tail of the piece it began in, then the heads after it
+  if (head_row[wave] >= 0 && head_closed[wave]) {
+    int ws = -1;
+    for (int k = 0; k < wave; ++k)
+      if (tail_row[k] >= 0) ws = k;
+    if (ws >= 0) {
+      P sum[NCH], other;
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) sum[ch].from_lds(&part[ws][1][(ch * kWave + lane) * EPL]);
+      for (int k = ws + 1; k <= wave; ++k) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+          other.from_lds(&part[k][0][(ch * kWave + lane) * EPL]);
+          sum[ch].add(other);
+        }
+      }
+      store_row(head_row[wave], sum);
+    }
+  }
+}
+
+// acc += sum over entries [s, e) of val * X[col]; all lanes of the wavefront take part
+// (64/G entries at a time). Lane (grp, gl) handles 16-byte chunk gl of the feature row.
+template <int ES, int G, int U>
+__device__ __forceinline__ void walk_entries(const SpmmArgs& a, int64_t s, int64_t e, int lane,
+                                             Chunk<ES>& acc) {
   constexpr int NG = kWave / G;
   constexpr int EPL = Chunk<ES>::N;
   const int gl = lane % G;
   const int grp = lane / G;
-  const unsigned char* Xc = a.X + static_cast<int64_t>(col_base) * ES;
   for (int64_t base = s; base < e; base += kWave) {
     const int cnt = static_cast<int>(e - base < kWave ? e - base : kWave);
     int32_t c = 0;
@@ -166,145 +428,21 @@ __device__ __forceinline__ void walk_entries(const SpmmArgs& a, int64_t s, int64
         // entries past the end re-read the last valid row with weight 0
         const int idx = j0 + u * NG + grp;
         const int idc = idx < cnt ? idx : cnt - 1;
-        if constexpr (G == kWave) {
-          cj[u] = __builtin_amdgcn_readlane(c, idc);
-          vj[u] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), idc));
-        } else {
-          cj[u] = __shfl(c, idc);
-          vj[u] = __shfl(v, idc);
-        }
+        cj[u] = __shfl(c, idc);
+        vj[u] = __shfl(v, idc);
         if (idx >= cnt) vj[u] = 0.f;
       }
-      Chunk<ES> x[U][NCH];
+      Chunk<ES> x[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const unsigned char* xr = Xc + static_cast<int64_t>(cj[u]) * a.ld_x;
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
-          const int c0 = (ch * G + gl) * EPL;
-          if (col_base + c0 < a.d)
-            x[u][ch].load(xr + c0 * ES);
-          else
-            x[u][ch].zero();
-        }
+        if (gl * EPL < a.d)
+          x[u].load(a.X + static_cast<int64_t>(cj[u]) * a.ld_x + gl * EPL * ES);
+        else
+          x[u].zero();
       }
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) acc[ch].fma(vj[u], x[u][ch]);
+      for (int u = 0; u < U; ++u) acc.fma(vj[u], x[u]);
     }
-  }
-}
-
-template <int ES, int G, int NCH>
-__device__ __forceinline__ void reduce_groups(Chunk<ES> (&acc)[NCH]) {
-  if constexpr (G < kWave) {
-#pragma unroll
-    for (int off = G; off < kWave; off <<= 1) {
-#pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) acc[ch].xor_add(off);
-    }
-  }
-}
-
-// acc += self_val[row] * X[self_off + row] (lanes of group 0 only)
-template <int ES, int G, int NCH>
-__device__ __forceinline__ void add_self(const SpmmArgs& a, int64_t row, int col_base, int gl,
-                                         Chunk<ES> (&acc)[NCH]) {
-  constexpr int EPL = Chunk<ES>::N;
-  const float sv = a.self_val[row];
-  const unsigned char* xr = a.X + (a.self_off + row) * a.ld_x + static_cast<int64_t>(col_base) * ES;
-#pragma unroll
-  for (int ch = 0; ch < NCH; ++ch) {
-    const int c0 = (ch * G + gl) * EPL;
-    if (col_base + c0 < a.d) {
-      Chunk<ES> x;
-      x.load(xr + c0 * ES);
-      acc[ch].fma(sv, x);
-    }
-  }
-}
-
-template <int ES, int G, int NCH, int U>
-__global__ __launch_bounds__(kRowsPerBlock * kWave) void spmm_kernel(SpmmArgs a) {
-  constexpr int EPL = Chunk<ES>::N;
-  constexpr int kPartElems = G * EPL * NCH;  // elements of one wavefront's partial row
-  __shared__ int64_t long_s[kRowsPerBlock], long_e[kRowsPerBlock];
-  __shared__ __attribute__((aligned(16))) float part[kRowsPerBlock][kPartElems];
-
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock;
-  const int64_t row = row0 + wave;
-  const int gl = lane % G;
-  const int grp = lane / G;
-  const int col_base = blockIdx.y * kPartElems;
-
-  int64_t s = 0, e = 0;
-  if (row < a.n_rows) {
-    s = a.row_begin[row];
-    e = a.row_end[row];
-  }
-  const bool is_long = (e - s) > kLongRow;
-  if (lane == 0) {
-    long_s[wave] = is_long ? s : 0;
-    long_e[wave] = is_long ? e : 0;
-  }
-
-  // ---- short rows: one wavefront each
-  if (row < a.n_rows && !is_long) {
-    Chunk<ES> acc[NCH];
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) acc[ch].zero();
-    walk_entries<ES, G, NCH, U>(a, s, e, col_base, lane, acc);
-    if (a.self_val != nullptr && grp == 0) add_self<ES, G, NCH>(a, row, col_base, gl, acc);
-    reduce_groups<ES, G, NCH>(acc);
-    if (grp == 0) {
-      unsigned char* yr = a.Y + row * a.ld_y + static_cast<int64_t>(col_base) * ES;
-#pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) {
-        const int c0 = (ch * G + gl) * EPL;
-        const int left = a.d - (col_base + c0);
-        if (left > 0) acc[ch].store(yr + c0 * ES, left);
-      }
-    }
-  }
-  __syncthreads();
-
-  // ---- long rows of this workgroup: all wavefronts share each one
-  for (int w = 0; w < kRowsPerBlock; ++w) {
-    const int64_t ls = long_s[w], le = long_e[w];
-    if (le <= ls) continue;  // uniform over the workgroup
-    const int64_t piece = ((le - ls + kRowsPerBlock - 1) / kRowsPerBlock + kWave - 1) / kWave * kWave;
-    int64_t ps = ls + wave * piece;
-    int64_t pe = ps + piece < le ? ps + piece : le;
-    if (ps > le) ps = le;
-    Chunk<ES> acc[NCH];
-#pragma unroll
-    for (int ch = 0; ch < NCH; ++ch) acc[ch].zero();
-    walk_entries<ES, G, NCH, U>(a, ps, pe, col_base, lane, acc);
-    const int64_t lrow = row0 + w;
-    if (a.self_val != nullptr && wave == 0 && grp == 0) add_self<ES, G, NCH>(a, lrow, col_base, gl, acc);
-    reduce_groups<ES, G, NCH>(acc);
-    if (grp == 0) {
-#pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) acc[ch].to_lds(&part[wave][(ch * G + gl) * EPL]);
-    }
-    __syncthreads();
-    // fixed-order sum of the 8 partial rows, one 16-byte output chunk per thread
-    for (int q = threadIdx.x; q < kPartElems / EPL; q += kRowsPerBlock * kWave) {
-      Chunk<ES> sum, other;
-      sum.from_lds(&part[0][q * EPL]);
-#pragma unroll
-      for (int k = 1; k < kRowsPerBlock; ++k) {
-        other.from_lds(&part[k][q * EPL]);
-        sum.add(other);
-      }
-      const int left = a.d - (col_base + q * EPL);
-      if (left > 0)
-        sum.store(a.Y + lrow * a.ld_y + static_cast<int64_t>(col_base + q * EPL) * ES, left);
-    }
-    __syncthreads();
   }
 }
 
@@ -383,12 +521,17 @@ __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max
     const int src = __builtin_ctzll(todo);
     todo &= todo - 1;
     const int64_t rs = __shfl(s0, src), re = __shfl(e0, src), r = __shfl(row, src);
-    Chunk<ES> wacc[1];
-    wacc[0].zero();
-    walk_entries<ES, G, 1, U>(a, rs, re, 0, lane, wacc);
-    if (a.self_val != nullptr && grp == 0) add_self<ES, G, 1>(a, r, 0, gl, wacc);
-    reduce_groups<ES, G, 1>(wacc);
-    if (grp == 0 && col_ok) wacc[0].store(a.Y + r * a.ld_y + c0 * ES, a.d - c0);
+    Chunk<ES> wacc;
+    wacc.zero();
+    walk_entries<ES, G, U>(a, rs, re, lane, wacc);
+    if (a.self_val != nullptr && grp == 0 && col_ok) {
+      Chunk<ES> x;
+      x.load(a.X + (a.self_off + r) * a.ld_x + c0 * ES);
+      wacc.fma(a.self_val[r], x);
+    }
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1) wacc.xor_add(off);
+    if (grp == 0 && col_ok) wacc.store(a.Y + r * a.ld_y + c0 * ES, a.d - c0);
   }
 }
 
@@ -397,19 +540,19 @@ __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max
 namespace sat {
 
 // Y[n_rows, d] = M * X (+ diag(self_val) * X[self_off + i]) where row i of M is
-// (col, val)[row_begin[i] .. row_end[i]). X and Y hold elements of es bytes
-// (4: fp32, 2: bf16; sums in fp32 either way), ld in elements. Pointers are
-// device pointers; X and Y 16-byte aligned with ld * es % 16 == 0 (checked by
-// the callers).
+// (col, val)[rowptr[i] .. row_end[i]) with row_end = rowptr + 1 if row_end is
+// NULL. A caller that passes row_end guarantees that the entries it cuts off,
+// [row_end[i], rowptr[i+1]), all have col >= n_x_rows (they are skipped by
+// their column id, not by position). X and Y hold elements of es bytes (4:
+// fp32, 2: bf16; sums in fp32 either way), ld in elements. Pointers are device
+// pointers; X and Y 16-byte aligned with ld * es % 16 == 0 (checked by the
+// callers). total_entries = rowptr[n_rows] - rowptr[0], known to the caller.
 template <int ES>
-static sat_status launch_spmm_es(const SpmmArgs& a, int64_t total_entries, hipStream_t stream) {
+static sat_status launch_spmm_es(SpmmArgs a, int64_t total_entries, hipStream_t stream) {
   const int64_t n_rows = a.n_rows;
   const int32_t d = a.d;
-  const int64_t bx = (n_rows + kRowsPerBlock - 1) / kRowsPerBlock;
-  if (bx > INT32_MAX) return SAT_EUNSUPPORTED;
   constexpr int EPL = 16 / ES;
   const int nvec = (d + EPL - 1) / EPL;   // 16-byte chunks per row
-  const dim3 block(kRowsPerBlock * kWave);
   // Few entries per row and narrow rows: a group of lanes per row.
   constexpr int64_t kGroupMaxLen = 64;
   if (nvec <= 32 && total_entries < 16 * n_rows) {
@@ -429,34 +572,51 @@ static sat_status launch_spmm_es(const SpmmArgs& a, int64_t total_entries, hipSt
     }
     return sat::check_launch();
   }
-#define SAT_SPMM_LAUNCH(G, NCH, U)                                                            \
+  // Stream kernel. Offsets inside a workgroup's span are 32-bit and 8 * (an eighth of the
+  // span, rounded up) must not overflow.
+  if (total_entries >= (int64_t{1} << 30)) return SAT_EUNSUPPORTED;
+  // rows per workgroup: about 384 entries per wavefront
+  int64_t R = 8;
+  const int64_t want = kWaves * 384 * n_rows / (total_entries > 0 ? total_entries : 1);
+  while (R < kMaxRowsPerBlock && R < want) R <<= 1;
+  a.rows_per_block = static_cast<int32_t>(R);
+  // Workgroups are dispatched in index order and live for a few hundred microseconds, so
+  // the last ones would run on a half-empty chip: the last eighth of the rows goes to
+  // workgroups a quarter the size.
+  const int64_t n_big = n_rows / R * 7 / 8;
+  const int64_t rest = n_rows - n_big * R;
+  const int64_t bx = n_big + (rest + R / 4 - 1) / (R / 4);
+  a.n_big_blocks = static_cast<int32_t>(n_big);
+  if (bx > INT32_MAX) return SAT_EUNSUPPORTED;
+  const dim3 block(kWaves * kWave);
+  const int row_bytes = d * ES;
+#define SAT_SPMM_LAUNCH(NW, NCH, U)                                                           \
   do {                                                                                        \
-    const int per_pass = (G) * EPL * (NCH);                                                   \
-    const dim3 grid(static_cast<unsigned>(bx), static_cast<unsigned>((d + per_pass - 1) / per_pass)); \
-    spmm_kernel<ES, G, NCH, U><<<grid, block, 0, stream>>>(a);                                \
+    const int per_pass = kWave * (NW) * 4 * (NCH);                                            \
+    const dim3 grid(static_cast<unsigned>(bx),                                                \
+                    static_cast<unsigned>((row_bytes + per_pass - 1) / per_pass));            \
+    spmm_stream_kernel<ES, NW, NCH, U><<<grid, block, 0, stream>>>(a);                        \
   } while (0)
-  if (nvec <= 1) SAT_SPMM_LAUNCH(1, 1, 4);
-  else if (nvec <= 2) SAT_SPMM_LAUNCH(2, 1, 4);
-  else if (nvec <= 4) SAT_SPMM_LAUNCH(4, 1, 4);
-  else if (nvec <= 8) SAT_SPMM_LAUNCH(8, 1, 4);
-  else if (nvec <= 16) SAT_SPMM_LAUNCH(16, 1, 4);
-  else if (nvec <= 32) SAT_SPMM_LAUNCH(32, 1, 4);
-  else if (nvec <= 64) SAT_SPMM_LAUNCH(64, 1, ES == 4 ? 8 : 4);
-  else if (nvec <= 128) SAT_SPMM_LAUNCH(64, 2, ES == 4 ? 4 : 2);
-  else if (nvec <= 192) SAT_SPMM_LAUNCH(64, 3, 2);
-  else SAT_SPMM_LAUNCH(64, 4, ES == 4 ? 2 : 1);
+  if (row_bytes <= 256) SAT_SPMM_LAUNCH(1, 1, 16);
+  else if (row_bytes <= 512) SAT_SPMM_LAUNCH(2, 1, 16);
+  else if (row_bytes <= 1024) SAT_SPMM_LAUNCH(4, 1, 16);
+  else if (row_bytes <= 2048 || ES == 2) SAT_SPMM_LAUNCH(4, 2, 8);
+  else if constexpr (ES == 4) {   // fp32 partial sums of wider bf16 rows would not fit LDS: more passes
+    if (row_bytes <= 3072) SAT_SPMM_LAUNCH(4, 3, 4);
+    else SAT_SPMM_LAUNCH(4, 4, 4);
+  }
 #undef SAT_SPMM_LAUNCH
   return sat::check_launch();
 }
 
-sat_status launch_spmm(const int64_t* row_begin, const int64_t* row_end, const int32_t* col,
+sat_status launch_spmm(const int64_t* rowptr, const int64_t* row_end, const int32_t* col,
                        const float* val, const void* X, int64_t ld_x, int64_t n_x_rows, void* Y,
                        int64_t ld_y, int64_t n_rows, int32_t d, int es, const float* self_val,
                        int64_t self_off, int64_t total_entries, hipStream_t stream) {
   if (n_rows == 0 || d == 0) return SAT_OK;
-  const SpmmArgs a{row_begin, row_end, col, val, static_cast<const unsigned char*>(X), ld_x * es,
-                   n_x_rows, static_cast<unsigned char*>(Y), ld_y * es, n_rows, d, self_val,
-                   self_off};
+  const SpmmArgs a{rowptr, row_end ? row_end : rowptr + 1, rowptr, col, val,
+                   static_cast<const unsigned char*>(X), ld_x * es, n_x_rows,
+                   static_cast<unsigned char*>(Y), ld_y * es, n_rows, d, 0, 0, self_val, self_off};
   return es == 2 ? launch_spmm_es<2>(a, total_entries, stream)
                  : launch_spmm_es<4>(a, total_entries, stream);
 }
@@ -504,7 +664,7 @@ extern "C" sat_status sat_spmm_fwd(const sat_part_view* pv, const void* Hbar, in
   const int es = dtype == SAT_BF16 ? 2 : 4;
   if ((st = validate_dense(Hbar, pv->n_local + pv->n_halo, ld_in, d, es)) != SAT_OK) return st;
   if ((st = validate_dense(AGG, pv->n_local, ld_out, d, es)) != SAT_OK) return st;
-  return launch_spmm(pv->rowptr, pv->rowptr + 1, pv->col, pv->val, Hbar, ld_in,
+  return launch_spmm(pv->rowptr, nullptr, pv->col, pv->val, Hbar, ld_in,
                      pv->n_local + pv->n_halo, AGG, ld_out, pv->n_local, d, es, nullptr, 0, pv->nnz,
                      static_cast<hipStream_t>(stream));
 }
@@ -528,10 +688,11 @@ extern "C" sat_status sat_spmm_bwd(const sat_part_view* pv, const void* dAGG, in
       return SAT_EINVAL;
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  // P_in^T = P_in: row i's local columns are [rowptr[i], split[i])
+  // P_in^T = P_in: row i's local columns are [rowptr[i], split[i]); the entries after
+  // split[i] are halo columns, whose relabelled ids are >= n_local
   st = launch_spmm(pv->rowptr, pv->split, pv->col, pv->val, dAGG, ld_in, pv->n_local, dH_local,
-                   ld_out, pv->n_local, d, es, nullptr, 0, pv->nnz - pv->nnz_halo, s);
+                   ld_out, pv->n_local, d, es, nullptr, 0, pv->nnz, s);
   if (st != SAT_OK || !dH_halo) return st;
-  return launch_spmm(pv->h_colptr, pv->h_colptr + 1, pv->h_row, pv->h_val, dAGG, ld_in,
+  return launch_spmm(pv->h_colptr, nullptr, pv->h_row, pv->h_val, dAGG, ld_in,
                      pv->n_local, dH_halo, ld_halo, pv->n_halo, d, es, nullptr, 0, pv->nnz_halo, s);
 }
