@@ -59,8 +59,11 @@ __global__ __launch_bounds__(256) void split_weights_kernel(const float* __restr
 
 // ESX = bytes per element of the cached embeddings x (4: fp32, split three ways;
 // 2: bf16, used as it is, so the input products need one x piece only).
-template <int DS, int ESX>
-__global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
+// WAVES = wavefronts per workgroup (4 or 8). LDS holds one workgroup per compute
+// unit whatever WAVES is, so with 8 every SIMD has two wavefronts and one of them
+// can read operands from LDS while the other's products run.
+template <int DS, int ESX, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
                                                       int64_t ld_slot,
                                                       const int32_t* __restrict__ ids,
                                                       int64_t n_nodes, int d, int k_pad,
@@ -69,13 +72,15 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
                                                       const float* __restrict__ bias,
                                                       float* __restrict__ S) {
   constexpr int NP = 3;
+  constexpr int NT = 64 * WAVES;    // threads
   constexpr int WN = DS / 32;       // wavefronts along hidden units
-  constexpr int WM = 4 / WN;        // wavefronts along nodes
+  constexpr int WM = WAVES / WN;    // wavefronts along nodes
   constexpr int RB = R / (32 * WM); // 32-row blocks per wavefront
+  static_assert(RB >= 1 && RB * 32 * WM == R, "wavefront grid must tile the node block");
   constexpr int NB = 4 * DS;        // gate columns
   constexpr int H_ROW_B = DS * 2 + 16;        // bytes per node row of a staged h piece
   constexpr int H_PIECE_B = R * H_ROW_B;
-  constexpr int B_CHUNKS = NP * NB * 4 / 256; // 16-byte weight chunks per thread per K step
+  constexpr int B_CHUNKS = NP * NB * 4 / NT;  // 16-byte weight chunks per thread per K step
   __shared__ __attribute__((aligned(16))) unsigned char As[2 * tile_bytes<R, NP>()];
   __shared__ __attribute__((aligned(16))) unsigned char Bs[tile_bytes<NB, NP>()];
   __shared__ __attribute__((aligned(16))) unsigned char Hs[NP * H_PIECE_B];
@@ -87,13 +92,15 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
   const int c = lane & 31;
   const int64_t node0 = static_cast<int64_t>(blockIdx.x) * R;
 
-  // table row of each node this thread loads x for (-1: nothing to load)
-  // (fp32: rows t / 8 + 32 i, four of them; bf16: rows t / 4 + 64 i, two of them)
-  constexpr int XROWS = ESX == 4 ? R / 32 : R / 64;
+  // An x tile is R rows of 32 elements = 16-byte chunks q = t + NT i of row q / CPR,
+  // CPR chunks per row (fp32: 8, bf16: 4). Table row of each chunk's node (-1: nothing
+  // to load):
+  constexpr int CPR = ESX == 4 ? 8 : 4;
+  constexpr int XROWS = R * CPR / NT;
   int64_t arow[XROWS];
 #pragma unroll
   for (int i = 0; i < XROWS; ++i) {
-    const int64_t node = node0 + (ESX == 4 ? (t >> 3) + 32 * i : (t >> 2) + 64 * i);
+    const int64_t node = node0 + (t + NT * i) / CPR;
     int64_t r = -1;
     if (node < n_nodes) {
       r = ids ? static_cast<int64_t>(ids[node]) : node;
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
   auto load_w = [&](const uint16_t* P, int kp, int k0, u32x4 (&rw)[B_CHUNKS]) {
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-      const int ch = t + 256 * i;
+      const int ch = t + NT * i;
       const int piece = ch / (NB * 4), n = (ch >> 2) % NB, kc = ch & 3;
       rw[i] = *reinterpret_cast<const u32x4*>(P + (static_cast<int64_t>(piece) * NB + n) * kp + k0 +
                                               8 * kc);
@@ -125,14 +132,16 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
   auto store_w = [&](const u32x4 (&rw)[B_CHUNKS]) {
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-      const int ch = t + 256 * i;
+      const int ch = t + NT * i;
       const int piece = ch / (NB * 4), n = (ch >> 2) % NB, kc = ch & 3;
       *reinterpret_cast<u32x4*>(Bs + piece * piece_bytes<NB>() + swz(n, kc)) = rw[i];
     }
   };
 
   const int nk = k_pad / BK;
-  typedef typename RegsOf<ESX, R>::type XRegs;
+  struct XRegs {
+    u32x4 v[XROWS];
+  };
   auto load_x = [&](int j, XRegs& ra) {   // x tile j of the stream (zeros past the end)
     const int sj = j / nk;
     const bool live = sj < tau;
@@ -141,13 +150,13 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
       const float* xs = static_cast<const float*>(slots.p[live ? sj : 0]);
 #pragma unroll
       for (int i = 0; i < XROWS; ++i) {
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        u32x4 v = {0u, 0u, 0u, 0u};
         if (live && arow[i] >= 0 && k < d) {
-          v = *reinterpret_cast<const f32x4*>(xs + arow[i] * ld_slot + k);
+          v = *reinterpret_cast<const u32x4*>(xs + arow[i] * ld_slot + k);
           if (k + 3 >= d) {
-            if (k + 1 >= d) v.y = 0.f;
-            if (k + 2 >= d) v.z = 0.f;
-            v.w = 0.f;
+            if (k + 1 >= d) v.y = 0u;
+            if (k + 2 >= d) v.z = 0u;
+            v.w = 0u;
           }
         }
         ra.v[i] = v;
@@ -166,8 +175,23 @@ __global__ __launch_bounds__(256) void lstm_mx_kernel(SlotPtrs slots, int tau, i
     }
   };
   auto store_x = [&](const XRegs& ra, unsigned char* dst) {
-    if constexpr (ESX == 4) store_tile<R, Layout::KContig, NP>(ra, dst, t);
-    else store_tile_b<R, Layout::KContig>(ra, dst, t);
+#pragma unroll
+    for (int i = 0; i < XROWS; ++i) {
+      const int q = t + NT * i;
+      if constexpr (ESX == 4) {   // 4 floats -> 4 bf16 of each of the three pieces
+        uint32_t lo[NP], hi[NP];
+        // (cast the whole vector: a bit cast applied to one vector element reads element 0)
+        const f32x4 f = __builtin_bit_cast(f32x4, ra.v[i]);
+        split2<NP>(f.x, f.y, lo);
+        split2<NP>(f.z, f.w, hi);
+        unsigned char* sdst = dst + swz(q >> 3, (q & 7) >> 1) + ((q & 1) << 3);
+#pragma unroll
+        for (int p = 0; p < NP; ++p)
+          *reinterpret_cast<u32x2*>(sdst + p * piece_bytes<R>()) = u32x2{lo[p], hi[p]};
+      } else {
+        *reinterpret_cast<u32x4*>(dst + swz(q >> 2, q & 3)) = ra.v[i];
+      }
+    }
   };
   XRegs ra0;
   load_x(0, ra0);
@@ -328,14 +352,14 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
   for (int s = 0; s < kMaxTau; ++s) sp.p[s] = s < tau ? slot_ptrs[s] : nullptr;
   const int64_t blocks = (n_nodes + R - 1) / R;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
-  const dim3 grid(static_cast<unsigned>(blocks)), block(256);
-#define SAT_LSTM_MX(DS, ESX)                                                                   \
-  lstm_mx_kernel<DS, ESX><<<grid, block, 0, st>>>(sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, \
-                                                  k_pad, WxP, WhP, b, S)
-  if (d_s == 32 && es_x == 4) SAT_LSTM_MX(32, 4);
-  else if (d_s == 32) SAT_LSTM_MX(32, 2);
-  else if (es_x == 4) SAT_LSTM_MX(64, 4);
-  else SAT_LSTM_MX(64, 2);
+  const dim3 grid(static_cast<unsigned>(blocks));
+#define SAT_LSTM_MX(DS, ESX, WAVES)                                                            \
+  lstm_mx_kernel<DS, ESX, WAVES><<<grid, dim3(64 * WAVES), 0, st>>>(                           \
+      sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S)
+  if (d_s == 32 && es_x == 4) SAT_LSTM_MX(32, 4, 4);
+  else if (d_s == 32) SAT_LSTM_MX(32, 2, 4);
+  else if (es_x == 4) SAT_LSTM_MX(64, 4, 8);
+  else SAT_LSTM_MX(64, 2, 8);
 #undef SAT_LSTM_MX
   return sat::check_launch();
 }
