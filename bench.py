@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "dense", "large", "scale_small"])
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "dense", "large", "scale_small", "scale_rows_small", "scale"])
     ap.add_argument("--dtype", default=None, choices=["f32", "bf16"],
                     help="storage type of features, activations, history and weights "
                          "(default: the workload's own; sums are fp32 either way)")
@@ -88,6 +88,10 @@ def main():
     ap.add_argument("--unfused-pull", action="store_true",
                     help="assemble the predictor window with sat_history_gather first")
     ap.add_argument("--bypass", action="store_true", help="plain historical embeddings")
+    ap.add_argument("--stale-grad", action="store_true",
+                    help="also run the stale-gradient term of the backward: halo output of the "
+                         "transpose aggregation pushed to a gradient table, table rows of the "
+                         "local nodes added to their gradient")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also launch one plain row copy of known size (1 GiB read + 1 GiB "
                          "written, identity ids) so that a rocprofv3 --pmc run of this command "
@@ -116,7 +120,7 @@ def main():
 
     timers = CallTimers(torch)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
-                        timers=timers, log=log, dtype=args.dtype)
+                        timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad)
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
     dims, tau, d_s, L = wl.dims, wl.tau, wl.d_s, wl.L
@@ -178,12 +182,15 @@ def main():
     for l in range(L):
         add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]))
         if l >= 1:
-            add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]))
+            add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]) + (
+                spmm_bytes(nnz_halo, n_h, dims[l]) if args.stale_grad else 0))
         add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dims[l + 1])
         add("dense_bwd", "dense_bwd_l%d" % l, "mfma",
             (4.0 if l >= 1 else 2.0) * n_l * dims[l] * dims[l + 1])
         if l >= 1:
             add("push", "push_l%d" % l, "hbm", n_l * (2 * dims[l] * s + 4))
+            add("push", "grad_push_l%d" % l, "hbm", n_h * (2 * dims[l] * s + 4))
+            add("gather_add", "grad_pull_l%d" % l, "hbm", n_l * (3 * dims[l] * s + 4))
             add("gather", "gather_l%d" % l, "hbm", n_bar * (2 * dims[l] * s + 4))
             if not args.bypass:
                 flops = (2.0 * n_bar * 4 * d_s * (tau * dims[l] + (tau - 1) * d_s)
@@ -220,7 +227,9 @@ def main():
 
     # ---- CPU oracle on a bounded sample, rank 0, host cores
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and wl.X_host is None:
+        log("cpu oracle: skipped (this workload's inputs are drawn on the device)")
+    elif not args.no_cpu_baseline:
         cpu = cpu_baseline(view, dims, tau, d_s, wl.X_host, wl.hist_host, wl.table_ids, wl.Ws,
                            wl.omegas, wl.y, edges, bypass=args.bypass, log=log)
 
@@ -236,6 +245,7 @@ def main():
                    "dims": dims, "tau": tau, "d_s": d_s,
                    "predictor": "bypass" if args.bypass else "every step",
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
+                   "stale_gradient_term": bool(args.stale_grad),
                    "entries_per_step": edges},
         "ms_per_layer_step": round(ms_per_step / L, 4),
         "ms_by_call": {k: round(v["total_ms"] / args.steps, 4) for k, v in sorted(calls.items())},

@@ -165,6 +165,20 @@ sat_status sat_history_push(void* table, int64_t n_rows, int64_t ld_table, const
                             int64_t n, int32_t d, const void* H, int64_t ld_h, int32_t dtype,
                             void* stream);
 
+/* ------ pull of the stale-gradient term (appendix, SAT backward: the second term
+ * P_out^T D~^(t-1) W^T of G_H). A partition's local nodes are halo nodes of other
+ * partitions; each of those computes P_out^T dAGG for them (sat_spmm_bwd's dH_halo),
+ * pushes it into a gradient table with sat_history_push, and one step later the
+ * owner adds its rows to its own gradient:
+ *   out[k, 0:d) += table[ids[k], 0:d) for k in [0, n), added in fp32 (bf16: one
+ * rounding of the sum). ids with repeats are allowed (each k is its own row of
+ * out); an id outside [0, n_rows) adds nothing. out must not overlap table.
+ * Unlike gather and push this call needs 16-byte aligned rows (SAT_EALIGN).
+ */
+sat_status sat_history_gather_add(const void* table, int64_t n_rows, int64_t ld_table,
+                                  const int32_t* ids, int64_t n, int32_t d, void* out,
+                                  int64_t ld_out, int32_t dtype, void* stream);
+
 /* -------------------- embedding predictor g_omega (Eq. 7; Sec. "Embedding Predictor")
  * Writes the predicted halo embeddings H_out_hat into rows [n_local, n_bar)
  * of Hbar [n_bar, ld]:

@@ -135,6 +135,70 @@ def partition_view(N, g_rowptr, g_col, part, m, g_deg=None):
                 h_self=h_self)
 
 
+def partition_view_sample(N, g_rowptr, g_col, part, m, rows, halo_sample, g_deg=None):
+    """The parts of partition_view that a graph too large for its per-node
+    loops still allows: the complete id lists and row offsets (array
+    operations over the partition's entries), and for the sampled local rows
+    `rows` and sampled halo nodes `halo_sample` (ranks) their entries exactly
+    as partition_view lays them out. Same definitions as partition_view; the
+    two are compared on small graphs by the tests.
+
+    Returns dict(local_ids, halo_ids, rowptr, n_local, n_halo, nnz, nnz_halo,
+    h_colptr, h_self, row_entries = {i: (col, val, split_offset)},
+    halo_entries = {u: (h_row, h_val)}).
+    """
+    part = np.asarray(part)
+    if g_deg is None:
+        g_deg = np.diff(g_rowptr)
+    isd = inv_sqrt_degree(g_deg)
+    local_ids = np.flatnonzero(part == m).astype(np.int32)
+    n_local = local_ids.size
+    lens = (g_rowptr[1:] - g_rowptr[:-1])[local_ids]
+    # every entry of the partition's rows, row by row (runs of consecutive ids are one slice)
+    brk = np.flatnonzero(np.diff(local_ids) != 1) + 1
+    starts = np.concatenate([[0], brk])
+    ends = np.concatenate([brk, [n_local]])
+    ent = np.concatenate([g_col[g_rowptr[local_ids[a]]:g_rowptr[local_ids[b - 1] + 1]]
+                          for a, b in zip(starts, ends)]) if n_local else np.zeros(0, np.int32)
+    outside = ent[part[ent] != m]
+    halo_ids = np.unique(outside).astype(np.int32)
+    n_halo = halo_ids.size
+    rowptr = np.zeros(n_local + 1, dtype=np.int64)
+    np.cumsum(lens + 1, out=rowptr[1:])                      # + the self-loop
+    h_colptr = np.zeros(n_halo + 1, dtype=np.int64)
+    np.cumsum(np.bincount(np.searchsorted(halo_ids, outside), minlength=n_halo), out=h_colptr[1:])
+    h_self = (isd[halo_ids] * isd[halo_ids]).astype(np.float32)
+
+    def relabel(ids):
+        ids = np.asarray(ids, dtype=np.int64)
+        loc = part[ids] == m
+        out = np.empty(ids.shape, dtype=np.int64)
+        out[loc] = np.searchsorted(local_ids, ids[loc])
+        out[~loc] = n_local + np.searchsorted(halo_ids, ids[~loc])
+        return out
+
+    row_entries = {}
+    for i in rows:
+        g = int(local_ids[i])
+        nb = np.concatenate([g_col[g_rowptr[g]:g_rowptr[g + 1]], [g]])
+        c = relabel(nb)
+        order = np.argsort(c, kind="stable")
+        c = c[order]
+        v = (isd[g] * isd[nb[order]]).astype(np.float32)
+        row_entries[int(i)] = (c.astype(np.int32), v, int(np.searchsorted(c, n_local)))
+    halo_entries = {}
+    if len(halo_sample):
+        ent_row = np.repeat(np.arange(n_local, dtype=np.int64), lens)   # local row of every entry
+        for u in halo_sample:
+            gid = int(halo_ids[u])
+            r = np.sort(ent_row[ent == gid])
+            v = (isd[local_ids[r]] * isd[gid]).astype(np.float32)
+            halo_entries[int(u)] = (r.astype(np.int32), v)
+    return dict(n_local=n_local, n_halo=n_halo, nnz=int(rowptr[-1]), nnz_halo=int(h_colptr[-1]),
+                local_ids=local_ids, halo_ids=halo_ids, rowptr=rowptr, h_colptr=h_colptr,
+                h_self=h_self, row_entries=row_entries, halo_entries=halo_entries)
+
+
 # --------------------------------------------------------------------------
 # bf16 storage mode: tensors kept in HBM as bfloat16 are rounded when they are
 # stored; all arithmetic stays fp64 here (fp32 on the GPU).
@@ -336,8 +400,15 @@ def predict(view, omega, slots, bypass=False):
 # --------------------------------------------------------------------------
 # Whole step of one partition (Alg. 1 inner body; Eq. 7; appendix fwd / bwd)
 # --------------------------------------------------------------------------
-def partition_step(view, X_local, X_halo, halo_hat, Ws, y, store=None):
+def partition_step(view, X_local, X_halo, halo_hat, Ws, y, store=None, stale_grad=None):
     """Forward and backward of an L-layer GCN on one partition.
+
+    stale_grad (optional): stale_grad[l] for l = 1..L-1, [n_local, d_l]: the second
+    term of the appendix's SAT backward, P_out^T D~^(t-1) W^T, as this partition's
+    local nodes receive it from the partitions that hold them as halo nodes (it
+    was computed there one step earlier); added to dH_in[l]. The matching
+    output is dH_halo[l] = P_out^T dAGG_l, this partition's contribution to the
+    owners of its halo nodes.
 
     store (optional): applied to every tensor the step keeps in memory between
     calls (AGG, H, the loss gradient, dAGG, dH_in) - the identity for fp32
@@ -371,6 +442,7 @@ def partition_step(view, X_local, X_halo, halo_hat, Ws, y, store=None):
     dH_in = [None] * L
     dZ = [None] * L
     dAGGs = [None] * L
+    dH_halo = [None] * L
     for l in range(L - 1, -1, -1):
         # relu'(Z) = [H > 0]: the stored forward output is the mask (for bf16 storage a
         # positive Z never rounds to zero, so this is the same decision)
@@ -379,10 +451,14 @@ def partition_step(view, X_local, X_halo, halo_hat, Ws, y, store=None):
         dAGG = store(dAGG)
         dAGGs[l] = dAGG
         if l >= 1:
-            g, _ = spmm_bwd(view, dAGG)
+            g, gh = spmm_bwd(view, dAGG, want_halo=True)
+            dH_halo[l] = store(gh)
+            if stale_grad is not None and stale_grad[l] is not None:
+                g = g + np.asarray(stale_grad[l], np.float64)
             g = store(g)
             dH_in[l] = g
-    return dict(AGG=AGG, Z=Z, H=H, loss=loss, dW=dW, dH_in=dH_in, dZ=dZ, dAGG=dAGGs)
+    return dict(AGG=AGG, Z=Z, H=H, loss=loss, dW=dW, dH_in=dH_in, dZ=dZ, dAGG=dAGGs,
+                dH_halo=dH_halo)
 
 
 def full_graph_gcn(N, g_rowptr, g_col, X, Ws):
@@ -402,6 +478,48 @@ def full_graph_gcn(N, g_rowptr, g_col, X, Ws):
         z = agg @ np.asarray(Ws[l], np.float64)
         H.append(np.maximum(z, 0.0) if l < L - 1 else z)
     return H
+
+
+def full_graph_backward(N, g_rowptr, g_col, X, Ws, y, part):
+    """Backward of the unpartitioned GCN for the loss sum over partitions m of
+    (mean cross-entropy over V_m): the appendix's G_H = P^T D W^T, G_W = (P H)^T D,
+    D = G_H o sigma'(Z), written on the global CSR. y: labels of all N nodes;
+    part: partition id of every node (it only sets each node's loss weight
+    1 / |V_part(v)|). Returns (G_H list indexed by layer, dW list)."""
+    isd = inv_sqrt_degree(np.diff(g_rowptr))
+    part = np.asarray(part)
+
+    def propagate(M):          # A_hat M (A_hat is symmetric, so this is also A_hat^T M)
+        out = np.zeros_like(M)
+        for i in range(N):
+            nb = g_col[g_rowptr[i]:g_rowptr[i + 1]]
+            w = (isd[i] * isd[nb]).astype(np.float64)
+            out[i] = w @ M[nb] + np.float64(isd[i] * isd[i]) * M[i]
+        return out
+
+    L = len(Ws)
+    H = [np.asarray(X, np.float64)]
+    PH, Z = [], []
+    for l in range(L):
+        a = propagate(H[l])
+        z = a @ np.asarray(Ws[l], np.float64)
+        PH.append(a)
+        Z.append(z)
+        H.append(np.maximum(z, 0.0) if l < L - 1 else z)
+    zmax = H[L].max(axis=1, keepdims=True)
+    p = np.exp(H[L] - zmax)
+    p /= p.sum(axis=1, keepdims=True)
+    p[np.arange(N), y] -= 1.0
+    sizes = np.bincount(part)
+    G = p / sizes[part][:, None]
+    G_H = [None] * (L + 1)
+    G_H[L] = G
+    dW = [None] * L
+    for l in range(L - 1, -1, -1):
+        D = G_H[l + 1] * (Z[l] > 0) if l < L - 1 else G_H[l + 1]
+        dW[l] = PH[l].T @ D
+        G_H[l] = propagate(D @ np.asarray(Ws[l], np.float64).T)
+    return G_H, dW
 
 
 def staleness(H_ref, H_approx):

@@ -47,6 +47,7 @@ _SIGNATURES = {
     "sat_partition_view_sizes": (_i32, [_i64, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
     "sat_partition_view_build": (_i32, [_i64, _vp, _vp, _vp, _vp, _i32] + [_vp] * 10),
     "sat_history_gather": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
+    "sat_history_gather_add": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_history_push": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_predict_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
     "sat_predict": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
@@ -163,6 +164,11 @@ def partition_view_build(N, g_rowptr, g_col, part, m, g_deg=None):
 def history_gather(table, n_rows, ld_table, ids, n, d, out, ld_out, dtype=F32, stream=None):
     _check(lib().sat_history_gather(_ptr(table), n_rows, ld_table, _ptr(ids), n, d, _ptr(out),
                                     ld_out, dtype, stream), "sat_history_gather")
+
+
+def history_gather_add(table, n_rows, ld_table, ids, n, d, out, ld_out, dtype=F32, stream=None):
+    _check(lib().sat_history_gather_add(_ptr(table), n_rows, ld_table, _ptr(ids), n, d, _ptr(out),
+                                        ld_out, dtype, stream), "sat_history_gather_add")
 
 
 def history_push(table, n_rows, ld_table, ids, n, d, H, ld_h, dtype=F32, stream=None):

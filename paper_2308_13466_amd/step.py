@@ -14,6 +14,11 @@ Order inside a step t (history ring of tau slots per hidden layer):
      layer's ring (it overwrites the oldest epoch);
   3. dH_L from the cross-entropy; for l = L-1..0: dW_l, dAGG_l; dH_l = P_in^T dAGG_l
      for l >= 1 (halo rows are constants of the step: no gradient for them).
+     With gradient tables (the second term of the appendix's SAT backward): also
+     dH_halo_l = P_out^T dAGG_l, pushed into the write table of the layer's gradient
+     ring for the owners of the halo nodes, and the rows the local nodes find in the
+     read table (written one step earlier by the partitions that hold them as halo
+     nodes) are added to dH_l.
 """
 import numpy as np
 import torch
@@ -39,10 +44,14 @@ class PartitionStep:
           history tables and Ws (dW, the loss and the predictor parameters are fp32).
     predictors: predictors[l] a binding.Predictor for l = 1..L-1 (None: bypass).
     y: device int32 [n_local] labels.
+    grad_tables: None, or grad_tables[l] for l = 1..L-1 a pair [table_a, table_b] of
+          device tables [n_rows_g, ld_l] (row of a node as in the history tables): step
+          t reads pair[t % 2] (stale term for the local rows) and writes pair[(t+1) % 2]
+          (this partition's term for its halo nodes).
     """
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
-                 fused_pull=True, timers=None, dtype=B.F32):
+                 fused_pull=True, timers=None, dtype=B.F32, grad_tables=None):
         dev = X_table.device
         self.dtype = dtype
         self.dims = list(dims)
@@ -61,6 +70,7 @@ class PartitionStep:
         self.local_table_ids = table_ids[:self.n_local]
         self.Ws, self.predictors, self.y = Ws, predictors, y
         self.fused_pull = fused_pull
+        self.grad_tables = grad_tables
         self.t = 0
         self.timers = timers
 
@@ -72,10 +82,14 @@ class PartitionStep:
         self.Hbar = [torch.zeros((n_bar, self.ld[l]), **act) for l in range(L)]
         self.logits = torch.zeros((n_l, self.ld[L]), **act)
         self.AGG = [torch.zeros((n_l, self.ld[l]), **act) for l in range(L)]
-        self.dH = [torch.zeros((n_l, self.ld[l]), **act) for l in range(L + 1)]
+        self.dH = [torch.zeros((n_l, self.ld[l]), **act) if l >= 1 else None for l in range(L + 1)]
         self.dAGG = [torch.zeros((n_l, self.ld[l]), **act) if l >= 1 else None for l in range(L)]
         self.ld_dw = [_ld(dims[l + 1], 4) for l in range(L)]
         self.dW = [torch.zeros((dims[l], self.ld_dw[l]), **f32) for l in range(L)]   # always fp32
+        self.dH_halo = [None] * L
+        if grad_tables is not None:
+            self.dH_halo = [torch.zeros((self.n_halo, self.ld[l]), **act) if l >= 1 else None
+                            for l in range(L)]
         self.loss = torch.zeros(1, **f32)
         ws_bytes = [B.loss_workspace_bytes(n_l)]
         ws_bytes += [B.dense_bwd_workspace_bytes(n_l, dims[l], dims[l + 1]) for l in range(L)]
@@ -161,13 +175,27 @@ class PartitionStep:
                 B.ACT_IDENTITY if last else B.ACT_RELU, self.dW[l], self.ld_dw[l],
                 self.dAGG[l], ld[l] if l >= 1 else 0, dtype=dt,
                 workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
-            if l >= 1:
+            if l >= 1 and self.grad_tables is None:
                 self._timed("spmm_bwd_l%d" % l, lambda: B.spmm_bwd(
                     self.pv, self.dAGG[l], ld[l], dims[l], self.dH[l], ld[l], dtype=dt, stream=st))
+            elif l >= 1:
+                rd, wr = self.grad_tables[l][self.t % 2], self.grad_tables[l][(self.t + 1) % 2]
+                self._timed("spmm_bwd_l%d" % l, lambda: B.spmm_bwd(
+                    self.pv, self.dAGG[l], ld[l], dims[l], self.dH[l], ld[l],
+                    dH_halo=self.dH_halo[l], ld_halo=ld[l], dtype=dt, stream=st))
+                if n_h > 0:
+                    self._timed("grad_push_l%d" % l, lambda: B.history_push(
+                        wr, wr.shape[0], wr.shape[1], self.halo_table_ids, n_h, dims[l],
+                        self.dH_halo[l], ld[l], dtype=dt, stream=st))
+                self._timed("grad_pull_l%d" % l, lambda: B.history_gather_add(
+                    rd, rd.shape[0], rd.shape[1], self.local_table_ids, n_l, dims[l],
+                    self.dH[l], ld[l], dtype=dt, stream=st))
         self.t += 1
 
     # ------------------------------------------------------------ accounting
     def edges_per_step(self):
         """CSR entries walked by the aggregation calls of one step: nnz per
-        forward layer plus the local-local entries per backward layer >= 1."""
-        return self.nnz * self.L + self.nnz_local * (self.L - 1)
+        forward layer plus the local-local entries per backward layer >= 1 (all
+        entries when the halo term of the backward is computed too)."""
+        bwd = self.nnz if self.grad_tables is not None else self.nnz_local
+        return self.nnz * self.L + bwd * (self.L - 1)

@@ -35,9 +35,11 @@ def _upload(a, bf16, dev):
 
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
-                   keep_host=True, device="cuda:0", dtype=None):
+                   keep_host=True, device="cuda:0", dtype=None, grad_tables=False):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
+    grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
+    of the history tables) and run the stale-gradient term of the backward.
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
     host copies kept for the tests hold the rounded values the device holds.
 
@@ -55,7 +57,11 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     L = len(dims) - 1
     ss = syn.substreams(cfg["seed"])
     t0 = time.time()
-    g = syn.cached_graph(cfg, ss["graph"])
+    device_inputs = bool(cfg.get("device_inputs"))
+    if device_inputs:     # too large to be worth a disk cache
+        g = syn.make_graph(cfg, np.random.Generator(np.random.PCG64(ss["graph"])))
+    else:
+        g = syn.cached_graph(cfg, ss["graph"])
     log("graph: N=%d nnz=%d (%.1fs)" % (g.N, g.nnz, time.time() - t0))
     wss = ss["weights"].spawn(L)
     Ws = [syn.glorot_uniform_f32(wss[l], dims[l], dims[l + 1]) for l in range(L)]
@@ -63,7 +69,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     omegas = [None] + [syn.predictor_params_f32(pss[l], dims[l], d_s) for l in range(1, L)]
 
     t0 = time.time()
-    view = B.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"])
+    view = B.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"], g_deg=g.deg)
     n_l, n_h = view["n_local"], view["n_halo"]
     log("partition view: n_local=%d n_halo=%d nnz=%d nnz_halo=%d max_deg=%d (%.1fs)" % (
         n_l, n_h, view["nnz"], view["nnz_halo"],
@@ -71,18 +77,36 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
 
     t0 = time.time()
     ld = [ld_of(d) for d in dims]
-    X_host = syn.normal_f32(ss["features"], g.N, dims[0], ld=ld[0])
-    X_d, X_host = _upload(X_host, bf16, dev)
+    n_bar = n_l + n_h
+    relabelled = cfg.get("tables") == "relabelled"
+    # table row of every local-then-halo node: its global id, or (tables = "relabelled":
+    # tables that hold the partition's local + halo rows only) its relabelled id
+    if relabelled:
+        table_ids = np.arange(n_bar, dtype=np.int32)
+        n_table = n_bar
+    else:
+        table_ids = np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32)
+        n_table = g.N
     hss = ss["history"].spawn(L)
     hist_d, hist_host = [None], [None]
-    for l in range(1, L):
-        slots = syn.history_standin_f32(hss[l], g.N, dims[l], tau, cfg["noise_std"], ld=ld[l])
-        up = [_upload(s, bf16, dev) for s in slots]
-        del slots
-        hist_d.append([u[0] for u in up])
-        hist_host.append([u[1] for u in up] if keep_host else None)
-        del up
-    table_ids = np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32)
+    if device_inputs:
+        # drawn on the device; tests read back the rows they need before the first step
+        seeds = np.random.Generator(np.random.PCG64(ss["features"])).integers(0, 2**31 - 1, size=L)
+        X_d, X_host = syn.device_normal(n_table, dims[0], ld[0], seeds[0], dev, bf16), None
+        for l in range(1, L):
+            hist_d.append(syn.device_history_standin(n_table, dims[l], ld[l], tau, cfg["noise_std"],
+                                                     seeds[l], dev, bf16))
+            hist_host.append(None)
+    else:
+        X_host = syn.normal_f32(ss["features"], n_table, dims[0], ld=ld[0])
+        X_d, X_host = _upload(X_host, bf16, dev)
+        for l in range(1, L):
+            slots = syn.history_standin_f32(hss[l], n_table, dims[l], tau, cfg["noise_std"], ld=ld[l])
+            up = [_upload(s, bf16, dev) for s in slots]
+            del slots
+            hist_d.append([u[0] for u in up])
+            hist_host.append([u[1] for u in up] if keep_host else None)
+            del up
     ids_d = torch.from_numpy(table_ids).to(dev)
     Ws_d = []
     for l in range(L):
@@ -99,8 +123,12 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
                                  bypass=bypass))
     y = syn.labels_i32(ss["labels"], n_l, dims[-1])
     y_d = torch.from_numpy(y).to(dev)
+    gt = None
+    if grad_tables:
+        gt = [None] + [[torch.zeros_like(hist_d[l][0]) for _ in range(2)] for l in range(1, L)]
     step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
-                         fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32)
+                         fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
+                         grad_tables=gt)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))

@@ -37,6 +37,20 @@ CONFIGS = {
         gamma=2.2, cut=0.20, dims=[128, 256, 256, 172], noise_std=0.05,
         tau=2, d_s=64, seed=0, dtype="bf16",
     ),
+    # ogbn-papers100M-shaped at full size: 111 M nodes, 8 partitions, only partition 0's
+    # rows are drawn (13.9 M local nodes, about 400 M CSR entries); no cut fraction is
+    # published for it, 10 % is assumed; history tables hold local + halo rows only
+    "scale": dict(
+        kind="chung_lu_rows", N=111_000_000, n_parts=8, part=0, mean_deg=29.0,
+        gamma=2.2, cut=0.10, dims=[128, 256, 256, 172], noise_std=0.05,
+        tau=2, d_s=64, seed=0, dtype="bf16", tables="relabelled", device_inputs=True,
+    ),
+    # the same recipe at 1/64 of the node count (CPU tests of the generator)
+    "scale_rows_small": dict(
+        kind="chung_lu_rows", N=1_734_375, n_parts=8, part=0, mean_deg=29.0,
+        gamma=2.2, cut=0.10, dims=[128, 256, 256, 172], noise_std=0.05,
+        tau=2, d_s=64, seed=0, dtype="bf16", tables="relabelled", device_inputs=True,
+    ),
 }
 
 

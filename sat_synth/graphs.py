@@ -19,6 +19,8 @@ class Graph:
     col: np.ndarray       # int32 [nnz], ascending within a row, no self-loops
     part: np.ndarray      # int32 [N], partition id of every node
     n_parts: int
+    deg: np.ndarray = None  # int32 [N] neighbour count of every node, when rowptr does not
+                            # hold every node's row (see chung_lu_partition_rows)
 
     @property
     def nnz(self):
@@ -159,6 +161,48 @@ def chung_lu_planted_graph(N, n_parts, mean_deg, gamma, cut, rng):
     return Graph(N, rowptr, col, part, n_parts)
 
 
+def chung_lu_partition_rows(N, n_parts, mean_deg, gamma, cut, rng):
+    """Rows of partition 0 only of a planted-partition power-law graph on N nodes.
+
+    For graphs whose other partitions nobody can afford to draw. Partition 0 is
+    the id range [0, N // n_parts). Its nodes get n_l * mean_deg * (1 - cut) / 2
+    undirected local-local edges (both endpoints ~ w inside the partition, so
+    the local block is symmetric) and n_l * mean_deg * cut cross entries (local
+    endpoint ~ w inside, outside endpoint ~ w over the other ids); loops and
+    duplicates are dropped. Rows of nodes outside the partition are left empty.
+    `deg` holds every node's neighbour count: the realised row length for the
+    partition's nodes; for an outside node the larger of its rounded expected
+    degree w and the number of entries it received from the partition.
+    """
+    part, pb = _contiguous_parts(N, n_parts)
+    n_l = int(pb[1])
+    w = _powerlaw_weights(N, mean_deg, gamma, rng)
+    n_ll = int(round(n_l * mean_deg * (1.0 - cut) / 2.0))
+    n_x = int(round(n_l * mean_deg * cut)) if n_parts > 1 else 0
+    u = _draw_weighted(0, n_l, w, n_ll, rng).astype(np.int32)
+    v = _draw_weighted(0, n_l, w, n_ll, rng).astype(np.int32)
+    keep = u != v
+    u, v = u[keep], v[keep]
+    xu = _draw_weighted(0, n_l, w, n_x, rng).astype(np.int32)
+    xv = _draw_weighted(n_l, N, w, n_x, rng).astype(np.int32)
+    rows = np.concatenate([u, v, xu])
+    cols = np.concatenate([v, u, xv])
+    del u, v, xu
+    m = sp.coo_matrix((np.ones(rows.shape[0], dtype=np.int8), (rows, cols)), shape=(n_l, N)).tocsr()
+    del rows, cols
+    m.sum_duplicates()
+    m.sort_indices()
+    rowptr = np.full(N + 1, m.indptr[-1], dtype=np.int64)
+    rowptr[:n_l + 1] = m.indptr
+    col = m.indices.astype(np.int32)
+    deg = np.rint(w).astype(np.int32)
+    deg[:n_l] = np.diff(m.indptr)
+    got = np.bincount(xv, minlength=N).astype(np.int32)   # upper bound on distinct entries received
+    np.maximum(deg[n_l:], got[n_l:], out=deg[n_l:])
+    np.maximum(deg[n_l:], 1, out=deg[n_l:])
+    return Graph(N, rowptr, col, part, n_parts, deg)
+
+
 def make_graph(cfg, rng):
     """Graph for one entry of configs.CONFIGS."""
     if cfg["kind"] == "sbm":
@@ -174,6 +218,9 @@ def make_graph(cfg, rng):
             cross = cfg["cut"] * cfg["mean_deg"] / share
             intra = cfg["mean_deg"] - cross
         return sbm_graph(cfg["N"], cfg["n_comm"], cfg["n_parts"], intra, cross, rng)
+    if cfg["kind"] == "chung_lu_rows":
+        return chung_lu_partition_rows(cfg["N"], cfg["n_parts"], cfg["mean_deg"], cfg["gamma"],
+                                       cfg["cut"], rng)
     if cfg["kind"] == "chung_lu":
         return chung_lu_planted_graph(cfg["N"], cfg["n_parts"], cfg["mean_deg"],
                                       cfg["gamma"], cfg["cut"], rng)
@@ -202,7 +249,8 @@ def cached_graph(cfg, seed_seq, cache_dir=None):
     if path and os.path.exists(path):
         try:
             z = np.load(path)
-            return Graph(int(z["N"]), z["rowptr"], z["col"], z["part"], int(z["n_parts"]))
+            return Graph(int(z["N"]), z["rowptr"], z["col"], z["part"], int(z["n_parts"]),
+                         z["deg"] if "deg" in z.files else None)
         except Exception:
             pass
     g = make_graph(cfg, np.random.Generator(np.random.PCG64(seed_seq)))
@@ -210,7 +258,8 @@ def cached_graph(cfg, seed_seq, cache_dir=None):
         try:
             os.makedirs(cache_dir, exist_ok=True)
             tmp = path + ".%d.tmp.npz" % os.getpid()
-            np.savez(tmp, N=g.N, rowptr=g.rowptr, col=g.col, part=g.part, n_parts=g.n_parts)
+            extra = {} if g.deg is None else {"deg": g.deg}
+            np.savez(tmp, N=g.N, rowptr=g.rowptr, col=g.col, part=g.part, n_parts=g.n_parts, **extra)
             os.replace(tmp, path)
         except OSError:
             pass

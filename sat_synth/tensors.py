@@ -115,3 +115,42 @@ def bf16_bits_from_f32(a):
 def f32_from_bf16_bits(b):
     """Exact fp32 value of every bfloat16 bit pattern in b (uint16)."""
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# ---- generators that fill device memory directly (inputs too large to draw on the host)
+
+def device_normal(rows, cols, ld, seed, device, bf16, std=1.0):
+    """[rows, ld] N(0, std^2) in the first `cols` columns (zeros in the padding), drawn
+    on `device` by torch's generator seeded with `seed`, 2^20 rows at a time.
+    Returns a torch tensor (float32 or bfloat16)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    out = torch.zeros((rows, ld), dtype=torch.bfloat16 if bf16 else torch.float32, device=device)
+    step = 1 << 20
+    for r0 in range(0, rows, step):
+        r1 = min(rows, r0 + step)
+        blk = torch.randn((r1 - r0, cols), generator=gen, device=device, dtype=torch.float32)
+        if std != 1.0:
+            blk *= std
+        out[r0:r1, :cols] = blk.to(out.dtype)
+    return out
+
+
+def device_history_standin(rows, cols, ld, tau, noise_std, seed, device, bf16):
+    """tau slots [rows, ld] of the stand-in of history_standin_f32 (shared base
+    max(0, N(0,1)) plus N(0, noise_std^2) per slot), drawn on the device. Oldest first."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    dt = torch.bfloat16 if bf16 else torch.float32
+    slots = [torch.zeros((rows, ld), dtype=dt, device=device) for _ in range(tau)]
+    step = 1 << 20
+    for r0 in range(0, rows, step):
+        r1 = min(rows, r0 + step)
+        base = torch.randn((r1 - r0, cols), generator=gen, device=device, dtype=torch.float32)
+        base.clamp_(min=0.0)
+        for s in range(tau):
+            noise = torch.randn((r1 - r0, cols), generator=gen, device=device, dtype=torch.float32)
+            slots[s][r0:r1, :cols] = (base + noise_std * noise).to(dt)
+    return slots

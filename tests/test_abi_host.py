@@ -111,6 +111,12 @@ def test_compute_calls_validate_before_launch(sat):
     assert L.sat_history_gather(None, 10, 8, None, 4, 8, None, 8, 7, None) == -1     # no such dtype
     assert L.sat_history_gather(None, 10, 8, None, 0, 8, None, 8, 0, None) == 0      # empty: no-op
     assert L.sat_history_push(None, 10, 4, None, 4, 8, None, 8, 0, None) == -1
+    assert L.sat_history_gather_add(None, 10, 8, None, 4, 8, None, 8, 0, None) == -1
+    assert L.sat_history_gather_add(None, 10, 8, None, 0, 8, None, 8, 1, None) == 0  # empty: no-op
+    # fake but non-null 16-byte aligned addresses: an ld that breaks the row alignment is
+    # refused on the host, before anything could dereference them
+    assert L.sat_history_gather_add(4096, 10, 9, 8192, 4, 8, 12288, 8, 0, None) == -3
+    assert L.sat_history_gather_add(4096, 10, 8, 8192, 4, 8, 12292, 8, 0, None) == -3
     assert L.sat_dense_fwd(None, 8, 4, 8, 8, None, 8, 1, 0, None, 8, None) == -1
     assert L.sat_dense_fwd(None, 8, 0, 8, 8, None, 8, 7, 0, None, 8, None) == -1     # bad act
     assert L.sat_spmm_fwd(None, None, 8, 8, 0, None, 8, None, 0, None) == -1

@@ -1,0 +1,147 @@
+"""Parity on the Scale recipe (papers100M-shaped, bf16 storage): only partition
+0's rows of the graph are drawn, explicit global degrees, history tables that
+hold the partition's local + halo rows (relabelled ids), features and history
+drawn on the device. `scale_rows_small` (1/64 of the node count) always runs;
+the full configuration (13.9 M local nodes, 412 M CSR entries, 195 GB of HBM,
+about 100 s) runs when the device has 230 GB free and the host 48 GB available
+(SAT_TEST_FULL_SCALE=0 switches it off).
+
+The oracle cannot loop over such a partition, so index arrays are compared in
+full where array operations give them (id lists, row offsets) and on sampled
+rows otherwise; numerical outputs on sampled rows computed one by one from
+inputs read back from the device BEFORE the step runs. Tolerance 2e-2 (bf16)."""
+import os
+import time
+
+import numpy as np
+import pytest
+
+import sat_synth as syn
+from oracle import sat_oracle as orc
+from tests.test_gpu_large import _say
+
+pytestmark = pytest.mark.gpu
+RTOL = 2e-2
+FULL = os.environ.get("SAT_TEST_FULL_SCALE", "1") != "0"
+
+
+def _mini_view(v, rows):
+    """Rows `rows` of the local CSR as a view of their own (columns renumbered to the
+    compact list of columns they touch), for the oracle's row-wise aggregation."""
+    segs = [(int(v["rowptr"][i]), int(v["rowptr"][i + 1])) for i in rows]
+    cols = np.concatenate([v["col"][s:e] for s, e in segs])
+    vals = np.concatenate([v["val"][s:e] for s, e in segs])
+    uniq, inv = np.unique(cols, return_inverse=True)
+    rowptr = np.concatenate([[0], np.cumsum([e - s for s, e in segs])]).astype(np.int64)
+    return dict(rowptr=rowptr, col=inv.astype(np.int32), val=vals), uniq.astype(np.int64)
+
+
+@pytest.mark.parametrize("name", ["scale_rows_small"] + (["scale"] if FULL else []))
+def test_scale_recipe_sampled_parity(name):
+    import torch
+    import paper_2308_13466_amd as sat
+    sat.lib()
+    from paper_2308_13466_amd.workload import build_workload
+    from tests import gpu_util as gu
+    if name == "scale":
+        import gc
+        import psutil
+        gc.collect()
+        torch.cuda.empty_cache()
+        free_dev = torch.cuda.mem_get_info()[0]
+        free_host = psutil.virtual_memory().available
+        _say("full Scale: %.0f GB free on the device, %.0f GB available on the host" % (
+            free_dev / 1e9, free_host / 1e9))
+        if free_dev < 230e9 or free_host < 48e9:
+            pytest.skip("the full Scale configuration needs 230 GB of free HBM and 48 GB of host memory")
+    t0 = time.time()
+    wl = build_workload(name, log=_say, keep_host=False)
+    _say("%s: workload built in %.0fs" % (name, time.time() - t0))
+    assert wl.dtype == "bf16"
+    g, v, step, dims = wl.graph, wl.view, wl.step, wl.dims
+    n_l, n_h = v["n_local"], v["n_halo"]
+    rng = np.random.default_rng(31)
+
+    # ---- index work: full id lists and offsets, sampled rows of the CSR and of the halo block
+    deg_rows = np.diff(v["rowptr"])
+    n_rows_s, n_halo_s = (200, 64) if name == "scale" else (400, 400)
+    rows = np.unique(np.concatenate([rng.choice(n_l, size=n_rows_s, replace=False),
+                                     np.argsort(deg_rows)[-4:], [0, n_l - 1]]))
+    halo_sample = np.unique(np.concatenate([rng.choice(n_h, size=n_halo_s, replace=False),
+                                            np.argsort(np.diff(v["h_colptr"]))[-4:], [0, n_h - 1]]))
+    t0 = time.time()
+    ref = orc.partition_view_sample(g.N, g.rowptr, g.col, g.part, wl.cfg["part"], rows, halo_sample,
+                                    g_deg=g.deg)
+    _say("oracle's sampled view in %.0fs" % (time.time() - t0))
+    for k in ("n_local", "n_halo", "nnz", "nnz_halo"):
+        assert v[k] == ref[k], k
+    for k in ("local_ids", "halo_ids", "rowptr", "h_colptr"):
+        assert np.array_equal(v[k], ref[k]), k
+    assert np.array_equal(v["h_self"].view(np.uint32), ref["h_self"].view(np.uint32))
+    for i in rows:
+        c, val, sp_off = ref["row_entries"][int(i)]
+        s, e = v["rowptr"][i], v["rowptr"][i + 1]
+        assert np.array_equal(v["col"][s:e], c) and v["split"][i] == s + sp_off
+        assert np.array_equal(v["val"][s:e].view(np.uint32), val.view(np.uint32))
+    for u in halo_sample:
+        r, val = ref["halo_entries"][int(u)]
+        s, e = v["h_colptr"][u], v["h_colptr"][u + 1]
+        assert np.array_equal(v["h_row"][s:e], r)
+        assert np.array_equal(v["h_val"][s:e].view(np.uint32), val.view(np.uint32))
+
+    # ---- inputs of the sampled outputs, read back before anything runs
+    def fetch(t, idx, d):
+        return t[torch.from_numpy(np.asarray(idx, dtype=np.int64)).to(gu.DEV)].float().cpu().numpy()[:, :d]
+
+    mini, cols0 = _mini_view(v, rows)
+    X_cols = fetch(step.X_table, wl.table_ids[cols0], dims[0])
+    cp = v["h_colptr"]
+    nbrs = [v["h_row"][cp[u]:cp[u + 1]] for u in halo_sample]
+    locs = np.unique(np.concatenate(nbrs))
+    node_ids = np.concatenate([locs, n_l + halo_sample])
+    order = step.slot_order()
+    wins = {l: [fetch(step.hist[l][s], wl.table_ids[node_ids], dims[l]) for s in order] for l in (1, 2)}
+    X_halo = fetch(step.X_table, wl.table_ids[n_l + halo_sample], dims[0])
+
+    step.forward_backward()
+    gu.sync()
+
+    def rows_of(t, idx, d):
+        return fetch(t, idx, d)
+
+    # pull of the static halo features: bit-exact
+    assert np.array_equal(rows_of(step.Hbar[0], n_l + halo_sample, dims[0]), X_halo)
+    # predicted halo rows of both hidden layers
+    pos = {int(r): k for k, r in enumerate(locs)}
+    sub = dict(n_local=len(locs), n_halo=len(halo_sample),
+               h_colptr=np.concatenate([[0], np.cumsum([len(x) for x in nbrs])]).astype(np.int64),
+               h_row=np.array([pos[int(r)] for x in nbrs for r in x], dtype=np.int32),
+               h_val=np.concatenate([v["h_val"][cp[u]:cp[u + 1]] for u in halo_sample]),
+               h_self=v["h_self"][halo_sample])
+    for l in (1, 2):
+        w = wl.omegas[l]
+        S = orc.lstm_last_hidden(wins[l], w["Wx"], w["Wh"], w["b"])
+        newest = wins[l][-1][len(locs):].astype(np.float64)
+        refp = orc.round_bf16(newest + orc.predictor_hop(sub, S, w["Wg"]))
+        gu.assert_close(rows_of(step.Hbar[l], n_l + halo_sample, dims[l]), refp, RTOL,
+                        "predicted halo rows, layer %d" % l)
+    # layer 0 aggregate and transform of the sampled rows
+    a0 = orc.round_bf16(orc.spmm_fwd_rows(mini, X_cols, np.arange(len(rows))))
+    gu.assert_close(rows_of(step.AGG[0], rows, dims[0]), a0, RTOL, "AGG_0 rows")
+    _, h1 = orc.dense_fwd(a0, wl.Ws[0], 1)
+    gu.assert_close(rows_of(step.Hbar[1], rows, dims[1]), orc.round_bf16(h1), RTOL, "H_1 rows")
+    # push: slot 0 of each ring holds the bits the forward stored (sampled rows)
+    for l in (1, 2):
+        a = step.hist[l][0][torch.from_numpy(wl.table_ids[rows].astype(np.int64)).to(gu.DEV), :dims[l]]
+        b = step.Hbar[l][torch.from_numpy(rows).to(gu.DEV), :dims[l]]
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    loss = float(step.loss.item())
+    assert np.isfinite(loss) and 0.5 * np.log(dims[-1]) < loss < 4 * np.log(dims[-1])
+    for l in range(3):
+        assert torch.isfinite(step.dW[l][:, :dims[l + 1]]).all()
+    _say("%s ok: n_local=%d n_halo=%d nnz=%d loss %.4f, %.1f GB on the device" % (
+        name, n_l, n_h, v["nnz"], loss, torch.cuda.memory_allocated() / 1e9))
+    del wl, step
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()

@@ -334,7 +334,11 @@ def test_halo_rows_change_the_loss_but_get_no_gradient():
     st = orc.partition_step(v, Xl, Xh, halo_hat, Ws, y)
     hh = [None, halo_hat[1] + 0.1, halo_hat[2]]
     assert abs(orc.partition_step(v, Xl, Xh, hh, Ws, y)["loss"] - st["loss"]) > 1e-6
-    assert set(st) >= {"dW", "dH_in"} and "dH_halo" not in st
+    # the step's own gradient stops at the local rows: dH_in is P_in^T dAGG alone; the
+    # halo term P_out^T dAGG is a separate output for the nodes' owners, used nowhere here
+    for l in (1, 2):
+        assert np.array_equal(st["dH_in"][l], orc.spmm_bwd(v, st["dAGG"][l])[0])
+        assert st["dH_halo"][l].shape == (v["n_halo"], st["dAGG"][l].shape[1])
 
 
 def test_one_layer_dW_equals_masked_full_graph_gradient():
@@ -476,3 +480,103 @@ def test_partition_step_store_hook_only_rounds_storage():
         assert np.array_equal(c["AGG"][l], orc.round_bf16(c["AGG"][l]))
         rel = np.linalg.norm(c["dW"][l] - a["dW"][l]) / np.linalg.norm(a["dW"][l])
         assert rel < 3e-2
+
+
+def test_partition_view_sample_agrees_with_the_full_view():
+    """The sampled form used for graphs too large for the per-node loops gives
+    the same id lists, offsets and entries as the full view (scattered and
+    contiguous partitions, explicit degrees)."""
+    rng = np.random.default_rng(5)
+    g = syn.make_graph(syn.get_config("tiny"), rng)
+    part_scattered = rng.integers(0, 3, size=g.N).astype(np.int32)
+    deg = (np.diff(g.rowptr) + rng.integers(0, 4, size=g.N)).astype(np.int32)
+    for part, m, gd in ((g.part, 1, None), (part_scattered, 2, deg)):
+        full = orc.partition_view(g.N, g.rowptr, g.col, part, m, g_deg=gd)
+        rows = rng.choice(full["n_local"], size=40, replace=False)
+        hs = rng.choice(full["n_halo"], size=40, replace=False)
+        smp = orc.partition_view_sample(g.N, g.rowptr, g.col, part, m, rows, hs, g_deg=gd)
+        for k in ("n_local", "n_halo", "nnz", "nnz_halo"):
+            assert smp[k] == full[k]
+        for k in ("local_ids", "halo_ids", "rowptr", "h_colptr"):
+            assert np.array_equal(smp[k], full[k]), k
+        assert np.array_equal(smp["h_self"].view(np.uint32), full["h_self"].view(np.uint32))
+        for i in rows:
+            c, v, sp_off = smp["row_entries"][int(i)]
+            s0, e0 = full["rowptr"][i], full["rowptr"][i + 1]
+            assert np.array_equal(c, full["col"][s0:e0])
+            assert np.array_equal(v.view(np.uint32), full["val"][s0:e0].view(np.uint32))
+            assert s0 + sp_off == full["split"][i]
+        for u in hs:
+            r, v = smp["halo_entries"][int(u)]
+            s0, e0 = full["h_colptr"][u], full["h_colptr"][u + 1]
+            assert np.array_equal(r, full["h_row"][s0:e0])
+            assert np.array_equal(v.view(np.uint32), full["h_val"][s0:e0].view(np.uint32))
+
+
+def test_partition_rows_generator_is_a_valid_partition_view_input():
+    """The partition-only generator: symmetric local block, no loops, ascending
+    duplicate-free rows, empty rows outside the partition, degrees >= what the
+    partition sees; and the oracle's view of it has P_in symmetric."""
+    cfg = syn.get_config("scale_rows_small")
+    cfg["N"] = 80_000
+    g = syn.make_graph(cfg, np.random.default_rng(1))
+    n_l = g.N // cfg["n_parts"]
+    assert g.deg is not None and np.all(np.diff(g.rowptr)[n_l:] == 0)
+    assert np.array_equal(g.deg[:n_l], np.diff(g.rowptr)[:n_l])
+    for i in (0, 1, n_l // 2, n_l - 1):
+        r = g.col[g.rowptr[i]:g.rowptr[i + 1]]
+        assert np.all(np.diff(r) > 0) and i not in r
+    v = orc.partition_view(g.N, g.rowptr, g.col, g.part, 0, g_deg=g.deg)
+    assert v["n_local"] == n_l and v["n_halo"] > 0
+    import scipy.sparse as sp
+    P = sp.csr_matrix((v["val"], v["col"], v["rowptr"]), shape=(n_l, n_l + v["n_halo"]))
+    P_in = P[:, :n_l]
+    assert abs(P_in - P_in.T).max() == 0
+    cross = g.col[g.col >= n_l]
+    assert np.all(g.deg[cross] >= 1)
+    frac = cross.size / g.nnz
+    assert 0.07 < frac < 0.13          # about the 10 % cut of the recipe
+
+
+def test_stale_gradient_term_completes_the_full_graph_backward():
+    """Appendix, SAT backward: G_H = P_in^T D W^T + P_out^T D~ W^T. With nothing stale
+    (true halo embeddings, the other partition's term taken from the same step) the
+    two partitions' backward passes, after exchanging their P_out^T terms, must give
+    the unpartitioned GCN's gradients: G_H^(1) row by row and dW summed over the
+    partitions. Dropping, transposing or mis-routing the second term breaks it."""
+    cfg = syn.get_config("tiny")
+    ss = syn.substreams(3)
+    g = syn.make_graph(cfg, np.random.default_rng(ss["graph"]))
+    dims = cfg["dims"]
+    X = syn.normal_f32(ss["features"], g.N, dims[0])
+    wss = ss["weights"].spawn(2)
+    Ws = [syn.glorot_uniform_f32(wss[l], dims[l], dims[l + 1]) for l in range(2)]
+    y_all = syn.labels_i32(ss["labels"], g.N, dims[-1])
+    Hfull = orc.full_graph_gcn(g.N, g.rowptr, g.col, X, Ws)
+    G_H, dW_full = orc.full_graph_backward(g.N, g.rowptr, g.col, X, Ws, y_all, g.part)
+    views = [orc.partition_view(g.N, g.rowptr, g.col, g.part, m) for m in (0, 1)]
+
+    def run(m, stale):
+        v = views[m]
+        return orc.partition_step(v, X[v["local_ids"]], X[v["halo_ids"]],
+                                  [None, Hfull[1][v["halo_ids"]]], Ws, y_all[v["local_ids"]],
+                                  stale_grad=stale)
+
+    first = [run(m, None) for m in (0, 1)]
+    second = []
+    for m in (0, 1):
+        v, other = views[m], views[1 - m]
+        # rows of this partition's local nodes in the other partition's halo gradient
+        recv = np.zeros((v["n_local"], dims[1]))
+        pos = np.searchsorted(v["local_ids"], other["halo_ids"])
+        recv[pos] = first[1 - m]["dH_halo"][1]
+        second.append(run(m, [None, recv]))
+        np.testing.assert_allclose(second[m]["dH_in"][1], G_H[1][v["local_ids"]], rtol=1e-9, atol=1e-12)
+        # without the second term the rows that have outside neighbours are wrong
+        touched = np.zeros(v["n_local"], bool)
+        touched[pos] = True
+        err = np.abs(first[m]["dH_in"][1] - G_H[1][v["local_ids"]]).max(axis=1)
+        assert err[touched].min() > 0 and err[~touched].max() < 1e-12
+    for l in range(2):
+        np.testing.assert_allclose(second[0]["dW"][l] + second[1]["dW"][l], dW_full[l],
+                                   rtol=1e-9, atol=1e-12)
