@@ -400,6 +400,81 @@ def predict(view, omega, slots, bypass=False):
 # --------------------------------------------------------------------------
 # Whole step of one partition (Alg. 1 inner body; Eq. 7; appendix fwd / bwd)
 # --------------------------------------------------------------------------
+def predictor_train_loss_and_grad(view, omega, slots, target, weight=None):
+    """Loss of the embedding predictor on this partition and its gradient (Eq. 11
+    restricted to one partition and one hidden layer; Eq. 12 through `weight`).
+
+    The partition knows this step's fresh embeddings only for its local nodes,
+    so that is where the predictor is supervised: for local node v
+        pred[v] = newest[v] + ( sum_u A_hat[v,u] S[u] ) Wg
+    with the sum over row v of [P_in | P_out] (self-loop, local and halo
+    neighbours: one GCN hop over the partition-plus-halo graph, the local-row
+    counterpart of predictor_hop) and S the LSTM state of every node of the
+    partition and its halo. target [n_local, d] holds the fresh embeddings (a
+    constant here). weight [n_local] (default all ones) selects / weights the
+    mini-batch:
+        loss = sum_v weight[v] |pred[v] - target[v]|^2 / (d * sum_v weight[v]).
+    Returns (loss, dict(Wx=, Wh=, b=, Wg=)) with the gradients, by
+    back-propagation through the hop and through the LSTM's tau steps.
+    """
+    Wx = np.asarray(omega["Wx"], np.float64)
+    Wh = np.asarray(omega["Wh"], np.float64)
+    b = np.asarray(omega["b"], np.float64)
+    Wg = np.asarray(omega["Wg"], np.float64)
+    d_s = Wh.shape[1]
+    n_local, n_halo = view["n_local"], view["n_halo"]
+    n_bar = n_local + n_halo
+    tau = len(slots)
+    xs = [np.asarray(x, np.float64) for x in slots]
+    target = np.asarray(target, np.float64)
+    d = target.shape[1]
+    w = np.ones(n_local) if weight is None else np.asarray(weight, np.float64)
+
+    # forward, keeping every step's gates
+    h = [np.zeros((n_bar, d_s))]
+    c = [np.zeros((n_bar, d_s))]
+    gi, gf, gg, go = [], [], [], []
+    for s in range(tau):
+        pre = xs[s] @ Wx.T + h[s] @ Wh.T + b
+        gi.append(_sigmoid(pre[:, 0 * d_s:1 * d_s]))
+        gf.append(_sigmoid(pre[:, 1 * d_s:2 * d_s]))
+        gg.append(np.tanh(pre[:, 2 * d_s:3 * d_s]))
+        go.append(_sigmoid(pre[:, 3 * d_s:4 * d_s]))
+        c.append(gf[s] * c[s] + gi[s] * gg[s])
+        h.append(go[s] * np.tanh(c[s + 1]))
+    S = h[tau]
+    agg = spmm_fwd(view, S)                              # [n_local, d_s]
+    pred = xs[-1][:n_local] + agg @ Wg
+    diff = pred - target
+    norm = d * w.sum()
+    loss = float((w[:, None] * diff * diff).sum() / norm)
+
+    # backward
+    dpred = 2.0 * w[:, None] * diff / norm
+    dWg = agg.T @ dpred
+    dagg = dpred @ Wg.T
+    dS_loc, dS_halo = spmm_bwd(view, dagg, want_halo=True)
+    dh = np.concatenate([dS_loc, dS_halo], axis=0)
+    dc = np.zeros((n_bar, d_s))
+    dWx = np.zeros_like(Wx)
+    dWh = np.zeros_like(Wh)
+    db = np.zeros_like(b)
+    for s in range(tau - 1, -1, -1):
+        tc = np.tanh(c[s + 1])
+        do = dh * tc
+        dc = dc + dh * go[s] * (1.0 - tc * tc)
+        da = np.concatenate([dc * gg[s] * gi[s] * (1.0 - gi[s]),          # i
+                             dc * c[s] * gf[s] * (1.0 - gf[s]),           # f
+                             dc * gi[s] * (1.0 - gg[s] * gg[s]),          # g
+                             do * go[s] * (1.0 - go[s])], axis=1)         # o
+        dWx += da.T @ xs[s]
+        dWh += da.T @ h[s]
+        db += da.sum(axis=0)
+        dh = da @ Wh
+        dc = dc * gf[s]
+    return loss, dict(Wx=dWx, Wh=dWh, b=db, Wg=dWg)
+
+
 def partition_step(view, X_local, X_halo, halo_hat, Ws, y, store=None, stale_grad=None):
     """Forward and backward of an L-layer GCN on one partition.
 

@@ -580,3 +580,71 @@ def test_stale_gradient_term_completes_the_full_graph_backward():
     for l in range(2):
         np.testing.assert_allclose(second[0]["dW"][l] + second[1]["dW"][l], dW_full[l],
                                    rtol=1e-9, atol=1e-12)
+
+
+# ---------------------------------------------------------------- predictor training (Eq. 11, 12)
+def _train_problem(seed=0, tau=3, d=6, d_s=4):
+    g = small_graph(seed=seed, N=70, n_parts=2)
+    v = orc.partition_view(g.N, g.rowptr, g.col, g.part, 0)
+    rng = np.random.default_rng(seed + 100)
+    n_bar = v["n_local"] + v["n_halo"]
+    omega = {k: a.astype(np.float64) for k, a in
+             syn.predictor_params_f32(np.random.SeedSequence(seed), d, d_s).items()}
+    slots = [rng.standard_normal((n_bar, d)) for _ in range(tau)]
+    target = rng.standard_normal((v["n_local"], d))
+    weight = rng.integers(0, 2, size=v["n_local"]).astype(np.float64)
+    return v, omega, slots, target, weight
+
+
+def test_predictor_training_gradients_by_finite_differences():
+    """Every parameter tensor of the predictor, tau = 1, 2, 3, with and without a
+    mini-batch mask: central differences of the loss itself."""
+    for tau in (1, 2, 3):
+        v, omega, slots, target, weight = _train_problem(seed=tau, tau=tau)
+        for wgt in (None, weight):
+            loss, grads = orc.predictor_train_loss_and_grad(v, omega, slots, target, wgt)
+            rng = np.random.default_rng(tau)
+            eps = 1e-6
+            for name in ("Wx", "Wh", "b", "Wg"):
+                if tau == 1 and name == "Wh":
+                    assert np.all(grads["Wh"] == 0)       # h_0 = 0: no recurrent term yet
+                    continue
+                for _ in range(6):
+                    idx = tuple(rng.integers(0, n) for n in omega[name].shape)
+                    op = {k: a.copy() for k, a in omega.items()}
+                    om = {k: a.copy() for k, a in omega.items()}
+                    op[name][idx] += eps
+                    om[name][idx] -= eps
+                    fd = (orc.predictor_train_loss_and_grad(v, op, slots, target, wgt)[0]
+                          - orc.predictor_train_loss_and_grad(v, om, slots, target, wgt)[0]) / (2 * eps)
+                    assert abs(fd - grads[name][idx]) <= 1e-9 + 2e-6 * abs(fd), (tau, name, idx)
+
+
+def test_predictor_training_special_cases():
+    v, omega, slots, target, weight = _train_problem(seed=7, tau=2)
+    n_l = v["n_local"]
+    # Wg = 0: the prediction is the newest cached embedding, the LSTM gets no gradient
+    o0 = dict(omega, Wg=np.zeros_like(omega["Wg"]))
+    loss, grads = orc.predictor_train_loss_and_grad(v, o0, slots, target)
+    assert abs(loss - np.mean((slots[-1][:n_l] - target) ** 2)) < 1e-14
+    assert np.all(grads["Wx"] == 0) and np.all(grads["Wh"] == 0) and np.all(grads["b"] == 0)
+    assert np.abs(grads["Wg"]).max() > 0
+    # the local-row hop is the same propagation as the halo-row hop of inference: a
+    # target equal to the prediction gives zero loss and zero gradients
+    S = orc.lstm_last_hidden(slots, omega["Wx"], omega["Wh"], omega["b"])
+    pred = slots[-1][:n_l] + orc.spmm_fwd(v, S) @ omega["Wg"]
+    loss, grads = orc.predictor_train_loss_and_grad(v, omega, slots, pred)
+    assert loss < 1e-28 and all(np.abs(gr).max() < 1e-13 for gr in grads.values())
+    # a 0/1 mask is the same as dropping the rows from the mean
+    loss_m, _ = orc.predictor_train_loss_and_grad(v, omega, slots, target, weight)
+    keep = weight > 0
+    assert abs(loss_m - np.mean(((pred - target) ** 2)[keep])) < 1e-12
+    # a few plain gradient steps lower the loss (Alg. 1, predictor update)
+    om = {k: a.copy() for k, a in omega.items()}
+    l0 = None
+    for it in range(5):
+        l, gr = orc.predictor_train_loss_and_grad(v, om, slots, target)
+        l0 = l if l0 is None else l0
+        for k in om:
+            om[k] -= 0.05 * gr[k]
+    assert orc.predictor_train_loss_and_grad(v, om, slots, target)[0] < l0
