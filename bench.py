@@ -88,6 +88,10 @@ def main():
     ap.add_argument("--unfused-pull", action="store_true",
                     help="assemble the predictor window with sat_history_gather first")
     ap.add_argument("--bypass", action="store_true", help="plain historical embeddings")
+    ap.add_argument("--predictor-train", action="store_true",
+                    help="after the timed steps also time one training step (loss, gradients, "
+                         "plain gradient update) of hidden layer 1's predictor; reported under "
+                         "\"predictor_train\", outside the step time (it runs every Delta T steps)")
     ap.add_argument("--stale-grad", action="store_true",
                     help="also run the stale-gradient term of the backward: halo output of the "
                          "transpose aggregation pushed to a gradient table, table rows of the "
@@ -225,6 +229,48 @@ def main():
     dominant = max(single, key=lambda k: roof_all[k]["ms_per_step"])
     roofline = dict(kernel=KERNEL_OF_CLASS.get(dominant, dominant), **roof_all[dominant])
 
+    # ---- optional: one training step of the predictor of hidden layer 1 (fp32 storage only)
+    ptrain = None
+    if args.predictor_train and not bf16 and not args.bypass and L >= 2:
+        from paper_2308_13466_amd import binding as B
+        l = 1
+        wsb = B.predictor_train_workspace_bytes(n_l, n_h, dims[l], d_s, tau)
+        ws = torch.empty((wsb + 3) // 4, dtype=torch.float32, device=dev)
+        pw = step.predictors[l]
+        keep_p = wl.device_keep[0][l - 1]
+        grads = {k: torch.empty_like(keep_p[k]) for k in ("Wx", "Wh", "b", "Wg")}
+        ploss = torch.zeros(1, dtype=torch.float32, device=dev)
+        slots = [step.hist[l][sidx] for sidx in step.slot_order()]
+        st_ptr = torch.cuda.current_stream().cuda_stream
+
+        def train_once():
+            B.predictor_grad(step.pv, pw, slots, slots[0].shape[0], slots[0].shape[1], step.table_ids,
+                             step.Hbar[l], step.ld[l], None, grads["Wx"], grads["Wh"], grads["b"],
+                             grads["Wg"], ploss, workspace=ws, workspace_bytes=wsb, stream=st_ptr)
+            for k in grads:
+                B.sgd_update(keep_p[k], grads[k], grads[k].numel(), 1e-3, stream=st_ptr)
+
+        train_once()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        e0.record()
+        for _ in range(reps):
+            train_once()
+        e1.record()
+        torch.cuda.synchronize()
+        t_ms = e0.elapsed_time(e1) / reps
+        fwd = 2.0 * n_bar * 4 * d_s * (tau * dims[l] + (tau - 1) * d_s) + 2.0 * nnz * d_s \
+            + 2.0 * n_l * d_s * dims[l]
+        bwd = 4.0 * n_l * d_s * dims[l] + 2.0 * nnz * d_s \
+            + 2.0 * n_bar * 4 * d_s * (tau * dims[l] + 2 * (tau - 1) * d_s)
+        ptrain = {"layer": l, "ms_per_training_step": round(t_ms, 4), "loss": round(float(ploss.item()), 6),
+                  "flops": fwd + bwd, "achieved_tflops": round((fwd + bwd) / (t_ms * 1e-3) / 1e12, 2),
+                  "workspace_gb": round(wsb / 1e9, 2),
+                  "batch": "all %d local nodes" % n_l}
+        log("predictor training step (layer %d): %.3f ms, loss %.6f" % (l, t_ms, ptrain["loss"]))
+        del ws
+
     # ---- CPU oracle on a bounded sample, rank 0, host cores
     cpu = None
     if not args.no_cpu_baseline and wl.X_host is None:
@@ -252,6 +298,7 @@ def main():
         "roofline": roofline,
         "roofline_all": roof_all,
         "cpu_baseline": cpu,
+        "predictor_train": ptrain,
         "loss": round(loss, 6),
     }
     print(json.dumps(out))

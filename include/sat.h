@@ -205,6 +205,35 @@ sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w, const vo
                        int64_t ld, int32_t dtype, void* workspace, int64_t workspace_bytes,
                        void* stream);
 
+/* ------- training of the embedding predictor (Eq. 11; mini-batches of Eq. 12; Alg. 1
+ * "embedding predictor update"). One hidden layer's predictor, one partition.
+ * The partition knows this step's fresh embeddings of its LOCAL nodes, so the
+ * predictor is supervised there: for local node v
+ *   pred[v] = newest cached embedding of v + (sum_u A_hat[v,u] S_u) Wg,
+ * the sum over row v of [P_in | P_out] (self-loop, local and halo neighbours), S as
+ * in sat_predict;
+ *   loss = sum_v weight[v] |pred[v] - target[v]|^2 / (d * sum_v weight[v]).
+ * slots / n_rows_slot / ld_slot / ids: as for sat_predict (the window the prediction
+ * was made from, i.e. the ring before this step's push). target: device
+ * [n_local, ld_target], the fresh embeddings (a constant of this call). weight:
+ * device float [n_local] or NULL (all ones); a 0/1 vector selects a mini-batch.
+ * Outputs (device, fp32, dense): dWx [4 d_s, d], dWh [4 d_s, d_s], db [4 d_s],
+ * dWg [d_s, d], loss [1]; all overwritten. Reductions run in a fixed order.
+ * fp32 storage only (SAT_BF16: SAT_EUNSUPPORTED); d_s = 32 or 64; d % 4 == 0.
+ * Workspace: sat_predictor_train_workspace_bytes(); 256-byte aligned.
+ */
+int64_t sat_predictor_train_workspace_bytes(int64_t n_local, int64_t n_halo, int32_t d,
+                                            int32_t d_s, int32_t tau);
+sat_status sat_predictor_grad(const sat_part_view* pv, const sat_predictor* w,
+                              const void* const* slots, int64_t n_rows_slot, int64_t ld_slot,
+                              const int32_t* ids, const void* target, int64_t ld_target,
+                              const float* weight, int32_t dtype, float* dWx, float* dWh, float* db,
+                              float* dWg, float* loss, void* workspace, int64_t workspace_bytes,
+                              void* stream);
+/* param[i] -= lr * grad[i] for i in [0, n): the plain gradient step of Alg. 1
+ * (theta with eta_1, omega with eta_2). Device pointers, fp32. */
+sat_status sat_sgd_update(float* param, const float* grad, int64_t n, float lr, void* stream);
+
 /* --------------- aggregation (appendix, SAT forward: P_in H_in + P_out H_out_hat)
  * AGG [n_local, ld_out] = [P_in | P_out] * Hbar [n_bar, ld_in], d columns.
  * AGG must not overlap Hbar.

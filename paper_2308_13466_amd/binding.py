@@ -51,6 +51,10 @@ _SIGNATURES = {
     "sat_history_push": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_predict_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
     "sat_predict": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
+    "sat_predictor_train_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
+    "sat_predictor_grad": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _vp, _i32, _vp, _vp,
+                                  _vp, _vp, _vp, _vp, _i64, _vp]),
+    "sat_sgd_update": (_i32, [_vp, _vp, _i64, C.c_float, _vp]),
     "sat_spmm_workspace_bytes": (_i64, [_vp, _i32]),
     "sat_spmm_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _i64, _vp]),
     "sat_spmm_bwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
@@ -190,6 +194,23 @@ def predict(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, dtype=F32, worksp
 
 def spmm_workspace_bytes(pv, d):
     return lib().sat_spmm_workspace_bytes(pv.ref, d)
+
+
+def predictor_train_workspace_bytes(n_local, n_halo, d, d_s, tau):
+    return lib().sat_predictor_train_workspace_bytes(n_local, n_halo, d, d_s, tau)
+
+
+def predictor_grad(pv, w, slots, n_rows_slot, ld_slot, ids, target, ld_target, weight, dWx, dWh,
+                   db, dWg, loss, dtype=F32, workspace=None, workspace_bytes=0, stream=None):
+    arr = (C.c_void_p * len(slots))(*[_ptr(s) for s in slots])
+    _check(lib().sat_predictor_grad(pv.ref, w.ref, C.addressof(arr), n_rows_slot, ld_slot, _ptr(ids),
+                                    _ptr(target), ld_target, _ptr(weight), dtype, _ptr(dWx),
+                                    _ptr(dWh), _ptr(db), _ptr(dWg), _ptr(loss), _ptr(workspace),
+                                    workspace_bytes, stream), "sat_predictor_grad")
+
+
+def sgd_update(param, grad, n, lr, stream=None):
+    _check(lib().sat_sgd_update(_ptr(param), _ptr(grad), n, lr, stream), "sat_sgd_update")
 
 
 def spmm_fwd(pv, Hbar, ld_in, d, AGG, ld_out, dtype=F32, workspace=None, workspace_bytes=0,

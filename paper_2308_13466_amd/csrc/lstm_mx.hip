@@ -70,7 +70,8 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
                                                       const uint16_t* __restrict__ WxP,
                                                       const uint16_t* __restrict__ WhP,
                                                       const float* __restrict__ bias,
-                                                      float* __restrict__ S) {
+                                                      float* __restrict__ S,
+                                                      float* __restrict__ save) {
   constexpr int NP = 3;
   constexpr int NT = 64 * WAVES;    // threads
   constexpr int WN = DS / 32;       // wavefronts along hidden units
@@ -284,13 +285,26 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
         const float gi = sigmoidf_(acc[rb][0][r] + b_i);
         const float gg = tanhf_(acc[rb][2][r] + b_g);
         const float go = sigmoidf_(acc[rb][3][r] + b_o);
+        float gf = 0.f;   // c_0 = 0: the forget gate does not matter at the first step
         if (s == 0) {
           cstate[rb][r] = gi * gg;
         } else {
-          const float gf = sigmoidf_(acc[rb][1][r] + b_f);
+          gf = sigmoidf_(acc[rb][1][r] + b_f);
           cstate[rb][r] = gf * cstate[rb][r] + gi * gg;
         }
         hval[rb][r] = go * tanhf_(cstate[rb][r]);
+        if (save != nullptr) {   // training: keep the step's gates, cell and hidden state
+          const int64_t node = node0 + 32 * (wm * RB + rb) + acc_row(r, lane);
+          if (node < n_nodes) {
+            float* rec = save + (static_cast<int64_t>(s) * n_nodes + node) * (6 * DS) + unit;
+            rec[0] = gi;
+            rec[DS] = gf;
+            rec[2 * DS] = gg;
+            rec[3 * DS] = go;
+            rec[4 * DS] = cstate[rb][r];
+            rec[5 * DS] = hval[rb][r];
+          }
+        }
       }
     if (s + 1 < tau) {
       __syncthreads();  // every wavefront has finished reading Hs for this step
@@ -334,10 +348,12 @@ int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
 // S [n_nodes, d_s] = last hidden state of the LSTM over the tau slots (elements of
 // es_x bytes: 4 fp32, 2 bf16; weights and S are fp32). ws points at
 // lstm_mx_workspace_bytes() bytes, 256-byte aligned. Only d_s = 32 and 64.
+// save (nullable): [tau][n_nodes][6 d_s] fp32, per step and node the activated gates
+// i, f, g, o, the cell state c and the hidden state h (what back-propagation needs).
 sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
-                          void* ws, hipStream_t st) {
+                          void* ws, hipStream_t st, float* save) {
   const int k_pad = static_cast<int>(round_up(d, 32));
   const int nb = 4 * d_s;
   uint16_t* WxP = static_cast<uint16_t*>(ws);
@@ -355,7 +371,7 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
   const dim3 grid(static_cast<unsigned>(blocks));
 #define SAT_LSTM_MX(DS, ESX, WAVES)                                                            \
   lstm_mx_kernel<DS, ESX, WAVES><<<grid, dim3(64 * WAVES), 0, st>>>(                           \
-      sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S)
+      sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S, save)
   if (d_s == 32 && es_x == 4) SAT_LSTM_MX(32, 4, 4);
   else if (d_s == 32) SAT_LSTM_MX(32, 2, 4);
   else if (es_x == 4) SAT_LSTM_MX(64, 4, 8);

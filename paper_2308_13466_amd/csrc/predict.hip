@@ -43,7 +43,7 @@ int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s);
 sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
-                          void* ws, hipStream_t st);
+                          void* ws, hipStream_t st, float* save = nullptr);
 }  // namespace sat
 
 namespace {
