@@ -41,9 +41,9 @@ MEASURED_TRAFFIC_BYTES = {      # profiles/large_step_hbm_traffic.md, average ov
 }
 
 
-KERNEL_OF_CLASS = {"spmm": "spmm_kernel", "gather": "row_copy_vec_kernel (gather)",
+KERNEL_OF_CLASS = {"spmm": "spmm_stream_kernel", "gather": "row_copy_vec_kernel (gather)",
                    "push": "row_copy_vec_kernel (scatter)", "dense_fwd": "mx::gemm_kernel",
-                   "loss": "xent_grad_kernel"}
+                   "loss": "xent_grad_kernel", "gather_add": "row_gather_add_kernel"}
 
 
 class CallTimers:
