@@ -13,6 +13,7 @@
 //             results are identical from run to run).
 // dZ = dH o [Hout > 0] is never written to memory: the mask is applied while the
 // operand tile is loaded.
+#include "dw_kernel.h"
 #include "mx_tile.h"
 #include "sat_internal.h"
 
@@ -53,23 +54,63 @@ struct SplitPlan {
   int64_t split_stride;  // floats per partial matrix
 };
 
-// How the reduction over the n rows of dW = AGG^T dZ is cut into blocks. Aims
-// at a few workgroups per compute unit while keeping every slice >= 8 K-steps.
+// How the reduction over the n rows of dW = AGG^T dZ is cut into node ranges: about one
+// workgroup per compute unit in total (a workgroup holds its whole output tile in
+// registers and fills a compute unit), every range a multiple of 32 nodes and at
+// least 256 nodes long.
 SplitPlan plan_dw(int64_t n, int32_t d_in, int32_t d_out) {
   SplitPlan p;
-  const int64_t tiles = ((d_in + BM - 1) / BM) * static_cast<int64_t>((d_out + BN - 1) / BN);
-  int64_t want = (1024 + tiles - 1) / tiles;
-  int64_t max_by_k = (n + 8 * BK - 1) / (8 * BK);
+  const int bmx = d_in <= 128 ? 128 : 256, bnx = d_out <= 128 ? 128 : 256;
+  const int64_t tiles = ((d_in + bmx - 1) / bmx) * static_cast<int64_t>((d_out + bnx - 1) / bnx);
+  int64_t want = (256 + tiles - 1) / tiles;
+  int64_t max_by_k = (n + 255) / 256;
   if (max_by_k < 1) max_by_k = 1;
   int64_t s = want < max_by_k ? want : max_by_k;
   if (s < 1) s = 1;
-  p.k_per_split = round_up((n + s - 1) / s, BK);
-  if (p.k_per_split < BK) p.k_per_split = BK;
+  p.k_per_split = round_up((n + s - 1) / s, 32);
+  if (p.k_per_split < 32) p.k_per_split = 32;
   p.splits = static_cast<int>((n + p.k_per_split - 1) / p.k_per_split);
   if (p.splits < 1) p.splits = 1;
   p.ld_part = round_up(d_out, 4);
   p.split_stride = static_cast<int64_t>(d_in) * p.ld_part;
   return p;
+}
+
+template <int ES, int MT, int NT, bool MASK>
+void launch_dw_one(const dim3 grid, const void* A, int64_t ld_a, int d_a, const void* B, int64_t ld_b,
+                   int d_b, const void* M, int64_t ld_m, int64_t n, const SplitPlan& p, float* part,
+                   hipStream_t s) {
+  constexpr int smem = sat::dw::smem_bytes<ES, MT, NT>();
+  static bool attr_set = false;   // dynamic LDS above 64 KB needs the opt-in once per kernel
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&sat::dw::dw_kernel<ES, MT, NT, MASK>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    attr_set = true;
+  }
+  sat::dw::dw_kernel<ES, MT, NT, MASK><<<grid, dim3(256), smem, s>>>(
+      A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p.k_per_split, part, p.ld_part, p.split_stride);
+}
+
+// part[z] = (rows of range z of A)^T (same rows of B, masked), z < p.splits
+template <int ES>
+sat_status launch_dw(const void* A, int64_t ld_a, int d_a, const void* B, int64_t ld_b, int d_b,
+                     const void* M, int64_t ld_m, int64_t n, const SplitPlan& p, float* part,
+                     hipStream_t s) {
+  const bool big_m = d_a > 128, big_n = d_b > 128;
+  const int bmx = big_m ? 256 : 128, bnx = big_n ? 256 : 128;
+  const dim3 grid(static_cast<unsigned>((d_a + bmx - 1) / bmx), static_cast<unsigned>((d_b + bnx - 1) / bnx),
+                  static_cast<unsigned>(p.splits));
+#define SAT_DW(MT, NT)                                                                          \
+  do {                                                                                          \
+    if (M) launch_dw_one<ES, MT, NT, true>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s); \
+    else launch_dw_one<ES, MT, NT, false>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s);  \
+  } while (0)
+  if (big_m && big_n) SAT_DW(4, 4);
+  else if (big_m) SAT_DW(4, 2);
+  else if (big_n) SAT_DW(2, 4);
+  else SAT_DW(2, 2);
+#undef SAT_DW
+  return sat::check_launch();
 }
 
 sat_status check_mat(const void* p, int64_t rows, int64_t cols, int64_t ld, int es = 4) {
@@ -106,21 +147,11 @@ sat_status run_bwd(const void* dH, int64_t ld_dh, const void* mask, int64_t ld_h
                    float* part, hipStream_t s) {
   sat_status st;
   const bool relu = mask != nullptr;
-  // dW = AGG^T dZ : M = d_in, N = d_out, K = n, split over blockIdx.z; fp32 out
+  // dW = AGG^T dZ : reduced over the n rows, node ranges over blockIdx.z; fp32 out
   {
     const SplitPlan p = plan_dw(n, d_in, d_out);
-    const dim3 grid(static_cast<unsigned>((d_in + BM - 1) / BM),
-                    static_cast<unsigned>((d_out + BN - 1) / BN), static_cast<unsigned>(p.splits));
-    const Operand a{AGG, ld_a, nullptr, 0};
-    const Operand b{dH, ld_dh, mask, ld_ho};
-    const EpiArgs ep{p.split_stride, nullptr, 0, nullptr, 0, 0};
-    if (relu)
-      gemm_kernel<ES, Layout::MNContig, false, Layout::MNContig, true, kStorePartial, 4>
-          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part, ep);
-    else
-      gemm_kernel<ES, Layout::MNContig, false, Layout::MNContig, false, kStorePartial, 4>
-          <<<grid, dim3(256), 0, s>>>(a, b, d_in, d_out, n, p.k_per_split, part, p.ld_part, ep);
-    if ((st = sat::check_launch()) != SAT_OK) return st;
+    if ((st = launch_dw<ES>(AGG, ld_a, d_in, dH, ld_dh, d_out, mask, ld_ho, n, p, part, s)) != SAT_OK)
+      return st;
     const int64_t total = static_cast<int64_t>(d_in) * d_out;
     reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(
         part, p.split_stride, p.splits, d_in, d_out, p.ld_part, dW, ld_dw);

@@ -93,42 +93,44 @@ __device__ __forceinline__ void split2(float x0, float x1, uint32_t (&out)[NP]) 
 //  KContig : v[i] = 4 consecutive k of row (t / 8 + 32 i), k = 4 (t % 8)
 //  MNContig: v[2g], v[2g+1] = 8 consecutive k of column mn = t % MN,
 //            k = 8 (t / MN + (256 / MN) g)            (needs MN >= 64)
+// load_tile only ISSUES the loads: nothing looks at the loaded values until
+// store_tile, so they stay in flight across the products of the previous step.
+// The relu mask (h, raw values of the mask matrix) and the zeroing of elements
+// past the end of K (kleft = valid elements from this thread's first k) are
+// therefore applied in store_tile.
 template <int MN>
 struct TileRegs {
   f32x4 v[MN / 32];
+  f32x4 h[MN / 32];
+  int kleft;
 };
 
 template <int MN, Layout L, bool MASK>
 __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_t mn_lim,
                                           int64_t k0, int64_t k_lim, TileRegs<MN>& r, int t) {
   if constexpr (L == Layout::KContig) {
+    const int64_t k = k0 + ((t & 7) << 2);
+    const int64_t left = k_lim - k;
+    r.kleft = left > 4 ? 4 : static_cast<int>(left);
 #pragma unroll
     for (int i = 0; i < MN / 32; ++i) {
-      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      f32x4 v = {0.f, 0.f, 0.f, 0.f}, h = {0.f, 0.f, 0.f, 0.f};
       const int64_t mn = mn0 + (t >> 3) + 32 * i;
-      const int64_t k = k0 + ((t & 7) << 2);
       if (mn < mn_lim && k < k_lim) {
         v = *reinterpret_cast<const f32x4*>(static_cast<const float*>(op.p) + mn * op.ld + k);
-        if constexpr (MASK) {
-          const f32x4 h = *reinterpret_cast<const f32x4*>(static_cast<const float*>(op.mask) + mn * op.ld_mask + k);
-          v.x = h.x > 0.f ? v.x : 0.f;
-          v.y = h.y > 0.f ? v.y : 0.f;
-          v.z = h.z > 0.f ? v.z : 0.f;
-          v.w = h.w > 0.f ? v.w : 0.f;
-        }
-        if (k + 3 >= k_lim) {
-          if (k + 1 >= k_lim) v.y = 0.f;
-          if (k + 2 >= k_lim) v.z = 0.f;
-          v.w = 0.f;
-        }
+        if constexpr (MASK)
+          h = *reinterpret_cast<const f32x4*>(static_cast<const float*>(op.mask) + mn * op.ld_mask + k);
       }
       r.v[i] = v;
+      if constexpr (MASK) r.h[i] = h;
     }
   } else {
+    static_assert(!MASK, "masked operands are row-major in k");
     static_assert(MN >= 64 && MN <= 256, "MNContig tiles are 64..256 wide");
     constexpr int KG = 256 / MN;  // k-groups of 8 covered by the thread index
     const int64_t mn = mn0 + (t % MN);
     const bool mn_ok = mn < mn_lim;
+    r.kleft = 4;
 #pragma unroll
     for (int g = 0; g < MN / 64; ++g) {
       const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
@@ -136,11 +138,7 @@ __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         float x = 0.f;
-        if (mn_ok && k8 + j < k_lim) {
-          x = static_cast<const float*>(op.p)[(k8 + j) * op.ld + mn];
-          if constexpr (MASK)
-            x = static_cast<const float*>(op.mask)[(k8 + j) * op.ld_mask + mn] > 0.f ? x : 0.f;
-        }
+        if (mn_ok && k8 + j < k_lim) x = static_cast<const float*>(op.p)[(k8 + j) * op.ld + mn];
         e[j] = x;
       }
       r.v[2 * g] = f32x4{e[0], e[1], e[2], e[3]};
@@ -149,16 +147,28 @@ __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_
   }
 }
 
-// Split the registers into NP bf16 pieces and write them to the staged tile at S
-// (piece p at S + p * piece_bytes<MN>()).
-template <int MN, Layout L, int NP>
+// Apply mask and K tail, split the registers into NP bf16 pieces and write them to
+// the staged tile at S (piece p at S + p * piece_bytes<MN>()).
+template <int MN, Layout L, int NP, bool MASK>
 __device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char* S, int t) {
   if constexpr (L == Layout::KContig) {
 #pragma unroll
     for (int i = 0; i < MN / 32; ++i) {
+      f32x4 v = r.v[i];
+      if constexpr (MASK) {
+        v.x = r.h[i].x > 0.f ? v.x : 0.f;
+        v.y = r.h[i].y > 0.f ? v.y : 0.f;
+        v.z = r.h[i].z > 0.f ? v.z : 0.f;
+        v.w = r.h[i].w > 0.f ? v.w : 0.f;
+      }
+      if (r.kleft < 4) {
+        if (r.kleft < 2) v.y = 0.f;
+        if (r.kleft < 3) v.z = 0.f;
+        v.w = 0.f;
+      }
       uint32_t lo[NP], hi[NP];
-      split2<NP>(r.v[i].x, r.v[i].y, lo);
-      split2<NP>(r.v[i].z, r.v[i].w, hi);
+      split2<NP>(v.x, v.y, lo);
+      split2<NP>(v.z, v.w, hi);
       unsigned char* s = S + swz((t >> 3) + 32 * i, (t & 7) >> 1) + ((t & 1) << 3);
 #pragma unroll
       for (int p = 0; p < NP; ++p)
@@ -189,6 +199,8 @@ __device__ __forceinline__ void store_tile(const TileRegs<MN>& r, unsigned char*
 template <int MN>
 struct TileRegsB {
   u32x4 v[MN / 64];
+  u32x4 h[MN / 64];   // raw mask chunks (MASK only)
+  int kleft;          // valid elements (<= 8) from this thread's first k
 };
 
 // bf16 value > 0: sign clear and not zero
@@ -200,39 +212,28 @@ __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int6
   const uint16_t* P = static_cast<const uint16_t*>(op.p);
   const uint16_t* Mk = static_cast<const uint16_t*>(op.mask);
   if constexpr (L == Layout::KContig) {
+    const int64_t k = k0 + ((t & 3) << 3);   // (t + 256 i) & 3 == t & 3
+    const int64_t left = k_lim - k;
+    r.kleft = left > 8 ? 8 : static_cast<int>(left);
 #pragma unroll
     for (int i = 0; i < MN / 64; ++i) {
       const int c = t + 256 * i;
       const int64_t mn = mn0 + (c >> 2);
-      const int64_t k = k0 + ((c & 3) << 3);
-      u32x4 v = {0u, 0u, 0u, 0u};
+      u32x4 v = {0u, 0u, 0u, 0u}, h = {0u, 0u, 0u, 0u};
       if (mn < mn_lim && k < k_lim) {
         v = *reinterpret_cast<const u32x4*>(P + mn * op.ld + k);
-        uint32_t w[4] = {v.x, v.y, v.z, v.w};
-        if constexpr (MASK) {
-          const u32x4 hv = *reinterpret_cast<const u32x4*>(Mk + mn * op.ld_mask + k);
-          const uint32_t h[4] = {hv.x, hv.y, hv.z, hv.w};
-#pragma unroll
-          for (int q = 0; q < 4; ++q)
-            w[q] &= (bf16_pos(h[q] & 0xffffu) ? 0xffffu : 0u) | (bf16_pos(h[q] >> 16) ? 0xffff0000u : 0u);
-        }
-        const int valid = static_cast<int>(k_lim - k);   // elements of this chunk inside K
-        if (valid < 8) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            if (2 * q >= valid) w[q] = 0u;
-            else if (2 * q + 1 >= valid) w[q] &= 0xffffu;
-          }
-        }
-        v = u32x4{w[0], w[1], w[2], w[3]};
+        if constexpr (MASK) h = *reinterpret_cast<const u32x4*>(Mk + mn * op.ld_mask + k);
       }
       r.v[i] = v;
+      if constexpr (MASK) r.h[i] = h;
     }
   } else {
+    static_assert(!MASK, "masked operands are row-major in k");
     static_assert(MN >= 64 && MN <= 256, "MNContig tiles are 64..256 wide");
     constexpr int KG = 256 / MN;
     const int64_t mn = mn0 + (t % MN);
     const bool mn_ok = mn < mn_lim;
+    r.kleft = 8;
 #pragma unroll
     for (int g = 0; g < MN / 64; ++g) {
       const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
@@ -240,10 +241,7 @@ __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int6
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         uint32_t x = 0u;
-        if (mn_ok && k8 + j < k_lim) {
-          x = P[(k8 + j) * op.ld + mn];
-          if constexpr (MASK) x = bf16_pos(Mk[(k8 + j) * op.ld_mask + mn]) ? x : 0u;
-        }
+        if (mn_ok && k8 + j < k_lim) x = P[(k8 + j) * op.ld + mn];
         e[j] = x;
       }
       r.v[g] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
@@ -251,13 +249,27 @@ __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int6
   }
 }
 
-template <int MN, Layout L>
+template <int MN, Layout L, bool MASK>
 __device__ __forceinline__ void store_tile_b(const TileRegsB<MN>& r, unsigned char* S, int t) {
   if constexpr (L == Layout::KContig) {
 #pragma unroll
     for (int i = 0; i < MN / 64; ++i) {
       const int c = t + 256 * i;
-      *reinterpret_cast<u32x4*>(S + swz(c >> 2, c & 3)) = r.v[i];
+      uint32_t w[4] = {r.v[i].x, r.v[i].y, r.v[i].z, r.v[i].w};
+      if constexpr (MASK) {
+        const uint32_t h[4] = {r.h[i].x, r.h[i].y, r.h[i].z, r.h[i].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          w[q] &= (bf16_pos(h[q] & 0xffffu) ? 0xffffu : 0u) | (bf16_pos(h[q] >> 16) ? 0xffff0000u : 0u);
+      }
+      if (r.kleft < 8) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (2 * q >= r.kleft) w[q] = 0u;
+          else if (2 * q + 1 >= r.kleft) w[q] &= 0xffffu;
+        }
+      }
+      *reinterpret_cast<u32x4*>(S + swz(c >> 2, c & 3)) = u32x4{w[0], w[1], w[2], w[3]};
     }
   } else {
     constexpr int KG = 256 / MN;
@@ -280,11 +292,11 @@ __device__ __forceinline__ void load_any(const Operand& op, int64_t mn0, int64_t
   if constexpr (ES == 4) load_tile<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t);
   else load_tile_b<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t);
 }
-template <int ES, int MN, Layout L>
+template <int ES, int MN, Layout L, bool MASK>
 __device__ __forceinline__ void store_any(const typename RegsOf<ES, MN>::type& r, unsigned char* S,
                                           int t) {
-  if constexpr (ES == 4) store_tile<MN, L, 3>(r, S, t);
-  else store_tile_b<MN, L>(r, S, t);
+  if constexpr (ES == 4) store_tile<MN, L, 3, MASK>(r, S, t);
+  else store_tile_b<MN, L, MASK>(r, S, t);
 }
 
 // 16-byte MFMA operand of `lane`: row (row0 + lane % 32), k = 16 kc + 8 (lane / 32) .. + 7
@@ -394,8 +406,8 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int6
   }
   for (int64_t k0 = k_begin; k0 < k_end; k0 += BK) {
     __syncthreads();
-    store_any<ESI, BM, LA>(ra, As, t);
-    store_any<ESI, BN, LB>(rb, Bs, t);
+    store_any<ESI, BM, LA, MASK_A>(ra, As, t);
+    store_any<ESI, BN, LB, MASK_B>(rb, Bs, t);
     __syncthreads();
     if (k0 + BK < k_end) {
       load_any<ESI, BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
