@@ -1,0 +1,184 @@
+// Second half of the predictor's hop (Eq. 7; Sec. "Embedding Predictor"):
+//   out[m, :] = add[row(m), :] + Agg[m, 0:DS) * Wg        Agg [M, DS], Wg [DS, d], fp32
+// i.e. the aggregated LSTM states times the hop's weight matrix plus the newest
+// cached embedding (the residual), written to the predicted rows.
+//
+// M is in the millions, DS is 32 or 64: two flops per 16 bytes moved, so this is a
+// streaming kernel and the products only have to stay out of the way. Layout of the
+// work, weights-stationary:
+//   * a workgroup has 8 wavefronts; wavefront w owns output columns [32 w, 32 w + 32)
+//     of a group of 256 and keeps ITS slice of Wg in registers for the whole
+//     workgroup, already split into the three bf16 pieces of the exact fp32 product
+//     (mx_tile.h) and already in MFMA operand order: 48 registers for DS = 64;
+//   * rows are streamed in tiles of 32: the tile of Agg (8 KiB) is read with one
+//     16-byte access per thread, split and staged in LDS (double-buffered, one
+//     barrier per tile); each wavefront multiplies it with its weight slice;
+//   * the product tile goes through LDS so that the residual rows (random rows of the
+//     history table, fetched through the id list) and the output rows move as 16-byte
+//     accesses, whole rows per 64 lanes; the residual rows are requested BEFORE the
+//     products of the tile and added after them, and the next tile of Agg is in flight
+//     meanwhile. Two workgroups fit a compute unit (registers capped at 128), which is
+//     what keeps enough bytes in flight.
+#include "mx_tile.h"
+#include "sat_internal.h"
+
+namespace {
+
+using namespace sat::mx;
+
+constexpr int kTilesPerBlock = 8;   // 32-row tiles per workgroup (256 rows)
+
+template <int DS>
+__global__ __launch_bounds__(512, 4) void hop_product_kernel(
+    const float* __restrict__ Agg, int64_t M, const float* __restrict__ Wg, int d,
+    const float* __restrict__ add, int64_t ld_add, const int32_t* __restrict__ add_ids,
+    int64_t add_base, int64_t add_rows, float* __restrict__ out, int64_t ld_out) {
+  constexpr int NP = 3;
+  constexpr int KC = DS / 16;                       // 16-wide k chunks
+  constexpr int NCH = DS / 32;                      // 32-wide staging chunks
+  constexpr int STAGE = NCH * tile_bytes<32, NP>(); // bytes of one staged Agg tile
+  constexpr int C_LDF = 256 + 4;                    // floats per staged output row
+  __shared__ __attribute__((aligned(16))) unsigned char As[2 * STAGE];
+  __shared__ __attribute__((aligned(16))) float Cs[32 * C_LDF];
+
+  const int t = threadIdx.x;
+  const int lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int col = blockIdx.y * 256 + 32 * wave + (lane & 31);
+  const bool col_ok = col < d;
+  const int64_t row_lo = static_cast<int64_t>(blockIdx.x) * (32 * kTilesPerBlock);
+
+  // ---- this wavefront's slice of Wg as MFMA B fragments: lane holds k = 16 kc + 8 (lane / 32)
+  // .. + 7 of column `col`, split into three pieces
+  bf16x8 bw[KC][NP];
+#pragma unroll
+  for (int kc = 0; kc < KC; ++kc) {
+    float e[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int k = 16 * kc + 8 * (lane >> 5) + j;
+      e[j] = col_ok ? Wg[static_cast<int64_t>(k) * d + col] : 0.f;
+    }
+    uint32_t q[4][NP];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) split2<NP>(e[2 * h], e[2 * h + 1], q[h]);
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      bw[kc][p] = __builtin_bit_cast(bf16x8, u32x4{q[0][p], q[1][p], q[2][p], q[3][p]});
+  }
+
+  // ---- Agg tile: 32 rows x DS floats = 8 DS 16-byte accesses, one per thread (t < 8 DS)
+  const int a_row = t / (DS / 4), a_k = (t % (DS / 4)) * 4;
+  const bool a_thread = t < 8 * DS;
+  auto load_a = [&](int64_t row0) {
+    u32x4 v = {0u, 0u, 0u, 0u};
+    const int64_t r = row0 + a_row;
+    if (a_thread && r < M) v = *reinterpret_cast<const u32x4*>(Agg + r * DS + a_k);
+    return v;
+  };
+  auto store_a = [&](const u32x4 v, int stage) {
+    if (!a_thread) return;
+    const f32x4 f = __builtin_bit_cast(f32x4, v);
+    uint32_t lo[NP], hi[NP];
+    split2<NP>(f.x, f.y, lo);
+    split2<NP>(f.z, f.w, hi);
+    const int kk = a_k & 31;
+    unsigned char* s = As + stage * STAGE + (a_k >> 5) * tile_bytes<32, NP>() + swz(a_row, kk >> 3) +
+                       (((kk >> 2) & 1) << 3);
+#pragma unroll
+    for (int p = 0; p < NP; ++p) *reinterpret_cast<u32x2*>(s + p * piece_bytes<32>()) = u32x2{lo[p], hi[p]};
+  };
+
+  u32x4 ra = load_a(row_lo);
+  store_a(ra, 0);
+  __syncthreads();
+  for (int it = 0; it < kTilesPerBlock; ++it) {
+    const int64_t row0 = row_lo + 32 * it;
+    if (row0 >= M) break;                        // uniform over the workgroup
+    const int stage = it & 1;
+    const bool more = it + 1 < kTilesPerBlock && row0 + 32 < M;
+    if (more) ra = load_a(row0 + 32);
+    // residual rows of this tile: requested now, used after the products. Thread t owns the
+    // 16-byte chunks c = t + 512 i of the 32 x 256 tile: row c / 64, columns 4 (c % 64) .. + 3.
+    f32x4 res[4];
+    bool ok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = t + 512 * i;
+      const int64_t r = row0 + (c >> 6);
+      const int cc = blockIdx.y * 256 + ((c & 63) << 2);
+      int64_t src = -1;
+      if (r < M && cc < d) {
+        src = add_ids ? static_cast<int64_t>(add_ids[r]) : add_base + r;
+        if (src < 0 || src >= add_rows) src = -1;    // bad id: the row is left alone
+      }
+      ok[i] = src >= 0;
+      res[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (ok[i]) res[i] = *reinterpret_cast<const f32x4*>(add + src * ld_add + cc);
+    }
+    f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    const unsigned char* S = As + stage * STAGE;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      bf16x8 a[NP];
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
+        a[p] = read_operand(S + (kc >> 1) * tile_bytes<32, NP>() + p * piece_bytes<32>(), 0, kc & 1, lane);
+#pragma unroll
+      for (int q = 0; q < n_products<NP>(); ++q)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[product_a<NP>(q)], bw[kc][product_b<NP>(q)], acc,
+                                                      0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Cs[acc_row(r, lane) * C_LDF + 32 * wave + (lane & 31)] = acc[r];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (!ok[i]) continue;
+      const int c = t + 512 * i;
+      const int64_t r = row0 + (c >> 6);
+      const int cc = blockIdx.y * 256 + ((c & 63) << 2);
+      const f32x4 v = *reinterpret_cast<const f32x4*>(&Cs[(c >> 6) * C_LDF + ((c & 63) << 2)]) + res[i];
+      float* y = out + r * ld_out + cc;
+      const int left = d - cc;
+      if (left >= 4) {
+        *reinterpret_cast<f32x4*>(y) = v;
+      } else {
+        y[0] = v.x;
+        if (left > 1) y[1] = v.y;
+        if (left > 2) y[2] = v.z;
+      }
+    }
+    if (more) store_a(ra, stage ^ 1);
+    __syncthreads();
+  }
+}
+
+}  // namespace
+
+namespace sat {
+
+// out[m, 0:d) = add[(add_ids ? add_ids[m] : add_base + m), 0:d) + Agg[m, 0:ds) Wg, m < M; rows
+// whose table row falls outside [0, add_rows) are not written. fp32 throughout; ds = 32 or 64.
+sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
+                              const float* add, int64_t ld_add, const int32_t* add_ids,
+                              int64_t add_base, int64_t add_rows, float* out, int64_t ld_out,
+                              hipStream_t st) {
+  if (M == 0 || d == 0) return SAT_OK;
+  const int64_t gx = (M + 32 * kTilesPerBlock - 1) / (32 * kTilesPerBlock);
+  if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
+  const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d + 255) / 256));
+  if (ds == 64)
+    hop_product_kernel<64><<<grid, dim3(512), 0, st>>>(Agg, M, Wg, d, add, ld_add, add_ids, add_base,
+                                                       add_rows, out, ld_out);
+  else if (ds == 32)
+    hop_product_kernel<32><<<grid, dim3(512), 0, st>>>(Agg, M, Wg, d, add, ld_add, add_ids, add_base,
+                                                       add_rows, out, ld_out);
+  else
+    return SAT_EUNSUPPORTED;
+  return sat::check_launch();
+}
+
+}  // namespace sat

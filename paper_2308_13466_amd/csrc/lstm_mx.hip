@@ -152,14 +152,10 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
 #pragma unroll
       for (int i = 0; i < XROWS; ++i) {
         u32x4 v = {0u, 0u, 0u, 0u};
-        if (live && arow[i] >= 0 && k < d) {
+        // only ISSUE the load here: anything that looks at v (the zeroing of elements past
+        // d is in store_x) would make the wavefront wait for HBM before its products
+        if (live && arow[i] >= 0 && k < d)
           v = *reinterpret_cast<const u32x4*>(xs + arow[i] * ld_slot + k);
-          if (k + 3 >= d) {
-            if (k + 1 >= d) v.y = 0u;
-            if (k + 2 >= d) v.z = 0u;
-            v.w = 0u;
-          }
-        }
         ra.v[i] = v;
       }
     } else {
@@ -175,14 +171,20 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
       }
     }
   };
-  auto store_x = [&](const XRegs& ra, unsigned char* dst) {
+  auto store_x = [&](const XRegs& ra, unsigned char* dst, int j) {   // j: the tile's stream index
+    const int kx = (j % nk) * BK + ((t & 7) << 2);   // fp32: first of this thread's 4 elements
 #pragma unroll
     for (int i = 0; i < XROWS; ++i) {
       const int q = t + NT * i;
       if constexpr (ESX == 4) {   // 4 floats -> 4 bf16 of each of the three pieces
         uint32_t lo[NP], hi[NP];
         // (cast the whole vector: a bit cast applied to one vector element reads element 0)
-        const f32x4 f = __builtin_bit_cast(f32x4, ra.v[i]);
+        f32x4 f = __builtin_bit_cast(f32x4, ra.v[i]);
+        if (kx + 3 >= d) {   // elements past d lie in the row's padding
+          if (kx + 1 >= d) f.y = 0.f;
+          if (kx + 2 >= d) f.z = 0.f;
+          f.w = 0.f;
+        }
         split2<NP>(f.x, f.y, lo);
         split2<NP>(f.z, f.w, hi);
         unsigned char* sdst = dst + swz(q >> 3, (q & 7) >> 1) + ((q & 1) << 3);
@@ -194,9 +196,11 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
       }
     }
   };
+  u32x4 rw[B_CHUNKS];
+  load_w(WxP, k_pad, 0, rw);
   XRegs ra0;
   load_x(0, ra0);
-  store_x(ra0, As);   // tile 0 -> half 0 of the double buffer
+  store_x(ra0, As, 0);   // tile 0 -> half 0 of the double buffer
   load_x(1, ra0);
 
   for (int s = 0; s < tau; ++s) {
@@ -218,7 +222,7 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
       constexpr int NQ = NPA == 3 ? 6 : 3;
 #pragma unroll
       for (int kc = 0; kc < BK / 16; ++kc) {
-        bf16x8 a[RB][NPA], b[4][NP];
+        bf16x8 a[RB][NPA];
 #pragma unroll
         for (int p = 0; p < NPA; ++p)
 #pragma unroll
@@ -227,23 +231,31 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
                           : *reinterpret_cast<const bf16x8*>(
                                 Hs + p * H_PIECE_B + (32 * (wm * RB + rb) + c) * H_ROW_B +
                                 32 * (a_kc0 + kc) + 16 * (lane >> 5));
+        // two gates at a time: their weight fragments are all that is held besides a
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
+        for (int gp = 0; gp < 2; ++gp) {
+          bf16x8 b[2][NP];
 #pragma unroll
-          for (int g = 0; g < 4; ++g)
-            b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), g * DS + 32 * wn, kc, lane);
+          for (int p = 0; p < NP; ++p)
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-          const int pa = NPA == 3 ? product_a<3>(q) : 0;
-          const int pb = NPA == 3 ? product_b<3>(q) : 2 - q;
+            for (int g = 0; g < 2; ++g)
+              b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), (2 * gp + g) * DS + 32 * wn, kc, lane);
 #pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
+          for (int q = 0; q < NQ; ++q) {
+            const int pa = NPA == 3 ? product_a<3>(q) : 0;
+            const int pb = NPA == 3 ? product_b<3>(q) : 2 - q;
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              if (s == 0 && g == 1) continue;  // c_0 = 0: the forget gate is not needed yet
-              acc[rb][g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[rb][pa], b[g][pb], acc[rb][g],
-                                                                   0, 0, 0);
-            }
+            for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+              for (int g = 0; g < 2; ++g) {
+                // c_0 = 0: the forget gate is not needed at the first step. (A run-time test on
+                // purpose: as a compile-time switch it removes the branches between the
+                // products, and the scheduler then hoists operand reads until it spills.)
+                if (s == 0 && 2 * gp + g == 1) continue;
+                acc[rb][2 * gp + g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    a[rb][pa], b[g][pb], acc[rb][2 * gp + g], 0, 0, 0);
+              }
+          }
         }
       }
     };
@@ -253,22 +265,24 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
     // from HBM through the id list (the slowest loads of the kernel), so they get
     // two product phases to arrive: while tile j is multiplied out of one half of
     // the LDS double buffer, tile j+1 already sits in the other half and tile j+2
-    // is in flight in registers. Weight tiles (L2) are one step ahead in registers.
-    u32x4 rw[B_CHUNKS];
-    load_w(WxP, k_pad, 0, rw);
+    // is in flight in registers. Weight tiles (L2) form one stream too (per time step
+    // the nk tiles of Wx, then from the second step on the tiles of Wh) and are always
+    // one tile ahead in registers, across the phase boundary as well (not across the cell
+    // update: the registers are needed there).
+    if (s > 0) load_w(WxP, k_pad, 0, rw);
     for (int i = 0; i < nk; ++i) {
       const int j = s * nk + i;
       __syncthreads();
       store_w(rw);
-      store_x(ra0, As + ((j + 1) & 1) * tile_bytes<R, NP>());
+      store_x(ra0, As + ((j + 1) & 1) * tile_bytes<R, NP>(), j + 1);
       __syncthreads();
       load_x(j + 2, ra0);
       if (i + 1 < nk) load_w(WxP, k_pad, (i + 1) * BK, rw);
+      else if (s > 0) load_w(WhP, DS, 0, rw);
       products(std::integral_constant<int, ESX == 4 ? 3 : 1>{}, As + (j & 1) * tile_bytes<R, NP>(), 0);
     }
     // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
     if (s > 0) {
-      load_w(WhP, DS, 0, rw);
       for (int k0 = 0; k0 < DS; k0 += BK) {
         __syncthreads();
         store_w(rw);

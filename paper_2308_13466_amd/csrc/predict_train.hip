@@ -40,6 +40,10 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
                           void* ws, hipStream_t st, float* save);
+sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
+                              const float* add, int64_t ld_add, const int32_t* add_ids,
+                              int64_t add_base, int64_t add_rows, float* out, int64_t ld_out,
+                              hipStream_t st);
 }  // namespace sat
 
 namespace {
@@ -282,16 +286,9 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
   rc = sat::launch_spmm(pv->rowptr, nullptr, pv->col, pv->val, S, ds, n_bar, aggS, ds, n_l, ds, 4,
                         nullptr, 0, pv->nnz, st);
   if (rc != SAT_OK) return rc;
-  {
-    using namespace sat::mx;
-    const dim3 grid(static_cast<unsigned>((n_l + BM - 1) / BM), static_cast<unsigned>((d + BN - 1) / BN), 1);
-    const Operand a{aggS, static_cast<int64_t>(ds), nullptr, 0};
-    const Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
-    const EpiArgs ep{0, slots[tau - 1], ld_slot, ids, 0, n_rows_slot};
-    gemm_kernel<4, Layout::KContig, false, Layout::MNContig, false, kStoreAddRows, 4>
-        <<<grid, dim3(256), 0, st>>>(a, b, n_l, d, ds, ds, pred, d, ep);
-    if ((rc = sat::check_launch()) != SAT_OK) return rc;
-  }
+  rc = sat::launch_hop_product(aggS, n_l, ds, w->Wg, d, static_cast<const float*>(slots[tau - 1]), ld_slot,
+                               ids, 0, n_rows_slot, pred, d, st);
+  if (rc != SAT_OK) return rc;
   const float* wsum_dev = nullptr;
   if (weight) {
     weight_sum_kernel<<<dim3(kRedBlocks), dim3(256), 0, st>>>(weight, n_l, part);
