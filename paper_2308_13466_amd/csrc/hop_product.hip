@@ -28,11 +28,13 @@ using namespace sat::mx;
 
 constexpr int kTilesPerBlock = 8;   // 32-row tiles per workgroup (256 rows)
 
-template <int DS>
+// ESO = bytes per element of the residual rows and of the output (4: fp32, 2: bf16, the
+// sum rounded to nearest-even once); Agg and Wg are fp32 either way.
+template <int DS, int ESO>
 __global__ __launch_bounds__(512, 4) void hop_product_kernel(
     const float* __restrict__ Agg, int64_t M, const float* __restrict__ Wg, int d,
-    const float* __restrict__ add, int64_t ld_add, const int32_t* __restrict__ add_ids,
-    int64_t add_base, int64_t add_rows, float* __restrict__ out, int64_t ld_out) {
+    const void* __restrict__ add, int64_t ld_add, const int32_t* __restrict__ add_ids,
+    int64_t add_base, int64_t add_rows, void* __restrict__ out, int64_t ld_out) {
   constexpr int NP = 3;
   constexpr int KC = DS / 16;                       // 16-wide k chunks
   constexpr int NCH = DS / 32;                      // 32-wide staging chunks
@@ -114,7 +116,18 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
       }
       ok[i] = src >= 0;
       res[i] = f32x4{0.f, 0.f, 0.f, 0.f};
-      if (ok[i]) res[i] = *reinterpret_cast<const f32x4*>(add + src * ld_add + cc);
+      if (ok[i]) {
+        if constexpr (ESO == 4) {
+          res[i] = *reinterpret_cast<const f32x4*>(static_cast<const float*>(add) + src * ld_add + cc);
+        } else {   // four bf16: kept raw in the first two lanes of res until they are added
+          const u32x2 w = *reinterpret_cast<const u32x2*>(static_cast<const uint16_t*>(add) +
+                                                          src * ld_add + cc);
+          // (scalars first: a bit cast applied directly to a vector element reads element 0)
+          const uint32_t wx = w.x, wy = w.y;
+          res[i].x = __builtin_bit_cast(float, wx);
+          res[i].y = __builtin_bit_cast(float, wy);
+        }
+      }
     }
     f32x16 acc;
 #pragma unroll
@@ -140,15 +153,34 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
       const int c = t + 512 * i;
       const int64_t r = row0 + (c >> 6);
       const int cc = blockIdx.y * 256 + ((c & 63) << 2);
-      const f32x4 v = *reinterpret_cast<const f32x4*>(&Cs[(c >> 6) * C_LDF + ((c & 63) << 2)]) + res[i];
-      float* y = out + r * ld_out + cc;
+      f32x4 v = *reinterpret_cast<const f32x4*>(&Cs[(c >> 6) * C_LDF + ((c & 63) << 2)]);
       const int left = d - cc;
-      if (left >= 4) {
-        *reinterpret_cast<f32x4*>(y) = v;
+      if constexpr (ESO == 4) {
+        v += res[i];
+        float* y = static_cast<float*>(out) + r * ld_out + cc;
+        if (left >= 4) {
+          *reinterpret_cast<f32x4*>(y) = v;
+        } else {
+          y[0] = v.x;
+          if (left > 1) y[1] = v.y;
+          if (left > 2) y[2] = v.z;
+        }
       } else {
-        y[0] = v.x;
-        if (left > 1) y[1] = v.y;
-        if (left > 2) y[2] = v.z;
+        const float rx = res[i].x, ry = res[i].y;
+        const uint32_t w0 = __builtin_bit_cast(uint32_t, rx), w1 = __builtin_bit_cast(uint32_t, ry);
+        v.x += low_as_f32(w0);
+        v.y += high_as_f32(w0);
+        v.z += low_as_f32(w1);
+        v.w += high_as_f32(w1);
+        const u32x2 w = {pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
+        uint16_t* y = static_cast<uint16_t*>(out) + r * ld_out + cc;
+        if (left >= 4) {
+          *reinterpret_cast<u32x2*>(y) = w;
+        } else {
+          y[0] = static_cast<uint16_t>(w.x & 0xffffu);
+          if (left > 1) y[1] = static_cast<uint16_t>(w.x >> 16);
+          if (left > 2) y[2] = static_cast<uint16_t>(w.y & 0xffffu);
+        }
       }
     }
     if (more) store_a(ra, stage ^ 1);
@@ -161,23 +193,25 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
 namespace sat {
 
 // out[m, 0:d) = add[(add_ids ? add_ids[m] : add_base + m), 0:d) + Agg[m, 0:ds) Wg, m < M; rows
-// whose table row falls outside [0, add_rows) are not written. fp32 throughout; ds = 32 or 64.
+// whose table row falls outside [0, add_rows) are not written. Agg and Wg fp32; add and out
+// elements of eso bytes (4 fp32, 2 bf16), ld in elements; ds = 32 or 64.
 sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
-                              const float* add, int64_t ld_add, const int32_t* add_ids,
-                              int64_t add_base, int64_t add_rows, float* out, int64_t ld_out,
+                              const void* add, int64_t ld_add, const int32_t* add_ids,
+                              int64_t add_base, int64_t add_rows, void* out, int64_t ld_out, int eso,
                               hipStream_t st) {
   if (M == 0 || d == 0) return SAT_OK;
   const int64_t gx = (M + 32 * kTilesPerBlock - 1) / (32 * kTilesPerBlock);
   if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
+  if ((ds != 32 && ds != 64) || (eso != 2 && eso != 4)) return SAT_EUNSUPPORTED;
   const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d + 255) / 256));
-  if (ds == 64)
-    hop_product_kernel<64><<<grid, dim3(512), 0, st>>>(Agg, M, Wg, d, add, ld_add, add_ids, add_base,
-                                                       add_rows, out, ld_out);
-  else if (ds == 32)
-    hop_product_kernel<32><<<grid, dim3(512), 0, st>>>(Agg, M, Wg, d, add, ld_add, add_ids, add_base,
-                                                       add_rows, out, ld_out);
-  else
-    return SAT_EUNSUPPORTED;
+#define SAT_HOP(DS, ESO)                                                                          \
+  hop_product_kernel<DS, ESO><<<grid, dim3(512), 0, st>>>(Agg, M, Wg, d, add, ld_add, add_ids,      \
+                                                          add_base, add_rows, out, ld_out)
+  if (ds == 64 && eso == 4) SAT_HOP(64, 4);
+  else if (ds == 64) SAT_HOP(64, 2);
+  else if (eso == 4) SAT_HOP(32, 4);
+  else SAT_HOP(32, 2);
+#undef SAT_HOP
   return sat::check_launch();
 }
 

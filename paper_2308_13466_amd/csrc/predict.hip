@@ -46,8 +46,8 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
                           void* ws, hipStream_t st, float* save = nullptr);
 // hop_product.hip: out[m] = add[row(m)] + Agg[m] Wg, fp32, weights-stationary streaming kernel
 sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
-                              const float* add, int64_t ld_add, const int32_t* add_ids,
-                              int64_t add_base, int64_t add_rows, float* out, int64_t ld_out,
+                              const void* add, int64_t ld_add, const int32_t* add_ids,
+                              int64_t add_base, int64_t add_rows, void* out, int64_t ld_out, int eso,
                               hipStream_t st);
 }  // namespace sat
 
@@ -339,10 +339,10 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
     const sat::mx::Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
     const sat::mx::EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
                               n_rows_slot};
-    if (es == 4 && w->d_s <= 64)
-      return sat::launch_hop_product(Agg, pv->n_halo, w->d_s, w->Wg, d, static_cast<const float*>(newest),
-                                     ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
-                                     n_rows_slot, static_cast<float*>(halo_out), ld, st);
+    if (w->d_s <= 64)
+      return sat::launch_hop_product(Agg, pv->n_halo, w->d_s, w->Wg, d, newest, ld_slot,
+                                     ids ? ids + pv->n_local : nullptr, pv->n_local, n_rows_slot,
+                                     halo_out, ld, es, st);
     if (es == 4)
       sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
                            sat::mx::kStoreAddRows, 4>

@@ -41,8 +41,8 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
                           void* ws, hipStream_t st, float* save);
 sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
-                              const float* add, int64_t ld_add, const int32_t* add_ids,
-                              int64_t add_base, int64_t add_rows, float* out, int64_t ld_out,
+                              const void* add, int64_t ld_add, const int32_t* add_ids,
+                              int64_t add_base, int64_t add_rows, void* out, int64_t ld_out, int eso,
                               hipStream_t st);
 }  // namespace sat
 
@@ -286,8 +286,8 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
   rc = sat::launch_spmm(pv->rowptr, nullptr, pv->col, pv->val, S, ds, n_bar, aggS, ds, n_l, ds, 4,
                         nullptr, 0, pv->nnz, st);
   if (rc != SAT_OK) return rc;
-  rc = sat::launch_hop_product(aggS, n_l, ds, w->Wg, d, static_cast<const float*>(slots[tau - 1]), ld_slot,
-                               ids, 0, n_rows_slot, pred, d, st);
+  rc = sat::launch_hop_product(aggS, n_l, ds, w->Wg, d, slots[tau - 1], ld_slot, ids, 0, n_rows_slot,
+                               pred, d, 4, st);
   if (rc != SAT_OK) return rc;
   const float* wsum_dev = nullptr;
   if (weight) {
