@@ -35,8 +35,8 @@ MEASURED_TRAFFIC_BYTES = {      # profiles/large_step_hbm_traffic.md, average ov
     ("large", "gather"): 1.064e9,
     ("large", "push"): 0.627e9,
     ("large", "dense_fwd"): 0.640e9,
-    ("large", "dense_bwd"): 1.83e9,   # call level: dW product + its reduction + dAGG product
-    ("large", "predict"): 8.49e9,     # call level: LSTM 4.36 + hop aggregation 1.24 + hop product 2.88
+    ("large", "dense_bwd"): 1.44e9,   # call level: weight-gradient product + its reduction + dAGG product
+    ("large", "predict"): 7.68e9,     # call level: LSTM 3.52 + hop aggregation 1.24 + hop product 2.91
     ("large", "loss"): 0.136e9,
 }
 
