@@ -597,6 +597,71 @@ def full_graph_backward(N, g_rowptr, g_col, X, Ws, y, part):
     return G_H, dW
 
 
+# --------------------------------------------------------------------------
+# Compression of stored embeddings (Sec. "Data Compression for Historical
+# Embedding Storage"): decimal rounding + the published Encoded Polyline
+# Algorithm Format's variable-length character coding, every value on its own.
+# --------------------------------------------------------------------------
+
+def polyline_quantise(H, precision, arith=np.float32):
+    """q = floor(v * 10^precision + 1/2) per element, as int64. `arith` is the
+    floating type the three operations run in: float32 is what the GPU path uses
+    (the quantised code is an integer decision, so both sides take it in that
+    precision); float64 serves the published worked examples."""
+    v = np.asarray(H).astype(arith)
+    scale = arith(10.0) ** arith(precision) if arith is np.float64 else np.float32(10.0 ** precision)
+    return np.floor(v * scale + arith(0.5)).astype(np.int64)
+
+
+def polyline_encode_value(q):
+    """Bytes of one signed integer: shift left one bit, invert all bits if the
+    value is negative, cut into 5-bit groups from the low end, set bit 0x20 on
+    every group that has a successor, add 63 to each group."""
+    u = (int(q) << 1) ^ (-1 if q < 0 else 0)          # ~(q << 1) for negative q
+    out = bytearray()
+    while True:
+        chunk = u & 0x1F
+        u >>= 5
+        if u:
+            out.append((chunk | 0x20) + 63)
+        else:
+            out.append(chunk + 63)
+            return bytes(out)
+
+
+def polyline_encode_rows(H, precision, arith=np.float32):
+    """Every row of H as the concatenation of its values' codes. Returns
+    (codes uint8 [total], row_off int64 [n + 1])."""
+    q = polyline_quantise(H, precision, arith)
+    rows = [b"".join(polyline_encode_value(x) for x in r) for r in q]
+    row_off = np.zeros(len(rows) + 1, dtype=np.int64)
+    np.cumsum([len(r) for r in rows], out=row_off[1:])
+    codes = np.frombuffer(b"".join(rows), dtype=np.uint8).copy() if rows else np.zeros(0, np.uint8)
+    return codes, row_off
+
+
+def polyline_decode_rows(codes, row_off, ids, d, precision):
+    """out[k, :] = decoded row ids[k] (d values each): q / 10^precision in fp32
+    (one correctly rounded division, which is what the GPU path does)."""
+    scale = np.float32(10.0 ** precision)
+    out = np.zeros((len(ids), d), dtype=np.float32)
+    for k, r in enumerate(ids):
+        pos = int(row_off[r])
+        for c in range(d):
+            u, shift = 0, 0
+            while True:
+                b = int(codes[pos]) - 63
+                pos += 1
+                u |= (b & 0x1F) << shift
+                shift += 5
+                if not (b & 0x20):
+                    break
+            q = ~(u >> 1) if (u & 1) else (u >> 1)
+            out[k, c] = np.float32(q) / scale
+        assert pos == row_off[r + 1], "row %d does not hold exactly %d values" % (r, d)
+    return out
+
+
 def staleness(H_ref, H_approx):
     """Frobenius norm of the difference (Eq. 6 with the Frobenius norm)."""
     return float(np.linalg.norm(np.asarray(H_ref, np.float64) - np.asarray(H_approx, np.float64)))

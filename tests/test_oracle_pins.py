@@ -648,3 +648,42 @@ def test_predictor_training_special_cases():
         for k in om:
             om[k] -= 0.05 * gr[k]
     assert orc.predictor_train_loss_and_grad(v, om, slots, target)[0] < l0
+
+
+# ---------------------------------------------------------------- compression codec
+def test_polyline_codes_match_the_published_examples():
+    path = os.path.join(os.path.dirname(__file__), "golden", "polyline_examples.txt")
+    rows = [ln.split() for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) == 3
+    for value, prec, code in rows:
+        q = orc.polyline_quantise(np.array([float(value)]), int(prec), arith=np.float64)[0]
+        assert orc.polyline_encode_value(q) == code.encode("ascii"), (value, q)
+    # two values in a row are the concatenation of their codes
+    codes, off = orc.polyline_encode_rows(np.array([[38.5, -120.2]]), 5, arith=np.float64)
+    assert codes.tobytes() == b"_p~iF~ps|U" and list(off) == [0, 10]
+
+
+def test_polyline_round_trip_error_bound_and_lengths():
+    rng = np.random.default_rng(4)
+    H = np.maximum(rng.standard_normal((50, 37)), 0).astype(np.float32) * 3.0   # relu-like: half zeros
+    H[3, 5], H[7, 0] = -123.456, 1e-9
+    for prec in (1, 2, 4):
+        codes, off = orc.polyline_encode_rows(H, prec)
+        assert codes.min() >= 63 and codes.max() <= 126             # printable ASCII, as the format says
+        back = orc.polyline_decode_rows(codes, off, np.arange(50), 37, prec)
+        # lossy by at most half a unit of the kept decimal place (plus fp32 rounding of the product)
+        assert np.abs(back.astype(np.float64) - H).max() <= 0.5 * 10.0 ** -prec * (1 + 1e-5) + 1e-6
+        # coding what was decoded gives the same bytes: the codec is idempotent
+        codes2, off2 = orc.polyline_encode_rows(back, prec)
+        assert np.array_equal(codes, codes2) and np.array_equal(off, off2)
+        # zero takes one byte ('?'), and the row offsets add up
+        assert orc.polyline_encode_value(0) == b"?"
+        assert off[-1] == codes.size and np.all(np.diff(off) >= 37)
+        # gather by id decodes the right rows
+        ids = np.array([49, 0, 7, 7])
+        assert np.array_equal(orc.polyline_decode_rows(codes, off, ids, 37, prec), back[ids])
+    # fewer decimals, fewer bytes; relu-shaped rows at one decimal beat 3x against fp32
+    sizes = [orc.polyline_encode_rows(H, p)[1][-1] for p in (1, 2, 4)]
+    assert sizes[0] < sizes[1] < sizes[2]
+    base = np.maximum(rng.standard_normal((200, 256)), 0).astype(np.float32)
+    assert 4.0 * base.size / orc.polyline_encode_rows(base, 1)[1][-1] > 3.0
