@@ -92,6 +92,11 @@ def main():
                     help="after the timed steps also time one training step (loss, gradients, "
                          "plain gradient update) of hidden layer 1's predictor; reported under "
                          "\"predictor_train\", outside the step time (it runs every Delta T steps)")
+    ap.add_argument("--codec", type=int, default=None, metavar="DECIMALS",
+                    help="after the timed steps also time the compression codec on the newest "
+                         "history slot of hidden layer 1 at this many decimal places: plan + encode "
+                         "of the partition's local + halo rows, decode of the halo rows through the "
+                         "id list; reported under \"codec\"")
     ap.add_argument("--stale-grad", action="store_true",
                     help="also run the stale-gradient term of the backward: halo output of the "
                          "transpose aggregation pushed to a gradient table, table rows of the "
@@ -271,6 +276,55 @@ def main():
         log("predictor training step (layer %d): %.3f ms, loss %.6f" % (l, t_ms, ptrain["loss"]))
         del ws
 
+    # ---- optional: compression codec on one history slot
+    codec = None
+    if args.codec is not None and L >= 2:
+        from paper_2308_13466_amd import binding as B
+        l, prec = 1, args.codec
+        dt = B.BF16 if bf16 else B.F32
+        st_ptr = torch.cuda.current_stream().cuda_stream
+        # the rows a partition stores / pulls: its local + halo nodes, compact
+        slot = step.hist[l][step.slot_order()[-1]]
+        rows = torch.empty((n_bar, step.ld[l]), dtype=slot.dtype, device=dev)
+        B.history_gather(slot, slot.shape[0], slot.shape[1], step.table_ids, n_bar, dims[l], rows,
+                         step.ld[l], dtype=dt, stream=st_ptr)
+        wsb = B.history_compress_workspace_bytes(n_bar)
+        ws = torch.zeros(wsb // 8 + 1, dtype=torch.int64, device=dev)
+        row_off = torch.zeros(n_bar + 1, dtype=torch.int64, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        B.history_compress_plan(rows, step.ld[l], n_bar, dims[l], prec, row_off, dtype=dt,
+                                workspace=ws, workspace_bytes=wsb, stream=st_ptr)
+        torch.cuda.synchronize()
+        total = int(row_off[-1].item())
+        codes = torch.empty(total, dtype=torch.uint8, device=dev)
+        out = torch.empty((n_h, step.ld[l]), dtype=slot.dtype, device=dev)
+        halo_rows = torch.arange(n_l, n_bar, dtype=torch.int32, device=dev)
+        reps = 5
+        ev[0].record()
+        for _ in range(reps):
+            B.history_compress_plan(rows, step.ld[l], n_bar, dims[l], prec, row_off, dtype=dt,
+                                    workspace=ws, workspace_bytes=wsb, stream=st_ptr)
+            B.history_compress_encode(rows, step.ld[l], n_bar, dims[l], prec, row_off, codes, total,
+                                      dtype=dt, stream=st_ptr)
+        ev[1].record()
+        for _ in range(reps):
+            B.history_decompress(codes, row_off, n_bar, halo_rows, n_h, dims[l], prec, out, step.ld[l],
+                                 dtype=dt, stream=st_ptr)
+        ev[2].record()
+        torch.cuda.synchronize()
+        enc_ms, dec_ms = ev[0].elapsed_time(ev[1]) / reps, ev[1].elapsed_time(ev[2]) / reps
+        dense = n_bar * dims[l] * s
+        halo_coded = int((row_off[-1] - row_off[n_l]).item())
+        codec = {"layer": l, "decimals": prec, "rows": n_bar, "coded_bytes": total,
+                 "ratio_vs_stored": round(dense / max(total, 1), 3),
+                 "encode_ms": round(enc_ms, 4),
+                 "encode_gbs": round((2 * dense + total + 16 * n_bar) / (enc_ms * 1e-3) / 1e9, 1),
+                 "decode_rows": n_h, "decode_ms": round(dec_ms, 4),
+                 "decode_gbs": round((halo_coded + n_h * (dims[l] * s + 12)) / (dec_ms * 1e-3) / 1e9, 1)}
+        log("codec (%d decimals): %.2fx, encode %.3f ms, decode of the halo rows %.3f ms" % (
+            prec, codec["ratio_vs_stored"], enc_ms, dec_ms))
+        del rows, codes, out, ws
+
     # ---- CPU oracle on a bounded sample, rank 0, host cores
     cpu = None
     if not args.no_cpu_baseline and wl.X_host is None:
@@ -299,6 +353,7 @@ def main():
         "roofline_all": roof_all,
         "cpu_baseline": cpu,
         "predictor_train": ptrain,
+        "codec": codec,
         "loss": round(loss, 6),
     }
     print(json.dumps(out))

@@ -205,6 +205,38 @@ sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w, const vo
                        int64_t ld, int32_t dtype, void* workspace, int64_t workspace_bytes,
                        void* stream);
 
+/* ------- compression of stored embeddings (Sec. "Data Compression for Historical
+ * Embedding Storage"). Every value v is rounded to `precision` decimal places,
+ * q = floor(v * 10^precision + 1/2) (three fp32 operations, each correctly rounded),
+ * and q is written in the Encoded Polyline Algorithm Format's character coding:
+ * shift left one bit and invert if negative, 5-bit groups from the low end, 0x20 set
+ * on every group but the last, plus 63 (bytes 63..126). Values are coded one by one,
+ * a row is the concatenation of its d codes, row k occupies bytes
+ * [row_off[k], row_off[k+1]) of `codes`. |q| saturates at 2^30 - 1; NaN codes as 0.
+ * Lossy: |decoded - v| <= 10^-precision / 2 (plus fp32 rounding).
+ *   _plan    row_off[0..n] (device int64) from the dense rows H [n, ld_h]: code sizes,
+ *            then an exclusive scan; row_off[n] is the total number of bytes. The caller
+ *            reads it back to size `codes`.
+ *   _encode  writes the codes of the same H; rows that would end beyond `capacity`
+ *            bytes are not written.
+ *   sat_history_decompress  out[k, 0:d) = decoded row ids[k] (ids == NULL: row k) of a
+ *            coded table of n_rows rows, value = float(q) / 10^precision (one correctly
+ *            rounded division; bf16: rounded again to nearest-even). The pull of a coded
+ *            table: gather and decode in one pass. d <= 2340.
+ * precision in [0, 9]. Workspace (_plan only): sat_history_compress_workspace_bytes(n),
+ * 8-byte aligned.
+ */
+int64_t sat_history_compress_workspace_bytes(int64_t n);
+sat_status sat_history_compress_plan(const void* H, int64_t ld_h, int64_t n, int32_t d,
+                                     int32_t precision, int32_t dtype, int64_t* row_off,
+                                     void* workspace, int64_t workspace_bytes, void* stream);
+sat_status sat_history_compress_encode(const void* H, int64_t ld_h, int64_t n, int32_t d,
+                                       int32_t precision, int32_t dtype, const int64_t* row_off,
+                                       uint8_t* codes, int64_t capacity, void* stream);
+sat_status sat_history_decompress(const uint8_t* codes, const int64_t* row_off, int64_t n_rows,
+                                  const int32_t* ids, int64_t n, int32_t d, int32_t precision,
+                                  int32_t dtype, void* out, int64_t ld_out, void* stream);
+
 /* ------- training of the embedding predictor (Eq. 11; mini-batches of Eq. 12; Alg. 1
  * "embedding predictor update"). One hidden layer's predictor, one partition.
  * The partition knows this step's fresh embeddings of its LOCAL nodes, so the

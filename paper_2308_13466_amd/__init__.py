@@ -7,7 +7,8 @@ from .binding import (  # noqa: F401
     SatError, lib, lib_path, PartView, Predictor,
     partition_view_build, history_gather, history_gather_add, history_push, predict,
     predict_workspace_bytes, predictor_train_workspace_bytes, predictor_grad, sgd_update,
-    spmm_fwd, spmm_bwd, spmm_workspace_bytes,
+    history_compress_workspace_bytes, history_compress_plan, history_compress_encode,
+    history_decompress, spmm_fwd, spmm_bwd, spmm_workspace_bytes,
     dense_fwd, dense_bwd, dense_bwd_workspace_bytes, loss_grad,
     loss_workspace_bytes, status_string, version, F32, BF16, ACT_IDENTITY,
     ACT_RELU,

@@ -48,6 +48,10 @@ _SIGNATURES = {
     "sat_partition_view_build": (_i32, [_i64, _vp, _vp, _vp, _vp, _i32] + [_vp] * 10),
     "sat_history_gather": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_history_gather_add": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
+    "sat_history_compress_workspace_bytes": (_i64, [_i64]),
+    "sat_history_compress_plan": (_i32, [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "sat_history_compress_encode": (_i32, [_vp, _i64, _i64, _i32, _i32, _i32, _vp, _vp, _i64, _vp]),
+    "sat_history_decompress": (_i32, [_vp, _vp, _i64, _vp, _i64, _i32, _i32, _i32, _vp, _i64, _vp]),
     "sat_history_push": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_predict_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
     "sat_predict": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
@@ -173,6 +177,31 @@ def history_gather(table, n_rows, ld_table, ids, n, d, out, ld_out, dtype=F32, s
 def history_gather_add(table, n_rows, ld_table, ids, n, d, out, ld_out, dtype=F32, stream=None):
     _check(lib().sat_history_gather_add(_ptr(table), n_rows, ld_table, _ptr(ids), n, d, _ptr(out),
                                         ld_out, dtype, stream), "sat_history_gather_add")
+
+
+def history_compress_workspace_bytes(n):
+    return lib().sat_history_compress_workspace_bytes(n)
+
+
+def history_compress_plan(H, ld_h, n, d, precision, row_off, dtype=F32, workspace=None,
+                          workspace_bytes=0, stream=None):
+    _check(lib().sat_history_compress_plan(_ptr(H), ld_h, n, d, precision, dtype, _ptr(row_off),
+                                           _ptr(workspace), workspace_bytes, stream),
+           "sat_history_compress_plan")
+
+
+def history_compress_encode(H, ld_h, n, d, precision, row_off, codes, capacity, dtype=F32,
+                            stream=None):
+    _check(lib().sat_history_compress_encode(_ptr(H), ld_h, n, d, precision, dtype, _ptr(row_off),
+                                             _ptr(codes), capacity, stream),
+           "sat_history_compress_encode")
+
+
+def history_decompress(codes, row_off, n_rows, ids, n, d, precision, out, ld_out, dtype=F32,
+                       stream=None):
+    _check(lib().sat_history_decompress(_ptr(codes), _ptr(row_off), n_rows, _ptr(ids), n, d,
+                                        precision, dtype, _ptr(out), ld_out, stream),
+           "sat_history_decompress")
 
 
 def history_push(table, n_rows, ld_table, ids, n, d, H, ld_h, dtype=F32, stream=None):

@@ -1,0 +1,330 @@
+// Compression of stored embeddings (Sec. "Data Compression for Historical
+// Embedding Storage"): every value is rounded to a number of decimal places and
+// written as a variable-length run of printable characters following the
+// published Encoded Polyline Algorithm Format (zigzag the signed integer, 5-bit
+// groups from the low end, bit 0x20 marks "more follows", plus 63). Values are
+// coded one by one (no deltas); a row of the table is the concatenation of its
+// values' codes and an offset array says where each row starts.
+//
+// All of it is byte and integer work on top of three fp32 operations per value
+// (multiply by 10^p, add 1/2, floor - each correctly rounded, never fused), so the
+// codes are reproducible bit for bit. Kernels:
+//   plan    one wavefront per row sums the code lengths of its values; an in-place
+//           exclusive scan (2048 elements per workgroup, recursive over the workgroup
+//           totals) turns the sizes into offsets, row_off[n] = total bytes;
+//   encode  one wavefront per row; 64 values at a time: code length per lane,
+//           wavefront prefix sum for the byte position, byte stores;
+//   decode  one wavefront per requested row (gathered through an id list): the row's
+//           bytes are staged in LDS; a ballot of the "last group" bits gives every
+//           byte its value index; the lane holding a value's first byte assembles it
+//           and stores q / 10^p (one correctly rounded division).
+// HBM-bound: the dense side moves d * s bytes per row, the coded side 1 - 3 bytes
+// per value.
+#include "sat_internal.h"
+
+namespace {
+
+using sat::kWave;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kScanBlock = 2048;   // elements per workgroup of the scan (256 threads x 8)
+constexpr int kMaxGroups = 7;      // 5-bit groups of a 32-bit zigzag value
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+template <int ES>
+__device__ __forceinline__ float load_elem(const void* row, int c) {
+  if constexpr (ES == 4) {
+    return static_cast<const float*>(row)[c];
+  } else {
+    const uint32_t h = static_cast<const uint16_t*>(row)[c];
+    return __builtin_bit_cast(float, h << 16);
+  }
+}
+
+// zigzag code of floor(v * scale + 1/2), saturated to 31 bits; NaN codes as 0
+__device__ __forceinline__ uint32_t zigzag_of(float v, float scale) {
+  float x = floorf(__fadd_rn(__fmul_rn(v, scale), 0.5f));
+  if (!(x == x)) x = 0.f;
+  x = fminf(fmaxf(x, -1073741823.0f), 1073741823.0f);
+  const int32_t q = static_cast<int32_t>(x);
+  return (static_cast<uint32_t>(q) << 1) ^ static_cast<uint32_t>(q >> 31);
+}
+__device__ __forceinline__ int groups_of(uint32_t u) {
+  const int bits = 32 - __builtin_clz(u | 1u);
+  return (bits + 4) / 5;
+}
+
+__device__ __forceinline__ int wave_sum(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
+  return x;
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int wave_scan(int x, int lane) {
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int y = __shfl_up(x, off);
+    if (lane >= off) x += y;
+  }
+  return x;
+}
+
+// sizes[k] = bytes of row k's code (k < n); sizes[n] = 0
+template <int ES>
+__global__ __launch_bounds__(256) void code_size_kernel(const void* __restrict__ H, int64_t ld_bytes,
+                                                        int64_t n, int d, float scale,
+                                                        int64_t* __restrict__ sizes) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t k = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (k > n) return;
+  if (k == n) {
+    if (lane == 0) sizes[n] = 0;
+    return;
+  }
+  const void* row = static_cast<const unsigned char*>(H) + k * ld_bytes;
+  int acc = 0;
+  for (int c = lane; c < d; c += kWave) acc += groups_of(zigzag_of(load_elem<ES>(row, c), scale));
+  acc = wave_sum(acc);
+  if (lane == 0) sizes[k] = acc;
+}
+
+// In-place exclusive scan of blocks of kScanBlock elements; totals[b] = sum of block b.
+__global__ __launch_bounds__(256) void scan_blocks_kernel(int64_t* __restrict__ a, int64_t n,
+                                                          int64_t* __restrict__ totals) {
+  __shared__ int64_t sh[256];
+  const int64_t base = static_cast<int64_t>(blockIdx.x) * kScanBlock + threadIdx.x * 8;
+  int64_t v[8];
+  int64_t sum = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    v[i] = base + i < n ? a[base + i] : 0;
+    sum += v[i];
+  }
+  sh[threadIdx.x] = sum;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {   // inclusive scan of the thread sums
+    const int64_t y = threadIdx.x >= off ? sh[threadIdx.x - off] : 0;
+    __syncthreads();
+    sh[threadIdx.x] += y;
+    __syncthreads();
+  }
+  int64_t run = sh[threadIdx.x] - sum;        // exclusive prefix of this thread
+  if (threadIdx.x == 255) totals[blockIdx.x] = sh[255];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (base + i < n) a[base + i] = run;
+    run += v[i];
+  }
+}
+__global__ __launch_bounds__(256) void add_block_offsets_kernel(int64_t* __restrict__ a, int64_t n,
+                                                                const int64_t* __restrict__ offs) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) a[i] += offs[i / kScanBlock];
+}
+
+// exclusive scan of a[0..n) in place; ws holds the totals of every level
+sat_status scan_in_place(int64_t* a, int64_t n, int64_t* ws, hipStream_t st) {
+  const int64_t nb = (n + kScanBlock - 1) / kScanBlock;
+  if (nb > INT32_MAX) return SAT_EUNSUPPORTED;
+  scan_blocks_kernel<<<dim3(static_cast<unsigned>(nb)), dim3(256), 0, st>>>(a, n, ws);
+  sat_status rc = sat::check_launch();
+  if (rc != SAT_OK || nb == 1) return rc;
+  if ((rc = scan_in_place(ws, nb, ws + round_up(nb, 32), st)) != SAT_OK) return rc;
+  add_block_offsets_kernel<<<dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0, st>>>(a, n, ws);
+  return sat::check_launch();
+}
+int64_t scan_ws_elems(int64_t n) {
+  int64_t total = 0;
+  while (n > 1) {
+    n = (n + kScanBlock - 1) / kScanBlock;
+    total += round_up(n, 32);
+    if (n == 1) break;
+  }
+  return total + 32;
+}
+
+template <int ES>
+__global__ __launch_bounds__(256) void encode_kernel(const void* __restrict__ H, int64_t ld_bytes,
+                                                     int64_t n, int d, float scale,
+                                                     const int64_t* __restrict__ row_off,
+                                                     uint8_t* __restrict__ codes, int64_t capacity) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t k = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (k >= n) return;
+  const int64_t b0 = row_off[k], b1 = row_off[k + 1];
+  if (b0 < 0 || b1 < b0 || b1 > capacity) return;   // never write outside the caller's buffer
+  const void* row = static_cast<const unsigned char*>(H) + k * ld_bytes;
+  int64_t pos = b0;
+  for (int c0 = 0; c0 < d; c0 += kWave) {
+    const int c = c0 + lane;
+    uint32_t u = 0;
+    int len = 0;
+    if (c < d) {
+      u = zigzag_of(load_elem<ES>(row, c), scale);
+      len = groups_of(u);
+    }
+    const int incl = wave_scan(len, lane);
+    int64_t p = pos + (incl - len);
+    if (p + len <= b1) {   // (holds when row_off came from the plan of the same data)
+      for (int j = 0; j < len; ++j) {
+        const uint32_t g = (u >> (5 * j)) & 0x1Fu;
+        codes[p + j] = static_cast<uint8_t>((j + 1 < len ? (g | 0x20u) : g) + 63u);
+      }
+    }
+    pos += __shfl(incl, kWave - 1);
+  }
+}
+
+// out[k, 0:d) = decoded row (ids ? ids[k] : k); one wavefront per k, LDS slice of row_cap bytes each
+template <int ES>
+__global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ codes,
+                                                     const int64_t* __restrict__ row_off,
+                                                     int64_t n_rows, const int32_t* __restrict__ ids,
+                                                     int64_t n, int d, float scale, int row_cap,
+                                                     void* __restrict__ out, int64_t ld_bytes) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int64_t k = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+  if (k >= n) return;
+  const int64_t r = ids ? static_cast<int64_t>(ids[k]) : k;
+  if (r < 0 || r >= n_rows) return;                 // bad id: the row is left alone
+  const int64_t b0 = row_off[r];
+  int64_t nb64 = row_off[r + 1] - b0;
+  if (nb64 < 0) return;
+  const int nb = nb64 > row_cap ? row_cap : static_cast<int>(nb64);   // a row never exceeds 7 d bytes
+  unsigned char* mine = lds + wave * row_cap;
+  for (int i = lane; i < nb; i += kWave) mine[i] = codes[b0 + i];
+  // (a wavefront reads back only what it wrote itself: no barrier needed, the LDS
+  // accesses of one wavefront are ordered)
+  unsigned char* orow = static_cast<unsigned char*>(out) + k * ld_bytes;
+  int done = 0;                 // values completed before this chunk
+  bool prev_last = true;        // the byte before this chunk ended a value (or the row starts)
+  for (int base = 0; base < nb; base += kWave) {
+    const int i = base + lane;
+    const uint32_t b = i < nb ? static_cast<uint32_t>(mine[i]) - 63u : 0u;
+    const bool last = i < nb && (b & 0x20u) == 0;
+    const uint64_t m = __ballot(last);
+    const uint64_t below = lane == 0 ? 0ull : (m & ((1ull << lane) - 1ull));
+    const bool starts = i < nb && (lane == 0 ? prev_last : ((m >> (lane - 1)) & 1ull) != 0);
+    if (starts) {
+      const int idx = done + __builtin_popcountll(below);
+      if (idx < d) {
+        uint32_t u = 0;
+        for (int j = 0; j < kMaxGroups && i + j < nb; ++j) {
+          const uint32_t g = static_cast<uint32_t>(mine[i + j]) - 63u;
+          u |= (g & 0x1Fu) << (5 * j);
+          if ((g & 0x20u) == 0) break;
+        }
+        const int32_t q = static_cast<int32_t>(u >> 1) ^ -static_cast<int32_t>(u & 1u);
+        const float v = __fdiv_rn(static_cast<float>(q), scale);
+        if constexpr (ES == 4) {
+          reinterpret_cast<float*>(orow)[idx] = v;
+        } else {
+          const f32x2 pr = {v, 0.f};
+          const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+          reinterpret_cast<uint16_t*>(orow)[idx] = static_cast<uint16_t>(w & 0xffffu);
+        }
+      }
+    }
+    done += __builtin_popcountll(m);
+    prev_last = ((m >> (kWave - 1)) & 1ull) != 0;
+  }
+}
+
+float scale_of(int precision) {
+  float s = 1.0f;
+  for (int i = 0; i < precision; ++i) s *= 10.0f;   // exact in fp32 up to 10^10
+  return s;
+}
+
+sat_status check_dense(const void* p, int64_t ld, int64_t n, int32_t d, int32_t precision,
+                       int32_t dtype) {
+  if (n < 0 || d < 0) return SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
+  if (precision < 0 || precision > 9) return SAT_EINVAL;
+  if (n > 0 && d > 0 && (!p || ld < d)) return SAT_EINVAL;
+  return SAT_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t sat_history_compress_workspace_bytes(int64_t n) {
+  if (n < 0) return 0;
+  return scan_ws_elems(n + 1) * static_cast<int64_t>(sizeof(int64_t));
+}
+
+extern "C" sat_status sat_history_compress_plan(const void* H, int64_t ld_h, int64_t n, int32_t d,
+                                                int32_t precision, int32_t dtype, int64_t* row_off,
+                                                void* workspace, int64_t workspace_bytes,
+                                                void* stream) {
+  sat_status rc = check_dense(H, ld_h, n, d, precision, dtype);
+  if (rc != SAT_OK) return rc;
+  if (!row_off) return SAT_EINVAL;
+  if (!workspace || workspace_bytes < sat_history_compress_workspace_bytes(n)) return SAT_EWORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 7u) != 0) return SAT_EALIGN;
+  const int64_t blocks = (n + 1 + 3) / 4;
+  if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int es = dtype == SAT_BF16 ? 2 : 4;
+  const float scale = scale_of(precision);
+  if (es == 4)
+    code_size_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(H, ld_h * es, n, d,
+                                                                                 scale, row_off);
+  else
+    code_size_kernel<2><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(H, ld_h * es, n, d,
+                                                                                 scale, row_off);
+  if ((rc = sat::check_launch()) != SAT_OK) return rc;
+  return scan_in_place(row_off, n + 1, static_cast<int64_t*>(workspace), st);
+}
+
+extern "C" sat_status sat_history_compress_encode(const void* H, int64_t ld_h, int64_t n, int32_t d,
+                                                  int32_t precision, int32_t dtype,
+                                                  const int64_t* row_off, uint8_t* codes,
+                                                  int64_t capacity, void* stream) {
+  sat_status rc = check_dense(H, ld_h, n, d, precision, dtype);
+  if (rc != SAT_OK) return rc;
+  if (capacity < 0) return SAT_EINVAL;
+  if (n == 0 || d == 0) return SAT_OK;
+  if (!row_off || (!codes && capacity > 0)) return SAT_EINVAL;
+  const int64_t blocks = (n + 3) / 4;
+  if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int es = dtype == SAT_BF16 ? 2 : 4;
+  const float scale = scale_of(precision);
+  if (es == 4)
+    encode_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(H, ld_h * es, n, d, scale,
+                                                                              row_off, codes, capacity);
+  else
+    encode_kernel<2><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(H, ld_h * es, n, d, scale,
+                                                                              row_off, codes, capacity);
+  return sat::check_launch();
+}
+
+extern "C" sat_status sat_history_decompress(const uint8_t* codes, const int64_t* row_off,
+                                             int64_t n_rows, const int32_t* ids, int64_t n, int32_t d,
+                                             int32_t precision, int32_t dtype, void* out,
+                                             int64_t ld_out, void* stream) {
+  sat_status rc = check_dense(out, ld_out, n, d, precision, dtype);
+  if (rc != SAT_OK) return rc;
+  if (n_rows < 0) return SAT_EINVAL;
+  if (n == 0 || d == 0) return SAT_OK;
+  if (!codes || !row_off) return SAT_EINVAL;
+  const int row_cap = static_cast<int>(round_up(static_cast<int64_t>(kMaxGroups) * d, 16));
+  const int smem = 4 * row_cap;
+  if (smem > 64 * 1024) return SAT_EUNSUPPORTED;   // rows wider than 2340 values
+  const int64_t blocks = (n + 3) / 4;
+  if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int es = dtype == SAT_BF16 ? 2 : 4;
+  const float scale = scale_of(precision);
+  if (es == 4)
+    decode_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), smem, st>>>(
+        codes, row_off, n_rows, ids, n, d, scale, row_cap, out, ld_out * es);
+  else
+    decode_kernel<2><<<dim3(static_cast<unsigned>(blocks)), dim3(256), smem, st>>>(
+        codes, row_off, n_rows, ids, n, d, scale, row_cap, out, ld_out * es);
+  return sat::check_launch();
+}
