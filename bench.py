@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--unfused-pull", action="store_true",
                     help="assemble the predictor window with sat_history_gather first")
     ap.add_argument("--bypass", action="store_true", help="plain historical embeddings")
+    ap.add_argument("--delta-t", type=int, default=1,
+                    help="refresh the predicted halo embeddings every DELTA_T steps (Alg. 1's update "
+                         "frequency); the default 1 predicts on every step")
     ap.add_argument("--predictor-train", action="store_true",
                     help="after the timed steps also time one training step (loss, gradients, "
                          "plain gradient update) of hidden layer 1's predictor; reported under "
@@ -129,7 +132,8 @@ def main():
 
     timers = CallTimers(torch)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
-                        timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad)
+                        timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
+                        predict_every=args.delta_t)
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
     dims, tau, d_s, L = wl.dims, wl.tau, wl.d_s, wl.L
@@ -343,7 +347,8 @@ def main():
                    "partition": "%d of %d" % (cfg["part"], cfg["n_parts"]),
                    "n_local": n_l, "n_halo": n_h, "nnz": nnz, "nnz_local_local": nnz_loc,
                    "dims": dims, "tau": tau, "d_s": d_s,
-                   "predictor": "bypass" if args.bypass else "every step",
+                   "predictor": "bypass" if args.bypass else (
+                       "every step" if args.delta_t <= 1 else "every %d steps" % args.delta_t),
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
                    "stale_gradient_term": bool(args.stale_grad),
                    "entries_per_step": edges},

@@ -44,6 +44,8 @@ class PartitionStep:
           history tables and Ws (dW, the loss and the predictor parameters are fp32).
     predictors: predictors[l] a binding.Predictor for l = 1..L-1 (None: bypass).
     y: device int32 [n_local] labels.
+    predict_every: Delta T of Alg. 1 - the predicted halo rows are refreshed on steps
+          t = 0, Delta T, 2 Delta T, ... and reused (they stay in the halo rows of Hbar_l) in between.
     grad_tables: None, or grad_tables[l] for l = 1..L-1 a pair [table_a, table_b] of
           device tables [n_rows_g, ld_l] (row of a node as in the history tables): step
           t reads pair[t % 2] (stale term for the local rows) and writes pair[(t+1) % 2]
@@ -51,7 +53,7 @@ class PartitionStep:
     """
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
-                 fused_pull=True, timers=None, dtype=B.F32, grad_tables=None):
+                 fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1):
         dev = X_table.device
         self.dtype = dtype
         self.dims = list(dims)
@@ -71,6 +73,7 @@ class PartitionStep:
         self.Ws, self.predictors, self.y = Ws, predictors, y
         self.fused_pull = fused_pull
         self.grad_tables = grad_tables
+        self.predict_every = max(1, int(predict_every))
         self.t = 0
         self.timers = timers
 
@@ -125,8 +128,8 @@ class PartitionStep:
         st = self._stream()
         dt = self.dtype
         order = self.slot_order()
-        # 1. predicted halo embeddings of every hidden layer
-        for l in range(1, L):
+        # 1. predicted halo embeddings of every hidden layer (every Delta T steps)
+        for l in range(1, L if self.t % self.predict_every == 0 else 1):
             slots = [self.hist[l][s] for s in order]
             n_rows, ld_t = slots[0].shape
             w = self.predictors[l]

@@ -35,7 +35,7 @@ def _upload(a, bf16, dev):
 
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
-                   keep_host=True, device="cuda:0", dtype=None, grad_tables=False):
+                   keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
@@ -128,7 +128,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
         gt = [None] + [[torch.zeros_like(hist_d[l][0]) for _ in range(2)] for l in range(1, L)]
     step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
                          fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
-                         grad_tables=gt)
+                         grad_tables=gt, predict_every=predict_every)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))

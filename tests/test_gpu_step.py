@@ -213,3 +213,40 @@ def test_zero_staleness_invariant_on_gpu():
             out = step.logits if l == L else step.Hbar[l]
             gu.assert_close(gu.to_host(out, dims[l])[:n_l], Hfull[l][view["local_ids"]], 2e-5,
                             "H^(%d) vs unpartitioned GCN, partition %d" % (l, m))
+
+
+def test_predictor_update_frequency():
+    """Delta T of Alg. 1: with predict_every = 2 the predicted halo rows of step 1 are the
+    ones step 0 left in place, and step 2 refreshes them from the ring as it stands then."""
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd.step import PartitionStep
+    from tests import gpu_util as gu
+    print("[case] predictor every 2 steps, tiny", flush=True)
+    cfg, ss, g, X, Ws, omegas = build_problem("tiny")
+    pss = ss["predictor"].spawn(len(Ws))
+    omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32) for l in range(1, len(Ws))]
+    dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
+    _, hist = fresh_history(cfg, ss, g, X, Ws)
+    view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    oview = orc.partition_view(g.N, g.rowptr, g.col, g.part, 0)
+    y = syn.labels_i32(ss["labels"], view["n_local"], dims[-1])
+    ld = [gu.ld_for(d) for d in dims]
+    hist_d = [None] + [[gu.to_dev(t, ld[l]) for t in hist[l]] for l in range(1, L)]
+    ids_d = gu.to_dev(np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32))
+    pd = {k: gu.to_dev(omegas[1][k]) for k in omegas[1]}
+    preds = [None, sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[1], 32, tau)]
+    step = PartitionStep(view, dims, gu.to_dev(X, ld[0]), hist_d, ids_d,
+                         [gu.to_dev(Ws[l], gu.ld_for(dims[l + 1], 4)) for l in range(L)], preds,
+                         gu.to_dev(y), tau, predict_every=2)
+    n_l = view["n_local"]
+    halo = []
+    for t in range(3):
+        step.forward_backward()
+        gu.sync()
+        halo.append(gu.to_host(step.Hbar[1], dims[1])[n_l:].copy())
+    assert np.array_equal(halo[0], halo[1])
+    assert not np.array_equal(halo[1], halo[2])
+    # step 2's prediction is the oracle's from the ring after two pushes (slot order [0, 1] again)
+    ids = np.concatenate([oview["local_ids"], oview["halo_ids"]])
+    ring = [gu.to_host(hist_d[1][s], dims[1])[ids] for s in (0, 1)]
+    gu.assert_close(halo[2], orc.predict(oview, omegas[1], ring), RTOL, "refreshed prediction")
