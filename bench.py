@@ -50,12 +50,16 @@ class CallTimers:
     """HIP event pairs around every library call, on the stream the calls are
     enqueued on (torch's current stream), collected over the timed steps."""
 
-    def __init__(self, torch):
+    def __init__(self, torch, flush=None):
         self.torch = torch
         self.pairs = []
         self.enabled = False
+        self.flush = flush      # optional: a buffer larger than every cache, rewritten
+                                # before each call so that the call starts cold
 
     def record(self, name, fn):
+        if self.flush is not None:
+            self.flush.add_(1.0)
         if not self.enabled:
             fn()
             return
@@ -69,10 +73,9 @@ class CallTimers:
     def summary(self):
         out = {}
         for name, a, b in self.pairs:
-            ms = a.elapsed_time(b)
-            tot, cnt = out.get(name, (0.0, 0))
-            out[name] = (tot + ms, cnt + 1)
-        return {k: dict(total_ms=v[0], launches=v[1], avg_ms=v[0] / v[1]) for k, v in out.items()}
+            out.setdefault(name, []).append(a.elapsed_time(b))
+        return {k: dict(total_ms=sum(v), launches=len(v), avg_ms=sum(v) / len(v), min_ms=min(v),
+                        median_ms=sorted(v)[len(v) // 2]) for k, v in out.items()}
 
 
 def main():
@@ -108,6 +111,10 @@ def main():
                     help="also launch one plain row copy of known size (1 GiB read + 1 GiB "
                          "written, identity ids) so that a rocprofv3 --pmc run of this command "
                          "can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--cold", action="store_true",
+                    help="rewrite a 1 GiB buffer before every library call, so that no call finds "
+                         "its inputs in the caches (for the workloads whose working set fits "
+                         "them); ms_per_step is then the sum of the calls' own times")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -130,7 +137,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    timers = CallTimers(torch)
+    flush = torch.zeros(1 << 28, dtype=torch.float32, device=dev) if args.cold else None
+    timers = CallTimers(torch, flush)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
                         predict_every=args.delta_t)
@@ -165,8 +173,11 @@ def main():
     timers.enabled = False
     ms_per_step = 1e3 * elapsed / args.steps
     edges = step.edges_per_step()
-    gteps = edges / (ms_per_step * 1e-3) / 1e9
     calls = timers.summary()
+    if args.cold:       # the flushes sit between the calls: count the calls alone
+        ms_per_step = sum(c["total_ms"] for c in calls.values()) / args.steps
+    gteps = edges / (ms_per_step * 1e-3) / 1e9
+    spmm_ms = sum(c["total_ms"] for k, c in calls.items() if k.startswith("spmm_")) / args.steps
     loss = float(step.loss.item())
     log("ms/step %.3f  GTEPS %.2f  loss %.5f" % (ms_per_step, gteps, loss))
 
@@ -351,9 +362,13 @@ def main():
                        "every step" if args.delta_t <= 1 else "every %d steps" % args.delta_t),
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
                    "stale_gradient_term": bool(args.stale_grad),
+                   "caches": "flushed before every call" if args.cold else "as the step leaves them",
                    "entries_per_step": edges},
         "ms_per_layer_step": round(ms_per_step / L, 4),
+        "gteps_aggregation_calls_only": round(edges / (spmm_ms * 1e-3) / 1e9, 3) if spmm_ms else None,
         "ms_by_call": {k: round(v["total_ms"] / args.steps, 4) for k, v in sorted(calls.items())},
+        "ms_by_call_min": {k: round(v["min_ms"], 4) for k, v in sorted(calls.items())},
+        "ms_by_call_median": {k: round(v["median_ms"], 4) for k, v in sorted(calls.items())},
         "roofline": roofline,
         "roofline_all": roof_all,
         "cpu_baseline": cpu,
