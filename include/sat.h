@@ -303,6 +303,8 @@ sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in,
  *   dW   [d_in, ld_dw] = AGG^T dZ   (fp32; reduced over all n rows in a fixed
  *                               order, so results are run-to-run identical);
  *   dAGG [n, ld_da]    = dZ W^T     (skipped if dAGG == NULL, e.g. layer 0).
+ * dW == NULL skips the weight gradient (AGG may then be NULL and no workspace
+ * is needed): only dAGG is computed.
  * Workspace: sat_dense_bwd_workspace_bytes(); 256-byte aligned device memory.
  */
 int64_t sat_dense_bwd_workspace_bytes(int64_t n, int32_t d_in, int32_t d_out);
@@ -323,6 +325,63 @@ int64_t sat_loss_workspace_bytes(int64_t n);
 sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
                          const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh, float* loss,
                          void* workspace, int64_t workspace_bytes, void* stream);
+
+/* =================== graph attention backbone (second backbone of the paper's
+ * experiments; the layer is Eq. 1 / Eq. 2 with attention as the aggregation
+ * function, defined as in Velickovic et al., "Graph Attention Networks",
+ * Eq. 1-4). One layer on a partition, Hbar = [local rows ; halo rows]:
+ *   Z = Hbar W                        sat_dense_fwd over all n_local + n_halo rows
+ *   el, er                            sat_gat_scores
+ *   H' = act(sum_j alpha_ij Z_j)      sat_gat_aggregate_fwd
+ * and backwards sat_gat_aggregate_bwd (dZ, gradients of the attention
+ * vectors), then sat_dense_bwd (dW over all rows, dHbar = dZ W^T over the local
+ * rows). The neighbourhood of local node i is row i of the view's CSR
+ * (self-loop included); the stored values A_hat are not used.
+ *
+ * Shapes: d = heads * d_head columns, head k owning columns [k d_head, (k+1) d_head).
+ * Supported: heads in {1, 2, 4, 8}; d <= 256; for heads > 1, d_head / 4 a power of
+ * two (else SAT_EUNSUPPORTED). Scores, statistics and attention vectors are fp32
+ * whatever the storage type; sums are fp32. All pointers are device pointers;
+ * el, er, stats 16-byte aligned; matrices as everywhere (16-byte aligned rows).
+ */
+
+/* Attention scores: er[r, k] = <a_src[k], Z[r, head k]> for r < n and
+ * el[r, k] = <a_dst[k], Z[r, head k]> for r < n_dst (n_dst <= n: the local rows).
+ * a_dst, a_src: [heads * d_head] fp32. el: [n_dst, heads], er: [n, heads]. */
+sat_status sat_gat_scores(const void* Z, int64_t ld_z, int64_t n, int64_t n_dst, int32_t heads,
+                          int32_t d_head, const float* a_dst, const float* a_src, int32_t dtype,
+                          float* el, float* er, void* stream);
+
+/* Edge softmax and aggregation for the n_local rows of the view:
+ *   e_ij = LeakyReLU(el[i] + er[j]; slope), alpha_ij = softmax over row i's entries,
+ *   H[i] = act(sum_j alpha_ij Z[j]) per head (act as in sat_dense_fwd).
+ * Z: [n_local + n_halo, ld_z]; H: [n_local, ld_h]; stats: [n_local, heads, 2] fp32
+ * receives (max_j e_ij, 1 / sum_j exp(e_ij - max)) for the backward. A row without
+ * entries gives H[i] = 0, stats (0, 0). */
+sat_status sat_gat_aggregate_fwd(const sat_part_view* pv, const void* Z, int64_t ld_z,
+                                 int32_t heads, int32_t d_head, int32_t dtype, const float* el,
+                                 const float* er, float slope, int32_t act, void* H, int64_t ld_h,
+                                 float* stats, void* stream);
+
+/* Backward of scores + aggregation. With dOUT = dH o [H > 0] (act = RELU; H is the
+ * forward's output) or dH (IDENTITY; H may be NULL):
+ *   dalpha_ij = <dOUT_i, Z_j>, ds_ij = alpha_ij (dalpha_ij - sum_k alpha_ik dalpha_ik)
+ *               LeakyReLU'(el_i + er_j), d_el_i = sum_j ds_ij, d_er_j = sum_i ds_ij,
+ *   dZ[j]  = sum_i alpha_ij dOUT_i + d_er_j a_src + d_el_j a_dst  (last term: local j),
+ *   da_dst = sum_i d_el_i Z_i, da_src = sum_j d_er_j Z_j          ([heads * d_head] fp32).
+ * dZ: [n_local + n_halo, ld_dz], every row written. Needs the view's transposed halo
+ * block (h_colptr, h_row) and relies on the local block's pattern being symmetric.
+ * Sums run in a fixed order (run-to-run identical results).
+ * Workspace: sat_gat_aggregate_bwd_workspace_bytes(); 256-byte aligned. */
+int64_t sat_gat_aggregate_bwd_workspace_bytes(int64_t n_local, int64_t n_halo, int32_t heads,
+                                              int32_t d_head, int32_t dtype);
+sat_status sat_gat_aggregate_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z,
+                                 int32_t heads, int32_t d_head, int32_t dtype, const float* el,
+                                 const float* er, const float* stats, float slope, int32_t act,
+                                 const void* dH, int64_t ld_dh, const void* H, int64_t ld_h,
+                                 const float* a_dst, const float* a_src, void* dZ, int64_t ld_dz,
+                                 float* da_dst, float* da_src, void* workspace,
+                                 int64_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -9,7 +9,8 @@ from .binding import (  # noqa: F401
     predict_workspace_bytes, predictor_train_workspace_bytes, predictor_grad, sgd_update,
     history_compress_workspace_bytes, history_compress_plan, history_compress_encode,
     history_decompress, spmm_fwd, spmm_bwd, spmm_workspace_bytes,
-    dense_fwd, dense_bwd, dense_bwd_workspace_bytes, loss_grad,
+    dense_fwd, dense_bwd, dense_bwd_workspace_bytes, loss_grad, gat_scores,
+    gat_aggregate_fwd, gat_aggregate_bwd, gat_aggregate_bwd_workspace_bytes,
     loss_workspace_bytes, status_string, version, F32, BF16, ACT_IDENTITY,
     ACT_RELU,
 )

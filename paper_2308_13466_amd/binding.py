@@ -66,6 +66,13 @@ _SIGNATURES = {
     "sat_dense_bwd_workspace_bytes": (_i64, [_i64, _i32, _i32]),
     "sat_dense_bwd": (_i32, [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i32, _i32, _i32,
                              _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp]),
+    "sat_gat_scores": (_i32, [_vp, _i64, _i64, _i64, _i32, _i32, _vp, _vp, _i32, _vp, _vp, _vp]),
+    "sat_gat_aggregate_fwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, C.c_float, _i32,
+                                     _vp, _i64, _vp, _vp]),
+    "sat_gat_aggregate_bwd_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
+    "sat_gat_aggregate_bwd": (_i32, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _vp, _vp, C.c_float,
+                                     _i32, _vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp,
+                                     _vp, _i64, _vp]),
     "sat_loss_workspace_bytes": (_i64, [_i64]),
     "sat_loss_grad": (_i32, [_vp, _i64, _i64, _i32, _vp, _i32, _vp, _i64, _vp, _vp, _i64, _vp]),
 }
@@ -269,6 +276,32 @@ def dense_bwd(dH, ld_dh, Hout, ld_ho, AGG, ld_a, W, ld_w, n, d_in, d_out, act, d
     _check(lib().sat_dense_bwd(_ptr(dH), ld_dh, _ptr(Hout), ld_ho, _ptr(AGG), ld_a, _ptr(W), ld_w,
                                n, d_in, d_out, act, dtype, _ptr(dW), ld_dw, _ptr(dAGG), ld_da,
                                _ptr(workspace), workspace_bytes, stream), "sat_dense_bwd")
+
+
+def gat_scores(Z, ld_z, n, n_dst, heads, d_head, a_dst, a_src, el, er, dtype=F32, stream=None):
+    _check(lib().sat_gat_scores(_ptr(Z), ld_z, n, n_dst, heads, d_head, _ptr(a_dst), _ptr(a_src),
+                                dtype, _ptr(el), _ptr(er), stream), "sat_gat_scores")
+
+
+def gat_aggregate_fwd(pv, Z, ld_z, heads, d_head, el, er, slope, act, H, ld_h, stats, dtype=F32,
+                      stream=None):
+    _check(lib().sat_gat_aggregate_fwd(pv.ref, _ptr(Z), ld_z, heads, d_head, dtype, _ptr(el),
+                                       _ptr(er), slope, act, _ptr(H), ld_h, _ptr(stats), stream),
+           "sat_gat_aggregate_fwd")
+
+
+def gat_aggregate_bwd_workspace_bytes(n_local, n_halo, heads, d_head, dtype=F32):
+    return lib().sat_gat_aggregate_bwd_workspace_bytes(n_local, n_halo, heads, d_head, dtype)
+
+
+def gat_aggregate_bwd(pv, Z, ld_z, heads, d_head, el, er, stats, slope, act, dH, ld_dh, H, ld_h,
+                      a_dst, a_src, dZ, ld_dz, da_dst, da_src, dtype=F32, workspace=None,
+                      workspace_bytes=0, stream=None):
+    _check(lib().sat_gat_aggregate_bwd(pv.ref, _ptr(Z), ld_z, heads, d_head, dtype, _ptr(el),
+                                       _ptr(er), _ptr(stats), slope, act, _ptr(dH), ld_dh, _ptr(H),
+                                       ld_h, _ptr(a_dst), _ptr(a_src), _ptr(dZ), ld_dz,
+                                       _ptr(da_dst), _ptr(da_src), _ptr(workspace),
+                                       workspace_bytes, stream), "sat_gat_aggregate_bwd")
 
 
 def loss_workspace_bytes(n):

@@ -148,7 +148,7 @@ sat_status run_bwd(const void* dH, int64_t ld_dh, const void* mask, int64_t ld_h
   sat_status st;
   const bool relu = mask != nullptr;
   // dW = AGG^T dZ : reduced over the n rows, node ranges over blockIdx.z; fp32 out
-  {
+  if (dW) {
     const SplitPlan p = plan_dw(n, d_in, d_out);
     if ((st = launch_dw<ES>(AGG, ld_a, d_in, dH, ld_dh, d_out, mask, ld_ho, n, p, part, s)) != SAT_OK)
       return st;
@@ -214,16 +214,17 @@ extern "C" sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* H
   sat_status st;
   if ((st = check_mat(dH, n, d_out, ld_dh, es)) != SAT_OK) return st;
   if (act == SAT_ACT_RELU && (st = check_mat(Hout, n, d_out, ld_ho, es)) != SAT_OK) return st;
-  if ((st = check_mat(AGG, n, d_in, ld_a, es)) != SAT_OK) return st;
+  if (dW && (st = check_mat(AGG, n, d_in, ld_a, es)) != SAT_OK) return st;
   if ((st = check_mat(W, d_in, d_out, ld_w, es)) != SAT_OK) return st;
-  if ((st = check_mat(dW, d_in, d_out, ld_dw, 4)) != SAT_OK) return st;
+  if (dW && (st = check_mat(dW, d_in, d_out, ld_dw, 4)) != SAT_OK) return st;
   if (dAGG && (st = check_mat(dAGG, n, d_in, ld_da, es)) != SAT_OK) return st;
   if (d_in == 0 || d_out == 0) return SAT_OK;
-  const int64_t need = sat_dense_bwd_workspace_bytes(n, d_in, d_out);
+  const int64_t need = dW ? sat_dense_bwd_workspace_bytes(n, d_in, d_out) : 0;
   if (need > 0 && (!workspace || workspace_bytes < need)) return SAT_EWORKSPACE;
   if (need > 0 && !sat::aligned256(workspace)) return SAT_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (n == 0) {
+    if (!dW) return SAT_OK;
     // empty reduction: dW = 0 (the reduce kernel with zero slices writes zeros)
     const int64_t total = static_cast<int64_t>(d_in) * d_out;
     reduce_partials_kernel<<<dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s>>>(

@@ -10,12 +10,14 @@ from .graphs import (Graph, sbm_graph, chung_lu_planted_graph, chung_lu_partitio
                      ring_graph, make_graph, cached_graph)
 from .tensors import (substreams, normal_f32, glorot_uniform_f32, labels_i32,
                       predictor_params_f32, history_standin_f32, bf16_bits_from_f32,
-                      f32_from_bf16_bits, device_normal, device_history_standin)
+                      f32_from_bf16_bits, device_normal, device_history_standin, gat_heads,
+                      attention_vectors_f32)
 
 __all__ = [
     "CONFIGS", "get_config", "Graph", "sbm_graph", "chung_lu_planted_graph",
     "ring_graph", "make_graph", "cached_graph", "substreams", "normal_f32",
     "glorot_uniform_f32", "labels_i32", "predictor_params_f32",
     "history_standin_f32", "bf16_bits_from_f32", "f32_from_bf16_bits",
-    "chung_lu_partition_rows", "device_normal", "device_history_standin",
+    "chung_lu_partition_rows", "device_normal", "device_history_standin", "gat_heads",
+    "attention_vectors_f32",
 ]

@@ -88,6 +88,23 @@ def predictor_params_f32(ss, d, d_s, scale_g=0.5):
     return dict(Wx=Wx, Wh=Wh, b=b, Wg=Wg)
 
 
+def gat_heads(dims):
+    """Heads per layer of the attention backbone for feature widths `dims`: four
+    heads on hidden layers whose width allows it (a multiple of 16), one head on
+    the last layer (the usual classifier) and otherwise."""
+    L = len(dims) - 1
+    return [4 if l < L - 1 and dims[l + 1] % 16 == 0 else 1 for l in range(L)]
+
+
+def attention_vectors_f32(ss, heads, d_head):
+    """(a_dst, a_src), each [heads, d_head] ~ N(0, 1 / d_head): scores of unit-scale
+    rows then have unit scale, so the attention is neither flat nor one-hot."""
+    r = _rng(ss)
+    std = 1.0 / np.sqrt(d_head)
+    return (r.normal(0.0, std, size=(heads, d_head)).astype(np.float32),
+            r.normal(0.0, std, size=(heads, d_head)).astype(np.float32))
+
+
 def history_standin_f32(ss, rows, cols, tau, noise_std, ld=None):
     """tau history slots [rows, ld] for sizes where nobody can afford the
     true full-graph embeddings: a shared base max(0, N(0,1)) (the shape of a
