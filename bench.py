@@ -43,7 +43,8 @@ MEASURED_TRAFFIC_BYTES = {      # profiles/large_step_hbm_traffic.md, average ov
 
 KERNEL_OF_CLASS = {"spmm": "spmm_stream_kernel", "gather": "row_copy_vec_kernel (gather)",
                    "push": "row_copy_vec_kernel (scatter)", "dense_fwd": "mx::gemm_kernel",
-                   "loss": "xent_grad_kernel", "gather_add": "row_gather_add_kernel"}
+                   "loss": "xent_grad_kernel", "gather_add": "row_gather_add_kernel",
+                   "gat_fwd": "gat_fwd_kernel", "gat_scores": "gat_scores_kernel"}
 
 
 class CallTimers:
@@ -111,6 +112,9 @@ def main():
                     help="also launch one plain row copy of known size (1 GiB read + 1 GiB "
                          "written, identity ids) so that a rocprofv3 --pmc run of this command "
                          "can scale FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--backbone", default="gcn", choices=["gcn", "gat"],
+                    help="gcn: the normalised-adjacency aggregation (the headline); gat: the graph "
+                         "attention backbone (edge softmax aggregation, three edge passes per layer)")
     ap.add_argument("--cold", action="store_true",
                     help="rewrite a 1 GiB buffer before every library call, so that no call finds "
                          "its inputs in the caches (for the workloads whose working set fits "
@@ -141,7 +145,8 @@ def main():
     timers = CallTimers(torch, flush)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
-                        predict_every=args.delta_t)
+                        predict_every=args.delta_t, backbone=args.backbone)
+    gat = args.backbone == "gat"
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
     dims, tau, d_s, L = wl.dims, wl.tau, wl.d_s, wl.L
@@ -177,7 +182,8 @@ def main():
     if args.cold:       # the flushes sit between the calls: count the calls alone
         ms_per_step = sum(c["total_ms"] for c in calls.values()) / args.steps
     gteps = edges / (ms_per_step * 1e-3) / 1e9
-    spmm_ms = sum(c["total_ms"] for k, c in calls.items() if k.startswith("spmm_")) / args.steps
+    spmm_ms = sum(c["total_ms"] for k, c in calls.items()
+                  if k.startswith(("spmm_", "gat_fwd_", "gat_bwd_"))) / args.steps
     loss = float(step.loss.item())
     log("ms/step %.3f  GTEPS %.2f  loss %.5f" % (ms_per_step, gteps, loss))
 
@@ -208,9 +214,24 @@ def main():
         if l >= 1:
             add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]) + (
                 spmm_bytes(nnz_halo, n_h, dims[l]) if args.stale_grad else 0))
-        add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dims[l + 1])
-        add("dense_bwd", "dense_bwd_l%d" % l, "mfma",
-            (4.0 if l >= 1 else 2.0) * n_l * dims[l] * dims[l + 1])
+        if gat:      # the transform runs over local + halo rows; three edge passes per layer
+            K = step.heads[l]
+            dl = dims[l + 1]
+            add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * dl)
+            add("dense_bwd", "dense_bwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * dl)
+            add("dense_bwd", "dense_bwd_in_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dl)
+            add("gat_scores", "gat_scores_l%d" % l, "hbm", n_bar * (dl * s + 4 * K) + n_l * 4 * K)
+            add("gat_fwd", "gat_fwd_l%d" % l, "hbm",
+                nnz * (4 + 4 * K + dl * s) + n_l * (8 + dl * s + 12 * K))
+            add("gat_bwd", "gat_bwd_l%d" % l, "hbm",
+                nnz * (4 + 4 * K + dl * s) + n_l * (8 + dl * s + 28 * K)          # destination side
+                + nnz * (4 + 16 * K + dl * s) + n_bar * (8 + 2 * dl * s + 8 * K)  # source side
+                + (3 * n_l * dl * s if l < L - 1 else 0)                          # masked gradient
+                + n_bar * (dl * s + 4 * K) + n_l * 4 * K)                         # attention vectors
+        else:
+            add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dims[l + 1])
+            add("dense_bwd", "dense_bwd_l%d" % l, "mfma",
+                (4.0 if l >= 1 else 2.0) * n_l * dims[l] * dims[l + 1])
         if l >= 1:
             add("push", "push_l%d" % l, "hbm", n_l * (2 * dims[l] * s + 4))
             add("push", "grad_push_l%d" % l, "hbm", n_h * (2 * dims[l] * s + 4))
@@ -245,7 +266,7 @@ def main():
     # made of several kernels, none of which outweighs the aggregation kernel (see the
     # rocprofv3 kernel statistics under profiles/), so they are listed in
     # roofline_all at call level and not eligible here.
-    single = [k for k in roof_all if k not in ("predict", "dense_bwd")]
+    single = [k for k in roof_all if k not in ("predict", "dense_bwd", "gat_bwd")]
     dominant = max(single, key=lambda k: roof_all[k]["ms_per_step"])
     roofline = dict(kernel=KERNEL_OF_CLASS.get(dominant, dominant), **roof_all[dominant])
 
@@ -346,7 +367,8 @@ def main():
         log("cpu oracle: skipped (this workload's inputs are drawn on the device)")
     elif not args.no_cpu_baseline:
         cpu = cpu_baseline(view, dims, tau, d_s, wl.X_host, wl.hist_host, wl.table_ids, wl.Ws,
-                           wl.omegas, wl.y, edges, bypass=args.bypass, log=log)
+                           wl.omegas, wl.y, edges, bypass=args.bypass, log=log,
+                           gat_attn=wl.attn if gat else None)
 
     out = {
         "metric": "GTEPS aggregated (CSR entries aggregated per second over one partition's "
@@ -354,7 +376,7 @@ def main():
         "value": round(gteps, 3), "unit": "GTEPS", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "graph": cfg["kind"], "N": g.N,
+        "config": {"workload": args.workload, "backbone": args.backbone, "graph": cfg["kind"], "N": g.N,
                    "partition": "%d of %d" % (cfg["part"], cfg["n_parts"]),
                    "n_local": n_l, "n_halo": n_h, "nnz": nnz, "nnz_local_local": nnz_loc,
                    "dims": dims, "tau": tau, "d_s": d_s,
@@ -380,7 +402,7 @@ def main():
 
 
 def cpu_baseline(view, dims, tau, d_s, X_host, hist_host, table_ids, Ws, omegas, y, edges,
-                 bypass, log, sample_rows=65536, sample_nodes=524288):
+                 bypass, log, sample_rows=65536, sample_nodes=524288, gat_attn=None):
     """Time the oracle (as it stands) on a row sample of every call of the step
     and extrapolate each call by rows_total / rows_sampled (rows of every call
     are independent of one another)."""
@@ -427,6 +449,8 @@ def cpu_baseline(view, dims, tau, d_s, X_host, hist_host, table_ids, Ws, omegas,
                 t0 = time.perf_counter()
                 orc.predictor_hop(sub, S, omegas[l]["Wg"])
                 est += (time.perf_counter() - t0) * f_halo
+        if gat_attn is not None:
+            return est + run_gat(Hbars), prep
         g = None
         aggs = []
         for l in range(L):
@@ -450,6 +474,42 @@ def cpu_baseline(view, dims, tau, d_s, X_host, hist_host, table_ids, Ws, omegas,
                 g = orc.spmm_bwd_rows(view, dA_full, rows)
                 est += (time.perf_counter() - t0) * f_rows
         return est, prep
+
+    def run_gat(Hbars):
+        """The attention backbone's calls: transform and scores on the node sample,
+        the edge passes on the row sample (stand-in values where a call needs the
+        rows of all nodes: only the time matters here)."""
+        from oracle import gat_oracle as gat
+        est = 0.0
+        srng = np.random.default_rng(4321)
+        for l in range(L):
+            a_dst, a_src = gat_attn[l]
+            K = a_dst.shape[0]
+            dl = dims[l + 1]
+            t0 = time.perf_counter()
+            Zs = Hbars[l][nodes].astype(np.float64) @ Ws[l].astype(np.float64)
+            gat.gat_scores(Zs, a_dst, a_src)
+            est += (time.perf_counter() - t0) * f_nodes
+            Zfull = srng.standard_normal((n_bar, dl)).astype(np.float32).astype(np.float64)
+            el = srng.standard_normal((n_l, K))
+            er = srng.standard_normal((n_bar, K))
+            dOUT = np.zeros((n_l, dl))
+            dOUT[rows] = srng.standard_normal((len(rows), dl))
+            t0 = time.perf_counter()
+            gat.gat_aggregate_fwd(view, Zfull, el, er, 0.2, rows=rows)
+            gat.gat_aggregate_bwd(view, Zfull, el, er, 0.2, dOUT, rows=rows)
+            est += (time.perf_counter() - t0) * f_rows
+            t0 = time.perf_counter()
+            Hbars[l][nodes].astype(np.float64).T @ Zs                       # dW over local + halo rows
+            est += (time.perf_counter() - t0) * f_nodes
+            if l >= 1:
+                t0 = time.perf_counter()
+                dOUT[rows] @ Ws[l].astype(np.float64).T                     # dH_in over the local rows
+                est += (time.perf_counter() - t0) * f_rows
+        t0 = time.perf_counter()
+        orc.loss_and_grad(srng.standard_normal((len(rows), dims[L])), y[rows])
+        est += (time.perf_counter() - t0) * f_rows
+        return est
 
     t0 = time.time()
     if threadpool_limits is not None:

@@ -75,9 +75,10 @@ def gat_aggregate_fwd(view, Z, el, er, slope, rows=None):
     return out
 
 
-def gat_aggregate_bwd(view, Z, el, er, slope, dOUT):
+def gat_aggregate_bwd(view, Z, el, er, slope, dOUT, rows=None):
     """Backward of gat_aggregate_fwd for given el, er (treated as inputs):
     returns (dZ_agg [n_bar, d], d_el [n_local, K], d_er [n_bar, K]).
+    rows: only these local rows contribute (all of them by default).
 
     With dalpha_ij = <dOUT_i, Z_j> per head: de_ij = alpha_ij (dalpha_ij - sum_k
     alpha_ik dalpha_ik) (softmax), ds_ij = de_ij LeakyReLU'(s_ij), d_el_i = sum_j
@@ -91,7 +92,7 @@ def gat_aggregate_bwd(view, Z, el, er, slope, dOUT):
     dZ = np.zeros((n_bar, K, F), dtype=np.float64)
     d_el = np.zeros((n_local, K), dtype=np.float64)
     d_er = np.zeros((n_bar, K), dtype=np.float64)
-    for i in range(n_local):
+    for i in (range(n_local) if rows is None else rows):
         cols, s, alpha = gat_row_attention(view, i, el, er, slope)
         zc = Z[cols].reshape(-1, K, F)
         dalpha = np.einsum("kf,jkf->jk", G[i], zc)

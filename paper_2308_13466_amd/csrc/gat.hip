@@ -43,13 +43,26 @@ constexpr int kLongRow = 1024;
 constexpr int kU = 8;
 constexpr int kMaxD = 256;     // 64 lanes x 4 elements
 
-// four consecutive elements of a row as fp32
+// Four consecutive elements of a row: the bits as loaded (nothing may touch them before
+// all gathers of a round have been issued, or each load is waited for on its own) ...
 template <int ES>
-__device__ __forceinline__ f32x4 load4(const unsigned char* p) {
+struct Raw4 {
+  typedef f32x4 T;
+};
+template <>
+struct Raw4<2> {
+  typedef u32x2 T;
+};
+template <int ES>
+__device__ __forceinline__ typename Raw4<ES>::T load_raw4(const unsigned char* p) {
+  return *reinterpret_cast<const typename Raw4<ES>::T*>(p);
+}
+// ... and as fp32
+template <int ES>
+__device__ __forceinline__ f32x4 widen4(typename Raw4<ES>::T w) {
   if constexpr (ES == 4) {
-    return *reinterpret_cast<const f32x4*>(p);
+    return w;
   } else {
-    const u32x2 w = *reinterpret_cast<const u32x2*>(p);
     const uint32_t w0 = w.x, w1 = w.y;
     f32x4 r;
     r.x = __builtin_bit_cast(float, w0 << 16);
@@ -58,6 +71,10 @@ __device__ __forceinline__ f32x4 load4(const unsigned char* p) {
     r.w = __builtin_bit_cast(float, w1 & 0xffff0000u);
     return r;
   }
+}
+template <int ES>
+__device__ __forceinline__ f32x4 load4(const unsigned char* p) {
+  return widen4<ES>(load_raw4<ES>(p));
 }
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {   // two RNE bf16
@@ -215,11 +232,13 @@ __device__ __forceinline__ void wave_lds_fence() {
 // a gathered row, w the weights of that entry in LDS. `fold()`: called after the last entry of
 // each batch of 64: the callers sum a batch on its own and add it to the row's running sum
 // there, which keeps the chains of additions short on rows of thousands of entries.
-template <int ES, int NW, class Entry, class Feature, class Fold>
+template <int ES, int NW, int U, class Entry, class Feature, class Fold>
 __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_t s, int64_t e,
                                      int32_t* s_col, float* s_w, Entry&& entry, Feature&& feature,
                                      Fold&& fold) {
-  const bool clip = (a.ln.d & 3) != 0;
+  // rows whose width is not a whole number of chunks, or fewer chunks than lanes in a group:
+  // the lanes' shares are clipped to the row (lanes past it get zeros)
+  const bool clip = a.ln.d != (4 << a.ln.lg_g);
   for (int64_t base = s; base < e; base += kWave) {
     const int cnt = static_cast<int>(e - base < kWave ? e - base : kWave);
     int32_t c = -1;
@@ -227,29 +246,40 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
     const bool ok = static_cast<uint64_t>(static_cast<uint32_t>(c)) < static_cast<uint64_t>(a.n_x_rows);
     if (!ok) c = 0;
     wave_lds_fence();               // the previous batch's reads of LDS are done
-    entry(c, ok, s_w + L.lane * NW);
     s_col[L.lane] = c;
     wave_lds_fence();
-    for (int j0 = 0; j0 < cnt; j0 += L.ng * kU) {
-      f32x4 x[kU];
-      int idc[kU];
-      bool valid[kU];
+    typename Raw4<ES>::T x[U];
+    int idc[U];
+    bool valid[U];
+    auto issue = [&](int j0) __attribute__((always_inline)) {
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
+      for (int u = 0; u < U; ++u) {
         const int idx = j0 + u * L.ng + L.grp;
         valid[u] = idx < cnt;
         idc[u] = valid[u] ? idx : cnt - 1;     // past the end: re-read the last row, weight 0
         const int32_t cj = s_col[idc[u]];
-        if (L.col_ok)
-          x[u] = load4<ES>(a.X + static_cast<int64_t>(cj) * a.ld_x + static_cast<int64_t>(L.el0) * ES);
-        else
-          x[u] = f32x4(0.f);
+        // lanes past the row's width re-read its first chunk; their sums are never stored
+        x[u] = load_raw4<ES>(a.X + static_cast<int64_t>(cj) * a.ld_x +
+                             static_cast<int64_t>(L.col_ok ? L.el0 : 0) * ES);
       }
+    };
+    auto consume = [&]() __attribute__((always_inline)) {
 #pragma unroll
-      for (int u = 0; u < kU; ++u) {
-        if (clip) x[u] = clip4(x[u], L.left);
-        feature(x[u], s_w + idc[u] * NW, valid[u]);
+      for (int u = 0; u < U; ++u) {
+        f32x4 xw = widen4<ES>(x[u]);
+        if (clip) xw = clip4(xw, L.left);
+        feature(xw, s_w + idc[u] * NW, valid[u]);
       }
+    };
+    // the first round of gathers needs the ids only: it is in flight while the entry phase
+    // reads the per-node scores and computes the weights
+    issue(0);
+    entry(c, ok, s_w + L.lane * NW);
+    wave_lds_fence();
+    consume();
+    for (int j0 = L.ng * U; j0 < cnt; j0 += L.ng * U) {
+      issue(j0);
+      consume();
     }
     fold();
   }
@@ -269,9 +299,17 @@ __device__ __forceinline__ int64_t uniform64(int64_t v) {
 // scalar that all lanes share by construction. (Drawing rows from a counter with one
 // lane and broadcasting the result let the compiler thread that lane's branch into the
 // neighbouring one-lane store of the previous iteration and split the wavefront for good.)
-__device__ __forceinline__ void flag_long_rows(const WalkArgs& a, int64_t row0, int nr, int* is_long) {
-  for (int t = threadIdx.x; t < nr; t += kWaves * kWave)
-    is_long[t] = a.row_end[row0 + t] - a.row_begin[row0 + t] > kLongRow ? 1 : 0;
+struct RowSpans {
+  int64_t begin[kRowsPerBlock], end[kRowsPerBlock];
+  int is_long[kRowsPerBlock];
+};
+__device__ __forceinline__ void flag_long_rows(const WalkArgs& a, int64_t row0, int nr, RowSpans* sp) {
+  for (int t = threadIdx.x; t < nr; t += kWaves * kWave) {
+    const int64_t b = a.row_begin[row0 + t], e = a.row_end[row0 + t];
+    sp->begin[t] = b;
+    sp->end[t] = e;
+    sp->is_long[t] = e - b > kLongRow ? 1 : 0;
+  }
   __syncthreads();
 }
 
@@ -285,40 +323,50 @@ __device__ __forceinline__ void piece_of(int64_t s, int64_t e, int wave, int64_t
 
 // ---------------------------------------------------------------- attention scores
 // el[r, k] = <a_dst[k], Z[r, k]> (r < n_dst), er[r, k] = <a_src[k], Z[r, k]> (r < n)
+constexpr int kScoreRows = 8;   // row slots per wavefront (each slot: 64/G rows)
 template <int ES>
 __global__ __launch_bounds__(256) void gat_scores_kernel(const unsigned char* Z, int64_t ld_z, int64_t n,
                                                         int64_t n_dst, int heads, Lanes ln,
                                                         const float* a_dst, const float* a_src,
                                                         float* el, float* er) {
   const LaneIds L = lane_ids(ln, heads);
-  const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * L.ng + L.grp;
-  f32x4 z(0.f), ad(0.f), as(0.f);
-  if (row < n && L.col_ok) {
-    z = clip4(load4<ES>(Z + row * ld_z + static_cast<int64_t>(L.el0) * ES), L.left);
-    if (L.left > 0) { ad.x = a_dst[L.el0]; as.x = a_src[L.el0]; }
-    if (L.left > 1) { ad.y = a_dst[L.el0 + 1]; as.y = a_src[L.el0 + 1]; }
-    if (L.left > 2) { ad.z = a_dst[L.el0 + 2]; as.z = a_src[L.el0 + 2]; }
-    if (L.left > 3) { ad.w = a_dst[L.el0 + 3]; as.w = a_src[L.el0 + 3]; }
+  const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6)) * kScoreRows * L.ng + L.grp;
+  f32x4 ad(0.f), as(0.f);
+  if (L.left > 0) { ad.x = a_dst[L.el0]; as.x = a_src[L.el0]; }
+  if (L.left > 1) { ad.y = a_dst[L.el0 + 1]; as.y = a_src[L.el0 + 1]; }
+  if (L.left > 2) { ad.z = a_dst[L.el0 + 2]; as.z = a_src[L.el0 + 2]; }
+  if (L.left > 3) { ad.w = a_dst[L.el0 + 3]; as.w = a_src[L.el0 + 3]; }
+  typename Raw4<ES>::T raw[kScoreRows];
+#pragma unroll
+  for (int q = 0; q < kScoreRows; ++q) {
+    int64_t row = row0 + q * L.ng;
+    if (row >= n) row = n - 1;            // n > 0: checked by the host
+    raw[q] = load_raw4<ES>(Z + row * ld_z + static_cast<int64_t>(L.col_ok ? L.el0 : 0) * ES);
   }
-  float pd = dot4(z, ad), ps = dot4(z, as);
-  for (int b = 0; b < ln.lg_lh; ++b) {
-    pd += __shfl_xor(pd, 1 << b);
-    ps += __shfl_xor(ps, 1 << b);
-  }
-  if (row < n && (L.gl & ((1 << ln.lg_lh) - 1)) == 0 && L.h < heads) {
-    er[row * heads + L.h] = ps;
-    if (row < n_dst) el[row * heads + L.h] = pd;
+#pragma unroll
+  for (int q = 0; q < kScoreRows; ++q) {
+    const int64_t row = row0 + q * L.ng;
+    const f32x4 z = clip4(widen4<ES>(raw[q]), L.left);
+    float pd = dot4(z, ad), ps = dot4(z, as);
+    for (int b = 0; b < ln.lg_lh; ++b) {
+      pd += __shfl_xor(pd, 1 << b);
+      ps += __shfl_xor(ps, 1 << b);
+    }
+    if (row < n && (L.gl & ((1 << ln.lg_lh) - 1)) == 0 && L.h < heads) {
+      er[row * heads + L.h] = ps;
+      if (row < n_dst) el[row * heads + L.h] = pd;
+    }
   }
 }
 
 // ---------------------------------------------------------------- forward
 // H[i] = act(sum_j alpha_ij Z_j), stats[i, k] = (max_j e_ij, 1 / sum_j exp(e_ij - max))
 template <int ES, int K>
-__global__ __launch_bounds__(kWaves * kWave) void gat_fwd_kernel(WalkArgs a, const float* el,
+__global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, const float* el,
                                                                 const float* er, int relu,
                                                                 unsigned char* Y, int64_t ld_y,
                                                                 float* stats) {
-  __shared__ int is_long[kRowsPerBlock];
+  __shared__ RowSpans sp;
   __shared__ int32_t s_col[kWaves][kWave];
   __shared__ float s_w[kWaves][kWave * K];
   constexpr int HDR = (2 * K + 3) / 4 * 4;
@@ -327,7 +375,7 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_fwd_kernel(WalkArgs a, con
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock;
   const int nr = static_cast<int>(a.n_rows - row0 < kRowsPerBlock ? a.n_rows - row0 : kRowsPerBlock);
-  flag_long_rows(a, row0, nr, is_long);
+  flag_long_rows(a, row0, nr, &sp);
 
   float m[K], l[K], eli[K];
   f32x4 acc;
@@ -392,11 +440,11 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_fwd_kernel(WalkArgs a, con
 
   // ---- short rows
   for (int r = wave; r < nr; r += kWaves) {
-    if (__builtin_amdgcn_readfirstlane(is_long[r])) continue;
+    if (__builtin_amdgcn_readfirstlane(sp.is_long[r])) continue;
     const int64_t row = row0 + r;
-    const int64_t s = uniform64(a.row_begin[row]), e = uniform64(a.row_end[row]);
+    const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, K>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, K, kU>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
     float ll[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ll[k] = wave_sum(l[k]);
@@ -405,13 +453,13 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_fwd_kernel(WalkArgs a, con
   __syncthreads();
   // ---- long rows: a contiguous piece per wavefront, combined in wavefront order
   for (int r = 0; r < nr; ++r) {
-    if (!__builtin_amdgcn_readfirstlane(is_long[r])) continue;   // the same for every wavefront
+    if (!__builtin_amdgcn_readfirstlane(sp.is_long[r])) continue;   // the same for every wavefront
     const int64_t row = row0 + r;
-    const int64_t s = uniform64(a.row_begin[row]), e = uniform64(a.row_end[row]);
+    const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, K>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
     const f32x4 part = group_sum(acc, a.ln);
     float lk[K];
 #pragma unroll
@@ -453,10 +501,10 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_fwd_kernel(WalkArgs a, con
 //   d_el_i = sum_j alpha_ij LeakyReLU'(s_ij) (<g_i, Z_j> - D_i)
 // and rowstat[i, k] = (el, max, 1/sum, D) for the source-side pass.
 template <int ES, int K>
-__global__ __launch_bounds__(kWaves * kWave) void gat_bwd_dst_kernel(
+__global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     WalkArgs a, const float* el, const float* er, const float* stats, const unsigned char* dOUT,
     int64_t ld_g, float* d_el, f32x4* rowstat) {
-  __shared__ int is_long[kRowsPerBlock];
+  __shared__ RowSpans sp;
   __shared__ int32_t s_col[kWaves][kWave];
   __shared__ float s_w[kWaves][kWave * 2 * K];
   __shared__ float s_part[kWaves][3 * K];
@@ -464,7 +512,7 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_dst_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock;
   const int nr = static_cast<int>(a.n_rows - row0 < kRowsPerBlock ? a.n_rows - row0 : kRowsPerBlock);
-  flag_long_rows(a, row0, nr, is_long);
+  flag_long_rows(a, row0, nr, &sp);
 
   float eli[K], mi[K], inv[K], w1s[K];
   f32x4 g;
@@ -525,11 +573,11 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_dst_kernel(
   };
 
   for (int r = wave; r < nr; r += kWaves) {
-    if (__builtin_amdgcn_readfirstlane(is_long[r])) continue;
+    if (__builtin_amdgcn_readfirstlane(sp.is_long[r])) continue;
     const int64_t row = row0 + r;
-    const int64_t s = uniform64(a.row_begin[row]), e = uniform64(a.row_end[row]);
+    const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, 2 * K>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, kU>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
     float ws[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ws[k] = wave_sum(w1s[k]);
@@ -537,13 +585,13 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_dst_kernel(
   }
   __syncthreads();
   for (int r = 0; r < nr; ++r) {
-    if (!__builtin_amdgcn_readfirstlane(is_long[r])) continue;   // the same for every wavefront
+    if (!__builtin_amdgcn_readfirstlane(sp.is_long[r])) continue;   // the same for every wavefront
     const int64_t row = row0 + r;
-    const int64_t s = uniform64(a.row_begin[row]), e = uniform64(a.row_end[row]);
+    const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, 2 * K>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
     const float D = head_sum(accD, a.ln), t1 = head_sum(acc1, a.ln);
     float wk[K];
 #pragma unroll
@@ -577,12 +625,12 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_dst_kernel(
 // a neighbour; gathered g_i = dOUT_i and rowstat_i), j = row_off + r:
 //   d_er_j = sum_i alpha_ij LeakyReLU'(s_ij) (<g_i, Z_j> - D_i)
 //   dZ_j   = sum_i alpha_ij g_i + d_er_j a_src + d_el_j a_dst   (the last term for local j)
-template <int ES, int K>
-__global__ __launch_bounds__(kWaves * kWave) void gat_bwd_src_kernel(
+template <int ES, int K, int U>
+__global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_kernel(
     WalkArgs a, int64_t row_off, int64_t n_local, const float* er, const f32x4* rowstat,
     const unsigned char* Z, int64_t ld_z, const float* d_el, const float* a_dst, const float* a_src,
     unsigned char* dZ, int64_t ld_dz, float* d_er) {
-  __shared__ int is_long[kRowsPerBlock];
+  __shared__ RowSpans sp;
   __shared__ int32_t s_col[kWaves][kWave];
   __shared__ float s_w[kWaves][kWave * 2 * K];
   constexpr int HDR = (2 * K + 3) / 4 * 4;
@@ -591,7 +639,7 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_src_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock;
   const int nr = static_cast<int>(a.n_rows - row0 < kRowsPerBlock ? a.n_rows - row0 : kRowsPerBlock);
-  flag_long_rows(a, row0, nr, is_long);
+  flag_long_rows(a, row0, nr, &sp);
 
   float erj[K], wds[K];
   f32x4 z, acc;
@@ -656,11 +704,11 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_src_kernel(
   };
 
   for (int r = wave; r < nr; r += kWaves) {
-    if (__builtin_amdgcn_readfirstlane(is_long[r])) continue;
+    if (__builtin_amdgcn_readfirstlane(sp.is_long[r])) continue;
     const int64_t row = row0 + r;
-    const int64_t s = uniform64(a.row_begin[row]), e = uniform64(a.row_end[row]);
+    const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row_off + row);
-    walk<ES, 2 * K>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, U>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
     float wd[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) wd[k] = wave_sum(wds[k]);
@@ -668,13 +716,13 @@ __global__ __launch_bounds__(kWaves * kWave) void gat_bwd_src_kernel(
   }
   __syncthreads();
   for (int r = 0; r < nr; ++r) {
-    if (!__builtin_amdgcn_readfirstlane(is_long[r])) continue;   // the same for every wavefront
+    if (!__builtin_amdgcn_readfirstlane(sp.is_long[r])) continue;   // the same for every wavefront
     const int64_t row = row0 + r;
-    const int64_t s = uniform64(a.row_begin[row]), e = uniform64(a.row_end[row]);
+    const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row_off + row);
-    walk<ES, 2 * K>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, U>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
     const f32x4 part = group_sum(acc, a.ln);
     const float t1 = head_sum(accd, a.ln);
     float wk[K];
@@ -761,14 +809,26 @@ __global__ __launch_bounds__(256) void gat_attn_grad_kernel(const unsigned char*
   }
 }
 
+// 32 outputs per workgroup; 8 slices of the workgroups' partial sums are added side by
+// side, then the slices in order
 __global__ __launch_bounds__(256) void gat_attn_finish_kernel(const float* part, int64_t n_blocks, int32_t d,
                                                              float* da_dst, float* da_src) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
-  if (t >= 2 * d) return;
-  const int which = t / d, f = t - which * d;
+  __shared__ float red[8][32];
+  const int c = threadIdx.x & 31, sl = threadIdx.x >> 5;
+  const int t = blockIdx.x * 32 + c;           // output index in [0, 2 d)
   float s = 0.f;
-  for (int64_t b = 0; b < n_blocks; ++b) s += part[(b * 2 + which) * d + f];
-  (which == 0 ? da_dst : da_src)[f] = s;
+  if (t < 2 * d) {
+    const int which = t / d, f = t - which * d;
+    for (int64_t b = sl; b < n_blocks; b += 8) s += part[(b * 2 + which) * d + f];
+  }
+  red[sl][c] = s;
+  __syncthreads();
+  if (sl == 0 && t < 2 * d) {
+    float tot = 0.f;
+    for (int k = 0; k < 8; ++k) tot += red[k][c];
+    const int which = t / d, f = t - which * d;
+    (which == 0 ? da_dst : da_src)[f] = tot;
+  }
 }
 
 // ---------------------------------------------------------------- host side
@@ -895,7 +955,7 @@ sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes l
       // columns themselves (the local block's pattern is symmetric)
     const WalkArgs a{pv->rowptr, pv->split, pv->col, n_l, n_l, dOUT, ld_g, ln, slope};
     const int64_t gb = (n_l + kRowsPerBlock - 1) / kRowsPerBlock;
-    gat_bwd_src_kernel<ES, K><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
+    gat_bwd_src_kernel<ES, K, kU><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
         a, 0, n_l, er, rowstat, static_cast<const unsigned char*>(Z), ld_z * ES, d_el, a_dst, a_src,
         static_cast<unsigned char*>(dZ), ld_dz * ES, d_er);
     if ((st = sat::check_launch()) != SAT_OK) return st;
@@ -904,7 +964,9 @@ sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes l
     const WalkArgs a{pv->h_colptr, pv->h_colptr + 1, pv->h_row, n_h, n_l, dOUT, ld_g, ln, slope};
     const int64_t gb = (n_h + kRowsPerBlock - 1) / kRowsPerBlock;
     if (gb > INT32_MAX) return SAT_EUNSUPPORTED;
-    gat_bwd_src_kernel<ES, K><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
+    // rows of a few entries each: what counts is the number of rows in flight, so this
+    // instance keeps 2 gathers in flight per group and fits twice as many wavefronts
+    gat_bwd_src_kernel<ES, K, 2><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
         a, n_l, n_l, er, rowstat, static_cast<const unsigned char*>(Z), ld_z * ES, d_el, a_dst, a_src,
         static_cast<unsigned char*>(dZ), ld_dz * ES, d_er);
     if ((st = sat::check_launch()) != SAT_OK) return st;
@@ -915,7 +977,7 @@ sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes l
     gat_attn_grad_kernel<ES><<<dim3(static_cast<unsigned>(nb)), dim3(256), 0, s>>>(
         static_cast<const unsigned char*>(Z), ld_z * ES, n_bar, n_l, K, ln, d_el, d_er, rpb, part);
     if ((st = sat::check_launch()) != SAT_OK) return st;
-    gat_attn_finish_kernel<<<dim3(static_cast<unsigned>((2 * d + 255) / 256)), dim3(256), 0, s>>>(
+    gat_attn_finish_kernel<<<dim3(static_cast<unsigned>((2 * d + 31) / 32)), dim3(256), 0, s>>>(
         part, nb, d, da_dst, da_src);
     if ((st = sat::check_launch()) != SAT_OK) return st;
   }
@@ -938,7 +1000,7 @@ extern "C" sat_status sat_gat_scores(const void* Z, int64_t ld_z, int64_t n, int
   if ((st = check_dense(Z, n, ld_z, ln.d, es)) != SAT_OK) return st;
   if (n == 0) return SAT_OK;
   if (!a_dst || !a_src || !er || (n_dst > 0 && !el)) return SAT_EINVAL;
-  const int64_t rows_per_block = 4 * (kWave >> ln.lg_g);
+  const int64_t rows_per_block = 4 * kScoreRows * (kWave >> ln.lg_g);
   const int64_t gb = (n + rows_per_block - 1) / rows_per_block;
   if (gb > INT32_MAX) return SAT_EUNSUPPORTED;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1028,7 +1090,7 @@ extern "C" sat_status sat_gat_aggregate_bwd(const sat_part_view* pv, const void*
   hipStream_t s = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
   if (n_l == 0) {   // no rows, hence no halo rows either: only the attention gradients, zero
-    gat_attn_finish_kernel<<<dim3(static_cast<unsigned>((2 * ln.d + 255) / 256)), dim3(256), 0, s>>>(
+    gat_attn_finish_kernel<<<dim3(static_cast<unsigned>((2 * ln.d + 31) / 32)), dim3(256), 0, s>>>(
         reinterpret_cast<const float*>(ws), 0, ln.d, da_dst, da_src);
     return sat::check_launch();
   }

@@ -35,11 +35,14 @@ def _upload(a, bf16, dev):
 
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
-                   keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1):
+                   keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
+                   backbone="gcn"):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
     of the history tables) and run the stale-gradient term of the backward.
+    backbone: "gcn" (normalised-adjacency aggregation) or "gat" (graph attention; heads per
+    layer from sat_synth.gat_heads, attention vectors from sat_synth.attention_vectors_f32).
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
     host copies kept for the tests hold the rounded values the device holds.
 
@@ -126,9 +129,21 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     gt = None
     if grad_tables:
         gt = [None] + [[torch.zeros_like(hist_d[l][0]) for _ in range(2)] for l in range(1, L)]
-    step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
-                         fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
-                         grad_tables=gt, predict_every=predict_every)
+    attn = None
+    if backbone == "gat":
+        from .step_gat import GatPartitionStep
+        heads = syn.gat_heads(dims)
+        ass = ss["misc"].spawn(L)
+        attn = [syn.attention_vectors_f32(ass[l], heads[l], dims[l + 1] // heads[l]) for l in range(L)]
+        attn_d = [(torch.from_numpy(a.reshape(-1)).to(dev), torch.from_numpy(b.reshape(-1)).to(dev),
+                   heads[l]) for l, (a, b) in enumerate(attn)]
+        step = GatPartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, attn_d, preds, y_d, tau,
+                                timers=timers, dtype=B.BF16 if bf16 else B.F32,
+                                predict_every=predict_every)
+    else:
+        step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
+                             fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
+                             grad_tables=gt, predict_every=predict_every)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))
@@ -138,4 +153,5 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     w.dims, w.tau, w.d_s, w.L, w.ld, w.dtype = dims, tau, d_s, L, ld, dtype
     w.X_host, w.hist_host, w.table_ids, w.Ws, w.omegas, w.y = X_host, hist_host, table_ids, Ws, omegas, y
     w.device_keep = (keep, X_d, hist_d, ids_d, Ws_d, y_d)
+    w.backbone, w.attn = backbone, attn
     return w
