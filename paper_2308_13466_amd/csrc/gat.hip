@@ -40,7 +40,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 constexpr int kWaves = 8;
 constexpr int kRowsPerBlock = 64;
 constexpr int kLongRow = 1024;
-constexpr int kU = 8;
+constexpr int kU = 8;         // gathers in flight per lane group (more of them for the 8-byte
+                             // lane shares of bf16 rows spilled registers and ran slower)
 constexpr int kMaxD = 256;     // 64 lanes x 4 elements
 
 // Four consecutive elements of a row: the bits as loaded (nothing may touch them before
@@ -249,26 +250,31 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
     s_col[L.lane] = c;
     wave_lds_fence();
     typename Raw4<ES>::T x[U];
-    int idc[U];
-    bool valid[U];
+    // entry handled in slot u of the round that starts at j0 (past the end: the last
+    // entry again, with weight 0); recomputed where it is needed rather than kept
+    auto slot = [&](int j0, int u, bool& valid) __attribute__((always_inline)) {
+      const int idx = j0 + u * L.ng + L.grp;
+      valid = idx < cnt;
+      return valid ? idx : cnt - 1;
+    };
     auto issue = [&](int j0) __attribute__((always_inline)) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int idx = j0 + u * L.ng + L.grp;
-        valid[u] = idx < cnt;
-        idc[u] = valid[u] ? idx : cnt - 1;     // past the end: re-read the last row, weight 0
-        const int32_t cj = s_col[idc[u]];
+        bool valid;
+        const int32_t cj = s_col[slot(j0, u, valid)];
         // lanes past the row's width re-read its first chunk; their sums are never stored
         x[u] = load_raw4<ES>(a.X + static_cast<int64_t>(cj) * a.ld_x +
                              static_cast<int64_t>(L.col_ok ? L.el0 : 0) * ES);
       }
     };
-    auto consume = [&]() __attribute__((always_inline)) {
+    auto consume = [&](int j0) __attribute__((always_inline)) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
+        bool valid;
+        const int idc = slot(j0, u, valid);
         f32x4 xw = widen4<ES>(x[u]);
         if (clip) xw = clip4(xw, L.left);
-        feature(xw, s_w + idc[u] * NW, valid[u]);
+        feature(xw, s_w + idc * NW, valid);
       }
     };
     // the first round of gathers needs the ids only: it is in flight while the entry phase
@@ -276,10 +282,10 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
     issue(0);
     entry(c, ok, s_w + L.lane * NW);
     wave_lds_fence();
-    consume();
+    consume(0);
     for (int j0 = L.ng * U; j0 < cnt; j0 += L.ng * U) {
       issue(j0);
-      consume();
+      consume(j0);
     }
     fold();
   }

@@ -42,7 +42,10 @@ class GatPartitionStep(PartitionStep):
         self.AGG = None          # the GCN step's aggregates are not used
         self.dAGG = None
         self.Z = [torch.zeros((n_bar, self.ld[l + 1]), **act) for l in range(L)]
-        self.dZ = [torch.zeros((n_bar, self.ld[l + 1]), **act) for l in range(L)]
+        # dZ_l lives only between the two backward calls of layer l: one buffer for all layers
+        ld_max = max(self.ld[1:])
+        self._dZ_buf = torch.zeros(n_bar * ld_max, **act)
+        self.dZ = [self._dZ_buf[:n_bar * self.ld[l + 1]].view(n_bar, self.ld[l + 1]) for l in range(L)]
         self.el = [torch.zeros((n_l, self.heads[l]), **f32) for l in range(L)]
         self.er = [torch.zeros((n_bar, self.heads[l]), **f32) for l in range(L)]
         self.stats = [torch.zeros((n_l, self.heads[l], 2), **f32) for l in range(L)]

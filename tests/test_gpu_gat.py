@@ -287,8 +287,9 @@ def test_gat_partition_step_two_steps(env, name, bf16):
         for l in range(L):
             gr = ref["grads"][l]
             K, F = heads[l], dims[l + 1] // heads[l]
-            _compare_grad(gu, _download(gu, torch, step.dZ[l], dims[l + 1], bf16), gr["dZ"], rtol,
-                          "dZ layer %d step %d" % (l, t), exact)
+            if l == 0:   # the layers share one dZ buffer: layer 0's is what is left after the step
+                _compare_grad(gu, _download(gu, torch, step.dZ[l], dims[l + 1], bf16), gr["dZ"], rtol,
+                              "dZ layer %d step %d" % (l, t), exact)
             _compare_grad(gu, step.dW[l].cpu().numpy()[:, :dims[l + 1]], gr["dW"], rtol,
                           "dW layer %d step %d" % (l, t), exact)
             # the attention-vector gradients are sums over all rows of terms of either sign
