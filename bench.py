@@ -270,9 +270,9 @@ def main():
     dominant = max(single, key=lambda k: roof_all[k]["ms_per_step"])
     roofline = dict(kernel=KERNEL_OF_CLASS.get(dominant, dominant), **roof_all[dominant])
 
-    # ---- optional: one training step of the predictor of hidden layer 1 (fp32 storage only)
+    # ---- optional: one training step of the predictor of hidden layer 1
     ptrain = None
-    if args.predictor_train and not bf16 and not args.bypass and L >= 2:
+    if args.predictor_train and not args.bypass and L >= 2:
         from paper_2308_13466_amd import binding as B
         l = 1
         wsb = B.predictor_train_workspace_bytes(n_l, n_h, dims[l], d_s, tau)
@@ -287,7 +287,8 @@ def main():
         def train_once():
             B.predictor_grad(step.pv, pw, slots, slots[0].shape[0], slots[0].shape[1], step.table_ids,
                              step.Hbar[l], step.ld[l], None, grads["Wx"], grads["Wh"], grads["b"],
-                             grads["Wg"], ploss, workspace=ws, workspace_bytes=wsb, stream=st_ptr)
+                             grads["Wg"], ploss, dtype=B.BF16 if bf16 else B.F32, workspace=ws,
+                             workspace_bytes=wsb, stream=st_ptr)
             for k in grads:
                 B.sgd_update(keep_p[k], grads[k], grads[k].numel(), 1e-3, stream=st_ptr)
 

@@ -21,7 +21,8 @@
 //             the nodes (dense.hip), db as column sums (here), and the gradient
 //             of the previous hidden state (the feature transform, dense.hip).
 // Every reduction over nodes runs in a fixed order: results are run-to-run
-// identical. fp32 storage only.
+// identical. With bfloat16 storage (history tables and targets) everything computed here
+// stays fp32: the window's rows are widened on the way in.
 #include <math.h>
 
 #include "mx_tile.h"
@@ -101,11 +102,27 @@ __global__ __launch_bounds__(256) void finish_sum_kernel(const float* __restrict
   if (threadIdx.x == 0) out[0] = denominator ? s * scale / denominator[0] : s * scale;
 }
 
+// element i of a matrix stored as fp32 (ES = 4) or bfloat16 (ES = 2)
+template <int ES>
+__device__ __forceinline__ float elem(const void* p, int64_t i) {
+  if constexpr (ES == 4) {
+    return static_cast<const float*>(p)[i];
+  } else {
+    return __builtin_bit_cast(float, static_cast<uint32_t>(static_cast<const uint16_t*>(p)[i]) << 16);
+  }
+}
+
 // P [n, ld_p] holds pred on entry and d loss / d pred on exit:
 //   diff = pred - target;  P = 2 w diff / (d wsum);  part[b] = sum w diff^2 over the block's rows
 // wsum_dev: device scalar sum of the weights (weights given) or nullptr (wsum = n).
+// T (and N) hold elements of ES bytes. If N != nullptr the residual term has not been added
+// to P yet: pred = P + N[row(r)], row(r) = ids ? ids[r] : r (rows outside [0, n_rows_n) add 0).
+template <int ES>
 __global__ __launch_bounds__(256) void sq_error_kernel(float* __restrict__ P, int64_t ld_p,
-                                                       const float* __restrict__ T, int64_t ld_t,
+                                                       const void* __restrict__ T, int64_t ld_t,
+                                                       const void* __restrict__ N, int64_t ld_n,
+                                                       const int32_t* __restrict__ ids,
+                                                       int64_t n_rows_n,
                                                        const float* __restrict__ w,
                                                        const float* __restrict__ wsum_dev, int64_t n,
                                                        int d, float* __restrict__ part) {
@@ -117,14 +134,41 @@ __global__ __launch_bounds__(256) void sq_error_kernel(float* __restrict__ P, in
   float acc = 0.f;
   for (int64_t r = lo; r < hi; ++r) {
     const float wr = w ? w[r] : 1.0f;
+    int64_t nr = -1;
+    if (N) {
+      nr = ids ? static_cast<int64_t>(ids[r]) : r;
+      if (nr < 0 || nr >= n_rows_n) nr = -1;
+    }
     for (int c = threadIdx.x; c < d; c += 256) {
-      const float diff = P[r * ld_p + c] - T[r * ld_t + c];
+      float pred = P[r * ld_p + c];
+      if (nr >= 0) pred += elem<ES>(N, nr * ld_n + c);
+      const float diff = pred - elem<ES>(T, r * ld_t + c);
       acc += wr * diff * diff;
       P[r * ld_p + c] = k * wr * diff;
     }
   }
   const float s = block_sum_256(acc, sh);
   if (threadIdx.x == 0) part[blockIdx.x] = s;
+}
+
+// dst [n, ld_dst] fp32 = rows (ids ? ids[r] : r) of a bfloat16 table, widened (rows outside the
+// table: zeros)
+__global__ __launch_bounds__(256) void widen_rows_kernel(const uint16_t* __restrict__ src, int64_t ld_src,
+                                                         const int32_t* __restrict__ ids,
+                                                         int64_t n_src_rows, float* __restrict__ dst,
+                                                         int64_t ld_dst, int64_t n, int d) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int pairs = d / 2;                       // d % 8 == 0 here
+  if (idx >= n * pairs) return;
+  const int64_t r = idx / pairs;
+  const int c = 2 * static_cast<int>(idx - r * pairs);
+  int64_t sr = ids ? static_cast<int64_t>(ids[r]) : r;
+  uint32_t wv = 0;
+  if (sr >= 0 && sr < n_src_rows) wv = *reinterpret_cast<const uint32_t*>(src + sr * ld_src + c);
+  float2 o;
+  o.x = __builtin_bit_cast(float, wv << 16);
+  o.y = __builtin_bit_cast(float, wv & 0xffff0000u);
+  *reinterpret_cast<float2*>(dst + r * ld_dst + c) = o;
 }
 
 // One time step of the LSTM's back-propagation, element-wise over (node, hidden unit).
@@ -243,12 +287,12 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
   if (pv->n_local < 0 || pv->n_halo < 0 || pv->nnz < 0 || pv->nnz_halo < 0 || n_rows_slot < 0)
     return SAT_EINVAL;
   if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
-  if (dtype != SAT_F32) return SAT_EUNSUPPORTED;
   if (w->d <= 0 || w->tau < 1 || w->bypass) return SAT_EINVAL;
   if (w->tau > kMaxTau) return SAT_EUNSUPPORTED;
   if (w->d_s != 32 && w->d_s != 64) return SAT_EUNSUPPORTED;
   const int d = w->d, ds = w->d_s, tau = w->tau;
-  if ((d % 4) != 0) return SAT_EUNSUPPORTED;
+  const int es = dtype == SAT_BF16 ? 2 : 4;
+  if ((d % (16 / es)) != 0) return SAT_EUNSUPPORTED;
   const int64_t n_l = pv->n_local, n_h = pv->n_halo, n_bar = n_l + n_h;
   if (n_bar > INT32_MAX) return SAT_EUNSUPPORTED;
   if (!w->Wx || !w->Wh || !w->b || !w->Wg || !dWx || !dWh || !db || !dWg || !loss) return SAT_EINVAL;
@@ -258,7 +302,8 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
     if (!slots[s]) return SAT_EINVAL;
   if (!pv->rowptr || !pv->split || !pv->col || !pv->val) return SAT_EINVAL;
   if (n_h > 0 && (!pv->h_colptr || (pv->nnz_halo > 0 && (!pv->h_row || !pv->h_val)))) return SAT_EINVAL;
-  if (!sat::aligned16(target) || (ld_target % 4) != 0 || (ld_slot % 4) != 0) return SAT_EALIGN;
+  if (!sat::aligned16(target) || (ld_target % (16 / es)) != 0 || (ld_slot % (16 / es)) != 0)
+    return SAT_EALIGN;
   for (int s = 0; s < tau; ++s)
     if (!sat::aligned16(slots[s])) return SAT_EALIGN;
   if (!sat::aligned16(w->Wx) || !sat::aligned16(w->Wh) || !sat::aligned16(w->Wg) ||
@@ -280,14 +325,18 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
   sat_status rc;
 
   // ---- forward
-  rc = sat::launch_lstm_mx(slots, 4, tau, n_rows_slot, ld_slot, ids, n_bar, d, ds, w->Wx, w->Wh, w->b,
+  rc = sat::launch_lstm_mx(slots, es, tau, n_rows_slot, ld_slot, ids, n_bar, d, ds, w->Wx, w->Wh, w->b,
                            S, base + L.wsplit, st, save);
   if (rc != SAT_OK) return rc;
   rc = sat::launch_spmm(pv->rowptr, nullptr, pv->col, pv->val, S, ds, n_bar, aggS, ds, n_l, ds, 4,
                         nullptr, 0, pv->nnz, st);
   if (rc != SAT_OK) return rc;
-  rc = sat::launch_hop_product(aggS, n_l, ds, w->Wg, d, slots[tau - 1], ld_slot, ids, 0, n_rows_slot,
-                               pred, d, 4, st);
+  if (es == 4) {   // pred = newest rows + aggS Wg in one kernel
+    rc = sat::launch_hop_product(aggS, n_l, ds, w->Wg, d, slots[tau - 1], ld_slot, ids, 0, n_rows_slot,
+                                 pred, d, 4, st);
+  } else {         // bf16 tables: the product alone (fp32), the newest rows are added with the error
+    rc = sat_dense_fwd(aggS, ds, n_l, ds, d, w->Wg, d, SAT_ACT_IDENTITY, SAT_F32, pred, d, stream);
+  }
   if (rc != SAT_OK) return rc;
   const float* wsum_dev = nullptr;
   if (weight) {
@@ -295,8 +344,13 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
     finish_sum_kernel<<<dim3(1), dim3(256), 0, st>>>(part, kRedBlocks, 1.0f, nullptr, wsum);
     wsum_dev = wsum;
   }
-  sq_error_kernel<<<dim3(kRedBlocks), dim3(256), 0, st>>>(pred, d, static_cast<const float*>(target),
-                                                          ld_target, weight, wsum_dev, n_l, d, part);
+  if (es == 4)
+    sq_error_kernel<4><<<dim3(kRedBlocks), dim3(256), 0, st>>>(pred, d, target, ld_target, nullptr, 0, nullptr,
+                                                               0, weight, wsum_dev, n_l, d, part);
+  else
+    sq_error_kernel<2><<<dim3(kRedBlocks), dim3(256), 0, st>>>(pred, d, target, ld_target, slots[tau - 1],
+                                                               ld_slot, ids, n_rows_slot, weight, wsum_dev,
+                                                               n_l, d, part);
   if (weight)
     finish_sum_kernel<<<dim3(1), dim3(256), 0, st>>>(part, kRedBlocks, 1.0f / d, wsum, loss);
   else
@@ -328,13 +382,18 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
     // dWx += da^T x_s  (x_s: the slot's rows of the partition's nodes, local then halo)
     const void* xs = slots[s];
     int64_t ld_x = ld_slot;
-    if (ids) {
+    if (!ids && n_rows_slot < n_bar) return SAT_EINVAL;
+    if (es == 2) {   // the products below are fp32: widen the window's rows on the way
+      widen_rows_kernel<<<blocks_for(n_bar * (d / 2)), dim3(256), 0, st>>>(
+          static_cast<const uint16_t*>(slots[s]), ld_slot, ids, n_rows_slot, xwin, d, n_bar, d);
+      if ((rc = sat::check_launch()) != SAT_OK) return rc;
+      xs = xwin;
+      ld_x = d;
+    } else if (ids) {
       rc = sat::row_gather(slots[s], ld_slot, xwin, d, ids, 0, n_bar, n_rows_slot, d, 4, st);
       if (rc != SAT_OK) return rc;
       xs = xwin;
       ld_x = d;
-    } else if (n_rows_slot < n_bar) {
-      return SAT_EINVAL;
     }
     rc = sat_dense_bwd(xs, ld_x, nullptr, 0, da, 4 * ds, w->Wx, d, n_bar, 4 * ds, d, SAT_ACT_IDENTITY,
                        SAT_F32, tmpW, d, nullptr, 0, dws, dws_bytes, stream);

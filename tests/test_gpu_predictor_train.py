@@ -30,7 +30,7 @@ def _problem(kind, d, d_s, tau, use_ids, seed):
     return g, rng, syn.predictor_params_f32(np.random.SeedSequence(seed), d, d_s)
 
 
-def _setup(env, kind, d, d_s, tau, use_ids, masked, seed):
+def _setup(env, kind, d, d_s, tau, use_ids, masked, seed, bf16=False):
     sat, gu, torch = env
     g, rng, p = _problem(kind, d, d_s, tau, use_ids, seed)
     v = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
@@ -48,8 +48,18 @@ def _setup(env, kind, d, d_s, tau, use_ids, masked, seed):
     # "fresh" embeddings of the local nodes: the shared base moved a little further
     target = (win[-1][:n_l] + 0.1 * rng.standard_normal((n_l, d))).astype(np.float32)
     weight = (rng.random(n_l) < 0.3).astype(np.float32) if masked else None
-    dev = dict(pv=gu.upload_view(v), slots=[gu.to_dev(t, ld) for t in tables],
-               ids=gu.to_dev(ids) if use_ids else None, target=gu.to_dev(target, ld),
+
+    def up(a):
+        if not bf16:
+            return gu.to_dev(a, ld)
+        return gu.to_dev_bits(syn.bf16_bits_from_f32(a), ld).view(torch.bfloat16)
+
+    if bf16:   # the tables and the target hold bfloat16: both sides start from the rounded values
+        tables = [syn.f32_from_bf16_bits(syn.bf16_bits_from_f32(t)) for t in tables]
+        target = syn.f32_from_bf16_bits(syn.bf16_bits_from_f32(target))
+        win = [t[ids] if use_ids else t for t in tables]
+    dev = dict(pv=gu.upload_view(v), slots=[up(t) for t in tables],
+               ids=gu.to_dev(ids) if use_ids else None, target=up(target),
                weight=gu.to_dev(weight) if masked else None,
                p={k: gu.to_dev(p[k]) for k in p})
     wsb = sat.predictor_train_workspace_bytes(n_l, n_h, d, d_s, tau)
@@ -61,27 +71,30 @@ def _setup(env, kind, d, d_s, tau, use_ids, masked, seed):
     return v, p, win, target, weight, n_rows, ld, dev
 
 
-def _grad(env, v, dev, d, d_s, tau, n_rows, ld):
+def _grad(env, v, dev, d, d_s, tau, n_rows, ld, bf16=False):
     sat, gu, torch = env
     w = sat.Predictor(dev["p"]["Wx"], dev["p"]["Wh"], dev["p"]["b"], dev["p"]["Wg"], d, d_s, tau)
     sat.predictor_grad(dev["pv"], w, dev["slots"], n_rows, ld, dev["ids"], dev["target"], ld,
                        dev["weight"], dev["g"]["Wx"], dev["g"]["Wh"], dev["g"]["b"], dev["g"]["Wg"],
-                       dev["loss"], workspace=dev["ws"], workspace_bytes=dev["wsb"],
-                       stream=gu.stream_ptr())
+                       dev["loss"], dtype=sat.BF16 if bf16 else sat.F32, workspace=dev["ws"],
+                       workspace_bytes=dev["wsb"], stream=gu.stream_ptr())
     gu.sync()
 
 
-@pytest.mark.parametrize("kind,d,d_s,tau,use_ids,masked", [
-    ("tiny", 32, 32, 2, False, False), ("tiny", 32, 32, 1, True, True),
-    ("powerlaw", 256, 64, 2, True, False), ("powerlaw", 100, 64, 3, False, True),
-    ("hub", 40, 32, 2, True, False)])
-def test_predictor_grad_parity(env, kind, d, d_s, tau, use_ids, masked):
+@pytest.mark.parametrize("kind,d,d_s,tau,use_ids,masked,bf16", [
+    ("tiny", 32, 32, 2, False, False, False), ("tiny", 32, 32, 1, True, True, False),
+    ("powerlaw", 256, 64, 2, True, False, False), ("powerlaw", 100, 64, 3, False, True, False),
+    ("hub", 40, 32, 2, True, False, False),
+    # bfloat16 tables and target: the same arithmetic (fp32 inside) on the rounded inputs
+    ("tiny", 32, 32, 2, True, False, True), ("powerlaw", 256, 64, 2, True, True, True),
+    ("hub", 40, 32, 3, False, False, True)])
+def test_predictor_grad_parity(env, kind, d, d_s, tau, use_ids, masked, bf16):
     sat, gu, torch = env
-    print("[case] predictor_grad %s d=%d d_s=%d tau=%d ids=%s masked=%s" % (
-        kind, d, d_s, tau, use_ids, masked), flush=True)
+    print("[case] predictor_grad %s d=%d d_s=%d tau=%d ids=%s masked=%s bf16=%s" % (
+        kind, d, d_s, tau, use_ids, masked, bf16), flush=True)
     v, p, win, target, weight, n_rows, ld, dev = _setup(env, kind, d, d_s, tau, use_ids, masked,
-                                                        seed=d + d_s + tau)
-    _grad(env, v, dev, d, d_s, tau, n_rows, ld)
+                                                        seed=d + d_s + tau, bf16=bf16)
+    _grad(env, v, dev, d, d_s, tau, n_rows, ld, bf16)
     loss, grads = orc.predictor_train_loss_and_grad(v, p, win, target, weight)
     got_loss = float(dev["loss"].item())
     assert abs(got_loss - loss) <= 2 * RTOL * abs(loss), (got_loss, loss)
@@ -128,8 +141,11 @@ def test_predictor_grad_rejects_what_it_does_not_do(env):
     w = sat.Predictor(dev["p"]["Wx"], dev["p"]["Wh"], dev["p"]["b"], dev["p"]["Wg"], 32, 32, 2)
     args = (dev["pv"], w, dev["slots"], n_rows, ld, dev["ids"], dev["target"], ld, None,
             dev["g"]["Wx"], dev["g"]["Wh"], dev["g"]["b"], dev["g"]["Wg"], dev["loss"])
+    # bfloat16 rows are read in 16-byte chunks: widths that are not a multiple of 8 are refused
+    w36 = sat.Predictor(dev["p"]["Wx"], dev["p"]["Wh"], dev["p"]["b"], dev["p"]["Wg"], 36, 32, 2)
     with pytest.raises(sat.SatError) as e:
-        sat.predictor_grad(*args, dtype=B.BF16, workspace=dev["ws"], workspace_bytes=dev["wsb"])
+        sat.predictor_grad(*((args[0], w36) + args[2:]), dtype=B.BF16, workspace=dev["ws"],
+                           workspace_bytes=dev["wsb"])
     assert e.value.status == -2
     with pytest.raises(sat.SatError) as e:
         sat.predictor_grad(*args, workspace=dev["ws"], workspace_bytes=dev["wsb"] - 1024)
