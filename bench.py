@@ -38,6 +38,11 @@ MEASURED_TRAFFIC_BYTES = {      # profiles/large_step_hbm_traffic.md, average ov
     ("large", "dense_bwd"): 1.44e9,   # call level: weight-gradient product + its reduction + dAGG product
     ("large", "predict"): 7.68e9,     # call level: LSTM 3.52 + hop aggregation 1.24 + hop product 2.91
     ("large", "loss"): 0.136e9,
+    # graph attention backbone, profiles/large_gat_step_hbm_traffic.md
+    ("large", "gat_fwd"): 12.06e9,    # two launches of 16.02 GB (4 heads x 64) and one of 4.13 GB (1 x 47)
+    ("large", "gat_scores"): 1.10e9,
+    ("large", "gat_bwd"): 27.9e9,     # call level: mask 0.92 + destination side 16.06 + source side 12.83 + 5.88
+                                      # + attention vectors 1.10 (last layer: 4.16 + 3.48 + 1.41 + 0.37)
 }
 
 
@@ -259,8 +264,9 @@ def main():
                              avg_launch_ms=round(c["ms"] / c["launches"], 4),
                              ms_per_step=round(c["ms"] / args.steps, 4),
                              launches_per_step=c["launches"] // args.steps,
-                             traffic=None if bf16 != (cfg.get("dtype") == "bf16") else
-                             MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
+                             traffic=None if bf16 != (cfg.get("dtype") == "bf16") or (
+                                 gat and not cls.startswith("gat_") and cls not in ("predict", "push", "loss"))
+                             else MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
     # The dominant KERNEL: classes whose calls are one kernel each (aggregation, pull,
     # push, forward transform, loss) are kernels; "predict" and "dense_bwd" are calls
     # made of several kernels, none of which outweighs the aggregation kernel (see the

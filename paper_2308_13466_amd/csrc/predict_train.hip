@@ -208,9 +208,21 @@ __global__ __launch_bounds__(256) void col_sum_kernel(const float* __restrict__ 
   const int64_t lo = blockIdx.x * per, hi = lo + per < n ? lo + per : n;
   const int c = threadIdx.x;
   if (c >= cols) return;
-  float acc = 0.f;
-  for (int64_t r = lo; r < hi; ++r) acc += A[r * cols + c];
-  part[static_cast<int64_t>(blockIdx.x) * cols + c] = acc;
+  // eight rows at a time, each into its own partial sum: eight loads in flight per thread
+  float a[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) a[u] = 0.f;
+  int64_t r = lo;
+  for (; r + 8 <= hi; r += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = A[(r + u) * cols + c];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] += v[u];
+  }
+  for (; r < hi; ++r) a[0] += A[r * cols + c];
+  part[static_cast<int64_t>(blockIdx.x) * cols + c] =
+      ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
 }
 // out[c] += sum over b of part[b][c], b ascending
 __global__ __launch_bounds__(256) void col_sum_finish_kernel(const float* __restrict__ part,
