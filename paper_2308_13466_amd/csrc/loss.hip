@@ -1,7 +1,8 @@
 // Gradient of the local loss (Eq. 4 with softmax cross-entropy as Loss):
 // dH = (softmax(H^(L)) - onehot(y)) / n over the partition's local nodes, and
-// optionally the mean loss itself. One wavefront per node; classes are spread
-// over the 64 lanes and reduced with lane-xor shuffles. The loss is summed in
+// optionally the mean loss itself. One wavefront per node (eight nodes one after
+// another, their rows requested together); classes are spread over the 64 lanes
+// and reduced with lane-xor shuffles. The loss is summed in
 // two fixed-order stages (per block into the workspace, then one block), so
 // it is identical from run to run.
 #include <math.h>
@@ -40,7 +41,10 @@ __device__ __forceinline__ void st_elem(void* row, int c, float x) {
   }
 }
 
-template <int ES>
+// NV > 0: at most 64 NV classes; a lane keeps its NV elements of each of the wavefront's
+// rows in registers, and the rows of all kRowsPerWave nodes are requested before the first
+// is used. NV = 0: any number of classes, the row is re-read for each of the three sweeps.
+template <int ES, int NV>
 __global__ __launch_bounds__(256) void xent_grad_kernel(const unsigned char* __restrict__ HL,
                                                         int64_t ld_hl, int64_t n, int32_t C,
                                                         const int32_t* __restrict__ y,
@@ -50,25 +54,67 @@ __global__ __launch_bounds__(256) void xent_grad_kernel(const unsigned char* __r
   __shared__ float wave_loss[4];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
+  const float inv_n = 1.0f / static_cast<float>(n);
+  const int64_t first = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave;
   float nll = 0.f;
-  for (int rr = 0; rr < kRowsPerWave; ++rr) {
-    const int64_t row = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave + rr;
-    if (row >= n) break;
-    const unsigned char* h = HL + row * ld_hl * ES;
-    float mx = -INFINITY;
-    for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, ld_elem<ES>(h, c));
-    mx = wave_max(mx);
-    float se = 0.f;
-    for (int c = lane; c < C; c += kWave) se += expf(ld_elem<ES>(h, c) - mx);
-    se = wave_sum(se);
-    const float inv_n = 1.0f / static_cast<float>(n);
-    const int32_t label = y[row];
-    unsigned char* g = dH + row * ld_dh * ES;
-    for (int c = lane; c < C; c += kWave) {
-      const float p = expf(ld_elem<ES>(h, c) - mx) / se;
-      st_elem<ES>(g, c, (p - (c == label ? 1.f : 0.f)) * inv_n);
+  if constexpr (NV > 0) {
+    float v[kRowsPerWave][NV], at_label[kRowsPerWave];
+    int32_t label[kRowsPerWave];
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+      const int64_t row = first + rr < n ? first + rr : n - 1;   // past the end: the last row again
+      const unsigned char* h = HL + row * ld_hl * ES;
+      label[rr] = y[row];
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int c = lane + kWave * k;
+        v[rr][k] = c < C ? ld_elem<ES>(h, c) : -INFINITY;
+      }
+      const bool lab_ok = label[rr] >= 0 && label[rr] < C;
+      at_label[rr] = lab_ok ? ld_elem<ES>(h, label[rr]) : 0.f;
     }
-    if (label >= 0 && label < C) nll += logf(se) + mx - ld_elem<ES>(h, label);
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+      const int64_t row = first + rr;
+      if (row >= n) break;
+      float mx = v[rr][0];
+#pragma unroll
+      for (int k = 1; k < NV; ++k) mx = fmaxf(mx, v[rr][k]);
+      mx = wave_max(mx);
+      float p[NV], se = 0.f;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        p[k] = expf(v[rr][k] - mx);      // exp(-inf) = 0 for the lanes past the last class
+        se += p[k];
+      }
+      se = wave_sum(se);
+      unsigned char* g = dH + row * ld_dh * ES;
+#pragma unroll
+      for (int k = 0; k < NV; ++k) {
+        const int c = lane + kWave * k;
+        if (c < C) st_elem<ES>(g, c, (p[k] / se - (c == label[rr] ? 1.f : 0.f)) * inv_n);
+      }
+      if (label[rr] >= 0 && label[rr] < C) nll += logf(se) + mx - at_label[rr];
+    }
+  } else {
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+      const int64_t row = first + rr;
+      if (row >= n) break;
+      const unsigned char* h = HL + row * ld_hl * ES;
+      float mx = -INFINITY;
+      for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, ld_elem<ES>(h, c));
+      mx = wave_max(mx);
+      float se = 0.f;
+      for (int c = lane; c < C; c += kWave) se += expf(ld_elem<ES>(h, c) - mx);
+      se = wave_sum(se);
+      const int32_t label = y[row];
+      unsigned char* g = dH + row * ld_dh * ES;
+      for (int c = lane; c < C; c += kWave) {
+        const float p = expf(ld_elem<ES>(h, c) - mx) / se;
+        st_elem<ES>(g, c, (p - (c == label ? 1.f : 0.f)) * inv_n);
+      }
+      if (label >= 0 && label < C) nll += logf(se) + mx - ld_elem<ES>(h, label);
+    }
   }
   if (block_loss) {
     if (lane == 0) wave_loss[wave] = nll;
@@ -116,12 +162,27 @@ extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, in
   const unsigned char* hl = static_cast<const unsigned char*>(HL);
   unsigned char* dh = static_cast<unsigned char*>(dH);
   float* bl = loss ? static_cast<float*>(workspace) : nullptr;
-  if (dtype == SAT_BF16)
-    xent_grad_kernel<2><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(
-        hl, ld_hl, n, n_classes, y, dh, ld_dh, bl);
-  else
-    xent_grad_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, s>>>(
-        hl, ld_hl, n, n_classes, y, dh, ld_dh, bl);
+  const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+  const int nv = n_classes <= 4 * kWave ? (n_classes + kWave - 1) / kWave : 0;
+#define SAT_XENT(ES, NV) xent_grad_kernel<ES, NV><<<grid, block, 0, s>>>(hl, ld_hl, n, n_classes, y, dh, ld_dh, bl)
+  if (dtype == SAT_BF16) {
+    switch (nv) {
+      case 1: SAT_XENT(2, 1); break;
+      case 2: SAT_XENT(2, 2); break;
+      case 3: SAT_XENT(2, 3); break;
+      case 4: SAT_XENT(2, 4); break;
+      default: SAT_XENT(2, 0); break;
+    }
+  } else {
+    switch (nv) {
+      case 1: SAT_XENT(4, 1); break;
+      case 2: SAT_XENT(4, 2); break;
+      case 3: SAT_XENT(4, 3); break;
+      case 4: SAT_XENT(4, 4); break;
+      default: SAT_XENT(4, 0); break;
+    }
+  }
+#undef SAT_XENT
   sat_status st = sat::check_launch();
   if (st != SAT_OK || !loss) return st;
   loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(static_cast<const float*>(workspace), blocks,

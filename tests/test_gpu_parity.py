@@ -225,7 +225,8 @@ def test_dense_bwd_workspace_is_checked(env):
 
 
 # ------------------------------------------------------------------------ loss
-@pytest.mark.parametrize("n,C", [(2048, 8), (1001, 40), (333, 47), (70, 172), (1, 2)])
+@pytest.mark.parametrize("n,C", [(2048, 8), (1001, 40), (333, 47), (70, 172), (1, 2), (500, 128),
+                                 (301, 256), (203, 300), (37, 65)])
 def test_loss_grad_parity(env, n, C):
     sat, gu, torch = env
     _say("loss n=%d C=%d" % (n, C))
@@ -242,6 +243,7 @@ def test_loss_grad_parity(env, n, C):
     gu.sync()
     loss, g = orc.loss_and_grad(HL, y)
     gu.assert_close(gu.to_host(g_d, C), g, RTOL, "dH^(L)")
+    assert torch.all(g_d[:, C:] == -3.0)          # padding columns untouched
     assert abs(float(loss_d.item()) - loss) <= RTOL * abs(loss) * 2
 
 
