@@ -17,6 +17,13 @@
 #include "mx_tile.h"
 #include "sat_internal.h"
 
+namespace sat {
+bool dense_ws_serves(int32_t K);
+sat_status launch_dense_ws(const void* A, int64_t ld_a, const void* Mk, int64_t ld_m, int64_t M,
+                           int32_t K, const void* W, int64_t ld_w, bool transb, int32_t N, bool relu,
+                           void* out, int64_t ld_out, hipStream_t st);
+}  // namespace sat
+
 namespace {
 
 using namespace sat::mx;
@@ -125,6 +132,12 @@ sat_status check_mat(const void* p, int64_t rows, int64_t cols, int64_t ld, int 
 template <int ES>
 sat_status run_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in, int32_t d_out,
                    const void* W, int64_t ld_w, int32_t act, void* H, int64_t ld_h, hipStream_t s) {
+  if constexpr (ES == 2) {   // bf16: one product per operand pair, a streaming kernel serves it
+    // (up to 128 output columns the tile GEMM reads A once as well and starts faster)
+    if (sat::dense_ws_serves(d_in) && d_out > 128)
+      return sat::launch_dense_ws(AGG, ld_a, nullptr, 0, n, d_in, W, ld_w, false, d_out,
+                                  act == SAT_ACT_RELU, H, ld_h, s);
+  }
   const int64_t gx = (n + BM - 1) / BM;
   if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
   const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>((d_out + BN - 1) / BN), 1);
@@ -158,6 +171,11 @@ sat_status run_bwd(const void* dH, int64_t ld_dh, const void* mask, int64_t ld_h
     if ((st = sat::check_launch()) != SAT_OK) return st;
   }
   // dAGG = dZ W^T : M = n, N = d_in, K = d_out
+  if constexpr (ES == 2) {
+    if (dAGG && sat::dense_ws_serves(d_out) && d_in > 128)
+      return sat::launch_dense_ws(dH, ld_dh, mask, ld_ho, n, d_out, W, ld_w, true, d_in, false, dAGG,
+                                  ld_da, s);
+  }
   if (dAGG) {
     const int64_t gx = (n + BM - 1) / BM;
     if (gx > INT32_MAX) return SAT_EUNSUPPORTED;

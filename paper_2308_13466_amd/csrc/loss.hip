@@ -124,6 +124,127 @@ __global__ __launch_bounds__(256) void xent_grad_kernel(const unsigned char* __r
   }
 }
 
+// Rows that start on 16-byte boundaries (ld a multiple of 16 / ES elements): a lane holds NQ
+// groups of 4 consecutive classes (classes 4 (lane + 64 q) .. + 3), read and written with one
+// 8- or 16-byte access each; at most 256 NQ classes.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+
+template <int ES>
+__device__ __forceinline__ f32x4 ld_quad(const unsigned char* p) {
+  if constexpr (ES == 4) {
+    return *reinterpret_cast<const f32x4*>(p);
+  } else {
+    const u32x2 w = *reinterpret_cast<const u32x2*>(p);
+    const uint32_t w0 = w.x, w1 = w.y;
+    f32x4 r;
+    r.x = __builtin_bit_cast(float, w0 << 16);
+    r.y = __builtin_bit_cast(float, w0 & 0xffff0000u);
+    r.z = __builtin_bit_cast(float, w1 << 16);
+    r.w = __builtin_bit_cast(float, w1 & 0xffff0000u);
+    return r;
+  }
+}
+template <int ES>
+__device__ __forceinline__ void st_quad(unsigned char* p, f32x4 v) {
+  if constexpr (ES == 4) {
+    *reinterpret_cast<f32x4*>(p) = v;
+  } else {
+    const f32x2v lo = {v.x, v.y}, hi = {v.z, v.w};
+    u32x2 w;
+    w.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, bf16x2v));
+    w.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, bf16x2v));
+    *reinterpret_cast<u32x2*>(p) = w;
+  }
+}
+
+template <int ES, int NQ>
+__global__ __launch_bounds__(256) void xent_grad_quad_kernel(const unsigned char* __restrict__ HL,
+                                                             int64_t ld_hl, int64_t n, int32_t C,
+                                                             const int32_t* __restrict__ y,
+                                                             unsigned char* __restrict__ dH,
+                                                             int64_t ld_dh,
+                                                             float* __restrict__ block_loss) {
+  __shared__ float wave_loss[4];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const float inv_n = 1.0f / static_cast<float>(n);
+  const int64_t first = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave;
+  float nll = 0.f;
+  f32x4 v[kRowsPerWave][NQ];
+  float at_label[kRowsPerWave];
+  int32_t label[kRowsPerWave];
+#pragma unroll
+  for (int rr = 0; rr < kRowsPerWave; ++rr) {
+    const int64_t row = first + rr < n ? first + rr : n - 1;   // past the end: the last row again
+    const unsigned char* h = HL + row * ld_hl * ES;
+    label[rr] = y[row];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int c0 = 4 * (lane + kWave * q);
+      f32x4 t = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      if (c0 < C) t = ld_quad<ES>(h + static_cast<int64_t>(c0) * ES);
+      v[rr][q] = t;
+    }
+    const bool lab_ok = label[rr] >= 0 && label[rr] < C;
+    at_label[rr] = lab_ok ? ld_elem<ES>(h, label[rr]) : 0.f;
+  }
+#pragma unroll
+  for (int rr = 0; rr < kRowsPerWave; ++rr) {
+    const int64_t row = first + rr;
+    if (row >= n) break;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int c0 = 4 * (lane + kWave * q);
+      // classes past C inside the last group are padding of the row
+      if (c0 + 1 >= C) v[rr][q].y = -INFINITY;
+      if (c0 + 2 >= C) v[rr][q].z = -INFINITY;
+      if (c0 + 3 >= C) v[rr][q].w = -INFINITY;
+      mx = fmaxf(fmaxf(mx, fmaxf(v[rr][q].x, v[rr][q].y)), fmaxf(v[rr][q].z, v[rr][q].w));
+    }
+    mx = wave_max(mx);
+    f32x4 p[NQ];
+    float se = 0.f;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      p[q].x = expf(v[rr][q].x - mx);
+      p[q].y = expf(v[rr][q].y - mx);
+      p[q].z = expf(v[rr][q].z - mx);
+      p[q].w = expf(v[rr][q].w - mx);
+      se += (p[q].x + p[q].y) + (p[q].z + p[q].w);
+    }
+    se = wave_sum(se);
+    unsigned char* g = dH + row * ld_dh * ES;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const int c0 = 4 * (lane + kWave * q);
+      if (c0 >= C) continue;
+      f32x4 o;
+      o.x = (p[q].x / se - (c0 == label[rr] ? 1.f : 0.f)) * inv_n;
+      o.y = (p[q].y / se - (c0 + 1 == label[rr] ? 1.f : 0.f)) * inv_n;
+      o.z = (p[q].z / se - (c0 + 2 == label[rr] ? 1.f : 0.f)) * inv_n;
+      o.w = (p[q].w / se - (c0 + 3 == label[rr] ? 1.f : 0.f)) * inv_n;
+      if (c0 + 3 < C) {
+        st_quad<ES>(g + static_cast<int64_t>(c0) * ES, o);
+      } else {
+        st_elem<ES>(g, c0, o.x);
+        if (c0 + 1 < C) st_elem<ES>(g, c0 + 1, o.y);
+        if (c0 + 2 < C) st_elem<ES>(g, c0 + 2, o.z);
+      }
+    }
+    if (label[rr] >= 0 && label[rr] < C) nll += logf(se) + mx - at_label[rr];
+  }
+  if (block_loss) {
+    if (lane == 0) wave_loss[wave] = nll;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      block_loss[blockIdx.x] = (wave_loss[0] + wave_loss[1]) + (wave_loss[2] + wave_loss[3]);
+  }
+}
+
 // Single block: loss = (sum of m partials, fixed strided order + tree) / n.
 __global__ __launch_bounds__(256) void loss_finish_kernel(const float* __restrict__ part,
                                                           int64_t m, int64_t n,
@@ -163,6 +284,35 @@ extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, in
   unsigned char* dh = static_cast<unsigned char*>(dH);
   float* bl = loss ? static_cast<float*>(workspace) : nullptr;
   const dim3 grid(static_cast<unsigned>(blocks)), block(256);
+  const int es_b = dtype == SAT_BF16 ? 2 : 4;
+  // (with few classes the groups of 4 would leave most lanes idle: one class per lane then)
+  const bool quads = n_classes >= 2 * kWave && n_classes <= 16 * kWave && (ld_hl * es_b) % 16 == 0 && (ld_dh * es_b) % 16 == 0 &&
+                     sat::aligned16(HL) && sat::aligned16(dH);
+  if (quads) {   // the library's own buffers: rows start on 16-byte boundaries
+    const int nq = (n_classes + 4 * kWave - 1) / (4 * kWave);
+#define SAT_XENT_Q(ES, NQ) \
+  xent_grad_quad_kernel<ES, NQ><<<grid, block, 0, s>>>(hl, ld_hl, n, n_classes, y, dh, ld_dh, bl)
+    if (dtype == SAT_BF16) {
+      switch (nq) {
+        case 1: SAT_XENT_Q(2, 1); break;
+        case 2: SAT_XENT_Q(2, 2); break;
+        case 3: SAT_XENT_Q(2, 3); break;
+        default: SAT_XENT_Q(2, 4); break;
+      }
+    } else {
+      switch (nq) {
+        case 1: SAT_XENT_Q(4, 1); break;
+        case 2: SAT_XENT_Q(4, 2); break;
+        case 3: SAT_XENT_Q(4, 3); break;
+        default: SAT_XENT_Q(4, 4); break;
+      }
+    }
+#undef SAT_XENT_Q
+    sat_status stq = sat::check_launch();
+    if (stq != SAT_OK || !loss) return stq;
+    loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(static_cast<const float*>(workspace), blocks, n, loss);
+    return sat::check_launch();
+  }
   const int nv = n_classes <= 4 * kWave ? (n_classes + kWave - 1) / kWave : 0;
 #define SAT_XENT(ES, NV) xent_grad_kernel<ES, NV><<<grid, block, 0, s>>>(hl, ld_hl, n, n_classes, y, dh, ld_dh, bl)
   if (dtype == SAT_BF16) {

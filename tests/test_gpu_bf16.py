@@ -98,7 +98,9 @@ def test_bf16_spmm_parity(env, kind, d):
 
 @pytest.mark.parametrize("n,d_in,d_out,act", [(2048, 64, 32, 1), (1000, 128, 256, 1),
                                               (777, 256, 256, 1), (513, 256, 176, 0),
-                                              (300, 600, 256, 1), (129, 104, 48, 0), (5, 8, 8, 1)])
+                                              (300, 600, 256, 1), (129, 104, 48, 0), (5, 8, 8, 1),
+                                              (1500, 256, 47, 0), (4100, 128, 172, 0),
+                                              (70001, 256, 256, 1), (33, 16, 300, 1)])
 def test_bf16_dense_fwd_bwd_parity(env, n, d_in, d_out, act):
     sat, gu, torch = env
     _say("bf16 dense n=%d %d->%d act=%d" % (n, d_in, d_out, act))
@@ -133,7 +135,7 @@ def test_bf16_dense_fwd_bwd_parity(env, n, d_in, d_out, act):
     gu.assert_close(syn.f32_from_bf16_bits(gu.bits_to_host(dA_d, d_in)), dA, RTOL_BF16, "bf16 dAGG")
 
 
-@pytest.mark.parametrize("n,C", [(2048, 8), (1001, 40), (70, 172)])
+@pytest.mark.parametrize("n,C", [(2048, 8), (1001, 40), (70, 172), (333, 47), (90, 700)])
 def test_bf16_loss_grad_parity(env, n, C):
     sat, gu, torch = env
     _say("bf16 loss n=%d C=%d" % (n, C))
@@ -150,6 +152,7 @@ def test_bf16_loss_grad_parity(env, n, C):
     gu.sync()
     loss, g = orc.loss_and_grad(HL, y)
     gu.assert_close(syn.f32_from_bf16_bits(gu.bits_to_host(g_d, C)), g, RTOL_BF16, "bf16 dH^(L)")
+    assert np.all(gu.bits_to_host(g_d)[:, C:] == 77)          # padding columns untouched
     assert abs(float(loss_d.item()) - loss) <= 2e-5 * abs(loss)
 
 

@@ -247,6 +247,28 @@ def test_loss_grad_parity(env, n, C):
     assert abs(float(loss_d.item()) - loss) <= RTOL * abs(loss) * 2
 
 
+@pytest.mark.parametrize("n,C,ld", [(400, 47, 47), (129, 300, 301), (64, 130, 131), (1000, 1100, 1100)])
+def test_loss_grad_rows_not_on_16_byte_boundaries(env, n, C, ld):
+    """Leading dimensions that do not put rows on 16-byte boundaries (and more classes than the
+    register-resident kernels hold) take the element-wise kernels."""
+    sat, gu, torch = env
+    _say("loss n=%d C=%d ld=%d" % (n, C, ld))
+    rng = np.random.default_rng(C + ld)
+    HL = (3.0 * rng.standard_normal((n, C))).astype(np.float32)
+    y = rng.integers(0, C, size=n).astype(np.int32)
+    g_d = gu.dev_empty(n, ld, fill=-3.0)
+    loss_d = torch.zeros(1, dtype=torch.float32, device=gu.DEV)
+    wsb = sat.loss_workspace_bytes(n)
+    ws = gu.workspace(wsb)
+    sat.loss_grad(gu.to_dev(HL, ld), ld, n, C, gu.to_dev(y), g_d, ld, loss=loss_d, workspace=ws,
+                  workspace_bytes=wsb, stream=gu.stream_ptr())
+    gu.sync()
+    loss, g = orc.loss_and_grad(HL, y)
+    gu.assert_close(gu.to_host(g_d, C), g, RTOL, "dH^(L)")
+    assert torch.all(g_d[:, C:] == -3.0)
+    assert abs(float(loss_d.item()) - loss) <= RTOL * abs(loss) * 2
+
+
 # ------------------------------------------------------------------- predictor
 @pytest.mark.parametrize("kind,d,d_s,tau,use_ids", [("tiny", 32, 32, 2, False),
                                                     ("tiny", 32, 32, 1, True),
