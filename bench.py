@@ -196,9 +196,9 @@ def main():
     s = 2 if bf16 else 4
     # dense MFMA peak the contractions are priced against: fp32 data is split into
     # three bf16 pieces (six products per element pair); bf16 data needs one product
-    # in the feature transforms and three in the predictor (fp32 parameters, bf16 x)
+    # in the feature transforms and two in the predictor (fp32 parameters to 16 bits, bf16 x)
     peak_dense = 2500.0 if bf16 else MFMA_SPLIT_PEAK_TFLOPS
-    peak_predict = 2500.0 / 3.0 if bf16 else MFMA_SPLIT_PEAK_TFLOPS
+    peak_predict = 2500.0 / 2.0 if bf16 else MFMA_SPLIT_PEAK_TFLOPS
     nnz, nnz_loc, nnz_halo = view["nnz"], step.nnz_local, view["nnz_halo"]
 
     def spmm_bytes(entries, rows, d):       # per entry: col + val + one feature row;

@@ -72,7 +72,10 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
                                                       const float* __restrict__ bias,
                                                       float* __restrict__ S,
                                                       float* __restrict__ save) {
-  constexpr int NP = 3;
+  constexpr int NP = 3;             // pieces of an fp32 operand (x rows, h)
+  // pieces of the weights: all three against fp32 rows (the exact product); two against bf16
+  // rows, whose own precision (8 bits) the third piece (bits 17..24 of a weight) cannot matter to
+  constexpr int NPB = ESX == 4 ? 3 : 2;
   constexpr int NT = 64 * WAVES;    // threads
   constexpr int WN = DS / 32;       // wavefronts along hidden units
   constexpr int WM = WAVES / WN;    // wavefronts along nodes
@@ -81,9 +84,9 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
   constexpr int NB = 4 * DS;        // gate columns
   constexpr int H_ROW_B = DS * 2 + 16;        // bytes per node row of a staged h piece
   constexpr int H_PIECE_B = R * H_ROW_B;
-  constexpr int B_CHUNKS = NP * NB * 4 / NT;  // 16-byte weight chunks per thread per K step
+  constexpr int B_CHUNKS = NPB * NB * 4 / NT; // 16-byte weight chunks per thread per K step
   __shared__ __attribute__((aligned(16))) unsigned char As[2 * tile_bytes<R, NP>()];
-  __shared__ __attribute__((aligned(16))) unsigned char Bs[tile_bytes<NB, NP>()];
+  __shared__ __attribute__((aligned(16))) unsigned char Bs[tile_bytes<NB, NPB>()];
   __shared__ __attribute__((aligned(16))) unsigned char Hs[NP * H_PIECE_B];
 
   const int t = threadIdx.x;
@@ -219,7 +222,7 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
     // the value itself against each weight piece, smallest first).
     auto products = [&](auto npa_tag, const unsigned char* Ax, int a_kc0) {
       constexpr int NPA = decltype(npa_tag)::value;
-      constexpr int NQ = NPA == 3 ? 6 : 3;
+      constexpr int NQ = NPA == 3 ? (NPB == 3 ? 6 : 5) : NPB;
 #pragma unroll
       for (int kc = 0; kc < BK / 16; ++kc) {
         bf16x8 a[RB][NPA];
@@ -234,16 +237,18 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
         // two gates at a time: their weight fragments are all that is held besides a
 #pragma unroll
         for (int gp = 0; gp < 2; ++gp) {
-          bf16x8 b[2][NP];
+          bf16x8 b[2][NPB];
 #pragma unroll
-          for (int p = 0; p < NP; ++p)
+          for (int p = 0; p < NPB; ++p)
 #pragma unroll
             for (int g = 0; g < 2; ++g)
               b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), (2 * gp + g) * DS + 32 * wn, kc, lane);
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
-            const int pa = NPA == 3 ? product_a<3>(q) : 0;
-            const int pb = NPA == 3 ? product_b<3>(q) : 2 - q;
+            // (a piece, b piece), smallest terms first; with two weight pieces against three
+            // pieces of h: (2,0) (1,1) (1,0) (0,1) (0,0)
+            const int pa = NPA == 3 ? (NPB == 3 ? product_a<3>(q) : (q == 0 ? 2 : (q < 3 ? 1 : 0))) : 0;
+            const int pb = NPA == 3 ? (NPB == 3 ? product_b<3>(q) : (q == 1 || q == 3 ? 1 : 0)) : NPB - 1 - q;
 #pragma unroll
             for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
