@@ -7,13 +7,16 @@
 // it is identical from run to run.
 #include <math.h>
 
+#include <type_traits>
+
 #include "sat_internal.h"
 
 namespace {
 
 using sat::kWave;
-constexpr int kRowsPerWave = 8;    // nodes a wavefront handles one after another
-constexpr int kRowsPerBlock = 4 * kRowsPerWave;
+constexpr int kRowsPerWave = 8;    // nodes a wavefront holds in registers at a time
+constexpr int kRounds = 4;         // such batches per wavefront (fewer, longer-lived workgroups)
+constexpr int kRowsPerBlock = 4 * kRowsPerWave * kRounds;
 
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
@@ -55,62 +58,81 @@ __global__ __launch_bounds__(256) void xent_grad_kernel(const unsigned char* __r
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
   const float inv_n = 1.0f / static_cast<float>(n);
-  const int64_t first = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave;
+  const int64_t first0 = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave * kRounds;
   float nll = 0.f;
   if constexpr (NV > 0) {
-    float v[kRowsPerWave][NV], at_label[kRowsPerWave];
-    int32_t label[kRowsPerWave];
+    for (int rd = 0; rd < kRounds; ++rd) {
+      const int64_t first = first0 + rd * kRowsPerWave;
+      if (first >= n) break;
+      // every load of the batch is requested before anything is looked at (a bf16 element is
+      // widened only in the second loop)
+      typedef typename std::conditional<ES == 4, float, uint16_t>::type RawT;
+      RawT raw[kRowsPerWave][NV];
+      int32_t label[kRowsPerWave];
 #pragma unroll
-    for (int rr = 0; rr < kRowsPerWave; ++rr) {
-      const int64_t row = first + rr < n ? first + rr : n - 1;   // past the end: the last row again
-      const unsigned char* h = HL + row * ld_hl * ES;
-      label[rr] = y[row];
+      for (int rr = 0; rr < kRowsPerWave; ++rr) {
+        const int64_t row = first + rr < n ? first + rr : n - 1;   // past the end: the last row again
+        const RawT* h = reinterpret_cast<const RawT*>(HL + row * ld_hl * ES);
+        label[rr] = y[row];
 #pragma unroll
-      for (int k = 0; k < NV; ++k) {
-        const int c = lane + kWave * k;
-        v[rr][k] = c < C ? ld_elem<ES>(h, c) : -INFINITY;
+        for (int k = 0; k < NV; ++k) {
+          const int c = lane + kWave * k;
+          raw[rr][k] = h[c < C ? c : 0];      // lanes past the last class: discarded below
+        }
       }
-      const bool lab_ok = label[rr] >= 0 && label[rr] < C;
-      at_label[rr] = lab_ok ? ld_elem<ES>(h, label[rr]) : 0.f;
-    }
 #pragma unroll
-    for (int rr = 0; rr < kRowsPerWave; ++rr) {
-      const int64_t row = first + rr;
-      if (row >= n) break;
-      float mx = v[rr][0];
+      for (int rr = 0; rr < kRowsPerWave; ++rr) {
+        const int64_t row = first + rr;
+        if (row >= n) break;
+        const int32_t lab = label[rr];
+        float v[NV], own = 0.f;               // own: the logit of the label, on the lane that holds it
 #pragma unroll
-      for (int k = 1; k < NV; ++k) mx = fmaxf(mx, v[rr][k]);
-      mx = wave_max(mx);
-      float p[NV], se = 0.f;
+        for (int k = 0; k < NV; ++k) {
+          const int c = lane + kWave * k;
+          if constexpr (ES == 4) v[k] = raw[rr][k];
+          else v[k] = __builtin_bit_cast(float, static_cast<uint32_t>(raw[rr][k]) << 16);
+          if (c == lab) own = v[k];
+          if (c >= C) v[k] = -INFINITY;
+        }
+        float mx = v[0];
 #pragma unroll
-      for (int k = 0; k < NV; ++k) {
-        p[k] = expf(v[rr][k] - mx);      // exp(-inf) = 0 for the lanes past the last class
-        se += p[k];
+        for (int k = 1; k < NV; ++k) mx = fmaxf(mx, v[k]);
+        mx = wave_max(mx);
+        float p[NV], se = 0.f;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          p[k] = __expf(v[k] - mx);      // exp(-inf) = 0 for the lanes past the last class
+          se += p[k];
+        }
+        se = wave_sum(se);
+        const float inv_se = 1.0f / se;
+        unsigned char* g = dH + row * ld_dh * ES;
+#pragma unroll
+        for (int k = 0; k < NV; ++k) {
+          const int c = lane + kWave * k;
+          if (c < C) st_elem<ES>(g, c, (p[k] * inv_se - (c == lab ? 1.f : 0.f)) * inv_n);
+        }
+        if (lab >= 0 && lab < C) {
+          // the label is the same on every lane: its logit is read from the lane that holds it
+          nll += logf(se) + mx - __shfl(own, lab & (kWave - 1));
+        }
       }
-      se = wave_sum(se);
-      unsigned char* g = dH + row * ld_dh * ES;
-#pragma unroll
-      for (int k = 0; k < NV; ++k) {
-        const int c = lane + kWave * k;
-        if (c < C) st_elem<ES>(g, c, (p[k] / se - (c == label[rr] ? 1.f : 0.f)) * inv_n);
-      }
-      if (label[rr] >= 0 && label[rr] < C) nll += logf(se) + mx - at_label[rr];
     }
   } else {
-    for (int rr = 0; rr < kRowsPerWave; ++rr) {
-      const int64_t row = first + rr;
+    for (int rr = 0; rr < kRowsPerWave * kRounds; ++rr) {
+      const int64_t row = first0 + rr;
       if (row >= n) break;
       const unsigned char* h = HL + row * ld_hl * ES;
       float mx = -INFINITY;
       for (int c = lane; c < C; c += kWave) mx = fmaxf(mx, ld_elem<ES>(h, c));
       mx = wave_max(mx);
       float se = 0.f;
-      for (int c = lane; c < C; c += kWave) se += expf(ld_elem<ES>(h, c) - mx);
+      for (int c = lane; c < C; c += kWave) se += __expf(ld_elem<ES>(h, c) - mx);
       se = wave_sum(se);
       const int32_t label = y[row];
       unsigned char* g = dH + row * ld_dh * ES;
       for (int c = lane; c < C; c += kWave) {
-        const float p = expf(ld_elem<ES>(h, c) - mx) / se;
+        const float p = __expf(ld_elem<ES>(h, c) - mx) / se;
         st_elem<ES>(g, c, (p - (c == label ? 1.f : 0.f)) * inv_n);
       }
       if (label >= 0 && label < C) nll += logf(se) + mx - ld_elem<ES>(h, label);
@@ -132,12 +154,21 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
 typedef float f32x2v __attribute__((ext_vector_type(2)));
 
+// four elements as loaded (nothing may look at them before all rows of a batch have been
+// requested, or every load is waited for on its own), and widened to fp32
 template <int ES>
-__device__ __forceinline__ f32x4 ld_quad(const unsigned char* p) {
+struct RawQuad {
+  typedef f32x4 T;
+};
+template <>
+struct RawQuad<2> {
+  typedef u32x2 T;
+};
+template <int ES>
+__device__ __forceinline__ f32x4 widen_quad(typename RawQuad<ES>::T w) {
   if constexpr (ES == 4) {
-    return *reinterpret_cast<const f32x4*>(p);
+    return w;
   } else {
-    const u32x2 w = *reinterpret_cast<const u32x2*>(p);
     const uint32_t w0 = w.x, w1 = w.y;
     f32x4 r;
     r.x = __builtin_bit_cast(float, w0 << 16);
@@ -171,71 +202,86 @@ __global__ __launch_bounds__(256) void xent_grad_quad_kernel(const unsigned char
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x >> 6;
   const float inv_n = 1.0f / static_cast<float>(n);
-  const int64_t first = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave;
+  const int64_t first0 = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kRowsPerWave * kRounds;
   float nll = 0.f;
-  f32x4 v[kRowsPerWave][NQ];
-  float at_label[kRowsPerWave];
-  int32_t label[kRowsPerWave];
+  for (int rd = 0; rd < kRounds; ++rd) {
+    const int64_t first = first0 + rd * kRowsPerWave;
+    if (first >= n) break;
+    // every load of the batch is requested before anything is looked at
+    typename RawQuad<ES>::T raw[kRowsPerWave][NQ];
+    int32_t label[kRowsPerWave];
 #pragma unroll
-  for (int rr = 0; rr < kRowsPerWave; ++rr) {
-    const int64_t row = first + rr < n ? first + rr : n - 1;   // past the end: the last row again
-    const unsigned char* h = HL + row * ld_hl * ES;
-    label[rr] = y[row];
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+      const int64_t row = first + rr < n ? first + rr : n - 1;   // past the end: the last row again
+      const unsigned char* h = HL + row * ld_hl * ES;
+      label[rr] = y[row];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int c0 = 4 * (lane + kWave * q);
-      f32x4 t = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      if (c0 < C) t = ld_quad<ES>(h + static_cast<int64_t>(c0) * ES);
-      v[rr][q] = t;
-    }
-    const bool lab_ok = label[rr] >= 0 && label[rr] < C;
-    at_label[rr] = lab_ok ? ld_elem<ES>(h, label[rr]) : 0.f;
-  }
-#pragma unroll
-  for (int rr = 0; rr < kRowsPerWave; ++rr) {
-    const int64_t row = first + rr;
-    if (row >= n) break;
-    float mx = -INFINITY;
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int c0 = 4 * (lane + kWave * q);
-      // classes past C inside the last group are padding of the row
-      if (c0 + 1 >= C) v[rr][q].y = -INFINITY;
-      if (c0 + 2 >= C) v[rr][q].z = -INFINITY;
-      if (c0 + 3 >= C) v[rr][q].w = -INFINITY;
-      mx = fmaxf(fmaxf(mx, fmaxf(v[rr][q].x, v[rr][q].y)), fmaxf(v[rr][q].z, v[rr][q].w));
-    }
-    mx = wave_max(mx);
-    f32x4 p[NQ];
-    float se = 0.f;
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      p[q].x = expf(v[rr][q].x - mx);
-      p[q].y = expf(v[rr][q].y - mx);
-      p[q].z = expf(v[rr][q].z - mx);
-      p[q].w = expf(v[rr][q].w - mx);
-      se += (p[q].x + p[q].y) + (p[q].z + p[q].w);
-    }
-    se = wave_sum(se);
-    unsigned char* g = dH + row * ld_dh * ES;
-#pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-      const int c0 = 4 * (lane + kWave * q);
-      if (c0 >= C) continue;
-      f32x4 o;
-      o.x = (p[q].x / se - (c0 == label[rr] ? 1.f : 0.f)) * inv_n;
-      o.y = (p[q].y / se - (c0 + 1 == label[rr] ? 1.f : 0.f)) * inv_n;
-      o.z = (p[q].z / se - (c0 + 2 == label[rr] ? 1.f : 0.f)) * inv_n;
-      o.w = (p[q].w / se - (c0 + 3 == label[rr] ? 1.f : 0.f)) * inv_n;
-      if (c0 + 3 < C) {
-        st_quad<ES>(g + static_cast<int64_t>(c0) * ES, o);
-      } else {
-        st_elem<ES>(g, c0, o.x);
-        if (c0 + 1 < C) st_elem<ES>(g, c0 + 1, o.y);
-        if (c0 + 2 < C) st_elem<ES>(g, c0 + 2, o.z);
+      for (int q = 0; q < NQ; ++q) {
+        // lanes past the last class re-read the row's first group; it is discarded below
+        const int c0 = 4 * (lane + kWave * q);
+        raw[rr][q] = *reinterpret_cast<const typename RawQuad<ES>::T*>(
+            h + static_cast<int64_t>(c0 < C ? c0 : 0) * ES);
       }
     }
-    if (label[rr] >= 0 && label[rr] < C) nll += logf(se) + mx - at_label[rr];
+#pragma unroll
+    for (int rr = 0; rr < kRowsPerWave; ++rr) {
+      const int64_t row = first + rr;
+      if (row >= n) break;
+      const int32_t lab = label[rr];
+      float mx = -INFINITY, own = 0.f;     // own: the logit of the label, on the lane that holds it
+      f32x4 v[NQ];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const int c0 = 4 * (lane + kWave * q);
+        v[q] = widen_quad<ES>(raw[rr][q]);
+        if (c0 == (lab & ~3)) {
+          const int j = lab & 3;
+          own = j == 0 ? v[q].x : (j == 1 ? v[q].y : (j == 2 ? v[q].z : v[q].w));
+        }
+        // classes past C (inside the last group: padding of the row) do not take part
+        if (c0 >= C) v[q].x = -INFINITY;
+        if (c0 + 1 >= C) v[q].y = -INFINITY;
+        if (c0 + 2 >= C) v[q].z = -INFINITY;
+        if (c0 + 3 >= C) v[q].w = -INFINITY;
+        mx = fmaxf(fmaxf(mx, fmaxf(v[q].x, v[q].y)), fmaxf(v[q].z, v[q].w));
+      }
+      mx = wave_max(mx);
+      f32x4 p[NQ];
+      float se = 0.f;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        p[q].x = __expf(v[q].x - mx);
+        p[q].y = __expf(v[q].y - mx);
+        p[q].z = __expf(v[q].z - mx);
+        p[q].w = __expf(v[q].w - mx);
+        se += (p[q].x + p[q].y) + (p[q].z + p[q].w);
+      }
+      se = wave_sum(se);
+      const float inv_se = 1.0f / se;
+      unsigned char* g = dH + row * ld_dh * ES;
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const int c0 = 4 * (lane + kWave * q);
+        if (c0 >= C) continue;
+        f32x4 o;
+        o.x = (p[q].x * inv_se - (c0 == lab ? 1.f : 0.f)) * inv_n;
+        o.y = (p[q].y * inv_se - (c0 + 1 == lab ? 1.f : 0.f)) * inv_n;
+        o.z = (p[q].z * inv_se - (c0 + 2 == lab ? 1.f : 0.f)) * inv_n;
+        o.w = (p[q].w * inv_se - (c0 + 3 == lab ? 1.f : 0.f)) * inv_n;
+        if (c0 + 3 < C) {
+          st_quad<ES>(g + static_cast<int64_t>(c0) * ES, o);
+        } else {
+          st_elem<ES>(g, c0, o.x);
+          if (c0 + 1 < C) st_elem<ES>(g, c0 + 1, o.y);
+          if (c0 + 2 < C) st_elem<ES>(g, c0 + 2, o.z);
+        }
+      }
+      if (lab >= 0 && lab < C) {
+        // the label is the same on every lane: its logit is read from the lane that holds it
+        const float at_label = __shfl(own, (lab >> 2) & (kWave - 1));
+        nll += logf(se) + mx - at_label;
+      }
+    }
   }
   if (block_loss) {
     if (lane == 0) wave_loss[wave] = nll;
