@@ -120,6 +120,10 @@ def main():
     ap.add_argument("--backbone", default="gcn", choices=["gcn", "gat"],
                     help="gcn: the normalised-adjacency aggregation (the headline); gat: the graph "
                          "attention backbone (edge softmax aggregation, three edge passes per layer)")
+    ap.add_argument("--graph", action="store_true",
+                    help="after the timed steps also replay the step from a HIP graph (one graph holds "
+                         "tau consecutive steps) and report its time under \"graph\": for the workloads "
+                         "whose step is bound by launch latency")
     ap.add_argument("--cold", action="store_true",
                     help="rewrite a 1 GiB buffer before every library call, so that no call finds "
                          "its inputs in the caches (for the workloads whose working set fits "
@@ -276,6 +280,25 @@ def main():
     dominant = max(single, key=lambda k: roof_all[k]["ms_per_step"])
     roofline = dict(kernel=KERNEL_OF_CLASS.get(dominant, dominant), **roof_all[dominant])
 
+    # ---- optional: the same steps replayed from a HIP graph
+    graph_info = None
+    if args.graph:
+        while step.t % step.graph_period() != 0:
+            step.forward_backward()
+        torch.cuda.synchronize()
+        replay = step.capture()
+        replay()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // replay.period)
+        tg = time.perf_counter()
+        for _ in range(reps):
+            replay()
+        torch.cuda.synchronize()
+        g_ms = 1e3 * (time.perf_counter() - tg) / (reps * replay.period)
+        graph_info = {"steps_per_replay": replay.period, "replays": reps, "ms_per_step": round(g_ms, 4),
+                      "gteps": round(edges / (g_ms * 1e-3) / 1e9, 3), "loss": round(float(step.loss.item()), 6)}
+        log("HIP graph replay: %.3f ms/step (eager %.3f)" % (g_ms, ms_per_step))
+
     # ---- optional: one training step of the predictor of hidden layer 1
     ptrain = None
     if args.predictor_train and not args.bypass and L >= 2:
@@ -401,6 +424,7 @@ def main():
         "roofline": roofline,
         "roofline_all": roof_all,
         "cpu_baseline": cpu,
+        "graph": graph_info,
         "predictor_train": ptrain,
         "codec": codec,
         "loss": round(loss, 6),

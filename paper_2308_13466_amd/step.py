@@ -195,6 +195,41 @@ class PartitionStep:
                     self.dH[l], ld[l], dtype=dt, stream=st))
         self.t += 1
 
+    # ------------------------------------------------------------ HIP graph
+    def graph_period(self):
+        """Steps after which the call sequence repeats with the same buffers: the history ring
+        comes back to the same slots every tau steps, the predictions to the same cadence
+        every predict_every steps, the gradient tables every 2 steps."""
+        period = int(np.lcm(self.tau, self.predict_every))
+        if self.grad_tables is not None:
+            period = int(np.lcm(period, 2))
+        return period
+
+    def capture(self):
+        """Record graph_period() consecutive steps into one HIP graph (every entry point of the
+        library only enqueues kernels on the given stream, so the whole step is capturable) and
+        return a function that replays them; each replay advances the step counter by the
+        period. For the workloads whose step is bound by launch latency. Must be called with
+        self.t a multiple of the period and after at least one eager step (so that nothing is
+        loaded lazily during capture); per-call timers are off inside the graph."""
+        period = self.graph_period()
+        assert self.t % period == 0 and self.t > 0, "capture after a whole number of periods, not at t = 0"
+        timers, self.timers = self.timers, None
+        t0 = self.t
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(period):
+                self.forward_backward()
+        self.t = t0               # capturing ran nothing
+        self.timers = timers
+
+        def replay():
+            graph.replay()
+            self.t += period
+        replay.period = period
+        replay.graph = graph
+        return replay
+
     # ------------------------------------------------------------ accounting
     def edges_per_step(self):
         """CSR entries walked by the aggregation calls of one step: nnz per

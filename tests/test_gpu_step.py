@@ -250,3 +250,40 @@ def test_predictor_update_frequency():
     ids = np.concatenate([oview["local_ids"], oview["halo_ids"]])
     ring = [gu.to_host(hist_d[1][s], dims[1])[ids] for s in (0, 1)]
     gu.assert_close(halo[2], orc.predict(oview, omegas[1], ring), RTOL, "refreshed prediction")
+
+
+def test_step_replayed_from_a_hip_graph_matches_eager_steps():
+    """tau consecutive steps captured into one HIP graph and replayed several times, with the
+    program's own eager work and synchronisations between the replays: after every replay the
+    loss, the weight gradients and the history ring equal, bit for bit, what the same number
+    of eager steps leaves on an identical second instance."""
+    import torch
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd.workload import build_workload
+    print("[case] HIP graph replay vs eager steps, tiny", flush=True)
+    sat.lib()
+    eager = build_workload("tiny").step
+    graphed = build_workload("tiny").step
+    period = graphed.graph_period()
+    assert period == graphed.tau
+    for _ in range(period):           # one eager period on both before the capture
+        eager.forward_backward()
+        graphed.forward_backward()
+    torch.cuda.synchronize()
+    replay = graphed.capture()
+    scratch = torch.zeros(1 << 20, device="cuda:0")
+    for rep in range(4):
+        replay()
+        for _ in range(period):
+            eager.forward_backward()
+        scratch.add_(1.0)             # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        assert graphed.t == eager.t
+        assert torch.equal(graphed.loss, eager.loss), rep
+        for l in range(eager.L):
+            assert torch.equal(graphed.dW[l], eager.dW[l]), (rep, l)
+        for l in range(1, eager.L):
+            for s in range(eager.tau):
+                assert torch.equal(graphed.hist[l][s], eager.hist[l][s]), (rep, l, s)
+            assert torch.equal(graphed.Hbar[l], eager.Hbar[l]), (rep, l)
+    assert float(scratch[0].item()) == 4.0
