@@ -15,10 +15,15 @@
 // Layout: a workgroup of 256 threads (4 wavefronts, 2 x 2) owns a 128 x 128
 // tile, K in steps of 32. Operand tiles are staged in LDS per piece as
 // [mn][k] bf16 with k contiguous, 64 bytes per row and no padding; the four
-// 16-byte chunks of a row are stored at chunk ^ ((row >> 1) & 3). A lane's MFMA
-// operand (8 consecutive k of one row) is one 16-byte LDS read, and with this
-// swizzle both those reads (32 consecutive rows, one chunk) and the tile
-// writes (whole rows) are free of bank conflicts. fp32 operands are split while
+// 16-byte chunks of a row are stored at chunk ^ f(row), f = (bit1 ^ bit3) | bit2 << 1
+// of the row number. A lane's MFMA operand (8 consecutive k of one row) is one
+// 16-byte LDS read; LDS has 64 banks of 4 bytes and serves such a read 16 lanes
+// at a time, so 16 consecutive rows of one chunk must land on 16 different
+// 16-byte bank groups: the row's bit 0 picks the half of the 128-byte line, f
+// the chunk, and bits 1..3 all enter f, which makes them distinct (measured:
+// no bank conflicts in these reads; with f = (row >> 1) & 3 rows r and r + 8
+// collided and a third of the LDS cycles were conflicts). Tile writes (whole
+// rows) are conflict free under either. fp32 operands are split while
 // they are written to LDS; global loads for step i+1 are issued before the
 // MFMAs of step i.
 #ifndef SAT_MX_TILE_H_
@@ -43,7 +48,8 @@ constexpr int ROW_B = BK * 2;  // bytes per staged row: 32 bf16, chunks swizzled
 
 // byte offset inside a staged piece of 16-byte chunk `chunk` (0..3) of row `row`
 __device__ __forceinline__ int swz(int row, int chunk) {
-  return row * ROW_B + ((chunk ^ ((row >> 1) & 3)) << 4);
+  const int f = (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
+  return row * ROW_B + ((chunk ^ f) << 4);
 }
 
 template <int MN>
