@@ -133,6 +133,17 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
                                               8 * kc);
     }
   };
+  // the chunks i with i % 6 == part only (the six parts together are load_w)
+  auto load_w_part = [&](const uint16_t* P, int kp, int k0, u32x4 (&rw)[B_CHUNKS], auto part_tag) {
+    constexpr int PART = decltype(part_tag)::value;
+#pragma unroll
+    for (int i = PART; i < B_CHUNKS; i += 6) {
+      const int ch = t + NT * i;
+      const int piece = ch / (NB * 4), n = (ch >> 2) % NB, kc = ch & 3;
+      rw[i] = *reinterpret_cast<const u32x4*>(P + (static_cast<int64_t>(piece) * NB + n) * kp + k0 +
+                                              8 * kc);
+    }
+  };
   auto store_w = [&](const u32x4 (&rw)[B_CHUNKS]) {
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
@@ -220,7 +231,7 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
     // the h pieces in Hs (padded rows), k chunk offset a_kc0. NPA = number of A
     // pieces: 3 for fp32 data (six products), 1 for bf16 x (three products:
     // the value itself against each weight piece, smallest first).
-    auto products = [&](auto npa_tag, const unsigned char* Ax, int a_kc0) {
+    auto products = [&](auto npa_tag, const unsigned char* Ax, int a_kc0, auto&& mid) {
       constexpr int NPA = decltype(npa_tag)::value;
       constexpr int NQ = NPA == 3 ? (NPB == 3 ? 6 : 5) : NPB;
 #pragma unroll
@@ -237,6 +248,8 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
         // two gates at a time: their weight fragments are all that is held besides a
 #pragma unroll
         for (int gp = 0; gp < 2; ++gp) {
+          // the step's global loads go out a few at a time between the blocks of products: issued
+          // in one burst they hold the wavefront at the memory pipe while the matrix pipe idles
           bf16x8 b[2][NPB];
 #pragma unroll
           for (int p = 0; p < NPB; ++p)
@@ -245,6 +258,13 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
               b[g][p] = read_operand(Bs + p * piece_bytes<NB>(), (2 * gp + g) * DS + 32 * wn, kc, lane);
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
+            // the step's global loads go out one or two at a time between the products: issued in
+            // one burst they hold the wavefront at the memory pipe while the matrix pipe idles
+            if (q == 0 || q == NQ / 2) {
+              __builtin_amdgcn_sched_barrier(0);
+              mid(4 * kc + 2 * gp + (q == 0 ? 0 : 1));
+              __builtin_amdgcn_sched_barrier(0);
+            }
             // (a piece, b piece), smallest terms first; with two weight pieces against three
             // pieces of h: (2,0) (1,1) (1,0) (0,1) (0,0)
             const int pa = NPA == 3 ? (NPB == 3 ? product_a<3>(q) : (q == 0 ? 2 : (q < 3 ? 1 : 0))) : 0;
@@ -281,10 +301,23 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
       store_w(rw);
       store_x(ra0, As + ((j + 1) & 1) * tile_bytes<R, NP>(), j + 1);
       __syncthreads();
-      load_x(j + 2, ra0);
-      if (i + 1 < nk) load_w(WxP, k_pad, (i + 1) * BK, rw);
-      else if (s > 0) load_w(WhP, DS, 0, rw);
-      products(std::integral_constant<int, ESX == 4 ? 3 : 1>{}, As + (j & 1) * tile_bytes<R, NP>(), 0);
+      // next weight tile: the input part's next one, or the recurrent part's first
+      const bool w_in = i + 1 < nk;
+      const bool w_any = w_in || s > 0;
+      const uint16_t* wP = w_in ? WxP : WhP;
+      const int w_kp = w_in ? k_pad : DS;
+      const int w_k0 = w_in ? (i + 1) * BK : 0;
+      auto mid = [&](int blk) __attribute__((always_inline)) {   // blk = 0..7
+        if (blk == 0) load_x(j + 2, ra0);
+        else if (!w_any || blk == 1) return;
+        else if (blk == 2) load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 0>{});
+        else if (blk == 3) load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 1>{});
+        else if (blk == 4) load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 2>{});
+        else if (blk == 5) load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 3>{});
+        else if (blk == 6) load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 4>{});
+        else load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 5>{});
+      };
+      products(std::integral_constant<int, ESX == 4 ? 3 : 1>{}, As + (j & 1) * tile_bytes<R, NP>(), 0, mid);
     }
     // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
     if (s > 0) {
@@ -292,8 +325,17 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
         __syncthreads();
         store_w(rw);
         __syncthreads();
-        if (k0 + BK < DS) load_w(WhP, DS, k0 + BK, rw);
-        products(std::integral_constant<int, 3>{}, nullptr, k0 / 16);
+        const bool w_more = k0 + BK < DS;
+        auto mid = [&](int blk) __attribute__((always_inline)) {
+          if (blk < 2 || !w_more) return;
+          if (blk == 2) load_w_part(WhP, DS, k0 + BK, rw, std::integral_constant<int, 0>{});
+          else if (blk == 3) load_w_part(WhP, DS, k0 + BK, rw, std::integral_constant<int, 1>{});
+          else if (blk == 4) load_w_part(WhP, DS, k0 + BK, rw, std::integral_constant<int, 2>{});
+          else if (blk == 5) load_w_part(WhP, DS, k0 + BK, rw, std::integral_constant<int, 3>{});
+          else if (blk == 6) load_w_part(WhP, DS, k0 + BK, rw, std::integral_constant<int, 4>{});
+          else load_w_part(WhP, DS, k0 + BK, rw, std::integral_constant<int, 5>{});
+        };
+        products(std::integral_constant<int, 3>{}, nullptr, k0 / 16, mid);
       }
     }
     // ---- cell update, register-local
