@@ -111,15 +111,18 @@ struct TileRegs {
   int kleft;
 };
 
+// part: -1 = the whole share, 0 / 1 = its first / second half (the two halves together are the whole)
 template <int MN, Layout L, bool MASK>
 __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_t mn_lim,
-                                          int64_t k0, int64_t k_lim, TileRegs<MN>& r, int t) {
+                                          int64_t k0, int64_t k_lim, TileRegs<MN>& r, int t,
+                                          int part = -1) {
   if constexpr (L == Layout::KContig) {
     const int64_t k = k0 + ((t & 7) << 2);
     const int64_t left = k_lim - k;
     r.kleft = left > 4 ? 4 : static_cast<int>(left);
 #pragma unroll
     for (int i = 0; i < MN / 32; ++i) {
+      if (part >= 0 && (2 * i) / (MN / 32) != part) continue;
       f32x4 v = {0.f, 0.f, 0.f, 0.f}, h = {0.f, 0.f, 0.f, 0.f};
       const int64_t mn = mn0 + (t >> 3) + 32 * i;
       if (mn < mn_lim && k < k_lim) {
@@ -139,6 +142,7 @@ __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_
     r.kleft = 4;
 #pragma unroll
     for (int g = 0; g < MN / 64; ++g) {
+      if (part >= 0 && (2 * g) / (MN / 64) != part) continue;
       const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
       float e[8];
 #pragma unroll
@@ -214,7 +218,8 @@ __device__ __forceinline__ bool bf16_pos(uint32_t h) { return (h & 0x8000u) == 0
 
 template <int MN, Layout L, bool MASK>
 __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int64_t mn_lim,
-                                            int64_t k0, int64_t k_lim, TileRegsB<MN>& r, int t) {
+                                            int64_t k0, int64_t k_lim, TileRegsB<MN>& r, int t,
+                                            int part = -1) {
   const uint16_t* P = static_cast<const uint16_t*>(op.p);
   const uint16_t* Mk = static_cast<const uint16_t*>(op.mask);
   if constexpr (L == Layout::KContig) {
@@ -223,6 +228,7 @@ __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int6
     r.kleft = left > 8 ? 8 : static_cast<int>(left);
 #pragma unroll
     for (int i = 0; i < MN / 64; ++i) {
+      if (part >= 0 && (2 * i) / (MN / 64) != part) continue;
       const int c = t + 256 * i;
       const int64_t mn = mn0 + (c >> 2);
       u32x4 v = {0u, 0u, 0u, 0u}, h = {0u, 0u, 0u, 0u};
@@ -242,6 +248,7 @@ __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int6
     r.kleft = 8;
 #pragma unroll
     for (int g = 0; g < MN / 64; ++g) {
+      if (part >= 0 && (2 * g) / (MN / 64) != part) continue;
       const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
       uint32_t e[8];
 #pragma unroll
@@ -294,9 +301,10 @@ template <int MN> struct RegsOf<2, MN> { typedef TileRegsB<MN> type; };
 
 template <int ES, int MN, Layout L, bool MASK>
 __device__ __forceinline__ void load_any(const Operand& op, int64_t mn0, int64_t mn_lim, int64_t k0,
-                                         int64_t k_lim, typename RegsOf<ES, MN>::type& r, int t) {
-  if constexpr (ES == 4) load_tile<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t);
-  else load_tile_b<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t);
+                                         int64_t k_lim, typename RegsOf<ES, MN>::type& r, int t,
+                                         int part = -1) {
+  if constexpr (ES == 4) load_tile<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t, part);
+  else load_tile_b<MN, L, MASK>(op, mn0, mn_lim, k0, k_lim, r, t, part);
 }
 template <int ES, int MN, Layout L, bool MASK>
 __device__ __forceinline__ void store_any(const typename RegsOf<ES, MN>::type& r, unsigned char* S,
@@ -325,9 +333,12 @@ constexpr int product_b(int q) {
 }
 
 // acc[i][j] += A(64 wm + 32 i .., :) * B(64 wn + 32 j .., :)^T over one BK step.
-template <int NP>
+// mid(b), b = 0..3: called between blocks of products; the kernel issues the next step's global
+// loads there, a quarter at a time (issued in one burst they hold the wavefront at the memory
+// pipe while the matrix pipe idles).
+template <int NP, class Mid>
 __device__ __forceinline__ void mma_step(const unsigned char* As, const unsigned char* Bs, int wm,
-                                         int wn, int lane, f32x16 (&acc)[2][2]) {
+                                         int wn, int lane, f32x16 (&acc)[2][2], Mid&& mid) {
 #pragma unroll
   for (int kc = 0; kc < BK / 16; ++kc) {
     bf16x8 a[2][NP], b[2][NP];
@@ -339,13 +350,20 @@ __device__ __forceinline__ void mma_step(const unsigned char* As, const unsigned
         b[i][p] = read_operand(Bs + p * piece_bytes<BN>(), 64 * wn + 32 * i, kc, lane);
       }
 #pragma unroll
-    for (int q = 0; q < n_products<NP>(); ++q)
+    for (int q = 0; q < n_products<NP>(); ++q) {
+      if (q == 0 || (n_products<NP>() > 1 && q == n_products<NP>() / 2)) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (n_products<NP>() > 1) mid(2 * kc + (q == 0 ? 0 : 1));
+        else { mid(2 * kc); mid(2 * kc + 1); }   // one product per block: two quarters at once
+        __builtin_amdgcn_sched_barrier(0);
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
               a[i][product_a<NP>(q)], b[j][product_b<NP>(q)], acc[i][j], 0, 0, 0);
+    }
   }
 }
 
@@ -415,11 +433,13 @@ __global__ __launch_bounds__(256, 2) void gemm_kernel(Operand A, Operand B, int6
     store_any<ESI, BM, LA, MASK_A>(ra, As, t);
     store_any<ESI, BN, LB, MASK_B>(rb, Bs, t);
     __syncthreads();
-    if (k0 + BK < k_end) {
-      load_any<ESI, BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t);
-      load_any<ESI, BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t);
-    }
-    mma_step<NP>(As, Bs, wm, wn, lane, acc);
+    const bool more = k0 + BK < k_end;
+    auto mid = [&](int blk) __attribute__((always_inline)) {   // blk = 0..3: A halves, then B halves
+      if (!more) return;
+      if (blk < 2) load_any<ESI, BM, LA, MASK_A>(A, m0, M, k0 + BK, k_end, ra, t, blk);
+      else load_any<ESI, BN, LB, MASK_B>(B, n0, N, k0 + BK, k_end, rb, t, blk - 2);
+    };
+    mma_step<NP>(As, Bs, wm, wn, lane, acc, mid);
   }
 
   // ---- epilogue: the tile goes through LDS (the operand staging is free now)
