@@ -20,6 +20,9 @@ rows, which are constants of the step):
     H'     = relu(OUT) on hidden layers, OUT on the last
 The neighbourhood of a local node i is row i of the partition view's CSR
 [P_in | P_out] (self-loop included); its stored values A_hat are not used.
+A row without entries cannot come from a partition view (the self-loop is always
+there); for hand-made views it is defined as OUT_i = 0, contributing nothing to
+any gradient (an empty sum).
 
 Readings (the paper is silent on all of them): heads are concatenated on every
 layer (a last layer with one head is the usual classifier); slope 0.2; no bias, no
@@ -70,6 +73,8 @@ def gat_aggregate_fwd(view, Z, el, er, slope, rows=None):
     rows = range(view["n_local"]) if rows is None else rows
     out = np.zeros((len(rows), K * F), dtype=np.float64)
     for r, i in enumerate(rows):
+        if view["rowptr"][i + 1] == view["rowptr"][i]:
+            continue                          # empty sum
         cols, _, alpha = gat_row_attention(view, i, el, er, slope)
         out[r] = np.einsum("jk,jkf->kf", alpha, Z[cols].reshape(-1, K, F)).reshape(-1)
     return out
@@ -93,6 +98,8 @@ def gat_aggregate_bwd(view, Z, el, er, slope, dOUT, rows=None):
     d_el = np.zeros((n_local, K), dtype=np.float64)
     d_er = np.zeros((n_bar, K), dtype=np.float64)
     for i in (range(n_local) if rows is None else rows):
+        if view["rowptr"][i + 1] == view["rowptr"][i]:
+            continue                          # empty sum
         cols, s, alpha = gat_row_attention(view, i, el, er, slope)
         zc = Z[cols].reshape(-1, K, F)
         dalpha = np.einsum("kf,jkf->jk", G[i], zc)

@@ -6,6 +6,7 @@ row among empty ones, zero rows, and the halo-free / local-free partitions."""
 import numpy as np
 import pytest
 
+from oracle import gat_oracle as gat
 from oracle import sat_oracle as orc
 
 pytestmark = pytest.mark.gpu
@@ -160,3 +161,121 @@ def test_partition_without_halo_whole_step(env):
     Hfull = orc.full_graph_gcn(g.N, g.rowptr, g.col, X, Ws)
     gu.assert_close(gu.to_host(step.logits, dims[2]), Hfull[2], 2e-5, "logits")
     gu.assert_close(gu.to_host(step.Hbar[1], dims[1]), Hfull[1], 2e-5, "H^(1)")
+
+
+def _gat_view(case, rng):
+    """Hand-made view for the attention kernels. The local-local block is symmetric
+    (the backward walks rows for the transposed product, as the aggregation's does)."""
+    n_local, n_halo = 70, (0 if case == "halo_free" else 9)
+    adj = rng.random((n_local, n_local)) < 0.08
+    adj = adj | adj.T
+    np.fill_diagonal(adj, True)
+    hal = rng.random((n_local, n_halo)) < 0.15
+    isolated = [3, 4, 5, 31, 32, 63, 64, 69]       # rows without entries, runs of them, the last row
+    selfonly = [10, 11]                            # the self-loop and nothing else
+    for i in isolated + selfonly:
+        adj[i, :] = False
+        adj[:, i] = False
+        hal[i, :] = False
+    for i in selfonly:
+        adj[i, i] = True
+    if n_halo:
+        hal[:, n_halo - 1] = False                 # a halo node that no row refers to
+    if case == "all_empty":
+        adj[:] = False
+        hal[:] = False
+    rows = []
+    for i in range(n_local):
+        c = np.concatenate([np.nonzero(adj[i])[0], n_local + np.nonzero(hal[i])[0]])
+        rows.append((c, np.ones(c.size)))
+    return _view(n_local, n_halo, rows), isolated
+
+
+@pytest.mark.parametrize("case", ["mixed", "halo_free", "all_empty"])
+def test_gat_degenerate_views(env, case):
+    """Attention forward and backward on views with rows without entries (output 0, statistics
+    (0, 0), no contribution to any gradient), rows that hold their self-loop only (alpha = 1),
+    a halo node nobody refers to (zero gradient), no halo at all, no entries at all."""
+    sat, gu, torch = env
+    print("[case] gat degenerate view: " + case, flush=True)
+    rng = np.random.default_rng(77)
+    v, isolated = _gat_view(case, rng)
+    n_l, n_h = v["n_local"], v["n_halo"]
+    n_bar, heads, d_head, slope = n_l + n_h, 2, 8, 0.2
+    d = heads * d_head
+    ld = gu.ld_for(d, 8)
+    Z = rng.standard_normal((n_bar, d)).astype(np.float32)
+    a_dst = (rng.standard_normal((heads, d_head)) / np.sqrt(d_head)).astype(np.float32)
+    a_src = (rng.standard_normal((heads, d_head)) / np.sqrt(d_head)).astype(np.float32)
+    el_ref, er_ref = gat.gat_scores(Z, a_dst, a_src)
+    el32, er32 = el_ref[:n_l].astype(np.float32), er_ref.astype(np.float32)
+    el64, er64 = el32.astype(np.float64), er32.astype(np.float64)
+    Z_d, el_d, er_d = gu.to_dev(Z, ld), gu.to_dev(el32), gu.to_dev(er32)
+    a_dst_d, a_src_d = gu.to_dev(a_dst.reshape(-1)), gu.to_dev(a_src.reshape(-1))
+    pv = gu.upload_view(v)
+    st = gu.stream_ptr()
+    H_d = torch.full((n_l, ld), float("nan"), dtype=torch.float32, device=gu.DEV)
+    stats_d = torch.full((n_l, heads, 2), float("nan"), dtype=torch.float32, device=gu.DEV)
+    sat.gat_aggregate_fwd(pv, Z_d, ld, heads, d_head, el_d, er_d, slope, sat.ACT_IDENTITY, H_d, ld,
+                          stats_d, dtype=sat.F32, stream=st)
+    gu.sync()
+    OUT = gat.gat_aggregate_fwd(v, Z, el64, er64, slope)
+    H = H_d.cpu().numpy()
+    gu.assert_close(H[:, :d], OUT, RTOL, "H")
+    stats = stats_d.cpu().numpy()
+    lengths = np.diff(v["rowptr"])
+    assert np.all(H[lengths == 0, :d] == 0.0) and np.all(stats[lengths == 0] == 0.0)
+    one = lengths == 1     # a single entry: alpha = 1, the row is a copy, 1 / sum = 1
+    if one.any():
+        rows1 = np.nonzero(one)[0]
+        assert np.array_equal(H[rows1, :d], Z[v["col"][v["rowptr"][rows1]]])
+        assert np.all(stats[one, :, 1] == 1.0)
+
+    dH = (rng.standard_normal((n_l, d)) / np.sqrt(n_l)).astype(np.float32)
+    cache = dict(Z=Z.astype(np.float64), el=el64, er=er64, H=OUT, Hbar=np.zeros((n_bar, 1)))
+    ref = gat.gat_layer_bwd(v, cache, np.zeros((1, d)), a_dst, a_src, slope, 0, dH.astype(np.float64))
+    wsb = sat.gat_aggregate_bwd_workspace_bytes(n_l, n_h, heads, d_head, sat.F32)
+    ws = gu.workspace(wsb)
+    dZ_d = torch.full((n_bar, ld), float("nan"), dtype=torch.float32, device=gu.DEV)
+    da_dst_d = torch.full((d,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    da_src_d = torch.full((d,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    sat.gat_aggregate_bwd(pv, Z_d, ld, heads, d_head, el_d, er_d, stats_d, slope, sat.ACT_IDENTITY,
+                          gu.to_dev(dH, ld), ld, None, 0, a_dst_d, a_src_d, dZ_d, ld, da_dst_d, da_src_d,
+                          dtype=sat.F32, workspace=ws, workspace_bytes=wsb, stream=st)
+    gu.sync()
+    dZ = dZ_d.cpu().numpy()[:, :d]
+    assert np.all(np.isfinite(dZ))
+    gu.assert_close(dZ, ref["dZ"], 4 * RTOL, "dZ")       # three terms that may cancel
+    gu.assert_close(da_dst_d.cpu().numpy().reshape(heads, d_head), ref["da_dst"], RTOL, "da_dst")
+    gu.assert_close(da_src_d.cpu().numpy().reshape(heads, d_head), ref["da_src"], RTOL, "da_src")
+    # nodes nobody aggregates from get no gradient: the isolated rows, the unreferenced halo node
+    untouched = list(isolated) if case != "all_empty" else list(range(n_bar))
+    if n_h and case != "all_empty":
+        untouched.append(n_bar - 1)
+    assert np.all(dZ[untouched] == 0.0)
+
+
+def test_gat_zero_sized_calls(env):
+    sat, gu, torch = env
+    print("[case] gat zero-sized calls", flush=True)
+    st = gu.stream_ptr()
+    heads, d_head = 2, 8
+    d = heads * d_head
+    x = gu.dev_empty(4, d)
+    a = gu.to_dev(np.ones(d, np.float32))
+    sc = torch.full((8,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    sat.gat_scores(x, d, 0, 0, heads, d_head, a, a, sc, sc, dtype=sat.F32, stream=st)
+    v = _view(0, 0, [])
+    pv = gu.upload_view(v)
+    stats = torch.full((8,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    sat.gat_aggregate_fwd(pv, x, d, heads, d_head, sc, sc, 0.2, sat.ACT_IDENTITY, x, d, stats,
+                          dtype=sat.F32, stream=st)
+    wsb = sat.gat_aggregate_bwd_workspace_bytes(0, 0, heads, d_head, sat.F32)
+    ws = gu.workspace(wsb)
+    da1 = torch.full((d,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    da2 = torch.full((d,), float("nan"), dtype=torch.float32, device=gu.DEV)
+    sat.gat_aggregate_bwd(pv, x, d, heads, d_head, sc, sc, stats, 0.2, sat.ACT_IDENTITY, x, d, None, 0,
+                          a, a, x, d, da1, da2, dtype=sat.F32, workspace=ws, workspace_bytes=wsb, stream=st)
+    gu.sync()
+    assert np.all(np.isnan(x.cpu().numpy())) and torch.isnan(sc).all() and torch.isnan(stats).all()
+    assert torch.all(da1 == 0.0) and torch.all(da2 == 0.0)      # empty sums
