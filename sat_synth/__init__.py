@@ -11,7 +11,7 @@ from .graphs import (Graph, sbm_graph, chung_lu_planted_graph, chung_lu_partitio
 from .tensors import (substreams, normal_f32, glorot_uniform_f32, labels_i32,
                       predictor_params_f32, history_standin_f32, bf16_bits_from_f32,
                       f32_from_bf16_bits, device_normal, device_history_standin, gat_heads,
-                      attention_vectors_f32)
+                      attention_vectors_f32, drifting_history_f32)
 
 __all__ = [
     "CONFIGS", "get_config", "Graph", "sbm_graph", "chung_lu_planted_graph",
@@ -19,5 +19,5 @@ __all__ = [
     "glorot_uniform_f32", "labels_i32", "predictor_params_f32",
     "history_standin_f32", "bf16_bits_from_f32", "f32_from_bf16_bits",
     "chung_lu_partition_rows", "device_normal", "device_history_standin", "gat_heads",
-    "attention_vectors_f32",
+    "attention_vectors_f32", "drifting_history_f32",
 ]

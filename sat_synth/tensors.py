@@ -121,6 +121,19 @@ def history_standin_f32(ss, rows, cols, tau, noise_std, ld=None):
     return slots
 
 
+def drifting_history_f32(ss, rows, cols, epochs, drift=0.3, spread=0.03, noise=0.01):
+    """`epochs` matrices [rows, cols] (fp32, oldest first) that move at a steady pace:
+    row r of epoch t is base[r] + t * (v + w[r]) + noise, with a velocity v shared by all rows
+    (std `drift` per column), a small row-specific part w (std `spread`) and observation noise.
+    A stand-in for hidden embeddings that keep evolving from epoch to epoch: the newest
+    cached matrix is then a stale estimate of the next one, by about |v| per entry."""
+    rng = _rng(ss)
+    base = np.maximum(rng.standard_normal((rows, cols)), 0)
+    vel = drift * rng.standard_normal(cols)[None, :] + spread * rng.standard_normal((rows, cols))
+    return [(base + t * vel + noise * rng.standard_normal((rows, cols))).astype(np.float32)
+            for t in range(epochs)]
+
+
 def bf16_bits_from_f32(a):
     """Round fp32 values to bfloat16 (nearest, ties to even); returns the 16-bit
     patterns as uint16. A storage-format conversion only."""

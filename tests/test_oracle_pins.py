@@ -687,3 +687,38 @@ def test_polyline_round_trip_error_bound_and_lengths():
     assert sizes[0] < sizes[1] < sizes[2]
     base = np.maximum(rng.standard_normal((200, 256)), 0).astype(np.float32)
     assert 4.0 * base.size / orc.polyline_encode_rows(base, 1)[1][-1] > 3.0
+
+
+# ------------------------------------------------ what the predictor is for
+def test_trained_predictor_alleviates_staleness_on_drifting_embeddings():
+    """The method's premise (Sec. "Embedding Predictor", the constraint of Eq. 8': the predicted
+    embedding must be less stale than the cached one): on embeddings that keep moving from
+    epoch to epoch, a predictor trained on the partition's own fresh embeddings (local rows,
+    Eq. 11) must bring the HALO rows, which it never saw a target for, closer to their true
+    next value than the newest cached rows are. Plain gradient steps, the oracle alone."""
+    cfg = syn.get_config("tiny")
+    g = syn.make_graph(cfg, np.random.default_rng(syn.substreams(0)["graph"]))
+    v = orc.partition_view(g.N, g.rowptr, g.col, g.part, 0)
+    n_l, n_bar = v["n_local"], v["n_local"] + v["n_halo"]
+    d, d_s, tau = 16, 32, 2
+    H = syn.drifting_history_f32(np.random.SeedSequence(3), n_bar, d, tau + 1)
+    win, fresh = H[:tau], H[tau].astype(np.float64)
+    p = syn.predictor_params_f32(np.random.SeedSequence(3), d, d_s)
+    om = {k: p[k].astype(np.float64) for k in p}
+    cached = orc.staleness(fresh[n_l:], win[-1][n_l:])
+    before = orc.staleness(fresh[n_l:], orc.predict(v, om, win))
+    losses = []
+    for _ in range(20):
+        loss, gr = orc.predictor_train_loss_and_grad(v, om, win, fresh[:n_l])
+        losses.append(loss)
+        for k in om:
+            om[k] -= 2.0 * gr[k]
+    after = orc.staleness(fresh[n_l:], orc.predict(v, om, win))
+    assert losses[-1] < 0.1 * losses[0]
+    assert after < 0.8 * cached and after < before       # delta(H_hat) < delta(H): Eq. 8'
+    # the untrained predictor (random parameters) is no better than the cached rows
+    assert before > 0.95 * cached
+    # and without drift there is nothing to gain: the loss starts at the noise floor
+    still = [H[0]] * tau
+    l0, _ = orc.predictor_train_loss_and_grad(v, {k: p[k] * 0 for k in p}, still, H[0][:n_l])
+    assert l0 == 0.0
