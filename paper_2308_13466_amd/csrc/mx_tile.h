@@ -145,11 +145,17 @@ __device__ __forceinline__ void load_tile(const Operand& op, int64_t mn0, int64_
       if (part >= 0 && (2 * g) / (MN / 64) != part) continue;
       const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
       float e[8];
+      if (mn_ok && k8 + 8 <= k_lim) {   // the usual case: one test for the eight loads
+        const float* src = static_cast<const float*>(op.p) + k8 * op.ld + mn;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        float x = 0.f;
-        if (mn_ok && k8 + j < k_lim) x = static_cast<const float*>(op.p)[(k8 + j) * op.ld + mn];
-        e[j] = x;
+        for (int j = 0; j < 8; ++j) e[j] = src[j * op.ld];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          float x = 0.f;
+          if (mn_ok && k8 + j < k_lim) x = static_cast<const float*>(op.p)[(k8 + j) * op.ld + mn];
+          e[j] = x;
+        }
       }
       r.v[2 * g] = f32x4{e[0], e[1], e[2], e[3]};
       r.v[2 * g + 1] = f32x4{e[4], e[5], e[6], e[7]};
@@ -251,11 +257,17 @@ __device__ __forceinline__ void load_tile_b(const Operand& op, int64_t mn0, int6
       if (part >= 0 && (2 * g) / (MN / 64) != part) continue;
       const int64_t k8 = k0 + 8 * ((t / MN) + KG * g);
       uint32_t e[8];
+      if (mn_ok && k8 + 8 <= k_lim) {   // the usual case: one test for the eight loads
+        const uint16_t* src = P + k8 * op.ld + mn;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        uint32_t x = 0u;
-        if (mn_ok && k8 + j < k_lim) x = P[(k8 + j) * op.ld + mn];
-        e[j] = x;
+        for (int j = 0; j < 8; ++j) e[j] = src[j * op.ld];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          uint32_t x = 0u;
+          if (mn_ok && k8 + j < k_lim) x = P[(k8 + j) * op.ld + mn];
+          e[j] = x;
+        }
       }
       r.v[g] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
     }
