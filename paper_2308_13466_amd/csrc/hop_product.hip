@@ -102,19 +102,23 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
     if (more) ra = load_a(row0 + 32);
     // residual rows of this tile: requested now, used after the products. Thread t owns the
     // 16-byte chunks c = t + 512 i of the 32 x 256 tile: row c / 64, columns 4 (c % 64) .. + 3.
+    // (chunk c's row, c / 64 = wave + 8 i, is the same for the whole wavefront: its table row is
+    // looked up with scalar loads, all four before any of them is waited for)
     f32x4 res[4];
     bool ok[4];
+    int64_t srcs[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int c = t + 512 * i;
-      const int64_t r = row0 + (c >> 6);
-      const int cc = blockIdx.y * 256 + ((c & 63) << 2);
-      int64_t src = -1;
-      if (r < M && cc < d) {
-        src = add_ids ? static_cast<int64_t>(add_ids[r]) : add_base + r;
-        if (src < 0 || src >= add_rows) src = -1;    // bad id: the row is left alone
-      }
-      ok[i] = src >= 0;
+      const int64_t r = row0 + wave + 8 * i;
+      int64_t sr = -1;
+      if (r < M) sr = add_ids ? static_cast<int64_t>(add_ids[r]) : add_base + r;
+      srcs[i] = sr;
+    }
+    const int cc = blockIdx.y * 256 + (lane << 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t src = srcs[i] < add_rows ? srcs[i] : -1;    // bad id (negative or too large): the row is left alone
+      ok[i] = src >= 0 && cc < d;
       res[i] = f32x4{0.f, 0.f, 0.f, 0.f};
       if (ok[i]) {
         if constexpr (ESO == 4) {
