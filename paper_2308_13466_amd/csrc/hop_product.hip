@@ -91,6 +91,16 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
     for (int p = 0; p < NP; ++p) *reinterpret_cast<u32x2*>(s + p * piece_bytes<32>()) = u32x2{lo[p], hi[p]};
   };
 
+  // Chunk c = t + 512 i of a tile lies in row c / 64 = wave + 8 i: the same for the whole wavefront.
+  // Lanes 0..3 fetch the ids of the wavefront's four rows, one tile ahead (so the id list's
+  // latency is never waited for), and the rows' table rows are read out of those lanes.
+  auto load_ids = [&](int64_t row0) __attribute__((always_inline)) {
+    const int64_t r = row0 + wave + 8 * (lane & 3);
+    int32_t v = -1;
+    if (add_ids != nullptr && r < M) v = add_ids[r];
+    return v;
+  };
+  int32_t id_next = load_ids(row_lo);
   u32x4 ra = load_a(row_lo);
   store_a(ra, 0);
   __syncthreads();
@@ -99,11 +109,13 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
     if (row0 >= M) break;                        // uniform over the workgroup
     const int stage = it & 1;
     const bool more = it + 1 < kTilesPerBlock && row0 + 32 < M;
-    if (more) ra = load_a(row0 + 32);
+    const int32_t id_cur = id_next;
+    if (more) {
+      id_next = load_ids(row0 + 32);
+      ra = load_a(row0 + 32);
+    }
     // residual rows of this tile: requested now, used after the products. Thread t owns the
     // 16-byte chunks c = t + 512 i of the 32 x 256 tile: row c / 64, columns 4 (c % 64) .. + 3.
-    // (chunk c's row, c / 64 = wave + 8 i, is the same for the whole wavefront: its table row is
-    // looked up with scalar loads, all four before any of them is waited for)
     f32x4 res[4];
     bool ok[4];
     int64_t srcs[4];
@@ -111,7 +123,8 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
     for (int i = 0; i < 4; ++i) {
       const int64_t r = row0 + wave + 8 * i;
       int64_t sr = -1;
-      if (r < M) sr = add_ids ? static_cast<int64_t>(add_ids[r]) : add_base + r;
+      if (r < M)
+        sr = add_ids ? static_cast<int64_t>(__builtin_amdgcn_readlane(id_cur, i)) : add_base + r;
       srcs[i] = sr;
     }
     const int cc = blockIdx.y * 256 + (lane << 2);
@@ -151,16 +164,35 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) Cs[acc_row(r, lane) * C_LDF + 32 * wave + (lane & 31)] = acc[r];
     __syncthreads();
+    // sums first (one wait for the residual rows), then the stores back to back
+    f32x4 sum[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = t + 512 * i;
+      f32x4 v = *reinterpret_cast<const f32x4*>(&Cs[(c >> 6) * C_LDF + ((c & 63) << 2)]);
+      if constexpr (ESO == 4) {
+        v += res[i];
+      } else {
+        const float rx = res[i].x, ry = res[i].y;
+        const uint32_t w0 = __builtin_bit_cast(uint32_t, rx), w1 = __builtin_bit_cast(uint32_t, ry);
+        v.x += low_as_f32(w0);
+        v.y += high_as_f32(w0);
+        v.z += low_as_f32(w1);
+        v.w += high_as_f32(w1);
+      }
+      sum[i] = v;
+    }
+    // (keeps the four sums, and with them the one wait for the residual rows, in front of the
+    // stores: sunk into the guarded blocks below, each sum would wait for the previous row's
+    // stores to complete as well)
+    asm volatile("" : "+v"(sum[0]), "+v"(sum[1]), "+v"(sum[2]), "+v"(sum[3]));
+    const int left = d - cc;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (!ok[i]) continue;
-      const int c = t + 512 * i;
-      const int64_t r = row0 + (c >> 6);
-      const int cc = blockIdx.y * 256 + ((c & 63) << 2);
-      f32x4 v = *reinterpret_cast<const f32x4*>(&Cs[(c >> 6) * C_LDF + ((c & 63) << 2)]);
-      const int left = d - cc;
+      const int64_t r = row0 + wave + 8 * i;
+      const f32x4 v = sum[i];
       if constexpr (ESO == 4) {
-        v += res[i];
         float* y = static_cast<float*>(out) + r * ld_out + cc;
         if (left >= 4) {
           *reinterpret_cast<f32x4*>(y) = v;
@@ -170,12 +202,6 @@ __global__ __launch_bounds__(512, 4) void hop_product_kernel(
           if (left > 2) y[2] = v.z;
         }
       } else {
-        const float rx = res[i].x, ry = res[i].y;
-        const uint32_t w0 = __builtin_bit_cast(uint32_t, rx), w1 = __builtin_bit_cast(uint32_t, ry);
-        v.x += low_as_f32(w0);
-        v.y += high_as_f32(w0);
-        v.z += low_as_f32(w1);
-        v.w += high_as_f32(w1);
         const u32x2 w = {pack_bf16(v.x, v.y), pack_bf16(v.z, v.w)};
         uint16_t* y = static_cast<uint16_t*>(out) + r * ld_out + cc;
         if (left >= 4) {
