@@ -177,6 +177,95 @@ __global__ __launch_bounds__(256) void encode_kernel(const void* __restrict__ H,
   }
 }
 
+// The same codes, assembled in LDS and written out in 16-byte pieces. One wavefront per row;
+// a lane takes the 16 / ES values of one 16-byte load at a time, so a wavefront covers
+// 64 * 16 / ES values per pass: code lengths per lane, one wavefront prefix sum for the lane's
+// byte position, the bytes go to the row's image in LDS. The image sits at the same offset
+// modulo 16 as the row's place in the code array (phase = row_off % 16), so that its whole
+// 16-byte pieces go out as aligned 16-byte stores and only the two ends byte by byte. Needs
+// the code array 16-byte aligned and rows of at most row_cap - 16 bytes of code.
+template <int ES>
+__global__ __launch_bounds__(256) void encode_lds_kernel(const void* __restrict__ H, int64_t ld_bytes,
+                                                         int64_t n, int d, float scale,
+                                                         const int64_t* __restrict__ row_off,
+                                                         uint8_t* __restrict__ codes, int64_t capacity,
+                                                         int row_cap) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  constexpr int VPL = 16 / ES;   // values per lane and pass
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int64_t k = static_cast<int64_t>(blockIdx.x) * 4 + wave;
+  if (k >= n) return;
+  const int64_t b0 = row_off[k], b1 = row_off[k + 1];
+  if (b0 < 0 || b1 < b0 || b1 > capacity) return;   // never write outside the caller's buffer
+  const int phase = static_cast<int>(b0 & 15);
+  if (b1 - b0 > row_cap - 16) return;               // (cannot happen: a value takes at most 7 bytes)
+  const int nb = static_cast<int>(b1 - b0);
+  unsigned char* mine = lds + wave * row_cap;
+  const unsigned char* row = static_cast<const unsigned char*>(H) + k * ld_bytes;
+  const bool row_vec = (reinterpret_cast<uintptr_t>(row) & 15u) == 0;
+  int pos = phase;
+  for (int c0 = 0; c0 < d; c0 += kWave * VPL) {
+    const int c = c0 + lane * VPL;
+    uint32_t u[VPL];
+    int len[VPL];
+    int total = 0;
+    if (row_vec && c + VPL <= d) {
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      const u32x4 w = *reinterpret_cast<const u32x4*>(row + static_cast<int64_t>(c) * ES);
+      const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) {
+        float v;
+        if constexpr (ES == 4) v = __builtin_bit_cast(float, ww[j]);
+        else v = __builtin_bit_cast(float, (j & 1) ? (ww[j >> 1] & 0xffff0000u) : (ww[j >> 1] << 16));
+        u[j] = zigzag_of(v, scale);
+        len[j] = groups_of(u[j]);
+        total += len[j];
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) {
+        u[j] = 0;
+        len[j] = 0;
+        if (c + j < d) {
+          u[j] = zigzag_of(load_elem<ES>(row, c + j), scale);
+          len[j] = groups_of(u[j]);
+        }
+        total += len[j];
+      }
+    }
+    const int incl = wave_scan(total, lane);
+    int p = pos + (incl - total);
+    if (p + total <= phase + nb) {   // (holds when row_off came from the plan of the same data)
+#pragma unroll
+      for (int j = 0; j < VPL; ++j) {
+        for (int g = 0; g < len[j]; ++g) {
+          const uint32_t grp = (u[j] >> (5 * g)) & 0x1Fu;
+          mine[p + g] = static_cast<uint8_t>((g + 1 < len[j] ? (grp | 0x20u) : grp) + 63u);
+        }
+        p += len[j];
+      }
+    }
+    pos += __shfl(incl, kWave - 1);
+  }
+  // (a wavefront reads back only what it wrote itself: no barrier needed)
+  // ---- flush: 16-byte pieces of [phase, phase + nb) relative to the aligned address below
+  uint8_t* gbase = codes + (b0 - phase);             // 16-byte aligned (codes is)
+  const int end = phase + nb;
+  const int pieces = (end + 15) >> 4;
+  for (int pc = lane; pc < pieces; pc += kWave) {
+    const int lo = pc << 4, hi = lo + 16;
+    if (lo >= phase && hi <= end) {
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      *reinterpret_cast<u32x4*>(gbase + lo) = *reinterpret_cast<const u32x4*>(mine + lo);
+    } else {
+      const int a = lo > phase ? lo : phase, b = hi < end ? hi : end;
+      for (int i = a; i < b; ++i) gbase[i] = mine[i];
+    }
+  }
+}
+
 // out[k, 0:d) = decoded row (ids ? ids[k] : k); one wavefront per k, LDS slice of row_cap bytes each
 template <int ES>
 __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ codes,
@@ -294,6 +383,19 @@ extern "C" sat_status sat_history_compress_encode(const void* H, int64_t ld_h, i
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int es = dtype == SAT_BF16 ? 2 : 4;
   const float scale = scale_of(precision);
+  // rows of up to 2338 values with a 16-byte aligned code array: assembled in LDS, written in
+  // 16-byte pieces; otherwise byte stores straight to memory
+  const int row_cap = static_cast<int>(round_up(static_cast<int64_t>(kMaxGroups) * d, 16)) + 32;
+  const int smem = 4 * row_cap;
+  if (smem <= 64 * 1024 && (reinterpret_cast<uintptr_t>(codes) & 15u) == 0) {
+    if (es == 4)
+      encode_lds_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), smem, st>>>(
+          H, ld_h * es, n, d, scale, row_off, codes, capacity, row_cap);
+    else
+      encode_lds_kernel<2><<<dim3(static_cast<unsigned>(blocks)), dim3(256), smem, st>>>(
+          H, ld_h * es, n, d, scale, row_off, codes, capacity, row_cap);
+    return sat::check_launch();
+  }
   if (es == 4)
     encode_kernel<4><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(H, ld_h * es, n, d, scale,
                                                                               row_off, codes, capacity);
