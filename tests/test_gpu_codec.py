@@ -72,6 +72,38 @@ def test_codec_fp32_bit_exact(env, n, d, ld, prec):
     print("[case] ratio %.2fx against fp32" % (4.0 * n * d / max(total, 1)), flush=True)
 
 
+@pytest.mark.parametrize("case", ["unaligned_codes", "wide_rows", "unaligned_rows"])
+def test_codec_encoder_paths_give_the_same_bytes(env, case):
+    """The encoder assembles rows in LDS and writes 16-byte pieces when the code array is 16-byte
+    aligned and a row has at most 2338 values, and writes byte by byte otherwise; rows whose start
+    is not 16-byte aligned are read value by value. Every path must give the oracle's bytes."""
+    sat, gu, torch = env
+    print("[case] codec encoder path: " + case, flush=True)
+    rng = np.random.default_rng(31)
+    n, d, ld, prec = (300, 2400, 2400, 2) if case == "wide_rows" else (1500, 130, 131 if case == "unaligned_rows" else 136, 2)
+    H = (np.maximum(rng.standard_normal((n, d)), 0) * 2.0).astype(np.float32)
+    H[rng.integers(0, n, 20), rng.integers(0, d, 20)] = -rng.random(20).astype(np.float32) * 3000.0
+    H_dev = gu.to_dev(H, ld)
+    wsb = sat.history_compress_workspace_bytes(n)
+    ws = torch.zeros(max(wsb // 8, 1) + 1, dtype=torch.int64, device=gu.DEV)
+    row_off = torch.full((n + 1,), -1, dtype=torch.int64, device=gu.DEV)
+    sat.history_compress_plan(H_dev, ld, n, d, prec, row_off, workspace=ws, workspace_bytes=wsb,
+                              stream=gu.stream_ptr())
+    gu.sync()
+    total = int(row_off[-1].item())
+    ref_codes, ref_off = orc.polyline_encode_rows(H, prec)
+    assert np.array_equal(row_off.cpu().numpy(), ref_off) and total == ref_codes.size
+    buf = torch.full((total + 64,), 7, dtype=torch.uint8, device=gu.DEV)
+    shift = 5 if case == "unaligned_codes" else 16
+    codes = buf[shift:shift + total + 16]
+    assert (codes.data_ptr() % 16 == 0) == (case != "unaligned_codes")
+    sat.history_compress_encode(H_dev, ld, n, d, prec, row_off, codes, total, stream=gu.stream_ptr())
+    gu.sync()
+    got = buf.cpu().numpy()
+    assert np.array_equal(got[shift:shift + total], ref_codes)
+    assert np.all(got[:shift] == 7) and np.all(got[shift + total:] == 7)     # nothing outside [0, total)
+
+
 def test_codec_bf16_storage(env):
     sat, gu, torch = env
     from paper_2308_13466_amd import binding as B
