@@ -124,3 +124,16 @@ def test_compute_calls_validate_before_launch(sat):
     assert sat.dense_bwd_workspace_bytes(1000, 64, 32) > 0
     assert sat.predict_workspace_bytes(10, 5, 64, 32, 2) >= 15 * 32 * 4
     assert sat.loss_workspace_bytes(9) >= 4
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One partition on one GPU is all this library does: the benchmark must say so and exit,
+    before it touches a device, when asked for more."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stdout + r.stderr) and "{" not in r.stdout     # no result line
