@@ -473,19 +473,34 @@ __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max
   const bool col_ok = c0 < a.d;
   Chunk<ES> acc;
   acc.zero();
-  if (mine && a.self_val != nullptr && col_ok) {
-    Chunk<ES> x;
-    x.load(a.X + (a.self_off + row) * a.ld_x + c0 * ES);
-    acc.fma(a.self_val[row], x);
-  }
-  for (int64_t base = s; base < e; base += G) {
-    const int cnt = static_cast<int>(e - base < G ? e - base : G);
-    int32_t c = 0;
-    float v = 0.f;
-    if (gl < cnt) {
+  // A row is a chain of dependent loads (its bounds, its entries' ids, the rows they name), and
+  // the chain's length is the kernel's time. So the first chunk of ids is requested before the
+  // loop, together with the diagonal term, and the diagonal term is added after the row's
+  // entries: added first, its load would be waited for before the ids are even requested.
+  auto load_ids = [&](int64_t base, int32_t& c, float& v) {
+    c = 0;
+    v = 0.f;
+    if (base + gl < e) {
       c = a.col[base + gl];
       v = a.val[base + gl];
     }
+  };
+  int32_t c_next;
+  float v_next;
+  load_ids(s, c_next, v_next);
+  const bool with_self = mine && a.self_val != nullptr && col_ok;
+  Chunk<ES> xself;
+  xself.zero();
+  float vself = 0.f;
+  if (with_self) {
+    xself.load(a.X + (a.self_off + row) * a.ld_x + c0 * ES);
+    vself = a.self_val[row];
+  }
+  for (int64_t base = s; base < e; base += G) {
+    const int cnt = static_cast<int>(e - base < G ? e - base : G);
+    int32_t c = c_next;
+    float v = v_next;
+    if (base + G < e) load_ids(base + G, c_next, v_next);
     if (static_cast<uint32_t>(c) >= static_cast<uint64_t>(a.n_x_rows)) {
       c = 0;
       v = 0.f;
@@ -513,6 +528,7 @@ __global__ __launch_bounds__(256) void spmm_group_kernel(SpmmArgs a, int64_t max
       for (int u = 0; u < U; ++u) acc.fma(vj[u], x[u]);
     }
   }
+  if (with_self) acc.fma(vself, xself);
   if (mine && col_ok) acc.store(a.Y + row * a.ld_y + c0 * ES, a.d - c0);
 
   // rows too long for one group: one bit per group, handled one after another
