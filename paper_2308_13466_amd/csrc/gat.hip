@@ -641,11 +641,19 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
   __shared__ float s_w[kWaves][kWave * 2 * K];
   constexpr int HDR = (2 * K + 3) / 4 * 4;
   __shared__ __attribute__((aligned(16))) float s_part[kWaves][HDR + kMaxD];
+  // the two attention vectors, zero past their end: every row's last step adds a multiple of
+  // them, and read from memory there they would be a dependent load (and a wait for every
+  // gather in flight) per row
+  __shared__ __attribute__((aligned(16))) float s_avec[2][kMaxD];
+  for (int i = threadIdx.x; i < kMaxD; i += kWaves * kWave) {
+    s_avec[0][i] = i < a.ln.d ? a_src[i] : 0.f;
+    s_avec[1][i] = i < a.ln.d ? a_dst[i] : 0.f;
+  }
   const LaneIds L = lane_ids(a.ln, K);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock;
   const int nr = static_cast<int>(a.n_rows - row0 < kRowsPerBlock ? a.n_rows - row0 : kRowsPerBlock);
-  flag_long_rows(a, row0, nr, &sp);
+  flag_long_rows(a, row0, nr, &sp);   // (its barrier publishes s_avec as well)
 
   float erj[K], wds[K];
   f32x4 z, acc;
@@ -691,17 +699,10 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
   auto store = [&](int64_t jj, f32x4 sum, float t1, const float (&wd)[K]) {
     const float der = t1 - pick<K>(wd, L.h);
     if (L.grp == 0 && L.col_ok) {
-      f32x4 as(0.f), ad(0.f);
-      if (L.left > 0) as.x = a_src[L.el0];
-      if (L.left > 1) as.y = a_src[L.el0 + 1];
-      if (L.left > 2) as.z = a_src[L.el0 + 2];
-      if (L.left > 3) as.w = a_src[L.el0 + 3];
+      const f32x4 as = *reinterpret_cast<const f32x4*>(&s_avec[0][L.el0]);
       f32x4 o = sum + der * as;
       if (jj < n_local) {
-        if (L.left > 0) ad.x = a_dst[L.el0];
-        if (L.left > 1) ad.y = a_dst[L.el0 + 1];
-        if (L.left > 2) ad.z = a_dst[L.el0 + 2];
-        if (L.left > 3) ad.w = a_dst[L.el0 + 3];
+        const f32x4 ad = *reinterpret_cast<const f32x4*>(&s_avec[1][L.el0]);
         o += d_el[jj * K + L.h] * ad;
       }
       store4<ES>(dZ + jj * ld_dz + static_cast<int64_t>(L.el0) * ES, o, L.left);
