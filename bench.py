@@ -109,6 +109,10 @@ def main():
                          "history slot of hidden layer 1 at this many decimal places: plan + encode "
                          "of the partition's local + halo rows, decode of the halo rows through the "
                          "id list; reported under \"codec\"")
+    ap.add_argument("--coded-ring", type=int, default=None, metavar="DECIMALS",
+                    help="keep the history ring coded (compression codec at this many decimal "
+                         "places) inside the step: the predictor's window is decoded from the "
+                         "codes on every pull and every push codes the fresh rows; GCN backbone")
     ap.add_argument("--stale-grad", action="store_true",
                     help="also run the stale-gradient term of the backward: halo output of the "
                          "transpose aggregation pushed to a gradient table, table rows of the "
@@ -136,6 +140,12 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    if args.coded_ring is not None and (args.backbone != "gcn" or args.predictor_train
+                                        or args.codec is not None or args.unfused_pull):
+        print("bench.py: --coded-ring goes with the GCN backbone and without --predictor-train, "
+              "--codec and --unfused-pull (they read the dense ring)", file=sys.stderr)
+        sys.exit(2)
+
     def log(msg):
         if not args.quiet:
             print("[bench] " + msg, file=sys.stderr, flush=True)
@@ -154,7 +164,7 @@ def main():
     timers = CallTimers(torch, flush)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
-                        predict_every=args.delta_t, backbone=args.backbone)
+                        predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring)
     gat = args.backbone == "gat"
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
@@ -195,6 +205,21 @@ def main():
                   if k.startswith(("spmm_", "gat_fwd_", "gat_bwd_"))) / args.steps
     loss = float(step.loss.item())
     log("ms/step %.3f  GTEPS %.2f  loss %.5f" % (ms_per_step, gteps, loss))
+    coded_ring = None
+    if wl.coded is not None:
+        over = step.coded_overflow()
+        assert not over, "a push did not fit its part of the coded ring: %r" % (over,)
+        own = remote = dense = 0
+        for l in range(1, L):
+            for slot in wl.coded.slots[l]:
+                o, r = slot.coded_bytes()
+                own, remote = own + o, remote + r
+                dense += n_bar * dims[l] * (2 if bf16 else 4)
+        coded_ring = {"decimals": args.coded_ring, "coded_bytes_local_rows": own,
+                      "coded_bytes_halo_rows": remote, "dense_ring_bytes": dense,
+                      "ratio_vs_dense_ring": round(dense / max(1, own + remote), 3)}
+        log("coded ring: %.3f GB of codes for a %.3f GB dense ring (%.2fx)" % (
+            (own + remote) / 1e9, dense / 1e9, coded_ring["ratio_vs_dense_ring"]))
 
     # ---- per-kernel-class roofline figures (algorithmic bytes / flops per launch)
     s = 2 if bf16 else 4
@@ -242,10 +267,17 @@ def main():
             add("dense_bwd", "dense_bwd_l%d" % l, "mfma",
                 (4.0 if l >= 1 else 2.0) * n_l * dims[l] * dims[l + 1])
         if l >= 1:
-            add("push", "push_l%d" % l, "hbm", n_l * (2 * dims[l] * s + 4))
+            if args.coded_ring is None:
+                add("push", "push_l%d" % l, "hbm", n_l * (2 * dims[l] * s + 4))
+            else:
+                add("coded_push", "push_l%d" % l, "hbm", 2.0 * n_l * dims[l] * s)
             add("push", "grad_push_l%d" % l, "hbm", n_h * (2 * dims[l] * s + 4))
             add("gather_add", "grad_pull_l%d" % l, "hbm", n_l * (3 * dims[l] * s + 4))
             add("gather", "gather_l%d" % l, "hbm", n_bar * (2 * dims[l] * s + 4))
+            # coded ring: a decode writes the dense rows (the codes it reads are the smaller
+            # part and vary); a push reads the dense rows twice (sizes, then codes)
+            add("coded_pull", "pull_l%d" % l, "hbm",
+                n_h * dims[l] * s if args.bypass else n_bar * dims[l] * s / 2.0)   # two launches per slot
             if not args.bypass:
                 flops = (2.0 * n_bar * 4 * d_s * (tau * dims[l] + (tau - 1) * d_s)
                          + 2.0 * nnz_halo * d_s + 2.0 * n_h * d_s * dims[l])
@@ -269,14 +301,15 @@ def main():
                              ms_per_step=round(c["ms"] / args.steps, 4),
                              launches_per_step=c["launches"] // args.steps,
                              traffic=None if bf16 != (cfg.get("dtype") == "bf16") or (
-                                 gat and not cls.startswith("gat_") and cls not in ("predict", "push", "loss"))
+                                 gat and not cls.startswith("gat_") and cls not in ("predict", "push", "loss")) or (
+                                 args.coded_ring is not None and cls == "predict")
                              else MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
     # The dominant KERNEL: classes whose calls are one kernel each (aggregation, pull,
     # push, forward transform, loss) are kernels; "predict" and "dense_bwd" are calls
     # made of several kernels, none of which outweighs the aggregation kernel (see the
     # rocprofv3 kernel statistics under profiles/), so they are listed in
     # roofline_all at call level and not eligible here.
-    single = [k for k in roof_all if k not in ("predict", "dense_bwd", "gat_bwd")]
+    single = [k for k in roof_all if k not in ("predict", "dense_bwd", "gat_bwd", "coded_pull", "coded_push")]
     dominant = max(single, key=lambda k: roof_all[k]["ms_per_step"])
     roofline = dict(kernel=KERNEL_OF_CLASS.get(dominant, dominant), **roof_all[dominant])
 
@@ -395,6 +428,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline and wl.X_host is None:
         log("cpu oracle: skipped (this workload's inputs are drawn on the device)")
+    elif not args.no_cpu_baseline and wl.coded is not None:
+        log("cpu oracle: skipped (timed on the dense ring; run without --coded-ring)")
     elif not args.no_cpu_baseline:
         cpu = cpu_baseline(view, dims, tau, d_s, wl.X_host, wl.hist_host, wl.table_ids, wl.Ws,
                            wl.omegas, wl.y, edges, bypass=args.bypass, log=log,
@@ -414,6 +449,7 @@ def main():
                        "every step" if args.delta_t <= 1 else "every %d steps" % args.delta_t),
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
                    "stale_gradient_term": bool(args.stale_grad),
+                   "history_ring": "dense" if args.coded_ring is None else "coded, %d decimals" % args.coded_ring,
                    "caches": "flushed before every call" if args.cold else "as the step leaves them",
                    "entries_per_step": edges},
         "ms_per_layer_step": round(ms_per_step / L, 4),
@@ -427,6 +463,7 @@ def main():
         "graph": graph_info,
         "predictor_train": ptrain,
         "codec": codec,
+        "coded_ring": coded_ring,
         "loss": round(loss, 6),
     }
     print(json.dumps(out))

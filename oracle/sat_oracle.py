@@ -662,6 +662,16 @@ def polyline_decode_rows(codes, row_off, ids, d, precision):
     return out
 
 
+def polyline_stored_value(H, precision):
+    """What a reader of a coded table gets back for every element of H: the value
+    quantised as in polyline_quantise and divided by 10^precision as in
+    polyline_decode_rows, without building the byte strings (the coding of the
+    integers is lossless). For whole tables, where the byte-by-byte functions are
+    too slow; pinned against them on small matrices."""
+    q = polyline_quantise(H, precision)
+    return (q.astype(np.float32) / np.float32(10.0 ** precision)).astype(np.float32)
+
+
 def staleness(H_ref, H_approx):
     """Frobenius norm of the difference (Eq. 6 with the Frobenius norm)."""
     return float(np.linalg.norm(np.asarray(H_ref, np.float64) - np.asarray(H_approx, np.float64)))

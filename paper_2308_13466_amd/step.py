@@ -19,6 +19,11 @@ Order inside a step t (history ring of tau slots per hidden layer):
      ring for the owners of the halo nodes, and the rows the local nodes find in the
      read table (written one step earlier by the partitions that hold them as halo
      nodes) are added to dH_l.
+
+With a coded ring (CodedRing; the paper's section on compressing the stored historical
+embeddings) the slots hold the variable-length codes instead of dense rows: step 1 decodes
+the window of every hidden layer into dense scratch rows first (pull and decode in one
+pass) and the push of step 2 codes the fresh rows straight from the layer's output.
 """
 import numpy as np
 import torch
@@ -28,6 +33,47 @@ from . import binding as B
 
 def _ld(d, mult=32):
     return (d + mult - 1) // mult * mult
+
+
+class CodedSlot:
+    """One epoch of one hidden layer, stored coded, in the two parts the owner-sharded ring
+    has: `own` - the rows of the partition's local nodes in local order, rewritten whole by
+    every push (rows of variable length cannot be replaced in place) - and `remote` - the
+    rows of its halo nodes in halo order, as their owners pushed them. Each part is
+    (codes uint8 [capacity], row_off int64 [rows + 1]) on the device."""
+
+    def __init__(self, own_codes, own_off, remote_codes, remote_off):
+        self.own_codes, self.own_off = own_codes, own_off
+        self.remote_codes, self.remote_off = remote_codes, remote_off
+
+    def coded_bytes(self):
+        """Bytes of code the two parts hold now (reads two offsets back: synchronises)."""
+        return int(self.own_off[-1].item()), int(self.remote_off[-1].item())
+
+
+class CodedRing:
+    """slots[l][s] for l = 1..L-1, s = 0..tau-1: CodedSlot; precision: decimals kept."""
+
+    def __init__(self, precision, slots):
+        self.precision, self.slots = int(precision), slots
+
+
+def encode_rows(H, ld_h, n, d, precision, dtype, capacity=None, stream=None):
+    """Code the dense rows H [n, ld_h] into a new (codes, row_off) pair. capacity None: the
+    exact size (read back after the sizing pass, which synchronises); else the bytes to
+    allocate (rows that would end beyond it are not written; row_off still tells)."""
+    dev = H.device
+    row_off = torch.zeros(n + 1, dtype=torch.int64, device=dev)
+    wsb = B.history_compress_workspace_bytes(n)
+    ws = torch.empty((wsb + 7) // 8, dtype=torch.int64, device=dev)
+    B.history_compress_plan(H, ld_h, n, d, precision, row_off, dtype=dtype, workspace=ws,
+                            workspace_bytes=wsb, stream=stream)
+    if capacity is None:
+        capacity = int(row_off[-1].item())
+    codes = torch.zeros(max(int(capacity), 16), dtype=torch.uint8, device=dev)
+    B.history_compress_encode(H, ld_h, n, d, precision, row_off, codes, int(capacity), dtype=dtype,
+                              stream=stream)
+    return codes, row_off
 
 
 class PartitionStep:
@@ -50,10 +96,16 @@ class PartitionStep:
           device tables [n_rows_g, ld_l] (row of a node as in the history tables): step
           t reads pair[t % 2] (stale term for the local rows) and writes pair[(t+1) % 2]
           (this partition's term for its halo nodes).
+    coded: None, or a CodedRing that replaces hist (hist is then ignored): the window is
+          decoded into dense scratch rows before the predictions and every push codes the
+          layer's fresh rows into the `own` part of the write slot. A push whose codes do
+          not fit the part's capacity leaves the rows beyond it unwritten: coded_overflow()
+          tells (the caller sizes the parts; see encode_rows).
     """
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
-                 fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1):
+                 fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1,
+                 coded=None):
         dev = X_table.device
         self.dtype = dtype
         self.dims = list(dims)
@@ -71,7 +123,9 @@ class PartitionStep:
         self.halo_table_ids = table_ids[self.n_local:]
         self.local_table_ids = table_ids[:self.n_local]
         self.Ws, self.predictors, self.y = Ws, predictors, y
-        self.fused_pull = fused_pull
+        self.coded = coded
+        self.fused_pull = fused_pull and coded is None
+        fused_pull = self.fused_pull
         self.grad_tables = grad_tables
         self.predict_every = max(1, int(predict_every))
         self.t = 0
@@ -100,10 +154,15 @@ class PartitionStep:
             if predictors[l] is not None:
                 ws_bytes.append(B.predict_workspace_bytes(n_l, self.n_halo, dims[l],
                                                           predictors[l].d_s, tau))
+        if coded is not None:
+            ws_bytes.append(B.history_compress_workspace_bytes(n_l))
         self.ws_bytes = max(ws_bytes + [256])
         self.ws = torch.empty((self.ws_bytes + 3) // 4, **f32)
-        if not fused_pull:
-            self.window = [[torch.zeros((n_bar, self.ld[l]), **act) for _ in range(tau)]
+        if not fused_pull and L >= 2:
+            # dense rows of one layer's window, shared by the hidden layers (a layer's pull
+            # and prediction are over before the next layer's pull starts)
+            flat = [torch.zeros(n_bar * max(self.ld[1:L]), **act) for _ in range(tau)]
+            self.window = [[f[:n_bar * self.ld[l]].view(n_bar, self.ld[l]) for f in flat]
                            if l >= 1 else None for l in range(L)]
         # local rows of layer 0 are static: pulled once
         B.history_gather(X_table, X_table.shape[0], X_table.shape[1], self.local_table_ids,
@@ -130,9 +189,15 @@ class PartitionStep:
         order = self.slot_order()
         # 1. predicted halo embeddings of every hidden layer (every Delta T steps)
         for l in range(1, L if self.t % self.predict_every == 0 else 1):
+            w = self.predictors[l]
+            if self.coded is not None:
+                self._pull_coded(l, order, st)
+                self._timed("predict_l%d" % l, lambda: B.predict(
+                    self.pv, w, self.window[l], n_bar, ld[l], None, self.Hbar[l], ld[l], dtype=dt,
+                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+                continue
             slots = [self.hist[l][s] for s in order]
             n_rows, ld_t = slots[0].shape
-            w = self.predictors[l]
             if self.fused_pull or w.bypass:
                 self._timed("predict_l%d" % l, lambda: B.predict(
                     self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], ld[l], dtype=dt,
@@ -160,7 +225,9 @@ class PartitionStep:
             self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
                 self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
                 B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], dtype=dt, stream=st))
-            if not last:
+            if not last and self.coded is not None:
+                self._push_coded(l + 1, w_slot, st)
+            elif not last:
                 tab = self.hist[l + 1][w_slot]
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
@@ -194,6 +261,54 @@ class PartitionStep:
                     rd, rd.shape[0], rd.shape[1], self.local_table_ids, n_l, dims[l],
                     self.dH[l], ld[l], dtype=dt, stream=st))
         self.t += 1
+
+    # ------------------------------------------------------------ coded ring
+    def _pull_coded(self, l, order, st):
+        """Decode the tau slots of layer l, oldest first, into the dense window rows (local
+        rows from the `own` part, halo rows from the `remote` part; a bypass predictor reads
+        the newest slot's halo rows only)."""
+        n_l, n_h, d, P = self.n_local, self.n_halo, self.dims[l], self.coded.precision
+        bypass = self.predictors[l].bypass
+        for k, s in enumerate(order):
+            if bypass and k != self.tau - 1:
+                continue
+            slot, win = self.coded.slots[l][s], self.window[l][k]
+            if n_l > 0 and not bypass:
+                self._timed("pull_l%d" % l, lambda: B.history_decompress(
+                    slot.own_codes, slot.own_off, n_l, None, n_l, d, P, win, self.ld[l],
+                    dtype=self.dtype, stream=st))
+            if n_h > 0:
+                halo = win[n_l:]
+                self._timed("pull_l%d" % l, lambda: B.history_decompress(
+                    slot.remote_codes, slot.remote_off, n_h, None, n_h, d, P, halo, self.ld[l],
+                    dtype=self.dtype, stream=st))
+
+    def _push_coded(self, l, w_slot, st):
+        """Code the fresh local rows of layer l into the `own` part of the write slot: a sizing
+        pass (row offsets), then the codes."""
+        n_l, d, P = self.n_local, self.dims[l], self.coded.precision
+        slot = self.coded.slots[l][w_slot]
+        if n_l == 0:
+            return
+
+        def push():
+            B.history_compress_plan(self.Hbar[l], self.ld[l], n_l, d, P, slot.own_off, dtype=self.dtype,
+                                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st)
+            B.history_compress_encode(self.Hbar[l], self.ld[l], n_l, d, P, slot.own_off, slot.own_codes,
+                                      slot.own_codes.numel(), dtype=self.dtype, stream=st)
+        self._timed("push_l%d" % l, push)
+
+    def coded_overflow(self):
+        """[(layer, slot, bytes needed, capacity)] of the `own` parts whose last push did not fit
+        (empty when all did). Reads the offsets back: synchronises."""
+        bad = []
+        if self.coded is not None:
+            for l in range(1, self.L):
+                for s, slot in enumerate(self.coded.slots[l]):
+                    need = int(slot.own_off[-1].item())
+                    if need > slot.own_codes.numel():
+                        bad.append((l, s, need, slot.own_codes.numel()))
+        return bad
 
     # ------------------------------------------------------------ HIP graph
     def graph_period(self):

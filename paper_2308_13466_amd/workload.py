@@ -12,7 +12,7 @@ import torch
 
 import sat_synth as syn
 from . import binding as B
-from .step import PartitionStep
+from .step import CodedRing, CodedSlot, PartitionStep, encode_rows
 
 
 def ld_of(d, mult=32):
@@ -36,13 +36,17 @@ def _upload(a, bf16, dev):
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
                    keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
-                   backbone="gcn"):
+                   backbone="gcn", coded_ring=None, own_bytes_per_value=2.0):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
     of the history tables) and run the stale-gradient term of the backward.
     backbone: "gcn" (normalised-adjacency aggregation) or "gat" (graph attention; heads per
     layer from sat_synth.gat_heads, attention vectors from sat_synth.attention_vectors_f32).
+    coded_ring: None, or the number of decimals: the history ring is kept coded (GCN backbone
+    only). Every dense slot generated below is coded once - the local nodes' rows into the
+    `own` part (allocated with own_bytes_per_value bytes per element, since later pushes have
+    other sizes), the halo nodes' rows into the `remote` part (exact size) - and then freed.
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
     host copies kept for the tests hold the rounded values the device holds.
 
@@ -129,6 +133,30 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     gt = None
     if grad_tables:
         gt = [None] + [[torch.zeros_like(hist_d[l][0]) for _ in range(2)] for l in range(1, L)]
+    coded = None
+    if coded_ring is not None:
+        assert backbone == "gcn", "the coded ring is wired into the GCN step only"
+        dt = B.BF16 if bf16 else B.F32
+        st = torch.cuda.current_stream().cuda_stream
+        cslots = [None]
+        for l in range(1, L):
+            own_cap = int(n_l * dims[l] * own_bytes_per_value)
+            dense = torch.zeros((n_bar, ld[l]), dtype=hist_d[l][0].dtype, device=dev)
+            layer = []
+            for s in range(tau):
+                tab = hist_d[l][s]
+                B.history_gather(tab, tab.shape[0], tab.shape[1], ids_d, n_bar, dims[l], dense, ld[l],
+                                 dtype=dt, stream=st)
+                oc, oo = encode_rows(dense, ld[l], n_l, dims[l], coded_ring, dt, capacity=own_cap, stream=st)
+                rc, ro = encode_rows(dense[n_l:], ld[l], n_h, dims[l], coded_ring, dt, stream=st)
+                layer.append(CodedSlot(oc, oo, rc, ro))
+                hist_d[l][s] = None
+                del tab
+            cslots.append(layer)
+            del dense
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        coded = CodedRing(coded_ring, cslots)
     attn = None
     if backbone == "gat":
         from .step_gat import GatPartitionStep
@@ -143,7 +171,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     else:
         step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
                              fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
-                             grad_tables=gt, predict_every=predict_every)
+                             grad_tables=gt, predict_every=predict_every, coded=coded)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))
@@ -153,5 +181,5 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     w.dims, w.tau, w.d_s, w.L, w.ld, w.dtype = dims, tau, d_s, L, ld, dtype
     w.X_host, w.hist_host, w.table_ids, w.Ws, w.omegas, w.y = X_host, hist_host, table_ids, Ws, omegas, y
     w.device_keep = (keep, X_d, hist_d, ids_d, Ws_d, y_d)
-    w.backbone, w.attn = backbone, attn
+    w.backbone, w.attn, w.coded = backbone, attn, coded
     return w

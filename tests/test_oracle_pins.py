@@ -682,6 +682,8 @@ def test_polyline_round_trip_error_bound_and_lengths():
         # gather by id decodes the right rows
         ids = np.array([49, 0, 7, 7])
         assert np.array_equal(orc.polyline_decode_rows(codes, off, ids, 37, prec), back[ids])
+        # the whole-table shortcut returns bit for bit what goes through the bytes
+        assert np.array_equal(orc.polyline_stored_value(H, prec).view(np.uint32), back.view(np.uint32))
     # fewer decimals, fewer bytes; relu-shaped rows at one decimal beat 3x against fp32
     sizes = [orc.polyline_encode_rows(H, p)[1][-1] for p in (1, 2, 4)]
     assert sizes[0] < sizes[1] < sizes[2]
