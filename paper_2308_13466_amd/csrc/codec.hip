@@ -266,29 +266,12 @@ __global__ __launch_bounds__(256) void encode_lds_kernel(const void* __restrict_
   }
 }
 
-// out[k, 0:d) = decoded row (ids ? ids[k] : k); one wavefront per k, LDS slice of row_cap bytes each
+// The values of one row whose nb bytes a wavefront has staged in LDS (`mine`): a lane per
+// byte, 64 at a time; a ballot of the "last group" bits numbers the values, the lane that
+// holds a value's first byte assembles it and writes element idx of the output row.
 template <int ES>
-__global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ codes,
-                                                     const int64_t* __restrict__ row_off,
-                                                     int64_t n_rows, const int32_t* __restrict__ ids,
-                                                     int64_t n, int d, float scale, int row_cap,
-                                                     void* __restrict__ out, int64_t ld_bytes) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-  const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x >> 6;
-  const int64_t k = static_cast<int64_t>(blockIdx.x) * 4 + wave;
-  if (k >= n) return;
-  const int64_t r = ids ? static_cast<int64_t>(ids[k]) : k;
-  if (r < 0 || r >= n_rows) return;                 // bad id: the row is left alone
-  const int64_t b0 = row_off[r];
-  int64_t nb64 = row_off[r + 1] - b0;
-  if (nb64 < 0) return;
-  const int nb = nb64 > row_cap ? row_cap : static_cast<int>(nb64);   // a row never exceeds 7 d bytes
-  unsigned char* mine = lds + wave * row_cap;
-  for (int i = lane; i < nb; i += kWave) mine[i] = codes[b0 + i];
-  // (a wavefront reads back only what it wrote itself: no barrier needed, the LDS
-  // accesses of one wavefront are ordered)
-  unsigned char* orow = static_cast<unsigned char*>(out) + k * ld_bytes;
+__device__ __forceinline__ void decode_staged_row(const unsigned char* mine, int nb, int d, float scale,
+                                                  unsigned char* orow, int lane) {
   int done = 0;                 // values completed before this chunk
   bool prev_last = true;        // the byte before this chunk ended a value (or the row starts)
   for (int base = 0; base < nb; base += kWave) {
@@ -320,6 +303,78 @@ __global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__
     }
     done += __builtin_popcountll(m);
     prev_last = ((m >> (kWave - 1)) & 1ull) != 0;
+  }
+}
+
+// out[k, 0:d) = decoded row (ids ? ids[k] : k). A wavefront takes kDecRows consecutive k; its
+// LDS slice holds one row (row_cap bytes) at a time. A row is a chain of dependent accesses
+// (id, offsets, bytes, values): lanes 0..kDecRows-1 fetch ids and offsets of all the
+// wavefront's rows at once, and when every row has at most kDecFast bytes (the usual case)
+// the bytes of all of them are requested before the first is decoded.
+constexpr int kDecRows = 4, kDecFast = 512;
+template <int ES>
+__global__ __launch_bounds__(256) void decode_kernel(const uint8_t* __restrict__ codes,
+                                                     const int64_t* __restrict__ row_off,
+                                                     int64_t n_rows, const int32_t* __restrict__ ids,
+                                                     int64_t n, int d, float scale, int row_cap,
+                                                     void* __restrict__ out, int64_t ld_bytes) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x >> 6;
+  const int64_t k0 = (static_cast<int64_t>(blockIdx.x) * 4 + wave) * kDecRows;
+  if (k0 >= n) return;
+  int64_t b0_l = 0;
+  int nb_l = -1;                                    // -1: nothing to do for this row
+  if (lane < kDecRows && k0 + lane < n) {
+    const int64_t r = ids ? static_cast<int64_t>(ids[k0 + lane]) : k0 + lane;
+    if (r >= 0 && r < n_rows) {                     // bad id: the row is left alone
+      b0_l = row_off[r];
+      const int64_t nb64 = row_off[r + 1] - b0_l;
+      if (nb64 >= 0) nb_l = nb64 > row_cap ? row_cap : static_cast<int>(nb64);   // never over 7 d bytes
+    }
+  }
+  int64_t b0[kDecRows];
+  int nb[kDecRows];
+  bool fast = true;
+#pragma unroll
+  for (int j = 0; j < kDecRows; ++j) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<uint32_t>(b0_l), j);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<uint32_t>(static_cast<uint64_t>(b0_l) >> 32), j);
+    b0[j] = static_cast<int64_t>((static_cast<uint64_t>(hi) << 32) | lo);
+    nb[j] = __builtin_amdgcn_readlane(nb_l, j);
+    fast = fast && nb[j] <= kDecFast;
+  }
+  // (a wavefront reads back only what it wrote itself: no barrier needed, the LDS
+  // accesses of one wavefront are ordered)
+  unsigned char* mine = lds + wave * row_cap;
+  unsigned char* orow = static_cast<unsigned char*>(out) + k0 * ld_bytes;
+  if (fast) {
+    constexpr int NC = kDecFast / kWave;
+    uint8_t reg[kDecRows][NC];
+#pragma unroll
+    for (int j = 0; j < kDecRows; ++j)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int i = c * kWave + lane;
+        reg[j][c] = i < nb[j] ? codes[b0[j] + i] : static_cast<uint8_t>(0);
+      }
+#pragma unroll
+    for (int j = 0; j < kDecRows; ++j) {
+      if (nb[j] < 0) continue;
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        const int i = c * kWave + lane;
+        if (i < nb[j]) mine[i] = reg[j][c];
+      }
+      decode_staged_row<ES>(mine, nb[j], d, scale, orow + j * ld_bytes, lane);
+    }
+  } else {
+#pragma unroll 1
+    for (int j = 0; j < kDecRows; ++j) {
+      if (nb[j] < 0) continue;
+      for (int i = lane; i < nb[j]; i += kWave) mine[i] = codes[b0[j] + i];
+      decode_staged_row<ES>(mine, nb[j], d, scale, orow + j * ld_bytes, lane);
+    }
   }
 }
 
@@ -417,7 +472,7 @@ extern "C" sat_status sat_history_decompress(const uint8_t* codes, const int64_t
   const int row_cap = static_cast<int>(round_up(static_cast<int64_t>(kMaxGroups) * d, 16));
   const int smem = 4 * row_cap;
   if (smem > 64 * 1024) return SAT_EUNSUPPORTED;   // rows wider than 2340 values
-  const int64_t blocks = (n + 3) / 4;
+  const int64_t blocks = (n + 4 * kDecRows - 1) / (4 * kDecRows);
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int es = dtype == SAT_BF16 ? 2 : 4;

@@ -38,7 +38,8 @@ def _compress(sat, gu, torch, H_dev, ld, n, d, prec, dtype):
 
 
 @pytest.mark.parametrize("n,d,ld,prec", [(3000, 256, 256, 2), (5000, 100, 104, 1), (777, 37, 40, 4),
-                                         (2049, 1, 4, 3), (4100, 602, 608, 2), (1, 64, 64, 0)])
+                                         (2049, 1, 4, 3), (4100, 602, 608, 2), (1, 64, 64, 0),
+                                         (1501, 370, 376, 2)])   # rows around 512 bytes: both decoder paths
 def test_codec_fp32_bit_exact(env, n, d, ld, prec):
     sat, gu, torch = env
     print("[case] codec fp32 n=%d d=%d precision=%d" % (n, d, prec), flush=True)
