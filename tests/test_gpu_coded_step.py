@@ -241,3 +241,98 @@ def test_coded_ring_step_at_full_size():
     step.forward_backward()
     gu.sync()
     assert step.coded_overflow() == [] and np.isfinite(float(step.loss.item()))
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium"])
+def test_coded_ring_step_bf16_storage(name):
+    """bf16 tables behind the codec: a coded value is the quantised bfloat16 element, a decoded
+    one is rounded to bfloat16 again. One step from bit-identical windows; the pushed part
+    must hold exactly the stored form of the forward's own rows."""
+    import torch
+    import paper_2308_13466_amd as sat
+    from paper_2308_13466_amd import binding as B
+    from paper_2308_13466_amd.step import CodedRing, CodedSlot, PartitionStep, encode_rows
+    from tests import gpu_util as gu
+    prec, rtol = 2, 2e-2
+    print("[case] coded-ring step %s, bf16 storage, %d decimals" % (name, prec), flush=True)
+
+    def r(a):
+        return syn.f32_from_bf16_bits(syn.bf16_bits_from_f32(a))
+
+    def up(a, ld):
+        return gu.to_dev_bits(syn.bf16_bits_from_f32(a), ld).view(torch.bfloat16)
+
+    def down(t, d):
+        return syn.f32_from_bf16_bits(gu.bits_to_host(t.view(torch.int16), d))
+
+    def stored(a):      # oracle: what a reader of a coded bf16 table gets back
+        return orc.round_bf16(orc.polyline_stored_value(a, prec)).astype(np.float32)
+
+    cfg, ss, g, X, Ws, omegas = build_problem(name)
+    if name == "tiny":
+        cfg["d_s"] = 32
+        pss = ss["predictor"].spawn(len(Ws))
+        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32) for l in range(1, len(Ws))]
+    dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
+    _, hist = fresh_history(cfg, ss, g, X, Ws)
+    X = r(X)
+    Ws = [r(w) for w in Ws]
+    hist = [None] + [[r(t) for t in hist[l]] for l in range(1, L)]
+    view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"])
+    oview = orc.partition_view(g.N, g.rowptr, g.col, g.part, cfg["part"])
+    n_l, n_h = view["n_local"], view["n_halo"]
+    y = syn.labels_i32(ss["labels"], n_l, dims[-1])
+    ld = [gu.ld_for(d) for d in dims]
+    X_d = up(X, ld[0])
+    ids_d = gu.to_dev(np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32))
+    Ws_d = [up(Ws[l], gu.ld_for(dims[l + 1], 8)) for l in range(L)]
+    preds, keep = [None], []
+    for l in range(1, L):
+        pd = {k: gu.to_dev(omegas[l][k]) for k in omegas[l]}
+        keep.append(pd)
+        preds.append(sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], cfg["d_s"], tau))
+    slots = [None]
+    for l in range(1, L):
+        layer = []
+        for s in range(tau):
+            own, rem = up(hist[l][s][view["local_ids"]], ld[l]), up(hist[l][s][view["halo_ids"]], ld[l])
+            oc, oo = encode_rows(own, ld[l], n_l, dims[l], prec, B.BF16, capacity=n_l * dims[l] * 4,
+                                 stream=gu.stream_ptr())
+            rc, ro = encode_rows(rem, ld[l], n_h, dims[l], prec, B.BF16, stream=gu.stream_ptr())
+            layer.append(CodedSlot(oc, oo, rc, ro))
+        slots.append(layer)
+    gu.sync()
+    ring = CodedRing(prec, slots)
+    step = PartitionStep(view, dims, X_d, [None] * L, ids_d, Ws_d, preds, gu.to_dev(y), tau,
+                         dtype=B.BF16, coded=ring)
+    ohist = [None] + [[stored(t) for t in hist[l]] for l in range(1, L)]
+    order = step.slot_order()
+    step.forward_backward()
+    gu.sync()
+    assert step.coded_overflow() == []
+    ids = np.concatenate([view["local_ids"], view["halo_ids"]])
+    for k, s in enumerate(order):       # the decoded window (last hidden layer's is left in place)
+        assert np.array_equal(down(step.window[L - 1][k], dims[L - 1]), ohist[L - 1][s][ids])
+    st = oracle_step(oview, X, ohist, order, 0, Ws, omegas, y, store=orc.round_bf16)
+    for l in range(1, L):
+        gu.assert_close(down(step.Hbar[l], dims[l])[n_l:], st["halo_hat"][l], rtol,
+                        "predicted halo rows, layer %d" % l)
+    for l in range(L):
+        gu.assert_close(down(step.AGG[l], dims[l]), st["AGG"][l], rtol, "AGG %d" % l)
+        out = step.logits if l == L - 1 else step.Hbar[l + 1]
+        gu.assert_close(down(out, dims[l + 1])[:n_l], st["H"][l + 1], rtol, "H %d" % (l + 1))
+    assert abs(float(step.loss.item()) - st["loss"]) <= 5e-3 * abs(st["loss"])
+    unit = 10.0 ** -prec
+    for l in range(1, L):
+        slot = ring.slots[l][0]
+        out = torch.zeros((n_l, ld[l]), dtype=torch.bfloat16, device=gu.DEV)
+        sat.history_decompress(slot.own_codes, slot.own_off, n_l, None, n_l, dims[l], prec, out, ld[l],
+                               dtype=B.BF16, stream=gu.stream_ptr())
+        gu.sync()
+        got = down(out, dims[l])
+        fresh = down(step.Hbar[l], dims[l])[:n_l]
+        assert np.array_equal(got, stored(fresh)), "pushed part, layer %d" % l
+        ref = st["H"][l]
+        rms = np.sqrt(np.mean(ref * ref))
+        assert np.all(np.abs(got - ref) <= 0.5 * unit + rtol * (np.abs(ref) + rms))
+    print("[case] ok: loss %.6f" % st["loss"], flush=True)
