@@ -252,18 +252,20 @@ def test_predictor_update_frequency():
     gu.assert_close(halo[2], orc.predict(oview, omegas[1], ring), RTOL, "refreshed prediction")
 
 
-def test_step_replayed_from_a_hip_graph_matches_eager_steps():
+@pytest.mark.parametrize("coded_ring", [None, 3])
+def test_step_replayed_from_a_hip_graph_matches_eager_steps(coded_ring):
     """tau consecutive steps captured into one HIP graph and replayed several times, with the
     program's own eager work and synchronisations between the replays: after every replay the
-    loss, the weight gradients and the history ring equal, bit for bit, what the same number
-    of eager steps leaves on an identical second instance."""
+    loss, the weight gradients and the history ring (dense tables, or the codes and offsets
+    of a coded ring) equal, bit for bit, what the same number of eager steps leaves on an
+    identical second instance."""
     import torch
     import paper_2308_13466_amd as sat
     from paper_2308_13466_amd.workload import build_workload
-    print("[case] HIP graph replay vs eager steps, tiny", flush=True)
+    print("[case] HIP graph replay vs eager steps, tiny, coded ring: %s" % coded_ring, flush=True)
     sat.lib()
-    eager = build_workload("tiny").step
-    graphed = build_workload("tiny").step
+    eager = build_workload("tiny", coded_ring=coded_ring, own_bytes_per_value=4.0).step
+    graphed = build_workload("tiny", coded_ring=coded_ring, own_bytes_per_value=4.0).step
     period = graphed.graph_period()
     assert period == graphed.tau
     for _ in range(period):           # one eager period on both before the capture
@@ -284,6 +286,13 @@ def test_step_replayed_from_a_hip_graph_matches_eager_steps():
             assert torch.equal(graphed.dW[l], eager.dW[l]), (rep, l)
         for l in range(1, eager.L):
             for s in range(eager.tau):
-                assert torch.equal(graphed.hist[l][s], eager.hist[l][s]), (rep, l, s)
+                if coded_ring is None:
+                    assert torch.equal(graphed.hist[l][s], eager.hist[l][s]), (rep, l, s)
+                    continue
+                a, b = graphed.coded.slots[l][s], eager.coded.slots[l][s]
+                assert torch.equal(a.own_off, b.own_off), (rep, l, s)
+                used = int(a.own_off[-1].item())
+                assert torch.equal(a.own_codes[:used], b.own_codes[:used]), (rep, l, s)
             assert torch.equal(graphed.Hbar[l], eager.Hbar[l]), (rep, l)
+    assert graphed.coded_overflow() == []
     assert float(scratch[0].item()) == 4.0
