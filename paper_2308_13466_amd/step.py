@@ -58,10 +58,11 @@ class CodedRing:
         self.precision, self.slots = int(precision), slots
 
 
-def encode_rows(H, ld_h, n, d, precision, dtype, capacity=None, stream=None):
+def encode_rows(H, ld_h, n, d, precision, dtype, capacity=None, headroom=1.0, stream=None):
     """Code the dense rows H [n, ld_h] into a new (codes, row_off) pair. capacity None: the
-    exact size (read back after the sizing pass, which synchronises); else the bytes to
-    allocate (rows that would end beyond it are not written; row_off still tells)."""
+    size these rows need (read back after the sizing pass, which synchronises) times
+    `headroom` (room for later pushes into the same part); else the bytes to allocate (rows
+    that would end beyond it are not written; row_off still tells)."""
     dev = H.device
     row_off = torch.zeros(n + 1, dtype=torch.int64, device=dev)
     wsb = B.history_compress_workspace_bytes(n)
@@ -69,7 +70,7 @@ def encode_rows(H, ld_h, n, d, precision, dtype, capacity=None, stream=None):
     B.history_compress_plan(H, ld_h, n, d, precision, row_off, dtype=dtype, workspace=ws,
                             workspace_bytes=wsb, stream=stream)
     if capacity is None:
-        capacity = int(row_off[-1].item())
+        capacity = int(int(row_off[-1].item()) * headroom) + 1
     codes = torch.zeros(max(int(capacity), 16), dtype=torch.uint8, device=dev)
     B.history_compress_encode(H, ld_h, n, d, precision, row_off, codes, int(capacity), dtype=dtype,
                               stream=stream)

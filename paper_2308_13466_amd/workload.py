@@ -36,7 +36,7 @@ def _upload(a, bf16, dev):
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
                    keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
-                   backbone="gcn", coded_ring=None, own_bytes_per_value=2.0):
+                   backbone="gcn", coded_ring=None, own_headroom=1.5):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
@@ -45,7 +45,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     layer from sat_synth.gat_heads, attention vectors from sat_synth.attention_vectors_f32).
     coded_ring: None, or the number of decimals: the history ring is kept coded (GCN backbone
     only). Every dense slot generated below is coded once - the local nodes' rows into the
-    `own` part (allocated with own_bytes_per_value bytes per element, since later pushes have
+    `own` part (allocated own_headroom times the size they need now, since later pushes have
     other sizes), the halo nodes' rows into the `remote` part (exact size) - and then freed.
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
     host copies kept for the tests hold the rounded values the device holds.
@@ -140,14 +140,14 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
         st = torch.cuda.current_stream().cuda_stream
         cslots = [None]
         for l in range(1, L):
-            own_cap = int(n_l * dims[l] * own_bytes_per_value)
             dense = torch.zeros((n_bar, ld[l]), dtype=hist_d[l][0].dtype, device=dev)
             layer = []
             for s in range(tau):
                 tab = hist_d[l][s]
                 B.history_gather(tab, tab.shape[0], tab.shape[1], ids_d, n_bar, dims[l], dense, ld[l],
                                  dtype=dt, stream=st)
-                oc, oo = encode_rows(dense, ld[l], n_l, dims[l], coded_ring, dt, capacity=own_cap, stream=st)
+                oc, oo = encode_rows(dense, ld[l], n_l, dims[l], coded_ring, dt, headroom=own_headroom,
+                                     stream=st)
                 rc, ro = encode_rows(dense[n_l:], ld[l], n_h, dims[l], coded_ring, dt, stream=st)
                 layer.append(CodedSlot(oc, oo, rc, ro))
                 hist_d[l][s] = None

@@ -264,8 +264,8 @@ def test_step_replayed_from_a_hip_graph_matches_eager_steps(coded_ring):
     from paper_2308_13466_amd.workload import build_workload
     print("[case] HIP graph replay vs eager steps, tiny, coded ring: %s" % coded_ring, flush=True)
     sat.lib()
-    eager = build_workload("tiny", coded_ring=coded_ring, own_bytes_per_value=4.0).step
-    graphed = build_workload("tiny", coded_ring=coded_ring, own_bytes_per_value=4.0).step
+    eager = build_workload("tiny", coded_ring=coded_ring, own_headroom=2.0).step
+    graphed = build_workload("tiny", coded_ring=coded_ring, own_headroom=2.0).step
     period = graphed.graph_period()
     assert period == graphed.tau
     for _ in range(period):           # one eager period on both before the capture
