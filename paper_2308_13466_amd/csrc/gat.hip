@@ -227,16 +227,18 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_wave_barrier();
 }
 
-// Walk entries [s, e) of a.col. `entry(c, ok, w)`: called with one entry per lane (ok false
-// for lanes past the end and for ids out of range; c is then 0); it writes the entry's NW
-// per-head weights to w[0 .. NW). `feature(x, w, valid)`: called for each lane's share x of
+// Walk entries [s, e) of a.col. `pre(c, ok)`: called first with one entry per lane (ok false
+// for lanes past the end and for ids out of range; c is then 0); it only REQUESTS the
+// per-node scores the entry needs. `entry(c, ok, w)`: called for the same lane and entry once
+// the first round of gathers has been issued; it writes the entry's NW per-head weights to
+// w[0 .. NW). `feature(x, w, valid)`: called for each lane's share x of
 // a gathered row, w the weights of that entry in LDS. `fold()`: called after the last entry of
 // each batch of 64: the callers sum a batch on its own and add it to the row's running sum
 // there, which keeps the chains of additions short on rows of thousands of entries.
-template <int ES, int NW, int U, class Entry, class Feature, class Fold>
+template <int ES, int NW, int U, class Pre, class Entry, class Feature, class Fold>
 __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_t s, int64_t e,
-                                     int32_t* s_col, float* s_w, Entry&& entry, Feature&& feature,
-                                     Fold&& fold) {
+                                     int32_t* s_col, float* s_w, Pre&& pre, Entry&& entry,
+                                     Feature&& feature, Fold&& fold) {
   // rows whose width is not a whole number of chunks, or fewer chunks than lanes in a group:
   // the lanes' shares are clipped to the row (lanes past it get zeros)
   const bool clip = a.ln.d != (4 << a.ln.lg_g);
@@ -277,9 +279,14 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
         feature(xw, s_w + idc * NW, valid);
       }
     };
-    // the first round of gathers needs the ids only: it is in flight while the entry phase
-    // reads the per-node scores and computes the weights
+    // The first round of gathers needs the ids only: it is in flight while the entry phase
+    // computes the weights. The scores are requested BEFORE the gathers: a wavefront's loads
+    // complete in the order they were issued, so requested after them the scores would only
+    // be there once every gathered row of the round is.
+    pre(c, ok);
+    __builtin_amdgcn_sched_barrier(0);
     issue(0);
+    __builtin_amdgcn_sched_barrier(0);
     entry(c, ok, s_w + L.lane * NW);
     wave_lds_fence();
     consume(0);
@@ -394,9 +401,12 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     acc = f32x4(0.f);
     load_heads<K>(el + row * K, eli);
   };
-  auto entry = [&](int32_t c, bool ok, float* w) __attribute__((always_inline)) {
-    float erv[K], e[K];
+  float erv[K];
+  auto pre = [&](int32_t c, bool) __attribute__((always_inline)) {
     load_heads<K>(er + static_cast<int64_t>(c) * K, erv);
+  };
+  auto entry = [&](int32_t, bool ok, float* w) __attribute__((always_inline)) {
+    float e[K];
     float scale[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
@@ -450,7 +460,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, K, kU>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, K, kU>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float ll[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ll[k] = wave_sum(l[k]);
@@ -465,7 +475,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
     const f32x4 part = group_sum(acc, a.ln);
     float lk[K];
 #pragma unroll
@@ -537,9 +547,11 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     accD = 0.f;
     acc1 = 0.f;
   };
-  auto entry = [&](int32_t c, bool ok, float* w) __attribute__((always_inline)) {
-    float erv[K];
+  float erv[K];
+  auto pre = [&](int32_t c, bool) __attribute__((always_inline)) {
     load_heads<K>(er + static_cast<int64_t>(c) * K, erv);
+  };
+  auto entry = [&](int32_t, bool ok, float* w) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const float s = eli[k] + erv[k];
@@ -583,7 +595,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, 2 * K, kU>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, kU>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float ws[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ws[k] = wave_sum(w1s[k]);
@@ -597,7 +609,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, 2 * K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
     const float D = head_sum(accD, a.ln), t1 = head_sum(acc1, a.ln);
     float wk[K];
 #pragma unroll
@@ -667,10 +679,20 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
     acc = f32x4(0.f);
     accd = 0.f;
   };
+  // (the instance with two gathers in flight has no registers to hold the row statistics across
+  // the gathers' issue: it requests them in the entry phase)
+  constexpr bool kEarly = U > 2;
+  f32x4 rsv[K];
+  auto pre = [&](int32_t c, bool) __attribute__((always_inline)) {
+    if constexpr (kEarly) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) rsv[k] = rowstat[static_cast<int64_t>(c) * K + k];
+    }
+  };
   auto entry = [&](int32_t c, bool ok, float* w) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const f32x4 rs = rowstat[static_cast<int64_t>(c) * K + k];
+      const f32x4 rs = kEarly ? rsv[k] : rowstat[static_cast<int64_t>(c) * K + k];
       const float rel = rs.x, rm = rs.y, rinv = rs.z, rD = rs.w;
       const float s = rel + erj[k];
       const float e = s > 0.f ? s : a.slope * s;
@@ -715,7 +737,7 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row_off + row);
-    walk<ES, 2 * K, U>(a, L, s, e, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, U>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float wd[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) wd[k] = wave_sum(wds[k]);
@@ -729,7 +751,7 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row_off + row);
-    walk<ES, 2 * K, U>(a, L, ps, pe, s_col[wave], s_w[wave], entry, feature, fold);
+    walk<ES, 2 * K, U>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
     const f32x4 part = group_sum(acc, a.ln);
     const float t1 = head_sum(accd, a.ln);
     float wk[K];
