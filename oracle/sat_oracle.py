@@ -603,6 +603,9 @@ def full_graph_backward(N, g_rowptr, g_col, X, Ws, y, part):
 # Algorithm Format's variable-length character coding, every value on its own.
 # --------------------------------------------------------------------------
 
+POLYLINE_Q_MAX = 1 << 30
+
+
 def polyline_quantise(H, precision, arith=np.float32):
     """q = floor(v * 10^precision + 1/2) per element, as int64. `arith` is the
     floating type the three operations run in: float32 is what the GPU path uses
@@ -610,7 +613,15 @@ def polyline_quantise(H, precision, arith=np.float32):
     precision); float64 serves the published worked examples."""
     v = np.asarray(H).astype(arith)
     scale = arith(10.0) ** arith(precision) if arith is np.float64 else np.float32(10.0 ** precision)
-    return np.floor(v * scale + arith(0.5)).astype(np.int64)
+    with np.errstate(over="ignore", invalid="ignore"):
+        x = np.floor(v * scale + arith(0.5))
+    # Out of range (the section is silent; reading): the character coding is defined on
+    # signed 32-bit integers after the left shift, so |q| is held at POLYLINE_Q_MAX = 2^30,
+    # the largest magnitude whose shifted code fits 32 bits for either sign (+-inf and
+    # overflowing products land there too); a NaN has no decimal rounding and codes as 0.
+    x = np.where(np.isnan(x), arith(0.0), x)
+    x = np.clip(x, -float(POLYLINE_Q_MAX), float(POLYLINE_Q_MAX))
+    return x.astype(np.int64)
 
 
 def polyline_encode_value(q):

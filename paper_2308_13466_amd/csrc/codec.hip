@@ -43,11 +43,13 @@ __device__ __forceinline__ float load_elem(const void* row, int c) {
   }
 }
 
-// zigzag code of floor(v * scale + 1/2), saturated to 31 bits; NaN codes as 0
+// zigzag code of floor(v * scale + 1/2); |q| is held at 2^30 (exact in fp32; the largest
+// magnitude whose shifted code fits 32 bits for either sign: 2^31 and 2^31 - 1); +-inf and
+// products that overflow land there; NaN codes as 0
 __device__ __forceinline__ uint32_t zigzag_of(float v, float scale) {
   float x = floorf(__fadd_rn(__fmul_rn(v, scale), 0.5f));
   if (!(x == x)) x = 0.f;
-  x = fminf(fmaxf(x, -1073741823.0f), 1073741823.0f);
+  x = fminf(fmaxf(x, -1073741824.0f), 1073741824.0f);
   const int32_t q = static_cast<int32_t>(x);
   return (static_cast<uint32_t>(q) << 1) ^ static_cast<uint32_t>(q >> 31);
 }

@@ -73,6 +73,51 @@ def test_codec_fp32_bit_exact(env, n, d, ld, prec):
     print("[case] ratio %.2fx against fp32" % (4.0 * n * d / max(total, 1)), flush=True)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_codec_out_of_range_nan_and_inf(env, dtype):
+    """Values whose quantised magnitude would pass 2^30 saturate there (7-byte codes), +-inf
+    with them, NaN and -0.0 code as 0: offsets, code bytes and decoded values bit for bit
+    against the oracle, rows mixing such values with ordinary ones (every encoder path)."""
+    sat, gu, torch = env
+    print("[case] codec edge values %s" % dtype, flush=True)
+    rng = np.random.default_rng(17)
+    n, d, ld = 530, 72, 72
+    H = (rng.standard_normal((n, d)) * 2.0).astype(np.float32)
+    edge = [1e30, -1e30, np.inf, -np.inf, np.nan, -0.0, 3.4e38, -3.4e38, 1073741824.0, -1073741824.0,
+            1.0737418e7, -1.0737418e7, 1.07374e7, 5e9, -5e9]
+    where = rng.integers(0, n * d, size=600)
+    H.reshape(-1)[where] = np.array([edge[i % len(edge)] for i in range(600)], dtype=np.float32)
+    H[7, :] = np.inf                      # a row of 7-byte codes only: the longest row a width can give
+    H[8, :] = np.nan
+    bf16 = dtype == "bf16"
+    if bf16:
+        bits = syn.bf16_bits_from_f32(H)
+        H = syn.f32_from_bf16_bits(bits)
+        H_dev = gu.to_dev_bits(bits, ld)
+    else:
+        H_dev = gu.to_dev(H, ld)
+    for prec in (0, 2):
+        row_off, codes, total = _compress(sat, gu, torch, H_dev, ld, n, d, prec, 1 if bf16 else 0)
+        ref_codes, ref_off = orc.polyline_encode_rows(H, prec)
+        assert np.array_equal(row_off.cpu().numpy(), ref_off)
+        assert ref_off[8] - ref_off[7] == 7 * d and ref_off[9] - ref_off[8] == d
+        got = codes.cpu().numpy()
+        assert np.array_equal(got[:total], ref_codes) and np.all(got[total:] == 7)
+        back = orc.polyline_decode_rows(ref_codes, ref_off, np.arange(n), d, prec)
+        if bf16:
+            out = torch.zeros((n, ld), dtype=torch.int16, device=gu.DEV)
+            sat.history_decompress(codes, row_off, n, None, n, d, prec, out, ld, dtype=1,
+                                   stream=gu.stream_ptr())
+            gu.sync()
+            assert np.array_equal(gu.bits_to_host(out, d), syn.bf16_bits_from_f32(back))
+        else:
+            out = gu.dev_empty(n, ld, fill=-9.0)
+            sat.history_decompress(codes, row_off, n, None, n, d, prec, out, ld, stream=gu.stream_ptr())
+            gu.sync()
+            assert np.array_equal(out.cpu().numpy()[:, :d].view(np.uint32), back.view(np.uint32))
+        assert np.isfinite(back).all() and np.abs(back).max() == np.float32(2.0 ** 30) / np.float32(10.0 ** prec)
+
+
 @pytest.mark.parametrize("case", ["unaligned_codes", "wide_rows", "unaligned_rows"])
 def test_codec_encoder_paths_give_the_same_bytes(env, case):
     """The encoder assembles rows in LDS and writes 16-byte pieces when the code array is 16-byte

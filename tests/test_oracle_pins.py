@@ -691,6 +691,41 @@ def test_polyline_round_trip_error_bound_and_lengths():
     assert 4.0 * base.size / orc.polyline_encode_rows(base, 1)[1][-1] > 3.0
 
 
+def test_polyline_out_of_range_values_saturate_and_nan_codes_as_zero():
+    """The edge clauses of the quantiser (the paper's compression section says nothing about
+    them; reading: hold |q| at 2^30, the largest magnitude whose shifted code fits 32 bits
+    for either sign, and code NaN as 0). The byte strings below are derived by hand from the
+    format's rules: 2^30 shifts to 2^31 = six zero groups with a successor (0x20 + 63 = '_')
+    and a last group 2 (+ 63 = 'A'); -2^30 shifts to 2^31 and inverts to 2^31 - 1 = six
+    all-ones groups with a successor (31 + 32 + 63 = '~') and a last group 1 ('@')."""
+    QM = 1 << 30
+    assert orc.POLYLINE_Q_MAX == QM
+    assert orc.polyline_encode_value(QM) == b"______A"
+    assert orc.polyline_encode_value(-QM) == b"~~~~~~@"
+    big = np.float32(QM)
+    for prec in (0, 2, 5):
+        sc = np.float32(10.0 ** prec)
+        edge = big / sc                          # v * 10^p lands on (or within rounding of) 2^30
+        H = np.array([[edge, -edge, 4.0 * edge, -4.0 * edge, 1e30, -1e30, np.inf, -np.inf,
+                       np.nan, -0.0, 0.0, 3.4e38, -3.4e38]], dtype=np.float32)
+        q = orc.polyline_quantise(H, prec)[0]
+        assert list(q[2:8]) == [QM, -QM, QM, -QM, QM, -QM], (prec, q)
+        assert abs(int(q[0])) <= QM and abs(int(q[1])) <= QM and q[0] > 0 > q[1]
+        assert list(q[8:11]) == [0, 0, 0]                      # NaN, -0.0, 0.0
+        assert list(q[11:]) == [QM, -QM]                       # the product overflows to +-inf in fp32
+        codes, off = orc.polyline_encode_rows(H, prec)
+        assert codes.min() >= 63 and codes.max() <= 126 and np.all(np.diff(off) <= 7 * H.shape[1])
+        back = orc.polyline_decode_rows(codes, off, [0], H.shape[1], prec)[0]
+        assert np.array_equal(back[2:8], np.float32(QM) / sc * np.array([1, -1, 1, -1, 1, -1], np.float32))
+        assert np.all(back[8:11] == 0) and not np.signbit(back[8:11]).any()
+        assert np.array_equal(orc.polyline_stored_value(H, prec)[0].view(np.uint32), back.view(np.uint32))
+    # just inside the range nothing is clipped: the largest fp32 below 2^30 keeps its own code
+    below = np.nextafter(big, np.float32(0))
+    assert orc.polyline_quantise(np.array([[below, -below]], np.float32), 0).tolist() == [[int(below), -int(below)]]
+    # fp64 arithmetic (the published examples' path) takes the same clauses
+    assert orc.polyline_quantise(np.array([1e300, -1e300, np.nan]), 5, arith=np.float64).tolist() == [QM, -QM, 0]
+
+
 # ------------------------------------------------ what the predictor is for
 def test_trained_predictor_alleviates_staleness_on_drifting_embeddings():
     """The method's premise (Sec. "Embedding Predictor", the constraint of Eq. 8': the predicted
