@@ -123,6 +123,10 @@ class PartitionStep:
         self.X_table, self.hist, self.table_ids = X_table, hist, table_ids
         self.halo_table_ids = table_ids[self.n_local:]
         self.local_table_ids = table_ids[:self.n_local]
+        # None stands for plain historical embeddings: a predictor in bypass mode (no parameters)
+        predictors = [None] + [w if w is not None else B.Predictor(None, None, None, None, dims[l], 0, tau,
+                                                                   bypass=True)
+                               for l, w in enumerate(predictors) if l >= 1]
         self.Ws, self.predictors, self.y = Ws, predictors, y
         self.coded = coded
         self.fused_pull = fused_pull and coded is None
@@ -152,7 +156,7 @@ class PartitionStep:
         ws_bytes = [B.loss_workspace_bytes(n_l)]
         ws_bytes += [B.dense_bwd_workspace_bytes(n_l, dims[l], dims[l + 1]) for l in range(L)]
         for l in range(1, L):
-            if predictors[l] is not None:
+            if not predictors[l].bypass:
                 ws_bytes.append(B.predict_workspace_bytes(n_l, self.n_halo, dims[l],
                                                           predictors[l].d_s, tau))
         if coded is not None:

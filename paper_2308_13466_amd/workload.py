@@ -56,8 +56,6 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     """
     dev = torch.device(device)
     cfg = syn.get_config(name)
-    if name == "tiny":
-        cfg["d_s"] = 32
     dims, tau, d_s = cfg["dims"], cfg["tau"], cfg["d_s"]
     dtype = dtype or cfg.get("dtype", "f32")
     bf16 = dtype == "bf16"

@@ -10,7 +10,7 @@ CONFIGS = {
     "tiny": dict(
         kind="sbm", N=4096, n_comm=2, n_parts=2, part=0,
         intra_deg=7.0, cross_deg=1.0,          # expected neighbours per node
-        dims=[64, 32, 8], noise_std=0.01, tau=2, d_s=16, seed=0,
+        dims=[64, 32, 8], noise_std=0.01, tau=2, d_s=32, seed=0,
     ),
     # ogbn-arxiv-shaped: 169,343 nodes / 2.3 M edges / 128 features / 40 classes
     "medium": dict(

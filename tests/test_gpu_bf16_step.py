@@ -29,11 +29,6 @@ def test_partition_step_bf16_two_steps(name):
     from tests import gpu_util as gu
     print("[case] bf16 step %s" % name, flush=True)
     cfg, ss, g, X, Ws, omegas = build_problem(name)
-    if name == "tiny":
-        cfg["d_s"] = 32
-        pss = ss["predictor"].spawn(len(Ws))
-        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32)
-                           for l in range(1, len(Ws))]
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     m = cfg["part"]
     _, hist = fresh_history(cfg, ss, g, X, Ws)

@@ -59,10 +59,6 @@ def test_partition_step_with_a_coded_ring(name, prec, bypass):
     from tests import gpu_util as gu
     print("[case] coded-ring step %s, %d decimals, bypass=%s" % (name, prec, bypass), flush=True)
     cfg, ss, g, X, Ws, omegas = build_problem(name)
-    if name == "tiny":
-        cfg["d_s"] = 32
-        pss = ss["predictor"].spawn(len(Ws))
-        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32) for l in range(1, len(Ws))]
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     Hfull, hist = fresh_history(cfg, ss, g, X, Ws)
     view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, cfg["part"])
@@ -269,10 +265,6 @@ def test_coded_ring_step_bf16_storage(name):
         return orc.round_bf16(orc.polyline_stored_value(a, prec)).astype(np.float32)
 
     cfg, ss, g, X, Ws, omegas = build_problem(name)
-    if name == "tiny":
-        cfg["d_s"] = 32
-        pss = ss["predictor"].spawn(len(Ws))
-        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32) for l in range(1, len(Ws))]
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     _, hist = fresh_history(cfg, ss, g, X, Ws)
     X = r(X)

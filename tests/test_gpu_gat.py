@@ -214,11 +214,6 @@ def test_gat_partition_step_two_steps(env, name, bf16):
     from tests.test_gpu_step import build_problem, fresh_history
     _say("gat step %s bf16=%s" % (name, bf16))
     cfg, ss, g, X, Ws, omegas = build_problem(name)
-    if name == "tiny":
-        cfg["d_s"] = 32
-        pss = ss["predictor"].spawn(len(Ws))
-        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32)
-                           for l in range(1, len(Ws))]
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     heads = syn.gat_heads(dims)
     ass = ss["misc"].spawn(L)

@@ -122,11 +122,6 @@ def test_partition_step_two_steps(name, fused):
     from tests import gpu_util as gu
     print("[case] step %s fused_pull=%s" % (name, fused), flush=True)
     cfg, ss, g, X, Ws, omegas = build_problem(name)
-    if name == "tiny":
-        cfg["d_s"] = 32
-        pss = ss["predictor"].spawn(len(Ws))
-        omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32)
-                           for l in range(1, len(Ws))]
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     m = cfg["part"]
     Hfull, hist = fresh_history(cfg, ss, g, X, Ws)
@@ -202,8 +197,9 @@ def test_zero_staleness_invariant_on_gpu():
                            for l in range(1, L)]
         ids_d = gu.to_dev(np.concatenate([view["local_ids"], view["halo_ids"]]).astype(np.int32))
         Ws_d = [gu.to_dev(Ws[l], gu.ld_for(dims[l + 1], 4)) for l in range(L)]
+        # the two spellings of "no predictor": an explicit bypass predictor, or None
         preds = [None] + [sat.Predictor(None, None, None, None, dims[l], 32, tau, bypass=True)
-                          for l in range(1, L)]
+                          if m == 0 else None for l in range(1, L)]
         step = PartitionStep(view, dims, gu.to_dev(X, ld[0]), hist_d, ids_d, Ws_d, preds,
                              gu.to_dev(y), tau)
         step.forward_backward()
@@ -223,8 +219,6 @@ def test_predictor_update_frequency():
     from tests import gpu_util as gu
     print("[case] predictor every 2 steps, tiny", flush=True)
     cfg, ss, g, X, Ws, omegas = build_problem("tiny")
-    pss = ss["predictor"].spawn(len(Ws))
-    omegas = [None] + [syn.predictor_params_f32(pss[l], cfg["dims"][l], 32) for l in range(1, len(Ws))]
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     _, hist = fresh_history(cfg, ss, g, X, Ws)
     view = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
