@@ -212,8 +212,9 @@ sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w, const vo
  * shift left one bit and invert if negative, 5-bit groups from the low end, 0x20 set
  * on every group but the last, plus 63 (bytes 63..126). Values are coded one by one,
  * a row is the concatenation of its d codes, row k occupies bytes
- * [row_off[k], row_off[k+1]) of `codes`. |q| saturates at 2^30 - 1; NaN codes as 0.
- * Lossy: |decoded - v| <= 10^-precision / 2 (plus fp32 rounding).
+ * [row_off[k], row_off[k+1]) of `codes`. |q| saturates at 2^30 (the largest magnitude
+ * whose shifted code fits 32 bits for either sign; +-inf land there), NaN codes as 0.
+ * Lossy: |decoded - v| <= 10^-precision / 2 (plus fp32 rounding) for |v| 10^precision < 2^30.
  *   _plan    row_off[0..n] (device int64) from the dense rows H [n, ld_h]: code sizes,
  *            then an exclusive scan; row_off[n] is the total number of bytes. The caller
  *            reads it back to size `codes`.
@@ -308,6 +309,9 @@ sat_status sat_dense_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in,
  * dW == NULL skips the weight gradient (AGG may then be NULL and no workspace
  * is needed): only dAGG is computed.
  * Workspace: sat_dense_bwd_workspace_bytes(); 256-byte aligned device memory.
+ * The first call with dW != NULL on a device raises that device's limit on dynamic
+ * LDS for the weight-gradient kernel (a HIP runtime setting, no allocation; failure is
+ * SAT_EHIP): make one such call per device before capturing the call into a HIP graph.
  */
 int64_t sat_dense_bwd_workspace_bytes(int64_t n, int32_t d_in, int32_t d_out);
 sat_status sat_dense_bwd(const void* dH, int64_t ld_dh, const void* Hout, int64_t ld_ho,

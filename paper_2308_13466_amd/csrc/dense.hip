@@ -13,6 +13,8 @@
 //             results are identical from run to run).
 // dZ = dH o [Hout > 0] is never written to memory: the mask is applied while the
 // operand tile is loaded.
+#include <atomic>
+
 #include "dw_kernel.h"
 #include "mx_tile.h"
 #include "sat_internal.h"
@@ -84,18 +86,29 @@ SplitPlan plan_dw(int64_t n, int32_t d_in, int32_t d_out) {
 }
 
 template <int ES, int MT, int NT, bool MASK>
-void launch_dw_one(const dim3 grid, const void* A, int64_t ld_a, int d_a, const void* B, int64_t ld_b,
-                   int d_b, const void* M, int64_t ld_m, int64_t n, const SplitPlan& p, float* part,
-                   hipStream_t s) {
+sat_status launch_dw_one(const dim3 grid, const void* A, int64_t ld_a, int d_a, const void* B,
+                         int64_t ld_b, int d_b, const void* M, int64_t ld_m, int64_t n,
+                         const SplitPlan& p, float* part, hipStream_t s) {
   constexpr int smem = sat::dw::smem_bytes<ES, MT, NT>();
-  static bool attr_set = false;   // dynamic LDS above 64 KB needs the opt-in once per kernel
-  if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&sat::dw::dw_kernel<ES, MT, NT, MASK>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    attr_set = true;
+  // Dynamic LDS above 64 KB needs an opt-in per kernel AND per device. One bit per device,
+  // set after the call succeeded; two threads that both find it clear both make the call,
+  // which is harmless. A failed opt-in is reported here, not as a launch error later.
+  static std::atomic<uint64_t> opted_in{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess && (dev < 0 || dev >= 64)) return SAT_EUNSUPPORTED;
+  if (e == hipSuccess && !((opted_in.load(std::memory_order_acquire) >> dev) & 1ull)) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sat::dw::dw_kernel<ES, MT, NT, MASK>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e == hipSuccess) opted_in.fetch_or(1ull << dev, std::memory_order_release);
+  }
+  if (e != hipSuccess) {
+    sat::set_last_hip_error(e);
+    return SAT_EHIP;
   }
   sat::dw::dw_kernel<ES, MT, NT, MASK><<<grid, dim3(256), smem, s>>>(
       A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p.k_per_split, part, p.ld_part, p.split_stride);
+  return sat::check_launch();
 }
 
 // part[z] = (rows of range z of A)^T (same rows of B, masked), z < p.splits
@@ -107,17 +120,14 @@ sat_status launch_dw(const void* A, int64_t ld_a, int d_a, const void* B, int64_
   const int bmx = big_m ? 256 : 128, bnx = big_n ? 256 : 128;
   const dim3 grid(static_cast<unsigned>((d_a + bmx - 1) / bmx), static_cast<unsigned>((d_b + bnx - 1) / bnx),
                   static_cast<unsigned>(p.splits));
-#define SAT_DW(MT, NT)                                                                          \
-  do {                                                                                          \
-    if (M) launch_dw_one<ES, MT, NT, true>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s); \
-    else launch_dw_one<ES, MT, NT, false>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s);  \
-  } while (0)
-  if (big_m && big_n) SAT_DW(4, 4);
-  else if (big_m) SAT_DW(4, 2);
-  else if (big_n) SAT_DW(2, 4);
-  else SAT_DW(2, 2);
+#define SAT_DW(MT, NT)                                                                                 \
+  (M ? launch_dw_one<ES, MT, NT, true>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s)        \
+     : launch_dw_one<ES, MT, NT, false>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s))
+  if (big_m && big_n) return SAT_DW(4, 4);
+  if (big_m) return SAT_DW(4, 2);
+  if (big_n) return SAT_DW(2, 4);
+  return SAT_DW(2, 2);
 #undef SAT_DW
-  return sat::check_launch();
 }
 
 sat_status check_mat(const void* p, int64_t rows, int64_t cols, int64_t ld, int es = 4) {
