@@ -332,6 +332,22 @@ sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_cla
                          const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh, float* loss,
                          void* workspace, int64_t workspace_bytes, void* stream);
 
+/* sat_loss_grad for callers that cannot allocate device memory or carry a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the same kernels and results, with the per-block partial sums of the loss in an
+ * array the library holds statically on every GPU it runs on (1 MiB per GPU, kept until
+ * the process ends) instead of a workspace. Calls no hipMalloc / hipFree. Limit:
+ * n <= sat_loss_grad_static_max_rows() (33,554,432), beyond it SAT_EUNSUPPORTED and
+ * nothing is enqueued. Every call on one GPU shares that GPU's array: two calls that may
+ * overlap in time on one GPU (different streams) race on it; calls on one stream do not.
+ * Nothing in the array has to be cleared between calls (each call overwrites the part it
+ * reads). The first call on a device looks the array's address up (a HIP runtime query,
+ * no allocation); make one call per device before capturing a graph. */
+int64_t sat_loss_grad_static_max_rows(void);
+sat_status sat_loss_grad_static(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
+                                const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh,
+                                float* loss, void* stream);
+
 /* =================== graph attention backbone (second backbone of the paper's
  * experiments; the layer is Eq. 1 / Eq. 2 with attention as the aggregation
  * function, defined as in Velickovic et al., "Graph Attention Networks",

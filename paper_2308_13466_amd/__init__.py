@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     history_decompress, spmm_fwd, spmm_bwd, spmm_workspace_bytes,
     dense_fwd, dense_bwd, dense_bwd_workspace_bytes, loss_grad, gat_scores,
     gat_aggregate_fwd, gat_aggregate_bwd, gat_aggregate_bwd_workspace_bytes,
-    loss_workspace_bytes, status_string, version, F32, BF16, ACT_IDENTITY,
+    loss_workspace_bytes, loss_grad_static, loss_grad_static_max_rows, status_string, version,
+    F32, BF16, ACT_IDENTITY,
     ACT_RELU,
 )

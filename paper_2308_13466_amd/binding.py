@@ -75,6 +75,8 @@ _SIGNATURES = {
                                      _vp, _i64, _vp]),
     "sat_loss_workspace_bytes": (_i64, [_i64]),
     "sat_loss_grad": (_i32, [_vp, _i64, _i64, _i32, _vp, _i32, _vp, _i64, _vp, _vp, _i64, _vp]),
+    "sat_loss_grad_static_max_rows": (_i64, []),
+    "sat_loss_grad_static": (_i32, [_vp, _i64, _i64, _i32, _vp, _i32, _vp, _i64, _vp, _vp]),
 }
 EXPORTS = tuple(sorted(_SIGNATURES))
 
@@ -313,3 +315,12 @@ def loss_grad(HL, ld_hl, n, n_classes, y, dH, ld_dh, loss=None, dtype=F32, works
     _check(lib().sat_loss_grad(_ptr(HL), ld_hl, n, n_classes, _ptr(y), dtype, _ptr(dH), ld_dh,
                                _ptr(loss), _ptr(workspace), workspace_bytes, stream),
            "sat_loss_grad")
+
+
+def loss_grad_static_max_rows():
+    return lib().sat_loss_grad_static_max_rows()
+
+
+def loss_grad_static(HL, ld_hl, n, n_classes, y, dH, ld_dh, loss=None, dtype=F32, stream=None):
+    _check(lib().sat_loss_grad_static(_ptr(HL), ld_hl, n, n_classes, _ptr(y), dtype, _ptr(dH),
+                                      ld_dh, _ptr(loss), stream), "sat_loss_grad_static")

@@ -7,6 +7,7 @@
 // it is identical from run to run.
 #include <math.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "sat_internal.h"
@@ -314,21 +315,30 @@ extern "C" int64_t sat_loss_workspace_bytes(int64_t n) {
   return ((n + kRowsPerBlock - 1) / kRowsPerBlock) * static_cast<int64_t>(sizeof(float));
 }
 
-extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
-                                    const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh,
-                                    float* loss, void* workspace, int64_t workspace_bytes,
-                                    void* stream) {
+namespace {
+
+// Argument checks shared by the two entry points (everything but the scratch).
+sat_status loss_grad_check(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
+                           const int32_t* y, int32_t dtype, const void* dH, int64_t ld_dh) {
   if (n < 0 || n_classes <= 0) return SAT_EINVAL;
   if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
   if (n == 0) return SAT_OK;
   if (!HL || !y || !dH || ld_hl < n_classes || ld_dh < n_classes) return SAT_EINVAL;
+  if ((n + kRowsPerBlock - 1) / kRowsPerBlock > INT32_MAX) return SAT_EUNSUPPORTED;
+  return SAT_OK;
+}
+
+// Enqueues the kernels. partials: device floats, one per block, every one of them written by
+// the first kernel before the second reads it (nothing has to be cleared); only used when
+// loss != NULL. Arguments have been checked and n > 0.
+sat_status loss_grad_launch(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
+                            const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh, float* loss,
+                            float* partials, void* stream) {
   const int64_t blocks = (n + kRowsPerBlock - 1) / kRowsPerBlock;
-  if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
-  if (loss && (!workspace || workspace_bytes < sat_loss_workspace_bytes(n))) return SAT_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const unsigned char* hl = static_cast<const unsigned char*>(HL);
   unsigned char* dh = static_cast<unsigned char*>(dH);
-  float* bl = loss ? static_cast<float*>(workspace) : nullptr;
+  float* bl = loss ? partials : nullptr;
   const dim3 grid(static_cast<unsigned>(blocks)), block(256);
   const int es_b = dtype == SAT_BF16 ? 2 : 4;
   // (with few classes the groups of 4 would leave most lanes idle: one class per lane then)
@@ -356,7 +366,7 @@ extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, in
 #undef SAT_XENT_Q
     sat_status stq = sat::check_launch();
     if (stq != SAT_OK || !loss) return stq;
-    loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(static_cast<const float*>(workspace), blocks, n, loss);
+    loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(bl, blocks, n, loss);
     return sat::check_launch();
   }
   const int nv = n_classes <= 4 * kWave ? (n_classes + kWave - 1) / kWave : 0;
@@ -381,7 +391,73 @@ extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, in
 #undef SAT_XENT
   sat_status st = sat::check_launch();
   if (st != SAT_OK || !loss) return st;
-  loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(static_cast<const float*>(workspace), blocks,
-                                                   n, loss);
+  loss_finish_kernel<<<dim3(1), dim3(256), 0, s>>>(bl, blocks, n, loss);
   return sat::check_launch();
+}
+
+}  // namespace
+
+extern "C" sat_status sat_loss_grad(const void* HL, int64_t ld_hl, int64_t n, int32_t n_classes,
+                                    const int32_t* y, int32_t dtype, void* dH, int64_t ld_dh,
+                                    float* loss, void* workspace, int64_t workspace_bytes,
+                                    void* stream) {
+  const sat_status st = loss_grad_check(HL, ld_hl, n, n_classes, y, dtype, dH, ld_dh);
+  if (st != SAT_OK || n == 0) return st;
+  if (loss && (!workspace || workspace_bytes < sat_loss_workspace_bytes(n))) return SAT_EWORKSPACE;
+  return loss_grad_launch(HL, ld_hl, n, n_classes, y, dtype, dH, ld_dh, loss,
+                          static_cast<float*>(workspace), stream);
+}
+
+// ---- the same call for callers that cannot allocate: the per-block partial sums of the loss
+// live in a file-scope device array instead of a caller's workspace.
+namespace {
+
+constexpr int64_t kStaticPartials = 262144;          // floats: 1 MiB per GPU the library runs on
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) float scratch[kStaticPartials];
+
+// Device address of `scratch` on each GPU (every GPU holds its own copy of the array at its
+// own address). In host code the array's name is not that address: it is looked up once per
+// device with that device current, and only the looked-up pointer is handed to kernels.
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};
+
+sat_status static_partials(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) {
+    sat::set_last_hip_error(e);
+    return SAT_EHIP;
+  }
+  if (dev < 0 || dev >= kMaxDevices) return SAT_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      sat::set_last_hip_error(e);
+      return SAT_EHIP;
+    }
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return SAT_OK;
+}
+
+}  // namespace
+
+extern "C" int64_t sat_loss_grad_static_max_rows(void) { return kStaticPartials * kRowsPerBlock; }
+
+extern "C" sat_status sat_loss_grad_static(const void* HL, int64_t ld_hl, int64_t n,
+                                           int32_t n_classes, const int32_t* y, int32_t dtype,
+                                           void* dH, int64_t ld_dh, float* loss, void* stream) {
+  const sat_status st = loss_grad_check(HL, ld_hl, n, n_classes, y, dtype, dH, ld_dh);
+  if (st != SAT_OK || n == 0) return st;
+  if (n > sat_loss_grad_static_max_rows()) return SAT_EUNSUPPORTED;
+  float* partials = nullptr;
+  if (loss) {
+    const sat_status sp = static_partials(&partials);
+    if (sp != SAT_OK) return sp;
+  }
+  return loss_grad_launch(HL, ld_hl, n, n_classes, y, dtype, dH, ld_dh, loss, partials, stream);
 }

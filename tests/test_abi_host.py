@@ -121,6 +121,11 @@ def test_compute_calls_validate_before_launch(sat):
     assert L.sat_dense_fwd(None, 8, 0, 8, 8, None, 8, 7, 0, None, 8, None) == -1     # bad act
     assert L.sat_spmm_fwd(None, None, 8, 8, 0, None, 8, None, 0, None) == -1
     assert L.sat_loss_grad(None, 8, 4, 0, None, 0, None, 8, None, None, 0, None) == -1
+    # the entry point with static scratch: same checks, and its size limit, all on the host
+    assert L.sat_loss_grad_static(None, 8, 4, 0, None, 0, None, 8, None, None) == -1
+    assert L.sat_loss_grad_static(None, 8, 0, 8, None, 0, None, 8, None, None) == 0      # empty: no-op
+    assert L.sat_loss_grad_static(4096, 8, sat.loss_grad_static_max_rows() + 1, 8, 8192, 0, 12288, 8,
+                                  16384, None) == -2
     assert sat.dense_bwd_workspace_bytes(1000, 64, 32) > 0
     assert sat.predict_workspace_bytes(10, 5, 64, 32, 2) >= 15 * 32 * 4
     assert sat.loss_workspace_bytes(9) >= 4
