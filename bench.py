@@ -27,23 +27,22 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 # algorithmic (fp32) flops are therefore priced against 2500 / 6 TFLOP/s.
 MFMA_SPLIT_PEAK_TFLOPS = 2500.0 / 6.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE,
-# scaled by a copy kernel of known size); filled in from the committed profile
-# summaries, None where no counter run exists for that workload / kernel.
-MEASURED_TRAFFIC_BYTES = {      # profiles/large_step_hbm_traffic.md, average over the class's launches
-    ("large", "spmm"): 11.54e9,       # 4 launches of 12.71 GB (d = 256) and one of 6.86 GB (d = 100)
-    ("large", "gather"): 1.064e9,
-    ("large", "push"): 0.627e9,
-    ("large", "dense_fwd"): 0.640e9,
-    ("large", "dense_bwd"): 1.44e9,   # call level: weight-gradient product + its reduction + dAGG product
-    ("large", "predict"): 7.68e9,     # call level: LSTM 3.52 + hop aggregation 1.24 + hop product 2.91
-    ("large", "loss"): 0.136e9,
-    # graph attention backbone, profiles/large_gat_step_hbm_traffic.md
-    ("large", "gat_fwd"): 12.06e9,    # two launches of 16.02 GB (4 heads x 64) and one of 4.13 GB (1 x 47)
-    ("large", "gat_scores"): 1.10e9,
-    ("large", "gat_bwd"): 27.9e9,     # call level: mask 0.92 + destination side 16.06 + source side 12.83 + 5.88
-                                      # + attention vectors 1.10 (last layer: 4.16 + 3.48 + 1.41 + 0.37)
-}
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE, scaled by a
+# copy kernel of known size): read from the data file that is written together with the
+# counter summaries under profiles/. None where no counter run covers a workload / class.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_class.txt")
+
+
+def measured_traffic():
+    """{(workload, backbone, dtype, class): bytes per launch}. Lines: five whitespace-separated
+    fields, '#' starts a comment."""
+    table = {}
+    if os.path.exists(TRAFFIC_FILE):
+        for ln in open(TRAFFIC_FILE):
+            f = ln.split("#")[0].split()
+            if len(f) == 5:
+                table[(f[0], f[1], f[2], f[3])] = float(f[4])
+    return table
 
 
 KERNEL_OF_CLASS = {"spmm": "spmm_stream_kernel", "gather": "row_copy_vec_kernel (gather)",
@@ -132,6 +131,12 @@ def main():
                     help="rewrite a 1 GiB buffer before every library call, so that no call finds "
                          "its inputs in the caches (for the workloads whose working set fits "
                          "them); ms_per_step is then the sum of the calls' own times")
+    ap.add_argument("--predict-ahead", action="store_true",
+                    help="enqueue the predictions of step t + 1 on a second stream beside step t's "
+                         "backward (they only need the ring as step t's pushes leave it)")
+    ap.add_argument("--no-scale-leg", action="store_true",
+                    help="do not append the full Scale configuration (bf16; run by a child process "
+                         "after the headline workload has been timed) under the key \"scale\"")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -164,7 +169,8 @@ def main():
     timers = CallTimers(torch, flush)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
-                        predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring)
+                        predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring,
+                        predict_ahead=args.predict_ahead)
     gat = args.backbone == "gat"
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
@@ -183,6 +189,23 @@ def main():
         log("calibration copy: %d rows x %d floats (%.0f bytes read, same written)" % (
             rows, width, rows * width * 4.0))
         del src, dst, ident
+
+    # ---- CPU-baseline samples. Inputs that only exist on the device are read back now,
+    # before any step overwrites a history slot; host copies are sampled after the timing.
+    def fetch_rows(kind, l, slot, node_ids):
+        tid = wl.table_ids[node_ids]
+        if wl.X_host is not None:
+            t = wl.X_host if kind == "X" else wl.hist_host[l][slot]
+            return t[tid][:, :dims[l]]
+        t = step.X_table if kind == "X" else step.hist[l][slot]
+        idx = torch.from_numpy(tid.astype(np.int64)).to(dev)
+        return t[idx][:, :dims[l]].float().cpu().numpy()
+
+    want_cpu = not args.no_cpu_baseline and wl.coded is None
+    cpu_prep = None
+    if want_cpu and wl.X_host is None:
+        cpu_prep = cpu_baseline_prepare(view, dims, tau, d_s, fetch_rows, wl.y, args.bypass, gat)
+        log("cpu oracle: samples read back from the device in %.1fs" % cpu_prep["build_s"])
 
     # ---- warm-up, then the timed region
     for _ in range(args.warmup):
@@ -233,21 +256,30 @@ def main():
     def spmm_bytes(entries, rows, d):       # per entry: col + val + one feature row;
         return entries * (8 + d * s) + rows * (8 + d * s)   # per row: rowptr + output row
 
+    def spmm_compulsory(entries, rows, distinct, d):
+        # what the call cannot avoid moving: the index arrays once, every DISTINCT operand row
+        # once (however often it is gathered), every output row once
+        return 8 * entries + 8 * rows + distinct * d * s + rows * d * s
+
     classes = {}
 
-    def add(cls, name, bound, work):
+    def add(cls, name, bound, work, compulsory=None):
         if name not in calls:
             return
-        c = classes.setdefault(cls, dict(bound=bound, work=0.0, ms=0.0, launches=0))
+        c = classes.setdefault(cls, dict(bound=bound, work=0.0, ms=0.0, launches=0, compulsory=0.0))
         c["work"] += work * calls[name]["launches"]
+        c["compulsory"] += (work if compulsory is None else compulsory) * calls[name]["launches"]
         c["ms"] += calls[name]["total_ms"]
         c["launches"] += calls[name]["launches"]
 
     for l in range(L):
-        add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]))
+        add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]),
+            spmm_compulsory(nnz, n_l, n_bar, dims[l]))
         if l >= 1:
             add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]) + (
-                spmm_bytes(nnz_halo, n_h, dims[l]) if args.stale_grad else 0))
+                spmm_bytes(nnz_halo, n_h, dims[l]) if args.stale_grad else 0),
+                spmm_compulsory(nnz_loc, n_l, n_l, dims[l]) + (
+                    spmm_compulsory(nnz_halo, n_h, n_l, dims[l]) if args.stale_grad else 0))
         if gat:      # the transform runs over local + halo rows; three edge passes per layer
             K = step.heads[l]
             dl = dims[l + 1]
@@ -288,6 +320,7 @@ def main():
     add("loss", "loss_grad", "hbm", n_l * (2 * dims[L] * s + 4))
 
     roof_all = {}
+    traffic_table = measured_traffic()
     for cls, c in classes.items():
         sec = c["ms"] * 1e-3
         if c["bound"] == "hbm":
@@ -295,15 +328,30 @@ def main():
         else:
             ach, unit = c["work"] / sec / 1e12, "TFLOP/s"
             peak = round(peak_predict if cls == "predict" else peak_dense, 1)
+        # measured bytes exist for the plain configuration of a workload only
+        plain_cfg = (args.coded_ring is None and not args.stale_grad and not args.bypass
+                     and not args.unfused_pull)
+        traffic = traffic_table.get((args.workload, args.backbone, wl.dtype, cls)) if plain_cfg else None
         roof_all[cls] = dict(bound=c["bound"], achieved=round(ach, 2), peak=peak, unit=unit,
                              frac=round(ach / peak, 4),
                              avg_launch_ms=round(c["ms"] / c["launches"], 4),
                              ms_per_step=round(c["ms"] / args.steps, 4),
                              launches_per_step=c["launches"] // args.steps,
-                             traffic=None if bf16 != (cfg.get("dtype") == "bf16") or (
-                                 gat and not cls.startswith("gat_") and cls not in ("predict", "push", "loss")) or (
-                                 args.coded_ring is not None and cls == "predict")
-                             else MEASURED_TRAFFIC_BYTES.get((args.workload, cls)))
+                             traffic=traffic)
+        if cls == "spmm":
+            # Three readings of the same launches. `frac` prices what the lanes REQUEST (a row
+            # per entry): re-gathered rows that a cache serves count as if they came from HBM,
+            # so it is an upper bound on the HBM fraction and can pass 1. The measured one
+            # divides the bytes that crossed the L2-to-fabric interface (rocprofv3 counters) by
+            # the same time. The compulsory one counts every distinct row once.
+            r = roof_all[cls]
+            r["model"] = "gather traffic: per entry 8 B of indices + one operand row of d*s B; per row 8 B + one output row"
+            r["frac_gather_model"] = r["frac"]
+            r["frac_measured_traffic"] = (round(traffic * c["launches"] / sec / 1e9 / HBM_PEAK_GBS, 4)
+                                          if traffic else None)
+            r["compulsory_bytes"] = round(c["compulsory"] / c["launches"])
+            r["frac_compulsory"] = round(c["compulsory"] / sec / 1e9 / HBM_PEAK_GBS, 4)
+            r["traffic_over_compulsory"] = round(traffic * c["launches"] / c["compulsory"], 2) if traffic else None
     # The dominant KERNEL: classes whose calls are one kernel each (aggregation, pull,
     # push, forward transform, loss) are kernels; "predict" and "dense_bwd" are calls
     # made of several kernels, none of which outweighs the aggregation kernel (see the
@@ -424,16 +472,15 @@ def main():
             prec, codec["ratio_vs_stored"], enc_ms, dec_ms))
         del rows, codes, out, ws
 
-    # ---- CPU oracle on a bounded sample, rank 0, host cores
+    # ---- CPU oracle on a bounded sample, rank 0, host cores (one core, then all of them)
     cpu = None
-    if not args.no_cpu_baseline and wl.X_host is None:
-        log("cpu oracle: skipped (this workload's inputs are drawn on the device)")
-    elif not args.no_cpu_baseline and wl.coded is not None:
+    if not args.no_cpu_baseline and wl.coded is not None:
         log("cpu oracle: skipped (timed on the dense ring; run without --coded-ring)")
-    elif not args.no_cpu_baseline:
-        cpu = cpu_baseline(view, dims, tau, d_s, wl.X_host, wl.hist_host, wl.table_ids, wl.Ws,
-                           wl.omegas, wl.y, edges, bypass=args.bypass, log=log,
-                           gat_attn=wl.attn if gat else None)
+    elif want_cpu:
+        if cpu_prep is None:
+            cpu_prep = cpu_baseline_prepare(view, dims, tau, d_s, fetch_rows, wl.y, args.bypass, gat)
+        cpu = cpu_baseline_run(cpu_prep, wl.Ws, wl.omegas, wl.attn if gat else None, edges, log)
+        cpu_prep = None
 
     out = {
         "metric": "GTEPS aggregated (CSR entries aggregated per second over one partition's "
@@ -448,6 +495,7 @@ def main():
                    "predictor": "bypass" if args.bypass else (
                        "every step" if args.delta_t <= 1 else "every %d steps" % args.delta_t),
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
+                   "predictions": "one step ahead, on a second stream" if args.predict_ahead else "in the step",
                    "stale_gradient_term": bool(args.stale_grad),
                    "history_ring": "dense" if args.coded_ring is None else "coded, %d decimals" % args.coded_ring,
                    "caches": "flushed before every call" if args.cold else "as the step leaves them",
@@ -460,142 +508,265 @@ def main():
         "roofline": roofline,
         "roofline_all": roof_all,
         "cpu_baseline": cpu,
+        "scale": None,
         "graph": graph_info,
         "predictor_train": ptrain,
         "codec": codec,
         "coded_ring": coded_ring,
         "loss": round(loss, 6),
     }
+    # ---- the Scale configuration (bf16 by its own definition) in a child process of its own,
+    # after everything of the headline workload has been measured and its memory released;
+    # whatever happens to the child, the line below is printed
+    plain = (not gat and args.coded_ring is None and not args.cold and not args.pmc_calibration
+             and not args.stale_grad and not args.bypass and not args.predictor_train
+             and args.codec is None and not args.graph and args.dtype is None and not args.predict_ahead)
+    if args.workload == "large" and not args.no_scale_leg and plain:
+        import gc
+        del wl, step, timers, cpu_prep
+        gc.collect()
+        torch.cuda.empty_cache()
+        try:
+            out["scale"] = scale_leg(log)
+        except Exception as e:                       # noqa: BLE001 - the headline must still print
+            out["scale"] = {"error": "%s: %s" % (type(e).__name__, e)}
     print(json.dumps(out))
 
 
-def cpu_baseline(view, dims, tau, d_s, X_host, hist_host, table_ids, Ws, omegas, y, edges,
-                 bypass, log, sample_rows=65536, sample_nodes=524288, gat_attn=None):
-    """Time the oracle (as it stands) on a row sample of every call of the step
-    and extrapolate each call by rows_total / rows_sampled (rows of every call
-    are independent of one another)."""
+def scale_leg(log, steps=5, warmup=2, timeout_s=600):
+    """Runs `bench.py --workload scale` (13.9 M local nodes, 412 M CSR entries, bf16 storage,
+    195 GB of HBM) in a fresh child process and returns the parts of its JSON line that
+    describe the measurement. The child logs to this process's stderr."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), "--workload", "scale", "--steps", str(steps),
+           "--warmup", str(warmup), "--no-scale-leg"]
+    log("scale leg: %s" % " ".join(cmd[1:]))
+    t0 = time.time()
+    try:
+        r = subprocess.run(cmd, stdout=subprocess.PIPE, text=True, timeout=timeout_s)
+    except subprocess.TimeoutExpired:
+        return {"error": "the child did not finish within %d s" % timeout_s}
+    lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]
+    if r.returncode != 0 or not lines:
+        return {"error": "the child exited with status %d and %d result lines" % (r.returncode, len(lines))}
+    j = json.loads(lines[-1])
+    keep = ("value", "unit", "ms_per_step", "steps", "warmup", "dtype", "data", "config", "ms_per_layer_step",
+            "gteps_aggregation_calls_only", "ms_by_call", "roofline", "roofline_all", "cpu_baseline", "loss")
+    res = {k: j.get(k) for k in keep}
+    res["child_wall_s"] = round(time.time() - t0, 1)
+    return res
+
+
+# --------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands, timed on a bounded sample of the step.
+# Rows of every call are independent of one another, so a call is timed on a sample of
+# its rows and scaled by rows_total / rows_sampled. A "pack" holds everything the oracle
+# needs for one shard of the sample, in compact numbering (the oracle's functions take
+# any view; nothing in them is changed or specialised for this).
+# --------------------------------------------------------------------------
+def _build_pack(view, dims, tau, d_s, fetch, y, rows, nodes, halo, bypass, gat):
+    """rows: sampled local rows (aggregation, transform, loss, backward); nodes: sampled
+    local + halo nodes (predictor LSTM); halo: sampled halo nodes (predictor hop), or None.
+    fetch(kind, l, s, node_ids) -> float32 rows of the layer-l input of those nodes in
+    local-then-halo numbering: kind "X" the features, "hist" slot s of hidden layer l."""
     import numpy as np
-    from oracle import sat_oracle as orc
+    L = len(dims) - 1
+    n_l = view["n_local"]
+    rp, sp = view["rowptr"], view["split"]
+    segs = [(int(rp[i]), int(rp[i + 1])) for i in rows]
+    cols = np.concatenate([view["col"][a:b] for a, b in segs]) if segs else np.zeros(0, np.int32)
+    uniq, inv = np.unique(np.concatenate([cols, rows.astype(cols.dtype)]), return_inverse=True)
+    lens = np.array([b - a for a, b in segs], dtype=np.int64)
+    m_rowptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    pack = dict(L=L, dims=list(dims), tau=tau, d_s=d_s, bypass=bypass, gat=gat,
+                n_rows=len(rows), n_nodes=len(nodes), n_halo=0 if halo is None else len(halo),
+                mini=dict(n_local=len(rows), n_halo=len(uniq), rowptr=m_rowptr,
+                          split=m_rowptr[:-1] + np.array([int(sp[i]) - a for i, (a, b) in zip(rows, segs)],
+                                                          dtype=np.int64),
+                          col=inv[:len(cols)].astype(np.int32),
+                          val=np.concatenate([view["val"][a:b] for a, b in segs])),
+                own=inv[len(cols):].astype(np.int64),          # compact column id of each sampled row itself
+                y=np.asarray(y)[rows],
+                # stand-in activations of the hidden layers: the newest history slot
+                Hb=[fetch("X", 0, 0, uniq)] + [fetch("hist", l, tau - 1, uniq) for l in range(1, L)])
+    if not bypass:
+        pack["win"] = [None] + [[fetch("hist", l, s, nodes) for s in range(tau)] for l in range(1, L)]
+        if halo is not None and len(halo):
+            cp = view["h_colptr"]
+            nb = [view["h_row"][cp[u]:cp[u + 1]] for u in halo]
+            locs, hinv = np.unique(np.concatenate(nb), return_inverse=True)
+            pack["hop"] = dict(n_local=len(locs), n_halo=len(halo),
+                               h_colptr=np.concatenate([[0], np.cumsum([len(x) for x in nb])]).astype(np.int64),
+                               h_row=hinv.astype(np.int32),
+                               h_val=np.concatenate([view["h_val"][cp[u]:cp[u + 1]] for u in halo]),
+                               h_self=view["h_self"][halo])
+    return pack
+
+
+def _oracle_pack_seconds(args):
+    """Runs the step's oracle calls on one pack; returns seconds per class of sampled unit
+    ("rows", "nodes", "halo"). Top level so that a spawned worker can import it."""
+    pack, Ws, omegas, gat_attn, blas_threads = args
     try:
         from threadpoolctl import threadpool_limits
     except ImportError:                                   # pragma: no cover
-        threadpool_limits = None
-    L = len(dims) - 1
+        return _pack_seconds(pack, Ws, omegas, gat_attn)
+    with threadpool_limits(limits=blas_threads):
+        return _pack_seconds(pack, Ws, omegas, gat_attn)
+
+
+def _pack_seconds(pack, Ws, omegas, gat_attn):
+    import numpy as np
+    from oracle import sat_oracle as orc
+    L, dims, tau, d_s = pack["L"], pack["dims"], pack["tau"], pack["d_s"]
+    mini, Hb, yy = pack["mini"], pack["Hb"], pack["y"]
+    ar = np.arange(pack["n_rows"])
+    sec = dict(rows=0.0, nodes=0.0, halo=0.0)
+    for l in range(1, L):
+        if pack["bypass"]:
+            continue
+        t0 = time.perf_counter()
+        orc.lstm_last_hidden(pack["win"][l], omegas[l]["Wx"], omegas[l]["Wh"], omegas[l]["b"])
+        sec["nodes"] += time.perf_counter() - t0
+        if "hop" in pack:
+            hop = pack["hop"]
+            S = np.zeros((hop["n_local"] + hop["n_halo"], d_s), np.float32)
+            t0 = time.perf_counter()
+            orc.predictor_hop(hop, S, omegas[l]["Wg"])
+            sec["halo"] += time.perf_counter() - t0
+    if pack["gat"]:
+        from oracle import gat_oracle as gat
+        srng = np.random.default_rng(4321)
+        n_u = mini["n_halo"]
+        for l in range(L):
+            a_dst, a_src = gat_attn[l]
+            K, dl = a_dst.shape[0], dims[l + 1]
+            xs = pack["win"][l][-1] if (l >= 1 and not pack["bypass"]) else Hb[l][:pack["n_nodes"]]
+            t0 = time.perf_counter()                                   # transform and scores: per node
+            Zs = np.asarray(xs, np.float64) @ np.asarray(Ws[l], np.float64)
+            gat.gat_scores(Zs, a_dst, a_src)
+            np.asarray(xs, np.float64).T @ Zs                          # dW over local + halo rows
+            sec["nodes"] += (time.perf_counter() - t0) * (pack["n_nodes"] / max(1, len(xs)))
+            Z = srng.standard_normal((pack["n_rows"] + n_u, dl))       # stand-in values: only the time matters
+            el = srng.standard_normal((pack["n_rows"], K))
+            er = srng.standard_normal((pack["n_rows"] + n_u, K))
+            dOUT = srng.standard_normal((pack["n_rows"], dl))
+            t0 = time.perf_counter()                                   # the edge passes: per row
+            gat.gat_aggregate_fwd(mini, Z, el, er, 0.2, rows=ar)
+            gat.gat_aggregate_bwd(mini, Z, el, er, 0.2, dOUT, rows=ar)
+            if l >= 1:
+                dOUT @ np.asarray(Ws[l], np.float64).T                 # dH_in over the local rows
+            sec["rows"] += time.perf_counter() - t0
+        t0 = time.perf_counter()
+        orc.loss_and_grad(srng.standard_normal((pack["n_rows"], dims[L])), yy)
+        sec["rows"] += time.perf_counter() - t0
+    else:
+        t_rows = time.perf_counter()
+        aggs = []
+        for l in range(L):
+            a = orc.spmm_fwd_rows(mini, Hb[l], ar)
+            z, h = orc.dense_fwd(a, Ws[l], 1 if l < L - 1 else 0)
+            aggs.append((a, z, h))
+        _, g = orc.loss_and_grad(aggs[-1][2], yy)
+        for l in range(L - 1, -1, -1):
+            a, z, h = aggs[l]
+            dW, dA, _ = orc.dense_bwd(g[:, :dims[l + 1]], z, a, Ws[l], 1 if l < L - 1 else 0)
+            if l >= 1:
+                G = np.zeros((mini["n_halo"], dims[l]), np.float32)   # stand-in upstream gradient
+                G[pack["own"]] = dA
+                g = orc.spmm_bwd_rows(mini, G, ar)
+        sec["rows"] += time.perf_counter() - t_rows
+    return sec
+
+
+def host_cores():
+    """Cores this process may use: its affinity mask, capped by OMP_NUM_THREADS when the
+    environment sets it (a GPU machine gives one job a share of a larger machine)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:                                 # pragma: no cover
+        n = os.cpu_count() or 1
+    cap = os.environ.get("OMP_NUM_THREADS", "")
+    if cap.isdigit() and int(cap) > 0:
+        n = min(n, int(cap))
+    return max(1, n)
+
+
+def cpu_baseline_prepare(view, dims, tau, d_s, fetch, y, bypass, gat, sample_rows=65536,
+                         sample_nodes=524288, all_cores=True):
+    """Draws the samples and builds the packs: one for the one-core run and one per core for
+    the all-cores run. Done before the timed steps when the inputs only exist on the device
+    (the rows are read back while the tables still hold what was drawn)."""
+    import numpy as np
     n_l, n_h = view["n_local"], view["n_halo"]
     n_bar = n_l + n_h
     rng = np.random.default_rng(1234)
-    rows = np.sort(rng.choice(n_l, size=min(sample_rows, n_l), replace=False))
-    nodes = np.sort(rng.choice(n_bar, size=min(sample_nodes, n_bar), replace=False))
-    halo = np.sort(rng.choice(n_h, size=min(sample_rows, n_h), replace=False)) if n_h else None
-    f_rows, f_nodes = n_l / len(rows), n_bar / len(nodes)
-    f_halo = (n_h / len(halo)) if n_h else 0.0
 
-    def run():
-        est = 0.0
-        t_all = time.perf_counter()
-        Hbars = [X_host[table_ids][:, :dims[0]]]
-        for l in range(1, L):
-            Hbars.append(hist_host[l][-1][table_ids][:, :dims[l]])   # stand-in activations
-        prep = time.perf_counter() - t_all
-        for l in range(1, L):
-            if bypass:
-                continue
-            win = [hist_host[l][s][table_ids[nodes]][:, :dims[l]] for s in range(tau)]
-            t0 = time.perf_counter()
-            orc.lstm_last_hidden(win, omegas[l]["Wx"], omegas[l]["Wh"], omegas[l]["b"])
-            est += (time.perf_counter() - t0) * f_nodes
-            if n_h:
-                sub = dict(view, n_halo=len(halo),
-                           h_colptr=np.concatenate([[0], np.cumsum(
-                               view["h_colptr"][halo + 1] - view["h_colptr"][halo])]),
-                           h_row=np.concatenate([view["h_row"][view["h_colptr"][u]:view["h_colptr"][u + 1]]
-                                                 for u in halo]),
-                           h_val=np.concatenate([view["h_val"][view["h_colptr"][u]:view["h_colptr"][u + 1]]
-                                                 for u in halo]),
-                           h_self=view["h_self"][halo])
-                S = np.zeros((n_l + len(halo), d_s), np.float32)
-                t0 = time.perf_counter()
-                orc.predictor_hop(sub, S, omegas[l]["Wg"])
-                est += (time.perf_counter() - t0) * f_halo
-        if gat_attn is not None:
-            return est + run_gat(Hbars), prep
-        g = None
-        aggs = []
-        for l in range(L):
-            t0 = time.perf_counter()
-            a = orc.spmm_fwd_rows(view, Hbars[l], rows)
-            z, h = orc.dense_fwd(a, Ws[l], 1 if l < L - 1 else 0)
-            est += (time.perf_counter() - t0) * f_rows
-            aggs.append((a, z, h))
-        t0 = time.perf_counter()
-        _, g = orc.loss_and_grad(aggs[-1][2], y[rows])
-        est += (time.perf_counter() - t0) * f_rows
-        for l in range(L - 1, -1, -1):
-            a, z, h = aggs[l]
-            t0 = time.perf_counter()
-            dW, dA, _ = orc.dense_bwd(g[:, :dims[l + 1]], z, a, Ws[l], 1 if l < L - 1 else 0)
-            est += (time.perf_counter() - t0) * f_rows
-            if l >= 1:
-                dA_full = np.zeros((n_l, dims[l]), np.float32)      # stand-in upstream gradient
-                dA_full[rows] = dA
-                t0 = time.perf_counter()
-                g = orc.spmm_bwd_rows(view, dA_full, rows)
-                est += (time.perf_counter() - t0) * f_rows
-        return est, prep
-
-    def run_gat(Hbars):
-        """The attention backbone's calls: transform and scores on the node sample,
-        the edge passes on the row sample (stand-in values where a call needs the
-        rows of all nodes: only the time matters here)."""
-        from oracle import gat_oracle as gat
-        est = 0.0
-        srng = np.random.default_rng(4321)
-        for l in range(L):
-            a_dst, a_src = gat_attn[l]
-            K = a_dst.shape[0]
-            dl = dims[l + 1]
-            t0 = time.perf_counter()
-            Zs = Hbars[l][nodes].astype(np.float64) @ Ws[l].astype(np.float64)
-            gat.gat_scores(Zs, a_dst, a_src)
-            est += (time.perf_counter() - t0) * f_nodes
-            Zfull = srng.standard_normal((n_bar, dl)).astype(np.float32).astype(np.float64)
-            el = srng.standard_normal((n_l, K))
-            er = srng.standard_normal((n_bar, K))
-            dOUT = np.zeros((n_l, dl))
-            dOUT[rows] = srng.standard_normal((len(rows), dl))
-            t0 = time.perf_counter()
-            gat.gat_aggregate_fwd(view, Zfull, el, er, 0.2, rows=rows)
-            gat.gat_aggregate_bwd(view, Zfull, el, er, 0.2, dOUT, rows=rows)
-            est += (time.perf_counter() - t0) * f_rows
-            t0 = time.perf_counter()
-            Hbars[l][nodes].astype(np.float64).T @ Zs                       # dW over local + halo rows
-            est += (time.perf_counter() - t0) * f_nodes
-            if l >= 1:
-                t0 = time.perf_counter()
-                dOUT[rows] @ Ws[l].astype(np.float64).T                     # dH_in over the local rows
-                est += (time.perf_counter() - t0) * f_rows
-        t0 = time.perf_counter()
-        orc.loss_and_grad(srng.standard_normal((len(rows), dims[L])), y[rows])
-        est += (time.perf_counter() - t0) * f_rows
-        return est
+    def draw(k_rows, k_nodes):
+        rows = np.sort(rng.choice(n_l, size=min(k_rows, n_l), replace=False))
+        nodes = np.sort(rng.choice(n_bar, size=min(k_nodes, n_bar), replace=False))
+        halo = np.sort(rng.choice(n_h, size=min(k_rows, n_h), replace=False)) if n_h else None
+        return _build_pack(view, dims, tau, d_s, fetch, y, rows, nodes, halo, bypass, gat)
 
     t0 = time.time()
-    if threadpool_limits is not None:
-        with threadpool_limits(limits=1):
-            est, prep = run()
-        cores = 1
-    else:
-        est, prep = run()
-        cores = os.cpu_count() or 1
-    log("cpu oracle: estimated %.1f s per step on %d core(s) (sample run took %.1fs)" % (
-        est, cores, time.time() - t0))
-    return {"value": round(edges / est / 1e9, 6), "unit": "GTEPS", "cores": cores,
-            "kind": "oracle",
-            "sample": "%d of %d local rows per aggregation/transform call, %d of %d nodes for the "
-                      "predictor LSTM, %d of %d halo rows for its hop; each call's time scaled by "
-                      "rows_total/rows_sampled; estimated %.1f s per step" % (
-                          len(rows), n_l, len(nodes), n_bar, 0 if halo is None else len(halo),
-                          n_h, est)}
+    prep = dict(one=draw(sample_rows, sample_nodes), many=[], totals=dict(rows=n_l, nodes=n_bar, halo=n_h))
+    cores = host_cores()
+    if all_cores and cores > 1:
+        per_rows, per_nodes = max(256, sample_rows // (4 * cores)), max(2048, sample_nodes // (4 * cores))
+        prep["many"] = [draw(per_rows, per_nodes) for _ in range(cores)]
+    prep["build_s"] = time.time() - t0
+    return prep
+
+
+def cpu_baseline_run(prep, Ws, omegas, gat_attn, edges, log):
+    """Times the oracle (as it stands) twice on row samples of every call of the step: on
+    ONE core (one pack, BLAS held to one thread) and on ALL host cores (one pack per core,
+    each in a worker process of its own started as a fresh interpreter, BLAS held to one
+    thread per worker; the wall time of a class of calls is that of the slowest worker).
+    Every call's time is scaled by rows_total / rows_sampled."""
+    tot = prep["totals"]
+
+    def estimate(sec, pack, shards):
+        got = {"rows": pack["n_rows"], "nodes": pack["n_nodes"], "halo": pack["n_halo"]}
+        return sum(sec[c] * tot[c] / (got[c] * shards) for c in sec if got[c])
+
+    pack = prep["one"]
+    sec1 = _oracle_pack_seconds((pack, Ws, omegas, gat_attn, 1))
+    est1 = estimate(sec1, pack, 1)
+    log("cpu oracle: estimated %.1f s per step on 1 core (samples built in %.1fs, run in %.1fs)" % (
+        est1, prep["build_s"], sum(sec1.values())))
+    out = {"value": round(edges / est1 / 1e9, 6), "unit": "GTEPS", "cores": 1, "kind": "oracle",
+           "sample": "%d of %d local rows per aggregation/transform call, %d of %d nodes for the "
+                     "predictor LSTM, %d of %d halo rows for its hop; each call's time scaled by "
+                     "rows_total/rows_sampled; estimated %.1f s per step" % (
+                         pack["n_rows"], tot["rows"], pack["n_nodes"], tot["nodes"], pack["n_halo"],
+                         tot["halo"], est1)}
+    packs = prep["many"]
+    if packs:
+        import multiprocessing as mp
+        from concurrent.futures import ProcessPoolExecutor
+        t0 = time.time()
+        cores = len(packs)
+        ctx = mp.get_context("spawn")          # fresh interpreters: the workers never see the GPU
+        try:                                   # (a worker that dies breaks the pool: no endless respawn)
+            with ProcessPoolExecutor(max_workers=cores, mp_context=ctx) as pool:
+                futs = [pool.submit(_oracle_pack_seconds, (p, Ws, omegas, gat_attn, 1)) for p in packs]
+                secs = [f.result(timeout=600) for f in futs]
+        except Exception as e:                 # noqa: BLE001 - the one-core figure still stands
+            log("cpu oracle on all cores failed: %s: %s" % (type(e).__name__, e))
+            out["all_cores"] = {"error": "%s: %s" % (type(e).__name__, e)}
+            return out
+        worst = {c: max(sk[c] for sk in secs) for c in secs[0]}
+        estN = estimate(worst, packs[0], cores)
+        log("cpu oracle: estimated %.1f s per step on %d cores (%d worker processes, %.1fs in all)" % (
+            estN, cores, cores, time.time() - t0))
+        out["all_cores"] = {
+            "value": round(edges / estN / 1e9, 6), "unit": "GTEPS", "cores": cores, "kind": "oracle",
+            "sample": "%d worker processes, each %d local rows, %d nodes and %d halo rows of its own; a "
+                      "class of calls takes the slowest worker's time, scaled by rows_total/(rows per "
+                      "worker x workers); estimated %.1f s per step" % (
+                          cores, packs[0]["n_rows"], packs[0]["n_nodes"], packs[0]["n_halo"], estN)}
+    return out
 
 
 if __name__ == "__main__":
