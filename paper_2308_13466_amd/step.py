@@ -91,6 +91,12 @@ class PartitionStep:
           history tables and Ws (dW, the loss and the predictor parameters are fp32).
     predictors: predictors[l] a binding.Predictor for l = 1..L-1 (None: bypass).
     y: device int32 [n_local] labels.
+    predict_ahead: the predictions of step t + 1 only need the ring as step t's pushes leave
+          it, and nothing in step t's backward reads the halo rows they write: with this
+          flag they are enqueued on a second stream (same priority) right after step t's
+          last push, beside step t's loss and backward, and step t + 1 waits for them before
+          its first use of a predicted row and before its first push into a slot they read.
+          Results are identical to the sequential order. Dense ring, fused pull only.
     predict_every: Delta T of Alg. 1 - the predicted halo rows are refreshed on steps
           t = 0, Delta T, 2 Delta T, ... and reused (they stay in the halo rows of Hbar_l) in between.
     grad_tables: None, or grad_tables[l] for l = 1..L-1 a pair [table_a, table_b] of
@@ -106,8 +112,9 @@ class PartitionStep:
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
                  fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1,
-                 coded=None):
+                 coded=None, predict_ahead=False):
         dev = X_table.device
+        self.predict_ahead = bool(predict_ahead)
         self.dtype = dtype
         self.dims = list(dims)
         self.L = len(dims) - 1
@@ -163,6 +170,12 @@ class PartitionStep:
             ws_bytes.append(B.history_compress_workspace_bytes(n_l))
         self.ws_bytes = max(ws_bytes + [256])
         self.ws = torch.empty((self.ws_bytes + 3) // 4, **f32)
+        self._side = None
+        if self.predict_ahead:
+            assert coded is None and self.fused_pull, "predict_ahead goes with the dense ring and the fused pull"
+            self._side = torch.cuda.Stream(device=dev)          # default priority
+            self._ws_side = torch.empty((self.ws_bytes + 3) // 4, **f32)   # the predictor's own scratch
+            self._pred_done = None      # event: predictions for step self.t are in place
         if not fused_pull and L >= 2:
             # dense rows of one layer's window, shared by the hidden layers (a layer's pull
             # and prediction are over before the next layer's pull starts)
@@ -192,6 +205,8 @@ class PartitionStep:
         st = self._stream()
         dt = self.dtype
         order = self.slot_order()
+        if self.predict_ahead:
+            return self._forward_backward_predict_ahead(st)
         # 1. predicted halo embeddings of every hidden layer (every Delta T steps)
         for l in range(1, L if self.t % self.predict_every == 0 else 1):
             w = self.predictors[l]
@@ -237,7 +252,13 @@ class PartitionStep:
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
                     self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))
-        # 3. loss gradient and backward
+        self._backward(st)
+        self.t += 1
+
+    def _backward(self, st):
+        """3. loss gradient and backward."""
+        L, dims, ld, n_l, n_h = self.L, self.dims, self.ld, self.n_local, self.n_halo
+        dt = self.dtype
         self._timed("loss_grad", lambda: B.loss_grad(
             self.logits, ld[L], n_l, dims[L], self.y, self.dH[L], ld[L], loss=self.loss, dtype=dt,
             workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
@@ -265,6 +286,59 @@ class PartitionStep:
                 self._timed("grad_pull_l%d" % l, lambda: B.history_gather_add(
                     rd, rd.shape[0], rd.shape[1], self.local_table_ids, n_l, dims[l],
                     self.dH[l], ld[l], dtype=dt, stream=st))
+
+    # ------------------------------------------------ predictions one step ahead
+    def _enqueue_predictions(self, t):
+        """Predictions for step t on the side stream, after everything the main stream has
+        enqueued so far (the pushes that complete the ring as of the end of step t - 1)."""
+        main = torch.cuda.current_stream()
+        self._side.wait_stream(main)
+        if t % self.predict_every == 0:
+            order = [(t + s) % self.tau for s in range(self.tau)]
+            with torch.cuda.stream(self._side):
+                sp = self._side.cuda_stream
+                for l in range(1, self.L):
+                    slots = [self.hist[l][s] for s in order]
+                    n_rows, ld_t = slots[0].shape
+                    self._timed("predict_l%d" % l, lambda: B.predict(
+                        self.pv, self.predictors[l], slots, n_rows, ld_t, self.table_ids,
+                        self.Hbar[l], self.ld[l], dtype=self.dtype, workspace=self._ws_side,
+                        workspace_bytes=self.ws_bytes, stream=sp))
+        self._pred_done = torch.cuda.Event()
+        self._pred_done.record(self._side)
+
+    def _forward_backward_predict_ahead(self, st):
+        L, dims, ld, n_l, n_h = self.L, self.dims, self.ld, self.n_local, self.n_halo
+        dt = self.dtype
+        main = torch.cuda.current_stream()
+        if self._pred_done is None:             # first step: nothing was enqueued ahead
+            self._enqueue_predictions(self.t)
+        w_slot = self.t % self.tau
+        for l in range(L):
+            if l == 0 and n_h > 0:
+                halo0 = self.Hbar[0][n_l:]
+                self._timed("gather_l0", lambda: B.history_gather(
+                    self.X_table, self.X_table.shape[0], self.X_table.shape[1],
+                    self.halo_table_ids, n_h, dims[0], halo0, ld[0], dtype=dt, stream=st))
+            self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
+                self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], dtype=dt, stream=st))
+            last = l == L - 1
+            out = self.logits if last else self.Hbar[l + 1]
+            self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
+                self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
+                B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], dtype=dt, stream=st))
+            if l == 0:
+                # the first push overwrites a slot the predictions read, and the next layer
+                # reads predicted rows: both wait here (layer 0 itself needs neither)
+                main.wait_event(self._pred_done)
+            if not last:
+                tab = self.hist[l + 1][w_slot]
+                self._timed("push_l%d" % (l + 1), lambda: B.history_push(
+                    tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
+                    self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))
+        # the ring is complete for step t + 1: its predictions run beside this step's backward
+        self._enqueue_predictions(self.t + 1)
+        self._backward(st)
         self.t += 1
 
     # ------------------------------------------------------------ coded ring

@@ -36,7 +36,7 @@ def _upload(a, bf16, dev):
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
                    keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
-                   backbone="gcn", coded_ring=None, own_headroom=1.5):
+                   backbone="gcn", coded_ring=None, own_headroom=1.5, predict_ahead=False):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
@@ -169,7 +169,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     else:
         step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
                              fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
-                             grad_tables=gt, predict_every=predict_every, coded=coded)
+                             grad_tables=gt, predict_every=predict_every, coded=coded,
+                             predict_ahead=predict_ahead)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))

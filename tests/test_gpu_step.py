@@ -290,3 +290,28 @@ def test_step_replayed_from_a_hip_graph_matches_eager_steps(coded_ring):
             assert torch.equal(graphed.Hbar[l], eager.Hbar[l]), (rep, l)
     assert graphed.coded_overflow() == []
     assert float(scratch[0].item()) == 4.0
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium"])
+def test_predictions_one_step_ahead_change_nothing(name):
+    """predict_ahead only moves the predictor's calls to a second stream, beside the previous
+    step's backward: every buffer of three steps must equal, bit for bit, what the in-step
+    order leaves (same kernels, same inputs, fixed-order reductions)."""
+    import torch
+    from paper_2308_13466_amd.workload import build_workload
+    print("[case] predictions one step ahead, %s" % name, flush=True)
+    runs = []
+    for ahead in (False, True):
+        wl = build_workload(name, predict_ahead=ahead)
+        for _ in range(3):
+            wl.step.forward_backward()
+        torch.cuda.synchronize()
+        st = wl.step
+        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
+        keep += [h.clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
+        keep += [t.clone() for l in range(1, st.L) for t in st.hist[l]]
+        runs.append(keep)
+        del wl, st
+    for a, b in zip(*runs):
+        assert a.dtype == b.dtype and torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                                                  b.view(torch.int32) if b.dtype == torch.float32 else b)
