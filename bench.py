@@ -131,9 +131,16 @@ def main():
                     help="rewrite a 1 GiB buffer before every library call, so that no call finds "
                          "its inputs in the caches (for the workloads whose working set fits "
                          "them); ms_per_step is then the sum of the calls' own times")
-    ap.add_argument("--predict-ahead", action="store_true",
-                    help="enqueue the predictions of step t + 1 on a second stream beside step t's "
-                         "backward (they only need the ring as step t's pushes leave it)")
+    ap.add_argument("--no-predict-ahead", action="store_true",
+                    help="run the predictor's calls inside the step. By default (GCN backbone, dense "
+                         "ring, fused pull) the predictions of step t + 1 are enqueued on a second "
+                         "stream beside step t's backward: they only need the ring as step t's pushes "
+                         "leave it; the results are bit-identical")
+    ap.add_argument("--no-transform-first", action="store_true",
+                    help="evaluate the last layer as (P Hbar) W like the others. By default it is "
+                         "evaluated as P (Hbar W) when it narrows to half the width or less (the "
+                         "appendix's Z = P H W fixes no order): the aggregation and its transpose then "
+                         "gather rows of n_classes elements")
     ap.add_argument("--no-scale-leg", action="store_true",
                     help="do not append the full Scale configuration (bf16; run by a child process "
                          "after the headline workload has been timed) under the key \"scale\"")
@@ -165,12 +172,16 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    predict_ahead = not (args.no_predict_ahead or args.backbone != "gcn" or args.coded_ring is not None
+                         or args.unfused_pull or args.graph or args.cold or args.bypass)
+    gat_flag = args.backbone == "gat"
     flush = torch.zeros(1 << 28, dtype=torch.float32, device=dev) if args.cold else None
     timers = CallTimers(torch, flush)
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
                         predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring,
-                        predict_ahead=args.predict_ahead)
+                        predict_ahead=predict_ahead,
+                        transform_first=False if (args.no_transform_first or gat_flag) else "auto")
     gat = args.backbone == "gat"
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
@@ -272,10 +283,22 @@ def main():
         c["ms"] += calls[name]["total_ms"]
         c["launches"] += calls[name]["launches"]
 
+    tf = bool(getattr(step, "transform_first", False))
     for l in range(L):
-        add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]),
-            spmm_compulsory(nnz, n_l, n_bar, dims[l]))
-        if l >= 1:
+        if tf and l == L - 1:
+            # last layer as P (Hbar W): transform over all rows, both aggregations at n_classes
+            # columns, the transpose one over local and halo entries (dW needs P_out^T dH too)
+            C = dims[L]
+            add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, C), spmm_compulsory(nnz, n_l, n_bar, C))
+            add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, C) + spmm_bytes(nnz_halo, n_h, C),
+                spmm_compulsory(nnz_loc, n_l, n_l, C) + spmm_compulsory(nnz_halo, n_h, n_l, C))
+            add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * C)
+            add("dense_bwd", "dense_bwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * C)
+            add("dense_bwd", "dense_bwd_in_l%d" % l, "mfma", 2.0 * n_l * dims[l] * C)
+        else:
+            add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]),
+                spmm_compulsory(nnz, n_l, n_bar, dims[l]))
+        if l >= 1 and not (tf and l == L - 1):
             add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]) + (
                 spmm_bytes(nnz_halo, n_h, dims[l]) if args.stale_grad else 0),
                 spmm_compulsory(nnz_loc, n_l, n_l, dims[l]) + (
@@ -294,7 +317,7 @@ def main():
                 + nnz * (4 + 16 * K + dl * s) + n_bar * (8 + 2 * dl * s + 8 * K)  # source side
                 + (3 * n_l * dl * s if l < L - 1 else 0)                          # masked gradient
                 + n_bar * (dl * s + 4 * K) + n_l * 4 * K)                         # attention vectors
-        else:
+        elif not (tf and l == L - 1):
             add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dims[l + 1])
             add("dense_bwd", "dense_bwd_l%d" % l, "mfma",
                 (4.0 if l >= 1 else 2.0) * n_l * dims[l] * dims[l + 1])
@@ -495,7 +518,8 @@ def main():
                    "predictor": "bypass" if args.bypass else (
                        "every step" if args.delta_t <= 1 else "every %d steps" % args.delta_t),
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
-                   "predictions": "one step ahead, on a second stream" if args.predict_ahead else "in the step",
+                   "predictions": "one step ahead, on a second stream" if predict_ahead else "in the step",
+                   "last_layer": "P (Hbar W)" if tf else "(P Hbar) W",
                    "stale_gradient_term": bool(args.stale_grad),
                    "history_ring": "dense" if args.coded_ring is None else "coded, %d decimals" % args.coded_ring,
                    "caches": "flushed before every call" if args.cold else "as the step leaves them",
@@ -520,7 +544,7 @@ def main():
     # whatever happens to the child, the line below is printed
     plain = (not gat and args.coded_ring is None and not args.cold and not args.pmc_calibration
              and not args.stale_grad and not args.bypass and not args.predictor_train
-             and args.codec is None and not args.graph and args.dtype is None and not args.predict_ahead)
+             and args.codec is None and not args.graph and args.dtype is None and not args.no_predict_ahead)
     if args.workload == "large" and not args.no_scale_leg and plain:
         import gc
         del wl, step, timers, cpu_prep

@@ -15,3 +15,4 @@ from .binding import (  # noqa: F401
     F32, BF16, ACT_IDENTITY,
     ACT_RELU,
 )
+from .minibatch import minibatch_view  # noqa: F401

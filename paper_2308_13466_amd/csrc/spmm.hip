@@ -26,6 +26,9 @@
 //   * entries whose column id is outside the operand (the halo columns, when
 //     the transpose product P_in^T walks only local columns) are squeezed out
 //     of each 64-entry chunk before the ring sees them.
+// spmm_slot_kernel: the same split for rows of at most 256 bytes, several entries per
+//   gather instruction (a group of lanes per row), because there the wavefront's per-entry
+//   bookkeeping, not memory, is what one entry per instruction waits for.
 // spmm_group_kernel: rows of a handful of entries and narrow features (the
 //   transposed halo block of the predictor's hop): a group of G lanes per row,
 //   64/G rows per wavefront, because there the number of independent rows in
@@ -83,6 +86,12 @@ struct Piece {
   __device__ __forceinline__ void fma(float s, const Piece& x) {
 #pragma unroll
     for (int k = 0; k < NQ; ++k) q[k] += s * x.q[k];
+  }
+  __device__ __forceinline__ void keep_if(bool keep) {   // per lane: zero unless keep
+#pragma unroll
+    for (int k = 0; k < NQ; ++k)
+#pragma unroll
+      for (int i = 0; i < NW; ++i) q[k][i] = keep ? q[k][i] : 0.f;
   }
   __device__ __forceinline__ void add(const Piece& x) {
 #pragma unroll
@@ -399,6 +408,252 @@ __global__ __launch_bounds__(kWaves * kWave) void spmm_stream_kernel(SpmmArgs a)
   }
 }
 
+// Rows of at most 512 bytes: the same entry-balanced split of a workgroup's span into eight
+// pieces, but the stream is consumed a SLOT at a time: a group of G lanes (16 bytes per
+// lane) covers one feature row, so one gather instruction fetches the rows of 64 / G
+// consecutive entries, each group with its own entry's column id, weight and stream position
+// (cross-lane reads of the 64-entry index chunk). With one entry per instruction the
+// wavefront's per-entry bookkeeping - three cross-lane reads into scalar registers, the
+// scalar address, the row-end compare - is what short rows wait for (the counters show few
+// requests in flight and no translation misses); here it is paid once per slot. A lane
+// accumulates its group's entries; when a row ends the groups' partial sums are added across
+// the wavefront and group 0 stores the row. A row that ends inside a slot is handled by
+// weight masks: entries at or past the row's end are held back until the row has been
+// stored. Everything else (pieces, rows cut by piece boundaries, the squeeze of out-of-range
+// columns, two-level sums) is as in spmm_stream_kernel.
+template <int ES, int G, int U>
+__global__ __launch_bounds__(kWaves * kWave) void spmm_slot_kernel(SpmmArgs a) {
+  typedef Chunk<ES> P;
+  constexpr int EPL = P::N;                 // elements per lane
+  constexpr int EPI = kWave / G;            // entries per gather instruction
+  constexpr int kRowElems = G * EPL;        // elements of a row one pass covers
+  __shared__ int64_t rp[kMaxRowsPerBlock + 1];
+  __shared__ int32_t head_row[kWaves], head_closed[kWaves], tail_row[kWaves];
+  __shared__ __attribute__((aligned(16))) float part[kWaves][2][kRowElems];
+
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int gl = lane % G, grp = lane / G;
+  const int big = a.rows_per_block, nbig = a.n_big_blocks;
+  const int bid = blockIdx.x;
+  const int R = bid < nbig ? big : big / 4;
+  const int64_t row0 = bid < nbig ? static_cast<int64_t>(bid) * big
+                                  : static_cast<int64_t>(nbig) * big + static_cast<int64_t>(bid - nbig) * R;
+  const int nr = static_cast<int>(a.n_rows - row0 < R ? a.n_rows - row0 : R);
+
+  for (int t = threadIdx.x; t <= nr; t += kWaves * kWave) rp[t] = a.rowptr[row0 + t];
+  if (threadIdx.x < kWaves) {
+    head_row[threadIdx.x] = -1;
+    head_closed[threadIdx.x] = 0;
+    tail_row[threadIdx.x] = -1;
+  }
+  __syncthreads();
+
+  const int el0 = gl * EPL;                 // this lane's elements of a row
+  const bool el_ok = el0 < a.d;
+
+  auto store_row = [&](int r, P& sum) {     // final value of local row r; group 0 holds it
+    if (grp != 0 || !el_ok) return;
+    const int64_t row = row0 + r;
+    if (a.self_val != nullptr) {
+      P x;
+      x.load(a.X + (a.self_off + row) * a.ld_x + static_cast<int64_t>(el0) * ES);
+      sum.fma(a.self_val[row], x);
+    }
+    sum.store(a.Y + row * a.ld_y + static_cast<int64_t>(el0) * ES, a.d - el0);
+  };
+  auto across_groups = [&](P& x) {          // every lane ends up with the sum over the groups
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1) x.xor_add(off);
+  };
+
+  const int64_t e0 = rp[0];
+  const int32_t total = static_cast<int32_t>(rp[nr] - e0);   // < 2^31: checked by the host
+  const int32_t per = ((total + kWaves - 1) / kWaves + kWave - 1) / kWave * kWave;
+  const int32_t ps = wave * per;                                  // offsets relative to e0
+  const int32_t pe = ps + per < total ? ps + per : total;
+
+  if (wave == 0 || ps < total) {
+    int cur = 0;
+    if (wave != 0)
+      for (int k0 = 0; k0 < nr; k0 += kWave) {
+        const int k = k0 + lane;
+        cur += __builtin_popcountll(__ballot(k < nr && static_cast<int32_t>(rp[k + 1] - e0) <= ps));
+      }
+    cur = __builtin_amdgcn_readfirstlane(cur);
+    const int first = cur;
+    const bool head_partial =
+        __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur < nr ? cur : nr] - e0)) < ps;
+    int32_t cur_end =
+        cur < nr ? __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur + 1] - e0)) : kEnd;
+
+    P acc, tot;
+    acc.zero();
+    tot.zero();
+    int rounds = 0;
+
+    auto flush = [&]() {   // row `cur` ends inside this piece
+      acc.add(tot);
+      across_groups(acc);
+      if (cur == first && head_partial) {
+        if (grp == 0) acc.to_lds(&part[wave][0][el0]);
+        if (lane == 0) {
+          head_row[wave] = cur;
+          head_closed[wave] = 1;
+        }
+      } else {
+        store_row(cur, acc);
+      }
+      acc.zero();
+      tot.zero();
+      ++cur;
+      cur_end = cur < nr ? __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur + 1] - e0)) : kEnd;
+    };
+
+    // ---- index chunks, exactly as in spmm_stream_kernel
+    int32_t c = 0, p = 0, rc = 0;
+    float v = 0.f, rv = 0.f;
+    int cnt = 0, idx = 0;
+    int32_t raw_base = ps;
+    bool has_raw = ps < pe;
+    auto load_raw = [&]() {
+      const int32_t o = raw_base + lane;
+      rc = -1;
+      rv = 0.f;
+      if (o < pe) {
+        rc = a.col[e0 + o];
+        rv = a.val[e0 + o];
+      }
+    };
+    if (has_raw) load_raw();
+    auto shift = [&]() {
+      const bool ok = static_cast<uint32_t>(rc) < static_cast<uint64_t>(a.n_x_rows);
+      const uint64_t mask = __ballot(ok);
+      cnt = __builtin_popcountll(mask);
+      const int32_t o = raw_base + lane;
+      const int n_raw = pe - raw_base < kWave ? pe - raw_base : kWave;
+      if (cnt == n_raw) {
+        c = rc;
+        v = rv;
+        p = o;
+      } else {
+        const int below = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0));
+        const int dest = (ok ? below : cnt + (lane - below)) << 2;
+        c = __builtin_amdgcn_ds_permute(dest, rc);
+        v = __builtin_bit_cast(float, __builtin_amdgcn_ds_permute(dest, __builtin_bit_cast(int, rv)));
+        p = __builtin_amdgcn_ds_permute(dest, o);
+      }
+      idx = 0;
+      raw_base += kWave;
+      has_raw = raw_base < pe;
+      if (has_raw) load_raw();
+    };
+
+    // ---- ring of U slots: per lane the raw words of its group's row, the entry's weight and
+    // stream position; per slot (scalar) the position of its last entry
+    typename P::W x[U];
+    float wv[U];
+    int32_t wp[U];
+    int32_t slast[U];
+    auto fetch = [&](int u) {
+      while (idx >= cnt) {
+        if (!has_raw) {
+          slast[u] = kEnd;
+          return;
+        }
+        shift();
+      }
+      // entry of this lane's group; groups past the chunk's last entry re-read that entry's
+      // row with weight 0
+      const int e = idx + grp;
+      const int ec = e < cnt ? e : cnt - 1;
+      const int32_t cj = __builtin_amdgcn_ds_bpermute(ec << 2, c);
+      const float vj = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(ec << 2, __builtin_bit_cast(int, v)));
+      wp[u] = __builtin_amdgcn_ds_bpermute(ec << 2, p);
+      wv[u] = e < cnt ? vj : 0.f;
+      const int last = idx + EPI < cnt ? idx + EPI : cnt;
+      slast[u] = rl(p, last - 1);
+      idx += EPI;
+      if (el_ok)
+        x[u] = P::load_raw(a.X + static_cast<int64_t>(cj) * a.ld_x + static_cast<int64_t>(el0) * ES);
+      else
+        x[u] = typename P::W(0u);
+    };
+#pragma unroll
+    for (int u = 0; u < U; ++u) fetch(u);
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (slast[u] == kEnd) {
+          more = false;
+          break;
+        }
+        P xw;
+        xw.widen(x[u]);
+        if (slast[u] < cur_end) {
+          // the whole slot lies inside row `cur` (rows that ended before it were stored when the
+          // slot that held their last entry was consumed, or are stored right below)
+          acc.fma(wv[u], xw);
+        } else {
+          // a row ends inside the slot, or ended exactly before it: entries are applied row by
+          // row, selected by their stream position. The rows of the other entries are masked
+          // out, not multiplied by zero: a non-finite value must not leak into a row that does
+          // not reference it.
+          int32_t lo = -kEnd;
+          while (true) {
+            P xm = xw;
+            xm.keep_if(wp[u] >= lo && wp[u] < cur_end);
+            acc.fma(wv[u], xm);
+            if (slast[u] < cur_end) break;
+            lo = cur_end;
+            flush();
+          }
+        }
+        fetch(u);
+      }
+      if (++rounds == kFold / U) {
+        rounds = 0;
+        tot.add(acc);
+        acc.zero();
+      }
+    }
+    // rows that end inside this piece after its last entry (trailing skipped entries, empty rows)
+    while (cur < nr && cur_end <= pe) flush();
+    // a row that continues into the next piece
+    if (cur < nr && __builtin_amdgcn_readfirstlane(static_cast<int32_t>(rp[cur] - e0)) < pe) {
+      const int slot = (cur == first && head_partial) ? 0 : 1;
+      acc.add(tot);
+      across_groups(acc);
+      if (grp == 0) acc.to_lds(&part[wave][slot][el0]);
+      if (lane == 0) {
+        if (slot == 0)
+          head_row[wave] = cur;   // the whole piece lies inside one row; head_closed stays 0
+        else
+          tail_row[wave] = cur;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- rows cut by piece boundaries, added in piece order by the wavefront the row ended in
+  if (head_row[wave] >= 0 && head_closed[wave]) {
+    int ws = -1;
+    for (int k = 0; k < wave; ++k)
+      if (tail_row[k] >= 0) ws = k;
+    if (ws >= 0 && grp == 0) {
+      P sum, other;
+      sum.from_lds(&part[ws][1][el0]);
+      for (int k = ws + 1; k <= wave; ++k) {
+        other.from_lds(&part[k][0][el0]);
+        sum.add(other);
+      }
+      store_row(head_row[wave], sum);
+    }
+  }
+}
+
 // acc += sum over entries [s, e) of val * X[col]; all lanes of the wavefront take part
 // (64/G entries at a time). Lane (grp, gl) handles 16-byte chunk gl of the feature row.
 template <int ES, int G, int U>
@@ -613,8 +868,18 @@ static sat_status launch_spmm_es(SpmmArgs a, int64_t total_entries, hipStream_t 
                     static_cast<unsigned>((row_bytes + per_pass - 1) / per_pass));            \
     spmm_stream_kernel<ES, NW, NCH, U><<<grid, block, 0, stream>>>(a);                        \
   } while (0)
-  if (row_bytes <= 256) SAT_SPMM_LAUNCH(1, 1, 16);
-  else if (row_bytes <= 512) SAT_SPMM_LAUNCH(2, 1, 16);
+  // Rows up to 256 bytes: four or eight entries per gather instruction (22 G rows/s against
+  // 14 with one entry per instruction on 256-byte rows). From 257 bytes on a row fills two
+  // or more cache lines per entry and the one-entry kernel already runs at the memory
+  // system's rate (with two entries per instruction it was measured slower on 400-byte rows,
+  // 1.72 against 1.21 ms, and the same on 512-byte rows).
+  if (row_bytes <= 256) {
+    const dim3 grid(static_cast<unsigned>(bx));
+    if (row_bytes <= 128) spmm_slot_kernel<ES, 8, 8><<<grid, block, 0, stream>>>(a);
+    else spmm_slot_kernel<ES, 16, 8><<<grid, block, 0, stream>>>(a);
+    return sat::check_launch();
+  }
+  if (row_bytes <= 512) SAT_SPMM_LAUNCH(2, 1, 16);
   else if (row_bytes <= 1024) SAT_SPMM_LAUNCH(4, 1, 16);
   else if (row_bytes <= 2048 || ES == 2) SAT_SPMM_LAUNCH(4, 2, 8);
   else if constexpr (ES == 4) {   // fp32 partial sums of wider bf16 rows would not fit LDS: more passes

@@ -97,6 +97,14 @@ class PartitionStep:
           last push, beside step t's loss and backward, and step t + 1 waits for them before
           its first use of a predicted row and before its first push into a slot they read.
           Results are identical to the sequential order. Dense ring, fused pull only.
+    transform_first: the appendix writes a layer as Z = P H W without saying which product
+          comes first. The last layer has no activation between the two and usually narrows
+          (256 -> 47 classes), so with this flag it is evaluated as P (Hbar W): the transform
+          runs over all local + halo rows, and the aggregation and its transpose then gather
+          rows of n_classes instead of d_{L-1} elements. Backward accordingly: G = [P_in |
+          P_out]^T dH^(L) (local and halo rows), dW = Hbar^T G over all rows, dH^(L-1) =
+          G_local W^T. AGG_{L-1} and dAGG_{L-1} are then never formed. "auto": when the last
+          layer narrows to half or less. Not with gradient tables.
     predict_every: Delta T of Alg. 1 - the predicted halo rows are refreshed on steps
           t = 0, Delta T, 2 Delta T, ... and reused (they stay in the halo rows of Hbar_l) in between.
     grad_tables: None, or grad_tables[l] for l = 1..L-1 a pair [table_a, table_b] of
@@ -112,9 +120,13 @@ class PartitionStep:
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
                  fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1,
-                 coded=None, predict_ahead=False):
+                 coded=None, predict_ahead=False, transform_first=False):
         dev = X_table.device
         self.predict_ahead = bool(predict_ahead)
+        L_ = len(dims) - 1
+        if transform_first == "auto":     # worth it when the last layer narrows to half or less
+            transform_first = 2 * dims[L_] <= dims[L_ - 1]
+        self.transform_first = bool(transform_first) and grad_tables is None
         self.dtype = dtype
         self.dims = list(dims)
         self.L = len(dims) - 1
@@ -150,9 +162,15 @@ class PartitionStep:
         self.ld_w = [Ws[l].shape[1] for l in range(L)]
         self.Hbar = [torch.zeros((n_bar, self.ld[l]), **act) for l in range(L)]
         self.logits = torch.zeros((n_l, self.ld[L]), **act)
-        self.AGG = [torch.zeros((n_l, self.ld[l]), **act) for l in range(L)]
+        tf = self.transform_first
+        self.AGG = [torch.zeros((n_l, self.ld[l]), **act) if not (tf and l == L - 1) else None
+                    for l in range(L)]
         self.dH = [torch.zeros((n_l, self.ld[l]), **act) if l >= 1 else None for l in range(L + 1)]
-        self.dAGG = [torch.zeros((n_l, self.ld[l]), **act) if l >= 1 else None for l in range(L)]
+        self.dAGG = [torch.zeros((n_l, self.ld[l]), **act) if l >= 1 and not (tf and l == L - 1) else None
+                     for l in range(L)]
+        # transform first: Zbar = Hbar_{L-1} W over all rows, G = P^T dH^(L) over all rows
+        self.Zbar = torch.zeros((n_bar, self.ld[L]), **act) if tf else None
+        self.G = torch.zeros((n_bar, self.ld[L]), **act) if tf else None
         self.ld_dw = [_ld(dims[l + 1], 4) for l in range(L)]
         self.dW = [torch.zeros((dims[l], self.ld_dw[l]), **f32) for l in range(L)]   # always fp32
         self.dH_halo = [None] * L
@@ -161,7 +179,8 @@ class PartitionStep:
                             for l in range(L)]
         self.loss = torch.zeros(1, **f32)
         ws_bytes = [B.loss_workspace_bytes(n_l)]
-        ws_bytes += [B.dense_bwd_workspace_bytes(n_l, dims[l], dims[l + 1]) for l in range(L)]
+        ws_bytes += [B.dense_bwd_workspace_bytes(n_bar if (tf and l == L - 1) else n_l, dims[l], dims[l + 1])
+                     for l in range(L)]
         for l in range(1, L):
             if not predictors[l].bypass:
                 ws_bytes.append(B.predict_workspace_bytes(n_l, self.n_halo, dims[l],
@@ -238,13 +257,8 @@ class PartitionStep:
                 self._timed("gather_l0", lambda: B.history_gather(
                     self.X_table, self.X_table.shape[0], self.X_table.shape[1],
                     self.halo_table_ids, n_h, dims[0], halo0, ld[0], dtype=dt, stream=st))
-            self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
-                self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], dtype=dt, stream=st))
+            self._layer_forward(l, st)
             last = l == L - 1
-            out = self.logits if last else self.Hbar[l + 1]
-            self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
-                self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
-                B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], dtype=dt, stream=st))
             if not last and self.coded is not None:
                 self._push_coded(l + 1, w_slot, st)
             elif not last:
@@ -255,8 +269,28 @@ class PartitionStep:
         self._backward(st)
         self.t += 1
 
-    def _backward(self, st):
-        """3. loss gradient and backward."""
+    def _layer_forward(self, l, st):
+        """AGG_l = [P_in | P_out] Hbar_l, H_{l+1} = act(AGG_l W_l); on the last layer with
+        transform_first: Zbar = Hbar_l W_l over all rows, logits = [P_in | P_out] Zbar."""
+        L, dims, ld, n_l, n_bar, dt = self.L, self.dims, self.ld, self.n_local, self.n_bar, self.dtype
+        last = l == L - 1
+        if last and self.transform_first:
+            self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
+                self.Hbar[l], ld[l], n_bar, dims[l], dims[L], self.Ws[l], self.ld_w[l],
+                B.ACT_IDENTITY, self.Zbar, ld[L], dtype=dt, stream=st))
+            self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
+                self.pv, self.Zbar, ld[L], dims[L], self.logits, ld[L], dtype=dt, stream=st))
+            return
+        self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
+            self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], dtype=dt, stream=st))
+        out = self.logits if last else self.Hbar[l + 1]
+        self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
+            self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
+            B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], dtype=dt, stream=st))
+
+    def _backward(self, st, after_last_layer=None):
+        """3. loss gradient and backward. after_last_layer: called once the calls of layer
+        L - 1 have been enqueued."""
         L, dims, ld, n_l, n_h = self.L, self.dims, self.ld, self.n_local, self.n_halo
         dt = self.dtype
         self._timed("loss_grad", lambda: B.loss_grad(
@@ -264,6 +298,23 @@ class PartitionStep:
             workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
         for l in range(L - 1, -1, -1):
             last = l == L - 1
+            if last and self.transform_first:
+                n_bar = self.n_bar
+                g_halo = self.G[n_l:] if n_h > 0 else None
+                self._timed("spmm_bwd_l%d" % l, lambda: B.spmm_bwd(
+                    self.pv, self.dH[L], ld[L], dims[L], self.G, ld[L], dH_halo=g_halo, ld_halo=ld[L],
+                    dtype=dt, stream=st))
+                self._timed("dense_bwd_l%d" % l, lambda: B.dense_bwd(
+                    self.G, ld[L], None, 0, self.Hbar[l], ld[l], self.Ws[l], self.ld_w[l], n_bar,
+                    dims[l], dims[L], B.ACT_IDENTITY, self.dW[l], self.ld_dw[l], None, 0, dtype=dt,
+                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+                if l >= 1:
+                    self._timed("dense_bwd_in_l%d" % l, lambda: B.dense_bwd(
+                        self.G, ld[L], None, 0, None, 0, self.Ws[l], self.ld_w[l], n_l, dims[l],
+                        dims[L], B.ACT_IDENTITY, None, 0, self.dH[l], ld[l], dtype=dt, stream=st))
+                if after_last_layer is not None:
+                    after_last_layer()
+                continue
             hout = None if last else self.Hbar[l + 1]
             self._timed("dense_bwd_l%d" % l, lambda: B.dense_bwd(
                 self.dH[l + 1], ld[l + 1], hout, 0 if last else ld[l + 1], self.AGG[l], ld[l],
@@ -320,13 +371,8 @@ class PartitionStep:
                 self._timed("gather_l0", lambda: B.history_gather(
                     self.X_table, self.X_table.shape[0], self.X_table.shape[1],
                     self.halo_table_ids, n_h, dims[0], halo0, ld[0], dtype=dt, stream=st))
-            self._timed("spmm_fwd_l%d" % l, lambda: B.spmm_fwd(
-                self.pv, self.Hbar[l], ld[l], dims[l], self.AGG[l], ld[l], dtype=dt, stream=st))
+            self._layer_forward(l, st)
             last = l == L - 1
-            out = self.logits if last else self.Hbar[l + 1]
-            self._timed("dense_fwd_l%d" % l, lambda: B.dense_fwd(
-                self.AGG[l], ld[l], n_l, dims[l], dims[l + 1], self.Ws[l], self.ld_w[l],
-                B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], dtype=dt, stream=st))
             if l == 0:
                 # the first push overwrites a slot the predictions read, and the next layer
                 # reads predicted rows: both wait here (layer 0 itself needs neither)
@@ -336,9 +382,15 @@ class PartitionStep:
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
                     self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))
-        # the ring is complete for step t + 1: its predictions run beside this step's backward
-        self._enqueue_predictions(self.t + 1)
-        self._backward(st)
+        # The ring is complete for step t + 1: its predictions run beside this step's backward.
+        # They overwrite the halo rows of every Hbar_l, which the backward reads in one place
+        # only: the weight gradient of a last layer evaluated as P (Hbar W) sums over local
+        # AND halo rows of Hbar_{L-1}. In that order they are enqueued after that layer.
+        if self.transform_first:
+            self._backward(st, after_last_layer=lambda: self._enqueue_predictions(self.t + 1))
+        else:
+            self._enqueue_predictions(self.t + 1)
+            self._backward(st)
         self.t += 1
 
     # ------------------------------------------------------------ coded ring
@@ -407,6 +459,7 @@ class PartitionStep:
         self.t a multiple of the period and after at least one eager step (so that nothing is
         loaded lazily during capture); per-call timers are off inside the graph."""
         period = self.graph_period()
+        assert not self.predict_ahead, "predictions one step ahead cross the graph's boundary: capture the in-step order"
         assert self.t % period == 0 and self.t > 0, "capture after a whole number of periods, not at t = 0"
         timers, self.timers = self.timers, None
         t0 = self.t

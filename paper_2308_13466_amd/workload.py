@@ -36,7 +36,8 @@ def _upload(a, bf16, dev):
 
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
                    keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
-                   backbone="gcn", coded_ring=None, own_headroom=1.5, predict_ahead=False):
+                   backbone="gcn", coded_ring=None, own_headroom=1.5, predict_ahead=False,
+                   transform_first="auto"):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
@@ -47,6 +48,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     only). Every dense slot generated below is coded once - the local nodes' rows into the
     `own` part (allocated own_headroom times the size they need now, since later pushes have
     other sizes), the halo nodes' rows into the `remote` part (exact size) - and then freed.
+    transform_first: see PartitionStep ("auto": the last layer is evaluated as P (Hbar W)
+    when it narrows to half the width or less).
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
     host copies kept for the tests hold the rounded values the device holds.
 
@@ -170,7 +173,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
         step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
                              fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
                              grad_tables=gt, predict_every=predict_every, coded=coded,
-                             predict_ahead=predict_ahead)
+                             predict_ahead=predict_ahead, transform_first=transform_first)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))

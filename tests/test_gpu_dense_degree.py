@@ -64,8 +64,7 @@ def test_dense_whole_step_sampled(dense):
     tab = step.hist[1][0]
     assert torch.equal(tab[step.local_table_ids.long(), :dims[1]], step.Hbar[1][:n_l, :dims[1]])
     assert np.isfinite(float(step.loss.item()))
-    # backward aggregation at d = 256 on the dense rows: sampled rows of P_in^T dAGG
-    dA = step.dAGG[1].cpu().numpy()[:, :dims[1]]
-    few = rows[:64]
-    gu.assert_close(step.dH[1][torch.from_numpy(few).to(gu.DEV)].cpu().numpy()[:, :dims[1]],
-                    orc.spmm_bwd_rows(v, dA, few), RTOL, "spmm_bwd rows")
+    # the last layer (256 -> 41) runs as P (Hbar W) in this configuration: its transform over
+    # all rows, both aggregations at 41 columns on the dense rows, dW over all rows
+    from tests.last_layer_util import check_last_layer_transform_first
+    check_last_layer_transform_first(gu, torch, wl, rows[:64], halo_sample[:64], RTOL, say=_say)

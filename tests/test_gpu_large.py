@@ -230,6 +230,10 @@ def test_whole_step_sampled(large):
     assert np.isfinite(float(step.loss.item()))
     for l in range(3):
         assert torch.isfinite(step.dW[l][:, :dims[l + 1]]).all()
+    # the last layer in the order the benchmark runs it (P (Hbar W)), call by call
+    from tests.last_layer_util import check_last_layer_transform_first
+    some = np.unique(np.concatenate([rows[::4], np.argsort(np.diff(v["rowptr"]))[-2:], [n_l - 1]]))
+    check_last_layer_transform_first(gu, torch, wl, some, halo_sample[::4], RTOL, say=_say)
     # second step: ring rotated, still finite and deterministic w.r.t. a re-run of step 1's calls
     step.forward_backward()
     gu.sync()

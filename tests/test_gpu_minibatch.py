@@ -1,0 +1,132 @@
+"""True mini-batches of the predictor's training (Eq. 12): the batch's nodes and their 1-hop
+neighbourhood cut out as a view of their own (paper_2308_13466_amd.minibatch_view), so that
+sat_predictor_grad's work falls with the batch. Loss and gradients must equal (a) the
+oracle's on that compact view, (b) the oracle's 0/1-weighted form over all local nodes, which
+is the same sum, and (c) the library's own 0/1-weighted call; and the call must get faster
+as the batch gets smaller."""
+import numpy as np
+import pytest
+
+import sat_synth as syn
+from oracle import sat_oracle as orc
+from tests.test_gpu_parity import _graph
+
+pytestmark = pytest.mark.gpu
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2308_13466_amd as sat
+    sat.lib()
+    from tests import gpu_util as gu
+    return sat, gu, torch
+
+
+def _grad_call(sat, gu, torch, view, node_ids, tables, target, weight, p, d, d_s, tau, ld, n_rows,
+               reps=1):
+    n_l, n_h = view["n_local"], view["n_halo"]
+    pv = gu.upload_view(view)
+    pd = {k: gu.to_dev(p[k]) for k in p}
+    g = dict(Wx=gu.dev_empty(4 * d_s, d), Wh=gu.dev_empty(4 * d_s, d_s),
+             b=torch.full((4 * d_s,), float("nan"), device=gu.DEV), Wg=gu.dev_empty(d_s, d))
+    loss = torch.full((1,), float("nan"), device=gu.DEV)
+    wsb = sat.predictor_train_workspace_bytes(n_l, n_h, d, d_s, tau)
+    ws = gu.workspace(wsb)
+    w = sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], d, d_s, tau)
+    ids_d, tgt_d = gu.to_dev(node_ids), gu.to_dev(target, ld)
+    wt_d = gu.to_dev(weight) if weight is not None else None
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for r in range(reps + 1):          # the first call warms up
+        if r == 1:
+            ev[0].record()
+        sat.predictor_grad(pv, w, tables, n_rows, ld, ids_d, tgt_d, ld, wt_d, g["Wx"], g["Wh"], g["b"],
+                           g["Wg"], loss, workspace=ws, workspace_bytes=wsb, stream=gu.stream_ptr())
+    ev[1].record()
+    gu.sync()
+    return float(loss.item()), {k: g[k].cpu().numpy() for k in g}, ev[0].elapsed_time(ev[1]) / reps
+
+
+def test_minibatch_view_matches_the_weighted_form(env):
+    sat, gu, torch = env
+    print("[case] predictor training on a compact mini-batch view, power-law graph", flush=True)
+    g = _graph("powerlaw")
+    d, d_s, tau = 64, 32, 2
+    ld = gu.ld_for(d, 32)
+    rng = np.random.default_rng(11)
+    p = syn.predictor_params_f32(np.random.SeedSequence(11), d, d_s)
+    full = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    n_l = full["n_local"]
+    base = np.maximum(rng.standard_normal((g.N, d)), 0).astype(np.float32)
+    tables = [(base + 0.05 * rng.standard_normal((g.N, d))).astype(np.float32) for _ in range(tau)]
+    fresh = (tables[-1] + 0.1 * rng.standard_normal((g.N, d))).astype(np.float32)   # by global id
+    tables_d = [gu.to_dev(t, ld) for t in tables]
+    batch = np.sort(rng.choice(full["local_ids"], size=n_l // 8, replace=False))
+    view, node_ids = sat.minibatch_view(g.N, g.rowptr, g.col, g.part, 0, batch)
+    assert np.array_equal(view["local_ids"], batch) and view["n_local"] == len(batch)
+    # the compact view is a partition view: the oracle builds the same one from the two-way split
+    split = np.ones(g.N, np.int32)
+    split[batch] = 0
+    oview = orc.partition_view(g.N, g.rowptr, g.col, split, 0)
+    for k in ("rowptr", "split", "col", "halo_ids", "h_colptr", "h_row"):
+        assert np.array_equal(view[k], oview[k]), k
+    assert np.array_equal(view["val"].view(np.uint32), oview["val"].view(np.uint32))
+    # (a) GPU on the compact view against the oracle on the compact view
+    loss_b, grads_b, _ = _grad_call(sat, gu, torch, view, node_ids, tables_d, fresh[batch], None, p, d, d_s,
+                                    tau, ld, g.N)
+    win_b = [t[node_ids] for t in tables]
+    loss_o, grads_o = orc.predictor_train_loss_and_grad(oview, p, win_b, fresh[batch])
+    assert abs(loss_b - loss_o) <= 2 * RTOL * abs(loss_o)
+    for k in ("Wg", "b", "Wx", "Wh"):
+        gu.assert_close(grads_b[k], grads_o[k], 2 * RTOL, "d%s, compact view vs oracle" % k)
+    # (b) the oracle's 0/1-weighted form over all local nodes is the same sum
+    ids_full = np.concatenate([full["local_ids"], full["halo_ids"]]).astype(np.int32)
+    weight = np.isin(full["local_ids"], batch).astype(np.float32)
+    ofull = orc.partition_view(g.N, g.rowptr, g.col, g.part, 0)
+    loss_w, grads_w = orc.predictor_train_loss_and_grad(ofull, p, [t[ids_full] for t in tables],
+                                                        fresh[full["local_ids"]], weight)
+    assert abs(loss_o - loss_w) <= 1e-10 * abs(loss_w)
+    for k in grads_w:
+        np.testing.assert_allclose(grads_o[k], grads_w[k], rtol=1e-9, atol=1e-14)
+    # (c) and the library's weighted call agrees with its compact call
+    loss_f, grads_f, _ = _grad_call(sat, gu, torch, full, ids_full, tables_d, fresh[full["local_ids"]],
+                                    weight, p, d, d_s, tau, ld, g.N)
+    assert abs(loss_b - loss_f) <= 4 * RTOL * abs(loss_f)
+    for k in grads_f:
+        gu.assert_close(grads_b[k], grads_f[k], 4 * RTOL, "d%s, compact vs weighted call" % k)
+
+
+def test_minibatch_time_falls_with_the_batch(env):
+    """Medium-sized partition (42.5 k local nodes): a sixteenth of the nodes must train in well
+    under half the time of all of them (the 0/1-weighted call takes the same time whatever the
+    batch)."""
+    sat, gu, torch = env
+    cfg = syn.get_config("medium")
+    g = syn.make_graph(cfg, np.random.default_rng(syn.substreams(cfg["seed"])["graph"]))
+    d, d_s, tau = 256, 64, 2
+    ld = gu.ld_for(d, 32)
+    rng = np.random.default_rng(5)
+    p = syn.predictor_params_f32(np.random.SeedSequence(5), d, d_s)
+    full = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    tables_d = [gu.to_dev(rng.standard_normal((g.N, d)).astype(np.float32), ld) for _ in range(tau)]
+    fresh = rng.standard_normal((g.N, d)).astype(np.float32)
+    times = {}
+    for frac in (1, 4, 16):
+        batch = np.sort(rng.choice(full["local_ids"], size=full["n_local"] // frac, replace=False))
+        view, node_ids = sat.minibatch_view(g.N, g.rowptr, g.col, g.part, 0, batch)
+        _, _, ms = _grad_call(sat, gu, torch, view, node_ids, tables_d, fresh[batch], None, p, d, d_s, tau,
+                              ld, g.N, reps=5)
+        times[frac] = ms
+        print("[case] batch = 1/%d of the local nodes: %d rows, %d nodes in the view, %.3f ms" % (
+            frac, view["n_local"], view["n_local"] + view["n_halo"], ms), flush=True)
+    assert times[16] < 0.5 * times[1] and times[4] < times[1]
+
+
+def test_minibatch_view_refuses_foreign_nodes(env):
+    sat, gu, torch = env
+    g = _graph("tiny")
+    other = np.flatnonzero(g.part != 0)[:3]
+    with pytest.raises(ValueError):
+        sat.minibatch_view(g.N, g.rowptr, g.col, g.part, 0, other)

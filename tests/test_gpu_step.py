@@ -296,22 +296,38 @@ def test_step_replayed_from_a_hip_graph_matches_eager_steps(coded_ring):
 def test_predictions_one_step_ahead_change_nothing(name):
     """predict_ahead only moves the predictor's calls to a second stream, beside the previous
     step's backward: every buffer of three steps must equal, bit for bit, what the in-step
-    order leaves (same kernels, same inputs, fixed-order reductions)."""
+    order leaves (same kernels, same inputs, fixed-order reductions). After step 2 the halo
+    rows of Hbar_l already hold the predictions FOR step 3: those are compared with what the
+    in-step order computes at the start of its step 3."""
     import torch
     from paper_2308_13466_amd.workload import build_workload
     print("[case] predictions one step ahead, %s" % name, flush=True)
-    runs = []
+
+    def snapshot(st):
+        n_l = st.n_local
+        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
+        keep += [h[:n_l].clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
+        keep += [t.clone() for l in range(1, st.L) for t in st.hist[l]]
+        return keep
+
+    runs, halo = [], []
     for ahead in (False, True):
         wl = build_workload(name, predict_ahead=ahead)
-        for _ in range(3):
-            wl.step.forward_backward()
-        torch.cuda.synchronize()
         st = wl.step
-        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
-        keep += [h.clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
-        keep += [t.clone() for l in range(1, st.L) for t in st.hist[l]]
-        runs.append(keep)
+        for _ in range(3):
+            st.forward_backward()
+        torch.cuda.synchronize()
+        runs.append(snapshot(st))
+        if not ahead:
+            st.forward_backward()          # its predictions are the ones the other order has made already
+            torch.cuda.synchronize()
+        halo.append([h[st.n_local:].clone() for h in st.Hbar[1:]])
         del wl, st
-    for a, b in zip(*runs):
-        assert a.dtype == b.dtype and torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+
+    def same(a, b):
+        return a.dtype == b.dtype and torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
                                                   b.view(torch.int32) if b.dtype == torch.float32 else b)
+    for k, (a, b) in enumerate(zip(*runs)):
+        assert same(a, b), "buffer %d differs" % k
+    for k, (a, b) in enumerate(zip(*halo)):
+        assert same(a, b), "predicted halo rows of hidden layer %d differ" % (k + 1)
