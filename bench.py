@@ -141,6 +141,10 @@ def main():
                          "evaluated as P (Hbar W) when it narrows to half the width or less (the "
                          "appendix's Z = P H W fixes no order): the aggregation and its transpose then "
                          "gather rows of n_classes elements")
+    ap.add_argument("--no-projection-cache", action="store_true",
+                    help="multiply out the LSTM's input projection of every window slot on every "
+                         "step. By default (when it fits 8 GiB) x Wx^T of a ring slot is kept and "
+                         "read back on the steps where the slot is no longer the window's newest")
     ap.add_argument("--no-scale-leg", action="store_true",
                     help="do not append the full Scale configuration (bf16; run by a child process "
                          "after the headline workload has been timed) under the key \"scale\"")
@@ -181,7 +185,9 @@ def main():
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
                         predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring,
                         predict_ahead=predict_ahead,
-                        transform_first=False if (args.no_transform_first or gat_flag) else "auto")
+                        transform_first=False if (args.no_transform_first or gat_flag) else "auto",
+                        projection_cache=False if (args.no_projection_cache or gat_flag or args.predictor_train)
+                        else "auto")
     gat = args.backbone == "gat"
     bf16 = wl.dtype == "bf16"
     cfg, g, view, step = wl.cfg, wl.graph, wl.view, wl.step
@@ -520,6 +526,8 @@ def main():
                    "pull": "unfused" if args.unfused_pull else "fused into predict",
                    "predictions": "one step ahead, on a second stream" if predict_ahead else "in the step",
                    "last_layer": "P (Hbar W)" if tf else "(P Hbar) W",
+                   "lstm_input_projection": "kept per ring slot" if getattr(step, "proj", None) is not None
+                   else "multiplied out every step",
                    "stale_gradient_term": bool(args.stale_grad),
                    "history_ring": "dense" if args.coded_ring is None else "coded, %d decimals" % args.coded_ring,
                    "caches": "flushed before every call" if args.cold else "as the step leaves them",

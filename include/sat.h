@@ -205,6 +205,28 @@ sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w, const vo
                        int64_t ld, int32_t dtype, void* workspace, int64_t workspace_bytes,
                        void* stream);
 
+/* sat_predict with the LSTM's input projections kept between calls. Consecutive windows of
+ * the sliding window of Sec. "Embedding Predictor" share all but their newest slot, and
+ * x_s Wx^T of a slot does not depend on the slot's position in the window; so the caller
+ * keeps, per ring slot, a matrix proj [n_bar, 4 d_s] fp32 (row k = node k in local-then-
+ * halo order, gate blocks i, f, g, o; no padding) that this call reads or writes:
+ *   proj: HOST array of tau DEVICE pointers, oldest slot first (entries may be NULL:
+ *         nothing is kept for that slot);
+ *   n_proj_valid: the first n_proj_valid slots of the window are taken from proj (their
+ *         cached rows and the Wx tiles are not read at all); every later slot except the
+ *         window's first is multiplied out and, if its pointer is not NULL, written.
+ *         0 <= n_proj_valid < tau (the newest slot is always new).
+ * A cached matrix is valid as long as the slot's rows, the id list and Wx are unchanged:
+ * the caller invalidates it (passes a smaller n_proj_valid) after a push into the slot or
+ * an update of the predictor. The result is bit-identical to sat_predict's: the cached
+ * value is the same fp32 sum in the same order. d_s = 32 or 64 (else SAT_EUNSUPPORTED);
+ * with w->bypass the cache is ignored. Everything else as sat_predict. */
+sat_status sat_predict_cached(const sat_part_view* pv, const sat_predictor* w,
+                              const void* const* slots, int64_t n_rows_slot, int64_t ld_slot,
+                              const int32_t* ids, void* Hbar, int64_t ld, int32_t dtype,
+                              float* const* proj, int32_t n_proj_valid, void* workspace,
+                              int64_t workspace_bytes, void* stream);
+
 /* ------- compression of stored embeddings (Sec. "Data Compression for Historical
  * Embedding Storage"). Every value v is rounded to `precision` decimal places,
  * q = floor(v * 10^precision + 1/2) (three fp32 operations, each correctly rounded),

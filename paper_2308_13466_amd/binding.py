@@ -55,6 +55,8 @@ _SIGNATURES = {
     "sat_history_push": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_predict_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
     "sat_predict": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
+    "sat_predict_cached": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i32, _vp, _i64,
+                                  _vp]),
     "sat_predictor_train_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
     "sat_predictor_grad": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _vp, _i32, _vp, _vp,
                                   _vp, _vp, _vp, _vp, _i64, _vp]),
@@ -228,6 +230,15 @@ def predict(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, dtype=F32, worksp
     _check(lib().sat_predict(pv.ref, w.ref, C.addressof(arr), n_rows_slot, ld_slot, _ptr(ids),
                              _ptr(Hbar), ld, dtype, _ptr(workspace), workspace_bytes, stream),
            "sat_predict")
+
+
+def predict_cached(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, proj, n_proj_valid, dtype=F32,
+                   workspace=None, workspace_bytes=0, stream=None):
+    arr = (C.c_void_p * len(slots))(*[_ptr(s) for s in slots])
+    parr = (C.c_void_p * len(proj))(*[_ptr(p) for p in proj])
+    _check(lib().sat_predict_cached(pv.ref, w.ref, C.addressof(arr), n_rows_slot, ld_slot, _ptr(ids),
+                                    _ptr(Hbar), ld, dtype, C.addressof(parr), n_proj_valid,
+                                    _ptr(workspace), workspace_bytes, stream), "sat_predict_cached")
 
 
 def spmm_workspace_bytes(pv, d):

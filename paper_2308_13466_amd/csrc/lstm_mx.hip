@@ -33,6 +33,18 @@ struct SlotPtrs {
   const void* p[kMaxTau];
 };
 
+// Cached input projections (optional): proj[s] [n_nodes, 4 DS] fp32 holds x_s Wx^T of window
+// slot s, node-major, gate blocks i, f, g, o. The first n_valid slots are READ instead of
+// being multiplied out again (their x rows and the Wx tiles are then not loaded at all); a
+// later slot (other than the window's first) whose pointer is not null is WRITTEN once its
+// input part has been accumulated, before the recurrent part is added. Consecutive windows share all but one slot, and the
+// accumulator of the input part is the same sum in the same order whichever step of the
+// window the slot is, so reading it back gives bit-identical gates.
+struct ProjPtrs {
+  float* p[kMaxTau];
+  int n_valid;
+};
+
 __device__ __forceinline__ float sigmoidf_(float x) {
   return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x));
 }
@@ -62,7 +74,7 @@ __global__ __launch_bounds__(256) void split_weights_kernel(const float* __restr
 // WAVES = wavefronts per workgroup (4 or 8). LDS holds one workgroup per compute
 // unit whatever WAVES is, so with 8 every SIMD has two wavefronts and one of them
 // can read operands from LDS while the other's products run.
-template <int DS, int ESX, int WAVES>
+template <int DS, int ESX, int WAVES, bool CACHE>
 __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
                                                       int64_t ld_slot,
                                                       const int32_t* __restrict__ ids,
@@ -71,7 +83,7 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
                                                       const uint16_t* __restrict__ WhP,
                                                       const float* __restrict__ bias,
                                                       float* __restrict__ S,
-                                                      float* __restrict__ save) {
+                                                      float* __restrict__ save, ProjPtrs proj) {
   constexpr int NP = 3;             // pieces of an fp32 operand (x rows, h)
   // pieces of the weights: all three against fp32 rows (the exact product); two against bf16
   // rows, whose own precision (8 bits) the third piece (bits 17..24 of a weight) cannot matter to
@@ -210,21 +222,67 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
       }
     }
   };
+  // steps [0, s_first) take their input part from the cache: the stream of x tiles starts at
+  // step s_first
+  const int s_first = CACHE ? (proj.n_valid < tau ? proj.n_valid : tau) : 0;
+  const int j0 = s_first * nk;
   u32x4 rw[B_CHUNKS];
-  load_w(WxP, k_pad, 0, rw);
   XRegs ra0;
-  load_x(0, ra0);
-  store_x(ra0, As, 0);   // tile 0 -> half 0 of the double buffer
-  load_x(1, ra0);
+  if (s_first < tau) {
+    if constexpr (!CACHE) load_w(WxP, k_pad, 0, rw);
+    load_x(j0, ra0);
+    store_x(ra0, As + (j0 & 1) * tile_bytes<R, NP>(), j0);   // first tile -> its half of the double buffer
+    load_x(j0 + 1, ra0);
+  }
 
-  for (int s = 0; s < tau; ++s) {
+  // One time step. cached_tag: whether the step's input part comes from the kept projections
+  // (a compile-time switch: the two kinds of step are separate loops below, so neither
+  // carries the other's registers).
+  auto step = [&](int s, auto cached_tag) __attribute__((always_inline)) {
+    constexpr bool cached = CACHE && decltype(cached_tag)::value;
     f32x16 acc[RB][4];
+    const bool whole = CACHE && node0 + R <= n_nodes;      // uniform: every node of the block exists
+    if constexpr (cached) {
+      // gate pre-activations of the input part, in the accumulator's layout: for a fixed
+      // register the 32 lanes of a half-wavefront read 128 contiguous bytes of one node's row.
+      // One base address per group of four registers (rows 8 q + 4 (lane / 32) + 0..3): the
+      // sixteen loads of a group differ by constants that fit the instruction's offset field.
+      const float* P = proj.p[s];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
+        for (int q = 0; q < 4; ++q) {
+          const int64_t nodeq = node0 + 32 * (wm * RB + rb) + 8 * q + 4 * (lane >> 5);
+          if (whole) {
+            const float* base = P + nodeq * NB + unit;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[rb][g][r] = 0.f;
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                if (g == 1 && s == 0) continue;     // c_0 = 0: the forget gate is not looked at
+                acc[rb][g][4 * q + i] = base[i * NB + g * DS];
+              }
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const bool ok = nodeq + i < n_nodes;
+              const float* row = P + (ok ? nodeq + i : 0) * NB + unit;
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                if (g == 1 && s == 0) continue;
+                acc[rb][g][4 * q + i] = ok ? row[g * DS] : 0.f;
+              }
+            }
+          }
+        }
+    } else {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[rb][g][r] = 0.f;
+    }
 
     // one K step of products, B from the staged weight tile (always three pieces).
     // A operand: the staged x tile `Ax` (swizzled 64-byte rows), or if Ax == nullptr
@@ -294,8 +352,13 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
     // the nk tiles of Wx, then from the second step on the tiles of Wh) and are always
     // one tile ahead in registers, across the phase boundary as well (not across the cell
     // update: the registers are needed there).
-    if (s > 0) load_w(WxP, k_pad, 0, rw);
-    for (int i = 0; i < nk; ++i) {
+    if constexpr (CACHE) {
+      if (!cached) load_w(WxP, k_pad, 0, rw);
+      if (cached && s > 0) load_w(WhP, DS, 0, rw);   // (the input part, when it runs, leaves this tile in flight)
+    } else {
+      if (s > 0) load_w(WxP, k_pad, 0, rw);
+    }
+    for (int i = 0; i < (cached ? 0 : nk); ++i) {
       const int j = s * nk + i;
       __syncthreads();
       store_w(rw);
@@ -318,6 +381,29 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
         else load_w_part(wP, w_kp, w_k0, rw, std::integral_constant<int, 5>{});
       };
       products(std::integral_constant<int, ESX == 4 ? 3 : 1>{}, As + (j & 1) * tile_bytes<R, NP>(), 0, mid);
+    }
+    // keep the input part for the windows to come (not at s = 0: the forget gate's columns are
+    // skipped there, and a window's oldest slot is never read again anyway)
+    if (CACHE && !cached && s > 0 && proj.p[s] != nullptr) {
+      float* P = proj.p[s];
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int64_t nodeq = node0 + 32 * (wm * RB + rb) + 8 * q + 4 * (lane >> 5);
+          float* base = P + nodeq * NB + unit;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (whole || nodeq + i < n_nodes) {
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                // with a window of two a kept matrix is only ever read at the first step, where
+                // the forget gate is not looked at: its block is not written at all
+                if (g == 1 && tau == 2) continue;
+                base[i * NB + g * DS] = acc[rb][g][4 * q + i];
+              }
+            }
+        }
     }
     // ---- recurrent part: h_{s-1} Wh^T, K = DS (h_0 = 0: nothing to add at s = 0)
     if (s > 0) {
@@ -383,7 +469,10 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
         }
       // the next step's first __syncthreads orders these writes before any read
     }
-  }
+  };
+  if constexpr (CACHE)
+    for (int s = 0; s < s_first; ++s) step(s, std::true_type{});
+  for (int s = s_first; s < tau; ++s) step(s, std::false_type{});
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -409,12 +498,14 @@ int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
 // S [n_nodes, d_s] = last hidden state of the LSTM over the tau slots (elements of
 // es_x bytes: 4 fp32, 2 bf16; weights and S are fp32). ws points at
 // lstm_mx_workspace_bytes() bytes, 256-byte aligned. Only d_s = 32 and 64.
+// proj (nullable): HOST array of tau device pointers (each nullable), see ProjPtrs; the first
+// n_proj_valid of them are read, the others written.
 // save (nullable): [tau][n_nodes][6 d_s] fp32, per step and node the activated gates
 // i, f, g, o, the cell state c and the hidden state h (what back-propagation needs).
 sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
-                          void* ws, hipStream_t st, float* save) {
+                          void* ws, hipStream_t st, float* save, float* const* proj, int n_proj_valid) {
   const int k_pad = static_cast<int>(round_up(d, 32));
   const int nb = 4 * d_s;
   uint16_t* WxP = static_cast<uint16_t*>(ws);
@@ -427,12 +518,21 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
   if (rc != SAT_OK) return rc;
   SlotPtrs sp;
   for (int s = 0; s < kMaxTau; ++s) sp.p[s] = s < tau ? slot_ptrs[s] : nullptr;
+  ProjPtrs pp;
+  for (int s = 0; s < kMaxTau; ++s) pp.p[s] = (proj && s < tau) ? proj[s] : nullptr;
+  pp.n_valid = proj ? n_proj_valid : 0;
   const int64_t blocks = (n_nodes + R - 1) / R;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
   const dim3 grid(static_cast<unsigned>(blocks));
 #define SAT_LSTM_MX(DS, ESX, WAVES)                                                            \
-  lstm_mx_kernel<DS, ESX, WAVES><<<grid, dim3(64 * WAVES), 0, st>>>(                           \
-      sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S, save)
+  do {                                                                                         \
+    if (proj)                                                                                  \
+      lstm_mx_kernel<DS, ESX, WAVES, true><<<grid, dim3(64 * WAVES), 0, st>>>(                 \
+          sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S, save, pp);    \
+    else                                                                                       \
+      lstm_mx_kernel<DS, ESX, WAVES, false><<<grid, dim3(64 * WAVES), 0, st>>>(                \
+          sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S, save, pp);    \
+  } while (0)
   if (d_s == 32 && es_x == 4) SAT_LSTM_MX(32, 4, 4);
   else if (d_s == 32) SAT_LSTM_MX(32, 2, 4);
   else if (es_x == 4) SAT_LSTM_MX(64, 4, 8);

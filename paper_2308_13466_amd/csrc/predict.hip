@@ -43,7 +43,8 @@ int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s);
 sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
-                          void* ws, hipStream_t st, float* save = nullptr);
+                          void* ws, hipStream_t st, float* save = nullptr, float* const* proj = nullptr,
+                          int n_proj_valid = 0);
 // hop_product.hip: out[m] = add[row(m)] + Agg[m] Wg, fp32, weights-stationary streaming kernel
 sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
                               const void* add, int64_t ld_add, const int32_t* add_ids,
@@ -260,11 +261,14 @@ extern "C" int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, 
          round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256) + (w_mx > 0 ? w_mx : w_fp32);
 }
 
-extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w,
-                                  const void* const* slots, int64_t n_rows_slot,
-                                  int64_t ld_slot, const int32_t* ids, void* Hbar, int64_t ld,
-                                  int32_t dtype, void* workspace, int64_t workspace_bytes,
-                                  void* stream) {
+namespace {
+
+// sat_predict; with proj != nullptr the input projections of the window's slots are read from /
+// written to the caller's cache (sat_predict_cached).
+sat_status predict_impl(const sat_part_view* pv, const sat_predictor* w, const void* const* slots,
+                        int64_t n_rows_slot, int64_t ld_slot, const int32_t* ids, void* Hbar,
+                        int64_t ld, int32_t dtype, float* const* proj, int32_t n_proj_valid,
+                        void* workspace, int64_t workspace_bytes, void* stream) {
   if (!pv || !w || !slots) return SAT_EINVAL;
   if (pv->n_local < 0 || pv->n_halo < 0 || pv->nnz_halo < 0 || n_rows_slot < 0) return SAT_EINVAL;
   if (w->d < 0 || w->tau < 1) return SAT_EINVAL;
@@ -305,9 +309,15 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
   float* Agg = S + round_up(n_bar * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
   float* WxT = Agg + round_up(pv->n_halo * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
   sat_status rc;
+  if (proj) {
+    if (w->d_s > 64) return SAT_EUNSUPPORTED;      // only the split-bf16 LSTM keeps projections
+    if (n_proj_valid < 0 || n_proj_valid >= w->tau) return SAT_EINVAL;   // the newest slot is always new
+    for (int s = 0; s < w->tau; ++s)
+      if ((s < n_proj_valid && !proj[s]) || (reinterpret_cast<uintptr_t>(proj[s]) & 3u)) return SAT_EINVAL;
+  }
   if (w->d_s <= 64) {
     rc = sat::launch_lstm_mx(slots, es, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->d_s, w->Wx,
-                             w->Wh, w->b, S, WxT, st);
+                             w->Wh, w->b, S, WxT, st, nullptr, proj, n_proj_valid);
   } else {
     float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
     const int nb = 4 * w->d_s;
@@ -353,4 +363,26 @@ extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* 
           <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
   }
   return sat::check_launch();
+}
+
+}  // namespace
+
+extern "C" sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w,
+                                  const void* const* slots, int64_t n_rows_slot,
+                                  int64_t ld_slot, const int32_t* ids, void* Hbar, int64_t ld,
+                                  int32_t dtype, void* workspace, int64_t workspace_bytes,
+                                  void* stream) {
+  return predict_impl(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, dtype, nullptr, 0, workspace,
+                      workspace_bytes, stream);
+}
+
+extern "C" sat_status sat_predict_cached(const sat_part_view* pv, const sat_predictor* w,
+                                         const void* const* slots, int64_t n_rows_slot,
+                                         int64_t ld_slot, const int32_t* ids, void* Hbar,
+                                         int64_t ld, int32_t dtype, float* const* proj,
+                                         int32_t n_proj_valid, void* workspace,
+                                         int64_t workspace_bytes, void* stream) {
+  if (!proj) return SAT_EINVAL;
+  return predict_impl(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, dtype, proj, n_proj_valid,
+                      workspace, workspace_bytes, stream);
 }

@@ -40,7 +40,8 @@ int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s);
 sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64_t n_rows_slot,
                           int64_t ld_slot, const int32_t* ids, int64_t n_nodes, int32_t d,
                           int32_t d_s, const float* Wx, const float* Wh, const float* b, float* S,
-                          void* ws, hipStream_t st, float* save);
+                          void* ws, hipStream_t st, float* save, float* const* proj = nullptr,
+                          int n_proj_valid = 0);
 sat_status launch_hop_product(const float* Agg, int64_t M, int32_t ds, const float* Wg, int32_t d,
                               const void* add, int64_t ld_add, const int32_t* add_ids,
                               int64_t add_base, int64_t add_rows, void* out, int64_t ld_out, int eso,

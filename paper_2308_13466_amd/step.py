@@ -105,6 +105,13 @@ class PartitionStep:
           P_out]^T dH^(L) (local and halo rows), dW = Hbar^T G over all rows, dH^(L-1) =
           G_local W^T. AGG_{L-1} and dAGG_{L-1} are then never formed. "auto": when the last
           layer narrows to half or less. Not with gradient tables.
+    projection_cache: keep the LSTM's input projection x Wx^T of every ring slot (one
+          [n_bar, 4 d_s] fp32 matrix per slot and hidden layer) and let the predictor read it
+          for the slots it has already seen (sat_predict_cached): consecutive windows share
+          all but their newest slot, so with tau = 2 the input products of a step halve.
+          Bit-identical results. A push into a slot invalidates its matrix; after an update of
+          the predictor's parameters call invalidate_projection_cache(). Dense ring, fused
+          pull, d_s <= 64 only.
     predict_every: Delta T of Alg. 1 - the predicted halo rows are refreshed on steps
           t = 0, Delta T, 2 Delta T, ... and reused (they stay in the halo rows of Hbar_l) in between.
     grad_tables: None, or grad_tables[l] for l = 1..L-1 a pair [table_a, table_b] of
@@ -120,7 +127,7 @@ class PartitionStep:
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
                  fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1,
-                 coded=None, predict_ahead=False, transform_first=False):
+                 coded=None, predict_ahead=False, transform_first=False, projection_cache=False):
         dev = X_table.device
         self.predict_ahead = bool(predict_ahead)
         L_ = len(dims) - 1
@@ -189,6 +196,13 @@ class PartitionStep:
             ws_bytes.append(B.history_compress_workspace_bytes(n_l))
         self.ws_bytes = max(ws_bytes + [256])
         self.ws = torch.empty((self.ws_bytes + 3) // 4, **f32)
+        self.proj = None
+        if projection_cache and L >= 2:
+            assert coded is None and self.fused_pull, "the projection cache goes with the dense ring and the fused pull"
+            self.proj = [None] + [[torch.zeros((n_bar, 4 * predictors[l].d_s), **f32) for _ in range(tau)]
+                                  if (not predictors[l].bypass and predictors[l].d_s <= 64) else None
+                                  for l in range(1, L)]
+            self._proj_valid = [None] + [[False] * tau for _ in range(1, L)]
         self._side = None
         if self.predict_ahead:
             assert coded is None and self.fused_pull, "predict_ahead goes with the dense ring and the fused pull"
@@ -215,6 +229,33 @@ class PartitionStep:
         else:
             self.timers.record(name, fn)
 
+    def invalidate_projection_cache(self):
+        """After the predictor's parameters changed: every kept projection is stale."""
+        if self.proj is not None:
+            for l in range(1, self.L):
+                self._proj_valid[l] = [False] * self.tau
+
+    def _predict_in_place(self, l, order, ws, stream):
+        """sat_predict of hidden layer l straight from the ring (slots in window order), with the
+        kept input projections where there are any."""
+        w = self.predictors[l]
+        slots = [self.hist[l][s] for s in order]
+        n_rows, ld_t = slots[0].shape
+        if self.proj is None or self.proj[l] is None:
+            B.predict(self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], self.ld[l],
+                      dtype=self.dtype, workspace=ws, workspace_bytes=self.ws_bytes, stream=stream)
+            return
+        valid = self._proj_valid[l]
+        n_valid = 0
+        while n_valid < len(order) - 1 and valid[order[n_valid]]:
+            n_valid += 1
+        B.predict_cached(self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], self.ld[l],
+                         [self.proj[l][s] for s in order], n_valid, dtype=self.dtype, workspace=ws,
+                         workspace_bytes=self.ws_bytes, stream=stream)
+        for pos, s in enumerate(order):      # every slot but the window's first now has its matrix
+            if pos >= 1:
+                valid[s] = True
+
     def slot_order(self):
         """Ring slots oldest -> newest as seen by step t's predictions."""
         return [(self.t + s) % self.tau for s in range(self.tau)]
@@ -238,9 +279,7 @@ class PartitionStep:
             slots = [self.hist[l][s] for s in order]
             n_rows, ld_t = slots[0].shape
             if self.fused_pull or w.bypass:
-                self._timed("predict_l%d" % l, lambda: B.predict(
-                    self.pv, w, slots, n_rows, ld_t, self.table_ids, self.Hbar[l], ld[l], dtype=dt,
-                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+                self._timed("predict_l%d" % l, lambda: self._predict_in_place(l, order, self.ws, st))
             else:
                 for k, s in enumerate(slots):
                     self._timed("gather_l%d" % l, lambda: B.history_gather(
@@ -263,6 +302,8 @@ class PartitionStep:
                 self._push_coded(l + 1, w_slot, st)
             elif not last:
                 tab = self.hist[l + 1][w_slot]
+                if self.proj is not None:
+                    self._proj_valid[l + 1][w_slot] = False      # the slot's rows change
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
                     self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))
@@ -349,12 +390,7 @@ class PartitionStep:
             with torch.cuda.stream(self._side):
                 sp = self._side.cuda_stream
                 for l in range(1, self.L):
-                    slots = [self.hist[l][s] for s in order]
-                    n_rows, ld_t = slots[0].shape
-                    self._timed("predict_l%d" % l, lambda: B.predict(
-                        self.pv, self.predictors[l], slots, n_rows, ld_t, self.table_ids,
-                        self.Hbar[l], self.ld[l], dtype=self.dtype, workspace=self._ws_side,
-                        workspace_bytes=self.ws_bytes, stream=sp))
+                    self._timed("predict_l%d" % l, lambda: self._predict_in_place(l, order, self._ws_side, sp))
         self._pred_done = torch.cuda.Event()
         self._pred_done.record(self._side)
 
@@ -379,6 +415,8 @@ class PartitionStep:
                 main.wait_event(self._pred_done)
             if not last:
                 tab = self.hist[l + 1][w_slot]
+                if self.proj is not None:
+                    self._proj_valid[l + 1][w_slot] = False      # the slot's rows change
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
                     self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))

@@ -1,0 +1,157 @@
+"""sat_predict_cached: the LSTM's input projections x Wx^T kept per ring slot and read back on
+the steps where a slot is no longer the window's newest. The cached value is the same fp32 sum
+in the same order, so every result must be BIT-identical to sat_predict's (which the other
+tests hold to the oracle), for every number of valid leading slots, fp32 and bf16 tables,
+with and without the id list; and a whole step with the cache switched on must leave the same
+bits in every buffer as one without."""
+import numpy as np
+import pytest
+
+import sat_synth as syn
+from oracle import sat_oracle as orc
+from tests.test_gpu_parity import _graph
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2308_13466_amd as sat
+    sat.lib()
+    from tests import gpu_util as gu
+    return sat, gu, torch
+
+
+@pytest.mark.parametrize("kind,d,d_s,tau,use_ids,bf16", [
+    ("tiny", 32, 32, 2, False, False), ("powerlaw", 256, 64, 2, True, False),
+    ("powerlaw", 100, 64, 3, True, False), ("hub", 40, 32, 3, False, False),
+    ("powerlaw", 256, 64, 2, True, True), ("tiny", 64, 32, 3, True, True)])
+def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
+    sat, gu, torch = env
+    print("[case] predict_cached %s d=%d d_s=%d tau=%d ids=%s bf16=%s" % (kind, d, d_s, tau, use_ids, bf16),
+          flush=True)
+    g = _graph(kind)
+    v = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    n_l, n_h = v["n_local"], v["n_halo"]
+    n_bar = n_l + n_h
+    rng = np.random.default_rng(d + tau)
+    p = syn.predictor_params_f32(np.random.SeedSequence(d_s + tau), d, d_s)
+    ld = gu.ld_for(d, 32)
+    if use_ids:
+        ids = np.concatenate([v["local_ids"], v["halo_ids"]]).astype(np.int32)
+        n_rows = g.N
+    else:
+        ids, n_rows = None, n_bar
+    # tau + 1 epochs: two consecutive windows that share tau - 1 slots
+    tabs = [rng.standard_normal((n_rows, d)).astype(np.float32) for _ in range(tau + 1)]
+    if bf16:
+        tabs = [syn.f32_from_bf16_bits(syn.bf16_bits_from_f32(t)) for t in tabs]
+        tabs_d = [gu.to_dev_bits(syn.bf16_bits_from_f32(t), ld).view(torch.bfloat16) for t in tabs]
+        dt = sat.BF16
+    else:
+        tabs_d = [gu.to_dev(t, ld) for t in tabs]
+        dt = sat.F32
+    pd = {k: gu.to_dev(p[k]) for k in p}
+    w = sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], d, d_s, tau)
+    wsb = sat.predict_workspace_bytes(n_l, n_h, d, d_s, tau)
+    ws = gu.workspace(wsb)
+    ids_d = gu.to_dev(ids) if use_ids else None
+    st = gu.stream_ptr()
+
+    def fresh_out():
+        return torch.zeros((n_bar, ld), dtype=tabs_d[0].dtype, device=gu.DEV)
+
+    def plain(window):
+        out = fresh_out()
+        sat.predict(v_d, w, window, n_rows, ld, ids_d, out, ld, dtype=dt, workspace=ws, workspace_bytes=wsb,
+                    stream=st)
+        gu.sync()
+        return out
+
+    v_d = gu.upload_view(v)
+    ref1, ref2 = plain(tabs_d[:tau]), plain(tabs_d[1:])
+    # projection matrices per EPOCH (the caller's ring): NaN until written
+    proj = [torch.full((n_bar, 4 * d_s), float("nan"), dtype=torch.float32, device=gu.DEV) for _ in range(tau + 1)]
+    out = fresh_out()
+    sat.predict_cached(v_d, w, tabs_d[:tau], n_rows, ld, ids_d, out, ld, proj[:tau], 0, dtype=dt,
+                       workspace=ws, workspace_bytes=wsb, stream=st)
+    gu.sync()
+    assert torch.equal(out.view(torch.int16 if bf16 else torch.int32), ref1.view(torch.int16 if bf16 else torch.int32))
+    assert torch.isnan(proj[0]).all()                       # the window's first slot is never kept
+    # the columns a later window can read: all of them, except that with a window of two a kept
+    # matrix is only ever read at the first step, where the forget gate (second block) is not used
+    used = np.ones(4 * d_s, dtype=bool)
+    if tau == 2:
+        used[d_s:2 * d_s] = False
+    used_d = torch.from_numpy(used).to(gu.DEV)
+    for s in range(1, tau):
+        assert torch.isfinite(proj[s][:, used_d]).all() and torch.isnan(proj[s][:, ~used_d]).all()
+    # the kept matrix is x Wx^T of the slot (no bias), node-major: against the oracle's product
+    x1 = tabs[1][ids] if use_ids else tabs[1]
+    from tests import gpu_util
+    # (against bfloat16 rows the weights enter to 16 bits, two bf16 pieces: 2^-17 per product)
+    gpu_util.assert_close(proj[1].cpu().numpy()[:, used], (x1.astype(np.float64) @ p["Wx"].astype(np.float64).T)[:, used],
+                          1e-4 if bf16 else 1e-5, "kept input projection")
+    # next window: every number of valid leading slots gives the same bits as the plain call
+    for n_valid in range(tau - 1, -1, -1):
+        pr = [q.clone() for q in proj[1:]]
+        out = fresh_out()
+        sat.predict_cached(v_d, w, tabs_d[1:], n_rows, ld, ids_d, out, ld, pr, n_valid, dtype=dt,
+                           workspace=ws, workspace_bytes=wsb, stream=st)
+        gu.sync()
+        assert torch.equal(out.view(torch.int16 if bf16 else torch.int32),
+                           ref2.view(torch.int16 if bf16 else torch.int32)), "n_valid = %d" % n_valid
+        assert torch.isfinite(pr[-1][:, used_d]).all()      # the newest slot's matrix has been written
+        for s in range(1, tau - 1):                         # re-written ones equal the kept ones
+            assert torch.equal(pr[s], proj[1 + s])
+    # and the oracle, once (the plain call is held to it elsewhere; this ties the cached one too)
+    win = [t[ids] if use_ids else t for t in tabs[1:]]
+    refo = orc.predict(v, p, win)
+    got = out.float().cpu().numpy()[n_l:, :d]
+    gpu_util.assert_close(got, orc.round_bf16(refo) if bf16 else refo, 2e-2 if bf16 else 1e-5, "predicted halo rows")
+
+
+def test_predict_cached_rejects_bad_arguments(env):
+    sat, gu, torch = env
+    g = _graph("tiny")
+    v = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    n_bar = v["n_local"] + v["n_halo"]
+    d, tau = 32, 2
+    ld = gu.ld_for(d, 32)
+    tabs = [gu.dev_empty(n_bar, ld, fill=0.5) for _ in range(tau)]
+    out = gu.dev_empty(n_bar, ld, fill=0.0)
+    for d_s, n_valid, status in ((32, 2, -1), (32, -1, -1), (128, 0, -2)):
+        p = syn.predictor_params_f32(np.random.SeedSequence(1), d, d_s)
+        pd = {k: gu.to_dev(p[k]) for k in p}
+        w = sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], d, d_s, tau)
+        wsb = sat.predict_workspace_bytes(v["n_local"], v["n_halo"], d, d_s, tau)
+        proj = [torch.zeros((n_bar, 4 * d_s), device=gu.DEV) for _ in range(tau)]
+        with pytest.raises(sat.SatError) as e:
+            sat.predict_cached(gu.upload_view(v), w, tabs, n_bar, ld, None, out, ld, proj, n_valid,
+                               workspace=gu.workspace(wsb), workspace_bytes=wsb, stream=gu.stream_ptr())
+        assert e.value.status == status
+    gu.sync()
+
+
+@pytest.mark.parametrize("name,ahead", [("tiny", False), ("medium", False), ("medium", True)])
+def test_step_with_projection_cache_leaves_the_same_bits(name, ahead):
+    import torch
+    from paper_2308_13466_amd.workload import build_workload
+    print("[case] step with kept projections, %s, predictions one step ahead: %s" % (name, ahead), flush=True)
+    runs = []
+    for cache in (False, True):
+        wl = build_workload(name, projection_cache=cache, predict_ahead=ahead)
+        st = wl.step
+        assert (st.proj is not None) == cache
+        for _ in range(4):
+            st.forward_backward()
+        torch.cuda.synchronize()
+        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
+        keep += [h.clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
+        keep += [t.clone() for l in range(1, st.L) for t in st.hist[l]]
+        runs.append(keep)
+        del wl, st
+    for k, (a, b) in enumerate(zip(*runs)):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32)), "buffer %d differs" % k
