@@ -24,6 +24,10 @@ bool dense_ws_serves(int32_t K);
 sat_status launch_dense_ws(const void* A, int64_t ld_a, const void* Mk, int64_t ld_m, int64_t M,
                            int32_t K, const void* W, int64_t ld_w, bool transb, int32_t N, bool relu,
                            void* out, int64_t ld_out, hipStream_t st);
+bool dense_narrow_serves(int32_t K, int32_t N);
+sat_status launch_dense_narrow(const void* A, int64_t ld_a, int64_t M, int32_t K, const void* W,
+                               int64_t ld_w, int32_t N, bool relu, void* out, int64_t ld_out,
+                               hipStream_t st);
 }  // namespace sat
 
 namespace {
@@ -69,7 +73,7 @@ struct SplitPlan {
 // least 256 nodes long.
 SplitPlan plan_dw(int64_t n, int32_t d_in, int32_t d_out) {
   SplitPlan p;
-  const int bmx = d_in <= 128 ? 128 : 256, bnx = d_out <= 128 ? 128 : 256;
+  const int bmx = d_in <= 128 ? 128 : 256, bnx = d_out <= 64 ? 64 : (d_out <= 128 ? 128 : 256);
   const int64_t tiles = ((d_in + bmx - 1) / bmx) * static_cast<int64_t>((d_out + bnx - 1) / bnx);
   int64_t want = (256 + tiles - 1) / tiles;
   int64_t max_by_k = (n + 255) / 256;
@@ -116,17 +120,17 @@ template <int ES>
 sat_status launch_dw(const void* A, int64_t ld_a, int d_a, const void* B, int64_t ld_b, int d_b,
                      const void* M, int64_t ld_m, int64_t n, const SplitPlan& p, float* part,
                      hipStream_t s) {
-  const bool big_m = d_a > 128, big_n = d_b > 128;
-  const int bmx = big_m ? 256 : 128, bnx = big_n ? 256 : 128;
+  const bool big_m = d_a > 128, big_n = d_b > 128, small_n = d_b <= 64;
+  const int bmx = big_m ? 256 : 128, bnx = big_n ? 256 : (small_n ? 64 : 128);
   const dim3 grid(static_cast<unsigned>((d_a + bmx - 1) / bmx), static_cast<unsigned>((d_b + bnx - 1) / bnx),
                   static_cast<unsigned>(p.splits));
 #define SAT_DW(MT, NT)                                                                                 \
   (M ? launch_dw_one<ES, MT, NT, true>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s)        \
      : launch_dw_one<ES, MT, NT, false>(grid, A, ld_a, d_a, B, ld_b, d_b, M, ld_m, n, p, part, s))
   if (big_m && big_n) return SAT_DW(4, 4);
-  if (big_m) return SAT_DW(4, 2);
+  if (big_m) return small_n ? SAT_DW(4, 1) : SAT_DW(4, 2);
   if (big_n) return SAT_DW(2, 4);
-  return SAT_DW(2, 2);
+  return small_n ? SAT_DW(2, 1) : SAT_DW(2, 2);
 #undef SAT_DW
 }
 
@@ -147,6 +151,10 @@ sat_status run_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in, int32
     if (sat::dense_ws_serves(d_in) && d_out > 128)
       return sat::launch_dense_ws(AGG, ld_a, nullptr, 0, n, d_in, W, ld_w, false, d_out,
                                   act == SAT_ACT_RELU, H, ld_h, s);
+  }
+  if constexpr (ES == 4) {   // fp32 onto few columns and many rows: the weights stay in LDS
+    if (sat::dense_narrow_serves(d_in, d_out) && n >= 8192)
+      return sat::launch_dense_narrow(AGG, ld_a, n, d_in, W, ld_w, d_out, act == SAT_ACT_RELU, H, ld_h, s);
   }
   const int64_t gx = (n + BM - 1) / BM;
   if (gx > INT32_MAX) return SAT_EUNSUPPORTED;

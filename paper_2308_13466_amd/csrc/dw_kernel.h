@@ -193,15 +193,17 @@ __global__ __launch_bounds__(256) void dw_kernel(const void* __restrict__ A, int
                    auto& out, int pidx) {
     constexpr int T = decltype(t_tag)::value;
     const unsigned char* p = piece + (16 * kc + 8 * (lane >> 5)) * row_bytes + (col0 + T * (lane & 31)) * 2;
-    uint32_t raw[8][T / 2];
+    uint32_t raw[8][(T + 1) / 2];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       if constexpr (T == 4) {
         const u32x2 v = *reinterpret_cast<const u32x2*>(p + e * row_bytes);
         raw[e][0] = v.x;
         raw[e][1] = v.y;
-      } else {
+      } else if constexpr (T == 2) {
         raw[e][0] = *reinterpret_cast<const uint32_t*>(p + e * row_bytes);
+      } else {   // one tile per wavefront (an operand of at most 64 columns): 2 bytes per node
+        raw[e][0] = *reinterpret_cast<const uint16_t*>(p + e * row_bytes);
       }
     }
 #pragma unroll

@@ -175,7 +175,11 @@ def test_spmm_rejects_misaligned(env):
 @pytest.mark.parametrize("n,d_in,d_out,act", [(2048, 64, 32, 1), (2051, 32, 8, 0),
                                               (1000, 128, 256, 1), (777, 256, 256, 1),
                                               (513, 256, 40, 0), (300, 602, 256, 1),
-                                              (129, 100, 47, 0), (5, 4, 4, 1), (1, 1, 1, 0)])
+                                              (129, 100, 47, 0), (5, 4, 4, 1), (1, 1, 1, 0),
+                                              # many rows onto few columns: the weights-in-LDS forward
+                                              # kernel and the 64-column tile of the weight gradient
+                                              (20011, 256, 47, 0), (9000, 64, 8, 1), (8192, 128, 64, 1),
+                                              (8200, 256, 33, 0), (9001, 40, 17, 1)])
 def test_dense_fwd_bwd_parity(env, n, d_in, d_out, act):
     sat, gu, torch = env
     _say("dense n=%d %d->%d act=%d" % (n, d_in, d_out, act))
