@@ -45,7 +45,7 @@ def measured_traffic():
     return table
 
 
-KERNEL_OF_CLASS = {"spmm": "spmm_stream_kernel", "gather": "row_copy_vec_kernel (gather)",
+KERNEL_OF_CLASS = {"spmm": "spmm_stream_kernel (rows over 256 bytes) / spmm_slot_kernel (up to 256 bytes)", "gather": "row_copy_vec_kernel (gather)",
                    "push": "row_copy_vec_kernel (scatter)", "dense_fwd": "mx::gemm_kernel",
                    "loss": "xent_grad_kernel", "gather_add": "row_gather_add_kernel",
                    "gat_fwd": "gat_fwd_kernel", "gat_scores": "gat_scores_kernel"}
@@ -359,7 +359,8 @@ def main():
             peak = round(peak_predict if cls == "predict" else peak_dense, 1)
         # measured bytes exist for the plain configuration of a workload only
         plain_cfg = (args.coded_ring is None and not args.stale_grad and not args.bypass
-                     and not args.unfused_pull)
+                     and not args.unfused_pull and not args.no_transform_first
+                     and (gat or not args.no_projection_cache))
         traffic = traffic_table.get((args.workload, args.backbone, wl.dtype, cls)) if plain_cfg else None
         roof_all[cls] = dict(bound=c["bound"], achieved=round(ach, 2), peak=peak, unit=unit,
                              frac=round(ach / peak, 4),
