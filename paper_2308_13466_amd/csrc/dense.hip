@@ -25,6 +25,10 @@ sat_status launch_dense_ws(const void* A, int64_t ld_a, const void* Mk, int64_t 
                            int32_t K, const void* W, int64_t ld_w, bool transb, int32_t N, bool relu,
                            void* out, int64_t ld_out, hipStream_t st);
 bool dense_narrow_serves(int32_t K, int32_t N);
+bool dense_ws32_serves(int32_t K, int64_t M);
+sat_status launch_dense_ws32(const void* A, int64_t ld_a, const void* Mk, int64_t ld_m, int64_t M,
+                             int32_t K, const void* W, int64_t ld_w, bool transb, int32_t N,
+                             bool relu, void* out, int64_t ld_out, hipStream_t st);
 sat_status launch_dense_narrow(const void* A, int64_t ld_a, int64_t M, int32_t K, const void* W,
                                int64_t ld_w, int32_t N, bool relu, void* out, int64_t ld_out,
                                hipStream_t st);
@@ -155,6 +159,17 @@ sat_status run_fwd(const void* AGG, int64_t ld_a, int64_t n, int32_t d_in, int32
   if constexpr (ES == 4) {   // fp32 onto few columns and many rows: the weights stay in LDS
     if (sat::dense_narrow_serves(d_in, d_out) && n >= 8192)
       return sat::launch_dense_narrow(AGG, ld_a, n, d_in, W, ld_w, d_out, act == SAT_ACT_RELU, H, ld_h, s);
+    // fp32 onto more than 128 columns: the weights stay in registers for whole 32-row tiles,
+    // the last n % 32 rows go through the tile GEMM below
+    if (sat::dense_ws32_serves(d_in, n) && d_out > 128) {
+      const int64_t n_ws = n & ~static_cast<int64_t>(31);
+      const sat_status st = sat::launch_dense_ws32(AGG, ld_a, nullptr, 0, n_ws, d_in, W, ld_w, false, d_out,
+                                                   act == SAT_ACT_RELU, H, ld_h, s);
+      if (st != SAT_OK || n_ws == n) return st;
+      AGG = static_cast<const float*>(AGG) + n_ws * ld_a;
+      H = static_cast<float*>(H) + n_ws * ld_h;
+      n -= n_ws;
+    }
   }
   const int64_t gx = (n + BM - 1) / BM;
   if (gx > INT32_MAX) return SAT_EUNSUPPORTED;
@@ -193,6 +208,18 @@ sat_status run_bwd(const void* dH, int64_t ld_dh, const void* mask, int64_t ld_h
     if (dAGG && sat::dense_ws_serves(d_out) && d_in > 128)
       return sat::launch_dense_ws(dH, ld_dh, mask, ld_ho, n, d_out, W, ld_w, true, d_in, false, dAGG,
                                   ld_da, s);
+  }
+  if constexpr (ES == 4) {
+    if (dAGG && sat::dense_ws32_serves(d_out, n) && d_in > 128) {
+      const int64_t n_ws = n & ~static_cast<int64_t>(31);
+      st = sat::launch_dense_ws32(dH, ld_dh, mask, ld_ho, n_ws, d_out, W, ld_w, true, d_in, false, dAGG,
+                                  ld_da, s);
+      if (st != SAT_OK || n_ws == n) return st;
+      dH = static_cast<const float*>(dH) + n_ws * ld_dh;
+      if (mask) mask = static_cast<const float*>(mask) + n_ws * ld_ho;
+      dAGG = static_cast<float*>(dAGG) + n_ws * ld_da;
+      n -= n_ws;
+    }
   }
   if (dAGG) {
     const int64_t gx = (n + BM - 1) / BM;

@@ -179,7 +179,13 @@ def test_spmm_rejects_misaligned(env):
                                               # many rows onto few columns: the weights-in-LDS forward
                                               # kernel and the 64-column tile of the weight gradient
                                               (20011, 256, 47, 0), (9000, 64, 8, 1), (8192, 128, 64, 1),
-                                              (8200, 256, 33, 0), (9001, 40, 17, 1)])
+                                              (8200, 256, 33, 0), (9001, 40, 17, 1),
+                                              # many rows onto many columns: the weights-in-registers
+                                              # kernel (whole 32-row tiles) plus the tile GEMM for the
+                                              # last rows; full and ragged K and N, with and without mask
+                                              (65606, 256, 256, 1), (66001, 100, 256, 1),
+                                              (65600, 256, 200, 0), (70000, 128, 256, 1),
+                                              (65540, 200, 136, 1), (65537, 64, 160, 0)])
 def test_dense_fwd_bwd_parity(env, n, d_in, d_out, act):
     sat, gu, torch = env
     _say("dense n=%d %d->%d act=%d" % (n, d_in, d_out, act))
