@@ -176,7 +176,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    predict_ahead = not (args.no_predict_ahead or args.backbone != "gcn" or args.coded_ring is not None
+    predict_ahead = not (args.no_predict_ahead or args.backbone != "gcn"
                          or args.unfused_pull or args.graph or args.cold or args.bypass)
     gat_flag = args.backbone == "gat"
     flush = torch.zeros(1 << 28, dtype=torch.float32, device=dev) if args.cold else None

@@ -205,7 +205,7 @@ class PartitionStep:
             self._proj_valid = [None] + [[False] * tau for _ in range(1, L)]
         self._side = None
         if self.predict_ahead:
-            assert coded is None and self.fused_pull, "predict_ahead goes with the dense ring and the fused pull"
+            assert coded is not None or self.fused_pull, "predict_ahead goes with the fused pull (or the coded ring)"
             self._side = torch.cuda.Stream(device=dev)          # default priority
             self._ws_side = torch.empty((self.ws_bytes + 3) // 4, **f32)   # the predictor's own scratch
             self._pred_done = None      # event: predictions for step self.t are in place
@@ -390,6 +390,13 @@ class PartitionStep:
             with torch.cuda.stream(self._side):
                 sp = self._side.cuda_stream
                 for l in range(1, self.L):
+                    if self.coded is not None:      # decode the window, then predict from the dense rows
+                        self._pull_coded(l, order, sp)
+                        self._timed("predict_l%d" % l, lambda: B.predict(
+                            self.pv, self.predictors[l], self.window[l], self.n_bar, self.ld[l], None,
+                            self.Hbar[l], self.ld[l], dtype=self.dtype, workspace=self._ws_side,
+                            workspace_bytes=self.ws_bytes, stream=sp))
+                        continue
                     self._timed("predict_l%d" % l, lambda: self._predict_in_place(l, order, self._ws_side, sp))
         self._pred_done = torch.cuda.Event()
         self._pred_done.record(self._side)
@@ -413,7 +420,9 @@ class PartitionStep:
                 # the first push overwrites a slot the predictions read, and the next layer
                 # reads predicted rows: both wait here (layer 0 itself needs neither)
                 main.wait_event(self._pred_done)
-            if not last:
+            if not last and self.coded is not None:
+                self._push_coded(l + 1, w_slot, st)
+            elif not last:
                 tab = self.hist[l + 1][w_slot]
                 if self.proj is not None:
                     self._proj_valid[l + 1][w_slot] = False      # the slot's rows change

@@ -328,3 +328,49 @@ def test_coded_ring_step_bf16_storage(name):
         rms = np.sqrt(np.mean(ref * ref))
         assert np.all(np.abs(got - ref) <= 0.5 * unit + rtol * (np.abs(ref) + rms))
     print("[case] ok: loss %.6f" % st["loss"], flush=True)
+
+
+@pytest.mark.parametrize("name", ["tiny", "medium"])
+def test_coded_ring_predictions_one_step_ahead_change_nothing(name):
+    """With the coded ring, predict_ahead moves the decode of the window and the predictor's
+    calls to a second stream, beside the previous step's backward: every buffer after three
+    steps, the codes in the ring included, equals bit for bit what the in-step order leaves.
+    The halo rows then already hold the predictions FOR step 3, which the in-step order makes
+    at the start of its fourth call."""
+    import torch
+    from paper_2308_13466_amd.workload import build_workload
+    print("[case] coded ring, predictions one step ahead, %s" % name, flush=True)
+
+    def snapshot(st):
+        n_l = st.n_local
+        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
+        keep += [h[:n_l].clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
+        for l in range(1, st.L):
+            for slot in st.coded.slots[l]:
+                used = int(slot.own_off[-1].item())
+                keep += [slot.own_off.clone(), slot.own_codes[:used].clone()]
+        return keep
+
+    runs, halo = [], []
+    for ahead in (False, True):
+        wl = build_workload(name, coded_ring=2, predict_ahead=ahead)
+        st = wl.step
+        for _ in range(3):
+            st.forward_backward()
+        torch.cuda.synchronize()
+        assert st.coded_overflow() == []
+        runs.append(snapshot(st))
+        if not ahead:
+            st.forward_backward()
+            torch.cuda.synchronize()
+        halo.append([h[st.n_local:].clone() for h in st.Hbar[1:]])
+        del wl, st
+
+    def same(a, b):
+        if a.dtype == torch.float32:
+            a, b = a.view(torch.int32), b.view(torch.int32)
+        return a.shape == b.shape and torch.equal(a, b)
+    for k, (a, b) in enumerate(zip(*runs)):
+        assert same(a, b), "buffer %d differs" % k
+    for k, (a, b) in enumerate(zip(*halo)):
+        assert same(a, b), "predicted halo rows of hidden layer %d differ" % (k + 1)
