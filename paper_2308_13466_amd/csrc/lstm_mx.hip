@@ -27,7 +27,7 @@ namespace {
 using namespace sat::mx;
 
 constexpr int kMaxTau = 8;
-constexpr int R = 128;  // nodes per workgroup
+constexpr int kR = 128;  // nodes per workgroup (64 in the instance that runs from kept projections only)
 
 struct SlotPtrs {
   const void* p[kMaxTau];
@@ -74,7 +74,10 @@ __global__ __launch_bounds__(256) void split_weights_kernel(const float* __restr
 // WAVES = wavefronts per workgroup (4 or 8). LDS holds one workgroup per compute
 // unit whatever WAVES is, so with 8 every SIMD has two wavefronts and one of them
 // can read operands from LDS while the other's products run.
-template <int DS, int ESX, int WAVES, bool CACHE>
+// R = nodes per workgroup. XPART false: every step's input part comes from the kept
+// projections (proj.n_valid == tau): no x tile and no Wx tile is touched, the x staging
+// buffer is not allocated.
+template <int DS, int ESX, int WAVES, bool CACHE, int R = kR, bool XPART = true>
 __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int tau, int64_t n_rows_slot,
                                                       int64_t ld_slot,
                                                       const int32_t* __restrict__ ids,
@@ -97,7 +100,8 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
   constexpr int H_ROW_B = DS * 2 + 16;        // bytes per node row of a staged h piece
   constexpr int H_PIECE_B = R * H_ROW_B;
   constexpr int B_CHUNKS = NPB * NB * 4 / NT; // 16-byte weight chunks per thread per K step
-  __shared__ __attribute__((aligned(16))) unsigned char As[2 * tile_bytes<R, NP>()];
+  static_assert(XPART || CACHE, "without an input part every step is a cached one");
+  __shared__ __attribute__((aligned(16))) unsigned char As[XPART ? 2 * tile_bytes<R, NP>() : 16];
   __shared__ __attribute__((aligned(16))) unsigned char Bs[tile_bytes<NB, NPB>()];
   __shared__ __attribute__((aligned(16))) unsigned char Hs[NP * H_PIECE_B];
 
@@ -118,7 +122,7 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
   for (int i = 0; i < XROWS; ++i) {
     const int64_t node = node0 + (t + NT * i) / CPR;
     int64_t r = -1;
-    if (node < n_nodes) {
+    if (XPART && node < n_nodes) {
       r = ids ? static_cast<int64_t>(ids[node]) : node;
       if (r < 0 || r >= n_rows_slot) r = -1;
     }
@@ -224,29 +228,24 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
   };
   // steps [0, s_first) take their input part from the cache: the stream of x tiles starts at
   // step s_first
-  const int s_first = CACHE ? (proj.n_valid < tau ? proj.n_valid : tau) : 0;
+  const int s_first = !XPART ? tau : CACHE ? (proj.n_valid < tau ? proj.n_valid : tau) : 0;
   const int j0 = s_first * nk;
   u32x4 rw[B_CHUNKS];
   XRegs ra0;
-  if (s_first < tau) {
+  if (XPART && s_first < tau) {
     if constexpr (!CACHE) load_w(WxP, k_pad, 0, rw);
     load_x(j0, ra0);
     store_x(ra0, As + (j0 & 1) * tile_bytes<R, NP>(), j0);   // first tile -> its half of the double buffer
     load_x(j0 + 1, ra0);
   }
 
-  // One time step. cached_tag: whether the step's input part comes from the kept projections
-  // (a compile-time switch: the two kinds of step are separate loops below, so neither
-  // carries the other's registers).
-  auto step = [&](int s, auto cached_tag) __attribute__((always_inline)) {
-    constexpr bool cached = CACHE && decltype(cached_tag)::value;
-    f32x16 acc[RB][4];
-    const bool whole = CACHE && node0 + R <= n_nodes;      // uniform: every node of the block exists
-    if constexpr (cached) {
-      // gate pre-activations of the input part, in the accumulator's layout: for a fixed
-      // register the 32 lanes of a half-wavefront read 128 contiguous bytes of one node's row.
-      // One base address per group of four registers (rows 8 q + 4 (lane / 32) + 0..3): the
-      // sixteen loads of a group differ by constants that fit the instruction's offset field.
+  // Gate pre-activations of the input part of step s from the kept projections, in the
+  // accumulator's layout: for a fixed register the 32 lanes of a half-wavefront read 128
+  // contiguous bytes of one node's row. One base address per group of four registers (rows
+  // 8 q + 4 (lane / 32) + 0..3): the sixteen loads of a group differ by constants that fit
+  // the instruction's offset field. Only issues the loads.
+  const bool whole = CACHE && node0 + R <= n_nodes;      // uniform: every node of the block exists
+  auto load_gates = [&](int s, f32x16 (&acc)[RB][4]) __attribute__((always_inline)) {
       const float* P = proj.p[s];
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
@@ -275,6 +274,17 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
             }
           }
         }
+  };
+  // One time step. cached_tag: whether the step's input part comes from the kept projections
+  // (a compile-time switch: the two kinds of step are separate loops below, so neither
+  // carries the other's registers).
+  auto step = [&](int s, auto cached_tag) __attribute__((always_inline)) {
+    constexpr bool cached = CACHE && decltype(cached_tag)::value;
+    f32x16 acc[RB][4];
+    if constexpr (cached) {
+      // (requesting step s + 1's gates a step ahead, into a second set of accumulators, was
+      // tried for the instance that runs from kept projections only: 36 registers spill)
+      load_gates(s, acc);
     } else {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
@@ -472,7 +482,8 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
   };
   if constexpr (CACHE)
     for (int s = 0; s < s_first; ++s) step(s, std::true_type{});
-  for (int s = s_first; s < tau; ++s) step(s, std::false_type{});
+  if constexpr (XPART)
+    for (int s = s_first; s < tau; ++s) step(s, std::false_type{});
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
@@ -487,6 +498,11 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 }  // namespace
 
 namespace sat {
+
+// lstm_proj.hip: P = x Wx^T for one slot, bit-compatible with the input part accumulated here
+bool lstm_proj_serves(int32_t d, int32_t d_s, int es_x, int64_t n_nodes);
+sat_status launch_lstm_proj(const void* X, int64_t n_rows_slot, int64_t ld_slot, const int32_t* ids,
+                            int64_t n_nodes, const void* WxP, float* P, hipStream_t st);
 
 // Bytes of workspace the split-weight copies need (0 if this path does not serve d_s).
 int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
@@ -521,7 +537,25 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
   ProjPtrs pp;
   for (int s = 0; s < kMaxTau; ++s) pp.p[s] = (proj && s < tau) ? proj[s] : nullptr;
   pp.n_valid = proj ? n_proj_valid : 0;
-  const int64_t blocks = (n_nodes + R - 1) / R;
+  // Steady state of a sliding window: every slot but the newest has its projection. The newest
+  // one's is then made by the weights-in-registers product kernel (same sums, bit for bit),
+  // and the time steps run from the kept matrices alone: no x tile, no Wx tile in this kernel.
+  if (proj && save == nullptr && n_proj_valid == tau - 1 && tau >= 2 && proj[tau - 1] != nullptr &&
+      lstm_proj_serves(d, d_s, es_x, n_nodes)) {
+    rc = launch_lstm_proj(slot_ptrs[tau - 1], n_rows_slot, ld_slot, ids, n_nodes, WxP, proj[tau - 1], st);
+    if (rc != SAT_OK) return rc;
+    pp.n_valid = tau;
+  }
+  if (pp.n_valid == tau && proj && d_s == 64 && es_x == 4) {   // the time steps alone
+    // (64 nodes and four wavefronts per workgroup, two workgroups per compute unit, was measured
+    // slower: 1.38 against 1.0 ms; the weight tiles are then staged twice as often per node)
+    const int64_t blocks = (n_nodes + kR - 1) / kR;
+    if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
+    lstm_mx_kernel<64, 4, 8, true, kR, false><<<dim3(static_cast<unsigned>(blocks)), dim3(512), 0, st>>>(
+        sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S, save, pp);
+    return sat::check_launch();
+  }
+  const int64_t blocks = (n_nodes + kR - 1) / kR;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
   const dim3 grid(static_cast<unsigned>(blocks));
 #define SAT_LSTM_MX(DS, ESX, WAVES)                                                            \

@@ -32,6 +32,8 @@ def _graph(kind, seed=0):
         g = syn.make_graph(cfg, np.random.default_rng(syn.substreams(seed)["graph"]))
     elif kind == "powerlaw":
         g = syn.chung_lu_planted_graph(30_000, 4, 13.0, 2.1, 0.15, np.random.default_rng(seed))
+    elif kind == "powerlaw_big":    # 78k local + halo rows in partition 0
+        g = syn.chung_lu_planted_graph(170_000, 4, 13.0, 2.1, 0.15, np.random.default_rng(seed))
     elif kind == "onepart":
         g = syn.chung_lu_planted_graph(3_000, 1, 9.0, 2.3, 0.0, np.random.default_rng(seed))
     elif kind == "hub":

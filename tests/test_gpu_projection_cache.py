@@ -27,9 +27,16 @@ def env():
 @pytest.mark.parametrize("kind,d,d_s,tau,use_ids,bf16", [
     ("tiny", 32, 32, 2, False, False), ("powerlaw", 256, 64, 2, True, False),
     ("powerlaw", 100, 64, 3, True, False), ("hub", 40, 32, 3, False, False),
-    ("powerlaw", 256, 64, 2, True, True), ("tiny", 64, 32, 3, True, True)])
+    ("powerlaw", 256, 64, 2, True, True), ("tiny", 64, 32, 3, True, True),
+    # enough rows, d = 256 and d_s = 64: in the steady state (every slot but the newest kept) the
+    # newest slot's projection comes from the product kernel of its own and the time steps run
+    # from kept matrices only; the row count is not a multiple of 32
+    ("powerlaw_big", 256, 64, 2, True, False), ("powerlaw_big", 256, 64, 3, False, False),
+    ("powerlaw_big_bad_ids", 256, 64, 2, True, False)])
 def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
     sat, gu, torch = env
+    bad_ids = kind.endswith("_bad_ids")
+    kind = kind.replace("_bad_ids", "")
     print("[case] predict_cached %s d=%d d_s=%d tau=%d ids=%s bf16=%s" % (kind, d, d_s, tau, use_ids, bf16),
           flush=True)
     g = _graph(kind)
@@ -42,6 +49,8 @@ def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
     if use_ids:
         ids = np.concatenate([v["local_ids"], v["halo_ids"]]).astype(np.int32)
         n_rows = g.N
+        if bad_ids:     # ids outside the table: such rows read as zeros in either call
+            ids[[3, 40, n_l - 1, n_l + 7, n_bar - 1]] = [-1, g.N, -5, g.N + 100, 2**31 - 1]
     else:
         ids, n_rows = None, n_bar
     # tau + 1 epochs: two consecutive windows that share tau - 1 slots
@@ -88,13 +97,16 @@ def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
     used_d = torch.from_numpy(used).to(gu.DEV)
     for s in range(1, tau):
         assert torch.isfinite(proj[s][:, used_d]).all() and torch.isnan(proj[s][:, ~used_d]).all()
+    if bad_ids:
+        ok = (ids >= 0) & (ids < g.N)
     # the kept matrix is x Wx^T of the slot (no bias), node-major: against the oracle's product
-    x1 = tabs[1][ids] if use_ids else tabs[1]
+    x1 = (tabs[1][np.where(ok, ids, 0)] * ok[:, None] if bad_ids else tabs[1][ids]) if use_ids else tabs[1]
     from tests import gpu_util
     # (against bfloat16 rows the weights enter to 16 bits, two bf16 pieces: 2^-17 per product)
     gpu_util.assert_close(proj[1].cpu().numpy()[:, used], (x1.astype(np.float64) @ p["Wx"].astype(np.float64).T)[:, used],
                           1e-4 if bf16 else 1e-5, "kept input projection")
     # next window: every number of valid leading slots gives the same bits as the plain call
+    newest = None
     for n_valid in range(tau - 1, -1, -1):
         pr = [q.clone() for q in proj[1:]]
         out = fresh_out()
@@ -104,8 +116,15 @@ def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
         assert torch.equal(out.view(torch.int16 if bf16 else torch.int32),
                            ref2.view(torch.int16 if bf16 else torch.int32)), "n_valid = %d" % n_valid
         assert torch.isfinite(pr[-1][:, used_d]).all()      # the newest slot's matrix has been written
+        # ... with the same bits whichever kernel made it (the LSTM itself, or the product kernel
+        # that serves the steady state of large inputs)
+        if newest is None:
+            newest = pr[-1][:, used_d].clone()
+        assert torch.equal(pr[-1][:, used_d].view(torch.int32), newest.view(torch.int32)), "n_valid = %d" % n_valid
         for s in range(1, tau - 1):                         # re-written ones equal the kept ones
             assert torch.equal(pr[s], proj[1 + s])
+    if bad_ids:
+        return
     # and the oracle, once (the plain call is held to it elsewhere; this ties the cached one too)
     win = [t[ids] if use_ids else t for t in tabs[1:]]
     refo = orc.predict(v, p, win)
