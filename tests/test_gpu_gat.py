@@ -196,14 +196,17 @@ def _compare_grad(gu, got, ref, rtol, what, exact_masks, scale=None):
     """Element-wise when no ReLU decision of the step was within rounding of zero;
     otherwise (either decision is valid there, and it reaches the rows around it)
     a norm-wise bound, relative to `scale` (the norm of the sum of the magnitudes of
-    the terms the result is formed from; default: the norm of the reference)."""
+    the terms the result is formed from; default: the norm of the reference). One flipped
+    decision changes one element of a gradient by its whole magnitude, which for the 2 * 10^7
+    elements of the medium case is already 2 * 10^-4 of the norm: the bound leaves room for a
+    handful of them."""
     if exact_masks:
         gu.assert_close(got, ref, rtol, what)
     else:
         ref = np.asarray(ref, np.float64)
         scale = np.linalg.norm(ref) if scale is None else scale
         err = np.linalg.norm(np.asarray(got, np.float64) - ref)
-        assert err < 20 * rtol * scale, "%s: |diff| %g, scale %g" % (what, err, scale)
+        assert err < 60 * rtol * scale, "%s: |diff| %g, scale %g" % (what, err, scale)
 
 
 @pytest.mark.parametrize("name,bf16", [("tiny", False), ("medium", False), ("tiny", True)])
