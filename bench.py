@@ -108,6 +108,9 @@ def main():
                          "history slot of hidden layer 1 at this many decimal places: plan + encode "
                          "of the partition's local + halo rows, decode of the halo rows through the "
                          "id list; reported under \"codec\"")
+    ap.add_argument("--coded-chunk-rows", type=int, default=None, metavar="ROWS",
+                    help="with --coded-ring: decode the predictor's window this many rows at a time "
+                         "(dense scratch of tau * ROWS rows instead of tau * n_bar)")
     ap.add_argument("--coded-ring", type=int, default=None, metavar="DECIMALS",
                     help="keep the history ring coded (compression codec at this many decimal "
                          "places) inside the step: the predictor's window is decoded from the "
@@ -184,6 +187,7 @@ def main():
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
                         predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring,
+                        coded_chunk_rows=args.coded_chunk_rows,
                         predict_ahead=predict_ahead,
                         transform_first=False if (args.no_transform_first or gat_flag) else "auto",
                         projection_cache=False if (args.no_projection_cache or gat_flag or args.predictor_train)

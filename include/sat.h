@@ -205,6 +205,38 @@ sat_status sat_predict(const sat_part_view* pv, const sat_predictor* w, const vo
                        int64_t ld, int32_t dtype, void* workspace, int64_t workspace_bytes,
                        void* stream);
 
+/* The two halves of sat_predict as calls of their own (Sec. "Embedding Predictor", Eq. (7)),
+ * for callers that cannot hold the whole window dense at once (a coded ring that is decoded a
+ * range of rows at a time): the LSTM is row-wise, only the hop needs every node's state.
+ *
+ * sat_predict_states: step 1 of sat_predict for n_nodes rows: S[k, 0:d_s) (device, fp32,
+ * dense [n_nodes, d_s], 16-byte aligned) = last LSTM state over the tau slots of node k, whose
+ * row inside a slot is ids[k] if ids != NULL, else k. For a range of nodes the caller passes
+ * ids + begin (or slots that hold just that range) and S + begin * d_s. Same restrictions on
+ * d, d_s and dtype as sat_predict; w->bypass set is SAT_EINVAL.
+ * Workspace: sat_predict_states_workspace_bytes(d, d_s), 256-byte aligned device memory (the
+ * re-laid weights; calls on one stream may share it).
+ *
+ * sat_predict_hop: steps 2 and 3 of sat_predict from S [n_local + n_halo, d_s] (local nodes
+ * first): Hbar[n_local + u, 0:d) = newest[row(u), 0:d) + Delta_u, row(u) = halo_ids[u] if
+ * halo_ids != NULL (device int32 [n_halo]) else u; rows outside [0, n_rows_newest) leave the
+ * output row untouched. `newest` [*, ld_newest] holds the newest cached embedding of the HALO
+ * nodes and may be the halo rows of Hbar themselves (newest == Hbar + n_local * ld elements,
+ * ld_newest == ld, halo_ids == NULL; d_s <= 64 only): the sum is then formed in place. Any
+ * other overlap of the two is SAT_EINVAL.
+ * Workspace: sat_predict_hop_workspace_bytes(n_halo, d_s), 256-byte aligned device memory.
+ */
+int64_t sat_predict_states_workspace_bytes(int32_t d, int32_t d_s);
+sat_status sat_predict_states(const sat_predictor* w, const void* const* slots,
+                              int64_t n_rows_slot, int64_t ld_slot, const int32_t* ids,
+                              int64_t n_nodes, int32_t dtype, float* S, void* workspace,
+                              int64_t workspace_bytes, void* stream);
+int64_t sat_predict_hop_workspace_bytes(int64_t n_halo, int32_t d_s);
+sat_status sat_predict_hop(const sat_part_view* pv, const sat_predictor* w, const float* S,
+                           const void* newest, int64_t n_rows_newest, int64_t ld_newest,
+                           const int32_t* halo_ids, void* Hbar, int64_t ld, int32_t dtype,
+                           void* workspace, int64_t workspace_bytes, void* stream);
+
 /* sat_predict with the LSTM's input projections kept between calls. Consecutive windows of
  * the sliding window of Sec. "Embedding Predictor" share all but their newest slot, and
  * x_s Wx^T of a slot does not depend on the slot's position in the window; so the caller

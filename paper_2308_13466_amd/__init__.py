@@ -5,7 +5,8 @@ used by callers for device memory and streams, never for the arithmetic.
 """
 from .binding import (  # noqa: F401
     SatError, lib, lib_path, PartView, Predictor,
-    partition_view_build, history_gather, history_gather_add, history_push, predict, predict_cached,
+    partition_view_build, history_gather, history_gather_add, history_push, predict, predict_cached, predict_states, predict_states_workspace_bytes,
+    predict_hop, predict_hop_workspace_bytes,
     predict_workspace_bytes, predictor_train_workspace_bytes, predictor_grad, sgd_update,
     history_compress_workspace_bytes, history_compress_plan, history_compress_encode,
     history_decompress, spmm_fwd, spmm_bwd, spmm_workspace_bytes,

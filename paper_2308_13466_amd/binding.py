@@ -55,6 +55,10 @@ _SIGNATURES = {
     "sat_history_push": (_i32, [_vp, _i64, _i64, _vp, _i64, _i32, _vp, _i64, _i32, _vp]),
     "sat_predict_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
     "sat_predict": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
+    "sat_predict_states_workspace_bytes": (_i64, [_i32, _i32]),
+    "sat_predict_states": (_i32, [_vp, _vp, _i64, _i64, _vp, _i64, _i32, _vp, _vp, _i64, _vp]),
+    "sat_predict_hop_workspace_bytes": (_i64, [_i64, _i32]),
+    "sat_predict_hop": (_i32, [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i64, _vp]),
     "sat_predict_cached": (_i32, [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _i64, _i32, _vp, _i32, _vp, _i64,
                                   _vp]),
     "sat_predictor_train_workspace_bytes": (_i64, [_i64, _i64, _i32, _i32, _i32]),
@@ -230,6 +234,29 @@ def predict(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, dtype=F32, worksp
     _check(lib().sat_predict(pv.ref, w.ref, C.addressof(arr), n_rows_slot, ld_slot, _ptr(ids),
                              _ptr(Hbar), ld, dtype, _ptr(workspace), workspace_bytes, stream),
            "sat_predict")
+
+
+def predict_states_workspace_bytes(d, d_s):
+    return lib().sat_predict_states_workspace_bytes(d, d_s)
+
+
+def predict_states(w, slots, n_rows_slot, ld_slot, ids, n_nodes, S, dtype=F32, workspace=None,
+                   workspace_bytes=0, stream=None):
+    arr = (C.c_void_p * len(slots))(*[_ptr(s) for s in slots])
+    _check(lib().sat_predict_states(w.ref, C.addressof(arr), n_rows_slot, ld_slot, _ptr(ids), n_nodes,
+                                    dtype, _ptr(S), _ptr(workspace), workspace_bytes, stream),
+           "sat_predict_states")
+
+
+def predict_hop_workspace_bytes(n_halo, d_s):
+    return lib().sat_predict_hop_workspace_bytes(n_halo, d_s)
+
+
+def predict_hop(pv, w, S, newest, n_rows_newest, ld_newest, halo_ids, Hbar, ld, dtype=F32,
+                workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().sat_predict_hop(pv.ref, w.ref, _ptr(S), _ptr(newest), n_rows_newest, ld_newest,
+                                 _ptr(halo_ids), _ptr(Hbar), ld, dtype, _ptr(workspace),
+                                 workspace_bytes, stream), "sat_predict_hop")
 
 
 def predict_cached(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, proj, n_proj_valid, dtype=F32,

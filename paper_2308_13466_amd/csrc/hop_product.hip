@@ -29,12 +29,14 @@ using namespace sat::mx;
 constexpr int kTilesPerBlock = 8;   // 32-row tiles per workgroup (256 rows)
 
 // ESO = bytes per element of the residual rows and of the output (4: fp32, 2: bf16, the
-// sum rounded to nearest-even once); Agg and Wg are fp32 either way.
+// sum rounded to nearest-even once); Agg and Wg are fp32 either way. `add` and `out` may be the
+// same matrix with row(m) = m (a thread reads the 16 bytes it later writes, and no others of
+// that row), so neither is declared free of aliases.
 template <int DS, int ESO>
 __global__ __launch_bounds__(512, 4) void hop_product_kernel(
     const float* __restrict__ Agg, int64_t M, const float* __restrict__ Wg, int d,
-    const void* __restrict__ add, int64_t ld_add, const int32_t* __restrict__ add_ids,
-    int64_t add_base, int64_t add_rows, void* __restrict__ out, int64_t ld_out) {
+    const void* add, int64_t ld_add, const int32_t* __restrict__ add_ids,
+    int64_t add_base, int64_t add_rows, void* out, int64_t ld_out) {
   constexpr int NP = 3;
   constexpr int KC = DS / 16;                       // 16-wide k chunks
   constexpr int NCH = DS / 32;                      // 32-wide staging chunks

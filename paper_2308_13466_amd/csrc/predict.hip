@@ -263,6 +263,77 @@ extern "C" int64_t sat_predict_workspace_bytes(int64_t n_local, int64_t n_halo, 
 
 namespace {
 
+// LSTM states of n_nodes rows (the first half of sat_predict): S [n_nodes, d_s]. wts: room for
+// the re-laid weights (bf16 pieces for d_s <= 64, k-major fp32 copies of Wx, Wh for d_s = 128).
+sat_status run_states(const sat_predictor* w, const void* const* slots, int64_t n_rows_slot,
+                      int64_t ld_slot, const int32_t* ids, int64_t n_bar, int es, float* S, float* WxT,
+                      float* const* proj, int32_t n_proj_valid, hipStream_t st) {
+  const int d = w->d;
+  sat_status rc;
+  if (proj) {
+    if (w->d_s > 64) return SAT_EUNSUPPORTED;      // only the split-bf16 LSTM keeps projections
+    if (n_proj_valid < 0 || n_proj_valid >= w->tau) return SAT_EINVAL;   // the newest slot is always new
+    for (int s = 0; s < w->tau; ++s)
+      if ((s < n_proj_valid && !proj[s]) || (reinterpret_cast<uintptr_t>(proj[s]) & 3u)) return SAT_EINVAL;
+  }
+  if (w->d_s <= 64) {
+    rc = sat::launch_lstm_mx(slots, es, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->d_s, w->Wx,
+                             w->Wh, w->b, S, WxT, st, nullptr, proj, n_proj_valid);
+  } else {
+    float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
+    const int nb = 4 * w->d_s;
+    transpose_kernel<<<dim3((nb * d + 255) / 256), dim3(256), 0, st>>>(w->Wx, nb, d, WxT);
+    transpose_kernel<<<dim3((nb * w->d_s + 255) / 256), dim3(256), 0, st>>>(w->Wh, nb, w->d_s, WhT);
+    if ((rc = sat::check_launch()) != SAT_OK) return rc;
+    SlotPtrs sp;
+    for (int s = 0; s < kMaxTau; ++s)
+      sp.p[s] = s < w->tau ? static_cast<const float*>(slots[s]) : nullptr;
+    constexpr int rows = 32;  // nodes per workgroup of lstm_kernel<128>
+    const int64_t blocks = (n_bar + rows - 1) / rows;
+    lstm_kernel<128><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
+        sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, WxT, WhT, w->b, S);
+    rc = sat::check_launch();
+  }
+  return rc;
+}
+
+// The hop (second half of sat_predict): halo_out[u, :] = add[row(u), :] + Agg[u, :] Wg with
+// Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]], row(u) = add_ids ? add_ids[u] : add_base + u.
+sat_status run_hop(const sat_part_view* pv, const sat_predictor* w, const float* S, float* Agg,
+                   const void* newest, int64_t n_rows_slot, int64_t ld_slot, const int32_t* add_ids,
+                   int64_t add_base, void* halo_out, int64_t ld, int es, hipStream_t st) {
+  const int d = w->d;
+  sat_status rc;
+  // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
+  rc = sat::launch_spmm(pv->h_colptr, nullptr, pv->h_row, pv->h_val, S, w->d_s,
+                        pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, 4, pv->h_self, pv->n_local,
+                        pv->nnz_halo, st);
+  if (rc != SAT_OK) return rc;
+  // hop, part 2: Hbar[n_local + u, :] = newest[row(u), :] + Agg[u, :] Wg
+  {
+    const int64_t gx = (pv->n_halo + sat::mx::BM - 1) / sat::mx::BM;
+    const dim3 grid(static_cast<unsigned>(gx),
+                    static_cast<unsigned>((d + sat::mx::BN - 1) / sat::mx::BN), 1);
+    const sat::mx::Operand a{Agg, static_cast<int64_t>(w->d_s), nullptr, 0};
+    const sat::mx::Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
+    const sat::mx::EpiArgs ep{0, newest, ld_slot, add_ids, add_base,
+                              n_rows_slot};
+    if (w->d_s <= 64)
+      return sat::launch_hop_product(Agg, pv->n_halo, w->d_s, w->Wg, d, newest, ld_slot,
+                                     add_ids, add_base, n_rows_slot,
+                                     halo_out, ld, es, st);
+    if (es == 4)
+      sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
+                           sat::mx::kStoreAddRows, 4>
+          <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
+    else   // fp32 aggregate and weights, bf16 residual rows and output
+      sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
+                           sat::mx::kStoreAddRows, 2>
+          <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
+  }
+  return sat::check_launch();
+}
+
 // sat_predict; with proj != nullptr the input projections of the window's slots are read from /
 // written to the caller's cache (sat_predict_cached).
 sat_status predict_impl(const sat_part_view* pv, const sat_predictor* w, const void* const* slots,
@@ -308,61 +379,10 @@ sat_status predict_impl(const sat_part_view* pv, const sat_predictor* w, const v
   float* S = static_cast<float*>(workspace);
   float* Agg = S + round_up(n_bar * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
   float* WxT = Agg + round_up(pv->n_halo * static_cast<int64_t>(w->d_s) * 4, 256) / 4;
-  sat_status rc;
-  if (proj) {
-    if (w->d_s > 64) return SAT_EUNSUPPORTED;      // only the split-bf16 LSTM keeps projections
-    if (n_proj_valid < 0 || n_proj_valid >= w->tau) return SAT_EINVAL;   // the newest slot is always new
-    for (int s = 0; s < w->tau; ++s)
-      if ((s < n_proj_valid && !proj[s]) || (reinterpret_cast<uintptr_t>(proj[s]) & 3u)) return SAT_EINVAL;
-  }
-  if (w->d_s <= 64) {
-    rc = sat::launch_lstm_mx(slots, es, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, w->d_s, w->Wx,
-                             w->Wh, w->b, S, WxT, st, nullptr, proj, n_proj_valid);
-  } else {
-    float* WhT = WxT + round_up(static_cast<int64_t>(d) * 4 * w->d_s * 4, 256) / 4;
-    const int nb = 4 * w->d_s;
-    transpose_kernel<<<dim3((nb * d + 255) / 256), dim3(256), 0, st>>>(w->Wx, nb, d, WxT);
-    transpose_kernel<<<dim3((nb * w->d_s + 255) / 256), dim3(256), 0, st>>>(w->Wh, nb, w->d_s, WhT);
-    if ((rc = sat::check_launch()) != SAT_OK) return rc;
-    SlotPtrs sp;
-    for (int s = 0; s < kMaxTau; ++s)
-      sp.p[s] = s < w->tau ? static_cast<const float*>(slots[s]) : nullptr;
-    constexpr int rows = 32;  // nodes per workgroup of lstm_kernel<128>
-    const int64_t blocks = (n_bar + rows - 1) / rows;
-    lstm_kernel<128><<<dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st>>>(
-        sp, w->tau, n_rows_slot, ld_slot, ids, n_bar, d, WxT, WhT, w->b, S);
-    rc = sat::check_launch();
-  }
+  sat_status rc = run_states(w, slots, n_rows_slot, ld_slot, ids, n_bar, es, S, WxT, proj, n_proj_valid, st);
   if (rc != SAT_OK) return rc;
-
-  // hop, part 1: Agg[u] = A_hat[u,u] S[n_local + u] + sum_k h_val[k] S[h_row[k]]
-  rc = sat::launch_spmm(pv->h_colptr, nullptr, pv->h_row, pv->h_val, S, w->d_s,
-                        pv->n_local, Agg, w->d_s, pv->n_halo, w->d_s, 4, pv->h_self, pv->n_local,
-                        pv->nnz_halo, st);
-  if (rc != SAT_OK) return rc;
-  // hop, part 2: Hbar[n_local + u, :] = newest[row(u), :] + Agg[u, :] Wg
-  {
-    const int64_t gx = (pv->n_halo + sat::mx::BM - 1) / sat::mx::BM;
-    const dim3 grid(static_cast<unsigned>(gx),
-                    static_cast<unsigned>((d + sat::mx::BN - 1) / sat::mx::BN), 1);
-    const sat::mx::Operand a{Agg, static_cast<int64_t>(w->d_s), nullptr, 0};
-    const sat::mx::Operand b{w->Wg, static_cast<int64_t>(d), nullptr, 0};
-    const sat::mx::EpiArgs ep{0, newest, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
-                              n_rows_slot};
-    if (w->d_s <= 64)
-      return sat::launch_hop_product(Agg, pv->n_halo, w->d_s, w->Wg, d, newest, ld_slot,
-                                     ids ? ids + pv->n_local : nullptr, pv->n_local, n_rows_slot,
-                                     halo_out, ld, es, st);
-    if (es == 4)
-      sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
-                           sat::mx::kStoreAddRows, 4>
-          <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
-    else   // fp32 aggregate and weights, bf16 residual rows and output
-      sat::mx::gemm_kernel<4, sat::mx::Layout::KContig, false, sat::mx::Layout::MNContig, false,
-                           sat::mx::kStoreAddRows, 2>
-          <<<grid, dim3(256), 0, st>>>(a, b, pv->n_halo, d, w->d_s, w->d_s, halo_out, ld, ep);
-  }
-  return sat::check_launch();
+  return run_hop(pv, w, S, Agg, newest, n_rows_slot, ld_slot, ids ? ids + pv->n_local : nullptr, pv->n_local,
+                 halo_out, ld, es, st);
 }
 
 }  // namespace
@@ -385,4 +405,83 @@ extern "C" sat_status sat_predict_cached(const sat_part_view* pv, const sat_pred
   if (!proj) return SAT_EINVAL;
   return predict_impl(pv, w, slots, n_rows_slot, ld_slot, ids, Hbar, ld, dtype, proj, n_proj_valid,
                       workspace, workspace_bytes, stream);
+}
+
+// ---- the two halves of sat_predict as calls of their own
+extern "C" int64_t sat_predict_states_workspace_bytes(int32_t d, int32_t d_s) {
+  if (d <= 0 || d_s <= 0) return 0;
+  const int64_t w_fp32 = round_up(static_cast<int64_t>(d) * 4 * d_s * 4, 256) +
+                         round_up(static_cast<int64_t>(d_s) * 4 * d_s * 4, 256);
+  const int64_t w_mx = sat::lstm_mx_workspace_bytes(d, d_s);
+  return w_mx > 0 ? w_mx : w_fp32;
+}
+
+extern "C" sat_status sat_predict_states(const sat_predictor* w, const void* const* slots,
+                                         int64_t n_rows_slot, int64_t ld_slot, const int32_t* ids,
+                                         int64_t n_nodes, int32_t dtype, float* S, void* workspace,
+                                         int64_t workspace_bytes, void* stream) {
+  if (!w || !slots || n_nodes < 0 || n_rows_slot < 0) return SAT_EINVAL;
+  if (w->d < 0 || w->tau < 1 || w->bypass) return SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
+  const int es = dtype == SAT_BF16 ? 2 : 4;
+  if (w->tau > kMaxTau || n_nodes > INT32_MAX) return SAT_EUNSUPPORTED;
+  const int d = w->d;
+  if (n_nodes == 0 || d == 0) return SAT_OK;
+  if (!S || ld_slot < d) return SAT_EINVAL;
+  for (int s = 0; s < w->tau; ++s)
+    if (!slots[s]) return SAT_EINVAL;
+  if (!w->Wx || !w->Wh || !w->b) return SAT_EINVAL;
+  if (w->d_s != 32 && w->d_s != 64 && w->d_s != 128) return SAT_EUNSUPPORTED;
+  if ((d % 4) != 0) return SAT_EUNSUPPORTED;
+  if (es == 2 && ((d % 8) != 0 || w->d_s > 64)) return SAT_EUNSUPPORTED;
+  if (((ld_slot * es) % 16) != 0 || !sat::aligned16(w->Wx) || !sat::aligned16(w->Wh) ||
+      (reinterpret_cast<uintptr_t>(S) & 15u))
+    return SAT_EALIGN;
+  for (int s = 0; s < w->tau; ++s)
+    if (!sat::aligned16(slots[s])) return SAT_EALIGN;
+  const int64_t need = sat_predict_states_workspace_bytes(d, w->d_s);
+  if (!workspace || workspace_bytes < need) return SAT_EWORKSPACE;
+  if (!sat::aligned256(workspace)) return SAT_EALIGN;
+  return run_states(w, slots, n_rows_slot, ld_slot, ids, n_nodes, es, S, static_cast<float*>(workspace),
+                    nullptr, 0, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int64_t sat_predict_hop_workspace_bytes(int64_t n_halo, int32_t d_s) {
+  if (n_halo < 0 || d_s <= 0) return 0;
+  return round_up(n_halo * static_cast<int64_t>(d_s) * 4, 256);
+}
+
+extern "C" sat_status sat_predict_hop(const sat_part_view* pv, const sat_predictor* w, const float* S,
+                                      const void* newest, int64_t n_rows_newest, int64_t ld_newest,
+                                      const int32_t* halo_ids, void* Hbar, int64_t ld, int32_t dtype,
+                                      void* workspace, int64_t workspace_bytes, void* stream) {
+  if (!pv || !w) return SAT_EINVAL;
+  if (pv->n_local < 0 || pv->n_halo < 0 || pv->nnz_halo < 0 || n_rows_newest < 0) return SAT_EINVAL;
+  if (w->d < 0 || w->bypass) return SAT_EINVAL;
+  if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
+  const int es = dtype == SAT_BF16 ? 2 : 4;
+  const int d = w->d;
+  if (pv->n_halo == 0 || d == 0) return SAT_OK;
+  if (!S || !newest || !Hbar || ld < d || ld_newest < d || !w->Wg) return SAT_EINVAL;
+  if (w->d_s != 32 && w->d_s != 64 && w->d_s != 128) return SAT_EUNSUPPORTED;
+  if ((d % 4) != 0) return SAT_EUNSUPPORTED;
+  if (es == 2 && ((d % 8) != 0 || w->d_s > 64)) return SAT_EUNSUPPORTED;
+  if (!sat::aligned16(Hbar) || !sat::aligned16(newest) || ((ld * es) % 16) != 0 ||
+      ((ld_newest * es) % 16) != 0 || !sat::aligned16(w->Wg) || (reinterpret_cast<uintptr_t>(S) & 15u))
+    return SAT_EALIGN;
+  if (!pv->h_colptr || !pv->h_self || (pv->nnz_halo > 0 && (!pv->h_row || !pv->h_val))) return SAT_EINVAL;
+  unsigned char* halo_out = static_cast<unsigned char*>(Hbar) + pv->n_local * ld * es;
+  // the residual rows may BE the output rows (row u onto row u); any other overlap is refused,
+  // and so is that one where the tile GEMM writes the output (d_s = 128)
+  const unsigned char* nb = static_cast<const unsigned char*>(newest);
+  const unsigned char* ne = nb + n_rows_newest * ld_newest * es;
+  const unsigned char* oe = halo_out + pv->n_halo * ld * es;
+  const bool overlap = nb < oe && halo_out < ne;
+  const bool in_place = nb == halo_out && ld_newest == ld && halo_ids == nullptr;
+  if (overlap && (!in_place || w->d_s > 64)) return SAT_EINVAL;
+  const int64_t need = sat_predict_hop_workspace_bytes(pv->n_halo, w->d_s);
+  if (!workspace || workspace_bytes < need) return SAT_EWORKSPACE;
+  if (!sat::aligned256(workspace)) return SAT_EALIGN;
+  return run_hop(pv, w, S, static_cast<float*>(workspace), newest, n_rows_newest, ld_newest, halo_ids, 0,
+                 halo_out, ld, es, static_cast<hipStream_t>(stream));
 }

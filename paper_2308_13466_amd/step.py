@@ -123,12 +123,21 @@ class PartitionStep:
           layer's fresh rows into the `own` part of the write slot. A push whose codes do
           not fit the part's capacity leaves the rows beyond it unwritten: coded_overflow()
           tells (the caller sizes the parts; see encode_rows).
+    coded_chunk_rows: with a coded ring, None (the whole window of a layer is decoded into
+          tau dense matrices of n_bar rows) or a row count: the window is decoded that many
+          rows at a time, each range goes through the LSTM at once (sat_predict_states; the
+          LSTM is row-wise) and only its d_s states are kept; the newest slot's halo rows are
+          decoded straight into the halo rows of Hbar_l, where the hop (sat_predict_hop) adds
+          its term in place. The dense scratch shrinks from tau * n_bar rows to tau * chunk
+          rows (at full Scale: 34 GB to 1 GB); every result keeps its bits.
     """
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
                  fused_pull=True, timers=None, dtype=B.F32, grad_tables=None, predict_every=1,
-                 coded=None, predict_ahead=False, transform_first=False, projection_cache=False):
+                 coded=None, predict_ahead=False, transform_first=False, projection_cache=False,
+                 coded_chunk_rows=None):
         dev = X_table.device
+        self.coded_chunk_rows = int(coded_chunk_rows) if (coded is not None and coded_chunk_rows) else None
         self.predict_ahead = bool(predict_ahead)
         L_ = len(dims) - 1
         if transform_first == "auto":     # worth it when the last layer narrows to half or less
@@ -189,11 +198,16 @@ class PartitionStep:
         ws_bytes += [B.dense_bwd_workspace_bytes(n_bar if (tf and l == L - 1) else n_l, dims[l], dims[l + 1])
                      for l in range(L)]
         for l in range(1, L):
-            if not predictors[l].bypass:
+            if not predictors[l].bypass and not self.coded_chunk_rows:   # (else: the two halves' own, below)
                 ws_bytes.append(B.predict_workspace_bytes(n_l, self.n_halo, dims[l],
                                                           predictors[l].d_s, tau))
         if coded is not None:
             ws_bytes.append(B.history_compress_workspace_bytes(n_l))
+        if self.coded_chunk_rows:
+            for l in range(1, L):
+                if not predictors[l].bypass:
+                    ws_bytes.append(B.predict_states_workspace_bytes(dims[l], predictors[l].d_s))
+                    ws_bytes.append(B.predict_hop_workspace_bytes(self.n_halo, predictors[l].d_s))
         self.ws_bytes = max(ws_bytes + [256])
         self.ws = torch.empty((self.ws_bytes + 3) // 4, **f32)
         self.proj = None
@@ -211,10 +225,15 @@ class PartitionStep:
             self._pred_done = None      # event: predictions for step self.t are in place
         if not fused_pull and L >= 2:
             # dense rows of one layer's window, shared by the hidden layers (a layer's pull
-            # and prediction are over before the next layer's pull starts)
-            flat = [torch.zeros(n_bar * max(self.ld[1:L]), **act) for _ in range(tau)]
-            self.window = [[f[:n_bar * self.ld[l]].view(n_bar, self.ld[l]) for f in flat]
+            # and prediction are over before the next layer's pull starts); with
+            # coded_chunk_rows: of one range of rows
+            n_win = min(n_bar, self.coded_chunk_rows) if self.coded_chunk_rows else n_bar
+            flat = [torch.zeros(n_win * max(self.ld[1:L]), **act) for _ in range(tau)]
+            self.window = [[f[:n_win * self.ld[l]].view(n_win, self.ld[l]) for f in flat]
                            if l >= 1 else None for l in range(L)]
+            if self.coded_chunk_rows:      # LSTM states of all rows of one layer
+                ds_max = max([predictors[l].d_s for l in range(1, L) if not predictors[l].bypass] + [1])
+                self.S = torch.zeros(n_bar * ds_max, **f32)
         # local rows of layer 0 are static: pulled once
         B.history_gather(X_table, X_table.shape[0], X_table.shape[1], self.local_table_ids,
                          n_l, dims[0], self.Hbar[0], self.ld[0], dtype=dtype, stream=self._stream())
@@ -271,10 +290,7 @@ class PartitionStep:
         for l in range(1, L if self.t % self.predict_every == 0 else 1):
             w = self.predictors[l]
             if self.coded is not None:
-                self._pull_coded(l, order, st)
-                self._timed("predict_l%d" % l, lambda: B.predict(
-                    self.pv, w, self.window[l], n_bar, ld[l], None, self.Hbar[l], ld[l], dtype=dt,
-                    workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+                self._predict_coded(l, order, self.ws, st)
                 continue
             slots = [self.hist[l][s] for s in order]
             n_rows, ld_t = slots[0].shape
@@ -391,11 +407,7 @@ class PartitionStep:
                 sp = self._side.cuda_stream
                 for l in range(1, self.L):
                     if self.coded is not None:      # decode the window, then predict from the dense rows
-                        self._pull_coded(l, order, sp)
-                        self._timed("predict_l%d" % l, lambda: B.predict(
-                            self.pv, self.predictors[l], self.window[l], self.n_bar, self.ld[l], None,
-                            self.Hbar[l], self.ld[l], dtype=self.dtype, workspace=self._ws_side,
-                            workspace_bytes=self.ws_bytes, stream=sp))
+                        self._predict_coded(l, order, self._ws_side, sp)
                         continue
                     self._timed("predict_l%d" % l, lambda: self._predict_in_place(l, order, self._ws_side, sp))
         self._pred_done = torch.cuda.Event()
@@ -441,6 +453,40 @@ class PartitionStep:
         self.t += 1
 
     # ------------------------------------------------------------ coded ring
+    def _predict_coded(self, l, order, ws, st):
+        """Predicted halo rows of hidden layer l from the coded ring: the whole window decoded
+        and sat_predict, or (coded_chunk_rows) a range of rows at a time."""
+        w = self.predictors[l]
+        if not self.coded_chunk_rows or w.bypass:
+            self._pull_coded(l, order, st)
+            self._timed("predict_l%d" % l, lambda: B.predict(
+                self.pv, w, self.window[l], self.n_bar, self.ld[l], None, self.Hbar[l], self.ld[l],
+                dtype=self.dtype, workspace=ws, workspace_bytes=self.ws_bytes, stream=st))
+            return
+        n_l, n_bar, d, ld, P = self.n_local, self.n_bar, self.dims[l], self.ld[l], self.coded.precision
+        C = self.coded_chunk_rows
+        S = self.S[:n_bar * w.d_s].view(n_bar, w.d_s)
+        # ranges of rows in local-then-halo order, none across the boundary between the two parts
+        ranges = [(b, min(b + C, n_l)) for b in range(0, n_l, C)] + \
+                 [(b, min(b + C, n_bar)) for b in range(n_l, n_bar, C)]
+        for b, e in ranges:
+            halo = b >= n_l
+            srcs = []
+            for k, s in enumerate(order):
+                slot = self.coded.slots[l][s]
+                codes, off = (slot.remote_codes, slot.remote_off[b - n_l:]) if halo else (slot.own_codes, slot.own_off[b:])
+                # the newest slot's halo rows are also the hop's residual: decoded where it adds its term
+                out = self.Hbar[l][b:e] if (halo and k == self.tau - 1) else self.window[l][k][:e - b]
+                self._timed("pull_l%d" % l, lambda: B.history_decompress(
+                    codes, off, e - b, None, e - b, d, P, out, ld, dtype=self.dtype, stream=st))
+                srcs.append(out)
+            self._timed("predict_l%d" % l, lambda: B.predict_states(
+                w, srcs, e - b, ld, None, e - b, S[b:], dtype=self.dtype, workspace=ws,
+                workspace_bytes=self.ws_bytes, stream=st))
+        self._timed("predict_l%d" % l, lambda: B.predict_hop(
+            self.pv, w, S, self.Hbar[l][n_l:], self.n_halo, ld, None, self.Hbar[l], ld, dtype=self.dtype,
+            workspace=ws, workspace_bytes=self.ws_bytes, stream=st))
+
     def _pull_coded(self, l, order, st):
         """Decode the tau slots of layer l, oldest first, into the dense window rows (local
         rows from the `own` part, halo rows from the `remote` part; a bypass predictor reads

@@ -37,7 +37,7 @@ def _upload(a, bf16, dev):
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
                    keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
                    backbone="gcn", coded_ring=None, own_headroom=1.5, predict_ahead=False,
-                   transform_first="auto", projection_cache="auto"):
+                   transform_first="auto", projection_cache="auto", coded_chunk_rows=None):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
@@ -50,6 +50,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     other sizes), the halo nodes' rows into the `remote` part (exact size) - and then freed.
     transform_first: see PartitionStep ("auto": the last layer is evaluated as P (Hbar W)
     when it narrows to half the width or less).
+    coded_chunk_rows: see PartitionStep (with coded_ring: rows of the window decoded at a time).
     projection_cache: see PartitionStep ("auto": when the matrices of all slots and hidden
     layers together stay under 8 GiB; the full Scale configuration would need 137 GB).
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
@@ -179,7 +180,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
                              fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
                              grad_tables=gt, predict_every=predict_every, coded=coded,
                              predict_ahead=predict_ahead, transform_first=transform_first,
-                             projection_cache=bool(projection_cache) and coded is None and fused_pull)
+                             projection_cache=bool(projection_cache) and coded is None and fused_pull,
+                             coded_chunk_rows=coded_chunk_rows)
     torch.cuda.synchronize()
     log("inputs resident in HBM: %.2f GB allocated (%.1fs)" % (
         torch.cuda.memory_allocated() / 1e9, time.time() - t0))

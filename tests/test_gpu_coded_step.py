@@ -374,3 +374,51 @@ def test_coded_ring_predictions_one_step_ahead_change_nothing(name):
         assert same(a, b), "buffer %d differs" % k
     for k, (a, b) in enumerate(zip(*halo)):
         assert same(a, b), "predicted halo rows of hidden layer %d differ" % (k + 1)
+
+
+@pytest.mark.parametrize("name,chunk,ahead", [("tiny", 777, False), ("medium", 10_000, False), ("medium", 30_011, True)])
+def test_coded_ring_window_decoded_a_range_of_rows_at_a_time(name, chunk, ahead):
+    """coded_chunk_rows: the window is decoded `chunk` rows at a time, each range goes through
+    the LSTM alone (sat_predict_states) and the hop adds its term in place on the newest
+    slot's halo rows (sat_predict_hop). Nothing but the size of the dense scratch may change:
+    every buffer after three steps, and the predictions of the fourth, equal bit for bit those
+    of the step that decodes the whole window (which the tests above hold to the oracle)."""
+    import torch
+    from paper_2308_13466_amd.workload import build_workload
+    print("[case] coded ring decoded %d rows at a time, %s, ahead=%s" % (chunk, name, ahead), flush=True)
+
+    def snapshot(st):
+        n_l = st.n_local
+        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
+        keep += [h[:n_l].clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
+        for l in range(1, st.L):
+            for slot in st.coded.slots[l]:
+                used = int(slot.own_off[-1].item())
+                keep += [slot.own_off.clone(), slot.own_codes[:used].clone()]
+        return keep
+
+    runs, halo = [], []
+    for c in (None, chunk):
+        wl = build_workload(name, coded_ring=2, predict_ahead=ahead, coded_chunk_rows=c)
+        st = wl.step
+        if c is not None:
+            assert st.window[1][0].shape[0] == min(chunk, st.n_bar)
+        for _ in range(3):
+            st.forward_backward()
+        torch.cuda.synchronize()
+        assert st.coded_overflow() == []
+        runs.append(snapshot(st))
+        if not ahead:
+            st.forward_backward()
+            torch.cuda.synchronize()
+        halo.append([h[st.n_local:].clone() for h in st.Hbar[1:]])
+        del wl, st
+
+    def same(a, b):
+        if a.dtype == torch.float32:
+            a, b = a.view(torch.int32), b.view(torch.int32)
+        return a.shape == b.shape and torch.equal(a, b)
+    for k, (a, b) in enumerate(zip(*runs)):
+        assert same(a, b), "buffer %d differs" % k
+    for k, (a, b) in enumerate(zip(*halo)):
+        assert same(a, b), "predicted halo rows of hidden layer %d differ" % (k + 1)
