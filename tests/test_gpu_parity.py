@@ -335,6 +335,45 @@ def test_predict_parity(env, kind, d, d_s, tau, use_ids):
     gu.sync()
     assert np.array_equal(Hb2.cpu().numpy()[n_l:, :d], newest)
     assert np.array_equal(Hb3.cpu().numpy()[n_l:, :d], newest)
+    # the two halves as calls of their own: states in two ranges of rows, then the hop with the
+    # residual rows (a) read through the halo ids from the table, (b) already in the halo rows
+    # of the output, summed in place - the same bits as the one call either way
+    if d_s <= 64:
+        S = torch.full((n_bar, d_s), -7.0, dtype=torch.float32, device=gu.DEV)
+        ws_s = gu.workspace(sat.predict_states_workspace_bytes(d, d_s))
+        cut = (n_bar // 3) | 1
+        for b, e in ((0, cut), (cut, n_bar)):
+            if use_ids:
+                sat.predict_states(w, slots_d, n_rows, ld, ids_d[b:], e - b, S[b:], workspace=ws_s,
+                                   workspace_bytes=ws_s.numel() * ws_s.element_size(), stream=gu.stream_ptr())
+            else:
+                sat.predict_states(w, [t[b:] for t in slots_d], e - b, ld, None, e - b, S[b:], workspace=ws_s,
+                                   workspace_bytes=ws_s.numel() * ws_s.element_size(), stream=gu.stream_ptr())
+        wsb_h = sat.predict_hop_workspace_bytes(n_h, d_s)
+        ws_h = gu.workspace(wsb_h)
+        Ha = gu.dev_empty(n_bar, ld, fill=-3.0)
+        if use_ids:
+            sat.predict_hop(pv, w, S, slots_d[-1], n_rows, ld, ids_d[n_l:], Ha, ld, workspace=ws_h,
+                            workspace_bytes=wsb_h, stream=gu.stream_ptr())
+        else:
+            sat.predict_hop(pv, w, S, slots_d[-1][n_l:], n_h, ld, None, Ha, ld, workspace=ws_h,
+                            workspace_bytes=wsb_h, stream=gu.stream_ptr())
+        Hi = gu.dev_empty(n_bar, ld, fill=-3.0)
+        Hi[n_l:, :d] = torch.from_numpy(np.ascontiguousarray(newest)).to(gu.DEV)
+        sat.predict_hop(pv, w, S, Hi[n_l:], n_h, ld, None, Hi, ld, workspace=ws_h, workspace_bytes=wsb_h,
+                        stream=gu.stream_ptr())
+        gu.sync()
+        assert np.array_equal(Ha.cpu().numpy().view(np.uint32), got.view(np.uint32))
+        assert np.array_equal(Hi.cpu().numpy().view(np.uint32), got.view(np.uint32))
+        # residual rows that overlap the output rows in any other way are refused
+        if n_h > 1:
+            with pytest.raises(sat.SatError) as e:
+                sat.predict_hop(pv, w, S, Hi[n_l + 1:], n_h - 1, ld, None, Hi, ld, workspace=ws_h,
+                                workspace_bytes=wsb_h, stream=gu.stream_ptr())
+            assert e.value.status == -1
+        with pytest.raises(sat.SatError) as e:
+            sat.predict_hop(pv, w, S, slots_d[-1], n_rows, ld, None, Ha, ld, workspace=None, workspace_bytes=0)
+        assert e.value.status == -4
 
 
 def test_predict_unsupported_hidden_size(env):
