@@ -153,7 +153,8 @@ def gat_layer_bwd(view, c, W, a_dst, a_src, slope, act, dH, store=None):
                 dOUT=dOUT)
 
 
-def gat_partition_step(view, X_local, X_halo, halo_hat, params, y, slope=0.2, store=None):
+def gat_partition_step(view, X_local, X_halo, halo_hat, params, y, slope=0.2, store=None,
+                       stale_grad=None):
     """Forward and backward of an L-layer GAT on one partition (Eq. 5 with the
     attention layer as f; Eq. 4 as the loss).
 
@@ -162,8 +163,15 @@ def gat_partition_step(view, X_local, X_halo, halo_hat, params, y, slope=0.2, st
     historical embeddings); layer 0 uses the true features X_halo.
     store: applied to every tensor kept in memory between calls (Z, H, the loss
     gradient, the masked gradient, dZ, dH_in); identity for fp32 storage.
+    stale_grad: None, or stale_grad[l] for l = 1..L-1 = [n_local, d_l]: what the other
+    partitions computed, one step ago, for the gradient reaching this partition's nodes
+    through THEIR halo copies (the second term of the appendix's SAT backward, G_H = (local
+    term) + P_out^T D~ W^T, carried over to this layer type: whatever the layer is, the term
+    is the other partitions' gradient with respect to their halo inputs); added to the local
+    term before it is kept and passed down.
     Returns dict with per-layer caches, loss, and per layer dW, da_dst, da_src,
-    dH_in (None for layer 0).
+    dH_in (None for layer 0) and dH_halo (this partition's gradient with respect to ITS halo
+    inputs of layer l, [n_halo, d_l]: what it would send to their owners; None for layer 0).
     """
     from .sat_oracle import loss_and_grad
     if store is None:
@@ -184,12 +192,17 @@ def gat_partition_step(view, X_local, X_halo, halo_hat, params, y, slope=0.2, st
     g = store(g)
     grads = [None] * L
     dH_in = [None] * L
+    dH_halo = [None] * L
     for l in range(L - 1, -1, -1):
         p = params[l]
         b = gat_layer_bwd(view, caches[l], p["W"], p["a_dst"], p["a_src"], slope,
                           1 if l < L - 1 else 0, g, store)
         grads[l] = b
         if l >= 1:
-            g = store(b["dHbar"][:n_local])
+            g = b["dHbar"][:n_local]
+            if stale_grad is not None:
+                g = store(g) + np.asarray(stale_grad[l], np.float64)
+            g = store(g)
             dH_in[l] = g
-    return dict(caches=caches, H=H, loss=loss, grads=grads, dH_in=dH_in)
+            dH_halo[l] = store(b["dHbar"][n_local:])
+    return dict(caches=caches, H=H, loss=loss, grads=grads, dH_in=dH_in, dH_halo=dH_halo)

@@ -53,7 +53,10 @@ def torch_gat_layer(mask, Hbar, W, a_dst, a_src, act, slope=SLOPE):
     return torch.relu(out) if act == 1 else out, alpha
 
 
-def torch_gat_step(mask, X_local, X_halo, halo_hat, params, y):
+def torch_gat_step(mask, X_local, X_halo, halo_hat, params, y, stale=None, halos=None):
+    """stale: optional per-layer [n_local, d_l] added to the gradient that reaches the local rows
+    of layer l's input - as a term <stale_l, h_l> of the objective, which has exactly that
+    gradient. halos: optional list that receives the halo inputs (leaves with gradients)."""
     t = lambda a: torch.tensor(np.asarray(a, np.float64), dtype=torch.float64)
     leaves = []
     for p in params:
@@ -62,15 +65,20 @@ def torch_gat_step(mask, X_local, X_halo, halo_hat, params, y):
     hs = [h]
     m = torch.tensor(mask)
     L = len(params)
+    extra = 0.0
     for l in range(L):
-        halo = t(X_halo if l == 0 else halo_hat[l])
+        halo = t(X_halo if l == 0 else halo_hat[l]).requires_grad_(True)
+        if halos is not None:
+            halos.append(halo)
+        if stale is not None and l >= 1:
+            extra = extra + (t(stale[l]) * h).sum()
         hbar = torch.cat([h, halo], dim=0)
         h, _ = torch_gat_layer(m, hbar, leaves[l]["W"], leaves[l]["a_dst"], leaves[l]["a_src"],
                                1 if l < L - 1 else 0)
         h.retain_grad()
         hs.append(h)
     loss = torch.nn.functional.cross_entropy(h, torch.tensor(np.asarray(y, np.int64)))
-    loss.backward()
+    (loss + extra).backward()
     return loss.item(), leaves, hs
 
 
@@ -106,6 +114,36 @@ def test_forward_and_all_gradients_match_dense_torch_autograd(case):
                                    rtol=0, atol=1e-12)
         if l >= 1:   # gradient reaching the local rows of the layer's input
             np.testing.assert_allclose(st["dH_in"][l], hs[l].grad.numpy(), rtol=0, atol=1e-12)
+
+
+def test_halo_gradient_and_stale_term_match_dense_torch_autograd(case):
+    """What the step returns for its halo inputs is the objective's gradient with respect to
+    them, and a stale term added to the gradient at the local rows of a layer's input reaches
+    every quantity below it as an extra term <stale_l, h_l> of the objective would."""
+    c = case
+    L = len(c["params"])
+    n_l = c["view"]["n_local"]
+    rng = np.random.default_rng(5)
+    stale = [None] + [rng.normal(0, 0.3, (n_l, c["dims"][l])) for l in range(1, L)]
+    st = gat.gat_partition_step(c["view"], c["X_local"], c["X_halo"], c["halo_hat"], c["params"],
+                                c["y"], SLOPE, stale_grad=stale)
+    halos = []
+    loss, leaves, hs = torch_gat_step(dense_mask(c["view"]), c["X_local"], c["X_halo"],
+                                      c["halo_hat"], c["params"], c["y"], stale=stale, halos=halos)
+    assert abs(st["loss"] - loss) < 1e-12
+    for l in range(L):
+        np.testing.assert_allclose(st["grads"][l]["dW"], leaves[l]["W"].grad.numpy(), rtol=0, atol=1e-12)
+        np.testing.assert_allclose(st["grads"][l]["da_src"], leaves[l]["a_src"].grad.numpy(),
+                                   rtol=0, atol=1e-12)
+        if l >= 1:
+            # (autograd's h.grad holds the stale term as well: it is part of the objective there)
+            np.testing.assert_allclose(st["dH_in"][l], hs[l].grad.numpy(), rtol=0, atol=1e-12)
+            np.testing.assert_allclose(st["dH_halo"][l], halos[l].grad.numpy(), rtol=0, atol=1e-12)
+    # without the stale term the halo gradient is unchanged at the last hidden layer only
+    st0 = gat.gat_partition_step(c["view"], c["X_local"], c["X_halo"], c["halo_hat"], c["params"],
+                                 c["y"], SLOPE)
+    np.testing.assert_allclose(st0["dH_halo"][L - 1], st["dH_halo"][L - 1], rtol=0, atol=0)
+    assert np.abs(st0["dH_halo"][1] - st["dH_halo"][1]).max() > 1e-6
 
 
 def test_zero_attention_vectors_give_the_neighbourhood_mean(case):
