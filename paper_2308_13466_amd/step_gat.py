@@ -11,7 +11,10 @@ predicted embeddings for l >= 1, exactly as in the GCN step):
   backward  dZ_l, da_dst_l, da_src_l                          sat_gat_aggregate_bwd
             dW_l = Hbar_l^T dZ_l over all rows                sat_dense_bwd (dAGG = NULL)
             dH_l = dZ_l[local rows] W_l^T for l >= 1          sat_dense_bwd (dW = NULL)
-The halo rows are constants of the step: no gradient is returned for them.
+The halo rows are constants of the step: no gradient flows into them. With gradient
+tables (the stale-gradient term of the appendix's SAT backward) the gradient FOR them,
+dZ_l[halo rows] W_l^T, is formed as well and pushed into the write table at the halo
+nodes' rows, and the read table's rows of the local nodes are added to dH_l.
 """
 import torch
 
@@ -21,13 +24,12 @@ from .step import PartitionStep
 
 class GatPartitionStep(PartitionStep):
     """attn[l] = (a_dst, a_src, heads): device fp32 vectors [heads * d_head] of layer l,
-    d_head = dims[l + 1] / heads. Everything else as PartitionStep (gradient tables are
-    not supported with this backbone)."""
+    d_head = dims[l + 1] / heads. Everything else as PartitionStep."""
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, attn, predictors, y, tau,
-                 slope=0.2, timers=None, dtype=B.F32, predict_every=1):
+                 slope=0.2, timers=None, dtype=B.F32, predict_every=1, grad_tables=None):
         super().__init__(view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
-                         fused_pull=True, timers=timers, dtype=dtype, grad_tables=None,
+                         fused_pull=True, timers=timers, dtype=dtype, grad_tables=grad_tables,
                          predict_every=predict_every)
         dev = X_table.device
         self.attn = attn
@@ -119,6 +121,20 @@ class GatPartitionStep(PartitionStep):
                     self.dZ[l], ld[l + 1], None, 0, None, 0, self.Ws[l], self.ld_w[l], n_l,
                     dims[l], dims[l + 1], B.ACT_IDENTITY, None, 0, self.dH[l], ld[l], dtype=dt,
                     workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+                if self.grad_tables is not None:
+                    rd, wr = self.grad_tables[l][self.t % 2], self.grad_tables[l][(self.t + 1) % 2]
+                    if n_h > 0:
+                        dz_halo = self.dZ[l][n_l:]
+                        self._timed("dense_bwd_halo_l%d" % l, lambda: B.dense_bwd(
+                            dz_halo, ld[l + 1], None, 0, None, 0, self.Ws[l], self.ld_w[l], n_h,
+                            dims[l], dims[l + 1], B.ACT_IDENTITY, None, 0, self.dH_halo[l], ld[l], dtype=dt,
+                            workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+                        self._timed("grad_push_l%d" % l, lambda: B.history_push(
+                            wr, wr.shape[0], wr.shape[1], self.halo_table_ids, n_h, dims[l],
+                            self.dH_halo[l], ld[l], dtype=dt, stream=st))
+                    self._timed("grad_pull_l%d" % l, lambda: B.history_gather_add(
+                        rd, rd.shape[0], rd.shape[1], self.local_table_ids, n_l, dims[l],
+                        self.dH[l], ld[l], dtype=dt, stream=st))
         self.t += 1
 
     def edges_per_step(self):

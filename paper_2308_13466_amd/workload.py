@@ -171,7 +171,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
                    heads[l]) for l, (a, b) in enumerate(attn)]
         step = GatPartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, attn_d, preds, y_d, tau,
                                 timers=timers, dtype=B.BF16 if bf16 else B.F32,
-                                predict_every=predict_every)
+                                predict_every=predict_every, grad_tables=gt)
     else:
         if projection_cache == "auto":
             projection_cache = (not bypass and coded is None and fused_pull and d_s <= 64

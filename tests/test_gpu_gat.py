@@ -209,13 +209,19 @@ def _compare_grad(gu, got, ref, rtol, what, exact_masks, scale=None):
         assert err < 60 * rtol * scale, "%s: |diff| %g, scale %g" % (what, err, scale)
 
 
-@pytest.mark.parametrize("name,bf16", [("tiny", False), ("medium", False), ("tiny", True)])
-def test_gat_partition_step_two_steps(env, name, bf16):
+@pytest.mark.parametrize("name,bf16,stale", [("tiny", False, False), ("medium", False, False),
+                                             ("tiny", True, False), ("tiny", False, True),
+                                             ("tiny", True, True)])
+def test_gat_partition_step_two_steps(env, name, bf16, stale):
+    """stale: with seeded gradient tables standing in for what other partitions wrote (the
+    stale-gradient term of the appendix's SAT backward): dH_l = local term + the read table's
+    rows, the gradient for the halo inputs lands in the write table's halo rows as the step
+    computed it, every other row of the tables stays as it was."""
     sat, gu, torch = env
     from paper_2308_13466_amd import binding as B
     from paper_2308_13466_amd.step_gat import GatPartitionStep
     from tests.test_gpu_step import build_problem, fresh_history
-    _say("gat step %s bf16=%s" % (name, bf16))
+    _say("gat step %s bf16=%s stale=%s" % (name, bf16, stale))
     cfg, ss, g, X, Ws, omegas = build_problem(name)
     dims, L, tau = cfg["dims"], len(Ws), cfg["tau"]
     heads = syn.gat_heads(dims)
@@ -256,8 +262,16 @@ def test_gat_partition_step_two_steps(env, name, bf16):
         pd = {k: gu.to_dev(omegas[l][k]) for k in omegas[l]}
         keep.append(pd)
         preds.append(B.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], dims[l], cfg["d_s"], tau))
+    gt = gt_host = None
+    if stale:
+        rng = np.random.default_rng(9)
+        gt_host, gt = [None], [None]
+        for l in range(1, L):
+            pairs = [up((1e-3 * rng.standard_normal((g.N, dims[l]))).astype(np.float32), ld[l]) for _ in range(2)]
+            gt.append([p[0] for p in pairs])
+            gt_host.append([p[1].copy() for p in pairs])
     step = GatPartitionStep(view, dims, X_d, hist_d, gu.to_dev(ids), Ws_d, attn_d, preds,
-                            gu.to_dev(y), tau, slope=SLOPE, dtype=dt)
+                            gu.to_dev(y), tau, slope=SLOPE, dtype=dt, grad_tables=gt)
     params = [dict(W=Ws[l], a_dst=attn[l][0], a_src=attn[l][1]) for l in range(L)]
     for t in range(2):
         order = [(t + s) % tau for s in range(tau)]
@@ -266,8 +280,11 @@ def test_gat_partition_step_two_steps(env, name, bf16):
             win = [hist[l][s][ids] for s in order]
             hh = orc.predict(view, omegas[l], win)
             halo_hat.append(hh if store is None else store(hh))
+        stale_rows = None
+        if stale:
+            stale_rows = [None] + [gt_host[l][t % 2][view["local_ids"]] for l in range(1, L)]
         ref = gat.gat_partition_step(view, X[view["local_ids"]], X[view["halo_ids"]], halo_hat,
-                                     params, y, SLOPE, store=store)
+                                     params, y, SLOPE, store=store, stale_grad=stale_rows)
         for l in range(1, L):
             orc.history_push(hist[l][t % tau], view["local_ids"], ref["H"][l].astype(np.float32))
         step.forward_backward()
@@ -304,6 +321,18 @@ def test_gat_partition_step_two_steps(env, name, bf16):
             if l >= 1:
                 _compare_grad(gu, _download(gu, torch, step.dH[l], dims[l], bf16), ref["dH_in"][l],
                               rtol, "dH_in layer %d step %d" % (l, t), exact)
+        if stale:
+            wr = (t + 1) % 2
+            others = np.setdiff1d(np.arange(g.N), view["halo_ids"])
+            for l in range(1, L):
+                got_halo = _download(gu, torch, step.dH_halo[l], dims[l], bf16)
+                _compare_grad(gu, got_halo, ref["dH_halo"][l], rtol, "dH_halo layer %d step %d" % (l, t), exact)
+                tab = _download(gu, torch, gt[l][wr], dims[l], bf16)
+                assert np.array_equal(tab[view["halo_ids"]], got_halo)
+                assert np.array_equal(tab[others], gt_host[l][wr][others][:, :dims[l]])
+                # the next step reads what the oracle says this one wrote
+                w_rows = np.asarray(ref["dH_halo"][l], np.float32)
+                gt_host[l][wr][view["halo_ids"], :dims[l]] = orc.round_bf16(w_rows) if bf16 else w_rows
         # the ring received this step's embeddings
         for l in range(1, L):
             got = _download(gu, torch, hist_d[l][t % tau], dims[l], bf16)[view["local_ids"]]
