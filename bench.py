@@ -319,6 +319,7 @@ def main():
             add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * dl)
             add("dense_bwd", "dense_bwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * dl)
             add("dense_bwd", "dense_bwd_in_l%d" % l, "mfma", 2.0 * n_l * dims[l] * dl)
+            add("dense_bwd", "dense_bwd_halo_l%d" % l, "mfma", 2.0 * n_h * dims[l] * dl)   # (--stale-grad)
             add("gat_scores", "gat_scores_l%d" % l, "hbm", n_bar * (dl * s + 4 * K) + n_l * 4 * K)
             add("gat_fwd", "gat_fwd_l%d" % l, "hbm",
                 nnz * (4 + 4 * K + dl * s) + n_l * (8 + dl * s + 12 * K))

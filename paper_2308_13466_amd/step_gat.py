@@ -24,13 +24,15 @@ from .step import PartitionStep
 
 class GatPartitionStep(PartitionStep):
     """attn[l] = (a_dst, a_src, heads): device fp32 vectors [heads * d_head] of layer l,
-    d_head = dims[l + 1] / heads. Everything else as PartitionStep."""
+    d_head = dims[l + 1] / heads. Everything else as PartitionStep (gradient tables, the coded
+    ring and its decoding a range of rows at a time included)."""
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, attn, predictors, y, tau,
-                 slope=0.2, timers=None, dtype=B.F32, predict_every=1, grad_tables=None):
+                 slope=0.2, timers=None, dtype=B.F32, predict_every=1, grad_tables=None, coded=None,
+                 coded_chunk_rows=None):
         super().__init__(view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
                          fused_pull=True, timers=timers, dtype=dtype, grad_tables=grad_tables,
-                         predict_every=predict_every)
+                         predict_every=predict_every, coded=coded, coded_chunk_rows=coded_chunk_rows)
         dev = X_table.device
         self.attn = attn
         self.slope = float(slope)
@@ -67,6 +69,9 @@ class GatPartitionStep(PartitionStep):
         dt = self.dtype
         order = self.slot_order()
         for l in range(1, L if self.t % self.predict_every == 0 else 1):
+            if self.coded is not None:      # the window decoded from the codes
+                self._predict_coded(l, order, self.ws, st)
+                continue
             slots = [self.hist[l][s] for s in order]
             n_rows, ld_t = slots[0].shape
             self._timed("predict_l%d" % l, lambda: B.predict(
@@ -93,7 +98,9 @@ class GatPartitionStep(PartitionStep):
                 self.pv, self.Z[l], ld[l + 1], K, F, self.el[l], self.er[l], self.slope,
                 B.ACT_IDENTITY if last else B.ACT_RELU, out, ld[l + 1], self.stats[l], dtype=dt,
                 stream=st))
-            if not last:
+            if not last and self.coded is not None:
+                self._push_coded(l + 1, w_slot, st)
+            elif not last:
                 tab = self.hist[l + 1][w_slot]
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],

@@ -44,8 +44,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     of the history tables) and run the stale-gradient term of the backward.
     backbone: "gcn" (normalised-adjacency aggregation) or "gat" (graph attention; heads per
     layer from sat_synth.gat_heads, attention vectors from sat_synth.attention_vectors_f32).
-    coded_ring: None, or the number of decimals: the history ring is kept coded (GCN backbone
-    only). Every dense slot generated below is coded once - the local nodes' rows into the
+    coded_ring: None, or the number of decimals: the history ring is kept coded. Every dense
+    slot generated below is coded once - the local nodes' rows into the
     `own` part (allocated own_headroom times the size they need now, since later pushes have
     other sizes), the halo nodes' rows into the `remote` part (exact size) - and then freed.
     transform_first: see PartitionStep ("auto": the last layer is evaluated as P (Hbar W)
@@ -139,7 +139,6 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
         gt = [None] + [[torch.zeros_like(hist_d[l][0]) for _ in range(2)] for l in range(1, L)]
     coded = None
     if coded_ring is not None:
-        assert backbone == "gcn", "the coded ring is wired into the GCN step only"
         dt = B.BF16 if bf16 else B.F32
         st = torch.cuda.current_stream().cuda_stream
         cslots = [None]
@@ -171,7 +170,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
                    heads[l]) for l, (a, b) in enumerate(attn)]
         step = GatPartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, attn_d, preds, y_d, tau,
                                 timers=timers, dtype=B.BF16 if bf16 else B.F32,
-                                predict_every=predict_every, grad_tables=gt)
+                                predict_every=predict_every, grad_tables=gt, coded=coded,
+                                coded_chunk_rows=coded_chunk_rows)
     else:
         if projection_cache == "auto":
             projection_cache = (not bypass and coded is None and fused_pull and d_s <= 64

@@ -337,3 +337,50 @@ def test_gat_partition_step_two_steps(env, name, bf16, stale):
         for l in range(1, L):
             got = _download(gu, torch, hist_d[l][t % tau], dims[l], bf16)[view["local_ids"]]
             gu.assert_close(got, ref["H"][l], rtol, "pushed layer %d" % l)
+
+
+@pytest.mark.parametrize("name,chunk", [("tiny", None), ("medium", None), ("medium", 20_000)])
+def test_gat_step_with_a_coded_ring_equals_the_dense_ring_of_stored_values(env, name, chunk):
+    """The graph attention step reads its predictor window from a CODED ring (decoded whole, or
+    `chunk` rows at a time) and codes what it pushes. A coded ring is a dense ring that holds
+    the codec's stored values (orc.polyline_stored_value, pinned byte by byte elsewhere), so
+    the step must leave, bit for bit, what the dense-ring step leaves when its tables hold
+    those values - over two steps, the second one reading what the first one pushed."""
+    sat, gu, torch = env
+    from paper_2308_13466_amd.workload import build_workload
+    from tests.test_gpu_coded_step import _decode_part
+    prec = 2
+    _say("gat step, coded ring, %s, chunk=%s" % (name, chunk))
+    wc = build_workload(name, backbone="gat", coded_ring=prec, coded_chunk_rows=chunk)
+    wd = build_workload(name, backbone="gat")
+    sc, sd = wc.step, wd.step
+    n_l, dims, L, tau = sc.n_local, wc.dims, wc.L, wc.tau
+    local_ids = torch.from_numpy(wc.view["local_ids"].astype(np.int64)).to(gu.DEV)
+    for l in range(1, L):       # the dense ring starts from the stored values of the same tables
+        for s in range(tau):
+            stored = orc.polyline_stored_value(wd.hist_host[l][s][:, :dims[l]], prec)
+            sd.hist[l][s][:, :dims[l]] = torch.from_numpy(stored).to(gu.DEV)
+
+    def same(a, b):
+        return a.shape == b.shape and torch.equal(a.view(torch.int32), b.view(torch.int32))
+    for t in range(2):
+        sc.forward_backward()
+        sd.forward_backward()
+        gu.sync()
+        assert sc.coded_overflow() == []
+        assert same(sc.loss, sd.loss) and same(sc.logits, sd.logits), "step %d" % t
+        for l in range(L):
+            assert same(sc.dW[l], sd.dW[l]) and same(sc.da_dst[l], sd.da_dst[l]) and same(sc.da_src[l], sd.da_src[l])
+            if l >= 1:
+                assert same(sc.Hbar[l], sd.Hbar[l]), "Hbar %d step %d" % (l, t)
+                assert same(sc.dH[l], sd.dH[l]), "dH %d step %d" % (l, t)
+        # the push: the `own` part of the write slot decodes to the stored values of the fresh
+        # rows; the dense ring is then given those values, as a coded table would hand them back
+        for l in range(1, L):
+            slot = wc.coded.slots[l][t % tau]
+            got = _decode_part(sat, gu, slot.own_codes, slot.own_off, n_l, dims[l], sc.ld[l], prec)
+            fresh = gu.to_host(sc.Hbar[l], dims[l])[:n_l]
+            want = orc.polyline_stored_value(fresh, prec)
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+            tab = sd.hist[l][t % tau]
+            tab[local_ids, :dims[l]] = torch.from_numpy(want).to(gu.DEV)
