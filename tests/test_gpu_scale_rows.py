@@ -16,7 +16,12 @@ longest rows, the first row, the last row and a block of rows at the very end,
 i.e. the highest byte offsets of buffers that exceed 4 GiB at full size - and
 the oracle computes those outputs from them; the weight gradients and the loss
 are sums over ALL rows and are recomputed in full, in row chunks, by the
-oracle's own functions. Tolerance 2e-2 (bf16)."""
+oracle's own functions. Tolerance 2e-2 (bf16).
+
+On the same view the graph attention calls (scores, forward, backward; 4 heads x 64, bf16
+rows: Z and dZ of 17 GB each at full size) are run on inputs drawn on the device and held,
+on sampled rows, to the attention oracle run on the compact view of the rows those outputs
+depend on."""
 import os
 import time
 
@@ -79,6 +84,115 @@ def _sum_over_row_chunks(fetch, work, n, size=1 << 19, in_flight=8, tick=None):
                 if tick is not None:
                     tick(done, len(spans))
     return total, t_fetch, sum(t_work)
+
+
+def _compact_view(v, rows):
+    """Local rows `rows` (sorted, distinct) of the view and every column they touch as a view
+    of their own for the attention oracle: the rows come first (compact ids 0..m-1, so that a
+    row that is also a neighbour is ONE node), the other columns after them.
+    Returns (view_c, nodes): nodes[c] = id of compact node c in the view's local-then-halo order."""
+    rows = np.asarray(rows, dtype=np.int64)
+    segs = [(int(v["rowptr"][i]), int(v["rowptr"][i + 1])) for i in rows]
+    cols = np.concatenate([v["col"][s:e] for s, e in segs]).astype(np.int64)
+    others = np.setdiff1d(np.unique(cols), rows)
+    nodes = np.concatenate([rows, others])
+    order = np.argsort(nodes, kind="stable")
+    pos = order[np.searchsorted(nodes[order], cols)]
+    rowptr = np.concatenate([[0], np.cumsum([e - s for s, e in segs])]).astype(np.int64)
+    return dict(n_local=len(rows), n_halo=len(others), rowptr=rowptr, col=pos.astype(np.int64)), nodes
+
+
+def _gat_calls_sampled(sat, gu, torch, v, rng, say, hubs):
+    """The graph attention calls (scores, forward, backward; 4 heads x 64, bf16 rows) on the
+    view, outputs on sampled rows against the oracle run on the compact view of the rows that
+    produce them. Inputs are drawn on the device and the needed rows read back. At full Scale
+    Z and dZ are 17 GB each: the calls' 64-bit row offsets are what this is for."""
+    from oracle import gat_oracle as gat
+    K, F, slope = 4, 64, 0.2
+    d = K * F
+    n_l, n_h = v["n_local"], v["n_halo"]
+    n_bar = n_l + n_h
+    dev = gu.DEV
+    st = gu.stream_ptr()
+    pv = gu.upload_view(v)
+    Z_d = syn.device_normal(n_bar, d, d, 101, dev, True)
+    a_dst, a_src = syn.attention_vectors_f32(np.random.SeedSequence(56), K, F)
+    a_dst_d, a_src_d = gu.to_dev(a_dst.reshape(-1)), gu.to_dev(a_src.reshape(-1))
+
+    def rows_f32(t, ids):
+        return t[torch.from_numpy(np.asarray(ids, np.int64)).to(dev)].float().cpu().numpy()
+
+    # scores
+    el_d = torch.empty((n_l, K), dtype=torch.float32, device=dev)
+    er_d = torch.empty((n_bar, K), dtype=torch.float32, device=dev)
+    sat.gat_scores(Z_d, d, n_bar, n_l, K, F, a_dst_d, a_src_d, el_d, er_d, dtype=sat.BF16, stream=st)
+    gu.sync()
+    pick = np.unique(np.concatenate([rng.choice(n_bar, size=3000, replace=False), [0, n_l - 1, n_l, n_bar - 1],
+                                     np.arange(n_bar - 64, n_bar)]))
+    el_ref, er_ref = gat.gat_scores(rows_f32(Z_d, pick), a_dst, a_src)
+    gu.assert_close(rows_f32(er_d, pick), er_ref, 1e-5, "er rows")
+    loc = pick < n_l
+    gu.assert_close(rows_f32(el_d, pick[loc]), el_ref[loc], 1e-5, "el rows")
+    # forward on sampled rows: random ones, the longest, the first, the last and a block at the end
+    H_d = torch.empty((n_l, d), dtype=torch.bfloat16, device=dev)
+    stats_d = torch.empty((n_l, K, 2), dtype=torch.float32, device=dev)
+    sat.gat_aggregate_fwd(pv, Z_d, d, K, F, el_d, er_d, slope, sat.ACT_IDENTITY, H_d, d, stats_d,
+                          dtype=sat.BF16, stream=st)
+    gu.sync()
+    deg = np.diff(v["rowptr"])
+    rows = np.unique(np.concatenate([rng.choice(n_l, size=300, replace=False), np.argsort(deg)[-hubs:],
+                                     [0, n_l - 1], np.arange(n_l - 32, n_l)]))
+    vc, nodes = _compact_view(v, rows)
+    ref = gat.gat_aggregate_fwd(vc, rows_f32(Z_d, nodes), rows_f32(el_d, rows).astype(np.float64),
+                                rows_f32(er_d, nodes).astype(np.float64), slope)
+    gu.assert_close(rows_f32(H_d, rows), orc.round_bf16(ref), RTOL, "aggregated rows")
+    say("attention scores and forward ok on %d sampled rows (%d nodes read back)" % (len(rows), len(nodes)))
+    # backward: dZ of sampled local and halo nodes needs every local row that has one of them as
+    # a neighbour (the graph is symmetric: a local node's local entries; a halo node's column
+    # of the halo block), with all of THEIR entries
+    dH_d = syn.device_normal(n_l, d, d, 103, dev, True, std=1.0 / np.sqrt(n_l))
+    wsb = sat.gat_aggregate_bwd_workspace_bytes(n_l, n_h, K, F, sat.BF16)
+    ws = gu.workspace(wsb)
+    dZ_d = torch.empty((n_bar, d), dtype=torch.bfloat16, device=dev)
+    da1 = torch.empty(d, dtype=torch.float32, device=dev)
+    da2 = torch.empty(d, dtype=torch.float32, device=dev)
+    sat.gat_aggregate_bwd(pv, Z_d, d, K, F, el_d, er_d, stats_d, slope, sat.ACT_IDENTITY, dH_d, d,
+                          None, 0, a_dst_d, a_src_d, dZ_d, d, da1, da2, dtype=sat.BF16, workspace=ws,
+                          workspace_bytes=wsb, stream=st)
+    gu.sync()
+    hdeg = np.diff(v["h_colptr"])
+    loc_j = np.unique(np.concatenate([rng.choice(n_l, size=60, replace=False), np.argsort(deg)[-1:],
+                                      [0, n_l - 1]]))
+    halo_j = np.unique(np.concatenate([rng.choice(n_h, size=60, replace=False), np.argsort(hdeg)[-1:],
+                                       [0, n_h - 1]]))
+    need = [loc_j]
+    for j in loc_j:
+        need.append(v["col"][v["rowptr"][j]:v["split"][j]].astype(np.int64))
+    for u in halo_j:
+        need.append(v["h_row"][v["h_colptr"][u]:v["h_colptr"][u + 1]].astype(np.int64))
+    src = np.unique(np.concatenate(need))
+    vc, nodes = _compact_view(v, src)
+    say("oracle backward over %d source rows, %d nodes read back, for %d rows of dZ" % (
+        len(src), len(nodes), len(loc_j) + len(halo_j)))
+    dZa, d_el, d_er = gat.gat_aggregate_bwd(vc, rows_f32(Z_d, nodes), rows_f32(el_d, src).astype(np.float64),
+                                            rows_f32(er_d, nodes).astype(np.float64), slope,
+                                            rows_f32(dH_d, src).astype(np.float64))
+    js = np.concatenate([loc_j, n_l + halo_j])
+    order = np.argsort(nodes, kind="stable")
+    cpos = order[np.searchsorted(nodes[order], js)]
+    assert np.array_equal(nodes[cpos], js)
+    A = np.zeros((len(js), K, F))
+    A[:len(loc_j)] = d_el[cpos[:len(loc_j)]][:, :, None] * a_dst[None].astype(np.float64)
+    Bm = d_er[cpos][:, :, None] * a_src[None].astype(np.float64)
+    A, Bm = A.reshape(len(js), d), Bm.reshape(len(js), d)
+    ref = dZa[cpos] + A + Bm
+    got = rows_f32(dZ_d, js).astype(np.float64)
+    mag = np.abs(dZa[cpos]) + np.abs(A) + np.abs(Bm)
+    rms = np.sqrt(np.mean(ref * ref))
+    assert np.all(np.abs(got - ref) <= RTOL * (mag + rms)), "dZ rows: worst %g" % float(
+        (np.abs(got - ref) / (mag + rms)).max())
+    assert torch.isfinite(da1).all() and torch.isfinite(da2).all()
+    say("attention backward ok")
 
 
 @pytest.mark.parametrize("name", ["scale_rows_small"] + (["scale"] if FULL else []))
@@ -251,5 +365,9 @@ def test_scale_recipe_sampled_parity(name, capsys):
         name, n_l, n_h, v["nnz"], loss, torch.cuda.memory_allocated() / 1e9))
     del wl, step
     import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    # ---- the graph attention calls on the same view (its own 50 GB of buffers at full size)
+    _gat_calls_sampled(sat, gu, torch, v, rng, _say, hubs=1 if name == "scale" else 3)
     gc.collect()
     torch.cuda.empty_cache()
