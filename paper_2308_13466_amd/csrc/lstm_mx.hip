@@ -447,7 +447,7 @@ __global__ __launch_bounds__(64 * WAVES) void lstm_mx_kernel(SlotPtrs slots, int
           cstate[rb][r] = gi * gg;
         } else {
           gf = sigmoidf_(acc[rb][1][r] + b_f);
-          cstate[rb][r] = gf * cstate[rb][r] + gi * gg;
+          cstate[rb][r] = __builtin_fmaf(gf, cstate[rb][r], gi * gg);   // (one rounding of gi gg, then one of the sum: spelt out so that every kernel that updates a cell does the same)
         }
         hval[rb][r] = go * tanhf_(cstate[rb][r]);
         if (save != nullptr) {   // training: keep the step's gates, cell and hidden state
@@ -504,6 +504,10 @@ bool lstm_proj_serves(int32_t d, int32_t d_s, int es_x, int64_t n_nodes);
 sat_status launch_lstm_proj(const void* X, int64_t n_rows_slot, int64_t ld_slot, const int32_t* ids,
                             int64_t n_nodes, const void* WxP, float* P, hipStream_t st);
 
+// lstm_recur.hip: the time steps alone, from kept projections of every slot (d_s = 64)
+sat_status launch_lstm_recur(float* const* proj, int tau, int64_t n_nodes, const void* WhP, const float* bias,
+                             float* S, hipStream_t st);
+
 // Bytes of workspace the split-weight copies need (0 if this path does not serve d_s).
 int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
   if (d_s != 32 && d_s != 64) return 0;
@@ -546,9 +550,16 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
     if (rc != SAT_OK) return rc;
     pp.n_valid = tau;
   }
-  if (pp.n_valid == tau && proj && d_s == 64 && es_x == 4) {   // the time steps alone
-    // (64 nodes and four wavefronts per workgroup, two workgroups per compute unit, was measured
-    // slower: 1.38 against 1.0 ms; the weight tiles are then staged twice as often per node)
+  if (pp.n_valid == tau && proj && d_s == 64 && (reinterpret_cast<uintptr_t>(b) & 15u) == 0) {
+    // the time steps alone: weights in registers, products transposed, gates requested a step
+    // ahead (lstm_recur.hip). (This kernel's own instance for the case, XPART = false, took
+    // 0.96 ms on the bench workload; with 64 nodes and four wavefronts per workgroup, two
+    // workgroups per compute unit, 1.38 ms: the weight tiles are then staged twice as often.)
+    bool aligned = true;
+    for (int s = 0; s < tau; ++s) aligned = aligned && (reinterpret_cast<uintptr_t>(proj[s]) & 15u) == 0;
+    if (aligned) return launch_lstm_recur(proj, tau, n_nodes, WhP, b, S, st);
+  }
+  if (pp.n_valid == tau && proj && d_s == 64 && es_x == 4) {   // the same from this file's kernel
     const int64_t blocks = (n_nodes + kR - 1) / kR;
     if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;
     lstm_mx_kernel<64, 4, 8, true, kR, false><<<dim3(static_cast<unsigned>(blocks)), dim3(512), 0, st>>>(
