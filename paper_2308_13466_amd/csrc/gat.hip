@@ -17,9 +17,11 @@
 //     column (a 4K-byte read), exponentials, per-head weights written to the
 //     wavefront's slice of LDS. In the forward this phase also carries the
 //     running maximum of the online softmax and rescales the sums;
-//   * feature phase: G = d/4 lanes cover a feature row (4 elements each), the
-//     64/G groups take different entries, 8 gathers per group are issued back to
-//     back before any is used; each lane reads the weight of its own head from LDS.
+//   * feature phase: G lanes cover a feature row (16 bytes each where the width allows:
+//     4 fp32 or 8 bf16 elements, so that one gather instruction requests 1 KiB either
+//     way; 4 bf16 elements otherwise), the 64/G groups take different entries, 8 gathers
+//     per group are issued back to back before any is used; each lane reads the weight
+//     of its own head from LDS.
 // Per-head dot products (the gradient with respect to alpha) are kept as per-lane
 // partial sums and reduced across lanes once per row, not per entry.
 // Rows longer than kLongRow entries are left for a second phase in which all 8
@@ -35,13 +37,16 @@ using sat::kWave;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 8;
 constexpr int kRowsPerBlock = 64;
 constexpr int kLongRow = 1024;
-constexpr int kU = 8;         // gathers in flight per lane group (more of them for the 8-byte
-                             // lane shares of bf16 rows spilled registers and ran slower)
+constexpr int kU = 8;         // gathers in flight per lane group
+// (with 16-byte shares of bf16 rows: 6, the most that keeps the entry loop free of spills)
+template <int V>
+constexpr int kUof = V == 2 ? 6 : kU;
 constexpr int kMaxD = 256;     // 64 lanes x 4 elements
 
 // Four consecutive elements of a row: the bits as loaded (nothing may touch them before
@@ -123,6 +128,48 @@ __device__ __forceinline__ float dot4(f32x4 a, f32x4 b) {
   return a.x * b.x + a.y * b.y + a.z * b.z + a.w * b.w;
 }
 
+// A lane's share of a gathered row: V chunks of four consecutive elements (V = 2: eight
+// bf16 elements, one 16-byte load), as loaded and as fp32.
+template <int ES, int V>
+struct RawV {
+  typedef typename Raw4<ES>::T T;
+};
+template <>
+struct RawV<2, 2> {
+  typedef u32x4 T;
+};
+template <int ES, int V>
+__device__ __forceinline__ typename RawV<ES, V>::T load_raw(const unsigned char* p) {
+  static_assert(V == 1 || (V == 2 && ES == 2), "lane shares are at most 16 bytes");
+  return *reinterpret_cast<const typename RawV<ES, V>::T*>(p);
+}
+template <int ES, int V>
+__device__ __forceinline__ void widen(typename RawV<ES, V>::T w, f32x4 (&out)[V]) {
+  if constexpr (V == 1) {
+    out[0] = widen4<ES>(w);
+  } else {
+    u32x2 lo, hi;
+    lo.x = w.x;
+    lo.y = w.y;
+    hi.x = w.z;
+    hi.y = w.w;
+    out[0] = widen4<2>(lo);
+    out[1] = widen4<2>(hi);
+  }
+}
+template <int ES, int V>
+__device__ __forceinline__ void load_share(const unsigned char* p, int left, f32x4 (&out)[V]) {
+  widen<ES, V>(load_raw<ES, V>(p), out);
+#pragma unroll
+  for (int v = 0; v < V; ++v) out[v] = clip4(out[v], left - 4 * v);
+}
+template <int ES, int V>
+__device__ __forceinline__ void store_share(unsigned char* p, const f32x4 (&o)[V], int left) {
+#pragma unroll
+  for (int v = 0; v < V; ++v)
+    if (left > 4 * v) store4<ES>(p + static_cast<int64_t>(4 * v) * ES, o[v], left - 4 * v);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
@@ -169,9 +216,9 @@ __device__ __forceinline__ void load_heads(const float* p, float (&v)[K]) {
 }
 
 // How the lanes of a wavefront cover rows of d = K * F elements: G = 2^lg_g lanes per
-// row (4 elements each), LH = 2^lg_lh consecutive lanes per head.
+// row (4 * 2^lg_v elements each), LH = 2^lg_lh consecutive lanes per head.
 struct Lanes {
-  int32_t d, lg_g, lg_lh;
+  int32_t d, lg_g, lg_lh, lg_v;
 };
 
 struct WalkArgs {
@@ -198,7 +245,7 @@ __device__ __forceinline__ LaneIds lane_ids(const Lanes& ln, int heads) {
   L.grp = L.lane >> ln.lg_g;
   L.ng = kWave >> ln.lg_g;
   L.h = L.gl >> ln.lg_lh;
-  L.el0 = L.gl * 4;
+  L.el0 = L.gl << (2 + ln.lg_v);
   L.left = ln.d - L.el0;
   L.col_ok = L.left > 0;
   // the lane that ends up holding (and writes) its head's reduced scalars
@@ -221,6 +268,11 @@ __device__ __forceinline__ f32x4 group_sum(f32x4 v, const Lanes& ln) {   // over
   }
   return v;
 }
+template <int V>
+__device__ __forceinline__ void group_sum(const f32x4 (&v)[V], const Lanes& ln, f32x4 (&out)[V]) {
+#pragma unroll
+  for (int i = 0; i < V; ++i) out[i] = group_sum(v[i], ln);
+}
 
 __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
@@ -231,17 +283,17 @@ __device__ __forceinline__ void wave_lds_fence() {
 // for lanes past the end and for ids out of range; c is then 0); it only REQUESTS the
 // per-node scores the entry needs. `entry(c, ok, w)`: called for the same lane and entry once
 // the first round of gathers has been issued; it writes the entry's NW per-head weights to
-// w[0 .. NW). `feature(x, w, valid)`: called for each lane's share x of
-// a gathered row, w the weights of that entry in LDS. `fold()`: called after the last entry of
+// w[0 .. NW). `feature(x, w, valid)`: called for each lane's share x (V chunks of four
+// elements) of a gathered row, w the weights of that entry in LDS. `fold()`: called after the last entry of
 // each batch of 64: the callers sum a batch on its own and add it to the row's running sum
 // there, which keeps the chains of additions short on rows of thousands of entries.
-template <int ES, int NW, int U, class Pre, class Entry, class Feature, class Fold>
+template <int ES, int V, int NW, int U, class Pre, class Entry, class Feature, class Fold>
 __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_t s, int64_t e,
                                      int32_t* s_col, float* s_w, Pre&& pre, Entry&& entry,
                                      Feature&& feature, Fold&& fold) {
   // rows whose width is not a whole number of chunks, or fewer chunks than lanes in a group:
   // the lanes' shares are clipped to the row (lanes past it get zeros)
-  const bool clip = a.ln.d != (4 << a.ln.lg_g);
+  const bool clip = a.ln.d != ((4 * V) << a.ln.lg_g);
   for (int64_t base = s; base < e; base += kWave) {
     const int cnt = static_cast<int>(e - base < kWave ? e - base : kWave);
     int32_t c = -1;
@@ -251,7 +303,7 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
     wave_lds_fence();               // the previous batch's reads of LDS are done
     s_col[L.lane] = c;
     wave_lds_fence();
-    typename Raw4<ES>::T x[U];
+    typename RawV<ES, V>::T x[U];
     // entry handled in slot u of the round that starts at j0 (past the end: the last
     // entry again, with weight 0); recomputed where it is needed rather than kept
     auto slot = [&](int j0, int u, bool& valid) __attribute__((always_inline)) {
@@ -265,8 +317,8 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
         bool valid;
         const int32_t cj = s_col[slot(j0, u, valid)];
         // lanes past the row's width re-read its first chunk; their sums are never stored
-        x[u] = load_raw4<ES>(a.X + static_cast<int64_t>(cj) * a.ld_x +
-                             static_cast<int64_t>(L.col_ok ? L.el0 : 0) * ES);
+        x[u] = load_raw<ES, V>(a.X + static_cast<int64_t>(cj) * a.ld_x +
+                               static_cast<int64_t>(L.col_ok ? L.el0 : 0) * ES);
       }
     };
     auto consume = [&](int j0) __attribute__((always_inline)) {
@@ -274,9 +326,15 @@ __device__ __forceinline__ void walk(const WalkArgs& a, const LaneIds& L, int64_
       for (int u = 0; u < U; ++u) {
         bool valid;
         const int idc = slot(j0, u, valid);
-        f32x4 xw = widen4<ES>(x[u]);
-        if (clip) xw = clip4(xw, L.left);
+        f32x4 xw[V];
+        widen<ES, V>(x[u], xw);
+        if (clip) {
+#pragma unroll
+          for (int v = 0; v < V; ++v) xw[v] = clip4(xw[v], L.left - 4 * v);
+        }
         feature(xw, s_w + idc * NW, valid);
+        // (the conversions of all U shares moved ahead of the first use would not fit the registers)
+        if constexpr (V == 2) __builtin_amdgcn_sched_barrier(0);
       }
     };
     // The first round of gathers needs the ids only: it is in flight while the entry phase
@@ -374,7 +432,7 @@ __global__ __launch_bounds__(256) void gat_scores_kernel(const unsigned char* Z,
 
 // ---------------------------------------------------------------- forward
 // H[i] = act(sum_j alpha_ij Z_j), stats[i, k] = (max_j e_ij, 1 / sum_j exp(e_ij - max))
-template <int ES, int K>
+template <int ES, int K, int V>
 __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, const float* el,
                                                                 const float* er, int relu,
                                                                 unsigned char* Y, int64_t ld_y,
@@ -391,14 +449,15 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
   flag_long_rows(a, row0, nr, &sp);
 
   float m[K], l[K], eli[K];
-  f32x4 acc;
+  f32x4 acc[V];
   auto reset = [&](int64_t row) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       m[k] = -INFINITY;
       l[k] = 0.f;
     }
-    acc = f32x4(0.f);
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = f32x4(0.f);
     load_heads<K>(el + row * K, eli);
   };
   float erv[K];
@@ -422,29 +481,47 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
       w[k] = p;
     }
     const float sc = pick<K>(scale, L.h);
-    acc *= sc;
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] *= sc;
   };
-  f32x4 bacc(0.f);       // the current batch of 64 entries (all under the current maximum)
-  auto feature = [&](f32x4 x, const float* w, bool valid) __attribute__((always_inline)) {
+  // the current batch of 64 entries (all under the current maximum). With 16-byte shares of
+  // bf16 rows the registers for it are not there, and the rounding of a long fp32 chain is far
+  // below that of the stored result: those sum into acc directly.
+  constexpr int VB = V == 1 ? 1 : 0;
+  f32x4 bacc[VB + 1];
+  bacc[0] = f32x4(0.f);
+  auto feature = [&](const f32x4 (&x)[V], const float* w, bool valid) __attribute__((always_inline)) {
     const float p = valid ? w[L.h] : 0.f;
-    bacc += p * x;
+    if constexpr (VB) {
+      bacc[0] += p * x[0];
+    } else {
+#pragma unroll
+      for (int v = 0; v < V; ++v) acc[v] += p * x[v];
+    }
   };
   auto fold = [&]() __attribute__((always_inline)) {
-    acc += bacc;
-    bacc = f32x4(0.f);
+    if constexpr (VB) {
+      acc[0] += bacc[0];
+      bacc[0] = f32x4(0.f);
+    }
   };
-  auto store = [&](int64_t row, f32x4 sum, const float (&mm)[K], const float (&ll)[K]) {
+  auto store = [&](int64_t row, const f32x4 (&sum)[V], const float (&mm)[K], const float (&ll)[K]) {
     float inv[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) inv[k] = ll[k] > 0.f ? 1.f / ll[k] : 0.f;
-    f32x4 o = sum * pick<K>(inv, L.h);
-    if (relu) {
-      o.x = fmaxf(o.x, 0.f);
-      o.y = fmaxf(o.y, 0.f);
-      o.z = fmaxf(o.z, 0.f);
-      o.w = fmaxf(o.w, 0.f);
+    f32x4 o[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      o[v] = sum[v] * pick<K>(inv, L.h);
+      if (relu) {
+        o[v].x = fmaxf(o[v].x, 0.f);
+        o[v].y = fmaxf(o[v].y, 0.f);
+        o[v].z = fmaxf(o[v].z, 0.f);
+        o[v].w = fmaxf(o[v].w, 0.f);
+      }
     }
-    if (L.grp == 0 && L.col_ok) store4<ES>(Y + row * ld_y + static_cast<int64_t>(L.el0) * ES, o, L.left);
+    if (L.grp == 0 && L.col_ok)
+      store_share<ES, V>(Y + row * ld_y + static_cast<int64_t>(L.el0) * ES, o, L.left);
     if (L.lane < K) {
       const float mv = pick<K>(mm, L.lane), iv = pick<K>(inv, L.lane);
       f32x2 t;
@@ -460,11 +537,13 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, K, kU>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, K, kUof<V>>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float ll[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ll[k] = wave_sum(l[k]);
-    store(row, group_sum(acc, a.ln), m, ll);
+    f32x4 tot[V];
+    group_sum<V>(acc, a.ln, tot);
+    store(row, tot, m, ll);
   }
   __syncthreads();
   // ---- long rows: a contiguous piece per wavefront, combined in wavefront order
@@ -475,8 +554,9 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
-    const f32x4 part = group_sum(acc, a.ln);
+    walk<ES, V, K, kUof<V>>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    f32x4 part[V];
+    group_sum<V>(acc, a.ln, part);
     float lk[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) lk[k] = wave_sum(l[k]);
@@ -484,7 +564,10 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
       s_part[wave][L.lane] = pick<K>(m, L.lane);
       s_part[wave][K + L.lane] = pick<K>(lk, L.lane);
     }
-    if (L.grp == 0) *reinterpret_cast<f32x4*>(&s_part[wave][HDR + L.el0]) = part;
+    if (L.grp == 0) {
+#pragma unroll
+      for (int v = 0; v < V; ++v) *reinterpret_cast<f32x4*>(&s_part[wave][HDR + L.el0 + 4 * v]) = part[v];
+    }
     __syncthreads();
     if (wave == 0) {
       float mm[K], ll[K], f[K];
@@ -494,7 +577,9 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
         for (int w = 0; w < kWaves; ++w) mm[k] = fmaxf(mm[k], s_part[w][k]);
         ll[k] = 0.f;
       }
-      f32x4 sum(0.f);
+      f32x4 sum[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) sum[v] = f32x4(0.f);
       for (int w = 0; w < kWaves; ++w) {
 #pragma unroll
         for (int k = 0; k < K; ++k) {
@@ -502,8 +587,11 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
           f[k] = mw == -INFINITY ? 0.f : expf(mw - mm[k]);
           ll[k] += s_part[w][K + k] * f[k];
         }
-        const f32x4 pw = *reinterpret_cast<const f32x4*>(&s_part[w][HDR + L.el0]);
-        sum += pick<K>(f, L.h) * pw;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          const f32x4 pw = *reinterpret_cast<const f32x4*>(&s_part[w][HDR + L.el0 + 4 * v]);
+          sum[v] += pick<K>(f, L.h) * pw;
+        }
       }
       store(row, sum, mm, ll);
     }
@@ -516,7 +604,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
 //   D_i   = sum_j alpha_ij <g_i, Z_j>            (per head)
 //   d_el_i = sum_j alpha_ij LeakyReLU'(s_ij) (<g_i, Z_j> - D_i)
 // and rowstat[i, k] = (el, max, 1/sum, D) for the source-side pass.
-template <int ES, int K>
+template <int ES, int K, int V>
 __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     WalkArgs a, const float* el, const float* er, const float* stats, const unsigned char* dOUT,
     int64_t ld_g, float* d_el, f32x4* rowstat) {
@@ -531,7 +619,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
   flag_long_rows(a, row0, nr, &sp);
 
   float eli[K], mi[K], inv[K], w1s[K];
-  f32x4 g;
+  f32x4 g[V];
   float accD, acc1;
   auto reset = [&](int64_t row) __attribute__((always_inline)) {
     load_heads<K>(el + row * K, eli);
@@ -542,8 +630,9 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
       inv[k] = t.y;
       w1s[k] = 0.f;
     }
-    g = f32x4(0.f);
-    if (L.col_ok) g = clip4(load4<ES>(dOUT + row * ld_g + static_cast<int64_t>(L.el0) * ES), L.left);
+#pragma unroll
+    for (int v = 0; v < V; ++v) g[v] = f32x4(0.f);
+    if (L.col_ok) load_share<ES, V>(dOUT + row * ld_g + static_cast<int64_t>(L.el0) * ES, L.left, g);
     accD = 0.f;
     acc1 = 0.f;
   };
@@ -564,8 +653,10 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     }
   };
   float bD = 0.f, b1 = 0.f;
-  auto feature = [&](f32x4 x, const float* w, bool valid) __attribute__((always_inline)) {
-    const float dt = dot4(g, x);
+  auto feature = [&](const f32x4 (&x)[V], const float* w, bool valid) __attribute__((always_inline)) {
+    float dt = dot4(g[0], x[0]);
+#pragma unroll
+    for (int v = 1; v < V; ++v) dt += dot4(g[v], x[v]);
     const float al = valid ? w[L.h] : 0.f;
     const float w1 = valid ? w[K + L.h] : 0.f;
     bD += al * dt;
@@ -595,7 +686,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, 2 * K, kU>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, 2 * K, kUof<V>>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float ws[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ws[k] = wave_sum(w1s[k]);
@@ -609,7 +700,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, 2 * K, kU>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, 2 * K, kUof<V>>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
     const float D = head_sum(accD, a.ln), t1 = head_sum(acc1, a.ln);
     float wk[K];
 #pragma unroll
@@ -643,7 +734,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
 // a neighbour; gathered g_i = dOUT_i and rowstat_i), j = row_off + r:
 //   d_er_j = sum_i alpha_ij LeakyReLU'(s_ij) (<g_i, Z_j> - D_i)
 //   dZ_j   = sum_i alpha_ij g_i + d_er_j a_src + d_el_j a_dst   (the last term for local j)
-template <int ES, int K, int U>
+template <int ES, int K, int V, int U>
 __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_kernel(
     WalkArgs a, int64_t row_off, int64_t n_local, const float* er, const f32x4* rowstat,
     const unsigned char* Z, int64_t ld_z, const float* d_el, const float* a_dst, const float* a_src,
@@ -668,15 +759,18 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
   flag_long_rows(a, row0, nr, &sp);   // (its barrier publishes s_avec as well)
 
   float erj[K], wds[K];
-  f32x4 z, acc;
+  f32x4 z[V], acc[V];
   float accd;
   auto reset = [&](int64_t jj) __attribute__((always_inline)) {
     load_heads<K>(er + jj * K, erj);
 #pragma unroll
     for (int k = 0; k < K; ++k) wds[k] = 0.f;
-    z = f32x4(0.f);
-    if (L.col_ok) z = clip4(load4<ES>(Z + jj * ld_z + static_cast<int64_t>(L.el0) * ES), L.left);
-    acc = f32x4(0.f);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+      z[v] = f32x4(0.f);
+      acc[v] = f32x4(0.f);
+    }
+    if (L.col_ok) load_share<ES, V>(Z + jj * ld_z + static_cast<int64_t>(L.el0) * ES, L.left, z);
     accd = 0.f;
   };
   // (the instance with two gathers in flight has no registers to hold the row statistics across
@@ -703,31 +797,53 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
       w[K + k] = w1;
     }
   };
-  f32x4 bacc(0.f);
+  // (batch sums as in the forward kernel: kept apart only where a lane's share is one chunk)
+  constexpr int VB = V == 1 ? 1 : 0;
+  f32x4 bacc[VB + 1];
+  bacc[0] = f32x4(0.f);
   float baccd = 0.f;
-  auto feature = [&](f32x4 x, const float* w, bool valid) __attribute__((always_inline)) {
+  auto feature = [&](const f32x4 (&x)[V], const float* w, bool valid) __attribute__((always_inline)) {
     const float al = valid ? w[L.h] : 0.f;
     const float w1 = valid ? w[K + L.h] : 0.f;
-    bacc += al * x;
-    baccd += w1 * dot4(z, x);
+    float dt = dot4(z[0], x[0]);
+    if constexpr (VB) {
+      bacc[0] += al * x[0];
+    } else {
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        acc[v] += al * x[v];
+        if (v > 0) dt += dot4(z[v], x[v]);
+      }
+    }
+    baccd += w1 * dt;
   };
   auto fold = [&]() __attribute__((always_inline)) {
-    acc += bacc;
+    if constexpr (VB) {
+      acc[0] += bacc[0];
+      bacc[0] = f32x4(0.f);
+    }
     accd += baccd;
-    bacc = f32x4(0.f);
     baccd = 0.f;
   };
   // sum: this lane's share of sum_i alpha_ij g_i; t1: sum_i w1 <g_i, Z_j> of the lane's head
-  auto store = [&](int64_t jj, f32x4 sum, float t1, const float (&wd)[K]) {
+  auto store = [&](int64_t jj, const f32x4 (&sum)[V], float t1, const float (&wd)[K]) {
     const float der = t1 - pick<K>(wd, L.h);
     if (L.grp == 0 && L.col_ok) {
-      const f32x4 as = *reinterpret_cast<const f32x4*>(&s_avec[0][L.el0]);
-      f32x4 o = sum + der * as;
-      if (jj < n_local) {
-        const f32x4 ad = *reinterpret_cast<const f32x4*>(&s_avec[1][L.el0]);
-        o += d_el[jj * K + L.h] * ad;
+      f32x4 o[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const f32x4 as = *reinterpret_cast<const f32x4*>(&s_avec[0][L.el0 + 4 * v]);
+        o[v] = sum[v] + der * as;
       }
-      store4<ES>(dZ + jj * ld_dz + static_cast<int64_t>(L.el0) * ES, o, L.left);
+      if (jj < n_local) {
+        const float de = d_el[jj * K + L.h];
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          const f32x4 ad = *reinterpret_cast<const f32x4*>(&s_avec[1][L.el0 + 4 * v]);
+          o[v] += de * ad;
+        }
+      }
+      store_share<ES, V>(dZ + jj * ld_dz + static_cast<int64_t>(L.el0) * ES, o, L.left);
     }
     if (L.leader) d_er[jj * K + L.h] = der;
   };
@@ -737,11 +853,13 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row_off + row);
-    walk<ES, 2 * K, U>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, 2 * K, U>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float wd[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) wd[k] = wave_sum(wds[k]);
-    store(row_off + row, group_sum(acc, a.ln), head_sum(accd, a.ln), wd);
+    f32x4 tot[V];
+    group_sum<V>(acc, a.ln, tot);
+    store(row_off + row, tot, head_sum(accd, a.ln), wd);
   }
   __syncthreads();
   for (int r = 0; r < nr; ++r) {
@@ -751,24 +869,31 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row_off + row);
-    walk<ES, 2 * K, U>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
-    const f32x4 part = group_sum(acc, a.ln);
+    walk<ES, V, 2 * K, U>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    f32x4 part[V];
+    group_sum<V>(acc, a.ln, part);
     const float t1 = head_sum(accd, a.ln);
     float wk[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) wk[k] = wave_sum(wds[k]);
     if (L.lane < K) s_part[wave][K + L.lane] = pick<K>(wk, L.lane);
     if (L.leader) s_part[wave][L.h] = t1;
-    if (L.grp == 0) *reinterpret_cast<f32x4*>(&s_part[wave][HDR + L.el0]) = part;
+    if (L.grp == 0) {
+#pragma unroll
+      for (int v = 0; v < V; ++v) *reinterpret_cast<f32x4*>(&s_part[wave][HDR + L.el0 + 4 * v]) = part[v];
+    }
     __syncthreads();
     if (wave == 0) {
-      f32x4 sum(0.f);
+      f32x4 sum[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) sum[v] = f32x4(0.f);
       float th = 0.f, wd[K];
 #pragma unroll
       for (int k = 0; k < K; ++k) wd[k] = 0.f;
       const int hh = L.h < K ? L.h : 0;
       for (int w = 0; w < kWaves; ++w) {
-        sum += *reinterpret_cast<const f32x4*>(&s_part[w][HDR + L.el0]);
+#pragma unroll
+        for (int v = 0; v < V; ++v) sum[v] += *reinterpret_cast<const f32x4*>(&s_part[w][HDR + L.el0 + 4 * v]);
         th += s_part[w][hh];
 #pragma unroll
         for (int k = 0; k < K; ++k) wd[k] += s_part[w][K + k];
@@ -883,7 +1008,20 @@ bool lanes_for(int32_t heads, int32_t d_head, Lanes* ln) {
   ln->d = static_cast<int32_t>(d);
   ln->lg_g = lg_g;
   ln->lg_lh = lg_lh;
+  ln->lg_v = 0;
   return true;
+}
+
+// The layout the edge kernels use: 16-byte lane shares (8 elements) for bf16 rows of 256
+// bytes and more whose width and head width are 8 times a power of two, else `ln` itself.
+Lanes edge_lanes(const Lanes& ln, int es) {
+  Lanes w = ln;
+  if (es == 2 && ln.d >= 128 && ln.d == (4 << ln.lg_g) && ln.lg_lh >= 1) {
+    w.lg_g = ln.lg_g - 1;
+    w.lg_lh = ln.lg_lh - 1;
+    w.lg_v = 1;
+  }
+  return w;
 }
 
 sat_status check_dense(const void* p, int64_t rows, int64_t ld, int64_t d, int es) {
@@ -929,7 +1067,7 @@ BwdPlan bwd_plan(int64_t n_local, int64_t n_halo, int32_t heads, int32_t d_head,
   return p;
 }
 
-template <int ES, int K>
+template <int ES, int K, int V>
 sat_status run_fwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes ln, const float* el,
                    const float* er, float slope, int32_t act, void* H, int64_t ld_h, float* stats,
                    hipStream_t s) {
@@ -937,13 +1075,14 @@ sat_status run_fwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes l
                    static_cast<const unsigned char*>(Z), ld_z * ES, ln, slope};
   const int64_t gb = (pv->n_local + kRowsPerBlock - 1) / kRowsPerBlock;
   if (gb > INT32_MAX) return SAT_EUNSUPPORTED;
-  gat_fwd_kernel<ES, K><<<dim3(static_cast<unsigned>(gb)), dim3(kWaves * kWave), 0, s>>>(
+  gat_fwd_kernel<ES, K, V><<<dim3(static_cast<unsigned>(gb)), dim3(kWaves * kWave), 0, s>>>(
       a, el, er, act == SAT_ACT_RELU ? 1 : 0, static_cast<unsigned char*>(H), ld_h * ES, stats);
   return sat::check_launch();
 }
 
-template <int ES, int K>
-sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes ln, const float* el,
+// ln: the layout of the row-streaming kernels, lw: that of the edge kernels (V chunks per lane)
+template <int ES, int K, int V>
+sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes ln, Lanes lw, const float* el,
                    const float* er, const float* stats, float slope, int32_t act, const void* dH,
                    int64_t ld_dh, const void* H, int64_t ld_h, const float* a_dst, const float* a_src,
                    void* dZ, int64_t ld_dz, float* da_dst, float* da_src, unsigned char* ws,
@@ -973,29 +1112,29 @@ sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes l
   const dim3 block(kWaves * kWave);
   {   // destination side: rows i, gathers Z_j
     const WalkArgs a{pv->rowptr, pv->rowptr + 1, pv->col, n_l, n_bar,
-                     static_cast<const unsigned char*>(Z), ld_z * ES, ln, slope};
+                     static_cast<const unsigned char*>(Z), ld_z * ES, lw, slope};
     const int64_t gb = (n_l + kRowsPerBlock - 1) / kRowsPerBlock;
     if (gb > INT32_MAX) return SAT_EUNSUPPORTED;
-    gat_bwd_dst_kernel<ES, K><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(a, el, er, stats, dOUT,
+    gat_bwd_dst_kernel<ES, K, V><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(a, el, er, stats, dOUT,
                                                                              ld_g, d_el, rowstat);
     if ((st = sat::check_launch()) != SAT_OK) return st;
   }
   {   // source side, local rows j: the transposed entries of row j's local columns are those
       // columns themselves (the local block's pattern is symmetric)
-    const WalkArgs a{pv->rowptr, pv->split, pv->col, n_l, n_l, dOUT, ld_g, ln, slope};
+    const WalkArgs a{pv->rowptr, pv->split, pv->col, n_l, n_l, dOUT, ld_g, lw, slope};
     const int64_t gb = (n_l + kRowsPerBlock - 1) / kRowsPerBlock;
-    gat_bwd_src_kernel<ES, K, kU><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
+    gat_bwd_src_kernel<ES, K, V, kUof<V>><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
         a, 0, n_l, er, rowstat, static_cast<const unsigned char*>(Z), ld_z * ES, d_el, a_dst, a_src,
         static_cast<unsigned char*>(dZ), ld_dz * ES, d_er);
     if ((st = sat::check_launch()) != SAT_OK) return st;
   }
   if (n_h > 0) {   // source side, halo rows: the transposed halo block
-    const WalkArgs a{pv->h_colptr, pv->h_colptr + 1, pv->h_row, n_h, n_l, dOUT, ld_g, ln, slope};
+    const WalkArgs a{pv->h_colptr, pv->h_colptr + 1, pv->h_row, n_h, n_l, dOUT, ld_g, lw, slope};
     const int64_t gb = (n_h + kRowsPerBlock - 1) / kRowsPerBlock;
     if (gb > INT32_MAX) return SAT_EUNSUPPORTED;
     // rows of a few entries each: what counts is the number of rows in flight, so this
     // instance keeps 2 gathers in flight per group and fits twice as many wavefronts
-    gat_bwd_src_kernel<ES, K, 2><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
+    gat_bwd_src_kernel<ES, K, V, 2><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
         a, n_l, n_l, er, rowstat, static_cast<const unsigned char*>(Z), ld_z * ES, d_el, a_dst, a_src,
         static_cast<unsigned char*>(dZ), ld_dz * ES, d_er);
     if ((st = sat::check_launch()) != SAT_OK) return st;
@@ -1044,19 +1183,27 @@ extern "C" sat_status sat_gat_scores(const void* Z, int64_t ld_z, int64_t n, int
 
 #define SAT_GAT_DISPATCH(FN, ...)                                   \
   do {                                                              \
+    if (es == 2 && lw.lg_v == 1) {                                  \
+      switch (heads) {                                              \
+        case 1: return FN<2, 1, 2>(__VA_ARGS__);                    \
+        case 2: return FN<2, 2, 2>(__VA_ARGS__);                    \
+        case 4: return FN<2, 4, 2>(__VA_ARGS__);                    \
+        default: return FN<2, 8, 2>(__VA_ARGS__);                   \
+      }                                                             \
+    }                                                               \
     if (es == 2) {                                                  \
       switch (heads) {                                              \
-        case 1: return FN<2, 1>(__VA_ARGS__);                       \
-        case 2: return FN<2, 2>(__VA_ARGS__);                       \
-        case 4: return FN<2, 4>(__VA_ARGS__);                       \
-        default: return FN<2, 8>(__VA_ARGS__);                      \
+        case 1: return FN<2, 1, 1>(__VA_ARGS__);                    \
+        case 2: return FN<2, 2, 1>(__VA_ARGS__);                    \
+        case 4: return FN<2, 4, 1>(__VA_ARGS__);                    \
+        default: return FN<2, 8, 1>(__VA_ARGS__);                   \
       }                                                             \
     }                                                               \
     switch (heads) {                                                \
-      case 1: return FN<4, 1>(__VA_ARGS__);                         \
-      case 2: return FN<4, 2>(__VA_ARGS__);                         \
-      case 4: return FN<4, 4>(__VA_ARGS__);                         \
-      default: return FN<4, 8>(__VA_ARGS__);                        \
+      case 1: return FN<4, 1, 1>(__VA_ARGS__);                      \
+      case 2: return FN<4, 2, 1>(__VA_ARGS__);                      \
+      case 4: return FN<4, 4, 1>(__VA_ARGS__);                      \
+      default: return FN<4, 8, 1>(__VA_ARGS__);                     \
     }                                                               \
   } while (0)
 
@@ -1079,7 +1226,8 @@ extern "C" sat_status sat_gat_aggregate_fwd(const sat_part_view* pv, const void*
   if (!el || !er || !stats) return SAT_EINVAL;
   if (!sat::aligned16(el) || !sat::aligned16(er) || !sat::aligned16(stats)) return SAT_EALIGN;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  SAT_GAT_DISPATCH(run_fwd, pv, Z, ld_z, ln, el, er, slope, act, H, ld_h, stats, s);
+  const Lanes lw = edge_lanes(ln, es);
+  SAT_GAT_DISPATCH(run_fwd, pv, Z, ld_z, lw, el, er, slope, act, H, ld_h, stats, s);
 }
 
 extern "C" int64_t sat_gat_aggregate_bwd_workspace_bytes(int64_t n_local, int64_t n_halo,
@@ -1123,6 +1271,7 @@ extern "C" sat_status sat_gat_aggregate_bwd(const sat_part_view* pv, const void*
         reinterpret_cast<const float*>(ws), 0, ln.d, da_dst, da_src);
     return sat::check_launch();
   }
-  SAT_GAT_DISPATCH(run_bwd, pv, Z, ld_z, ln, el, er, stats, slope, act, dH, ld_dh, H, ld_h, a_dst,
+  const Lanes lw = edge_lanes(ln, es);
+  SAT_GAT_DISPATCH(run_bwd, pv, Z, ld_z, ln, lw, el, er, stats, slope, act, dH, ld_dh, H, ld_h, a_dst,
                    a_src, dZ, ld_dz, da_dst, da_src, ws, s);
 }

@@ -69,6 +69,13 @@ CASES = [
     ("hub", 0, 1, 41, False, False),
     ("powerlaw", 0, 4, 64, True, True),
     ("hub", 1, 1, 40, False, True),
+    # bf16 rows of 256 bytes and more: 16-byte lane shares (8 elements per lane)
+    ("hub", 0, 4, 64, True, True),       # long rows combined through LDS
+    ("hub", 1, 2, 64, True, True),       # 256-byte rows; the hub is a halo node
+    ("powerlaw", 1, 8, 32, True, True),
+    ("powerlaw", 0, 1, 128, False, True),
+    ("powerlaw", 2, 1, 256, True, True),
+    ("powerlaw", 0, 2, 16, False, True),  # 64-byte rows: 4 elements per lane
     ("onepart", 0, 4, 16, True, False),  # no halo at all
 ]
 
