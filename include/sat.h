@@ -307,8 +307,8 @@ sat_status sat_history_decompress(const uint8_t* codes, const int64_t* row_off, 
  * Outputs (device, fp32, dense): dWx [4 d_s, d], dWh [4 d_s, d_s], db [4 d_s],
  * dWg [d_s, d], loss [1]; all overwritten. Reductions run in a fixed order.
  * dtype: element type of the slots and of target (SAT_BF16: bfloat16 tables; everything
- * computed here, the parameters and the outputs stay fp32). d_s = 32 or 64 and d % 4 == 0
- * (SAT_BF16: d % 8 == 0), else SAT_EUNSUPPORTED.
+ * computed here, the parameters and the outputs stay fp32). d_s = 32, 64 or 128 (SAT_BF16:
+ * 32 or 64) and d % 4 == 0 (SAT_BF16: d % 8 == 0), else SAT_EUNSUPPORTED.
  * Workspace: sat_predictor_train_workspace_bytes(); 256-byte aligned.
  */
 int64_t sat_predictor_train_workspace_bytes(int64_t n_local, int64_t n_halo, int32_t d,

@@ -11,7 +11,9 @@
 // The call is a sequence of kernels the library already has, plus four small
 // element-wise ones defined here:
 //   forward   LSTM over all nodes of the partition and its halo with every step's
-//             gates, cell and hidden state kept (lstm_mx.hip), aggregation of S
+//             gates, cell and hidden state kept (lstm_mx.hip; for d_s = 128, which that
+//             kernel does not take, each step as two products of the feature transform
+//             and an element-wise step defined here), aggregation of S
 //             over the local rows (spmm.hip), product with Wg plus the newest
 //             rows (tile GEMM, mx_tile.h), weighted squared error (here);
 //   backward  dWg and the gradient of the aggregate (the feature transform's
@@ -202,12 +204,58 @@ __global__ __launch_bounds__(256) void lstm_bwd_gates_kernel(const float* __rest
   dc[idx] = g_c * gf;
 }
 
-// part[b][c] = sum over block b's rows of A[r, c]   (A [n, cols], cols <= 256)
+// out [C, R] = in [R, C] transposed
+__global__ __launch_bounds__(256) void transpose_kernel(const float* __restrict__ in, int R, int C,
+                                                        float* __restrict__ out) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= R * C) return;
+  const int r = i / C, c = i - r * C;
+  out[static_cast<int64_t>(c) * R + r] = in[i];
+}
+
+// One time step of the LSTM with its record kept, element-wise over (node, hidden unit):
+// pre-activations a = px + ph + b (px = x_s Wx^T, ph = h_{s-1} Wh^T, both [n, 4 ds]; ph
+// nullptr at the first step, where h_0 = c_0 = 0), gates i, f, o = sigmoid, g = tanh,
+// c_s = f c_{s-1} + i g, h_s = o tanh(c_s); rec [n, 6 ds] = i, f, g, o, c_s, h_s.
+__global__ __launch_bounds__(256) void lstm_step_save_kernel(const float* __restrict__ px,
+                                                             const float* __restrict__ ph,
+                                                             const float* __restrict__ bias,
+                                                             const float* __restrict__ rec_prev,
+                                                             float* __restrict__ rec, int64_t n,
+                                                             int ds) {
+  const int64_t idx = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (idx >= n * ds) return;
+  const int64_t node = idx / ds;
+  const int u = static_cast<int>(idx - node * ds);
+  const int64_t a0 = node * (4 * ds) + u;
+  float a[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    a[g] = px[a0 + g * ds];
+    if (ph) a[g] += ph[a0 + g * ds];
+    a[g] += bias[g * ds + u];
+  }
+  const float gi = 1.0f / (1.0f + expf(-a[0]));
+  const float gf = 1.0f / (1.0f + expf(-a[1]));
+  const float gg = tanhf(a[2]);
+  const float go = 1.0f / (1.0f + expf(-a[3]));
+  const float cp = rec_prev ? rec_prev[node * (6 * ds) + 4 * ds + u] : 0.f;
+  const float c = gf * cp + gi * gg;
+  float* r = rec + node * (6 * ds) + u;
+  r[0] = gi;
+  r[ds] = gf;
+  r[2 * ds] = gg;
+  r[3 * ds] = go;
+  r[4 * ds] = c;
+  r[5 * ds] = go * tanhf(c);
+}
+
+// part[b][c] = sum over block b's rows of A[r, c]   (A [n, cols]; blockIdx.y: block of 256 columns)
 __global__ __launch_bounds__(256) void col_sum_kernel(const float* __restrict__ A, int64_t n,
                                                       int cols, float* __restrict__ part) {
   const int64_t per = (n + gridDim.x - 1) / gridDim.x;
   const int64_t lo = blockIdx.x * per, hi = lo + per < n ? lo + per : n;
-  const int c = threadIdx.x;
+  const int c = blockIdx.y * 256 + threadIdx.x;
   if (c >= cols) return;
   // eight rows at a time, each into its own partial sum: eight loads in flight per thread
   float a[8];
@@ -229,7 +277,7 @@ __global__ __launch_bounds__(256) void col_sum_kernel(const float* __restrict__ 
 __global__ __launch_bounds__(256) void col_sum_finish_kernel(const float* __restrict__ part,
                                                              int blocks, int cols,
                                                              float* __restrict__ out) {
-  const int c = threadIdx.x;
+  const int c = blockIdx.x * 256 + threadIdx.x;
   if (c >= cols) return;
   float acc = 0.f;
   for (int b = 0; b < blocks; ++b) acc += part[static_cast<int64_t>(b) * cols + c];
@@ -243,7 +291,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* __restrict__ p, const f
 }
 
 struct Plan {   // byte offsets into the workspace, all multiples of 256
-  int64_t S, save, wsplit, aggS, pred, part, wsum, daggS, dh0, dh1, dc, da, xwin, tmpW, dws, total;
+  int64_t S, save, wsplit, aggS, pred, part, wsum, daggS, dh0, dh1, dc, da, xwin, tmpW, dws, wT, ph, total;
 };
 
 Plan plan(int64_t n_l, int64_t n_h, int32_t d, int32_t ds, int32_t tau) {
@@ -275,6 +323,9 @@ Plan plan(int64_t n_l, int64_t n_h, int32_t d, int32_t ds, int32_t tau) {
   if (w2 > dws) dws = w2;
   if (w3 > dws) dws = w3;
   L.dws = take(dws);
+  // d_s = 128: transposed copies of Wx and Wh, and the recurrent part of a step's pre-activations
+  L.wT = take(ds > 64 ? static_cast<int64_t>(4 * ds) * (d + ds) * 4 : 0);
+  L.ph = take(ds > 64 ? n_bar * 4 * ds * 4 : 0);
   L.total = off;
   return L;
 }
@@ -302,9 +353,10 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
   if (dtype != SAT_F32 && dtype != SAT_BF16) return SAT_EINVAL;
   if (w->d <= 0 || w->tau < 1 || w->bypass) return SAT_EINVAL;
   if (w->tau > kMaxTau) return SAT_EUNSUPPORTED;
-  if (w->d_s != 32 && w->d_s != 64) return SAT_EUNSUPPORTED;
+  if (w->d_s != 32 && w->d_s != 64 && w->d_s != 128) return SAT_EUNSUPPORTED;
   const int d = w->d, ds = w->d_s, tau = w->tau;
   const int es = dtype == SAT_BF16 ? 2 : 4;
+  if (ds > 64 && es == 2) return SAT_EUNSUPPORTED;   // (as in sat_predict)
   if ((d % (16 / es)) != 0) return SAT_EUNSUPPORTED;
   const int64_t n_l = pv->n_local, n_h = pv->n_halo, n_bar = n_l + n_h;
   if (n_bar > INT32_MAX) return SAT_EUNSUPPORTED;
@@ -333,21 +385,59 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
         *tmpW = f(L.tmpW);
   float* dh[2] = {f(L.dh0), f(L.dh1)};
   void* dws = base + L.dws;
-  const int64_t dws_bytes = L.total - L.dws;
+  const int64_t dws_bytes = L.wT - L.dws;
   const int64_t rec = 6 * static_cast<int64_t>(ds);
   sat_status rc;
 
+  if (!ids && n_rows_slot < n_bar) return SAT_EINVAL;
   // ---- forward
-  rc = sat::launch_lstm_mx(slots, es, tau, n_rows_slot, ld_slot, ids, n_bar, d, ds, w->Wx, w->Wh, w->b,
-                           S, base + L.wsplit, st, save);
-  if (rc != SAT_OK) return rc;
-  rc = sat::launch_spmm(pv->rowptr, nullptr, pv->col, pv->val, S, ds, n_bar, aggS, ds, n_l, ds, 4,
+  const float* Sp = S;        // the last hidden states, ld_S floats per node
+  int64_t ld_S = ds;
+  if (ds <= 64) {
+    rc = sat::launch_lstm_mx(slots, es, tau, n_rows_slot, ld_slot, ids, n_bar, d, ds, w->Wx, w->Wh, w->b,
+                             S, base + L.wsplit, st, save);
+    if (rc != SAT_OK) return rc;
+  } else {
+    float* WxT = f(L.wT);
+    float* WhT = WxT + static_cast<int64_t>(4 * ds) * d;
+    float* ph = f(L.ph);
+    transpose_kernel<<<blocks_for(static_cast<int64_t>(4 * ds) * d), dim3(256), 0, st>>>(w->Wx, 4 * ds, d, WxT);
+    transpose_kernel<<<blocks_for(static_cast<int64_t>(4 * ds) * ds), dim3(256), 0, st>>>(w->Wh, 4 * ds, ds, WhT);
+    if ((rc = sat::check_launch()) != SAT_OK) return rc;
+    for (int s = 0; s < tau; ++s) {
+      const void* xs = slots[s];
+      int64_t ld_x = ld_slot;
+      if (ids) {
+        rc = sat::row_gather(slots[s], ld_slot, xwin, d, ids, 0, n_bar, n_rows_slot, d, 4, st);
+        if (rc != SAT_OK) return rc;
+        xs = xwin;
+        ld_x = d;
+      }
+      float* rec_s = save + static_cast<int64_t>(s) * n_bar * rec;
+      const float* rec_p = s > 0 ? save + static_cast<int64_t>(s - 1) * n_bar * rec : nullptr;
+      rc = sat_dense_fwd(xs, ld_x, n_bar, d, 4 * ds, WxT, 4 * ds, SAT_ACT_IDENTITY, SAT_F32, da, 4 * ds,
+                         stream);
+      if (rc != SAT_OK) return rc;
+      if (s > 0) {
+        rc = sat_dense_fwd(rec_p + 5 * ds, rec, n_bar, ds, 4 * ds, WhT, 4 * ds, SAT_ACT_IDENTITY, SAT_F32,
+                           ph, 4 * ds, stream);
+        if (rc != SAT_OK) return rc;
+      }
+      lstm_step_save_kernel<<<blocks_for(n_bar * ds), dim3(256), 0, st>>>(da, s > 0 ? ph : nullptr, w->b,
+                                                                          rec_p, rec_s, n_bar, ds);
+      if ((rc = sat::check_launch()) != SAT_OK) return rc;
+    }
+    Sp = save + static_cast<int64_t>(tau - 1) * n_bar * rec + 5 * ds;
+    ld_S = rec;
+  }
+  rc = sat::launch_spmm(pv->rowptr, nullptr, pv->col, pv->val, Sp, ld_S, n_bar, aggS, ds, n_l, ds, 4,
                         nullptr, 0, pv->nnz, st);
   if (rc != SAT_OK) return rc;
-  if (es == 4) {   // pred = newest rows + aggS Wg in one kernel
+  const bool fused_add = es == 4 && ds <= 64;
+  if (fused_add) {   // pred = newest rows + aggS Wg in one kernel
     rc = sat::launch_hop_product(aggS, n_l, ds, w->Wg, d, slots[tau - 1], ld_slot, ids, 0, n_rows_slot,
                                  pred, d, 4, st);
-  } else {         // bf16 tables: the product alone (fp32), the newest rows are added with the error
+  } else {         // bf16 tables, d_s = 128: the product alone (fp32), the newest rows are added with the error
     rc = sat_dense_fwd(aggS, ds, n_l, ds, d, w->Wg, d, SAT_ACT_IDENTITY, SAT_F32, pred, d, stream);
   }
   if (rc != SAT_OK) return rc;
@@ -357,9 +447,13 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
     finish_sum_kernel<<<dim3(1), dim3(256), 0, st>>>(part, kRedBlocks, 1.0f, nullptr, wsum);
     wsum_dev = wsum;
   }
-  if (es == 4)
+  if (fused_add)
     sq_error_kernel<4><<<dim3(kRedBlocks), dim3(256), 0, st>>>(pred, d, target, ld_target, nullptr, 0, nullptr,
                                                                0, weight, wsum_dev, n_l, d, part);
+  else if (es == 4)
+    sq_error_kernel<4><<<dim3(kRedBlocks), dim3(256), 0, st>>>(pred, d, target, ld_target, slots[tau - 1],
+                                                               ld_slot, ids, n_rows_slot, weight, wsum_dev,
+                                                               n_l, d, part);
   else
     sq_error_kernel<2><<<dim3(kRedBlocks), dim3(256), 0, st>>>(pred, d, target, ld_target, slots[tau - 1],
                                                                ld_slot, ids, n_rows_slot, weight, wsum_dev,
@@ -395,7 +489,6 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
     // dWx += da^T x_s  (x_s: the slot's rows of the partition's nodes, local then halo)
     const void* xs = slots[s];
     int64_t ld_x = ld_slot;
-    if (!ids && n_rows_slot < n_bar) return SAT_EINVAL;
     if (es == 2) {   // the products below are fp32: widen the window's rows on the way
       widen_rows_kernel<<<blocks_for(n_bar * (d / 2)), dim3(256), 0, st>>>(
           static_cast<const uint16_t*>(slots[s]), ld_slot, ids, n_rows_slot, xwin, d, n_bar, d);
@@ -413,8 +506,8 @@ extern "C" sat_status sat_predictor_grad(const sat_part_view* pv, const sat_pred
     if (rc != SAT_OK) return rc;
     axpy_rows_kernel<<<blocks_for(static_cast<int64_t>(4 * ds) * d), dim3(256), 0, st>>>(
         dWx, d, tmpW, d, 4 * ds, d, 1.0f);
-    col_sum_kernel<<<dim3(kRedBlocks), dim3(256), 0, st>>>(da, n_bar, 4 * ds, part);
-    col_sum_finish_kernel<<<dim3(1), dim3(256), 0, st>>>(part, kRedBlocks, 4 * ds, db);
+    col_sum_kernel<<<dim3(kRedBlocks, (4 * ds + 255) / 256), dim3(256), 0, st>>>(da, n_bar, 4 * ds, part);
+    col_sum_finish_kernel<<<dim3((4 * ds + 255) / 256), dim3(256), 0, st>>>(part, kRedBlocks, 4 * ds, db);
     if ((rc = sat::check_launch()) != SAT_OK) return rc;
     if (s > 0) {
       // dWh += da^T h_{s-1};  dh_{s-1} = da Wh

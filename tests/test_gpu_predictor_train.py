@@ -85,6 +85,9 @@ def _grad(env, v, dev, d, d_s, tau, n_rows, ld, bf16=False):
     ("tiny", 32, 32, 2, False, False, False), ("tiny", 32, 32, 1, True, True, False),
     ("powerlaw", 256, 64, 2, True, False, False), ("powerlaw", 100, 64, 3, False, True, False),
     ("hub", 40, 32, 2, True, False, False),
+    # d_s = 128: the forward as two transform products and an element-wise step per time step
+    ("powerlaw", 100, 128, 2, True, False, False), ("hub", 40, 128, 3, False, True, False),
+    ("tiny", 32, 128, 1, False, False, False),
     # bfloat16 tables and target: the same arithmetic (fp32 inside) on the rounded inputs
     ("tiny", 32, 32, 2, True, False, True), ("powerlaw", 256, 64, 2, True, True, True),
     ("hub", 40, 32, 3, False, False, True)])
