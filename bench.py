@@ -282,16 +282,36 @@ def main():
         # once (however often it is gathered), every output row once
         return 8 * entries + 8 * rows + distinct * d * s + rows * d * s
 
+    def spmm_kernel(entries, rows, d):
+        # the kernel instance the library's aggregation launcher picks for this shape
+        # (labels the launches; the dispatch itself is csrc/spmm.hip's)
+        row_bytes, nvec = d * s, (d * s + 15) // 16
+        if nvec <= 32 and entries < 16 * rows:
+            g = 1
+            while g < nvec:
+                g <<= 1
+            return "spmm_group_kernel<%d,%d,4>" % (s, g)
+        if row_bytes <= 256:
+            return "spmm_slot_kernel<%d,%d,8>" % (s, 8 if row_bytes <= 128 else 16)
+        if row_bytes <= 512:
+            return "spmm_stream_kernel<%d,2,1,16>" % s
+        if row_bytes <= 1024:
+            return "spmm_stream_kernel<%d,4,1,16>" % s
+        if row_bytes <= 2048 or s == 2:
+            return "spmm_stream_kernel<%d,4,2,8>" % s
+        return "spmm_stream_kernel<%d,4,%d,4>" % (s, 3 if row_bytes <= 3072 else 4)
+
     classes = {}
 
-    def add(cls, name, bound, work, compulsory=None):
+    def add(cls, name, bound, work, compulsory=None, kernel=None):
         if name not in calls:
             return
-        c = classes.setdefault(cls, dict(bound=bound, work=0.0, ms=0.0, launches=0, compulsory=0.0))
-        c["work"] += work * calls[name]["launches"]
-        c["compulsory"] += (work if compulsory is None else compulsory) * calls[name]["launches"]
-        c["ms"] += calls[name]["total_ms"]
-        c["launches"] += calls[name]["launches"]
+        for key in ((cls, kernel) if kernel else (cls,)):
+            c = classes.setdefault(key, dict(bound=bound, work=0.0, ms=0.0, launches=0, compulsory=0.0))
+            c["work"] += work * calls[name]["launches"]
+            c["compulsory"] += (work if compulsory is None else compulsory) * calls[name]["launches"]
+            c["ms"] += calls[name]["total_ms"]
+            c["launches"] += calls[name]["launches"]
 
     tf = bool(getattr(step, "transform_first", False))
     for l in range(L):
@@ -299,7 +319,9 @@ def main():
             # last layer as P (Hbar W): transform over all rows, both aggregations at n_classes
             # columns, the transpose one over local and halo entries (dW needs P_out^T dH too)
             C = dims[L]
-            add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, C), spmm_compulsory(nnz, n_l, n_bar, C))
+            add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, C), spmm_compulsory(nnz, n_l, n_bar, C),
+                kernel=spmm_kernel(nnz, n_l, C))
+            # (two launches: the local block's transpose and the halo block's)
             add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, C) + spmm_bytes(nnz_halo, n_h, C),
                 spmm_compulsory(nnz_loc, n_l, n_l, C) + spmm_compulsory(nnz_halo, n_h, n_l, C))
             add("dense_fwd", "dense_fwd_l%d" % l, "mfma", 2.0 * n_bar * dims[l] * C)
@@ -307,12 +329,13 @@ def main():
             add("dense_bwd", "dense_bwd_in_l%d" % l, "mfma", 2.0 * n_l * dims[l] * C)
         else:
             add("spmm", "spmm_fwd_l%d" % l, "hbm", spmm_bytes(nnz, n_l, dims[l]),
-                spmm_compulsory(nnz, n_l, n_bar, dims[l]))
+                spmm_compulsory(nnz, n_l, n_bar, dims[l]), kernel=spmm_kernel(nnz, n_l, dims[l]))
         if l >= 1 and not (tf and l == L - 1):
             add("spmm", "spmm_bwd_l%d" % l, "hbm", spmm_bytes(nnz_loc, n_l, dims[l]) + (
                 spmm_bytes(nnz_halo, n_h, dims[l]) if args.stale_grad else 0),
                 spmm_compulsory(nnz_loc, n_l, n_l, dims[l]) + (
-                    spmm_compulsory(nnz_halo, n_h, n_l, dims[l]) if args.stale_grad else 0))
+                    spmm_compulsory(nnz_halo, n_h, n_l, dims[l]) if args.stale_grad else 0),
+                kernel=None if args.stale_grad else spmm_kernel(nnz_loc, n_l, dims[l]))
         if gat:      # the transform runs over local + halo rows; three edge passes per layer
             K = step.heads[l]
             dl = dims[l + 1]
@@ -373,7 +396,7 @@ def main():
                              ms_per_step=round(c["ms"] / args.steps, 4),
                              launches_per_step=c["launches"] // args.steps,
                              traffic=traffic)
-        if cls == "spmm":
+        if cls == "spmm" or cls.startswith("spmm_"):
             # Three readings of the same launches. `frac` prices what the lanes REQUEST (a row
             # per entry): re-gathered rows that a cache serves count as if they came from HBM,
             # so it is an upper bound on the HBM fraction and can pass 1. The measured one
@@ -392,7 +415,9 @@ def main():
     # made of several kernels, none of which outweighs the aggregation kernel (see the
     # rocprofv3 kernel statistics under profiles/), so they are listed in
     # roofline_all at call level and not eligible here.
-    single = [k for k in roof_all if k not in ("predict", "dense_bwd", "gat_bwd", "coded_pull", "coded_push")]
+    # The aggregation launches are listed twice: all together ("spmm") and by kernel instance
+    # (the keys that name one); the dominant kernel is chosen among the instances.
+    single = [k for k in roof_all if k not in ("spmm", "predict", "dense_bwd", "gat_bwd", "coded_pull", "coded_push")]
     dominant = max(single, key=lambda k: roof_all[k]["ms_per_step"])
     roofline = dict(kernel=KERNEL_OF_CLASS.get(dominant, dominant), **roof_all[dominant])
 
