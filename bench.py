@@ -126,6 +126,8 @@ def main():
     ap.add_argument("--backbone", default="gcn", choices=["gcn", "gat"],
                     help="gcn: the normalised-adjacency aggregation (the headline); gat: the graph "
                          "attention backbone (edge softmax aggregation, three edge passes per layer)")
+    ap.add_argument("--gat-heads", type=int, default=4, choices=[1, 2, 4, 8],
+                    help="heads of the hidden layers of the graph attention backbone")
     ap.add_argument("--graph", action="store_true",
                     help="after the timed steps also replay the step from a HIP graph (one graph holds "
                          "tau consecutive steps) and report its time under \"graph\": for the workloads "
@@ -187,7 +189,7 @@ def main():
     wl = build_workload(args.workload, bypass=args.bypass, fused_pull=not args.unfused_pull,
                         timers=timers, log=log, dtype=args.dtype, grad_tables=args.stale_grad,
                         predict_every=args.delta_t, backbone=args.backbone, coded_ring=args.coded_ring,
-                        coded_chunk_rows=args.coded_chunk_rows,
+                        coded_chunk_rows=args.coded_chunk_rows, gat_hidden_heads=args.gat_heads,
                         predict_ahead=predict_ahead,
                         transform_first=False if (args.no_transform_first or gat_flag) else "auto",
                         projection_cache=False if (args.no_projection_cache or gat_flag or args.predictor_train)

@@ -44,9 +44,10 @@ constexpr int kWaves = 8;
 constexpr int kRowsPerBlock = 64;
 constexpr int kLongRow = 1024;
 constexpr int kU = 8;         // gathers in flight per lane group
-// (with 16-byte shares of bf16 rows: 6, the most that keeps the entry loop free of spills)
-template <int V>
-constexpr int kUof = V == 2 ? 6 : kU;
+// (with 16-byte shares of bf16 rows: 6, the most that keeps the entry loop free of spills; with
+// 8 heads, whose per-head values take the registers of two more gathers: 6 and 4)
+template <int K, int V>
+constexpr int kUof = (V == 2 ? 6 : kU) - (K == 8 ? 2 : 0);
 constexpr int kMaxD = 256;     // 64 lanes x 4 elements
 
 // Four consecutive elements of a row: the bits as loaded (nothing may touch them before
@@ -174,6 +175,10 @@ __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
   return v;
+}
+// a value all lanes hold alike, moved to a scalar register
+__device__ __forceinline__ float uniform_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int32_t, v)));
 }
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -433,8 +438,8 @@ __global__ __launch_bounds__(256) void gat_scores_kernel(const unsigned char* Z,
 // ---------------------------------------------------------------- forward
 // H[i] = act(sum_j alpha_ij Z_j), stats[i, k] = (max_j e_ij, 1 / sum_j exp(e_ij - max))
 template <int ES, int K, int V>
-__global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, const float* el,
-                                                                const float* er, int relu,
+__global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, const float* __restrict__ el,
+                                                                const float* __restrict__ er, int relu,
                                                                 unsigned char* Y, int64_t ld_y,
                                                                 float* stats) {
   __shared__ RowSpans sp;
@@ -471,8 +476,9 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     for (int k = 0; k < K; ++k) {
       const float s = eli[k] + erv[k];
       e[k] = ok ? (s > 0.f ? s : a.slope * s) : -INFINITY;
+      // (the running maximum is the same in every lane: kept in scalar registers)
       const float bm = wave_max(e[k]);
-      const float mn = fmaxf(m[k], bm);
+      const float mn = uniform_f32(fmaxf(m[k], bm));
       // first entries of the row: m = -inf, nothing accumulated yet to rescale
       scale[k] = m[k] == -INFINITY ? 0.f : expf(m[k] - mn);
       const float p = e[k] == -INFINITY ? 0.f : expf(e[k] - mn);
@@ -537,7 +543,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, V, K, kUof<V>>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, K, kUof<K, V>>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float ll[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ll[k] = wave_sum(l[k]);
@@ -554,7 +560,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, V, K, kUof<V>>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, K, kUof<K, V>>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
     f32x4 part[V];
     group_sum<V>(acc, a.ln, part);
     float lk[K];
@@ -606,8 +612,8 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_fwd_kernel(WalkArgs a, 
 // and rowstat[i, k] = (el, max, 1/sum, D) for the source-side pass.
 template <int ES, int K, int V>
 __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
-    WalkArgs a, const float* el, const float* er, const float* stats, const unsigned char* dOUT,
-    int64_t ld_g, float* d_el, f32x4* rowstat) {
+    WalkArgs a, const float* __restrict__ el, const float* __restrict__ er, const float* __restrict__ stats,
+    const unsigned char* dOUT, int64_t ld_g, float* d_el, f32x4* rowstat) {
   __shared__ RowSpans sp;
   __shared__ int32_t s_col[kWaves][kWave];
   __shared__ float s_w[kWaves][kWave * 2 * K];
@@ -686,7 +692,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     const int64_t row = row0 + r;
     const int64_t s = uniform64(sp.begin[r]), e = uniform64(sp.end[r]);
     reset(row);
-    walk<ES, V, 2 * K, kUof<V>>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, 2 * K, kUof<K, V>>(a, L, s, e, s_col[wave], s_w[wave], pre, entry, feature, fold);
     float ws[K];
 #pragma unroll
     for (int k = 0; k < K; ++k) ws[k] = wave_sum(w1s[k]);
@@ -700,7 +706,7 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
     int64_t ps, pe;
     piece_of(s, e, wave, ps, pe);
     reset(row);
-    walk<ES, V, 2 * K, kUof<V>>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
+    walk<ES, V, 2 * K, kUof<K, V>>(a, L, ps, pe, s_col[wave], s_w[wave], pre, entry, feature, fold);
     const float D = head_sum(accD, a.ln), t1 = head_sum(acc1, a.ln);
     float wk[K];
 #pragma unroll
@@ -735,9 +741,9 @@ __global__ __launch_bounds__(kWaves * kWave, 4) void gat_bwd_dst_kernel(
 //   d_er_j = sum_i alpha_ij LeakyReLU'(s_ij) (<g_i, Z_j> - D_i)
 //   dZ_j   = sum_i alpha_ij g_i + d_er_j a_src + d_el_j a_dst   (the last term for local j)
 template <int ES, int K, int V, int U>
-__global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_kernel(
-    WalkArgs a, int64_t row_off, int64_t n_local, const float* er, const f32x4* rowstat,
-    const unsigned char* Z, int64_t ld_z, const float* d_el, const float* a_dst, const float* a_src,
+__global__ __launch_bounds__(kWaves * kWave, (U <= 2 && K < 8) ? 6 : 4) void gat_bwd_src_kernel(
+    WalkArgs a, int64_t row_off, int64_t n_local, const float* __restrict__ er, const f32x4* __restrict__ rowstat,
+    const unsigned char* Z, int64_t ld_z, const float* __restrict__ d_el, const float* a_dst, const float* a_src,
     unsigned char* dZ, int64_t ld_dz, float* d_er) {
   __shared__ RowSpans sp;
   __shared__ int32_t s_col[kWaves][kWave];
@@ -775,7 +781,7 @@ __global__ __launch_bounds__(kWaves * kWave, U <= 2 ? 6 : 4) void gat_bwd_src_ke
   };
   // (the instance with two gathers in flight has no registers to hold the row statistics across
   // the gathers' issue: it requests them in the entry phase)
-  constexpr bool kEarly = U > 2;
+  constexpr bool kEarly = U > 2 && K < 8;   // (8 heads: 32 registers per entry)
   f32x4 rsv[K];
   auto pre = [&](int32_t c, bool) __attribute__((always_inline)) {
     if constexpr (kEarly) {
@@ -1123,7 +1129,7 @@ sat_status run_bwd(const sat_part_view* pv, const void* Z, int64_t ld_z, Lanes l
       // columns themselves (the local block's pattern is symmetric)
     const WalkArgs a{pv->rowptr, pv->split, pv->col, n_l, n_l, dOUT, ld_g, lw, slope};
     const int64_t gb = (n_l + kRowsPerBlock - 1) / kRowsPerBlock;
-    gat_bwd_src_kernel<ES, K, V, kUof<V>><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
+    gat_bwd_src_kernel<ES, K, V, kUof<K, V>><<<dim3(static_cast<unsigned>(gb)), block, 0, s>>>(
         a, 0, n_l, er, rowstat, static_cast<const unsigned char*>(Z), ld_z * ES, d_el, a_dst, a_src,
         static_cast<unsigned char*>(dZ), ld_dz * ES, d_er);
     if ((st = sat::check_launch()) != SAT_OK) return st;

@@ -37,7 +37,8 @@ def _upload(a, bf16, dev):
 def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda m: None,
                    keep_host=True, device="cuda:0", dtype=None, grad_tables=False, predict_every=1,
                    backbone="gcn", coded_ring=None, own_headroom=1.5, predict_ahead=False,
-                   transform_first="auto", projection_cache="auto", coded_chunk_rows=None):
+                   transform_first="auto", projection_cache="auto", coded_chunk_rows=None,
+                   gat_hidden_heads=4):
     """Generate workload `name` (see sat_synth.configs) and put it on the GPU.
 
     grad_tables: also allocate a pair of zeroed gradient tables per hidden layer (shape
@@ -163,7 +164,7 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     attn = None
     if backbone == "gat":
         from .step_gat import GatPartitionStep
-        heads = syn.gat_heads(dims)
+        heads = syn.gat_heads(dims, gat_hidden_heads)
         ass = ss["misc"].spawn(L)
         attn = [syn.attention_vectors_f32(ass[l], heads[l], dims[l + 1] // heads[l]) for l in range(L)]
         attn_d = [(torch.from_numpy(a.reshape(-1)).to(dev), torch.from_numpy(b.reshape(-1)).to(dev),

@@ -88,12 +88,12 @@ def predictor_params_f32(ss, d, d_s, scale_g=0.5):
     return dict(Wx=Wx, Wh=Wh, b=b, Wg=Wg)
 
 
-def gat_heads(dims):
-    """Heads per layer of the attention backbone for feature widths `dims`: four
-    heads on hidden layers whose width allows it (a multiple of 16), one head on
-    the last layer (the usual classifier) and otherwise."""
+def gat_heads(dims, hidden_heads=4):
+    """Heads per layer of the attention backbone for feature widths `dims`: `hidden_heads`
+    (four unless stated) on hidden layers whose width allows it (a multiple of four
+    elements per head), one head on the last layer (the usual classifier) and otherwise."""
     L = len(dims) - 1
-    return [4 if l < L - 1 and dims[l + 1] % 16 == 0 else 1 for l in range(L)]
+    return [hidden_heads if l < L - 1 and dims[l + 1] % (4 * hidden_heads) == 0 else 1 for l in range(L)]
 
 
 def attention_vectors_f32(ss, heads, d_head):
