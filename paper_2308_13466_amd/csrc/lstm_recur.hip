@@ -8,12 +8,17 @@
 // 8 w .. 8 w + 7, its 32 rows being row 8 g + u = gate g of unit 8 w + u: 48 registers), the
 // nodes are the columns. In the accumulator of such a product a lane holds, for ONE node,
 // rows 8 (r / 4) + 4 (lane / 32) + r % 4, i.e. all four gates of four units: the cell update is
-// register-local, the kept gates of a node and gate arrive as one 16-byte load (four
-// consecutive units), h leaves as 8-byte LDS writes per piece and S as 16-byte stores. No
-// weight tile is staged, the only barrier is the one that hands h_{s-1} to the other
-// wavefronts. A workgroup walks many tiles of 128 nodes and requests the kept gates of the
-// next (tile, step) a whole step ahead into a second set of accumulators, so the rows arrive
-// while the transcendentals of the current step run.
+// register-local, h leaves as 8-byte LDS writes per piece and S as 16-byte stores. No weight
+// tile is staged. The kept gates come in through LDS: read from memory in a lane's own
+// layout they would be 16-byte slivers of 64 different cache lines per load instruction (a
+// wavefront owns 8 of a row's 64 units per gate), which keeps the address and first-level
+// cache units busy 90 % of the time; instead wavefront w reads the whole rows of nodes
+// 8 w .. 8 w + 7 (one 1 KiB row per instruction, eight lines fully used), a step ahead into
+// registers, and writes them to a row-major tile in LDS at the end of the step; every
+// wavefront then starts its accumulators from its slivers of that tile (16-byte LDS reads,
+// rows padded by 16 bytes so that 16 lanes cover all banks). A workgroup walks many tiles of
+// 64 nodes; the rows of the next (tile, step) are in flight while the products and the
+// transcendentals of the current one run.
 //
 // Bit-compatibility with lstm_mx_kernel: the accumulator starts from the kept projection and
 // takes the same products in the same order (k chunks ascending; (h1 W3) (h3 W1) (h2 W2)
@@ -29,6 +34,8 @@ using namespace sat::mx;
 constexpr int kDS = 64, kNB = 4 * kDS, kR = 64, kBlocks = kR / 32, kMaxTau = 8;
 constexpr int kHRowB = kDS * 2 + 16;           // bytes per node row of a staged h piece (padded)
 constexpr int kHPieceB = kR * kHRowB;
+constexpr int kGRowB = kNB * 4 + 16;           // bytes per node row of the staged gates (padded)
+constexpr int kRowsPerWave = kR / 8;           // rows of the gate tile a wavefront brings in
 
 struct RecurProj {
   const float* p[kMaxTau];
@@ -46,7 +53,10 @@ __global__ __launch_bounds__(512, 2) void lstm_recur_kernel(RecurProj proj, int 
                                                            const float* __restrict__ bias,
                                                            float* __restrict__ S) {
   constexpr int NP = 3;
-  __shared__ __attribute__((aligned(16))) unsigned char Hs[NP * kHPieceB];
+  // h_s goes to Hs[s % 2]: the products of step s (reading h_{s-1}) and its cell update
+  // (writing h_s) then need no barrier between them and can be interleaved
+  __shared__ __attribute__((aligned(16))) unsigned char Hs[2][NP * kHPieceB];
+  __shared__ __attribute__((aligned(16))) unsigned char Gs[kR * kGRowB];
   const int t = threadIdx.x;
   const int lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -70,108 +80,119 @@ __global__ __launch_bounds__(512, 2) void lstm_recur_kernel(RecurProj proj, int 
 #pragma unroll
   for (int g = 0; g < 4; ++g) b_gate[g] = *reinterpret_cast<const f32x4*>(bias + g * kDS + unit0);
 
-  // kept gate pre-activations of step s of the tile at node0: dst[b][4 g + j] =
-  // P[node][64 g + unit0 + j]. Only issues the loads.
-  auto load_gates = [&](int64_t node0, int s, f32x16 (&dst)[kBlocks]) __attribute__((always_inline)) {
+  // Rows of the kept gate pre-activations of step s, nodes node0 + 8 wave + 0..7: lane L takes
+  // bytes 16 L .. 16 L + 15 of a row. At the first step the forget gate's block (lanes 16..31)
+  // is never looked at: those lanes read the input gate's block again (same lines). Only
+  // issues the loads.
+  f32x4 rows[kRowsPerWave];
+  auto load_rows = [&](int64_t node0, int s) __attribute__((always_inline)) {
     const float* P = proj.p[s];
+    const int col = (s == 0 && (lane >> 4) == 1) ? 4 * (lane - 16) : 4 * lane;
 #pragma unroll
-    for (int b = 0; b < kBlocks; ++b) {
-      int64_t node = node0 + 32 * b + c;
+    for (int i = 0; i < kRowsPerWave; ++i) {
+      int64_t node = node0 + kRowsPerWave * wave + i;
       node = node < n_nodes ? node : n_nodes - 1;       // (rows past the end: not stored)
-      const float* row = P + node * kNB + unit0;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        if (g == 1 && s == 0) continue;                 // c_0 = 0: the forget gate is not looked at
-        const f32x4 v = *reinterpret_cast<const f32x4*>(row + g * kDS);
-        dst[b][4 * g + 0] = v.x;
-        dst[b][4 * g + 1] = v.y;
-        dst[b][4 * g + 2] = v.z;
-        dst[b][4 * g + 3] = v.w;
-      }
+      rows[i] = *reinterpret_cast<const f32x4*>(P + node * kNB + col);
     }
   };
+  auto stage_rows = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < kRowsPerWave; ++i)
+      *reinterpret_cast<f32x4*>(Gs + (kRowsPerWave * wave + i) * kGRowB + 16 * lane) = rows[i];
+  };
 
-  // A workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...; the gates of the NEXT
-  // (tile, step) are requested before the current one's products and cell update, into a
-  // second set of accumulators (the registers are there: no tile of x or of the weights is
-  // held), so the rows arrive while the transcendentals run.
+  // A workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ...
   const int64_t n_tiles = (n_nodes + kR - 1) / kR;
   f32x4 cstate[kBlocks], hval[kBlocks];
-  // one (tile, step): the products and the cell update on `acc`, after the gates of the next
-  // (tile, step) have been requested into `nxt`
-  auto do_step = [&](int64_t tile, int s, f32x16 (&acc)[kBlocks], f32x16 (&nxt)[kBlocks]) __attribute__((always_inline)) {
+  f32x16 acc[kBlocks];
+  if (static_cast<int64_t>(blockIdx.x) < n_tiles) {
+    load_rows(static_cast<int64_t>(blockIdx.x) * kR, 0);
+    stage_rows();
+  }
+  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
     const int64_t node0 = tile * kR;
-    if (s + 1 < tau) load_gates(node0, s + 1, nxt);
-    else if (tile + gridDim.x < n_tiles) load_gates((tile + gridDim.x) * kR, 0, nxt);
-    if (s > 0) {
-      __syncthreads();          // h_{s-1} of every unit is in Hs
-      // (block by block: the cell update of a block's nodes can then issue between the products
-      // of the next block, which do not depend on it)
+    for (int s = 0; s < tau; ++s) {
+      // the rows of the next (tile, step), a whole step ahead. One call with scalar operands, also
+      // after the last tile's last step (where it re-reads the table's last row: clamped inside):
+      // two calls behind a branch meet in copies of the loaded registers, i.e. in a wait.
+      const bool same_tile = s + 1 < tau;
+      load_rows(same_tile ? node0 : (tile + gridDim.x) * kR, same_tile ? s + 1 : 0);
+      __syncthreads();          // the gate tile of this step and h_{s-1} of every unit are in LDS
+      const unsigned char* Hr = Hs[(s + 1) & 1];
+      unsigned char* Hw = Hs[s & 1];
+      // this lane's slivers: acc[b][4 g + j] = gates[32 b + c][64 g + unit0 + j]
 #pragma unroll
       for (int b = 0; b < kBlocks; ++b) {
 #pragma unroll
-        for (int kc = 0; kc < kDS / 16; ++kc) {
-          bf16x8 h[NP];
+        for (int g = 0; g < 4; ++g) {
+          if (g == 1 && s == 0) continue;                 // c_0 = 0: the forget gate is not looked at
+          const f32x4 v = *reinterpret_cast<const f32x4*>(Gs + (32 * b + c) * kGRowB + 4 * (g * kDS + unit0));
+          acc[b][4 * g + 0] = v.x;
+          acc[b][4 * g + 1] = v.y;
+          acc[b][4 * g + 2] = v.z;
+          acc[b][4 * g + 3] = v.w;
+        }
+      }
+      __syncthreads();          // every wavefront has taken its slivers: the tile may be overwritten
+      if (s > 0) {
+        // (block by block: the cell update of a block's nodes can then issue between the products
+        // of the next block, which do not depend on it)
+#pragma unroll
+        for (int b = 0; b < kBlocks; ++b) {
+#pragma unroll
+          for (int kc = 0; kc < kDS / 16; ++kc) {
+            bf16x8 h[NP];
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+              h[p] = *reinterpret_cast<const bf16x8*>(Hr + p * kHPieceB + (32 * b + c) * kHRowB + 32 * kc +
+                                                      16 * half);
+            // (h piece, W piece): (0,2) (2,0) (1,1) (0,1) (1,0) (0,0)
+#pragma unroll
+            for (int q = 0; q < n_products<NP>(); ++q)
+              acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[kc][product_b<NP>(q)], h[product_a<NP>(q)],
+                                                               acc[b], 0, 0, 0);
+          }
+        }
+      }
+      // cell update, register-local: gates i, f, g, o of units unit0 + j sit in acc[b][4 g + j]
+#pragma unroll
+      for (int b = 0; b < kBlocks; ++b) {
+        float cs[4] = {cstate[b].x, cstate[b].y, cstate[b].z, cstate[b].w};
+        if (s == 0) cs[0] = cs[1] = cs[2] = cs[3] = 0.f;
+        float hv[4];
+        const float bi[4] = {b_gate[0].x, b_gate[0].y, b_gate[0].z, b_gate[0].w};
+        const float bf[4] = {b_gate[1].x, b_gate[1].y, b_gate[1].z, b_gate[1].w};
+        const float bg[4] = {b_gate[2].x, b_gate[2].y, b_gate[2].z, b_gate[2].w};
+        const float bo[4] = {b_gate[3].x, b_gate[3].y, b_gate[3].z, b_gate[3].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float gi = sigmoidf_(acc[b][j] + bi[j]);
+          const float gg = tanhf_(acc[b][8 + j] + bg[j]);
+          const float go = sigmoidf_(acc[b][12 + j] + bo[j]);
+          if (s == 0) {
+            cs[j] = gi * gg;
+          } else {
+            const float gf = sigmoidf_(acc[b][4 + j] + bf[j]);
+            cs[j] = __builtin_fmaf(gf, cs[j], gi * gg);
+          }
+          hv[j] = go * tanhf_(cs[j]);
+        }
+        cstate[b] = f32x4{cs[0], cs[1], cs[2], cs[3]};
+        hval[b] = f32x4{hv[0], hv[1], hv[2], hv[3]};
+        if (s + 1 < tau) {        // h for the next step's product: three bf16 pieces, node-major
+          uint32_t lo[NP], hi[NP];
+          split2<NP>(hv[0], hv[1], lo);
+          split2<NP>(hv[2], hv[3], hi);
 #pragma unroll
           for (int p = 0; p < NP; ++p)
-            h[p] = *reinterpret_cast<const bf16x8*>(Hs + p * kHPieceB + (32 * b + c) * kHRowB + 32 * kc +
-                                                    16 * half);
-          // (h piece, W piece): (0,2) (2,0) (1,1) (0,1) (1,0) (0,0)
-#pragma unroll
-          for (int q = 0; q < n_products<NP>(); ++q)
-            acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[kc][product_b<NP>(q)], h[product_a<NP>(q)],
-                                                             acc[b], 0, 0, 0);
-        }
-      }
-    }
-    __syncthreads();            // every wavefront has read Hs (this tile's or the last one's)
-    // cell update, register-local: gates i, f, g, o of units unit0 + j sit in acc[b][4 g + j]
-#pragma unroll
-    for (int b = 0; b < kBlocks; ++b) {
-      float cs[4] = {cstate[b].x, cstate[b].y, cstate[b].z, cstate[b].w};
-      if (s == 0) cs[0] = cs[1] = cs[2] = cs[3] = 0.f;
-      float hv[4];
-      const float bi[4] = {b_gate[0].x, b_gate[0].y, b_gate[0].z, b_gate[0].w};
-      const float bf[4] = {b_gate[1].x, b_gate[1].y, b_gate[1].z, b_gate[1].w};
-      const float bg[4] = {b_gate[2].x, b_gate[2].y, b_gate[2].z, b_gate[2].w};
-      const float bo[4] = {b_gate[3].x, b_gate[3].y, b_gate[3].z, b_gate[3].w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float gi = sigmoidf_(acc[b][j] + bi[j]);
-        const float gg = tanhf_(acc[b][8 + j] + bg[j]);
-        const float go = sigmoidf_(acc[b][12 + j] + bo[j]);
-        if (s == 0) {
-          cs[j] = gi * gg;
+            *reinterpret_cast<u32x2*>(Hw + p * kHPieceB + (32 * b + c) * kHRowB + 2 * unit0) = u32x2{lo[p], hi[p]};
         } else {
-          const float gf = sigmoidf_(acc[b][4 + j] + bf[j]);
-          cs[j] = __builtin_fmaf(gf, cs[j], gi * gg);
+          const int64_t node = node0 + 32 * b + c;
+          if (node < n_nodes) *reinterpret_cast<f32x4*>(S + node * kDS + unit0) = hval[b];
         }
-        hv[j] = go * tanhf_(cs[j]);
       }
-      cstate[b] = f32x4{cs[0], cs[1], cs[2], cs[3]};
-      hval[b] = f32x4{hv[0], hv[1], hv[2], hv[3]};
-      if (s + 1 < tau) {        // h for the next step's product: three bf16 pieces, node-major
-        uint32_t lo[NP], hi[NP];
-        split2<NP>(hv[0], hv[1], lo);
-        split2<NP>(hv[2], hv[3], hi);
-#pragma unroll
-        for (int p = 0; p < NP; ++p)
-          *reinterpret_cast<u32x2*>(Hs + p * kHPieceB + (32 * b + c) * kHRowB + 2 * unit0) = u32x2{lo[p], hi[p]};
-      } else {
-        const int64_t node = node0 + 32 * b + c;
-        if (node < n_nodes) *reinterpret_cast<f32x4*>(S + node * kDS + unit0) = hval[b];
-      }
-    }
-  };
-  // two sets of accumulators that swap roles from one (tile, step) to the next (no copies)
-  f32x16 acc_a[kBlocks], acc_b[kBlocks];
-  if (static_cast<int64_t>(blockIdx.x) < n_tiles) load_gates(static_cast<int64_t>(blockIdx.x) * kR, 0, acc_a);
-  bool flip = false;
-  for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    for (int s = 0; s < tau; ++s) {
-      if (!flip) do_step(tile, s, acc_a, acc_b);
-      else do_step(tile, s, acc_b, acc_a);
-      flip = !flip;
+      // the next (tile, step)'s rows have had the whole step to arrive
+      stage_rows();
     }
   }
 }
@@ -191,7 +212,7 @@ sat_status launch_lstm_recur(float* const* proj, int tau, int64_t n_nodes, const
   RecurProj pp;
   for (int s = 0; s < kMaxTau; ++s) pp.p[s] = s < tau ? proj[s] : nullptr;
   // one workgroup per compute unit (its registers fill two wavefronts per SIMD), each walking
-  // its share of the 128-node tiles
+  // its share of the 64-node tiles
   const int64_t tiles = (n_nodes + kR - 1) / kR;
   const int64_t blocks = tiles < 256 ? tiles : 256;
   lstm_recur_kernel<<<dim3(static_cast<unsigned>(blocks)), dim3(512), 0, st>>>(
