@@ -508,6 +508,12 @@ sat_status launch_lstm_proj(const void* X, int64_t n_rows_slot, int64_t ld_slot,
 sat_status launch_lstm_recur(float* const* proj, int tau, int64_t n_nodes, const void* WhP, const float* bias,
                              float* S, hipStream_t st);
 
+// lstm_fused16.hip: the whole LSTM over bf16 rows of 256 elements with all weights in registers
+bool lstm_fused16_serves(int32_t d, int32_t d_s, int es_x, int64_t n_nodes);
+sat_status launch_lstm_fused16(const void* const* slot_ptrs, int tau, int64_t n_rows_slot, int64_t ld_slot,
+                               const int32_t* ids, int64_t n_nodes, const void* WxP, const void* WhP,
+                               const float* bias, float* S, hipStream_t st);
+
 // Bytes of workspace the split-weight copies need (0 if this path does not serve d_s).
 int64_t lstm_mx_workspace_bytes(int32_t d, int32_t d_s) {
   if (d_s != 32 && d_s != 64) return 0;
@@ -565,6 +571,14 @@ sat_status launch_lstm_mx(const void* const* slot_ptrs, int es_x, int tau, int64
     lstm_mx_kernel<64, 4, 8, true, kR, false><<<dim3(static_cast<unsigned>(blocks)), dim3(512), 0, st>>>(
         sp, tau, n_rows_slot, ld_slot, ids, n_nodes, d, k_pad, WxP, WhP, b, S, save, pp);
     return sat::check_launch();
+  }
+  // bf16 rows of 256 elements, nothing kept and nothing to keep: weights in registers, the
+  // rows through an LDS tile (same sums, bit for bit)
+  if (!proj && save == nullptr && lstm_fused16_serves(d, d_s, es_x, n_nodes) && n_rows_slot > 0 &&
+      (reinterpret_cast<uintptr_t>(b) & 15u) == 0 && (ld_slot % 8) == 0) {
+    bool aligned = true;
+    for (int s = 0; s < tau; ++s) aligned = aligned && (reinterpret_cast<uintptr_t>(slot_ptrs[s]) & 15u) == 0;
+    if (aligned) return launch_lstm_fused16(slot_ptrs, tau, n_rows_slot, ld_slot, ids, n_nodes, WxP, WhP, b, S, st);
   }
   const int64_t blocks = (n_nodes + kR - 1) / kR;
   if (blocks > INT32_MAX) return SAT_EUNSUPPORTED;

@@ -53,7 +53,8 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
     when it narrows to half the width or less).
     coded_chunk_rows: see PartitionStep (with coded_ring: rows of the window decoded at a time).
     projection_cache: see PartitionStep ("auto": when the matrices of all slots and hidden
-    layers together stay under 8 GiB; the full Scale configuration would need 137 GB).
+    layers together stay under 8 GiB - the full Scale configuration would need 137 GB - and
+    the tables are not bf16 rows the library's registers-only LSTM kernel serves).
     dtype: "f32" or "bf16" (default: the configuration's own). In bf16 mode the
     host copies kept for the tests hold the rounded values the device holds.
 
@@ -175,7 +176,11 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
                                 coded_chunk_rows=coded_chunk_rows)
     else:
         if projection_cache == "auto":
-            projection_cache = (not bypass and coded is None and fused_pull and d_s <= 64
+            # (bf16 rows of 256 elements with d_s = 64 and enough nodes: the library's LSTM kernel
+            # for that case, all weights in registers, is faster without kept projections than
+            # the one that reads them)
+            regs_only = bf16 and d_s == 64 and n_bar >= 32768 and all(dims[l] == 256 for l in range(1, L))
+            projection_cache = (not bypass and coded is None and fused_pull and d_s <= 64 and not regs_only
                                 and (L - 1) * tau * n_bar * 16 * d_s <= (8 << 30))
         step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
                              fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,

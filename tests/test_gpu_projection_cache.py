@@ -32,7 +32,11 @@ def env():
     # newest slot's projection comes from the product kernel of its own and the time steps run
     # from kept matrices only; the row count is not a multiple of 32
     ("powerlaw_big", 256, 64, 2, True, False), ("powerlaw_big", 256, 64, 3, False, False),
-    ("powerlaw_big_bad_ids", 256, 64, 2, True, False)])
+    ("powerlaw_big_bad_ids", 256, 64, 2, True, False),
+    # the same sizes with bf16 rows: the plain call then runs the LSTM kernel that keeps all
+    # weights in registers, the cached one the kernel that stages them; same bits
+    ("powerlaw_big", 256, 64, 2, True, True), ("powerlaw_big", 256, 64, 3, False, True),
+    ("powerlaw_big_bad_ids", 256, 64, 2, True, True)])
 def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
     sat, gu, torch = env
     bad_ids = kind.endswith("_bad_ids")
@@ -130,6 +134,50 @@ def test_predict_cached_bit_identical(env, kind, d, d_s, tau, use_ids, bf16):
     refo = orc.predict(v, p, win)
     got = out.float().cpu().numpy()[n_l:, :d]
     gpu_util.assert_close(got, orc.round_bf16(refo) if bf16 else refo, 2e-2 if bf16 else 1e-5, "predicted halo rows")
+
+
+@pytest.mark.parametrize("tau,use_ids", [(1, True), (4, False)])
+def test_registers_only_lstm_on_bf16_rows_other_windows(env, tau, use_ids):
+    """Windows of one and four slots over bf16 rows of 256 elements (the plain call runs the LSTM
+    kernel that keeps all weights in registers): same bits as the cached call with nothing kept
+    (the kernel that stages the weights), and the oracle."""
+    sat, gu, torch = env
+    from tests import gpu_util
+    d, d_s = 256, 64
+    print("[case] bf16 rows, weights in registers, tau=%d ids=%s" % (tau, use_ids), flush=True)
+    g = _graph("powerlaw_big")
+    v = sat.partition_view_build(g.N, g.rowptr, g.col, g.part, 0)
+    n_l, n_h = v["n_local"], v["n_halo"]
+    n_bar = n_l + n_h
+    rng = np.random.default_rng(7 + tau)
+    p = syn.predictor_params_f32(np.random.SeedSequence(40 + tau), d, d_s)
+    ld = gu.ld_for(d, 32)
+    if use_ids:
+        ids = np.concatenate([v["local_ids"], v["halo_ids"]]).astype(np.int32)
+        n_rows = g.N
+    else:
+        ids, n_rows = None, n_bar
+    tabs = [syn.f32_from_bf16_bits(syn.bf16_bits_from_f32(rng.standard_normal((n_rows, d)).astype(np.float32)))
+            for _ in range(tau)]
+    tabs_d = [gu.to_dev_bits(syn.bf16_bits_from_f32(t), ld).view(torch.bfloat16) for t in tabs]
+    pd = {k: gu.to_dev(p[k]) for k in p}
+    w = sat.Predictor(pd["Wx"], pd["Wh"], pd["b"], pd["Wg"], d, d_s, tau)
+    wsb = sat.predict_workspace_bytes(n_l, n_h, d, d_s, tau)
+    ws = gu.workspace(wsb)
+    ids_d = gu.to_dev(ids) if use_ids else None
+    v_d = gu.upload_view(v)
+    out = torch.zeros((n_bar, ld), dtype=torch.bfloat16, device=gu.DEV)
+    sat.predict(v_d, w, tabs_d, n_rows, ld, ids_d, out, ld, dtype=sat.BF16, workspace=ws, workspace_bytes=wsb,
+                stream=gu.stream_ptr())
+    out2 = torch.zeros((n_bar, ld), dtype=torch.bfloat16, device=gu.DEV)
+    proj = [torch.full((n_bar, 4 * d_s), float("nan"), dtype=torch.float32, device=gu.DEV) for _ in range(tau)]
+    sat.predict_cached(v_d, w, tabs_d, n_rows, ld, ids_d, out2, ld, proj, 0, dtype=sat.BF16, workspace=ws,
+                       workspace_bytes=wsb, stream=gu.stream_ptr())
+    gu.sync()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+    win = [t[ids] if use_ids else t for t in tabs]
+    refo = orc.predict(v, p, win)
+    gpu_util.assert_close(out.float().cpu().numpy()[n_l:, :d], orc.round_bf16(refo), 2e-2, "predicted halo rows")
 
 
 def test_predict_cached_rejects_bad_arguments(env):
