@@ -192,7 +192,7 @@ def main():
                         coded_chunk_rows=args.coded_chunk_rows, gat_hidden_heads=args.gat_heads,
                         predict_ahead=predict_ahead,
                         transform_first=False if (args.no_transform_first or gat_flag) else "auto",
-                        projection_cache=False if (args.no_projection_cache or gat_flag or args.predictor_train)
+                        projection_cache=False if (args.no_projection_cache or args.predictor_train)
                         else "auto")
     gat = args.backbone == "gat"
     bf16 = wl.dtype == "bf16"

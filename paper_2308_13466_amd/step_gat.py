@@ -25,14 +25,15 @@ from .step import PartitionStep
 class GatPartitionStep(PartitionStep):
     """attn[l] = (a_dst, a_src, heads): device fp32 vectors [heads * d_head] of layer l,
     d_head = dims[l + 1] / heads. Everything else as PartitionStep (gradient tables, the coded
-    ring and its decoding a range of rows at a time included)."""
+    ring and its decoding a range of rows at a time, kept input projections included)."""
 
     def __init__(self, view, dims, X_table, hist, table_ids, Ws, attn, predictors, y, tau,
                  slope=0.2, timers=None, dtype=B.F32, predict_every=1, grad_tables=None, coded=None,
-                 coded_chunk_rows=None):
+                 coded_chunk_rows=None, projection_cache=False):
         super().__init__(view, dims, X_table, hist, table_ids, Ws, predictors, y, tau,
                          fused_pull=True, timers=timers, dtype=dtype, grad_tables=grad_tables,
-                         predict_every=predict_every, coded=coded, coded_chunk_rows=coded_chunk_rows)
+                         predict_every=predict_every, coded=coded, coded_chunk_rows=coded_chunk_rows,
+                         projection_cache=projection_cache)
         dev = X_table.device
         self.attn = attn
         self.slope = float(slope)
@@ -72,11 +73,7 @@ class GatPartitionStep(PartitionStep):
             if self.coded is not None:      # the window decoded from the codes
                 self._predict_coded(l, order, self.ws, st)
                 continue
-            slots = [self.hist[l][s] for s in order]
-            n_rows, ld_t = slots[0].shape
-            self._timed("predict_l%d" % l, lambda: B.predict(
-                self.pv, self.predictors[l], slots, n_rows, ld_t, self.table_ids, self.Hbar[l], ld[l],
-                dtype=dt, workspace=self.ws, workspace_bytes=self.ws_bytes, stream=st))
+            self._timed("predict_l%d" % l, lambda: self._predict_in_place(l, order, self.ws, st))
         w_slot = self.t % self.tau
         for l in range(L):
             if l == 0 and n_h > 0:
@@ -102,6 +99,8 @@ class GatPartitionStep(PartitionStep):
                 self._push_coded(l + 1, w_slot, st)
             elif not last:
                 tab = self.hist[l + 1][w_slot]
+                if self.proj is not None:
+                    self._proj_valid[l + 1][w_slot] = False      # the slot's rows change
                 self._timed("push_l%d" % (l + 1), lambda: B.history_push(
                     tab, tab.shape[0], tab.shape[1], self.local_table_ids, n_l, dims[l + 1],
                     self.Hbar[l + 1], ld[l + 1], dtype=dt, stream=st))

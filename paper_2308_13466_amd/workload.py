@@ -163,6 +163,13 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
         torch.cuda.empty_cache()
         coded = CodedRing(coded_ring, cslots)
     attn = None
+    if projection_cache == "auto":
+        # (bf16 rows of 256 elements with d_s = 64 and enough nodes: the library's LSTM kernel
+        # for that case, all weights in registers, is faster without kept projections than
+        # the one that reads them)
+        regs_only = bf16 and d_s == 64 and n_bar >= 32768 and all(dims[l] == 256 for l in range(1, L))
+        projection_cache = (not bypass and coded is None and fused_pull and d_s <= 64 and not regs_only
+                            and (L - 1) * tau * n_bar * 16 * d_s <= (8 << 30))
     if backbone == "gat":
         from .step_gat import GatPartitionStep
         heads = syn.gat_heads(dims, gat_hidden_heads)
@@ -173,15 +180,9 @@ def build_workload(name, bypass=False, fused_pull=True, timers=None, log=lambda 
         step = GatPartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, attn_d, preds, y_d, tau,
                                 timers=timers, dtype=B.BF16 if bf16 else B.F32,
                                 predict_every=predict_every, grad_tables=gt, coded=coded,
-                                coded_chunk_rows=coded_chunk_rows)
+                                coded_chunk_rows=coded_chunk_rows,
+                                projection_cache=bool(projection_cache) and coded is None)
     else:
-        if projection_cache == "auto":
-            # (bf16 rows of 256 elements with d_s = 64 and enough nodes: the library's LSTM kernel
-            # for that case, all weights in registers, is faster without kept projections than
-            # the one that reads them)
-            regs_only = bf16 and d_s == 64 and n_bar >= 32768 and all(dims[l] == 256 for l in range(1, L))
-            projection_cache = (not bypass and coded is None and fused_pull and d_s <= 64 and not regs_only
-                                and (L - 1) * tau * n_bar * 16 * d_s <= (8 << 30))
         step = PartitionStep(view, dims, X_d, hist_d, ids_d, Ws_d, preds, y_d, tau,
                              fused_pull=fused_pull, timers=timers, dtype=B.BF16 if bf16 else B.F32,
                              grad_tables=gt, predict_every=predict_every, coded=coded,

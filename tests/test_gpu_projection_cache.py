@@ -222,3 +222,26 @@ def test_step_with_projection_cache_leaves_the_same_bits(name, ahead):
         del wl, st
     for k, (a, b) in enumerate(zip(*runs)):
         assert torch.equal(a.view(torch.int32), b.view(torch.int32)), "buffer %d differs" % k
+
+
+def test_gat_step_with_projection_cache_leaves_the_same_bits():
+    """The graph attention step runs its predictions through the same call: with the input
+    projections kept per ring slot every buffer of four steps has the same bits as without."""
+    import torch
+    from paper_2308_13466_amd.workload import build_workload
+    print("[case] graph attention step with kept projections, medium", flush=True)
+    runs = []
+    for cache in (False, True):
+        wl = build_workload("medium", backbone="gat", projection_cache=cache)
+        st = wl.step
+        assert (st.proj is not None) == cache
+        for _ in range(4):
+            st.forward_backward()
+        torch.cuda.synchronize()
+        keep = [st.logits.clone(), st.loss.clone()] + [w.clone() for w in st.dW]
+        keep += [h.clone() for h in st.Hbar[1:]] + [g.clone() for g in st.dH[1:]]
+        keep += [t.clone() for l in range(1, st.L) for t in st.hist[l]]
+        runs.append(keep)
+        del wl, st
+    for k, (a, b) in enumerate(zip(*runs)):
+        assert torch.equal(a.view(torch.int32), b.view(torch.int32)), "buffer %d differs" % k
